@@ -1,0 +1,153 @@
+"""fp64 CPU oracle (test infrastructure only).
+
+Thin ctypes loader around ``nq_oracle.c``.  Only ``tests/``, the smoke entry
+and the benchmark's ``cpu_baseline`` leg may import this package; the product
+(``paper_2602_06694_amd``) never does, and this package never imports the
+product.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "nq_oracle.c")
+_LIB = os.path.join(_HERE, "libnq_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, OpenMP).  Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+                               _SRC, "-o", tmp, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        i64, p, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+        L.nqo_pack_f64.argtypes = [p, i64, i64, p]; L.nqo_pack_f64.restype = ci
+        L.nqo_pack_i8.argtypes = [p, i64, i64, p]; L.nqo_pack_i8.restype = ci
+        L.nqo_unpack.argtypes = [p, i64, i64, p]; L.nqo_unpack.restype = None
+        L.nqo_dense_weight.argtypes = [p, p, p, p, i64, i64, i64, p]; L.nqo_dense_weight.restype = None
+        L.nqo_forward_dense.argtypes = [p, p, p, p, i64, i64, i64, p, i64, p]; L.nqo_forward_dense.restype = None
+        L.nqo_forward_dense_rows.argtypes = [p, p, p, p, i64, i64, i64, p, i64, p, i64, p]
+        L.nqo_forward_dense_rows.restype = None
+        L.nqo_forward_factored.argtypes = [p, p, p, p, i64, i64, i64, p, i64, p, p, ci]
+        L.nqo_forward_factored.restype = ci
+        L.nqo_layer_bits.argtypes = [i64, i64, i64]; L.nqo_layer_bits.restype = i64
+        _lib = L
+    return _lib
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _words(a, rows, r):
+    a = np.ascontiguousarray(a, dtype=np.uint32)
+    assert a.shape == (rows, (r + 31) // 32), (a.shape, rows, r)
+    return a
+
+
+def _f64(a, n):
+    a = np.ascontiguousarray(np.asarray(a).astype(np.float64))
+    assert a.shape == (n,), (a.shape, n)
+    return a
+
+
+def pack_signs(vals: np.ndarray) -> np.ndarray:
+    """Sign-and-pack of a [rows, cols] array (float -> bit = v>=0; int8 must be +-1)."""
+    L = _load()
+    rows, cols = vals.shape
+    out = np.empty((rows, (cols + 31) // 32), dtype=np.uint32)
+    if vals.dtype == np.int8:
+        v = np.ascontiguousarray(vals)
+        rc = L.nqo_pack_i8(_ptr(v), rows, cols, _ptr(out))
+    else:
+        v = np.ascontiguousarray(vals.astype(np.float64))
+        rc = L.nqo_pack_f64(_ptr(v), rows, cols, _ptr(out))
+    if rc != 0:
+        raise ValueError("pack_signs: NaN or non +-1 int8 input")
+    return out
+
+
+def unpack_signs(words: np.ndarray, cols: int) -> np.ndarray:
+    L = _load()
+    rows = words.shape[0]
+    w = _words(words, rows, cols)
+    out = np.empty((rows, cols), dtype=np.int8)
+    L.nqo_unpack(_ptr(w), rows, cols, _ptr(out))
+    return out
+
+
+def dense_weight(U_words, V_words, s_out, s_in, d_out, d_in, r) -> np.ndarray:
+    L = _load()
+    U, V = _words(U_words, d_out, r), _words(V_words, d_in, r)
+    so, si = _f64(s_out, d_out), _f64(s_in, d_in)
+    W = np.empty((d_out, d_in), dtype=np.float64)
+    L.nqo_dense_weight(_ptr(U), _ptr(V), _ptr(so), _ptr(si), d_out, d_in, r, _ptr(W))
+    return W
+
+
+def _x(x, d_in):
+    x = np.ascontiguousarray(np.asarray(x, dtype=np.float64))
+    if x.ndim == 1:
+        x = x[None, :]
+    assert x.shape[1] == d_in
+    return x
+
+
+def forward_dense(U_words, V_words, s_out, s_in, d_out, d_in, r, x) -> np.ndarray:
+    L = _load()
+    U, V = _words(U_words, d_out, r), _words(V_words, d_in, r)
+    so, si = _f64(s_out, d_out), _f64(s_in, d_in)
+    x = _x(x, d_in)
+    y = np.empty((x.shape[0], d_out), dtype=np.float64)
+    L.nqo_forward_dense(_ptr(U), _ptr(V), _ptr(so), _ptr(si), d_out, d_in, r, _ptr(x), x.shape[0], _ptr(y))
+    return y
+
+
+def forward_dense_rows(U_words, V_words, s_out, s_in, d_out, d_in, r, x, rows) -> np.ndarray:
+    L = _load()
+    U, V = _words(U_words, d_out, r), _words(V_words, d_in, r)
+    so, si = _f64(s_out, d_out), _f64(s_in, d_in)
+    x = _x(x, d_in)
+    rows = np.ascontiguousarray(np.asarray(rows, dtype=np.int64))
+    assert rows.min() >= 0 and rows.max() < d_out
+    y = np.empty((x.shape[0], rows.size), dtype=np.float64)
+    L.nqo_forward_dense_rows(_ptr(U), _ptr(V), _ptr(so), _ptr(si), d_out, d_in, r, _ptr(x), x.shape[0],
+                             _ptr(rows), rows.size, _ptr(y))
+    return y
+
+
+def forward_factored(U_words, V_words, s_out, s_in, d_out, d_in, r, x, threads: int = 0,
+                     return_t: bool = False, return_threads: bool = False):
+    """Tier B.  threads=0 -> OpenMP default (all cores); 1 -> single thread."""
+    L = _load()
+    U, V = _words(U_words, d_out, r), _words(V_words, d_in, r)
+    so, si = _f64(s_out, d_out), _f64(s_in, d_in)
+    x = _x(x, d_in)
+    y = np.empty((x.shape[0], d_out), dtype=np.float64)
+    t = np.empty((x.shape[0], r), dtype=np.float64) if return_t else None
+    used = L.nqo_forward_factored(_ptr(U), _ptr(V), _ptr(so), _ptr(si), d_out, d_in, r, _ptr(x), x.shape[0],
+                                  _ptr(y), _ptr(t) if return_t else None, threads)
+    out = (y,)
+    if return_t:
+        out += (t,)
+    if return_threads:
+        out += (used,)
+    return out[0] if len(out) == 1 else out
+
+
+def layer_bits(d_out: int, d_in: int, r: int) -> int:
+    return int(_load().nqo_layer_bits(d_out, d_in, r))

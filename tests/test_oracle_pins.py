@@ -1,0 +1,305 @@
+"""Pins for the CPU oracle: it is checked against things other than itself.
+
+Every check here uses either (a) an independent library routine
+(numpy.packbits / numpy.unpackbits / numpy.matmul), (b) a closed form that the
+mathematics fixes, (c) complete enumeration in plain Python integers, or
+(d) a value printed in the paper (tests/golden/).  A dropped term, a wrong
+sign, a transposed operand or a wrong bit order in the oracle fails at least
+one of them.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2602_06694_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ---------- independent helpers (numpy library routines, not the oracle) ----------
+
+def np_unpack(words: np.ndarray, cols: int) -> np.ndarray:
+    """+-1 int8 matrix from packed words via numpy.unpackbits (LSB first)."""
+    rows = words.shape[0]
+    bits = np.unpackbits(words.view(np.uint8).reshape(rows, -1), axis=1, bitorder="little")[:, :cols]
+    return (2 * bits.astype(np.int8) - 1).astype(np.int8)
+
+
+def np_pack(pm1: np.ndarray) -> np.ndarray:
+    rows, cols = pm1.shape
+    wpr = (cols + 31) // 32
+    bits = np.zeros((rows, wpr * 32), dtype=np.uint8)
+    bits[:, :cols] = (pm1 > 0)
+    return np.packbits(bits, axis=1, bitorder="little").view(np.uint32).reshape(rows, wpr)
+
+
+def np_dense_forward(U, V, s_out, s_in, x):
+    """y = (diag(s_out) U V^T diag(s_in)) x with numpy.matmul in fp64."""
+    W = (s_out.astype(np.float64)[:, None] * (U.astype(np.float64) @ V.astype(np.float64).T)
+         * s_in.astype(np.float64)[None, :])
+    return x @ W.T
+
+
+def small_case(d_out, d_in, r, batch, seed):
+    rng = np.random.default_rng(seed)
+    U = synth.gen_signs_pm1(d_out, r, seed + 1)
+    V = synth.gen_signs_pm1(d_in, r, seed + 2)
+    s_out = synth.gen_scales(d_out, seed + 3)
+    s_in = synth.gen_scales(d_in, seed + 4)
+    x = rng.standard_normal((batch, d_in))
+    return U, V, s_out, s_in, x
+
+
+# ---------- packing ----------
+
+@pytest.mark.parametrize("cols", [1, 31, 32, 33, 63, 64, 65, 256, 3520])
+def test_pack_matches_numpy_packbits(cols):
+    pm1 = synth.gen_signs_pm1(7, cols, 100 + cols)
+    w = oracle.pack_signs(pm1)
+    assert w.dtype == np.uint32 and w.shape == (7, (cols + 31) // 32)
+    assert np.array_equal(w, np_pack(pm1))
+    assert np.array_equal(oracle.unpack_signs(w, cols), pm1)
+    assert np.array_equal(np_unpack(w, cols), pm1)
+
+
+def test_pack_bit_positions_and_padding():
+    # a single +1 at column k sets exactly bit k%32 of word k//32; pad bits stay 0
+    cols = 70
+    for k in (0, 1, 31, 32, 33, 63, 64, 69):
+        v = -np.ones((1, cols), dtype=np.int8)
+        v[0, k] = 1
+        w = oracle.pack_signs(v)
+        expect = np.zeros(3, dtype=np.uint32)
+        expect[k // 32] = np.uint32(1) << np.uint32(k % 32)
+        assert np.array_equal(w[0], expect), k
+    allp = oracle.pack_signs(np.ones((2, cols), dtype=np.int8))
+    assert np.array_equal(allp[0], np.array([0xFFFFFFFF, 0xFFFFFFFF, 0x3F], dtype=np.uint32))
+    alln = oracle.pack_signs(-np.ones((2, cols), dtype=np.int8))
+    assert not alln.any()
+
+
+def test_pack_sign_rule_for_floats():
+    # polarity of Fig. 2(c): -1 -> 0, +1 -> 1; ties: +0.0 and -0.0 -> +1
+    v = np.array([[-1.0, 1.0, 0.0, -0.0, -1e-30, 1e-30, -np.inf, np.inf]])
+    w = oracle.pack_signs(v)
+    assert w[0, 0] == 0b10101110
+    with pytest.raises(ValueError):
+        oracle.pack_signs(np.array([[1.0, np.nan]]))
+    with pytest.raises(ValueError):
+        oracle.pack_signs(np.array([[1, 0]], dtype=np.int8))
+    with pytest.raises(ValueError):
+        oracle.pack_signs(np.array([[1, 2]], dtype=np.int8))
+
+
+def test_generated_words_have_zero_padding_and_uniform_signs():
+    w = synth.gen_sign_words(64, 100, 5)
+    assert (w[:, -1] >> 4 == 0).all()
+    pm1 = np_unpack(synth.gen_sign_words(512, 512, 6), 512)
+    assert abs(pm1.mean()) < 0.01
+
+
+# ---------- forward: closed forms ----------
+
+def test_all_plus_one_closed_form():
+    d_out, d_in, r, batch = 37, 53, 45, 3
+    _, _, s_out, s_in, x = small_case(d_out, d_in, r, batch, 11)
+    ones_u = oracle.pack_signs(np.ones((d_out, r), dtype=np.int8))
+    ones_v = oracle.pack_signs(np.ones((d_in, r), dtype=np.int8))
+    neg_u = oracle.pack_signs(-np.ones((d_out, r), dtype=np.int8))
+    neg_v = oracle.pack_signs(-np.ones((d_in, r), dtype=np.int8))
+    so, si = s_out.astype(np.float64), s_in.astype(np.float64)
+    expect = so[None, :] * r * (x * si[None, :]).sum(axis=1, keepdims=True)
+    for fwd in (oracle.forward_dense, oracle.forward_factored):
+        y = fwd(ones_u, ones_v, s_out, s_in, d_out, d_in, r, x)
+        np.testing.assert_allclose(y, expect, rtol=1e-13, atol=0)
+        # all(-1) V flips the sign; all(-1) both leaves y unchanged
+        np.testing.assert_allclose(fwd(ones_u, neg_v, s_out, s_in, d_out, d_in, r, x), -expect, rtol=1e-13)
+        np.testing.assert_allclose(fwd(neg_u, neg_v, s_out, s_in, d_out, d_in, r, x), expect, rtol=1e-13)
+
+
+def test_rank_one_closed_form():
+    d_out, d_in = 19, 23
+    U, V, s_out, s_in, x = small_case(d_out, d_in, 1, 2, 21)
+    so, si = s_out.astype(np.float64), s_in.astype(np.float64)
+    inner = (x * (V[:, 0] * si)[None, :]).sum(axis=1, keepdims=True)
+    expect = (so * U[:, 0])[None, :] * inner
+    for fwd in (oracle.forward_dense, oracle.forward_factored):
+        y = fwd(oracle.pack_signs(U), oracle.pack_signs(V), s_out, s_in, d_out, d_in, 1, x)
+        np.testing.assert_allclose(y, expect, rtol=1e-13)
+
+
+def test_one_hot_extracts_columns_of_dense_weight():
+    d_out, d_in, r = 9, 14, 40
+    U, V, s_out, s_in, _ = small_case(d_out, d_in, r, 1, 31)
+    Uw, Vw = oracle.pack_signs(U), oracle.pack_signs(V)
+    W = oracle.dense_weight(Uw, Vw, s_out, s_in, d_out, d_in, r)
+    # element-wise definition of Eq. 1 in plain Python integers / floats
+    for i in (0, 4, d_out - 1):
+        for j in (0, 7, d_in - 1):
+            dot = sum(int(U[i, k]) * int(V[j, k]) for k in range(r))
+            assert W[i, j] == float(s_out[i]) * dot * float(s_in[j])
+    eye = np.eye(d_in)
+    for fwd in (oracle.forward_dense, oracle.forward_factored):
+        y = fwd(Uw, Vw, s_out, s_in, d_out, d_in, r, eye)      # y[j] = W[:, j]
+        np.testing.assert_allclose(y, W.T, rtol=1e-13, atol=1e-13)
+
+
+# ---------- forward: complete enumeration on tiny shapes ----------
+
+@pytest.mark.parametrize("shape", [(2, 2, 2), (3, 2, 1), (1, 3, 2)])
+def test_brute_force_all_sign_patterns_exact_integers(shape):
+    d_out, d_in, r = shape
+    s_out = np.array([1, 2, 3][:d_out], dtype=np.float16)
+    s_in = np.array([2, 1, 4][:d_in], dtype=np.float16)
+    x = np.array([[3, -2, 5][:d_in], [-1, 4, 2][:d_in]], dtype=np.float64)
+    nU, nV = d_out * r, d_in * r
+    for ubits in itertools.product((-1, 1), repeat=nU):
+        U = np.array(ubits, dtype=np.int8).reshape(d_out, r)
+        Uw = oracle.pack_signs(U)
+        for vbits in itertools.product((-1, 1), repeat=nV):
+            V = np.array(vbits, dtype=np.int8).reshape(d_in, r)
+            Vw = oracle.pack_signs(V)
+            expect = [[int(s_out[i]) * sum(sum(int(U[i, k]) * int(V[j, k]) for k in range(r))
+                                            * int(s_in[j]) * int(x[b, j]) for j in range(d_in))
+                       for i in range(d_out)] for b in range(2)]
+            ya = oracle.forward_dense(Uw, Vw, s_out, s_in, d_out, d_in, r, x)
+            yb = oracle.forward_factored(Uw, Vw, s_out, s_in, d_out, d_in, r, x)
+            assert ya.tolist() == expect and yb.tolist() == expect
+
+
+# ---------- forward: independent library reduction ----------
+
+@pytest.mark.parametrize("shape", [(33, 65, 31, 2), (128, 96, 64, 3), (70, 257, 100, 1)])
+def test_forward_matches_numpy_matmul(shape):
+    d_out, d_in, r, batch = shape
+    U, V, s_out, s_in, x = small_case(d_out, d_in, r, batch, 41 + d_out)
+    Uw, Vw = np_pack(U), np_pack(V)                      # packed by numpy, not by the oracle
+    ref = np_dense_forward(U, V, s_out, s_in, x)
+    scale = np.abs(ref).max()
+    ya = oracle.forward_dense(Uw, Vw, s_out, s_in, d_out, d_in, r, x)
+    yb, t = oracle.forward_factored(Uw, Vw, s_out, s_in, d_out, d_in, r, x, return_t=True)
+    assert np.abs(ya - ref).max() <= 1e-12 * scale
+    assert np.abs(yb - ref).max() <= 1e-12 * scale
+    t_ref = (x * s_in.astype(np.float64)[None, :]) @ V.astype(np.float64)
+    assert np.abs(t - t_ref).max() <= 1e-12 * np.abs(t_ref).max()
+    rows = np.array([0, d_out - 1, d_out // 2])
+    yr = oracle.forward_dense_rows(Uw, Vw, s_out, s_in, d_out, d_in, r, x, rows)
+    assert np.abs(yr - ref[:, rows]).max() <= 1e-12 * scale
+
+
+def test_config1_tier_a_equals_tier_b_and_numpy():
+    c = synth.CONFIGS[1]
+    shp = c.block[0]
+    L = synth.gen_layer(1, 0, 0, shp)
+    x = synth.x_as_f64(synth.gen_layer_x(1, 0, 0, shp, 1, c.x_dtype), c.x_dtype)
+    ya = oracle.forward_dense(L.U_words, L.V_words, L.s_out, L.s_in, shp.d_out, shp.d_in, shp.r, x)
+    yb = oracle.forward_factored(L.U_words, L.V_words, L.s_out, L.s_in, shp.d_out, shp.d_in, shp.r, x)
+    ref = np_dense_forward(np_unpack(L.U_words, shp.r), np_unpack(L.V_words, shp.r), L.s_out, L.s_in, x)
+    scale = np.abs(ref).max()
+    assert np.abs(ya - yb).max() <= 1e-12 * scale
+    assert np.abs(ya - ref).max() <= 1e-12 * scale
+
+
+def test_factored_single_thread_equals_multi_thread():
+    d_out, d_in, r, batch = 200, 300, 96, 2
+    U, V, s_out, s_in, x = small_case(d_out, d_in, r, batch, 77)
+    Uw, Vw = oracle.pack_signs(U), oracle.pack_signs(V)
+    y1, n1 = oracle.forward_factored(Uw, Vw, s_out, s_in, d_out, d_in, r, x, threads=1, return_threads=True)
+    yN, nN = oracle.forward_factored(Uw, Vw, s_out, s_in, d_out, d_in, r, x, threads=0, return_threads=True)
+    assert n1 == 1 and nN >= 1
+    assert np.array_equal(y1, yN)       # same summation order per output -> identical bits
+
+
+# ---------- metamorphic properties of the factorization ----------
+
+def test_metamorphic_properties():
+    d_out, d_in, r, batch = 40, 72, 50, 2
+    U, V, s_out, s_in, x = small_case(d_out, d_in, r, batch, 51)
+    args = (d_out, d_in, r)
+    Uw, Vw = oracle.pack_signs(U), oracle.pack_signs(V)
+    y = oracle.forward_factored(Uw, Vw, s_out, s_in, *args, x)
+    scale = np.abs(y).max()
+    # linearity in x
+    x2 = np.random.default_rng(1).standard_normal(x.shape)
+    y2 = oracle.forward_factored(Uw, Vw, s_out, s_in, *args, x2)
+    y12 = oracle.forward_factored(Uw, Vw, s_out, s_in, *args, 3.0 * x - 0.5 * x2)
+    assert np.abs(y12 - (3.0 * y - 0.5 * y2)).max() <= 1e-12 * scale
+    # scale invariance of the factorization (Appendix A: (eta U)(V / eta)^T): power of two -> exact
+    yq = oracle.forward_factored(Uw, Vw, (s_out * np.float16(2)), (s_in / np.float16(2)), *args, x)
+    assert np.array_equal(yq, y)
+    # flipping column k of both factors leaves U V^T unchanged
+    U2, V2 = U.copy(), V.copy()
+    U2[:, 7] *= -1
+    V2[:, 7] *= -1
+    yf = oracle.forward_dense(oracle.pack_signs(U2), oracle.pack_signs(V2), s_out, s_in, *args, x)
+    assert np.abs(yf - y).max() <= 1e-12 * scale
+    # flipping only U's column changes the result (the test above is not vacuous)
+    yg = oracle.forward_dense(oracle.pack_signs(U2), Vw, s_out, s_in, *args, x)
+    assert np.abs(yg - y).max() > 1e-6 * scale
+    # permuting the rank axis of both factors together leaves y unchanged
+    perm = np.random.default_rng(2).permutation(r)
+    yp = oracle.forward_factored(oracle.pack_signs(U[:, perm]), oracle.pack_signs(V[:, perm]), s_out, s_in, *args, x)
+    assert np.abs(yp - y).max() <= 1e-12 * scale
+    # transposition guard: s_in scales columns of the dense weight, s_out its rows
+    W = oracle.dense_weight(Uw, Vw, s_out, s_in, *args)
+    assert W.shape == (d_out, d_in)
+    np.testing.assert_allclose(W[3, 5] / W[3, 6],
+                               (float(s_in[5]) * (U[3] @ V[5].astype(np.int64)))
+                               / (float(s_in[6]) * (U[3] @ V[6].astype(np.int64))), rtol=1e-12)
+
+
+# ---------- storage accounting against values the paper prints ----------
+
+def _golden():
+    out = {}
+    with open(os.path.join(GOLDEN, "model_sizes.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                k, v, tol = line.split()[:3]
+                out[k] = (float(v), float(tol))
+    return out
+
+
+def _model_linear_weights(block, n_layers):
+    return n_layers * sum(s.d_out * s.d_in for s in block)
+
+
+def test_storage_formula_and_paper_model_sizes():
+    g = _golden()
+    # formula r(n+m) + 16(n+m) (Appendix E.4)
+    assert oracle.layer_bits(4096, 4096, 1024) == 1024 * 8192 + 16 * 8192
+    for s in synth.llama2_70b_block():
+        assert oracle.layer_bits(s.d_out, s.d_in, s.r) == s.weight_bits
+    emb = {7: 2 * 32000 * 4096 * 2, 70: 2 * 32000 * 8192 * 2}      # bytes: embedding + head, 16-bit
+    n7 = _model_linear_weights(synth.llama2_7b_block(), 32)
+    n70 = _model_linear_weights(synth.llama2_70b_block(), 80)
+    v, tol = g["llama2_7b_bf16_gb"]
+    assert abs((2 * n7 + emb[7]) / 1e9 - v) <= tol
+    v, tol = g["llama2_70b_bf16_gb"]
+    assert abs((2 * n70 + emb[70]) / 1e9 - v) <= tol
+    # 1-bit: the largest integer rank with BPW <= 1 in every layer
+    bits = 0
+    for s in synth.llama2_7b_block():
+        r = (s.d_out * s.d_in) // (s.d_out + s.d_in) - 16
+        assert oracle.layer_bits(s.d_out, s.d_in, r) <= s.d_out * s.d_in < oracle.layer_bits(s.d_out, s.d_in, r + 1)
+        bits += 32 * oracle.layer_bits(s.d_out, s.d_in, r)
+    v, tol = g["llama2_7b_1bit_gb"]
+    assert abs((bits / 8 + emb[7]) / 1e9 - v) <= tol
+    # 0.55 bit on Llama-2-70B
+    v, tol = g["llama2_70b_0p55bit_gb"]
+    assert abs((0.55 * n70 / 8 + emb[70]) / 1e9 - v) <= tol
+    # the synthetic 70B ranks used here land at the same footprint scale (0.55-0.56 bit)
+    ours = 80 * sum(oracle.layer_bits(s.d_out, s.d_in, s.r) for s in synth.llama2_70b_block())
+    assert 0.55 <= ours / n70 <= 0.565
+    v, tol = g["plain_binary_bpw"]
+    assert v == 1.0
+
+
+def test_config_bpw_values():
+    expect = {(4096, 4096, 1024): 0.5078, (1024, 1024, 256): 0.5312, (11008, 4096, 1664): 0.5628,
+              (8192, 8192, 2240): 0.5508, (28672, 8192, 3520): 0.5550}
+    for (n, m, r), bpw in expect.items():
+        assert abs(oracle.layer_bits(n, m, r) / (n * m) - bpw) < 5e-5

@@ -1,0 +1,162 @@
+/*
+ * nq_binlr.h -- C ABI of the MI355X (gfx950) library for the forward pass of a
+ * NanoQuant low-rank binary factorized linear layer.
+ *
+ * Operation (quantization scheme, Section 3.1, Eq. 1; restated with diagonal
+ * matrices in Appendix E.4, "NanoQuant (Ours)"):
+ *
+ *     W^ = Diag(s_out) . U . V^T . Diag(s_in),   U in {-1,+1}^{d_out x r},
+ *                                                V in {-1,+1}^{d_in  x r},
+ *     y[b, :] = W^ . x[b, :]  evaluated as  s_out (.) ( U . ( V^T . ( s_in (.) x[b, :] ) ) )
+ *
+ * i.e. the two scale vectors act only at the input and output boundary and the
+ * two binary products run back to back (Section 3.3, Step 2, last sentence).
+ * s_out is the paper's output-channel scale s1, s_in its input-channel scale
+ * s2.  There is no bias.
+ *
+ * Canonical packed sign format (the interchange format of this ABI).  The
+ * paper fixes the polarity (Fig. 2(c): -1 -> bit 0, +1 -> bit 1) but neither
+ * word size nor bit order; this library uses: row-major over the factor's
+ * rows (U: d_out rows, V: d_in rows), packed along the rank axis, rank index
+ * k lives in 32-bit word k/32 of its row at bit position k%32 counted from
+ * the least significant bit, words little-endian, each row padded to a whole
+ * word with 0 bits.  The layout in device memory is private to the library.
+ *
+ * Conventions
+ *  - every function returns an int status (NQ_OK = 0, errors negative), never
+ *    throws, never aborts;  nq_last_error_string() describes the most recent
+ *    failure on the calling thread;
+ *  - "host" / "device" is stated for every pointer;  the caller owns every
+ *    buffer it passes in, the library copies what it keeps;
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Functions taking a stream only enqueue work and do not synchronise,
+ *    unless stated otherwise;
+ *  - batched activations are row-major contiguous: x[batch][d_in],
+ *    y[batch][d_out].
+ *  - a token whose input holds a NaN or an infinity yields NaN in every output
+ *    of that token (other tokens are unaffected).
+ */
+#ifndef NQ_BINLR_H
+#define NQ_BINLR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* status codes */
+#define NQ_OK             0
+#define NQ_E_INVALID_ARG (-1)  /* a value is not acceptable (NaN sign, int8 not +-1, bad dtype, batch < 1 ...) */
+#define NQ_E_SHAPE       (-2)  /* a dimension is < 1 or beyond what the kernels support */
+#define NQ_E_ALIGN       (-3)  /* a device pointer is not 16-byte aligned */
+#define NQ_E_NULL        (-4)  /* a required pointer is NULL */
+#define NQ_E_UNSUPPORTED (-5)  /* valid request that this build does not implement */
+#define NQ_E_HIP         (-6)  /* a HIP runtime call failed (see nq_last_error_string) */
+
+/* element types */
+#define NQ_I8   0   /* int8, values must be exactly -1 or +1 (pack input only) */
+#define NQ_F32  1
+#define NQ_F16  2   /* IEEE binary16 */
+#define NQ_BF16 3
+
+/* nq_binlr_create flags */
+#define NQ_FLAG_DEFAULT      0u
+#define NQ_FLAG_DECODE_VALU  1u  /* batch < 64 runs the plain fp32 vector-ALU kernels instead of the
+                                    fixed-point matrix-core kernels (slow; a second implementation
+                                    kept for cross-checks and as the paper-style "mask + FMA" GEMV) */
+#define NQ_FLAG_NO_PREFILL   2u  /* never take the dense MFMA path: batch >= 64 is run as chunks of 8 */
+
+typedef struct nq_binlr_s* nq_handle;   /* one factorized layer resident on one GPU */
+typedef struct nq_plan_s*  nq_plan;     /* a fixed list of independent forwards */
+
+/* Largest d_in, d_out or r accepted (exactness of the 32-bit accumulators). */
+#define NQ_MAX_DIM 65536
+/* Largest batch served by the streaming (decode) kernels in one pass. */
+#define NQ_DECODE_MAX_BATCH 8
+/* Batches at or above this take the dense matrix-core (prefill) path. */
+#define NQ_PREFILL_MIN_BATCH 64
+
+/* ---- packing (Algorithm 1, PackBinary; Fig. 2(c)) -- host only, no GPU needed ---- */
+
+/* Number of uint32 words of a packed [rows, cols] sign matrix: rows * ceil(cols/32). */
+size_t nq_packed_words(int64_t rows, int64_t cols);
+
+/* signs: host, [rows, cols] row-major of `dtype` (NQ_I8, NQ_F32, NQ_F16, NQ_BF16).
+ * out_words: host, nq_packed_words(rows, cols) words, fully overwritten.
+ * bit = 1 iff value >= 0 (both zeros -> +1), bit = 0 iff value < 0.
+ * NaN, or an int8 other than +-1 -> NQ_E_INVALID_ARG (out_words unspecified). */
+int nq_pack_signs(const void* signs, int dtype, int64_t rows, int64_t cols, uint32_t* out_words);
+
+/* Exact inverse on the first `cols` bits of every row. out_pm1: host int8 [rows, cols]. */
+int nq_unpack_signs(const uint32_t* words, int64_t rows, int64_t cols, int8_t* out_pm1);
+
+/* ---- layer objects ---- */
+
+/* Build a layer on the current HIP device.
+ * U_words: host, canonical [d_out, ceil(r/32)];  V_words: host, canonical [d_in, ceil(r/32)];
+ * s_out_fp16: host, d_out IEEE binary16 values;  s_in_fp16: host, d_in values.
+ * x_dtype: NQ_F32, NQ_F16 or NQ_BF16;  y_dtype: NQ_F32 (the only output type built).
+ * Copies everything, rearranges the bits on the GPU, and synchronises the device.
+ * Any r, d_in, d_out in [1, NQ_MAX_DIM] is accepted (tails are padded inside).
+ * Workspace for batch <= NQ_DECODE_MAX_BATCH is allocated here. */
+int nq_binlr_create(nq_handle* out, int64_t d_out, int64_t d_in, int64_t r,
+                    const uint32_t* U_words, const uint32_t* V_words,
+                    const uint16_t* s_out_fp16, const uint16_t* s_in_fp16,
+                    int x_dtype, int y_dtype, uint32_t flags);
+
+/* Grow the per-layer workspace so that forwards with batch <= max_batch allocate nothing.
+ * May allocate and synchronise. */
+int nq_binlr_reserve(nq_handle h, int max_batch);
+
+/* y = s_out (.) (U (V^T (s_in (.) x))) for `batch` tokens (Eq. 1).
+ * x: device, [batch, d_in] of x_dtype;  y: device, [batch, d_out] float32; both 16-byte
+ * aligned, must not overlap.  Asynchronous on `stream`.  Allocates nothing when
+ * batch <= the reserved batch (otherwise it reserves first, which synchronises).
+ * Not re-entrant on one handle (the handle's workspace is shared); different
+ * handles may run concurrently on different streams.
+ * batch <= 8: streaming kernels; 9..63: chunks of 8; >= 64: dense MFMA path. */
+int nq_binlr_forward(nq_handle h, const void* x, void* y, int batch, void* stream);
+
+/* n independent forwards (same batch <= NQ_DECODE_MAX_BATCH) in four launches in total:
+ * the streaming kernels walk a work list that covers all n layers, so small
+ * layers do not pay one launch each.  hs/xs/ys: host arrays of n entries; xs[i]/ys[i]
+ * device pointers as in nq_binlr_forward.  A handle may appear only once.
+ * The list is compiled into an internal plan that is cached while the
+ * arguments repeat (compiling allocates and synchronises; replays do not). */
+int nq_binlr_forward_many(const nq_handle* hs, const void* const* xs, void* const* ys,
+                          int n, int batch, void* stream);
+
+/* The same, with the plan made explicit. */
+int nq_plan_create(nq_plan* out, const nq_handle* hs, const void* const* xs, void* const* ys,
+                   int n, int batch);
+int nq_plan_forward(nq_plan p, void* stream);
+/* Runs the plan once with HIP events between its kernels, waits for it, and returns the
+ * duration of each kernel in milliseconds:
+ * ms[0] input quantisation, ms[1] stage 1 (t = V^T x'), ms[2] quantisation of t,
+ * ms[3] stage 2 (y = s_out (.) U t).  Synchronises `stream`. */
+int nq_plan_forward_timed(nq_plan p, void* stream, float ms[4]);
+int nq_plan_destroy(nq_plan p);
+
+int nq_binlr_destroy(nq_handle h);
+
+/* Bytes of the stored factorization: r(d_in+d_out)/8 + 2(d_in+d_out), i.e. the bit count
+ * r(n+m) + 16(n+m) of Appendix E.4 divided by 8 (padding not counted). 0 for NULL. */
+size_t nq_binlr_weight_bytes(nq_handle h);
+
+/* Debug: convert the device-resident bits back to canonical words (host buffers sized as
+ * in nq_binlr_create).  Synchronises.  Either pointer may be NULL to skip that factor. */
+int nq_binlr_export_words(nq_handle h, uint32_t* U_words, uint32_t* V_words);
+
+/* Debug: copy the intermediate t = V^T (s_in (.) x) of the most recent batch<=8 forward
+ * on this handle to host float32 [batch, r].  Synchronises the device. */
+int nq_binlr_read_intermediate(nq_handle h, float* t_host, int batch);
+
+const char* nq_status_string(int status);
+const char* nq_last_error_string(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NQ_BINLR_H */

@@ -1,0 +1,219 @@
+"""ctypes binding of libnq_binlr.so -- argument marshalling only.
+
+Every function has the name of the C entry point it calls (see
+``include/nq_binlr.h``).  Device buffers are passed as ``torch`` CUDA tensors
+(or raw integer addresses); the stream defaults to torch's current stream.
+Nothing is computed here, and there is no fallback: if the shared library has
+not been built, importing symbols from it raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+NQ_OK = 0
+NQ_E_INVALID_ARG, NQ_E_SHAPE, NQ_E_ALIGN, NQ_E_NULL, NQ_E_UNSUPPORTED, NQ_E_HIP = -1, -2, -3, -4, -5, -6
+NQ_I8, NQ_F32, NQ_F16, NQ_BF16 = 0, 1, 2, 3
+NQ_FLAG_DEFAULT, NQ_FLAG_DECODE_VALU, NQ_FLAG_NO_PREFILL = 0, 1, 2
+NQ_MAX_DIM = 65536
+NQ_DECODE_MAX_BATCH = 8
+NQ_PREFILL_MIN_BATCH = 64
+
+DTYPE_BY_NAME = {"f32": NQ_F32, "f16": NQ_F16, "bf16": NQ_BF16, "i8": NQ_I8}
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libnq_binlr.so")
+_lib = None
+
+
+class NQError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"nq status {status}: {message}")
+        self.status = status
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded shared library (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2602_06694_amd.build` "
+                              "(there is no CPU fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, ci, u32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_uint32
+        L.nq_packed_words.argtypes = [i64, i64]; L.nq_packed_words.restype = ctypes.c_size_t
+        L.nq_pack_signs.argtypes = [vp, ci, i64, i64, vp]; L.nq_pack_signs.restype = ci
+        L.nq_unpack_signs.argtypes = [vp, i64, i64, vp]; L.nq_unpack_signs.restype = ci
+        L.nq_binlr_create.argtypes = [ctypes.POINTER(vp), i64, i64, i64, vp, vp, vp, vp, ci, ci, u32]
+        L.nq_binlr_create.restype = ci
+        L.nq_binlr_reserve.argtypes = [vp, ci]; L.nq_binlr_reserve.restype = ci
+        L.nq_binlr_forward.argtypes = [vp, vp, vp, ci, vp]; L.nq_binlr_forward.restype = ci
+        L.nq_binlr_forward_many.argtypes = [vp, vp, vp, ci, ci, vp]; L.nq_binlr_forward_many.restype = ci
+        L.nq_plan_create.argtypes = [ctypes.POINTER(vp), vp, vp, vp, ci, ci]; L.nq_plan_create.restype = ci
+        L.nq_plan_forward.argtypes = [vp, vp]; L.nq_plan_forward.restype = ci
+        L.nq_plan_forward_timed.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_float)]; L.nq_plan_forward_timed.restype = ci
+        L.nq_plan_destroy.argtypes = [vp]; L.nq_plan_destroy.restype = ci
+        L.nq_binlr_destroy.argtypes = [vp]; L.nq_binlr_destroy.restype = ci
+        L.nq_binlr_weight_bytes.argtypes = [vp]; L.nq_binlr_weight_bytes.restype = ctypes.c_size_t
+        L.nq_binlr_export_words.argtypes = [vp, vp, vp]; L.nq_binlr_export_words.restype = ci
+        L.nq_binlr_read_intermediate.argtypes = [vp, vp, ci]; L.nq_binlr_read_intermediate.restype = ci
+        L.nq_status_string.argtypes = [ci]; L.nq_status_string.restype = ctypes.c_char_p
+        L.nq_last_error_string.argtypes = []; L.nq_last_error_string.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(status: int) -> None:
+    if status != NQ_OK:
+        L = lib()
+        raise NQError(status, f"{L.nq_status_string(status).decode()}: {L.nq_last_error_string().decode()}")
+
+
+def _np_ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _dev_ptr(t) -> Optional[int]:
+    """Address of a device buffer: torch tensor, int, or None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if not t.is_cuda:
+        raise ValueError("expected a device (cuda) tensor")
+    if not t.is_contiguous():
+        raise ValueError("expected a contiguous tensor")
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def nq_status_string(status: int) -> str:
+    return lib().nq_status_string(status).decode()
+
+
+def nq_last_error_string() -> str:
+    return lib().nq_last_error_string().decode()
+
+
+def nq_packed_words(rows: int, cols: int) -> int:
+    return int(lib().nq_packed_words(rows, cols))
+
+
+def nq_pack_signs(signs: np.ndarray, dtype: Optional[int] = None) -> np.ndarray:
+    """signs: host [rows, cols]; int8 (+-1), float32, float16, or uint16 holding bf16 bits
+    (then pass dtype=NQ_BF16).  Returns canonical uint32 [rows, ceil(cols/32)]."""
+    if signs.ndim != 2:
+        raise ValueError("signs must be 2-D")
+    if dtype is None:
+        dtype = {np.dtype(np.int8): NQ_I8, np.dtype(np.float32): NQ_F32, np.dtype(np.float16): NQ_F16}.get(signs.dtype)
+        if dtype is None:
+            raise ValueError(f"cannot infer NQ dtype from {signs.dtype}")
+    a = np.ascontiguousarray(signs)
+    rows, cols = a.shape
+    out = np.empty((rows, (cols + 31) // 32), dtype=np.uint32)
+    _check(lib().nq_pack_signs(_np_ptr(a), dtype, rows, cols, _np_ptr(out)))
+    return out
+
+
+def nq_unpack_signs(words: np.ndarray, cols: int) -> np.ndarray:
+    w = np.ascontiguousarray(words, dtype=np.uint32)
+    rows = w.shape[0]
+    if w.shape != (rows, (cols + 31) // 32):
+        raise ValueError("words has the wrong shape")
+    out = np.empty((rows, cols), dtype=np.int8)
+    _check(lib().nq_unpack_signs(_np_ptr(w), rows, cols, _np_ptr(out)))
+    return out
+
+
+def nq_binlr_create(d_out: int, d_in: int, r: int, U_words: np.ndarray, V_words: np.ndarray,
+                    s_out: np.ndarray, s_in: np.ndarray, x_dtype: int, y_dtype: int = NQ_F32,
+                    flags: int = NQ_FLAG_DEFAULT) -> int:
+    """Returns the opaque handle (an integer address)."""
+    wpr = (r + 31) // 32
+    U = np.ascontiguousarray(U_words, dtype=np.uint32)
+    V = np.ascontiguousarray(V_words, dtype=np.uint32)
+    so = np.ascontiguousarray(s_out, dtype=np.float16)
+    si = np.ascontiguousarray(s_in, dtype=np.float16)
+    if U.shape != (d_out, wpr) or V.shape != (d_in, wpr) or so.shape != (d_out,) or si.shape != (d_in,):
+        raise ValueError("argument shapes do not match d_out, d_in, r")
+    h = ctypes.c_void_p()
+    _check(lib().nq_binlr_create(ctypes.byref(h), d_out, d_in, r, _np_ptr(U), _np_ptr(V), _np_ptr(so), _np_ptr(si),
+                                 x_dtype, y_dtype, flags))
+    return h.value
+
+
+def nq_binlr_reserve(h: int, max_batch: int) -> None:
+    _check(lib().nq_binlr_reserve(h, max_batch))
+
+
+def nq_binlr_forward(h: int, x, y, batch: int, stream=None) -> None:
+    _check(lib().nq_binlr_forward(h, _dev_ptr(x), _dev_ptr(y), batch, _stream(stream)))
+
+
+def _ptr_array(vals: Sequence[Optional[int]]):
+    arr = (ctypes.c_void_p * len(vals))(*vals)
+    return arr
+
+
+def nq_binlr_forward_many(hs: Sequence[int], xs: Sequence, ys: Sequence, batch: int, stream=None) -> None:
+    n = len(hs)
+    if len(xs) != n or len(ys) != n:
+        raise ValueError("hs, xs, ys must have the same length")
+    _check(lib().nq_binlr_forward_many(_ptr_array(list(hs)), _ptr_array([_dev_ptr(x) for x in xs]),
+                                       _ptr_array([_dev_ptr(y) for y in ys]), n, batch, _stream(stream)))
+
+
+def nq_plan_create(hs: Sequence[int], xs: Sequence, ys: Sequence, batch: int) -> int:
+    n = len(hs)
+    if len(xs) != n or len(ys) != n:
+        raise ValueError("hs, xs, ys must have the same length")
+    p = ctypes.c_void_p()
+    _check(lib().nq_plan_create(ctypes.byref(p), _ptr_array(list(hs)), _ptr_array([_dev_ptr(x) for x in xs]),
+                                _ptr_array([_dev_ptr(y) for y in ys]), n, batch))
+    return p.value
+
+
+def nq_plan_forward(p: int, stream=None) -> None:
+    _check(lib().nq_plan_forward(p, _stream(stream)))
+
+
+def nq_plan_forward_timed(p: int, stream=None) -> List[float]:
+    ms = (ctypes.c_float * 4)()
+    _check(lib().nq_plan_forward_timed(p, _stream(stream), ms))
+    return [float(v) for v in ms]
+
+
+def nq_plan_destroy(p: Optional[int]) -> None:
+    _check(lib().nq_plan_destroy(p))
+
+
+def nq_binlr_destroy(h: Optional[int]) -> None:
+    _check(lib().nq_binlr_destroy(h))
+
+
+def nq_binlr_weight_bytes(h: Optional[int]) -> int:
+    return int(lib().nq_binlr_weight_bytes(h))
+
+
+def nq_binlr_export_words(h: int, d_out: int, d_in: int, r: int):
+    wpr = (r + 31) // 32
+    U = np.empty((d_out, wpr), dtype=np.uint32)
+    V = np.empty((d_in, wpr), dtype=np.uint32)
+    _check(lib().nq_binlr_export_words(h, _np_ptr(U), _np_ptr(V)))
+    return U, V
+
+
+def nq_binlr_read_intermediate(h: int, r: int, batch: int) -> np.ndarray:
+    t = np.empty((batch, r), dtype=np.float32)
+    _check(lib().nq_binlr_read_intermediate(h, _np_ptr(t), batch))
+    return t

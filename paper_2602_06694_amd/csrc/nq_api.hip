@@ -1,0 +1,581 @@
+// C ABI of libnq_binlr: host-side packing, layer handles, plans.  See include/nq_binlr.h.
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "nq_internal.h"
+
+namespace nq {
+
+static thread_local std::string g_last_error;
+
+void set_error(const std::string& msg) { g_last_error = msg; }
+
+int hip_fail(hipError_t e, const char* what, const char* file, int line)
+{
+    char buf[512];
+    snprintf(buf, sizeof buf, "HIP error %d (%s) in %s at %s:%d", (int)e, hipGetErrorString(e), what, file, line);
+    set_error(buf);
+    return NQ_E_HIP;
+}
+
+static int fail(int code, const char* msg)
+{
+    set_error(msg);
+    return code;
+}
+
+static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+static size_t dtype_size(int dt) { return dt == NQ_F32 ? 4 : 2; }
+
+}  // namespace nq
+
+using namespace nq;
+
+// ---------------------------------------------------------------------------------------------
+struct nq_binlr_s {
+    int64_t d_out, d_in, r;
+    int x_dtype, y_dtype;
+    uint32_t flags;
+    int device;
+    // weights (one allocation)
+    void* w_alloc;
+    uint32_t* vt_tiles;   // A = V^T : M = r,     N = d_in
+    uint32_t* u_tiles;    // A = U   : M = d_out, N = r
+    uint16_t* s_in;
+    uint16_t* s_out;
+    // decode workspace (one allocation, sized for NQ_DECODE_MAX_BATCH, never reallocated)
+    void* ws_alloc;
+    uint8_t* bq_x;
+    uint8_t* bq_t;
+    QMeta* meta_x;
+    QMeta* meta_t;
+    float* t;             // [8][t_stride]
+    int t_stride;
+    // prefill workspace (grown by reserve)
+    void* pf_alloc;
+    size_t pf_bytes;
+    int pf_batch;
+};
+
+struct nq_plan_s {
+    int n, batch, device;
+    void* alloc;
+    QuantDesc* qx;
+    StageDesc* s1;
+    QuantDesc* qt;
+    StageDesc* s2;
+    WorkItem* items1;
+    WorkItem* items2;
+    int n_items1, n_items2;
+    std::vector<nq_handle> handles;
+    hipEvent_t ev[5];
+    bool have_events;
+};
+
+// ---------------------------------------------------------------------------------------------
+// packing (host)
+// ---------------------------------------------------------------------------------------------
+extern "C" size_t nq_packed_words(int64_t rows, int64_t cols)
+{
+    if (rows < 0 || cols < 0) return 0;
+    return (size_t)rows * (size_t)((cols + 31) / 32);
+}
+
+static inline float half_to_float_host(uint16_t h)
+{
+    uint32_t sign = (uint32_t)(h >> 15) << 31, ex = (h >> 10) & 31u, man = h & 1023u;
+    uint32_t bits;
+    if (ex == 0) {
+        if (man == 0) bits = sign;
+        else {                                   // subnormal: value = man * 2^-24
+            float f = (float)man * 5.9604644775390625e-8f;
+            memcpy(&bits, &f, 4);
+            bits |= sign;
+        }
+    } else if (ex == 31) bits = sign | 0x7F800000u | (man << 13);
+    else bits = sign | ((ex + 112u) << 23) | (man << 13);
+    float f;
+    memcpy(&f, &bits, 4);
+    return f;
+}
+
+extern "C" int nq_pack_signs(const void* signs, int dtype, int64_t rows, int64_t cols, uint32_t* out_words)
+{
+    if (!signs || !out_words) return fail(NQ_E_NULL, "nq_pack_signs: NULL pointer");
+    if (rows < 1 || cols < 1) return fail(NQ_E_SHAPE, "nq_pack_signs: rows and cols must be >= 1");
+    if (dtype != NQ_I8 && dtype != NQ_F32 && dtype != NQ_F16 && dtype != NQ_BF16)
+        return fail(NQ_E_INVALID_ARG, "nq_pack_signs: unknown dtype");
+    const int64_t wpr = (cols + 31) / 32;
+    for (int64_t i = 0; i < rows; ++i) {
+        uint32_t* dst = out_words + i * wpr;
+        for (int64_t w = 0; w < wpr; ++w) {
+            uint32_t word = 0;
+            const int64_t k0 = w * 32, k1 = std::min<int64_t>(cols, k0 + 32);
+            for (int64_t k = k0; k < k1; ++k) {
+                const int64_t idx = i * cols + k;
+                bool plus;
+                if (dtype == NQ_I8) {
+                    int8_t v = ((const int8_t*)signs)[idx];
+                    if (v != 1 && v != -1) return fail(NQ_E_INVALID_ARG, "nq_pack_signs: int8 sign is not +-1");
+                    plus = v > 0;
+                } else {
+                    float v;
+                    if (dtype == NQ_F32) v = ((const float*)signs)[idx];
+                    else if (dtype == NQ_F16) v = half_to_float_host(((const uint16_t*)signs)[idx]);
+                    else {
+                        uint32_t b = (uint32_t)((const uint16_t*)signs)[idx] << 16;
+                        memcpy(&v, &b, 4);
+                    }
+                    if (std::isnan(v)) return fail(NQ_E_INVALID_ARG, "nq_pack_signs: NaN has no sign");
+                    plus = v >= 0.0f;
+                }
+                if (plus) word |= 1u << (k - k0);
+            }
+            dst[w] = word;
+        }
+    }
+    return NQ_OK;
+}
+
+extern "C" int nq_unpack_signs(const uint32_t* words, int64_t rows, int64_t cols, int8_t* out_pm1)
+{
+    if (!words || !out_pm1) return fail(NQ_E_NULL, "nq_unpack_signs: NULL pointer");
+    if (rows < 1 || cols < 1) return fail(NQ_E_SHAPE, "nq_unpack_signs: rows and cols must be >= 1");
+    const int64_t wpr = (cols + 31) / 32;
+    for (int64_t i = 0; i < rows; ++i)
+        for (int64_t k = 0; k < cols; ++k)
+            out_pm1[i * cols + k] = ((words[i * wpr + (k >> 5)] >> (k & 31)) & 1u) ? (int8_t)1 : (int8_t)-1;
+    return NQ_OK;
+}
+
+extern "C" const char* nq_status_string(int status)
+{
+    switch (status) {
+        case NQ_OK: return "ok";
+        case NQ_E_INVALID_ARG: return "invalid argument";
+        case NQ_E_SHAPE: return "bad shape";
+        case NQ_E_ALIGN: return "pointer not 16-byte aligned";
+        case NQ_E_NULL: return "null pointer";
+        case NQ_E_UNSUPPORTED: return "unsupported";
+        case NQ_E_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+extern "C" const char* nq_last_error_string(void) { return g_last_error.c_str(); }
+
+// ---------------------------------------------------------------------------------------------
+// handles
+// ---------------------------------------------------------------------------------------------
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+static void free_handle(nq_handle h)
+{
+    if (!h) return;
+    if (h->w_alloc) (void)hipFree(h->w_alloc);
+    if (h->ws_alloc) (void)hipFree(h->ws_alloc);
+    if (h->pf_alloc) (void)hipFree(h->pf_alloc);
+    delete h;
+}
+
+static std::mutex g_cache_mutex;
+static nq_plan g_cached_plan = nullptr;
+static std::vector<const void*> g_cached_key;
+static void drop_cached_plan_locked();
+
+extern "C" int nq_binlr_create(nq_handle* out, int64_t d_out, int64_t d_in, int64_t r, const uint32_t* U_words,
+                               const uint32_t* V_words, const uint16_t* s_out_fp16, const uint16_t* s_in_fp16,
+                               int x_dtype, int y_dtype, uint32_t flags)
+{
+    if (!out) return fail(NQ_E_NULL, "nq_binlr_create: out is NULL");
+    *out = nullptr;
+    if (d_out < 1 || d_in < 1 || r < 1) return fail(NQ_E_SHAPE, "nq_binlr_create: d_out, d_in, r must be >= 1");
+    if (d_out > NQ_MAX_DIM || d_in > NQ_MAX_DIM || r > NQ_MAX_DIM)
+        return fail(NQ_E_SHAPE, "nq_binlr_create: dimension exceeds NQ_MAX_DIM");
+    if (!U_words || !V_words || !s_out_fp16 || !s_in_fp16) return fail(NQ_E_NULL, "nq_binlr_create: NULL input");
+    if (x_dtype != NQ_F32 && x_dtype != NQ_F16 && x_dtype != NQ_BF16)
+        return fail(NQ_E_INVALID_ARG, "nq_binlr_create: x_dtype must be NQ_F32, NQ_F16 or NQ_BF16");
+    if (y_dtype == NQ_F16 || y_dtype == NQ_BF16)
+        return fail(NQ_E_UNSUPPORTED, "nq_binlr_create: only NQ_F32 output is built");
+    if (y_dtype != NQ_F32) return fail(NQ_E_INVALID_ARG, "nq_binlr_create: bad y_dtype");
+    if (flags & ~(NQ_FLAG_DECODE_VALU | NQ_FLAG_NO_PREFILL)) return fail(NQ_E_INVALID_ARG, "nq_binlr_create: unknown flag");
+
+    nq_handle h = new (std::nothrow) nq_binlr_s();
+    if (!h) return fail(NQ_E_HIP, "nq_binlr_create: out of host memory");
+    memset(h, 0, sizeof *h);
+    h->d_out = d_out; h->d_in = d_in; h->r = r;
+    h->x_dtype = x_dtype; h->y_dtype = y_dtype; h->flags = flags;
+    hipError_t e = hipGetDevice(&h->device);
+    if (e != hipSuccess) { delete h; return hip_fail(e, "hipGetDevice", __FILE__, __LINE__); }
+
+    const int64_t wpr = (r + 31) / 32;
+    const size_t vt_bytes = tile_words(r, d_in) * 4, u_bytes = tile_words(d_out, r) * 4;
+    const size_t sin_bytes = align_up((size_t)d_in * 2, 256), sout_bytes = align_up((size_t)d_out * 2, 256);
+    const size_t w_total = vt_bytes + u_bytes + sin_bytes + sout_bytes;
+
+    // decode workspace
+    const int mb = NQ_DECODE_MAX_BATCH;
+    const int nc = ncols_for(mb);
+    const size_t bqx_bytes = align_up((size_t)n_steps(d_in) * 4 * nc * 16, 256);
+    const size_t bqt_bytes = align_up((size_t)n_steps(r) * 4 * nc * 16, 256);
+    const size_t meta_bytes = align_up(sizeof(QMeta) * mb, 256);
+    h->t_stride = (int)round_up(r, kTileRows);
+    const size_t t_bytes = align_up((size_t)mb * h->t_stride * 4, 256);
+    const size_t ws_total = bqx_bytes + bqt_bytes + 2 * meta_bytes + t_bytes;
+
+    uint32_t* d_canon = nullptr;
+    const size_t canon_u = (size_t)d_out * wpr * 4, canon_v = (size_t)d_in * wpr * 4;
+    int rc = NQ_OK;
+#define CREATE_HIP(call)                                                   \
+    do {                                                                   \
+        hipError_t e__ = (call);                                           \
+        if (e__ != hipSuccess) {                                           \
+            rc = hip_fail(e__, #call, __FILE__, __LINE__);                 \
+            goto done;                                                     \
+        }                                                                  \
+    } while (0)
+    CREATE_HIP(hipMalloc(&h->w_alloc, w_total));
+    CREATE_HIP(hipMalloc(&h->ws_alloc, ws_total));
+    CREATE_HIP(hipMalloc((void**)&d_canon, std::max(canon_u, canon_v)));
+    {
+        char* p = (char*)h->w_alloc;
+        h->vt_tiles = (uint32_t*)p; p += vt_bytes;
+        h->u_tiles = (uint32_t*)p; p += u_bytes;
+        h->s_in = (uint16_t*)p; p += sin_bytes;
+        h->s_out = (uint16_t*)p;
+        char* q = (char*)h->ws_alloc;
+        h->bq_x = (uint8_t*)q; q += bqx_bytes;
+        h->bq_t = (uint8_t*)q; q += bqt_bytes;
+        h->meta_x = (QMeta*)q; q += meta_bytes;
+        h->meta_t = (QMeta*)q; q += meta_bytes;
+        h->t = (float*)q;
+    }
+    CREATE_HIP(hipMemset(h->ws_alloc, 0, ws_total));
+    CREATE_HIP(hipMemcpy(d_canon, V_words, canon_v, hipMemcpyHostToDevice));
+    rc = launch_repack(d_canon, wpr, true, r, d_in, h->vt_tiles, nullptr);
+    if (rc != NQ_OK) goto done;
+    CREATE_HIP(hipDeviceSynchronize());
+    CREATE_HIP(hipMemcpy(d_canon, U_words, canon_u, hipMemcpyHostToDevice));
+    rc = launch_repack(d_canon, wpr, false, d_out, r, h->u_tiles, nullptr);
+    if (rc != NQ_OK) goto done;
+    CREATE_HIP(hipMemcpy(h->s_in, s_in_fp16, (size_t)d_in * 2, hipMemcpyHostToDevice));
+    CREATE_HIP(hipMemcpy(h->s_out, s_out_fp16, (size_t)d_out * 2, hipMemcpyHostToDevice));
+    CREATE_HIP(hipDeviceSynchronize());
+#undef CREATE_HIP
+done:
+    if (d_canon) (void)hipFree(d_canon);
+    if (rc != NQ_OK) {
+        free_handle(h);
+        return rc;
+    }
+    *out = h;
+    return NQ_OK;
+}
+
+extern "C" int nq_binlr_destroy(nq_handle h)
+{
+    if (!h) return NQ_OK;
+    {
+        std::lock_guard<std::mutex> lk(g_cache_mutex);
+        drop_cached_plan_locked();
+    }
+    free_handle(h);
+    return NQ_OK;
+}
+
+extern "C" size_t nq_binlr_weight_bytes(nq_handle h)
+{
+    if (!h) return 0;
+    return (size_t)(h->r * (h->d_in + h->d_out) + 7) / 8 + 2 * (size_t)(h->d_in + h->d_out);
+}
+
+extern "C" int nq_binlr_reserve(nq_handle h, int max_batch)
+{
+    if (!h) return fail(NQ_E_NULL, "nq_binlr_reserve: NULL handle");
+    if (max_batch < 1) return fail(NQ_E_INVALID_ARG, "nq_binlr_reserve: max_batch must be >= 1");
+    if (max_batch < NQ_PREFILL_MIN_BATCH || (h->flags & NQ_FLAG_NO_PREFILL)) return NQ_OK;   // decode workspace is fixed
+    if (max_batch <= h->pf_batch) return NQ_OK;
+    size_t need = prefill_workspace_bytes(h->d_out, h->d_in, h->r, max_batch);
+    if (need > h->pf_bytes) {
+        NQ_HIP(hipDeviceSynchronize());
+        if (h->pf_alloc) NQ_HIP(hipFree(h->pf_alloc));
+        h->pf_alloc = nullptr;
+        h->pf_bytes = 0;
+        h->pf_batch = 0;
+        NQ_HIP(hipMalloc(&h->pf_alloc, need));
+        h->pf_bytes = need;
+    }
+    h->pf_batch = max_batch;
+    return NQ_OK;
+}
+
+static QuantDesc make_qx(nq_handle h, const void* x)
+{
+    QuantDesc q;
+    q.x = x; q.scale = h->s_in; q.bq = h->bq_x; q.meta = h->meta_x;
+    q.N = (int)h->d_in; q.n_chunks = (int)n_steps(h->d_in) * 4; q.x_stride = (int)h->d_in; q.dtype = h->x_dtype;
+    return q;
+}
+static StageDesc make_s1(nq_handle h)
+{
+    StageDesc s;
+    s.tiles = h->vt_tiles; s.bq = h->bq_x; s.meta = h->meta_x; s.out_scale = nullptr; s.out = h->t;
+    s.M = (int)h->r; s.n_steps = (int)n_steps(h->d_in); s.out_stride = h->t_stride; s.reserved = 0;
+    return s;
+}
+static QuantDesc make_qt(nq_handle h)
+{
+    QuantDesc q;
+    q.x = h->t; q.scale = nullptr; q.bq = h->bq_t; q.meta = h->meta_t;
+    q.N = (int)h->r; q.n_chunks = (int)n_steps(h->r) * 4; q.x_stride = h->t_stride; q.dtype = NQ_F32;
+    return q;
+}
+static StageDesc make_s2(nq_handle h, void* y)
+{
+    StageDesc s;
+    s.tiles = h->u_tiles; s.bq = h->bq_t; s.meta = h->meta_t; s.out_scale = h->s_out; s.out = (float*)y;
+    s.M = (int)h->d_out; s.n_steps = (int)n_steps(h->r); s.out_stride = (int)h->d_out; s.reserved = 0;
+    return s;
+}
+
+// one pass of the streaming path for batch <= 8
+static int decode_once(nq_handle h, const void* x, void* y, int batch, hipStream_t s)
+{
+    int rc;
+    if (h->flags & NQ_FLAG_DECODE_VALU) {
+        rc = launch_valu_gemv(h->vt_tiles, x, h->x_dtype, (int)h->d_in, h->s_in, nullptr, h->t, h->t_stride, h->r,
+                              h->d_in, batch, s);
+        if (rc != NQ_OK) return rc;
+        return launch_valu_gemv(h->u_tiles, h->t, NQ_F32, h->t_stride, nullptr, h->s_out, (float*)y, (int)h->d_out,
+                                h->d_out, h->r, batch, s);
+    }
+    QuantDesc qx = make_qx(h, x);
+    StageDesc s1 = make_s1(h);
+    QuantDesc qt = make_qt(h);
+    StageDesc s2 = make_s2(h, y);
+    if ((rc = launch_quantize(nullptr, qx, 1, batch, s)) != NQ_OK) return rc;
+    if ((rc = launch_stage(nullptr, s1, nullptr, (int)n_rowblocks(h->r), batch, s)) != NQ_OK) return rc;
+    if ((rc = launch_quantize(nullptr, qt, 1, batch, s)) != NQ_OK) return rc;
+    return launch_stage(nullptr, s2, nullptr, (int)n_rowblocks(h->d_out), batch, s);
+}
+
+static int check_xy(const char* who, const void* x, const void* y, size_t x_bytes, size_t y_bytes)
+{
+    char buf[160];
+    if (!x || !y) { snprintf(buf, sizeof buf, "%s: x or y is NULL", who); return fail(NQ_E_NULL, buf); }
+    if (!aligned16(x) || !aligned16(y)) { snprintf(buf, sizeof buf, "%s: x and y must be 16-byte aligned", who); return fail(NQ_E_ALIGN, buf); }
+    const char* xb = (const char*)x; const char* yb = (const char*)y;
+    if (xb < yb + y_bytes && yb < xb + x_bytes) { snprintf(buf, sizeof buf, "%s: x and y overlap", who); return fail(NQ_E_INVALID_ARG, buf); }
+    return NQ_OK;
+}
+
+extern "C" int nq_binlr_forward(nq_handle h, const void* x, void* y, int batch, void* stream)
+{
+    if (!h) return fail(NQ_E_NULL, "nq_binlr_forward: NULL handle");
+    if (batch < 1) return fail(NQ_E_INVALID_ARG, "nq_binlr_forward: batch must be >= 1");
+    const size_t xs = dtype_size(h->x_dtype);
+    int rc = check_xy("nq_binlr_forward", x, y, (size_t)batch * h->d_in * xs, (size_t)batch * h->d_out * 4);
+    if (rc != NQ_OK) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    if (batch <= NQ_DECODE_MAX_BATCH) return decode_once(h, x, y, batch, s);
+    if (batch >= NQ_PREFILL_MIN_BATCH && !(h->flags & (NQ_FLAG_NO_PREFILL | NQ_FLAG_DECODE_VALU))) {
+        if (batch > h->pf_batch && (rc = nq_binlr_reserve(h, batch)) != NQ_OK) return rc;
+        PrefillArgs a;
+        a.vt_tiles = h->vt_tiles; a.u_tiles = h->u_tiles; a.s_in = h->s_in; a.s_out = h->s_out;
+        a.x = x; a.y = (float*)y; a.workspace = h->pf_alloc;
+        a.d_out = h->d_out; a.d_in = h->d_in; a.r = h->r; a.batch = batch; a.x_dtype = h->x_dtype;
+        return launch_prefill(a, s);
+    }
+    // mid-size batches: chunks of 8 through the streaming path (each chunk re-reads the bits)
+    for (int b0 = 0; b0 < batch; b0 += NQ_DECODE_MAX_BATCH) {
+        int nb = std::min(NQ_DECODE_MAX_BATCH, batch - b0);
+        rc = decode_once(h, (const char*)x + (size_t)b0 * h->d_in * xs, (char*)y + (size_t)b0 * h->d_out * 4, nb, s);
+        if (rc != NQ_OK) return rc;
+    }
+    return NQ_OK;
+}
+
+extern "C" int nq_binlr_export_words(nq_handle h, uint32_t* U_words, uint32_t* V_words)
+{
+    if (!h) return fail(NQ_E_NULL, "nq_binlr_export_words: NULL handle");
+    const int64_t wpr = (h->r + 31) / 32;
+    const size_t canon_u = (size_t)h->d_out * wpr * 4, canon_v = (size_t)h->d_in * wpr * 4;
+    uint32_t* d_canon = nullptr;
+    NQ_HIP(hipMalloc((void**)&d_canon, std::max(canon_u, canon_v)));
+    int rc = NQ_OK;
+    hipError_t e = hipSuccess;
+    if (V_words) {
+        rc = launch_export(h->vt_tiles, wpr, true, h->r, h->d_in, d_canon, nullptr);
+        if (rc == NQ_OK && (e = hipMemcpy(V_words, d_canon, canon_v, hipMemcpyDeviceToHost)) != hipSuccess)
+            rc = hip_fail(e, "hipMemcpy", __FILE__, __LINE__);
+    }
+    if (rc == NQ_OK && U_words) {
+        rc = launch_export(h->u_tiles, wpr, false, h->d_out, h->r, d_canon, nullptr);
+        if (rc == NQ_OK && (e = hipMemcpy(U_words, d_canon, canon_u, hipMemcpyDeviceToHost)) != hipSuccess)
+            rc = hip_fail(e, "hipMemcpy", __FILE__, __LINE__);
+    }
+    (void)hipFree(d_canon);
+    return rc;
+}
+
+extern "C" int nq_binlr_read_intermediate(nq_handle h, float* t_host, int batch)
+{
+    if (!h || !t_host) return fail(NQ_E_NULL, "nq_binlr_read_intermediate: NULL pointer");
+    if (batch < 1 || batch > NQ_DECODE_MAX_BATCH) return fail(NQ_E_INVALID_ARG, "nq_binlr_read_intermediate: batch must be 1..8");
+    NQ_HIP(hipDeviceSynchronize());
+    NQ_HIP(hipMemcpy2D(t_host, (size_t)h->r * 4, h->t, (size_t)h->t_stride * 4, (size_t)h->r * 4, batch,
+                       hipMemcpyDeviceToHost));
+    return NQ_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// plans
+// ---------------------------------------------------------------------------------------------
+extern "C" int nq_plan_destroy(nq_plan p)
+{
+    if (!p) return NQ_OK;
+    if (p->have_events)
+        for (auto& e : p->ev) (void)hipEventDestroy(e);
+    if (p->alloc) (void)hipFree(p->alloc);
+    delete p;
+    return NQ_OK;
+}
+
+static void drop_cached_plan_locked()
+{
+    if (g_cached_plan) {
+        (void)hipDeviceSynchronize();
+        nq_plan_destroy(g_cached_plan);
+        g_cached_plan = nullptr;
+        g_cached_key.clear();
+    }
+}
+
+extern "C" int nq_plan_create(nq_plan* out, const nq_handle* hs, const void* const* xs, void* const* ys, int n,
+                              int batch)
+{
+    if (!out) return fail(NQ_E_NULL, "nq_plan_create: out is NULL");
+    *out = nullptr;
+    if (!hs || !xs || !ys) return fail(NQ_E_NULL, "nq_plan_create: NULL array");
+    if (n < 1) return fail(NQ_E_INVALID_ARG, "nq_plan_create: n must be >= 1");
+    if (batch < 1) return fail(NQ_E_INVALID_ARG, "nq_plan_create: batch must be >= 1");
+    if (batch > NQ_DECODE_MAX_BATCH) return fail(NQ_E_UNSUPPORTED, "nq_plan_create: batch must be <= NQ_DECODE_MAX_BATCH");
+    std::vector<nq_handle> sorted(hs, hs + n);
+    for (int i = 0; i < n; ++i) {
+        if (!hs[i]) return fail(NQ_E_NULL, "nq_plan_create: NULL handle in list");
+        if (hs[i]->flags & NQ_FLAG_DECODE_VALU) return fail(NQ_E_UNSUPPORTED, "nq_plan_create: handle uses NQ_FLAG_DECODE_VALU");
+        if (hs[i]->device != hs[0]->device) return fail(NQ_E_INVALID_ARG, "nq_plan_create: handles live on different devices");
+        int rc = check_xy("nq_plan_create", xs[i], ys[i], (size_t)batch * hs[i]->d_in * dtype_size(hs[i]->x_dtype),
+                          (size_t)batch * hs[i]->d_out * 4);
+        if (rc != NQ_OK) return rc;
+    }
+    std::sort(sorted.begin(), sorted.end());
+    if (std::adjacent_find(sorted.begin(), sorted.end()) != sorted.end())
+        return fail(NQ_E_INVALID_ARG, "nq_plan_create: a handle appears twice (its workspace would be shared)");
+
+    std::vector<QuantDesc> qx(n), qt(n);
+    std::vector<StageDesc> s1(n), s2(n);
+    std::vector<WorkItem> it1, it2;
+    for (int i = 0; i < n; ++i) {
+        qx[i] = make_qx(hs[i], xs[i]);
+        s1[i] = make_s1(hs[i]);
+        qt[i] = make_qt(hs[i]);
+        s2[i] = make_s2(hs[i], ys[i]);
+        for (int rb = 0; rb < (int)n_rowblocks(hs[i]->r); ++rb) it1.push_back(WorkItem{i, rb});
+        for (int rb = 0; rb < (int)n_rowblocks(hs[i]->d_out); ++rb) it2.push_back(WorkItem{i, rb});
+    }
+    // longest items first: round-robin assignment of a descending list balances the waves
+    std::stable_sort(it1.begin(), it1.end(), [&](const WorkItem& a, const WorkItem& b) { return s1[a.op].n_steps > s1[b.op].n_steps; });
+    std::stable_sort(it2.begin(), it2.end(), [&](const WorkItem& a, const WorkItem& b) { return s2[a.op].n_steps > s2[b.op].n_steps; });
+
+    nq_plan p = new (std::nothrow) nq_plan_s();
+    if (!p) return fail(NQ_E_HIP, "nq_plan_create: out of host memory");
+    p->n = n; p->batch = batch; p->device = hs[0]->device; p->alloc = nullptr; p->have_events = false;
+    p->handles.assign(hs, hs + n);
+    p->n_items1 = (int)it1.size(); p->n_items2 = (int)it2.size();
+    const size_t qb = align_up(sizeof(QuantDesc) * n, 256), sb = align_up(sizeof(StageDesc) * n, 256);
+    const size_t i1b = align_up(sizeof(WorkItem) * it1.size(), 256), i2b = align_up(sizeof(WorkItem) * it2.size(), 256);
+    hipError_t e = hipMalloc(&p->alloc, 2 * qb + 2 * sb + i1b + i2b);
+    if (e != hipSuccess) { delete p; return hip_fail(e, "hipMalloc(plan)", __FILE__, __LINE__); }
+    char* c = (char*)p->alloc;
+    p->qx = (QuantDesc*)c; c += qb;
+    p->qt = (QuantDesc*)c; c += qb;
+    p->s1 = (StageDesc*)c; c += sb;
+    p->s2 = (StageDesc*)c; c += sb;
+    p->items1 = (WorkItem*)c; c += i1b;
+    p->items2 = (WorkItem*)c;
+    const struct { void* dst; const void* src; size_t bytes; } copies[] = {
+        {p->qx, qx.data(), sizeof(QuantDesc) * n}, {p->qt, qt.data(), sizeof(QuantDesc) * n},
+        {p->s1, s1.data(), sizeof(StageDesc) * n}, {p->s2, s2.data(), sizeof(StageDesc) * n},
+        {p->items1, it1.data(), sizeof(WorkItem) * it1.size()}, {p->items2, it2.data(), sizeof(WorkItem) * it2.size()}};
+    for (const auto& cp : copies) {
+        e = hipMemcpy(cp.dst, cp.src, cp.bytes, hipMemcpyHostToDevice);
+        if (e != hipSuccess) { nq_plan_destroy(p); return hip_fail(e, "hipMemcpy(plan)", __FILE__, __LINE__); }
+    }
+    *out = p;
+    return NQ_OK;
+}
+
+static int plan_run(nq_plan p, hipStream_t s, bool timed)
+{
+    const QuantDesc qdummy{};
+    const StageDesc sdummy{};
+    int rc;
+    if (timed) NQ_HIP(hipEventRecord(p->ev[0], s));
+    if ((rc = launch_quantize(p->qx, qdummy, p->n, p->batch, s)) != NQ_OK) return rc;
+    if (timed) NQ_HIP(hipEventRecord(p->ev[1], s));
+    if ((rc = launch_stage(p->s1, sdummy, p->items1, p->n_items1, p->batch, s)) != NQ_OK) return rc;
+    if (timed) NQ_HIP(hipEventRecord(p->ev[2], s));
+    if ((rc = launch_quantize(p->qt, qdummy, p->n, p->batch, s)) != NQ_OK) return rc;
+    if (timed) NQ_HIP(hipEventRecord(p->ev[3], s));
+    if ((rc = launch_stage(p->s2, sdummy, p->items2, p->n_items2, p->batch, s)) != NQ_OK) return rc;
+    if (timed) NQ_HIP(hipEventRecord(p->ev[4], s));
+    return NQ_OK;
+}
+
+extern "C" int nq_plan_forward(nq_plan p, void* stream)
+{
+    if (!p) return fail(NQ_E_NULL, "nq_plan_forward: NULL plan");
+    return plan_run(p, (hipStream_t)stream, false);
+}
+
+extern "C" int nq_plan_forward_timed(nq_plan p, void* stream, float ms[4])
+{
+    if (!p || !ms) return fail(NQ_E_NULL, "nq_plan_forward_timed: NULL pointer");
+    if (!p->have_events) {
+        for (auto& e : p->ev) NQ_HIP(hipEventCreate(&e));
+        p->have_events = true;
+    }
+    int rc = plan_run(p, (hipStream_t)stream, true);
+    if (rc != NQ_OK) return rc;
+    NQ_HIP(hipEventSynchronize(p->ev[4]));
+    for (int i = 0; i < 4; ++i) NQ_HIP(hipEventElapsedTime(&ms[i], p->ev[i], p->ev[i + 1]));
+    return NQ_OK;
+}
+
+extern "C" int nq_binlr_forward_many(const nq_handle* hs, const void* const* xs, void* const* ys, int n, int batch,
+                                     void* stream)
+{
+    if (!hs || !xs || !ys) return fail(NQ_E_NULL, "nq_binlr_forward_many: NULL array");
+    if (n < 1) return fail(NQ_E_INVALID_ARG, "nq_binlr_forward_many: n must be >= 1");
+    std::vector<const void*> key;
+    key.reserve(3 * (size_t)n + 2);
+    key.push_back((const void*)(intptr_t)n);
+    key.push_back((const void*)(intptr_t)batch);
+    for (int i = 0; i < n; ++i) { key.push_back(hs[i]); key.push_back(xs[i]); key.push_back(ys[i]); }
+    std::lock_guard<std::mutex> lk(g_cache_mutex);
+    if (!g_cached_plan || key != g_cached_key) {
+        drop_cached_plan_locked();
+        nq_plan p = nullptr;
+        int rc = nq_plan_create(&p, hs, xs, ys, n, batch);
+        if (rc != NQ_OK) return rc;
+        g_cached_plan = p;
+        g_cached_key = key;
+    }
+    return plan_run(g_cached_plan, (hipStream_t)stream, false);
+}

@@ -1,0 +1,109 @@
+// Internal declarations shared by the translation units of libnq_binlr (not installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+#include "nq_binlr.h"
+
+namespace nq {
+
+// ---- device bit layout ("sign tiles") ------------------------------------------------------
+// A sign matrix A[M][N] (M output rows, N = reduction length; A = V^T for stage 1, A = U for
+// stage 2 of the two-stage product of Section 3.3 / Appendix D) is cut into tiles of
+// 128 rows x 64 reduction columns = 1 KiB.  Tile (rb, st) starts at word (rb*n_steps + st)*256.
+// Inside a tile, lane l of a wavefront owns words 4l..4l+3 (one 16-byte load).  In word v of
+// lane l, bit 8*b + p  (byte b = 0..3, bit-in-byte p = 0..7) is the sign bit of
+//     A[rb*128 + 16*p + (l & 15)][st*64 + 16*(l >> 4) + 4*v + b]      (1 -> +1, 0 -> -1).
+// Masking a word with 0x01010101 << p therefore yields four int8 values in {0, 2^p} that are
+// exactly the A operand (row l&15, depth 16*(l>>4) + 4v + b) of one 16x16x64 int8 MFMA for the
+// 16 rows of bit plane p.  Rows >= M and columns >= N hold 0 bits.
+constexpr int kTileRows = 128;
+constexpr int kTileCols = 64;
+constexpr int kTileWords = 256;
+
+// ---- fixed-point activations ---------------------------------------------------------------
+// The streaming kernels contract exact integers.  Each token's vector v (x' = s_in (.) x for
+// stage 1, t for stage 2) is written as v_j ~= step * q_j with step a power of two chosen from
+// the token's max |v_j| so that |q_j| <= 2^22, and q_j is split into three signed bytes
+// q = 65536*hi + 256*mid + lo.  A token occupies three MFMA columns (hi, mid, lo).
+// Column of (token, slice): tokens 0..4 sit in columns 0..14, tokens 5..7 in columns 16..24.
+constexpr int kSlices = 3;
+__host__ __device__ inline int col_of(int token, int slice) { return (token / 5) * 16 + (token % 5) * 3 + slice; }
+__host__ __device__ inline int ncols_for(int batch) { return batch <= 5 ? 3 * batch : 16 + 3 * (batch - 5); }
+
+struct QMeta {        // per token, written by the quantisation kernel
+    double sumq;      // sum_j q_j (exact)
+    float step;       // power of two; NaN when the token holds a non-finite value
+    float pad;
+};
+
+struct QuantDesc {
+    const void* x;           // device [batch][x_stride]
+    const uint16_t* scale;   // device fp16 [N] or nullptr (no scaling)
+    uint8_t* bq;             // device [n_chunks][ncols][16] signed bytes
+    QMeta* meta;             // device [batch]
+    int N;                   // real length
+    int n_chunks;            // 16-element chunks including padding (= 4 * n_steps)
+    int x_stride;            // elements between tokens
+    int dtype;               // NQ_F32 / NQ_F16 / NQ_BF16
+};
+
+struct StageDesc {
+    const uint32_t* tiles;       // sign tiles of A
+    const uint8_t* bq;           // quantised input of this stage
+    const QMeta* meta;
+    const uint16_t* out_scale;   // fp16 [M] or nullptr
+    float* out;                  // [batch][out_stride]
+    int M;                       // real rows
+    int n_steps;                 // 64-column steps
+    int out_stride;
+    int reserved;
+};
+
+struct WorkItem { int op; int rb; };
+
+inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
+inline int64_t n_rowblocks(int64_t M) { return (M + kTileRows - 1) / kTileRows; }
+inline int64_t n_steps(int64_t N) { return (N + kTileCols - 1) / kTileCols; }
+inline size_t tile_words(int64_t M, int64_t N) { return (size_t)n_rowblocks(M) * n_steps(N) * kTileWords; }
+
+// ---- error plumbing ------------------------------------------------------------------------
+void set_error(const std::string& msg);
+int hip_fail(hipError_t e, const char* what, const char* file, int line);
+#define NQ_HIP(call)                                                        \
+    do {                                                                    \
+        hipError_t e__ = (call);                                            \
+        if (e__ != hipSuccess) return ::nq::hip_fail(e__, #call, __FILE__, __LINE__); \
+    } while (0)
+
+// ---- launchers (nq_decode.hip) -------------------------------------------------------------
+int launch_repack(const uint32_t* d_canon, int64_t wpr, bool transposed, int64_t M, int64_t N,
+                  uint32_t* d_tiles, hipStream_t s);
+int launch_export(const uint32_t* d_tiles, int64_t wpr, bool transposed, int64_t M, int64_t N,
+                  uint32_t* d_canon, hipStream_t s);
+// single op (descriptor by value) or many (device arrays)
+int launch_quantize(const QuantDesc* d_descs, const QuantDesc& single, int n_ops, int batch, hipStream_t s);
+int launch_stage(const StageDesc* d_descs, const StageDesc& single, const WorkItem* d_items, int n_items,
+                 int batch, hipStream_t s);
+int launch_valu_gemv(const uint32_t* tiles, const void* x, int x_dtype, int x_stride, const uint16_t* in_scale,
+                     const uint16_t* out_scale, float* out, int out_stride, int64_t M, int64_t N, int batch,
+                     hipStream_t s);
+int device_cu_count();
+
+// ---- launchers (nq_prefill.hip) ------------------------------------------------------------
+struct PrefillArgs {
+    const uint32_t* vt_tiles;   // stage-1 sign tiles (A = V^T)
+    const uint32_t* u_tiles;    // stage-2 sign tiles (A = U)
+    const uint16_t* s_in;
+    const uint16_t* s_out;
+    const void* x;
+    float* y;
+    void* workspace;            // device, prefill_workspace_bytes()
+    int64_t d_out, d_in, r;
+    int batch;
+    int x_dtype;
+};
+size_t prefill_workspace_bytes(int64_t d_out, int64_t d_in, int64_t r, int batch);
+int launch_prefill(const PrefillArgs& a, hipStream_t s);
+
+}  // namespace nq

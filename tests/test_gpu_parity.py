@@ -1,0 +1,259 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 oracle."""
+import ctypes
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2602_06694_amd import binding as nq
+from paper_2602_06694_amd import synth
+from gpu_util import BAR, DECODE_TOL, Layer, rel_err, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def test_config1_full_against_dense_definition():
+    c = synth.CONFIGS[1]
+    shp = c.block[0]
+    data = synth.gen_layer(1, 0, 0, shp)
+    x = synth.gen_layer_x(1, 0, 0, shp, 1, c.x_dtype)
+    L = Layer(shp.d_out, shp.d_in, shp.r, c.x_dtype, data=data)
+    y = L.forward(x)
+    ref = oracle.forward_dense(data.U_words, data.V_words, data.s_out, data.s_in, shp.d_out, shp.d_in, shp.r,
+                               synth.x_as_f64(x, c.x_dtype))
+    err = rel_err(y, ref)
+    print(f"config 1: rel err {err:.3e}")
+    assert err <= BAR
+    assert err <= DECODE_TOL
+    L.close()
+
+
+def test_config1_valu_kernels():
+    c = synth.CONFIGS[1]
+    shp = c.block[0]
+    data = synth.gen_layer(1, 0, 0, shp)
+    x = synth.gen_layer_x(1, 0, 0, shp, 1, c.x_dtype)
+    L = Layer(shp.d_out, shp.d_in, shp.r, c.x_dtype, data=data, flags=nq.NQ_FLAG_DECODE_VALU)
+    err = rel_err(L.forward(x), L.oracle(x))
+    print(f"config 1 (VALU): rel err {err:.3e}")
+    assert err <= 2e-5          # fp32 accumulation over <= 1024 terms
+    L.close()
+
+
+SHAPES = [
+    # d_out, d_in, r : ragged tails in every dimension, several tiles, degenerate sizes
+    (1, 1, 1), (3, 2, 1), (16, 64, 32), (129, 65, 33), (300, 200, 100), (257, 1000, 96), (128, 64, 128),
+    (640, 130, 257), (100, 4100, 70),
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("x_dtype", ["bf16", "f16", "f32"])
+def test_ragged_shapes_all_decode_batches(shape, x_dtype):
+    d_out, d_in, r = shape
+    L = Layer(d_out, d_in, r, x_dtype, seed=17 * d_out + d_in + r)
+    for batch in (1, 2, 3, 5, 6, 8):
+        x = synth.gen_x(batch, d_in, 1000 + batch, x_dtype)
+        y = L.forward(x)
+        ref = L.oracle(x)
+        err = rel_err(y, ref)
+        assert err <= DECODE_TOL, (shape, x_dtype, batch, err)
+    L.close()
+
+
+@pytest.mark.parametrize("batch", [1, 8])
+def test_config2_full(batch):
+    c = synth.CONFIGS[2]
+    shp = c.block[0]
+    data = synth.gen_layer(2, 0, 0, shp)
+    x = synth.gen_layer_x(2, 0, 0, shp, batch, c.x_dtype)
+    L = Layer(shp.d_out, shp.d_in, shp.r, c.x_dtype, data=data)
+    y = L.forward(x)
+    ref, t_ref = L.oracle(x, return_t=True)
+    err = rel_err(y, ref)
+    t = nq.nq_binlr_read_intermediate(L.h, shp.r, batch)
+    t_err = rel_err(t, t_ref)
+    print(f"config 2 batch {batch}: rel err y {err:.3e}, t {t_err:.3e}")
+    assert err <= BAR and err <= DECODE_TOL
+    assert t_err <= DECODE_TOL
+    # sampled rows against the dense definition (Tier A)
+    rows = np.array([0, 1, 127, 128, 2047, 4095])
+    ya = L.oracle_rows(x, rows)
+    assert np.abs(y[:, rows] - ya).max() <= DECODE_TOL * np.abs(ref).max()
+    L.close()
+
+
+def test_device_layout_round_trip_is_bit_exact():
+    for (d_out, d_in, r) in [(300, 200, 100), (129, 65, 33), (1024, 1024, 256), (1, 1, 1)]:
+        L = Layer(d_out, d_in, r, "bf16", seed=5)
+        U, V = nq.nq_binlr_export_words(L.h, d_out, d_in, r)
+        assert np.array_equal(U, L.data.U_words)
+        assert np.array_equal(V, L.data.V_words)
+        assert nq.nq_binlr_weight_bytes(L.h) == (r * (d_out + d_in) + 7) // 8 + 2 * (d_out + d_in)
+        L.close()
+    L = Layer(4096, 4096, 1024, "bf16", seed=6)
+    assert nq.nq_binlr_weight_bytes(L.h) == oracle.layer_bits(4096, 4096, 1024) // 8
+    L.close()
+
+
+def test_integer_exact_mode_matches_bit_for_bit():
+    # power-of-two scales and small-integer activations: every intermediate is an exact
+    # integer multiple of a power of two, so fp64 oracle and GPU must agree exactly.
+    d_out, d_in, r = 384, 520, 200
+    rng = np.random.default_rng(7)
+    U = synth.gen_sign_words(d_out, r, 71)
+    V = synth.gen_sign_words(d_in, r, 72)
+    s_out = (2.0 ** rng.integers(-3, 4, d_out)).astype(np.float16)
+    s_in = (2.0 ** rng.integers(-3, 4, d_in)).astype(np.float16)
+    data = synth.LayerData(synth.LinearShape("e", d_out, d_in, r), U, V, s_out, s_in)
+    L = Layer(d_out, d_in, r, "f32", data=data)
+    for batch in (1, 4, 8):
+        x = rng.integers(-8, 9, (batch, d_in)).astype(np.float32)
+        y = L.forward(x)
+        ref = L.oracle(x)
+        assert np.array_equal(y.astype(np.float64), ref), batch
+    L.close()
+
+
+def test_closed_forms_on_gpu():
+    d_out, d_in, r = 200, 333, 77
+    ones_u = oracle.pack_signs(np.ones((d_out, r), dtype=np.int8))
+    ones_v = oracle.pack_signs(np.ones((d_in, r), dtype=np.int8))
+    s_out, s_in = synth.gen_scales(d_out, 1), synth.gen_scales(d_in, 2)
+    x = synth.gen_x(2, d_in, 3, "bf16")
+    xf = synth.x_as_f64(x, "bf16")
+    expect = s_out.astype(np.float64)[None, :] * r * (xf * s_in.astype(np.float64)[None, :]).sum(axis=1, keepdims=True)
+    data = synth.LayerData(synth.LinearShape("o", d_out, d_in, r), ones_u, ones_v, s_out, s_in)
+    L = Layer(d_out, d_in, r, "bf16", data=data)
+    assert rel_err(L.forward(x), expect) <= DECODE_TOL
+    L.close()
+    # one-hot inputs extract columns of the dense weight
+    d_out, d_in, r = 150, 70, 40
+    L = Layer(d_out, d_in, r, "f32", seed=9)
+    W = oracle.dense_weight(L.data.U_words, L.data.V_words, L.data.s_out, L.data.s_in, d_out, d_in, r)
+    cols = [0, 1, 63, 64, 69]
+    x = np.zeros((len(cols), d_in), dtype=np.float32)
+    for b, j in enumerate(cols):
+        x[b, j] = 1.0
+    y = L.forward(x)
+    assert np.abs(y - W[:, cols].T).max() <= 1e-6 * np.abs(W).max()
+    L.close()
+
+
+def test_rank_permutation_and_column_flip_leave_y_unchanged():
+    d_out, d_in, r = 260, 190, 150
+    U = synth.gen_signs_pm1(d_out, r, 31)
+    V = synth.gen_signs_pm1(d_in, r, 32)
+    s_out, s_in = synth.gen_scales(d_out, 33), synth.gen_scales(d_in, 34)
+    x = synth.gen_x(3, d_in, 35, "bf16")
+    perm = np.random.default_rng(36).permutation(r)
+    U2, V2 = U[:, perm].copy(), V[:, perm].copy()
+    U2[:, 5] *= -1
+    V2[:, 5] *= -1
+    outs = []
+    for (a, b) in ((U, V), (U2, V2)):
+        data = synth.LayerData(synth.LinearShape("p", d_out, d_in, r), nq.nq_pack_signs(a), nq.nq_pack_signs(b), s_out, s_in)
+        L = Layer(d_out, d_in, r, "bf16", data=data)
+        outs.append(L.forward(x))
+        ref = L.oracle(x)
+        L.close()
+    assert rel_err(outs[0], ref) <= DECODE_TOL
+    assert np.abs(outs[0].astype(np.float64) - outs[1]).max() <= 2 * DECODE_TOL * np.abs(ref).max()
+
+
+def test_mid_batches_run_as_chunks():
+    d_out, d_in, r = 300, 260, 130
+    L = Layer(d_out, d_in, r, "bf16", seed=44, flags=nq.NQ_FLAG_NO_PREFILL)
+    for batch in (9, 20, 70):
+        x = synth.gen_x(batch, d_in, 45 + batch, "bf16")
+        assert rel_err(L.forward(x), L.oracle(x)) <= DECODE_TOL
+    L.close()
+
+
+def test_outlier_channels_and_wide_dynamic_range():
+    d_out, d_in, r = 512, 2048, 256
+    L = Layer(d_out, d_in, r, "bf16", seed=55)
+    x = synth.gen_x(8, d_in, 56, "bf16", outlier_frac=0.01)
+    assert rel_err(L.forward(x), L.oracle(x)) <= DECODE_TOL
+    # tokens of very different magnitude share a launch: each has its own fixed-point step
+    xf = synth.bf16_bits_to_f32(synth.gen_x(4, d_in, 57, "bf16"))
+    xf *= np.array([1e-6, 1.0, 1e4, 1e-2], dtype=np.float32)[:, None]
+    xb = synth.f32_to_bf16_bits(xf)
+    y, ref = L.forward(xb), L.oracle(xb)
+    for b in range(4):
+        assert np.abs(y[b] - ref[b]).max() <= DECODE_TOL * np.abs(ref[b]).max(), b
+    # an all-zero token gives exact zeros
+    xz = xb.copy()
+    xz[2] = 0
+    y = L.forward(xz)
+    assert (y[2] == 0).all()
+    L.close()
+
+
+def test_non_finite_input_poisons_only_its_token():
+    d_out, d_in, r = 140, 100, 64
+    L = Layer(d_out, d_in, r, "f32", seed=66)
+    x = synth.gen_x(3, d_in, 67, "f32")
+    ref = L.oracle(x)
+    x[1, 17] = np.nan
+    import torch
+    xd = to_device(x, "f32")
+    y = torch.zeros((3, d_out), dtype=torch.float32, device="cuda")
+    nq.nq_binlr_forward(L.h, xd, y, 3)
+    torch.cuda.synchronize()
+    y = y.cpu().numpy()
+    assert np.isnan(y[1]).all()
+    assert np.abs(y[[0, 2]] - ref[[0, 2]]).max() <= DECODE_TOL * np.abs(ref).max()
+    L.close()
+
+
+def test_forward_many_and_plan_match_oracle():
+    import torch
+    shapes = [(300, 200, 100), (129, 65, 33), (512, 1024, 256), (1024, 512, 128), (64, 4100, 70), (1, 1, 1)]
+    for batch in (1, 3, 8):
+        layers = [Layer(*s, "bf16", seed=100 + i) for i, s in enumerate(shapes)]
+        xs_np = [synth.gen_x(batch, s[1], 200 + i, "bf16") for i, s in enumerate(shapes)]
+        xs = [to_device(x, "bf16") for x in xs_np]
+        ys = [torch.full((batch, s[0]), float("nan"), dtype=torch.float32, device="cuda") for s in shapes]
+        hs = [L.h for L in layers]
+        nq.nq_binlr_forward_many(hs, xs, ys, batch)
+        nq.nq_binlr_forward_many(hs, xs, ys, batch)      # cached plan replay
+        torch.cuda.synchronize()
+        for L, x, y in zip(layers, xs_np, ys):
+            assert rel_err(y.cpu().numpy(), L.oracle(x)) <= DECODE_TOL
+        plan = nq.nq_plan_create(hs, xs, ys, batch)
+        for y in ys:
+            y.fill_(float("nan"))
+        ms = nq.nq_plan_forward_timed(plan)
+        assert len(ms) == 4 and all(m >= 0 for m in ms)
+        for L, x, y in zip(layers, xs_np, ys):
+            assert rel_err(y.cpu().numpy(), L.oracle(x)) <= DECODE_TOL
+        for y in ys:
+            y.fill_(float("nan"))
+        nq.nq_plan_forward(plan)
+        torch.cuda.synchronize()
+        for L, x, y in zip(layers, xs_np, ys):
+            assert rel_err(y.cpu().numpy(), L.oracle(x)) <= DECODE_TOL
+        nq.nq_plan_destroy(plan)
+        with pytest.raises(nq.NQError) as e:
+            nq.nq_plan_create(hs + [hs[0]], xs + [xs[0]], ys + [ys[0]], batch)
+        assert e.value.status == nq.NQ_E_INVALID_ARG
+        for L in layers:
+            L.close()
+
+
+def test_forward_error_paths():
+    import torch
+    L = Layer(64, 64, 32, "bf16", seed=1)
+    x = torch.zeros(2 * 64 + 8, dtype=torch.bfloat16, device="cuda")
+    y = torch.zeros(2 * 64 + 8, dtype=torch.float32, device="cuda")
+    lib = nq.lib()
+    assert lib.nq_binlr_forward(L.h, x.data_ptr(), y.data_ptr(), 0, None) == nq.NQ_E_INVALID_ARG
+    assert lib.nq_binlr_forward(L.h, x.data_ptr() + 2, y.data_ptr(), 1, None) == nq.NQ_E_ALIGN
+    assert lib.nq_binlr_forward(L.h, x.data_ptr(), y.data_ptr() + 4, 1, None) == nq.NQ_E_ALIGN
+    assert lib.nq_binlr_forward(L.h, None, y.data_ptr(), 1, None) == nq.NQ_E_NULL
+    assert lib.nq_binlr_forward(L.h, y.data_ptr(), y.data_ptr(), 1, None) == nq.NQ_E_INVALID_ARG   # aliasing
+    assert "overlap" in nq.nq_last_error_string()
+    with pytest.raises(nq.NQError):
+        nq.nq_binlr_read_intermediate(L.h, 32, 9)
+    L.close()

@@ -1,0 +1,237 @@
+#!/usr/bin/env python3
+"""Benchmark of the NanoQuant binary low-rank forward on one MI355X.
+
+    python bench.py --gpus 1 --steps K --warmup W [--workload cfg2|cfg3|cfg4] [--batch B]
+
+One "step" is one pass of the whole hot path (input quantisation, stage 1
+t = V^T (s_in . x), quantisation of t, stage 2 y = s_out . (U t)) over every layer of
+the workload, issued as ONE nq_plan_forward (four kernel launches).
+
+Default workload "cfg2": the Llama-2-7B-shaped attention projection 4096x4096, r = 1024
+(0.5 bit/weight), bf16 activations, decode batch 1 -- as a pool of distinct seeded layer
+instances whose packed weights (~0.7 GB) exceed twice the 256 MB Infinity Cache, so every
+step streams its bits from HBM rather than from cache.  All inputs are resident in HBM
+before the timed region.
+
+Prints ONE JSON line.  `value` is effective weight GB/s = bytes of the stored
+factorization (r(n+m)/8 + 2(n+m) per layer, Appendix E.4) read per second.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+MFMA_F16_PEAK_TFLOPS = 2500.0   # MI355X published dense fp16/bf16 MFMA rate
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4"])
+    ap.add_argument("--batch", type=int, default=1)
+    ap.add_argument("--pool", type=int, default=640, help="cfg2: number of distinct layer instances")
+    ap.add_argument("--layers", type=int, default=0, help="cfg3/cfg4: decoder layers (0 = all)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target oracle time for the cpu_baseline sample")
+    ap.add_argument("--prefill", action="store_true", help="also time the config-5 prefill shapes (extra field)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch one plain 1 GiB device copy (reference for rocprofv3 --pmc byte counters)")
+    return ap.parse_args()
+
+
+def build_workload(args):
+    """Returns list of (shape, LayerData, x_numpy) for the chosen workload."""
+    from paper_2602_06694_amd import synth
+    out = []
+    if args.workload == "cfg2":
+        shp = synth.CONFIGS[2].block[0]
+        for i in range(args.pool):
+            out.append((shp, synth.gen_layer(2, i, 0, shp), synth.gen_layer_x(2, i, 0, shp, args.batch, "bf16")))
+        name = f"cfg2: {args.pool} x [4096x4096 r=1024], decode batch {args.batch}, bf16 x"
+    else:
+        cfg = 3 if args.workload == "cfg3" else 4
+        c = synth.CONFIGS[cfg]
+        nl = args.layers or c.n_layers
+        for layer, li, shp in synth.iter_config_layers(cfg, nl):
+            out.append((shp, synth.gen_layer(cfg, layer, li, shp), synth.gen_layer_x(cfg, layer, li, shp, args.batch, "bf16")))
+        name = f"cfg{cfg}: {c.name} ({nl} layers x 7 linears), decode batch {args.batch}, bf16 x"
+    return name, out
+
+
+def algorithmic_bytes(shp, batch):
+    """Bytes the method itself must move for one forward of one layer."""
+    bits = shp.r * (shp.d_in + shp.d_out) // 8
+    scales = 2 * (shp.d_in + shp.d_out)
+    x = batch * shp.d_in * 2
+    y = batch * shp.d_out * 4
+    t = 2 * batch * shp.r * 4      # intermediate written by stage 1 and read back for stage 2
+    return bits + scales, bits + scales + x + y + t
+
+
+def cpu_baseline(work, batch, target_s):
+    """Oracle (Tier B, fp64, OpenMP over the host cores) on a bounded sample of the same layers."""
+    import oracle
+    from paper_2602_06694_amd import synth
+    shp, data, x = work[0]
+    xf = synth.x_as_f64(x, "bf16")
+    t0 = time.perf_counter()
+    _, used = oracle.forward_factored(data.U_words, data.V_words, data.s_out, data.s_in, shp.d_out, shp.d_in, shp.r,
+                                      xf, threads=0, return_threads=True)
+    one = time.perf_counter() - t0
+    n = max(1, min(len(work), int(target_s / max(one, 1e-6))))
+    wbytes = 0
+    t0 = time.perf_counter()
+    for shp, data, x in work[:n]:
+        oracle.forward_factored(data.U_words, data.V_words, data.s_out, data.s_in, shp.d_out, shp.d_in, shp.r,
+                                synth.x_as_f64(x, "bf16"), threads=0)
+        wbytes += algorithmic_bytes(shp, batch)[0]
+    dt = time.perf_counter() - t0
+    return {"value": wbytes / dt / 1e9, "unit": "GB/s", "cores": int(used), "kind": "oracle",
+            "sample": f"first {n} of {len(work)} layers of the workload, fp64 factored oracle, {dt:.1f} s",
+            "layers_per_s": n / dt}
+
+
+def time_prefill(args):
+    """Config-5 shapes through nq_binlr_forward at batch 512 / 2048 (TFLOP/s = 2 B r (d_in + d_out) / time)."""
+    import numpy as np
+    import torch
+    from paper_2602_06694_amd import binding as nq
+    from paper_2602_06694_amd import synth
+    res = {}
+    c = synth.CONFIGS[5]
+    for li, shp in enumerate(c.block):
+        data = synth.gen_layer(5, 0, li, shp)
+        h = nq.nq_binlr_create(shp.d_out, shp.d_in, shp.r, data.U_words, data.V_words, data.s_out, data.s_in, nq.NQ_BF16)
+        for B in c.batches:
+            nq.nq_binlr_reserve(h, B)
+            xb = synth.gen_layer_x(5, 0, li, shp, B, "bf16", c.outlier_frac)
+            x = torch.from_numpy(xb.view(np.int16).copy()).view(torch.bfloat16).cuda()
+            y = torch.empty((B, shp.d_out), dtype=torch.float32, device="cuda")
+            for _ in range(2):
+                nq.nq_binlr_forward(h, x, y, B)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            iters = 5
+            e0.record()
+            for _ in range(iters):
+                nq.nq_binlr_forward(h, x, y, B)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / iters
+            flops = 2.0 * B * shp.r * (shp.d_in + shp.d_out)
+            res[f"{shp.name}_{shp.d_out}x{shp.d_in}_B{B}"] = {"ms": ms, "TFLOP/s": flops / ms / 1e9,
+                                                             "frac_of_f16_mfma_peak": flops / ms / 1e9 / MFMA_F16_PEAK_TFLOPS}
+            del x, y
+        nq.nq_binlr_destroy(h)
+    return res
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the path has no multi-GPU part); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2602_06694_amd import binding as nq
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    nq.lib()
+    batch = args.batch
+    name, work = build_workload(args)
+
+    handles, xs, ys = [], [], []
+    w_bytes = 0
+    all_bytes = 0
+    for shp, data, x in work:
+        handles.append(nq.nq_binlr_create(shp.d_out, shp.d_in, shp.r, data.U_words, data.V_words, data.s_out,
+                                          data.s_in, nq.NQ_BF16))
+        xs.append(torch.from_numpy(x.view(np.int16).copy()).view(torch.bfloat16).cuda())
+        ys.append(torch.empty((batch, shp.d_out), dtype=torch.float32, device="cuda"))
+        wb, ab = algorithmic_bytes(shp, batch)
+        w_bytes += wb
+        all_bytes += ab
+    plan = nq.nq_plan_create(handles, xs, ys, batch)
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        nq.nq_plan_forward(plan)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        nq.nq_plan_forward(plan)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    ev_ms = e0.elapsed_time(e1) / args.steps
+
+    # per-kernel durations (HIP events recorded between the four launches, on the same stream)
+    reps = max(3, min(args.steps, 20))
+    per_kernel = np.zeros(4)
+    for _ in range(reps):
+        per_kernel += np.array(nq.nq_plan_forward_timed(plan))
+    per_kernel /= reps
+    # dominant kernel: the streaming stage kernel, launched twice per step (over V^T tiles, over U tiles)
+    stage_ms = 0.5 * (per_kernel[1] + per_kernel[3])
+    stage_bytes = 0.5 * all_bytes                     # algorithmic bytes per stage launch (mean of the two)
+    achieved = stage_bytes / (stage_ms * 1e-3) / 1e9
+
+    if args.calibrate_copy:
+        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+        b = torch.empty_like(a)
+        b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
+
+    out = {
+        "metric": "effective weight GB/s per layer, decode batch %d" % batch,
+        "value": w_bytes / (wall_ms * 1e-3) / 1e9,
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall_ms,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int8 fixed-point (3 bytes/activation) x 1-bit signs, int32 accumulate; fp32 output",
+        "data": "synthetic",
+        "config": {"workload": name, "layers_per_step": len(work), "batch": batch,
+                   "weight_bytes_per_step": w_bytes, "algorithmic_bytes_per_step": all_bytes},
+        "tokens_per_s_per_layer": batch * len(work) / (wall_ms * 1e-3),
+        "ms_per_step_hip_events": ev_ms,
+        "kernel_ms": {"quantize_x": per_kernel[0], "stage1": per_kernel[1], "quantize_t": per_kernel[2],
+                      "stage2": per_kernel[3]},
+        "roofline": {"bound": "hbm", "kernel": "nq::stage_kernel (mean of the stage-1 and stage-2 launch)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None},
+    }
+    if args.prefill:
+        out["prefill"] = time_prefill(args)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(work, batch, args.cpu_seconds)
+
+    nq.nq_plan_destroy(plan)
+    for h in handles:
+        nq.nq_binlr_destroy(h)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

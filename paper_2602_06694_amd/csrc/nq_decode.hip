@@ -203,15 +203,28 @@ int launch_quantize(const QuantDesc* d_descs, const QuantDesc& single, int n_ops
 //   D  : software prefetch depth (tiles in flight per wave)
 // A work item is one 128-row block of one op, over the whole reduction length.
 // ---------------------------------------------------------------------------------------------
+#ifndef NQ_STAGE_WAVES
+#define NQ_STAGE_WAVES 4
+#endif
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+
+// streamed once, never reused: keep the sign tiles from displacing the (reused) activations in cache
+typedef const __attribute__((address_space(1))) v4u* gptr_v4u;    // global (not generic) address space
+__device__ inline v4u load_tile_words(const char* base, uint32_t off)
+{
+    return __builtin_nontemporal_load((gptr_v4u)(base + off));
+}
+__device__ inline v4u load_global_v4u(const char* base, uint32_t off) { return *(gptr_v4u)(base + off); }
+
 template <int NB, int W, int D>
-__global__ void __launch_bounds__(W == 1 ? 256 : 64 * W)
+__global__ void __launch_bounds__(W == 1 ? 256 : 64 * W) __attribute__((amdgpu_waves_per_eu(NB == 1 ? NQ_STAGE_WAVES : 2, 8)))
 stage_kernel(const StageDesc* __restrict__ descs, StageDesc single, const WorkItem* __restrict__ items, int n_items,
              int batch)
 {
     extern __shared__ int lds[];
     constexpr int WPB = (W == 1) ? 4 : W;               // waves per block
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int g = lane >> 4, n = lane & 15;
     const int ncols = ncols_for(batch);
     int* my_lds = lds + wave * (kTileRows * ncols);
@@ -221,27 +234,39 @@ stage_kernel(const StageDesc* __restrict__ descs, StageDesc single, const WorkIt
     const int st0 = (W == 1) ? 0 : wave;
 
     for (int it = stream; it < n_items; it += nstreams) {
-        StageDesc d;
-        int rb;
+        // descriptor fields are wave-uniform: fetch them with scalar loads
+        const uint32_t* tiles;
+        const uint8_t* bq;
+        const QMeta* meta;
+        const uint16_t* out_scale;
+        float* out;
+        int M, nst, out_stride, rb;
         if (items) {
-            WorkItem e = items[it];
-            d = descs[e.op];
+            const WorkItem e = items[it];
+            const StageDesc* dp = descs + e.op;
             rb = e.rb;
+            tiles = dp->tiles; bq = dp->bq; meta = dp->meta; out_scale = dp->out_scale; out = dp->out;
+            M = dp->M; nst = dp->n_steps; out_stride = dp->out_stride;
         } else {
-            d = single;
             rb = it;
+            tiles = single.tiles; bq = single.bq; meta = single.meta; out_scale = single.out_scale; out = single.out;
+            M = single.M; nst = single.n_steps; out_stride = single.out_stride;
         }
-        const int nst = d.n_steps;
-        const uint4* a_ptr = (const uint4*)d.tiles + (size_t)rb * nst * 64 + lane;
-        const uint4* b_ptr[NB];
-        bool b_ok[NB];
+        const int cnt = (nst - st0 + W - 1) / W;         // steps this wave performs (may be <= 0)
+        // 32-bit byte offsets from the (scalar) base pointers; a tile array is at most 512 MiB
+        // (a wave with no step of its own, possible when W > nst, aims its unused prefetches at step 0)
+        const int stf = cnt > 0 ? st0 : 0;
+        uint32_t a_off = (uint32_t)(((size_t)rb * nst + stf) * 1024 + lane * 16);
+        // lanes whose column is beyond ncols re-read column 0: their result columns are never used
+        uint32_t b_off[NB];
 #pragma unroll
         for (int cg = 0; cg < NB; ++cg) {
             int col = cg * 16 + n;
-            b_ok[cg] = col < ncols;
-            b_ptr[cg] = (const uint4*)d.bq + (size_t)g * ncols + (b_ok[cg] ? col : 0);
+            b_off[cg] = (uint32_t)(((stf * 4 + g) * ncols + (col < ncols ? col : 0)) * 16);
         }
-        const size_t b_step = (size_t)4 * ncols;
+        const uint32_t b_inc = (uint32_t)(W * 4 * ncols * 16);
+        const char* a_base = (const char*)tiles;
+        const char* b_base = (const char*)bq;
 
         v4i acc[NB][8];
 #pragma unroll
@@ -249,46 +274,71 @@ stage_kernel(const StageDesc* __restrict__ descs, StageDesc single, const WorkIt
 #pragma unroll
             for (int p = 0; p < 8; ++p) acc[cg][p] = v4i{0, 0, 0, 0};
 
-        uint4 wbuf[D];
-        uint4 bbuf[D][NB];
-#pragma unroll
-        for (int k = 0; k < D; ++k) {
-            int s = st0 + k * W;
-            if (s < nst) {
-                wbuf[k] = a_ptr[(size_t)s * 64];
-#pragma unroll
-                for (int cg = 0; cg < NB; ++cg)
-                    bbuf[k][cg] = b_ok[cg] ? b_ptr[cg][(size_t)s * b_step] : make_uint4(0, 0, 0, 0);
-            }
-        }
-        for (int sb = st0; sb < nst; sb += D * W) {
+        v4u wbuf[D];
+        v4u bbuf[D][NB];
+#define NQ_ISSUE(k)                                                              \
+    do {                                                                         \
+        wbuf[k] = load_tile_words(a_base, a_off);                                \
+        a_off += W * 1024;                                                       \
+        _Pragma("unroll") for (int cg = 0; cg < NB; ++cg) {                      \
+            bbuf[k][cg] = load_global_v4u(b_base, b_off[cg]);                    \
+            b_off[cg] += b_inc;                                                  \
+        }                                                                        \
+    } while (0)
+#define NQ_COMPUTE(w, b)                                                         \
+    do {                                                                         \
+        _Pragma("unroll") for (int p = 0; p < 8; ++p) {                          \
+            const uint32_t mask = 0x01010101u << p;                              \
+            const v4i a = (v4i)((w) & mask);                                     \
+            _Pragma("unroll") for (int cg = 0; cg < NB; ++cg)                    \
+                acc[cg][p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, (v4i)(b)[cg], acc[cg][p], 0, 0, 0); \
+        }                                                                        \
+    } while (0)
+
+        // prologue: D tiles in flight.  Issued unconditionally and branch-free (a short item
+        // re-reads its last tile into the unused slots) so that the number of outstanding loads
+        // at the loop head is the same on every path and the waits inside the loop stay partial.
+        {
 #pragma unroll
             for (int k = 0; k < D; ++k) {
-                int s = sb + k * W;
-                if (s < nst) {
-                    uint4 w = wbuf[k];
-                    v4i b[NB];
+                const int kk = k < cnt ? k : (cnt > 0 ? cnt - 1 : 0);
+                wbuf[k] = load_tile_words(a_base, a_off + (uint32_t)kk * (W * 1024));
 #pragma unroll
-                    for (int cg = 0; cg < NB; ++cg)
-                        b[cg] = v4i{(int)bbuf[k][cg].x, (int)bbuf[k][cg].y, (int)bbuf[k][cg].z, (int)bbuf[k][cg].w};
-                    int s2 = s + D * W;
-                    if (s2 < nst) {
-                        wbuf[k] = a_ptr[(size_t)s2 * 64];
+                for (int cg = 0; cg < NB; ++cg) bbuf[k][cg] = load_global_v4u(b_base, b_off[cg] + (uint32_t)kk * b_inc);
+            }
+            a_off += D * W * 1024;
 #pragma unroll
-                        for (int cg = 0; cg < NB; ++cg)
-                            bbuf[k][cg] = b_ok[cg] ? b_ptr[cg][(size_t)s2 * b_step] : make_uint4(0, 0, 0, 0);
-                    }
+            for (int cg = 0; cg < NB; ++cg) b_off[cg] += D * b_inc;
+        }
+        int i0 = 0;
+        // steady state: compute on a slot, then refill it; the scheduling barriers keep the
+        // loads interleaved with the compute (D-1 tiles stay in flight) instead of bunched
+        for (; i0 + 2 * D <= cnt; i0 += D) {
 #pragma unroll
-                    for (int p = 0; p < 8; ++p) {
-                        const uint32_t mask = 0x01010101u << p;
-                        v4i a = v4i{(int)(w.x & mask), (int)(w.y & mask), (int)(w.z & mask), (int)(w.w & mask)};
-#pragma unroll
-                        for (int cg = 0; cg < NB; ++cg)
-                            acc[cg][p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b[cg], acc[cg][p], 0, 0, 0);
-                    }
-                }
+            for (int k = 0; k < D; ++k) {
+                NQ_COMPUTE(wbuf[k], bbuf[k]);
+                NQ_ISSUE(k);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
+        // last D..2D-1 steps: refill only while tiles remain
+#pragma unroll
+        for (int k = 0; k < D; ++k) {
+            if (i0 + k < cnt) {
+                NQ_COMPUTE(wbuf[k], bbuf[k]);
+                if (i0 + k + D < cnt) NQ_ISSUE(k);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < D; ++k) {
+            if (i0 + D + k < cnt) {
+                NQ_COMPUTE(wbuf[k], bbuf[k]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+#undef NQ_ISSUE
+#undef NQ_COMPUTE
 
         // ---- epilogue: raw accumulators -> LDS [row][col], then one thread per (token, row) ----
         // accumulator layout of the 16x16 result: lane (g, n), register v  <->  D[row 4g+v][col n]
@@ -334,12 +384,12 @@ stage_kernel(const StageDesc* __restrict__ descs, StageDesc single, const WorkIt
                 l = -l;
             }
             double bsum = fma((double)h, 65536.0, fma((double)m, 256.0, (double)l));   // sum_n b_n q_n
-            QMeta mt = d.meta[tok];
+            QMeta mt = meta[tok];
             double val = (2.0 * bsum - mt.sumq) * (double)mt.step;
-            int64_t grow = (int64_t)rb * kTileRows + row;
-            if (grow < d.M) {
-                if (d.out_scale) val *= (double)half_bits_to_float(d.out_scale[grow]);
-                d.out[(size_t)tok * d.out_stride + grow] = (float)val;
+            int grow = rb * kTileRows + row;
+            if (grow < M) {
+                if (out_scale) val *= (double)half_bits_to_float(out_scale[grow]);
+                out[(size_t)tok * out_stride + grow] = (float)val;
             }
         }
         if (W == 1) {
@@ -376,7 +426,7 @@ template <int NB, int W>
 static int launch_stage_t(const StageDesc* d_descs, const StageDesc& single, const WorkItem* d_items, int n_items,
                           int batch, hipStream_t s)
 {
-    constexpr int D = (NB == 1) ? 6 : 4;
+    constexpr int D = (NB == 1) ? 4 : 4;
     constexpr int WPB = (W == 1) ? 4 : W;
     const int ncols = ncols_for(batch);
     size_t lds_bytes = (size_t)WPB * kTileRows * ncols * sizeof(int);

@@ -72,6 +72,7 @@ struct nq_plan_s {
     WorkItem* items1;
     WorkItem* items2;
     int n_items1, n_items2;
+    int w1, w2;                     // schedule of each stage launch (see stage_schedule)
     std::vector<nq_handle> handles;
     hipEvent_t ev[5];
     bool have_events;
@@ -343,6 +344,18 @@ static StageDesc make_s2(nq_handle h, void* y)
     return s;
 }
 
+// Row blocks chained into one item of the stream kernel for an op with `nst` steps per row block:
+// aim at stream_target_steps() steps per wave, but keep at least ~16 items per CU in the launch
+// (`total_rb` = row blocks of the whole launch).
+static int rbs_per_stream_item(int n_rb, int nst, int total_rb, int batch)
+{
+    int per = std::max(1, stream_target_steps() / std::max(1, nst));
+    per = std::min(per, stream_max_rbs(batch));
+    const int want_items = device_cu_count() * 16;
+    while (per > 1 && total_rb / per < want_items) per /= 2;
+    return std::min(per, std::max(1, n_rb));
+}
+
 // one pass of the streaming path for batch <= 8
 static int decode_once(nq_handle h, const void* x, void* y, int batch, hipStream_t s)
 {
@@ -358,10 +371,14 @@ static int decode_once(nq_handle h, const void* x, void* y, int batch, hipStream
     StageDesc s1 = make_s1(h);
     QuantDesc qt = make_qt(h);
     StageDesc s2 = make_s2(h, y);
+    const int rb1 = (int)n_rowblocks(h->r), rb2 = (int)n_rowblocks(h->d_out);
+    const int w1 = stage_schedule(rb1, s1.n_steps, batch), w2 = stage_schedule(rb2, s2.n_steps, batch);
+    const int per1 = w1 == 1 ? rbs_per_stream_item(rb1, s1.n_steps, rb1, batch) : 1;
+    const int per2 = w2 == 1 ? rbs_per_stream_item(rb2, s2.n_steps, rb2, batch) : 1;
     if ((rc = launch_quantize(nullptr, qx, 1, batch, s)) != NQ_OK) return rc;
-    if ((rc = launch_stage(nullptr, s1, nullptr, (int)n_rowblocks(h->r), batch, s)) != NQ_OK) return rc;
+    if ((rc = launch_stage(nullptr, s1, nullptr, (rb1 + per1 - 1) / per1, w1, per1, batch, s)) != NQ_OK) return rc;
     if ((rc = launch_quantize(nullptr, qt, 1, batch, s)) != NQ_OK) return rc;
-    return launch_stage(nullptr, s2, nullptr, (int)n_rowblocks(h->d_out), batch, s);
+    return launch_stage(nullptr, s2, nullptr, (rb2 + per2 - 1) / per2, w2, per2, batch, s);
 }
 
 static int check_xy(const char* who, const void* x, const void* y, size_t x_bytes, size_t y_bytes)
@@ -480,24 +497,48 @@ extern "C" int nq_plan_create(nq_plan* out, const nq_handle* hs, const void* con
 
     std::vector<QuantDesc> qx(n), qt(n);
     std::vector<StageDesc> s1(n), s2(n);
-    std::vector<WorkItem> it1, it2;
     for (int i = 0; i < n; ++i) {
         qx[i] = make_qx(hs[i], xs[i]);
         s1[i] = make_s1(hs[i]);
         qt[i] = make_qt(hs[i]);
         s2[i] = make_s2(hs[i], ys[i]);
-        for (int rb = 0; rb < (int)n_rowblocks(hs[i]->r); ++rb) it1.push_back(WorkItem{i, rb});
-        for (int rb = 0; rb < (int)n_rowblocks(hs[i]->d_out); ++rb) it2.push_back(WorkItem{i, rb});
     }
-    // longest items first: round-robin assignment of a descending list balances the waves
-    std::stable_sort(it1.begin(), it1.end(), [&](const WorkItem& a, const WorkItem& b) { return s1[a.op].n_steps > s1[b.op].n_steps; });
-    std::stable_sort(it2.begin(), it2.end(), [&](const WorkItem& a, const WorkItem& b) { return s2[a.op].n_steps > s2[b.op].n_steps; });
+    // one work list per stage launch; its shape follows the schedule the launch will use
+    int sched[2];
+    std::vector<WorkItem> lists[2];
+    for (int st = 0; st < 2; ++st) {
+        const std::vector<StageDesc>& sd = st == 0 ? s1 : s2;
+        double sq = 0, sm = 0;
+        int total_rb = 0;
+        for (int i = 0; i < n; ++i) {
+            const int nrb = (int)n_rowblocks(sd[i].M);
+            total_rb += nrb;
+            sq += (double)nrb * sd[i].n_steps * sd[i].n_steps;     // mean length seen by a streamed tile
+            sm += (double)nrb * sd[i].n_steps;
+        }
+        const int w = stage_schedule(total_rb, (int)(sq / sm), batch);
+        sched[st] = w;
+        for (int i = 0; i < n; ++i) {
+            const int nrb = (int)n_rowblocks(sd[i].M);
+            const int per = w == 1 ? rbs_per_stream_item(nrb, sd[i].n_steps, total_rb, batch) : 1;
+            for (int rb = 0; rb < nrb; rb += per)
+                lists[st].push_back(WorkItem{sd[i].tiles + (size_t)rb * sd[i].n_steps * kTileWords, sd[i].bq,
+                                             sd[i].n_steps, i, rb, std::min(per, nrb - rb)});
+        }
+        // longest items first: the hardware dispatches workgroups in order, so the short ones fill the tail
+        std::stable_sort(lists[st].begin(), lists[st].end(), [](const WorkItem& a, const WorkItem& b) {
+            return (int64_t)a.n_steps * a.n_rb > (int64_t)b.n_steps * b.n_rb;
+        });
+    }
+    std::vector<WorkItem>& it1 = lists[0];
+    std::vector<WorkItem>& it2 = lists[1];
 
     nq_plan p = new (std::nothrow) nq_plan_s();
     if (!p) return fail(NQ_E_HIP, "nq_plan_create: out of host memory");
     p->n = n; p->batch = batch; p->device = hs[0]->device; p->alloc = nullptr; p->have_events = false;
     p->handles.assign(hs, hs + n);
     p->n_items1 = (int)it1.size(); p->n_items2 = (int)it2.size();
+    p->w1 = sched[0]; p->w2 = sched[1];
     const size_t qb = align_up(sizeof(QuantDesc) * n, 256), sb = align_up(sizeof(StageDesc) * n, 256);
     const size_t i1b = align_up(sizeof(WorkItem) * it1.size(), 256), i2b = align_up(sizeof(WorkItem) * it2.size(), 256);
     hipError_t e = hipMalloc(&p->alloc, 2 * qb + 2 * sb + i1b + i2b);
@@ -529,11 +570,11 @@ static int plan_run(nq_plan p, hipStream_t s, bool timed)
     if (timed) NQ_HIP(hipEventRecord(p->ev[0], s));
     if ((rc = launch_quantize(p->qx, qdummy, p->n, p->batch, s)) != NQ_OK) return rc;
     if (timed) NQ_HIP(hipEventRecord(p->ev[1], s));
-    if ((rc = launch_stage(p->s1, sdummy, p->items1, p->n_items1, p->batch, s)) != NQ_OK) return rc;
+    if ((rc = launch_stage(p->s1, sdummy, p->items1, p->n_items1, p->w1, stream_max_rbs(p->batch), p->batch, s)) != NQ_OK) return rc;
     if (timed) NQ_HIP(hipEventRecord(p->ev[2], s));
     if ((rc = launch_quantize(p->qt, qdummy, p->n, p->batch, s)) != NQ_OK) return rc;
     if (timed) NQ_HIP(hipEventRecord(p->ev[3], s));
-    if ((rc = launch_stage(p->s2, sdummy, p->items2, p->n_items2, p->batch, s)) != NQ_OK) return rc;
+    if ((rc = launch_stage(p->s2, sdummy, p->items2, p->n_items2, p->w2, stream_max_rbs(p->batch), p->batch, s)) != NQ_OK) return rc;
     if (timed) NQ_HIP(hipEventRecord(p->ev[4], s));
     return NQ_OK;
 }

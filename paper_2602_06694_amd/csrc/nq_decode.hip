@@ -11,6 +11,8 @@
 // b in {0,1}; sum_n (2b-1) v = 2 sum_n b v - sum_n v, with sum_n v precomputed per token.
 // Activations are exact integers (3 signed bytes per value, power-of-two step), so the
 // accumulation is exact and the only rounding is the fixed-point step itself.
+#include <algorithm>
+
 #include "nq_internal.h"
 
 namespace nq {
@@ -101,44 +103,150 @@ int launch_export(const uint32_t* d_tiles, int64_t wpr, bool transposed, int64_t
 
 // ---------------------------------------------------------------------------------------------
 // fixed-point quantisation of one token's vector (step a1 of the path when `scale` is given)
-// grid = (n_ops, batch), block = 256
+// grid = (n_ops, batch), block = kQuantThreads.  A thread owns 16-element chunks (one 16-byte
+// group of the MFMA B operand per slice); up to kQuantHeld chunks stay in registers between the
+// max pass and the rounding pass, longer vectors are read twice.
 // ---------------------------------------------------------------------------------------------
-__device__ inline float block_max(float v, float* sm)
+constexpr int kQuantThreads = 1024;
+constexpr int kQuantHeld = 2;
+
+__device__ inline void load_chunk16(const QuantDesc& d, int64_t base, int c, bool vec, float v[16])
 {
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
-    __syncthreads();
-    float r = fmaxf(fmaxf(sm[0], sm[1]), fmaxf(sm[2], sm[3]));
-    __syncthreads();
-    return r;
+    const int j0 = c * 16;
+    if (vec && j0 + 16 <= d.N) {
+        if (d.dtype == NQ_F32) {
+            const float4* p = (const float4*)((const float*)d.x + base + j0);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float4 f = p[q];
+                v[4 * q] = f.x; v[4 * q + 1] = f.y; v[4 * q + 2] = f.z; v[4 * q + 3] = f.w;
+            }
+        } else {
+            const uint4* p = (const uint4*)((const uint16_t*)d.x + base + j0);
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                uint4 u = p[q];
+                uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    uint16_t lo = (uint16_t)(w[i] & 0xFFFFu), hi = (uint16_t)(w[i] >> 16);
+                    v[8 * q + 2 * i] = d.dtype == NQ_F16 ? half_bits_to_float(lo) : bf16_bits_to_float(lo);
+                    v[8 * q + 2 * i + 1] = d.dtype == NQ_F16 ? half_bits_to_float(hi) : bf16_bits_to_float(hi);
+                }
+            }
+        }
+        if (d.scale) {
+            const uint4* sp = (const uint4*)(d.scale + j0);
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                uint4 u = sp[q];
+                uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    v[8 * q + 2 * i] *= half_bits_to_float((uint16_t)(w[i] & 0xFFFFu));
+                    v[8 * q + 2 * i + 1] *= half_bits_to_float((uint16_t)(w[i] >> 16));
+                }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int j = j0 + i;
+            float f = 0.f;                                  // padding beyond N contributes nothing
+            if (j < d.N) {
+                f = load_as_float(d.x, d.dtype, base + j);
+                if (d.scale) f *= half_bits_to_float(d.scale[j]);
+            }
+            v[i] = f;
+        }
+    }
 }
 
-__global__ void __launch_bounds__(256)
+__device__ inline long long quantize_chunk16(const float v[16], float inv_step, bool bad, uint4* dst)
+{
+    uint32_t hi[4] = {0, 0, 0, 0}, mid[4] = {0, 0, 0, 0}, lo[4] = {0, 0, 0, 0};
+    int sum = 0;                                            // |q| <= 2^22, 16 of them: fits
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int q = bad ? 0 : (int)rintf(v[i] * inv_step);
+        sum += q;
+        const int l = ((q + 128) & 255) - 128;
+        const int q1 = (q - l) >> 8;
+        const int mm = ((q1 + 128) & 255) - 128;
+        const int h = (q1 - mm) >> 8;
+        const int sh = 8 * (i & 3);
+        hi[i >> 2] |= (uint32_t)(h & 255) << sh;
+        mid[i >> 2] |= (uint32_t)(mm & 255) << sh;
+        lo[i >> 2] |= (uint32_t)(l & 255) << sh;
+    }
+    dst[0] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+    dst[1] = make_uint4(mid[0], mid[1], mid[2], mid[3]);
+    dst[2] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+    return sum;
+}
+
+__global__ void __launch_bounds__(kQuantThreads)
 quantize_kernel(const QuantDesc* __restrict__ descs, QuantDesc single, int batch)
 {
-    __shared__ float smf[4];
-    __shared__ double smd[4];
+    __shared__ float smf[kQuantThreads / 64];
+    __shared__ double smd[kQuantThreads / 64];
+    __shared__ int sm_bad;
     const QuantDesc d = descs ? descs[blockIdx.x] : single;
     const int tok = blockIdx.y;
     const int ncols = ncols_for(batch);
     const int64_t base = (int64_t)tok * d.x_stride;
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6;
+    // 16-byte vector loads need every token row (and the row start) to be 16-byte aligned
+    const int esz = d.dtype == NQ_F32 ? 4 : 2;
+    const bool vec = (((size_t)d.x_stride * esz) & 15) == 0;
+    const bool held = d.n_chunks <= kQuantThreads * kQuantHeld;
+    if (tid == 0) sm_bad = 0;
+    __syncthreads();
 
-    // pass 1: max |v|; any NaN/Inf is remembered separately (fmaxf drops NaN)
+    // pass 1: max |v|; NaN/Inf is remembered separately (fmaxf drops NaN)
+    float hv[kQuantHeld][16];
     float m = 0.f;
     int bad = 0;
-    for (int j = threadIdx.x; j < d.N; j += 256) {
-        float v = load_as_float(d.x, d.dtype, base + j);
-        if (d.scale) v *= half_bits_to_float(d.scale[j]);
-        if (!(fabsf(v) <= 3.0e38f)) bad = 1;
-        m = fmaxf(m, fabsf(v));
+    if (held) {
+#pragma unroll
+        for (int k = 0; k < kQuantHeld; ++k) {
+            const int c = tid + k * kQuantThreads;
+            if (c < d.n_chunks) {
+                load_chunk16(d, base, c, vec, hv[k]);
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float a = fabsf(hv[k][i]);
+                    if (!(a <= 3.0e38f)) bad = 1;
+                    m = fmaxf(m, a);
+                }
+            }
+        }
+    } else {
+        for (int c = tid; c < d.n_chunks; c += kQuantThreads) {
+            float v[16];
+            load_chunk16(d, base, c, vec, v);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float a = fabsf(v[i]);
+                if (!(a <= 3.0e38f)) bad = 1;
+                m = fmaxf(m, a);
+            }
+        }
     }
-    m = block_max(m, smf);
-    bad = __syncthreads_or(bad);
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    if ((tid & 63) == 0) smf[wave] = m;
+    if (bad) sm_bad = 1;
+    __syncthreads();
+    m = smf[0];
+#pragma unroll
+    for (int w = 1; w < kQuantThreads / 64; ++w) m = fmaxf(m, smf[w]);
+    bad = sm_bad;
 
     // step = 2^(e-22) with m = f * 2^e, f in [0.5, 1)  ->  |q| <= 2^22
     int e = 0;
     float step = 1.0f;
-    if (m > 0.f) {
+    if (m > 0.f && !bad) {
         (void)frexpf(m, &e);
         int se = e - 22;
         se = se < -126 ? -126 : se;            // stay a normal float; tiny inputs just lose bits
@@ -149,38 +257,29 @@ quantize_kernel(const QuantDesc* __restrict__ descs, QuantDesc single, int batch
     // pass 2: q = rint(v / step), split into three signed bytes, write the MFMA B-operand layout
     long long local_sum = 0;
     const int c0 = col_of(tok, 0);
-    for (int c = threadIdx.x; c < d.n_chunks; c += 256) {
-        uint32_t hi[4] = {0, 0, 0, 0}, mid[4] = {0, 0, 0, 0}, lo[4] = {0, 0, 0, 0};
-        for (int i = 0; i < 16; ++i) {
-            int j = c * 16 + i;
-            int q = 0;
-            if (j < d.N && !bad) {
-                float v = load_as_float(d.x, d.dtype, base + j);
-                if (d.scale) v *= half_bits_to_float(d.scale[j]);
-                q = (int)rintf(v * inv_step);
-            }
-            local_sum += q;
-            int l = ((q + 128) & 255) - 128;
-            int q1 = (q - l) >> 8;
-            int mm = ((q1 + 128) & 255) - 128;
-            int h = (q1 - mm) >> 8;
-            int sh = 8 * (i & 3);
-            hi[i >> 2] |= (uint32_t)(h & 255) << sh;
-            mid[i >> 2] |= (uint32_t)(mm & 255) << sh;
-            lo[i >> 2] |= (uint32_t)(l & 255) << sh;
+    if (held) {
+#pragma unroll
+        for (int k = 0; k < kQuantHeld; ++k) {
+            const int c = tid + k * kQuantThreads;
+            if (c < d.n_chunks)
+                local_sum += quantize_chunk16(hv[k], inv_step, bad, (uint4*)(d.bq) + ((size_t)c * ncols + c0));
         }
-        uint4* dst = (uint4*)(d.bq) + ((size_t)c * ncols + c0);
-        dst[0] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-        dst[1] = make_uint4(mid[0], mid[1], mid[2], mid[3]);
-        dst[2] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+    } else {
+        for (int c = tid; c < d.n_chunks; c += kQuantThreads) {
+            float v[16];
+            load_chunk16(d, base, c, vec, v);
+            local_sum += quantize_chunk16(v, inv_step, bad, (uint4*)(d.bq) + ((size_t)c * ncols + c0));
+        }
     }
     double s = (double)local_sum;               // |sum| < 2^39: exact
     for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
-    if ((threadIdx.x & 63) == 0) smd[threadIdx.x >> 6] = s;
+    if ((tid & 63) == 0) smd[wave] = s;
     __syncthreads();
-    if (threadIdx.x == 0) {
+    if (tid == 0) {
         QMeta mt;
-        mt.sumq = smd[0] + smd[1] + smd[2] + smd[3];
+        double tot = 0.0;
+        for (int w = 0; w < kQuantThreads / 64; ++w) tot += smd[w];
+        mt.sumq = tot;
         mt.step = bad ? __builtin_nanf("") : step;
         mt.pad = 0.f;
         d.meta[tok] = mt;
@@ -189,75 +288,265 @@ quantize_kernel(const QuantDesc* __restrict__ descs, QuantDesc single, int batch
 
 int launch_quantize(const QuantDesc* d_descs, const QuantDesc& single, int n_ops, int batch, hipStream_t s)
 {
-    hipLaunchKernelGGL(quantize_kernel, dim3(n_ops, batch), dim3(256), 0, s, d_descs, single, batch);
+    hipLaunchKernelGGL(quantize_kernel, dim3(n_ops, batch), dim3(kQuantThreads), 0, s, d_descs, single, batch);
     NQ_HIP(hipGetLastError());
     return NQ_OK;
 }
 
 // ---------------------------------------------------------------------------------------------
-// streaming sign-matrix x fixed-point-vector kernel (steps a2 and a4, with a5 fused in stage 2)
+// streaming sign-matrix x fixed-point-vector kernels (steps a2 and a4, with a5 fused in stage 2)
 //   NB : number of 16-column groups of the B operand (1: batch <= 5, 2: batch 6..8)
-//   W  : wavefronts that share one work item (1: every wave walks its own items;
-//        4 / 16: the workgroup's waves interleave the 64-column steps of one item and are
-//        summed through LDS -- for launches with too few items to fill the chip)
-//   D  : software prefetch depth (tiles in flight per wave)
-// A work item is one 128-row block of one op, over the whole reduction length.
+//   D  : software prefetch ring (tiles per wave; D-1 stay in flight while one is consumed)
+// Two schedules over the same tiles:
+//   stage_stream_kernel : one wave per work item.  An item is a run of consecutive 128-row blocks
+//       of one op; their tiles are contiguous in memory, so the prefetch ring keeps running across
+//       block boundaries and only the accumulators are flushed there.  For short reductions.
+//   stage_split_kernel<W> : W waves of one workgroup interleave the 64-column steps of ONE row
+//       block and are summed through LDS.  For long reductions, and for launches with too few row
+//       blocks to fill the chip.
+// Either way a grid as large as the item list makes the hardware workgroup dispatcher the work
+// queue (the list is sorted longest first).
 // ---------------------------------------------------------------------------------------------
 #ifndef NQ_STAGE_WAVES
 #define NQ_STAGE_WAVES 4
 #endif
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
-
-// streamed once, never reused: keep the sign tiles from displacing the (reused) activations in cache
 typedef const __attribute__((address_space(1))) v4u* gptr_v4u;    // global (not generic) address space
-__device__ inline v4u load_tile_words(const char* base, uint32_t off)
+
+// sign tiles are streamed once, never reused: keep them from displacing the (reused) activations
+__device__ __forceinline__ v4u load_tile_words(const char* base, uint32_t off)
 {
     return __builtin_nontemporal_load((gptr_v4u)(base + off));
 }
-__device__ inline v4u load_global_v4u(const char* base, uint32_t off) { return *(gptr_v4u)(base + off); }
+__device__ __forceinline__ v4u load_global_v4u(const char* base, uint32_t off) { return *(gptr_v4u)(base + off); }
 
-template <int NB, int W, int D>
-__global__ void __launch_bounds__(W == 1 ? 256 : 64 * W) __attribute__((amdgpu_waves_per_eu(NB == 1 ? NQ_STAGE_WAVES : 2, 8)))
-stage_kernel(const StageDesc* __restrict__ descs, StageDesc single, const WorkItem* __restrict__ items, int n_items,
-             int batch)
+// one 64-column step: eight bit planes, each one AND per register and one MFMA per column group
+template <int NB>
+__device__ __forceinline__ void mac_tile(v4i (&acc)[NB][8], const v4u w, const v4u (&b)[NB])
+{
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        const uint32_t mask = 0x01010101u << p;
+        const v4i a = (v4i)(w & mask);
+#pragma unroll
+        for (int cg = 0; cg < NB; ++cg)
+            acc[cg][p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, (v4i)b[cg], acc[cg][p], 0, 0, 0);
+    }
+}
+
+struct EpilogueArgs {
+    const QMeta* meta;
+    const uint16_t* out_scale;
+    float* out;
+    int M, out_stride;
+};
+
+// raw accumulators -> LDS [col][row] -> one thread per (token, row): undo the plane weights,
+// join the three byte slices, apply 2*sum(b q) - sum(q), the step and the output scale.
+// W = 1: `lds` is this wave's private region and only the wave synchronises;
+// W > 1: `lds` is the workgroup's buffer of W regions and the partial sums of the W waves are added.
+// DEFER: the results go to `lds_out[128 * batch]` (token-major) instead of global memory; the stream
+// kernel flushes them after the item's last row block, because a pending global store in the middle
+// of the stream would force every later wait on the prefetch ring down to "wait for everything"
+// (loads and stores share one in-order counter only among their own kind).
+template <int NB, int W, bool DEFER>
+__device__ __forceinline__ void stage_epilogue(const v4i (&acc)[NB][8], int* lds, int wave, int lane, int ncols,
+                                               int batch, int rb, const EpilogueArgs& e, float* lds_out)
+{
+    const int g = lane >> 4, n = lane & 15;
+    int* my_lds = (W == 1) ? lds : lds + wave * (kTileRows * ncols);
+    // accumulator layout of the 16x16 result: lane (g, n), register v  <->  D[row 4g+v][col n];
+    // the four registers of a plane are four consecutive rows: one 16-byte LDS write per plane
+#pragma unroll
+    for (int cg = 0; cg < NB; ++cg) {
+        int col = cg * 16 + n;
+        if (col < ncols) {
+            v4i* dst = (v4i*)(my_lds + col * kTileRows + 4 * g);
+#pragma unroll
+            for (int p = 0; p < 8; ++p) dst[4 * p] = acc[cg][p];        // rows 16p + 4g .. +3
+        }
+    }
+    if (W == 1) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    } else {
+        __syncthreads();
+    }
+    constexpr int T = 64 * W;                              // threads that cooperate on the outputs
+    const int tid = (W == 1) ? lane : (int)threadIdx.x;
+    for (int o = tid; o < kTileRows * batch; o += T) {
+        int row = o & (kTileRows - 1), tok = o >> 7;
+        int c0 = col_of(tok, 0);
+        int h = 0, m = 0, l = 0;
+#pragma unroll
+        for (int w = 0; w < W; ++w) {
+            const int* q = lds + w * (kTileRows * ncols) + c0 * kTileRows + row;
+            h += q[0];
+            m += q[kTileRows];
+            l += q[2 * kTileRows];
+        }
+        // plane p holds 2^p * sum (p < 7) or -128 * sum (p = 7, the int8 sign bit): exact shifts
+        int p = row >> 4;
+        h >>= p;
+        m >>= p;
+        l >>= p;
+        if (p == 7) {
+            h = -h;
+            m = -m;
+            l = -l;
+        }
+        double bsum = fma((double)h, 65536.0, fma((double)m, 256.0, (double)l));   // sum_n b_n q_n
+        QMeta mt = e.meta[tok];
+        double val = (2.0 * bsum - mt.sumq) * (double)mt.step;
+        int grow = rb * kTileRows + row;
+        if (grow < e.M) {
+            if (e.out_scale) val *= (double)half_bits_to_float(e.out_scale[grow]);
+            if (DEFER) lds_out[o] = (float)val;
+            else e.out[(size_t)tok * e.out_stride + grow] = (float)val;
+        }
+    }
+    if (W == 1) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_wave_barrier();
+    } else {
+        __syncthreads();
+    }
+}
+
+#define NQ_LOAD_ITEM()                                                                             \
+    const uint32_t* tiles;                                                                         \
+    const uint8_t* bq;                                                                             \
+    int nst, rb0, n_rb;                                                                            \
+    EpilogueArgs ea;                                                                               \
+    if (items) {                                                                                   \
+        const WorkItem* e = items + it;                                                            \
+        tiles = e->tiles; bq = e->bq; nst = e->n_steps; rb0 = e->rb; n_rb = e->n_rb;               \
+        const StageDesc* dp = descs + e->op;                                                       \
+        ea.meta = dp->meta; ea.out_scale = dp->out_scale; ea.out = dp->out;                        \
+        ea.M = dp->M; ea.out_stride = dp->out_stride;                                              \
+    } else {                                                                                       \
+        nst = single.n_steps;                                                                      \
+        rb0 = it * rbs_per_item;                                                                   \
+        const int total_rb = (single.M + kTileRows - 1) / kTileRows;                               \
+        n_rb = total_rb - rb0 < rbs_per_item ? total_rb - rb0 : rbs_per_item;                      \
+        tiles = single.tiles + (size_t)rb0 * nst * kTileWords;                                     \
+        bq = single.bq;                                                                            \
+        ea.meta = single.meta; ea.out_scale = single.out_scale; ea.out = single.out;               \
+        ea.M = single.M; ea.out_stride = single.out_stride;                                        \
+    }
+
+template <int NB, int D>
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(NB == 1 ? NQ_STAGE_WAVES : 2, 8)))
+stage_stream_kernel(const StageDesc* __restrict__ descs, StageDesc single, const WorkItem* __restrict__ items,
+                    int n_items, int rbs_per_item, int batch)
 {
     extern __shared__ int lds[];
-    constexpr int WPB = (W == 1) ? 4 : W;               // waves per block
+    const int lane = threadIdx.x;
+    const int g = lane >> 4, n = lane & 15;
+    const int ncols = ncols_for(batch);
+    float* lds_out = (float*)(lds + kTileRows * ncols);     // [rbs of the item][batch][128 rows]
+    for (int it = blockIdx.x; it < n_items; it += gridDim.x) {
+        // descriptor fields are wave-uniform (scalar loads); what the first tile load depends on
+        // comes from the work item alone
+        NQ_LOAD_ITEM()
+        // 32-bit byte offsets from the (scalar) base pointers; a tile array is at most 512 MiB
+        const char* a_base = (const char*)tiles;
+        const char* b_base = (const char*)bq;
+        uint32_t a_off = (uint32_t)(lane * 16);
+        // lanes whose column is beyond ncols re-read column 0: their result columns are never used
+        uint32_t b_lane[NB];
+#pragma unroll
+        for (int cg = 0; cg < NB; ++cg) {
+            int col = cg * 16 + n;
+            b_lane[cg] = (uint32_t)((g * ncols + (col < ncols ? col : 0)) * 16);
+        }
+        const uint32_t b_inc = (uint32_t)(4 * ncols * 16);
+        int b_step = 0;                                    // step (inside its row block) of the next tile to fetch
+
+        v4u wbuf[D];
+        v4u bbuf[D][NB];
+        // fetch the next tile of the item's stream into slot k; the activation offset wraps at a
+        // row-block boundary (scalar arithmetic), the tile offset just runs on
+#define NQ_ISSUE(k)                                                              \
+    do {                                                                         \
+        wbuf[k] = load_tile_words(a_base, a_off);                                \
+        a_off += 1024;                                                           \
+        _Pragma("unroll") for (int cg = 0; cg < NB; ++cg)                        \
+            bbuf[k][cg] = load_global_v4u(b_base, b_lane[cg] + (uint32_t)b_step * b_inc); \
+        b_step = (b_step + 1 == nst) ? 0 : b_step + 1;                           \
+    } while (0)
+
+        // nst is a multiple of D (the tile layout pads the reduction to 4 steps), so every row
+        // block starts in slot 0 and the ring never needs a partial group
+#pragma unroll
+        for (int k = 0; k < D; ++k) {
+            NQ_ISSUE(k);
+            __builtin_amdgcn_sched_barrier(0);             // same issue order as inside the loop
+        }
+        const int groups = nst / D;
+        for (int u = 0; u < n_rb; ++u) {
+            v4i acc[NB][8];
+#pragma unroll
+            for (int cg = 0; cg < NB; ++cg)
+#pragma unroll
+                for (int p = 0; p < 8; ++p) acc[cg][p] = v4i{0, 0, 0, 0};
+            const bool last = (u == n_rb - 1);
+            // the last row block of the item must not fetch past its own tiles
+            const int n_refill = last ? groups - 1 : groups;
+            for (int gi = 0; gi < n_refill; ++gi) {
+#pragma unroll
+                for (int k = 0; k < D; ++k) {
+                    mac_tile<NB>(acc, wbuf[k], bbuf[k]);
+                    NQ_ISSUE(k);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            if (last) {
+#pragma unroll
+                for (int k = 0; k < D; ++k) {
+                    mac_tile<NB>(acc, wbuf[k], bbuf[k]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            stage_epilogue<NB, 1, true>(acc, lds, 0, lane, ncols, batch, rb0 + u, ea,
+                                        lds_out + u * (kTileRows * batch));
+        }
+#undef NQ_ISSUE
+        // flush the item's results: n_rb row blocks x batch tokens x 128 rows
+        for (int o = lane; o < n_rb * kTileRows * batch; o += 64) {
+            const int u = o / (kTileRows * batch), rem = o - u * (kTileRows * batch);
+            const int tok = rem >> 7, row = rem & (kTileRows - 1);
+            const int grow = (rb0 + u) * kTileRows + row;
+            if (grow < ea.M) ea.out[(size_t)tok * ea.out_stride + grow] = lds_out[o];
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+template <int NB, int W, int D>
+__global__ void __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(NB == 1 ? NQ_STAGE_WAVES : 2, 8)))
+stage_split_kernel(const StageDesc* __restrict__ descs, StageDesc single, const WorkItem* __restrict__ items,
+                   int n_items, int batch)
+{
+    extern __shared__ int lds[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int g = lane >> 4, n = lane & 15;
     const int ncols = ncols_for(batch);
-    int* my_lds = lds + wave * (kTileRows * ncols);
+    constexpr int rbs_per_item = 1;
+    const int st0 = wave;
 
-    const int stream = (W == 1) ? (int)blockIdx.x * WPB + wave : (int)blockIdx.x;
-    const int nstreams = (W == 1) ? (int)gridDim.x * WPB : (int)gridDim.x;
-    const int st0 = (W == 1) ? 0 : wave;
-
-    for (int it = stream; it < n_items; it += nstreams) {
-        // descriptor fields are wave-uniform: fetch them with scalar loads
-        const uint32_t* tiles;
-        const uint8_t* bq;
-        const QMeta* meta;
-        const uint16_t* out_scale;
-        float* out;
-        int M, nst, out_stride, rb;
-        if (items) {
-            const WorkItem e = items[it];
-            const StageDesc* dp = descs + e.op;
-            rb = e.rb;
-            tiles = dp->tiles; bq = dp->bq; meta = dp->meta; out_scale = dp->out_scale; out = dp->out;
-            M = dp->M; nst = dp->n_steps; out_stride = dp->out_stride;
-        } else {
-            rb = it;
-            tiles = single.tiles; bq = single.bq; meta = single.meta; out_scale = single.out_scale; out = single.out;
-            M = single.M; nst = single.n_steps; out_stride = single.out_stride;
-        }
+    for (int it = blockIdx.x; it < n_items; it += gridDim.x) {
+        NQ_LOAD_ITEM()
+        (void)n_rb;
         const int cnt = (nst - st0 + W - 1) / W;         // steps this wave performs (may be <= 0)
-        // 32-bit byte offsets from the (scalar) base pointers; a tile array is at most 512 MiB
         // (a wave with no step of its own, possible when W > nst, aims its unused prefetches at step 0)
         const int stf = cnt > 0 ? st0 : 0;
-        uint32_t a_off = (uint32_t)(((size_t)rb * nst + stf) * 1024 + lane * 16);
-        // lanes whose column is beyond ncols re-read column 0: their result columns are never used
+        const char* a_base = (const char*)tiles;
+        const char* b_base = (const char*)bq;
+        uint32_t a_off = (uint32_t)(stf * 1024 + lane * 16);
         uint32_t b_off[NB];
 #pragma unroll
         for (int cg = 0; cg < NB; ++cg) {
@@ -265,8 +554,6 @@ stage_kernel(const StageDesc* __restrict__ descs, StageDesc single, const WorkIt
             b_off[cg] = (uint32_t)(((stf * 4 + g) * ncols + (col < ncols ? col : 0)) * 16);
         }
         const uint32_t b_inc = (uint32_t)(W * 4 * ncols * 16);
-        const char* a_base = (const char*)tiles;
-        const char* b_base = (const char*)bq;
 
         v4i acc[NB][8];
 #pragma unroll
@@ -285,17 +572,8 @@ stage_kernel(const StageDesc* __restrict__ descs, StageDesc single, const WorkIt
             b_off[cg] += b_inc;                                                  \
         }                                                                        \
     } while (0)
-#define NQ_COMPUTE(w, b)                                                         \
-    do {                                                                         \
-        _Pragma("unroll") for (int p = 0; p < 8; ++p) {                          \
-            const uint32_t mask = 0x01010101u << p;                              \
-            const v4i a = (v4i)((w) & mask);                                     \
-            _Pragma("unroll") for (int cg = 0; cg < NB; ++cg)                    \
-                acc[cg][p] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, (v4i)(b)[cg], acc[cg][p], 0, 0, 0); \
-        }                                                                        \
-    } while (0)
 
-        // prologue: D tiles in flight.  Issued unconditionally and branch-free (a short item
+        // prologue: D tiles in flight.  Issued unconditionally and branch-free (a short share
         // re-reads its last tile into the unused slots) so that the number of outstanding loads
         // at the loop head is the same on every path and the waits inside the loop stay partial.
         {
@@ -316,7 +594,7 @@ stage_kernel(const StageDesc* __restrict__ descs, StageDesc single, const WorkIt
         for (; i0 + 2 * D <= cnt; i0 += D) {
 #pragma unroll
             for (int k = 0; k < D; ++k) {
-                NQ_COMPUTE(wbuf[k], bbuf[k]);
+                mac_tile<NB>(acc, wbuf[k], bbuf[k]);
                 NQ_ISSUE(k);
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -325,7 +603,7 @@ stage_kernel(const StageDesc* __restrict__ descs, StageDesc single, const WorkIt
 #pragma unroll
         for (int k = 0; k < D; ++k) {
             if (i0 + k < cnt) {
-                NQ_COMPUTE(wbuf[k], bbuf[k]);
+                mac_tile<NB>(acc, wbuf[k], bbuf[k]);
                 if (i0 + k + D < cnt) NQ_ISSUE(k);
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -333,73 +611,15 @@ stage_kernel(const StageDesc* __restrict__ descs, StageDesc single, const WorkIt
 #pragma unroll
         for (int k = 0; k < D; ++k) {
             if (i0 + D + k < cnt) {
-                NQ_COMPUTE(wbuf[k], bbuf[k]);
+                mac_tile<NB>(acc, wbuf[k], bbuf[k]);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
 #undef NQ_ISSUE
-#undef NQ_COMPUTE
-
-        // ---- epilogue: raw accumulators -> LDS [row][col], then one thread per (token, row) ----
-        // accumulator layout of the 16x16 result: lane (g, n), register v  <->  D[row 4g+v][col n]
-#pragma unroll
-        for (int cg = 0; cg < NB; ++cg) {
-            int col = cg * 16 + n;
-            if (col < ncols) {
-#pragma unroll
-                for (int p = 0; p < 8; ++p)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) my_lds[(16 * p + 4 * g + v) * ncols + col] = acc[cg][p][v];
-            }
-        }
-        if (W == 1) {
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-        } else {
-            __syncthreads();
-        }
-        constexpr int T = (W == 1) ? 64 : 64 * W;          // threads that cooperate on the outputs
-        const int tid = (W == 1) ? lane : (int)threadIdx.x;
-        const int* src = (W == 1) ? my_lds : lds;
-        for (int o = tid; o < kTileRows * batch; o += T) {
-            int row = o & (kTileRows - 1), tok = o >> 7;
-            int c0 = col_of(tok, 0);
-            int h = 0, m = 0, l = 0;
-#pragma unroll
-            for (int w = 0; w < (W == 1 ? 1 : W); ++w) {
-                const int* q = src + w * (kTileRows * ncols) + row * ncols + c0;
-                h += q[0];
-                m += q[1];
-                l += q[2];
-            }
-            // plane p holds 2^p * sum (p < 7) or -128 * sum (p = 7, the int8 sign bit): exact shifts
-            int p = row >> 4;
-            h >>= p;
-            m >>= p;
-            l >>= p;
-            if (p == 7) {
-                h = -h;
-                m = -m;
-                l = -l;
-            }
-            double bsum = fma((double)h, 65536.0, fma((double)m, 256.0, (double)l));   // sum_n b_n q_n
-            QMeta mt = meta[tok];
-            double val = (2.0 * bsum - mt.sumq) * (double)mt.step;
-            int grow = rb * kTileRows + row;
-            if (grow < M) {
-                if (out_scale) val *= (double)half_bits_to_float(out_scale[grow]);
-                out[(size_t)tok * out_stride + grow] = (float)val;
-            }
-        }
-        if (W == 1) {
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-            __builtin_amdgcn_wave_barrier();
-        } else {
-            __syncthreads();
-        }
+        stage_epilogue<NB, W, false>(acc, lds, wave, lane, ncols, batch, rb0, ea, nullptr);
     }
 }
+#undef NQ_LOAD_ITEM
 
 static int g_cu_count = 0;
 int device_cu_count()
@@ -422,49 +642,76 @@ static int env_int(const char* name, int dflt)
     return x > 0 ? x : dflt;
 }
 
-template <int NB, int W>
-static int launch_stage_t(const StageDesc* d_descs, const StageDesc& single, const WorkItem* d_items, int n_items,
-                          int batch, hipStream_t s)
+constexpr int kRingDepth = 4;        // the tile layout pads every reduction to a multiple of this many steps
+
+template <int NB>
+static int launch_stream_t(const StageDesc* d_descs, const StageDesc& single, const WorkItem* d_items, int n_items,
+                           int rbs_per_item, int max_rbs_per_item, int batch, hipStream_t s)
 {
-    constexpr int D = (NB == 1) ? 4 : 4;
-    constexpr int WPB = (W == 1) ? 4 : W;
     const int ncols = ncols_for(batch);
-    size_t lds_bytes = (size_t)WPB * kTileRows * ncols * sizeof(int);
-    int blocks;
-    if (W == 1) {
-        int per_cu = env_int("NQ_WG_PER_CU", 4);
-        int cap = device_cu_count() * per_cu;
-        blocks = (n_items + WPB - 1) / WPB;
-        if (blocks > cap) blocks = cap;
-    } else {
-        blocks = n_items;
-    }
-    if (blocks < 1) return NQ_OK;
-    hipLaunchKernelGGL((stage_kernel<NB, W, D>), dim3(blocks), dim3(64 * WPB), lds_bytes, s, d_descs, single, d_items,
-                       n_items, batch);
+    size_t lds_bytes = (size_t)kTileRows * ncols * sizeof(int) + (size_t)max_rbs_per_item * kTileRows * batch * sizeof(float);
+    if (n_items < 1) return NQ_OK;
+    hipLaunchKernelGGL((stage_stream_kernel<NB, kRingDepth>), dim3(n_items), dim3(64), lds_bytes, s, d_descs, single,
+                       d_items, n_items, rbs_per_item, batch);
     NQ_HIP(hipGetLastError());
     return NQ_OK;
 }
 
-int launch_stage(const StageDesc* d_descs, const StageDesc& single, const WorkItem* d_items, int n_items, int batch,
-                 hipStream_t s)
+template <int NB, int W>
+static int launch_split_t(const StageDesc* d_descs, const StageDesc& single, const WorkItem* d_items, int n_items,
+                          int batch, hipStream_t s)
 {
-    const int nb = batch <= 5 ? 1 : 2;
-    // enough independent items to give every SIMD of the chip a few waves?  then one wave per item
+    const int ncols = ncols_for(batch);
+    size_t lds_bytes = (size_t)W * kTileRows * ncols * sizeof(int);
+    if (n_items < 1) return NQ_OK;
+    hipLaunchKernelGGL((stage_split_kernel<NB, W, kRingDepth>), dim3(n_items), dim3(64 * W), lds_bytes, s, d_descs,
+                       single, d_items, n_items, batch);
+    NQ_HIP(hipGetLastError());
+    return NQ_OK;
+}
+
+// Which schedule a launch of `n_rb_total` row blocks with (work-weighted) mean reduction length
+// `mean_steps` takes.  Returns W: 1 = stream kernel, 4 / 16 = split kernel.
+//  - few row blocks (a single layer): split so that the launch still covers the chip;
+//  - many: long reductions (>= 64 steps) are split four ways, which shortens the longest serial
+//    stream and the tail of the launch; short ones run one wave per item, several row blocks in a
+//    row, where the LDS reduction and the barriers of a split would cost more than they give.
+int stage_schedule(int n_rb_total, int mean_steps, int batch)
+{
     const int full = device_cu_count() * 8;
-    int w = 1;
-    if (n_items < full) w = (n_items * 4 >= full || batch > 2) ? 4 : 16;
+    int w;
+    if (n_rb_total >= full) w = mean_steps >= env_int("NQ_SPLIT_STEPS", 64) ? 4 : 1;
+    else w = (n_rb_total * 4 >= full || batch > 2) ? 4 : 16;
     if (const char* f = getenv("NQ_FORCE_W")) {
         int fw = atoi(f);
         if (fw == 1 || fw == 4 || (fw == 16 && batch <= 2)) w = fw;
     }
-    if (nb == 1) {
-        if (w == 1) return launch_stage_t<1, 1>(d_descs, single, d_items, n_items, batch, s);
-        if (w == 4) return launch_stage_t<1, 4>(d_descs, single, d_items, n_items, batch, s);
-        return launch_stage_t<1, 16>(d_descs, single, d_items, n_items, batch, s);
+    return w;
+}
+
+// Steps one wave of the stream kernel should see per item (several short row blocks are chained).
+int stream_target_steps() { return env_int("NQ_STREAM_STEPS", 128); }
+
+int stream_max_rbs(int batch) { return std::max(1, 8 / batch); }
+
+int launch_stage(const StageDesc* d_descs, const StageDesc& single, const WorkItem* d_items, int n_items,
+                 int w, int rbs_per_item, int batch, hipStream_t s)
+{
+    const int nb = batch <= 5 ? 1 : 2;
+    if (w == 1) {
+        const int mx = stream_max_rbs(batch);
+        if (rbs_per_item > mx) {
+            set_error("launch_stage: item longer than the stream kernel's output buffer");
+            return NQ_E_INVALID_ARG;
+        }
+        if (nb == 1) return launch_stream_t<1>(d_descs, single, d_items, n_items, rbs_per_item, mx, batch, s);
+        return launch_stream_t<2>(d_descs, single, d_items, n_items, rbs_per_item, mx, batch, s);
     }
-    if (w == 1) return launch_stage_t<2, 1>(d_descs, single, d_items, n_items, batch, s);
-    return launch_stage_t<2, 4>(d_descs, single, d_items, n_items, batch, s);
+    if (nb == 1) {
+        if (w == 4) return launch_split_t<1, 4>(d_descs, single, d_items, n_items, batch, s);
+        return launch_split_t<1, 16>(d_descs, single, d_items, n_items, batch, s);
+    }
+    return launch_split_t<2, 4>(d_descs, single, d_items, n_items, batch, s);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -60,11 +60,22 @@ struct StageDesc {
     int reserved;
 };
 
-struct WorkItem { int op; int rb; };
+// One unit of streaming work: a run of 128-row blocks of one op, each over its whole reduction length.
+// Everything the wave needs before its first tile load sits in the item itself (one fetch).
+struct WorkItem {
+    const uint32_t* tiles;   // first tile of this row block
+    const uint8_t* bq;       // quantised input of the op
+    int n_steps;
+    int op;                  // index into the StageDesc array (epilogue fields)
+    int rb;                  // first row block of the item
+    int n_rb;                // consecutive row blocks in the item (1 for the split schedule)
+};
 
 inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
 inline int64_t n_rowblocks(int64_t M) { return (M + kTileRows - 1) / kTileRows; }
-inline int64_t n_steps(int64_t N) { return (N + kTileCols - 1) / kTileCols; }
+// the reduction is padded to a multiple of 4 steps (256 columns) so that the prefetch ring of the
+// stream kernel stays in phase across row blocks; padding tiles hold 0 bits and quantised zeros
+inline int64_t n_steps(int64_t N) { return (N + 4 * kTileCols - 1) / (4 * kTileCols) * 4; }
 inline size_t tile_words(int64_t M, int64_t N) { return (size_t)n_rowblocks(M) * n_steps(N) * kTileWords; }
 
 // ---- error plumbing ------------------------------------------------------------------------
@@ -83,8 +94,12 @@ int launch_export(const uint32_t* d_tiles, int64_t wpr, bool transposed, int64_t
                   uint32_t* d_canon, hipStream_t s);
 // single op (descriptor by value) or many (device arrays)
 int launch_quantize(const QuantDesc* d_descs, const QuantDesc& single, int n_ops, int batch, hipStream_t s);
+int stage_schedule(int n_rb_total, int mean_steps, int batch);
+int stream_target_steps();
+int stream_max_rbs(int batch);   // row blocks one stream item may chain (bounded by its LDS output buffer)
+// w = 1: stream kernel (items are runs of rbs_per_item row blocks); w = 4 / 16: split kernel (one row block per item)
 int launch_stage(const StageDesc* d_descs, const StageDesc& single, const WorkItem* d_items, int n_items,
-                 int batch, hipStream_t s);
+                 int w, int rbs_per_item, int batch, hipStream_t s);
 int launch_valu_gemv(const uint32_t* tiles, const void* x, int x_dtype, int x_stride, const uint16_t* in_scale,
                      const uint16_t* out_scale, float* out, int out_stride, int64_t M, int64_t N, int batch,
                      hipStream_t s);

@@ -295,23 +295,34 @@ extern "C" size_t nq_binlr_weight_bytes(nq_handle h)
     return (size_t)(h->r * (h->d_in + h->d_out) + 7) / 8 + 2 * (size_t)(h->d_in + h->d_out);
 }
 
+static int ensure_prefill_workspace(nq_handle h, int batch)
+{
+    const size_t need = prefill_workspace_bytes(h->d_out, h->d_in, h->r, batch);
+    if (need <= h->pf_bytes) return NQ_OK;
+    NQ_HIP(hipDeviceSynchronize());
+    if (h->pf_alloc) NQ_HIP(hipFree(h->pf_alloc));
+    h->pf_alloc = nullptr;
+    h->pf_bytes = 0;
+    NQ_HIP(hipMalloc(&h->pf_alloc, need));
+    h->pf_bytes = need;
+    NQ_HIP(hipMemset(h->pf_alloc, 0, need));
+    NQ_HIP(hipDeviceSynchronize());
+    return NQ_OK;
+}
+
 extern "C" int nq_binlr_reserve(nq_handle h, int max_batch)
 {
     if (!h) return fail(NQ_E_NULL, "nq_binlr_reserve: NULL handle");
     if (max_batch < 1) return fail(NQ_E_INVALID_ARG, "nq_binlr_reserve: max_batch must be >= 1");
-    if (max_batch < NQ_PREFILL_MIN_BATCH || (h->flags & NQ_FLAG_NO_PREFILL)) return NQ_OK;   // decode workspace is fixed
-    if (max_batch <= h->pf_batch) return NQ_OK;
-    size_t need = prefill_workspace_bytes(h->d_out, h->d_in, h->r, max_batch);
-    if (need > h->pf_bytes) {
-        NQ_HIP(hipDeviceSynchronize());
-        if (h->pf_alloc) NQ_HIP(hipFree(h->pf_alloc));
-        h->pf_alloc = nullptr;
-        h->pf_bytes = 0;
-        h->pf_batch = 0;
-        NQ_HIP(hipMalloc(&h->pf_alloc, need));
-        h->pf_bytes = need;
+    if (max_batch < NQ_PREFILL_MIN_BATCH || (h->flags & (NQ_FLAG_NO_PREFILL | NQ_FLAG_DECODE_VALU))) return NQ_OK;   // decode workspace is fixed
+    // the dense path's workspace need is not monotone in the batch (small batches split the
+    // reduction and keep partial sums): size it for every power of two up to max_batch
+    for (int b = NQ_PREFILL_MIN_BATCH; ; b *= 2) {
+        int rc = ensure_prefill_workspace(h, std::min(b, max_batch));
+        if (rc != NQ_OK) return rc;
+        if (b >= max_batch) break;
     }
-    h->pf_batch = max_batch;
+    h->pf_batch = std::max(h->pf_batch, max_batch);
     return NQ_OK;
 }
 
@@ -401,7 +412,7 @@ extern "C" int nq_binlr_forward(nq_handle h, const void* x, void* y, int batch, 
     hipStream_t s = (hipStream_t)stream;
     if (batch <= NQ_DECODE_MAX_BATCH) return decode_once(h, x, y, batch, s);
     if (batch >= NQ_PREFILL_MIN_BATCH && !(h->flags & (NQ_FLAG_NO_PREFILL | NQ_FLAG_DECODE_VALU))) {
-        if (batch > h->pf_batch && (rc = nq_binlr_reserve(h, batch)) != NQ_OK) return rc;
+        if ((rc = ensure_prefill_workspace(h, batch)) != NQ_OK) return rc;
         PrefillArgs a;
         a.vt_tiles = h->vt_tiles; a.u_tiles = h->u_tiles; a.s_in = h->s_in; a.s_out = h->s_out;
         a.x = x; a.y = (float*)y; a.workspace = h->pf_alloc;

@@ -1,14 +1,462 @@
-// Dense (prefill, batch >= 64) path -- placeholder until the MFMA GEMM kernels land.
+// Dense (prefill, batch >= 64) path of  y = s_out (.) (U (V^T (s_in (.) x)))   (Section 3.1 Eq. 1;
+// Appendix D, "Binary GEMM"): both contractions run on the fp16 matrix cores of gfx950.
+//
+//   pre   : x'' = fp16( s_in (.) x * 2^a_b )          per token b, 2^a_b puts max|x''| in [2^12, 2^13)
+//   gemm1 : T   = fp16( (X'' V) * g )                 g = power of two so that |T| <= 2^15 always
+//   gemm2 : y   = (T U^T) (.) s_out / (2^a_b * g)     fp32 out
+//
+// The sign matrices stay in the 1-bit tile layout of the streaming kernels.  A wave owns 128
+// output rows (one tile row block) and expands each 16-byte tile fragment in registers into the
+// +-1.0 fp16 A operands of v_mfma_f32_16x16x32_f16 with one shift + one bit-field insert per two
+// weights; the 128-token activation tile is shared by the four waves of a workgroup through LDS.
+// Bit = 1 lands in the fp16 sign bit, i.e. the operand is the NEGATED sign: the minus is folded
+// into the epilogue factors.
+//
+// fp16 (not bf16) operands: +-1 is exact in both and the MFMA rate is the same, but rounding x'
+// and t to 8 mantissa bits breaks the 1e-3 parity bar while 11 bits hold it with margin.
+//
+// Activation element order.  The two half2 registers made from one tile word hold reduction
+// indices (k0, k2) and (k1, k3); instead of permuting registers, X'' and T are STORED with the
+// middle two elements of every aligned group of four swapped, so a plain 16-byte LDS read yields
+// the matching B operand.
+#include <algorithm>
+#include <type_traits>
+
 #include "nq_internal.h"
 
 namespace nq {
 
-size_t prefill_workspace_bytes(int64_t, int64_t, int64_t, int) { return 0; }
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef unsigned int v4u32 __attribute__((ext_vector_type(4)));
 
-int launch_prefill(const PrefillArgs&, hipStream_t)
+constexpr int kPfTokens = 128;          // tokens per workgroup tile
+constexpr int kPfWaves = 4;             // waves per workgroup, one 128-row block each
+constexpr int kPfLdsStride = 72;        // halves per token row in LDS (64 + 8: conflict-free 16-byte reads)
+constexpr int kPfThreads = 64 * kPfWaves;
+
+enum { EPI_PARTIAL = 0, EPI_T = 1, EPI_Y = 2 };
+
+struct GemmArgs {
+    const _Float16* act;       // [m_pad][lda] halves, element order swizzled (see above)
+    const uint32_t* tiles;     // sign tiles of the weight: rows = outputs, columns = reduction
+    float* partial;            // EPI_PARTIAL: [splits][m_pad][n_pad] raw accumulators
+    _Float16* t_out;           // EPI_T: [m_pad][ldt]
+    float* y_out;              // EPI_Y: [batch][n_real]
+    const float* tok_scale;    // EPI_Y: per token 1 / (2^a_b * g)
+    const uint16_t* out_scale; // EPI_Y: fp16 [n_real]
+    float t_scale;             // EPI_T: g
+    int lda, ldt;
+    int n_real;                // real output rows
+    int n_rb;                  // row blocks of the weight
+    int nst;                   // 64-column steps of the reduction
+    int m_tiles, n_tiles;      // workgroup grid
+    int batch;                 // real tokens
+    int splits, steps_per_split;
+    int n_pad, m_pad;
+};
+
+__device__ __forceinline__ float h2f(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
+
+// ---------------------------------------------------------------------------------------------
+// pre-scale: one workgroup per token
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float pf_load(const void* p, int dtype, int64_t i)
 {
-    set_error("prefill path not built");
-    return NQ_E_UNSUPPORTED;
+    if (dtype == NQ_F32) return ((const float*)p)[i];
+    if (dtype == NQ_F16) return h2f(((const uint16_t*)p)[i]);
+    return __builtin_bit_cast(float, (uint32_t)((const uint16_t*)p)[i] << 16);
+}
+
+__global__ void __launch_bounds__(256)
+prefill_prescale_kernel(const void* __restrict__ x, int x_dtype, const uint16_t* __restrict__ s_in, int d_in, int lda,
+                        float g_t, _Float16* __restrict__ xs, float* __restrict__ tok_scale)
+{
+    __shared__ float sm[4];
+    const int tok = blockIdx.x;
+    const int64_t base = (int64_t)tok * d_in;
+    float m = 0.f;
+    for (int j = threadIdx.x; j < d_in; j += 256) m = fmaxf(m, fabsf(pf_load(x, x_dtype, base + j) * h2f(s_in[j])));
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(sm[0], sm[1]), fmaxf(sm[2], sm[3]));
+    // 2^a with max * 2^a in [2^12, 2^13); a NaN/Inf token keeps a = 0 and poisons only itself
+    float sc = 1.0f;
+    if (m > 0.f && m <= 3.0e38f) {
+        int e;
+        (void)frexpf(m, &e);
+        int a = 13 - e;
+        a = a > 100 ? 100 : (a < -100 ? -100 : a);
+        sc = ldexpf(1.0f, a);
+    }
+    _Float16* row = xs + (size_t)tok * lda;
+    for (int j = threadIdx.x; j < lda; j += 256) {
+        // storage position j holds reduction index k: middle two of every four swapped
+        const int s = j & 3;
+        const int k = (j & ~3) | (s == 1 ? 2 : (s == 2 ? 1 : s));
+        float v = 0.f;
+        if (k < d_in) v = pf_load(x, x_dtype, base + k) * h2f(s_in[k]) * sc;
+        row[j] = (_Float16)v;
+    }
+    if (threadIdx.x == 0) tok_scale[tok] = 1.0f / (sc * g_t);
+}
+
+// ---------------------------------------------------------------------------------------------
+// GEMM:  C[token][n] = sum_k act[token][k] * sign(tiles[n][k])
+// grid = (m_tiles * n_tiles, splits); block = 256 (4 waves x 128 output rows, 128 tokens)
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t bfi_sign(uint32_t x)
+{
+    // sign bits of both halves from x, everything else from the pattern of +1.0
+    return (x & 0x80008000u) | 0x3C003C00u;
+}
+
+template <int EPI>
+__global__ void __launch_bounds__(kPfThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+prefill_gemm_kernel(GemmArgs a)
+{
+    __shared__ __attribute__((aligned(16))) _Float16 lds_act[2][kPfTokens * kPfLdsStride];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4, j = lane & 15;
+
+    // workgroups that share a token tile run on the same XCD (ids are dealt round-robin to the
+    // 8 XCDs) so the activation tile is fetched into that XCD's L2 once
+    const int total = a.m_tiles * a.n_tiles;
+    int id = blockIdx.x;
+    {
+        const int per = total / 8;
+        if (id < per * 8) id = (id & 7) * per + (id >> 3);
+    }
+    const int m_tile = id / a.n_tiles, n_tile = id - m_tile * a.n_tiles;
+    const int split = blockIdx.y;
+    const int s_begin = split * a.steps_per_split;
+    const int s_end = min(a.nst, s_begin + a.steps_per_split);
+    const int n_my = s_end - s_begin;
+
+    int rb = n_tile * kPfWaves + wave;
+    const bool rb_valid = rb < a.n_rb;
+    if (!rb_valid) rb = a.n_rb - 1;                        // keep loading valid memory, store nothing
+    const int m0 = m_tile * kPfTokens;
+
+    // activation tile: 128 tokens x 64 halves = 1024 chunks of 16 bytes, 4 per thread:
+    // chunk c = tid + 256 i  ->  token c / 8, 16-byte column c % 8
+    const int ld_tok = tid >> 3, ld_kc = tid & 7;                       // chunk i adds 32 tokens
+    const _Float16* act_ptr = a.act + (size_t)(m0 + ld_tok) * a.lda + (size_t)s_begin * 64 + ld_kc * 8;
+    const size_t act_i = (size_t)32 * a.lda;
+    const int lds_off = ld_tok * kPfLdsStride + ld_kc * 8;
+    const v4u32* w_ptr = (const v4u32*)a.tiles + ((size_t)rb * a.nst + s_begin) * 64 + lane;
+
+    v4f acc[8][8];
+#pragma unroll
+    for (int p = 0; p < 8; ++p)
+#pragma unroll
+        for (int tg = 0; tg < 8; ++tg) acc[p][tg] = v4f{0.f, 0.f, 0.f, 0.f};
+
+    // two register sets for the activation chunks and the tile words: set (s & 1) belongs to step s
+    // (named registers, not arrays: arrays that are written under a condition end up in LDS)
+    uint4 a00, a01, a02, a03, a10, a11, a12, a13;
+    v4u32 wr0, wr1;
+#define PF_LOAD_ACT(R, step)                                                             \
+    do {                                                                                 \
+        const _Float16* q = act_ptr + (size_t)(step) * 64;                               \
+        R##0 = *(const uint4*)(q);                                                       \
+        R##1 = *(const uint4*)(q + act_i);                                               \
+        R##2 = *(const uint4*)(q + 2 * act_i);                                           \
+        R##3 = *(const uint4*)(q + 3 * act_i);                                           \
+    } while (0)
+#define PF_STORE_ACT(buf, R)                                                             \
+    do {                                                                                 \
+        _Float16* q = &lds_act[buf][lds_off];                                            \
+        *(uint4*)(q) = R##0;                                                             \
+        *(uint4*)(q + 32 * kPfLdsStride) = R##1;                                         \
+        *(uint4*)(q + 64 * kPfLdsStride) = R##2;                                         \
+        *(uint4*)(q + 96 * kPfLdsStride) = R##3;                                         \
+    } while (0)
+    // one reduction step on LDS buffer CUR with tile words W; the planes are kept in program
+    // order (scheduling barriers) so that only one expanded operand is alive at a time
+#define PF_MFMA(P, TG, B) acc[P][TG] = __builtin_amdgcn_mfma_f32_16x16x32_f16(aop, B, acc[P][TG], 0, 0, 0)
+#define PF_COMPUTE(CUR, W)                                                               \
+    do {                                                                                 \
+        const _Float16* lds_row = &lds_act[CUR][j * kPfLdsStride + 16 * g];              \
+        _Pragma("unroll") for (int h = 0; h < 2; ++h) {                                  \
+            /* named registers (not an array): the B operands of the 8 token groups */   \
+            const v8h b0 = *(const v8h*)(lds_row + 0 * 16 * kPfLdsStride + 8 * h);       \
+            const v8h b1 = *(const v8h*)(lds_row + 1 * 16 * kPfLdsStride + 8 * h);       \
+            const v8h b2 = *(const v8h*)(lds_row + 2 * 16 * kPfLdsStride + 8 * h);       \
+            const v8h b3 = *(const v8h*)(lds_row + 3 * 16 * kPfLdsStride + 8 * h);       \
+            const v8h b4 = *(const v8h*)(lds_row + 4 * 16 * kPfLdsStride + 8 * h);       \
+            const v8h b5 = *(const v8h*)(lds_row + 5 * 16 * kPfLdsStride + 8 * h);       \
+            const v8h b6 = *(const v8h*)(lds_row + 6 * 16 * kPfLdsStride + 8 * h);       \
+            const v8h b7 = *(const v8h*)(lds_row + 7 * 16 * kPfLdsStride + 8 * h);       \
+            const uint32_t w0 = h == 0 ? W.x : W.z, w1 = h == 0 ? W.y : W.w;             \
+            _Pragma("unroll") for (int p = 0; p < 8; ++p) {                              \
+                v4u32 au;                                                                \
+                au.x = bfi_sign(w0 << (15 - p));                                         \
+                au.y = bfi_sign(p == 7 ? w0 : (w0 << (7 - p)));                          \
+                au.z = bfi_sign(w1 << (15 - p));                                         \
+                au.w = bfi_sign(p == 7 ? w1 : (w1 << (7 - p)));                          \
+                const v8h aop = __builtin_bit_cast(v8h, au);                             \
+                PF_MFMA(p, 0, b0); PF_MFMA(p, 1, b1); PF_MFMA(p, 2, b2); PF_MFMA(p, 3, b3); \
+                PF_MFMA(p, 4, b4); PF_MFMA(p, 5, b5); PF_MFMA(p, 6, b6); PF_MFMA(p, 7, b7); \
+                __builtin_amdgcn_sched_barrier(0);                                       \
+            }                                                                            \
+        }                                                                                \
+    } while (0)
+
+    // byte b of a tile word holds reduction index 4v+b, its bit p the row 16p + lane%16:
+    // shifting by 15-p puts (k0, k2) into the two fp16 sign bits, by 7-p (k1, k3)
+    // n_my is even (the reduction is padded to 4 steps and splits are even), and the loop body is
+    // branch-free: prefetches past the end re-read the last step instead of being skipped, so no
+    // control-flow join forces copies of the 256 accumulator registers
+    if (n_my > 0) {
+        const int last = n_my - 1;
+        // prologue: step 0 into LDS, step 1 into registers, tile words of steps 0 and 1
+        PF_LOAD_ACT(a0, 0);
+        wr0 = w_ptr[0];
+        PF_LOAD_ACT(a1, 1);
+        wr1 = w_ptr[64];
+        PF_STORE_ACT(0, a0);
+        __syncthreads();
+        for (int s = 0; s < n_my; s += 2) {
+            {   // even step: LDS buffer 0; register set 0 is free for step s+2
+                const v4u32 w = wr0;
+                const int nx = min(s + 2, last);
+                PF_LOAD_ACT(a0, nx);
+                wr0 = w_ptr[(size_t)nx * 64];
+                PF_COMPUTE(0, w);
+                // buffer 1 was last read in step s-1, before the previous barrier
+                PF_STORE_ACT(1, a1);
+                __syncthreads();
+            }
+            {   // odd step: LDS buffer 1
+                const v4u32 w = wr1;
+                const int nx = min(s + 3, last);
+                PF_LOAD_ACT(a1, nx);
+                wr1 = w_ptr[(size_t)nx * 64];
+                PF_COMPUTE(1, w);
+                PF_STORE_ACT(0, a0);
+                __syncthreads();
+            }
+        }
+    }
+#undef PF_LOAD_ACT
+#undef PF_STORE_ACT
+#undef PF_COMPUTE
+#undef PF_MFMA
+
+    if (!rb_valid) return;
+    // result layout: lane (g, j), register v of acc[p][tg]  <->  C[token m0 + 16 tg + j][row 128 rb + 16 p + 4 g + v]
+    // (the operands were negated signs, so every factor below carries a minus)
+#pragma unroll
+    for (int tg = 0; tg < 8; ++tg) {
+        const int tok = m0 + tg * 16 + j;
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+            const int n0 = rb * kTileRows + 16 * p + 4 * g;
+            const v4f c = acc[p][tg];
+            if (EPI == EPI_PARTIAL) {
+                float* dst = a.partial + ((size_t)split * a.m_pad + tok) * a.n_pad + n0;
+                *(v4f*)dst = c;
+            } else if (EPI == EPI_T) {
+                const float f = -a.t_scale;
+                v4h o;
+                // rows >= n_real are padding of the next reduction: exact zeros
+                o.x = (_Float16)(n0 + 0 < a.n_real ? c.x * f : 0.f);
+                o.y = (_Float16)(n0 + 2 < a.n_real ? c.z * f : 0.f);     // swizzled order 0,2,1,3
+                o.z = (_Float16)(n0 + 1 < a.n_real ? c.y * f : 0.f);
+                o.w = (_Float16)(n0 + 3 < a.n_real ? c.w * f : 0.f);
+                *(v4h*)(a.t_out + (size_t)tok * a.ldt + n0) = o;
+            } else {
+                if (tok < a.batch) {
+                    const float f = -a.tok_scale[tok];
+                    float* dst = a.y_out + (size_t)tok * a.n_real + n0;
+                    const float cv[4] = {c.x, c.y, c.z, c.w};
+                    if ((a.n_real & 3) == 0) {             // rows are 16-byte aligned: one store per lane
+                        if (n0 < a.n_real) {
+                            const uint2 sc = *(const uint2*)(a.out_scale + n0);
+                            v4f o;
+                            o.x = cv[0] * f * h2f((uint16_t)(sc.x & 0xFFFFu));
+                            o.y = cv[1] * f * h2f((uint16_t)(sc.x >> 16));
+                            o.z = cv[2] * f * h2f((uint16_t)(sc.y & 0xFFFFu));
+                            o.w = cv[3] * f * h2f((uint16_t)(sc.y >> 16));
+                            *(v4f*)dst = o;
+                        }
+                    } else {
+#pragma unroll
+                        for (int v = 0; v < 4; ++v)
+                            if (n0 + v < a.n_real) dst[v] = cv[v] * f * h2f(a.out_scale[n0 + v]);
+                    }
+                }
+            }
+        }
+    }
+}
+
+// sum the split-K partials and apply the epilogue; one thread per four consecutive outputs
+template <int EPI>
+__global__ void __launch_bounds__(256)
+prefill_finalize_kernel(GemmArgs a)
+{
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const int n4 = a.n_pad / 4;
+    const size_t total = (size_t)a.m_pad * n4;
+    if (idx >= total) return;
+    const int tok = (int)(idx / n4), n0 = (int)(idx % n4) * 4;
+    v4f c = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < a.splits; ++s) c += *(const v4f*)(a.partial + ((size_t)s * a.m_pad + tok) * a.n_pad + n0);
+    if (EPI == EPI_T) {
+        const float f = -a.t_scale;
+        v4h o;
+        o.x = (_Float16)(n0 + 0 < a.n_real ? c.x * f : 0.f);
+        o.y = (_Float16)(n0 + 2 < a.n_real ? c.z * f : 0.f);
+        o.z = (_Float16)(n0 + 1 < a.n_real ? c.y * f : 0.f);
+        o.w = (_Float16)(n0 + 3 < a.n_real ? c.w * f : 0.f);
+        *(v4h*)(a.t_out + (size_t)tok * a.ldt + n0) = o;
+    } else {
+        if (tok < a.batch) {
+            const float f = -a.tok_scale[tok];
+            const float cv[4] = {c.x, c.y, c.z, c.w};
+            for (int v = 0; v < 4; ++v)
+                if (n0 + v < a.n_real) a.y_out[(size_t)tok * a.n_real + n0 + v] = cv[v] * f * h2f(a.out_scale[n0 + v]);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------
+static size_t al256(size_t v) { return (v + 255) / 256 * 256; }
+
+struct PfLayout {
+    int m_pad, k1, k2, n1_pad, n2_pad;
+    int splits1, splits2;
+    size_t off_x, off_t, off_scale, off_partial, total;
+};
+
+static int choose_splits(int m_tiles, int n_tiles, int nst)
+{
+    const int wgs = m_tiles * n_tiles;
+    const int cus = device_cu_count();
+    if (wgs >= cus) return 1;
+    int s = (cus + wgs - 1) / wgs;
+    const int max_s = std::max(1, nst / 8);               // keep at least 8 steps per split
+    s = std::min(std::min(s, max_s), 16);
+    return std::max(1, s);
+}
+
+// steps per split, rounded up to an even count (nst itself is a multiple of 4)
+static int even_steps_per_split(int nst, int splits)
+{
+    int per = (nst + splits - 1) / splits;
+    return per + (per & 1);
+}
+
+static PfLayout pf_layout(int64_t d_out, int64_t d_in, int64_t r, int batch)
+{
+    PfLayout L;
+    L.m_pad = (int)round_up(batch, kPfTokens);
+    L.k1 = (int)n_steps(d_in) * 64;
+    L.k2 = (int)n_steps(r) * 64;
+    L.n1_pad = (int)n_rowblocks(r) * kTileRows;
+    L.n2_pad = (int)n_rowblocks(d_out) * kTileRows;
+    const int m_tiles = L.m_pad / kPfTokens;
+    L.splits1 = choose_splits(m_tiles, (int)((n_rowblocks(r) + kPfWaves - 1) / kPfWaves), (int)n_steps(d_in));
+    L.splits2 = choose_splits(m_tiles, (int)((n_rowblocks(d_out) + kPfWaves - 1) / kPfWaves), (int)n_steps(r));
+    size_t o = 0;
+    L.off_x = o; o += al256((size_t)L.m_pad * L.k1 * 2);
+    L.off_t = o; o += al256((size_t)L.m_pad * L.k2 * 2);
+    L.off_scale = o; o += al256((size_t)L.m_pad * 4);
+    L.off_partial = o;
+    size_t p1 = L.splits1 > 1 ? (size_t)L.splits1 * L.m_pad * L.n1_pad * 4 : 0;
+    size_t p2 = L.splits2 > 1 ? (size_t)L.splits2 * L.m_pad * L.n2_pad * 4 : 0;
+    o += al256(std::max(p1, p2));
+    L.total = o;
+    return L;
+}
+
+size_t prefill_workspace_bytes(int64_t d_out, int64_t d_in, int64_t r, int batch)
+{
+    return pf_layout(d_out, d_in, r, batch).total;
+}
+
+// columns [c0, c1) of every row of a [rows][ld] fp16 matrix := 0
+__global__ void __launch_bounds__(256)
+prefill_zero_cols_kernel(_Float16* __restrict__ m, int ld, int c0, int c1, int rows)
+{
+    const int w = c1 - c0;
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (size_t)rows * w) return;
+    const int row = (int)(idx / w), col = c0 + (int)(idx % w);
+    m[(size_t)row * ld + col] = (_Float16)0.f;
+}
+
+template <int EPI>
+static int run_gemm(const GemmArgs& a, hipStream_t s)
+{
+    dim3 grid(a.m_tiles * a.n_tiles, a.splits);
+    if (a.splits > 1) {
+        hipLaunchKernelGGL((prefill_gemm_kernel<EPI_PARTIAL>), grid, dim3(kPfThreads), 0, s, a);
+        NQ_HIP(hipGetLastError());
+        const size_t total = (size_t)a.m_pad * (a.n_pad / 4);
+        hipLaunchKernelGGL((prefill_finalize_kernel<EPI>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, a);
+    } else {
+        hipLaunchKernelGGL((prefill_gemm_kernel<EPI>), grid, dim3(kPfThreads), 0, s, a);
+    }
+    NQ_HIP(hipGetLastError());
+    return NQ_OK;
+}
+
+int launch_prefill(const PrefillArgs& p, hipStream_t s)
+{
+    const PfLayout L = pf_layout(p.d_out, p.d_in, p.r, p.batch);
+    char* ws = (char*)p.workspace;
+    _Float16* xs = (_Float16*)(ws + L.off_x);
+    _Float16* t = (_Float16*)(ws + L.off_t);
+    float* tok_scale = (float*)(ws + L.off_scale);
+    float* partial = (float*)(ws + L.off_partial);
+    // |x''| < 2^13, so |t''| < d_in * 2^13; g brings that to <= 2^15 (fp16 range 65504)
+    int lg = 0;
+    while (((int64_t)1 << lg) < p.d_in) ++lg;
+    const float g_t = ldexpf(1.0f, -(lg > 2 ? lg - 2 : 0));
+
+    hipLaunchKernelGGL(prefill_prescale_kernel, dim3(p.batch), dim3(256), 0, s, p.x, p.x_dtype, p.s_in, (int)p.d_in,
+                       L.k1, g_t, xs, tok_scale);
+    NQ_HIP(hipGetLastError());
+
+    GemmArgs a{};
+    a.m_pad = L.m_pad;
+    a.m_tiles = L.m_pad / kPfTokens;
+    a.batch = p.batch;
+    a.partial = partial;
+    // gemm1: T = X'' V
+    a.act = xs; a.lda = L.k1; a.tiles = p.vt_tiles;
+    a.t_out = t; a.ldt = L.k2; a.t_scale = g_t;
+    a.n_real = (int)p.r; a.n_rb = (int)n_rowblocks(p.r); a.nst = (int)n_steps(p.d_in);
+    a.n_tiles = (a.n_rb + kPfWaves - 1) / kPfWaves;
+    a.splits = L.splits1; a.steps_per_split = even_steps_per_split(a.nst, a.splits);
+    a.n_pad = L.n1_pad;
+    int rc = run_gemm<EPI_T>(a, s);
+    if (rc != NQ_OK) return rc;
+    if (L.k2 > L.n1_pad) {
+        // columns of T beyond the last 128-row block of gemm1 are padding of gemm2's reduction:
+        // they must be exact zeros (the padded sign bits expand to -1, not to 0)
+        const size_t cnt = (size_t)L.m_pad * (L.k2 - L.n1_pad);
+        hipLaunchKernelGGL(prefill_zero_cols_kernel, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, s, t, L.k2,
+                           L.n1_pad, L.k2, L.m_pad);
+        NQ_HIP(hipGetLastError());
+    }
+    // gemm2: y = T U^T
+    a.act = t; a.lda = L.k2; a.tiles = p.u_tiles;
+    a.y_out = p.y; a.tok_scale = tok_scale; a.out_scale = p.s_out;
+    a.n_real = (int)p.d_out; a.n_rb = (int)n_rowblocks(p.d_out); a.nst = (int)n_steps(p.r);
+    a.n_tiles = (a.n_rb + kPfWaves - 1) / kPfWaves;
+    a.splits = L.splits2; a.steps_per_split = even_steps_per_split(a.nst, a.splits);
+    a.n_pad = L.n2_pad;
+    return run_gemm<EPI_Y>(a, s);
 }
 
 }  // namespace nq

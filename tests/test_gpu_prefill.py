@@ -1,0 +1,76 @@
+"""GPU parity of the dense (batch >= 64) path against the fp64 oracle."""
+import numpy as np
+import pytest
+
+from paper_2602_06694_amd import binding as nq
+from paper_2602_06694_amd import synth
+from gpu_util import BAR, Layer, rel_err
+
+pytestmark = pytest.mark.gpu
+
+# x' and t pass through fp16 (11-bit significands, per-token power-of-two guards): a few 1e-4
+PREFILL_TOL = 7e-4
+
+
+@pytest.mark.parametrize("shape", [(300, 200, 100), (129, 65, 33), (1024, 1024, 256), (640, 1500, 257), (1, 1, 1),
+                                   (2048, 512, 384)])
+@pytest.mark.parametrize("x_dtype", ["bf16", "f32"])
+def test_prefill_small_shapes(shape, x_dtype):
+    d_out, d_in, r = shape
+    L = Layer(d_out, d_in, r, x_dtype, seed=3 * d_out + d_in)
+    for batch in (64, 130, 256):
+        x = synth.gen_x(batch, d_in, 900 + batch, x_dtype, outlier_frac=0.01 if d_in >= 200 else 0.0)
+        y = L.forward(x)
+        ref = L.oracle(x)
+        err = rel_err(y, ref)
+        assert err <= PREFILL_TOL and err <= BAR, (shape, x_dtype, batch, err)
+    L.close()
+
+
+def test_prefill_matches_streaming_path():
+    d_out, d_in, r = 512, 768, 192
+    x = synth.gen_x(96, d_in, 5, "bf16")
+    La = Layer(d_out, d_in, r, "bf16", seed=77)
+    Lb = Layer(d_out, d_in, r, "bf16", seed=77, flags=nq.NQ_FLAG_NO_PREFILL)
+    ya, yb = La.forward(x), Lb.forward(x)
+    ref = La.oracle(x)
+    assert rel_err(ya, ref) <= PREFILL_TOL
+    assert rel_err(yb, ref) <= 1e-5
+    La.close()
+    Lb.close()
+
+
+def test_prefill_tokens_of_very_different_magnitude_and_nan():
+    d_out, d_in, r = 384, 512, 128
+    L = Layer(d_out, d_in, r, "f32", seed=12)
+    x = synth.gen_x(128, d_in, 6, "f32")
+    x *= (10.0 ** np.random.default_rng(1).integers(-6, 6, 128)).astype(np.float32)[:, None]
+    y, ref = L.forward(x), L.oracle(x)
+    for b in range(128):
+        assert np.abs(y[b] - ref[b]).max() <= PREFILL_TOL * np.abs(ref[b]).max(), b
+    x[5, 7] = np.nan
+    x[9] = 0.0
+    import torch
+    from gpu_util import to_device
+    xd = to_device(x, "f32")
+    yd = torch.zeros((128, d_out), dtype=torch.float32, device="cuda")
+    nq.nq_binlr_forward(L.h, xd, yd, 128)
+    torch.cuda.synchronize()
+    y = yd.cpu().numpy()
+    assert np.isnan(y[5]).all()
+    assert (y[9] == 0).all()
+    keep = [b for b in range(128) if b not in (5, 9)]
+    for b in keep:
+        assert np.abs(y[b] - ref[b]).max() <= PREFILL_TOL * np.abs(ref[b]).max(), b
+    L.close()
+
+
+def test_prefill_reserve_and_batch_changes():
+    d_out, d_in, r = 700, 300, 130
+    L = Layer(d_out, d_in, r, "bf16", seed=21)
+    nq.nq_binlr_reserve(L.h, 512)
+    for batch in (512, 64, 300, 64, 8, 512):
+        x = synth.gen_x(batch, d_in, 30 + batch, "bf16")
+        tol = PREFILL_TOL if batch >= 64 else 1e-5
+        assert rel_err(L.forward(x), L.oracle(x)) <= tol, batch
+    L.close()

@@ -8,7 +8,8 @@
 // The sign matrices stay in the 1-bit tile layout of the streaming kernels.  A wave owns 128
 // output rows (one tile row block) and expands each 16-byte tile fragment in registers into the
 // +-1.0 fp16 A operands of v_mfma_f32_16x16x32_f16 with one shift + one bit-field insert per two
-// weights; the 128-token activation tile is shared by the four waves of a workgroup through LDS.
+// weights; the 64-token activation tile is shared by the four waves of a workgroup through LDS,
+// and two workgroups share a CU (two waves per SIMD keep the matrix pipe fed).
 // Bit = 1 lands in the fp16 sign bit, i.e. the operand is the NEGATED sign: the minus is folded
 // into the epilogue factors.
 //
@@ -31,7 +32,8 @@ typedef _Float16 v4h __attribute__((ext_vector_type(4)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef unsigned int v4u32 __attribute__((ext_vector_type(4)));
 
-constexpr int kPfTokens = 128;          // tokens per workgroup tile
+constexpr int kPfTokens = 64;           // tokens per workgroup tile (4 MFMA column groups)
+constexpr int kPfTg = kPfTokens / 16;
 constexpr int kPfWaves = 4;             // waves per workgroup, one 128-row block each
 constexpr int kPfLdsStride = 72;        // halves per token row in LDS (64 + 8: conflict-free 16-byte reads)
 constexpr int kPfThreads = 64 * kPfWaves;
@@ -69,19 +71,91 @@ __device__ __forceinline__ float pf_load(const void* p, int dtype, int64_t i)
     return __builtin_bit_cast(float, (uint32_t)((const uint16_t*)p)[i] << 16);
 }
 
-__global__ void __launch_bounds__(256)
+// eight consecutive scaled inputs x'[k0..k0+7] of one token (zero beyond d_in)
+__device__ __forceinline__ void pf_load8(const void* x, int dtype, const uint16_t* s_in, int64_t base, int k0, int d_in,
+                                         bool vec, float v[8])
+{
+    if (vec && k0 + 8 <= d_in) {
+        if (dtype == NQ_F32) {
+            const float4 f0 = *(const float4*)((const float*)x + base + k0);
+            const float4 f1 = *(const float4*)((const float*)x + base + k0 + 4);
+            v[0] = f0.x; v[1] = f0.y; v[2] = f0.z; v[3] = f0.w; v[4] = f1.x; v[5] = f1.y; v[6] = f1.z; v[7] = f1.w;
+        } else {
+            const uint4 u = *(const uint4*)((const uint16_t*)x + base + k0);
+            const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint16_t lo = (uint16_t)(w[i] & 0xFFFFu), hi = (uint16_t)(w[i] >> 16);
+                v[2 * i] = dtype == NQ_F16 ? h2f(lo) : __builtin_bit_cast(float, (uint32_t)lo << 16);
+                v[2 * i + 1] = dtype == NQ_F16 ? h2f(hi) : __builtin_bit_cast(float, (uint32_t)hi << 16);
+            }
+        }
+        const uint4 su = *(const uint4*)(s_in + k0);
+        const uint32_t sw[4] = {su.x, su.y, su.z, su.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] *= h2f((uint16_t)(sw[i] & 0xFFFFu));
+            v[2 * i + 1] *= h2f((uint16_t)(sw[i] >> 16));
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = k0 + i < d_in ? pf_load(x, dtype, base + k0 + i) * h2f(s_in[k0 + i]) : 0.f;
+    }
+}
+
+// one workgroup per token: max |x'|, then x'' = fp16(x' * 2^a) in the swizzled element order.
+// Up to kPreHeld groups of eight values per thread stay in registers between the two passes
+// (rows up to 32768 elements are read once); longer rows are read twice.
+constexpr int kPreThreads = 1024;
+constexpr int kPreHeld = 4;
+
+__device__ __forceinline__ void pf_store8(_Float16* dst, const float v[8], float sc)
+{
+    // storage order inside every aligned group of four: 0, 2, 1, 3
+    v8h o;
+    o[0] = (_Float16)(v[0] * sc); o[1] = (_Float16)(v[2] * sc); o[2] = (_Float16)(v[1] * sc); o[3] = (_Float16)(v[3] * sc);
+    o[4] = (_Float16)(v[4] * sc); o[5] = (_Float16)(v[6] * sc); o[6] = (_Float16)(v[5] * sc); o[7] = (_Float16)(v[7] * sc);
+    *(v8h*)dst = o;
+}
+
+__global__ void __launch_bounds__(kPreThreads)
 prefill_prescale_kernel(const void* __restrict__ x, int x_dtype, const uint16_t* __restrict__ s_in, int d_in, int lda,
                         float g_t, _Float16* __restrict__ xs, float* __restrict__ tok_scale)
 {
-    __shared__ float sm[4];
+    __shared__ float sm[kPreThreads / 64];
     const int tok = blockIdx.x;
+    const int tid = threadIdx.x;
     const int64_t base = (int64_t)tok * d_in;
+    const int esz = x_dtype == NQ_F32 ? 4 : 2;
+    const bool vec = (((size_t)d_in * esz) & 15) == 0;      // every token row starts 16-byte aligned
+    const int n8 = lda / 8;
+    const bool held = n8 <= kPreThreads * kPreHeld;
+    float hv[kPreHeld][8];
     float m = 0.f;
-    for (int j = threadIdx.x; j < d_in; j += 256) m = fmaxf(m, fabsf(pf_load(x, x_dtype, base + j) * h2f(s_in[j])));
+    if (held) {
+#pragma unroll
+        for (int k = 0; k < kPreHeld; ++k) {
+            const int c = tid + k * kPreThreads;
+            if (c < n8) {
+                pf_load8(x, x_dtype, s_in, base, c * 8, d_in, vec, hv[k]);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) m = fmaxf(m, fabsf(hv[k][i]));
+            }
+        }
+    } else {
+        for (int c = tid; c < n8; c += kPreThreads) {
+            float v[8];
+            pf_load8(x, x_dtype, s_in, base, c * 8, d_in, vec, v);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) m = fmaxf(m, fabsf(v[i]));
+        }
+    }
     for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = m;
+    if ((tid & 63) == 0) sm[tid >> 6] = m;
     __syncthreads();
-    m = fmaxf(fmaxf(sm[0], sm[1]), fmaxf(sm[2], sm[3]));
+    m = sm[0];
+#pragma unroll
+    for (int w = 1; w < kPreThreads / 64; ++w) m = fmaxf(m, sm[w]);
     // 2^a with max * 2^a in [2^12, 2^13); a NaN/Inf token keeps a = 0 and poisons only itself
     float sc = 1.0f;
     if (m > 0.f && m <= 3.0e38f) {
@@ -92,29 +166,38 @@ prefill_prescale_kernel(const void* __restrict__ x, int x_dtype, const uint16_t*
         sc = ldexpf(1.0f, a);
     }
     _Float16* row = xs + (size_t)tok * lda;
-    for (int j = threadIdx.x; j < lda; j += 256) {
-        // storage position j holds reduction index k: middle two of every four swapped
-        const int s = j & 3;
-        const int k = (j & ~3) | (s == 1 ? 2 : (s == 2 ? 1 : s));
-        float v = 0.f;
-        if (k < d_in) v = pf_load(x, x_dtype, base + k) * h2f(s_in[k]) * sc;
-        row[j] = (_Float16)v;
+    if (held) {
+#pragma unroll
+        for (int k = 0; k < kPreHeld; ++k) {
+            const int c = tid + k * kPreThreads;
+            if (c < n8) pf_store8(row + c * 8, hv[k], sc);
+        }
+    } else {
+        for (int c = tid; c < n8; c += kPreThreads) {
+            float v[8];
+            pf_load8(x, x_dtype, s_in, base, c * 8, d_in, vec, v);
+            pf_store8(row + c * 8, v, sc);
+        }
     }
-    if (threadIdx.x == 0) tok_scale[tok] = 1.0f / (sc * g_t);
+    if (tid == 0) tok_scale[tok] = 1.0f / (sc * g_t);
 }
 
 // ---------------------------------------------------------------------------------------------
 // GEMM:  C[token][n] = sum_k act[token][k] * sign(tiles[n][k])
-// grid = (m_tiles * n_tiles, splits); block = 256 (4 waves x 128 output rows, 128 tokens)
+// grid = (m_tiles * n_tiles, splits); block = 256 (4 waves x 128 output rows, 64 tokens)
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ uint32_t bfi_sign(uint32_t x)
+// sign bits of both halves from x, everything else from `one2` (two fp16 1.0): one v_bfi_b32
+// (the mask sits in a scalar register, `one2` in a vector register)
+__device__ __forceinline__ uint32_t bfi_sign(uint32_t x, uint32_t one2)
 {
-    // sign bits of both halves from x, everything else from the pattern of +1.0
-    return (x & 0x80008000u) | 0x3C003C00u;
+    uint32_t d;
+    const uint32_t mask = 0x80008000u;
+    asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(d) : "s"(mask), "v"(x), "v"(one2));
+    return d;
 }
 
 template <int EPI>
-__global__ void __launch_bounds__(kPfThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+__global__ void __launch_bounds__(kPfThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 prefill_gemm_kernel(GemmArgs a)
 {
     __shared__ __attribute__((aligned(16))) _Float16 lds_act[2][kPfTokens * kPfLdsStride];
@@ -142,7 +225,7 @@ prefill_gemm_kernel(GemmArgs a)
     if (!rb_valid) rb = a.n_rb - 1;                        // keep loading valid memory, store nothing
     const int m0 = m_tile * kPfTokens;
 
-    // activation tile: 128 tokens x 64 halves = 1024 chunks of 16 bytes, 4 per thread:
+    // activation tile: 64 tokens x 64 halves = 512 chunks of 16 bytes, 2 per thread:
     // chunk c = tid + 256 i  ->  token c / 8, 16-byte column c % 8
     const int ld_tok = tid >> 3, ld_kc = tid & 7;                       // chunk i adds 32 tokens
     const _Float16* act_ptr = a.act + (size_t)(m0 + ld_tok) * a.lda + (size_t)s_begin * 64 + ld_kc * 8;
@@ -150,60 +233,68 @@ prefill_gemm_kernel(GemmArgs a)
     const int lds_off = ld_tok * kPfLdsStride + ld_kc * 8;
     const v4u32* w_ptr = (const v4u32*)a.tiles + ((size_t)rb * a.nst + s_begin) * 64 + lane;
 
-    v4f acc[8][8];
+    v4f acc[8][kPfTg];
 #pragma unroll
     for (int p = 0; p < 8; ++p)
 #pragma unroll
-        for (int tg = 0; tg < 8; ++tg) acc[p][tg] = v4f{0.f, 0.f, 0.f, 0.f};
+        for (int tg = 0; tg < kPfTg; ++tg) acc[p][tg] = v4f{0.f, 0.f, 0.f, 0.f};
 
     // two register sets for the activation chunks and the tile words: set (s & 1) belongs to step s
     // (named registers, not arrays: arrays that are written under a condition end up in LDS)
-    uint4 a00, a01, a02, a03, a10, a11, a12, a13;
+    uint4 a00, a01, a10, a11;
     v4u32 wr0, wr1;
 #define PF_LOAD_ACT(R, step)                                                             \
     do {                                                                                 \
         const _Float16* q = act_ptr + (size_t)(step) * 64;                               \
         R##0 = *(const uint4*)(q);                                                       \
         R##1 = *(const uint4*)(q + act_i);                                               \
-        R##2 = *(const uint4*)(q + 2 * act_i);                                           \
-        R##3 = *(const uint4*)(q + 3 * act_i);                                           \
     } while (0)
 #define PF_STORE_ACT(buf, R)                                                             \
     do {                                                                                 \
         _Float16* q = &lds_act[buf][lds_off];                                            \
         *(uint4*)(q) = R##0;                                                             \
         *(uint4*)(q + 32 * kPfLdsStride) = R##1;                                         \
-        *(uint4*)(q + 64 * kPfLdsStride) = R##2;                                         \
-        *(uint4*)(q + 96 * kPfLdsStride) = R##3;                                         \
     } while (0)
     // one reduction step on LDS buffer CUR with tile words W; the planes are kept in program
     // order (scheduling barriers) so that only one expanded operand is alive at a time
-#define PF_MFMA(P, TG, B) acc[P][TG] = __builtin_amdgcn_mfma_f32_16x16x32_f16(aop, B, acc[P][TG], 0, 0, 0)
-#define PF_COMPUTE(CUR, W)                                                               \
+    uint32_t one2 = 0x3C003C00u;
+    asm volatile("" : "+v"(one2));          // keep the constant in a vector register
+    // B operands (activations of the 4 token groups) for one half step: two named register sets
+    v8h p0, p1, p2, p3;      // set P: first half (reduction offsets 0..7 of each 16)
+    v8h q0, q1, q2, q3;      // set Q: second half
+#define PF_READ_B(R, BUF, H)                                                             \
     do {                                                                                 \
-        const _Float16* lds_row = &lds_act[CUR][j * kPfLdsStride + 16 * g];              \
-        _Pragma("unroll") for (int h = 0; h < 2; ++h) {                                  \
-            /* named registers (not an array): the B operands of the 8 token groups */   \
-            const v8h b0 = *(const v8h*)(lds_row + 0 * 16 * kPfLdsStride + 8 * h);       \
-            const v8h b1 = *(const v8h*)(lds_row + 1 * 16 * kPfLdsStride + 8 * h);       \
-            const v8h b2 = *(const v8h*)(lds_row + 2 * 16 * kPfLdsStride + 8 * h);       \
-            const v8h b3 = *(const v8h*)(lds_row + 3 * 16 * kPfLdsStride + 8 * h);       \
-            const v8h b4 = *(const v8h*)(lds_row + 4 * 16 * kPfLdsStride + 8 * h);       \
-            const v8h b5 = *(const v8h*)(lds_row + 5 * 16 * kPfLdsStride + 8 * h);       \
-            const v8h b6 = *(const v8h*)(lds_row + 6 * 16 * kPfLdsStride + 8 * h);       \
-            const v8h b7 = *(const v8h*)(lds_row + 7 * 16 * kPfLdsStride + 8 * h);       \
-            const uint32_t w0 = h == 0 ? W.x : W.z, w1 = h == 0 ? W.y : W.w;             \
-            _Pragma("unroll") for (int p = 0; p < 8; ++p) {                              \
-                v4u32 au;                                                                \
-                au.x = bfi_sign(w0 << (15 - p));                                         \
-                au.y = bfi_sign(p == 7 ? w0 : (w0 << (7 - p)));                          \
-                au.z = bfi_sign(w1 << (15 - p));                                         \
-                au.w = bfi_sign(p == 7 ? w1 : (w1 << (7 - p)));                          \
-                const v8h aop = __builtin_bit_cast(v8h, au);                             \
-                PF_MFMA(p, 0, b0); PF_MFMA(p, 1, b1); PF_MFMA(p, 2, b2); PF_MFMA(p, 3, b3); \
-                PF_MFMA(p, 4, b4); PF_MFMA(p, 5, b5); PF_MFMA(p, 6, b6); PF_MFMA(p, 7, b7); \
-                __builtin_amdgcn_sched_barrier(0);                                       \
+        const _Float16* lr = &lds_act[BUF][j * kPfLdsStride + 16 * g + 8 * (H)];         \
+        R##0 = *(const v8h*)(lr);                                                        \
+        R##1 = *(const v8h*)(lr + 1 * 16 * kPfLdsStride);                                \
+        R##2 = *(const v8h*)(lr + 2 * 16 * kPfLdsStride);                                \
+        R##3 = *(const v8h*)(lr + 3 * 16 * kPfLdsStride);                                \
+    } while (0)
+#define PF_MFMA(P, TG, B) acc[P][TG] = __builtin_amdgcn_mfma_f32_16x16x32_f16(aop, B, acc[P][TG], 0, 0, 0)
+    // one half step: 8 planes x 4 token groups.  w0 / w1 are the two tile words of this half.
+    // The scheduler is asked to alternate one MFMA with one vector op, so that the expansion of
+    // the next plane runs in the shadow of the current plane's MFMAs.
+#define PF_EXPAND(AU, p, w0, w1)                                                         \
+    do {                                                                                 \
+        AU.x = bfi_sign((w0) << (15 - (p)), one2);                                       \
+        AU.y = bfi_sign((p) == 7 ? (w0) : ((w0) << (7 - (p))), one2);                    \
+        AU.z = bfi_sign((w1) << (15 - (p)), one2);                                       \
+        AU.w = bfi_sign((p) == 7 ? (w1) : ((w1) << (7 - (p))), one2);                    \
+    } while (0)
+#define PF_HALF(R, w0, w1)                                                               \
+    do {                                                                                 \
+        v4u32 au_next;                                                                   \
+        PF_EXPAND(au_next, 0, w0, w1);                                                   \
+        __builtin_amdgcn_sched_barrier(0);                                               \
+        _Pragma("unroll") for (int p = 0; p < 8; ++p) {                                  \
+            const v8h aop = __builtin_bit_cast(v8h, au_next);                            \
+            if (p < 7) PF_EXPAND(au_next, p + 1, w0, w1);                                \
+            PF_MFMA(p, 0, R##0); PF_MFMA(p, 1, R##1); PF_MFMA(p, 2, R##2); PF_MFMA(p, 3, R##3); \
+            _Pragma("unroll") for (int i = 0; i < 4; ++i) {                              \
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   /* 1 MFMA  */       \
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);   /* 2 VALU  */       \
             }                                                                            \
+            __builtin_amdgcn_sched_barrier(0);                                           \
         }                                                                                \
     } while (0)
 
@@ -211,48 +302,59 @@ prefill_gemm_kernel(GemmArgs a)
     // shifting by 15-p puts (k0, k2) into the two fp16 sign bits, by 7-p (k1, k3)
     // n_my is even (the reduction is padded to 4 steps and splits are even), and the loop body is
     // branch-free: prefetches past the end re-read the last step instead of being skipped, so no
-    // control-flow join forces copies of the 256 accumulator registers
+    // control-flow join forces copies of the 256 accumulator registers.
+    // Per step on LDS buffer c (the other buffer is o):
+    //   read second-half operands from c | fetch step s+2 from global | MFMAs of the first half |
+    //   write step s+1 into o | barrier | read first-half operands of step s+1 from o | MFMAs of
+    //   the second half.  Every LDS read is issued half a step before its first use.
     if (n_my > 0) {
         const int last = n_my - 1;
-        // prologue: step 0 into LDS, step 1 into registers, tile words of steps 0 and 1
         PF_LOAD_ACT(a0, 0);
         wr0 = w_ptr[0];
         PF_LOAD_ACT(a1, 1);
         wr1 = w_ptr[64];
         PF_STORE_ACT(0, a0);
         __syncthreads();
+        PF_READ_B(p, 0, 0);
         for (int s = 0; s < n_my; s += 2) {
-            {   // even step: LDS buffer 0; register set 0 is free for step s+2
+            {   // even step: buffer 0
                 const v4u32 w = wr0;
+                PF_READ_B(q, 0, 1);
                 const int nx = min(s + 2, last);
                 PF_LOAD_ACT(a0, nx);
                 wr0 = w_ptr[(size_t)nx * 64];
-                PF_COMPUTE(0, w);
-                // buffer 1 was last read in step s-1, before the previous barrier
-                PF_STORE_ACT(1, a1);
+                PF_HALF(p, w.x, w.y);
+                PF_STORE_ACT(1, a1);           // buffer 1 was last read before the previous barrier
                 __syncthreads();
+                PF_READ_B(p, 1, 0);
+                PF_HALF(q, w.z, w.w);
             }
-            {   // odd step: LDS buffer 1
+            {   // odd step: buffer 1
                 const v4u32 w = wr1;
+                PF_READ_B(q, 1, 1);
                 const int nx = min(s + 3, last);
                 PF_LOAD_ACT(a1, nx);
                 wr1 = w_ptr[(size_t)nx * 64];
-                PF_COMPUTE(1, w);
+                PF_HALF(p, w.x, w.y);
                 PF_STORE_ACT(0, a0);
                 __syncthreads();
+                PF_READ_B(p, 0, 0);
+                PF_HALF(q, w.z, w.w);
             }
         }
     }
 #undef PF_LOAD_ACT
 #undef PF_STORE_ACT
-#undef PF_COMPUTE
+#undef PF_HALF
+#undef PF_EXPAND
+#undef PF_READ_B
 #undef PF_MFMA
 
     if (!rb_valid) return;
     // result layout: lane (g, j), register v of acc[p][tg]  <->  C[token m0 + 16 tg + j][row 128 rb + 16 p + 4 g + v]
     // (the operands were negated signs, so every factor below carries a minus)
 #pragma unroll
-    for (int tg = 0; tg < 8; ++tg) {
+    for (int tg = 0; tg < kPfTg; ++tg) {
         const int tok = m0 + tg * 16 + j;
 #pragma unroll
         for (int p = 0; p < 8; ++p) {
@@ -337,15 +439,26 @@ struct PfLayout {
     size_t off_x, off_t, off_scale, off_partial, total;
 };
 
-static int choose_splits(int m_tiles, int n_tiles, int nst)
+// Split the reduction over `s` workgroups when the output alone gives too few workgroups to cover
+// the chip.  Cost model in units of one reduction step of one workgroup: rounds over the CUs times
+// steps per split, plus the write and re-read of the fp32 partial sums.
+static int choose_splits(int m_tiles, int n_tiles, int nst, int m_pad, int n_pad)
 {
     const int wgs = m_tiles * n_tiles;
-    const int cus = device_cu_count();
-    if (wgs >= cus) return 1;
-    int s = (cus + wgs - 1) / wgs;
-    const int max_s = std::max(1, nst / 8);               // keep at least 8 steps per split
-    s = std::min(std::min(s, max_s), 16);
-    return std::max(1, s);
+    const int cus = device_cu_count() * 2;                // two workgroups fit a CU
+    const double step_us = 0.9, hbm_bytes_per_us = 4.0e6;
+    int best = 1;
+    double best_cost = 1e30;
+    for (int s = 1; s <= 16; ++s) {
+        int per = (nst + s - 1) / s;
+        per += per & 1;
+        if (s > 1 && per < 8) break;
+        const int rounds = (wgs * s + cus - 1) / cus;
+        double cost = (double)rounds * per * step_us;
+        if (s > 1) cost += 2.0 * s * (double)m_pad * n_pad * 4.0 / hbm_bytes_per_us;
+        if (cost < best_cost) { best_cost = cost; best = s; }
+    }
+    return best;
 }
 
 // steps per split, rounded up to an even count (nst itself is a multiple of 4)
@@ -364,8 +477,8 @@ static PfLayout pf_layout(int64_t d_out, int64_t d_in, int64_t r, int batch)
     L.n1_pad = (int)n_rowblocks(r) * kTileRows;
     L.n2_pad = (int)n_rowblocks(d_out) * kTileRows;
     const int m_tiles = L.m_pad / kPfTokens;
-    L.splits1 = choose_splits(m_tiles, (int)((n_rowblocks(r) + kPfWaves - 1) / kPfWaves), (int)n_steps(d_in));
-    L.splits2 = choose_splits(m_tiles, (int)((n_rowblocks(d_out) + kPfWaves - 1) / kPfWaves), (int)n_steps(r));
+    L.splits1 = choose_splits(m_tiles, (int)((n_rowblocks(r) + kPfWaves - 1) / kPfWaves), (int)n_steps(d_in), L.m_pad, L.n1_pad);
+    L.splits2 = choose_splits(m_tiles, (int)((n_rowblocks(d_out) + kPfWaves - 1) / kPfWaves), (int)n_steps(r), L.m_pad, L.n2_pad);
     size_t o = 0;
     L.off_x = o; o += al256((size_t)L.m_pad * L.k1 * 2);
     L.off_t = o; o += al256((size_t)L.m_pad * L.k2 * 2);
@@ -423,7 +536,7 @@ int launch_prefill(const PrefillArgs& p, hipStream_t s)
     while (((int64_t)1 << lg) < p.d_in) ++lg;
     const float g_t = ldexpf(1.0f, -(lg > 2 ? lg - 2 : 0));
 
-    hipLaunchKernelGGL(prefill_prescale_kernel, dim3(p.batch), dim3(256), 0, s, p.x, p.x_dtype, p.s_in, (int)p.d_in,
+    hipLaunchKernelGGL(prefill_prescale_kernel, dim3(p.batch), dim3(kPreThreads), 0, s, p.x, p.x_dtype, p.s_in, (int)p.d_in,
                        L.k1, g_t, xs, tok_scale);
     NQ_HIP(hipGetLastError());
 

@@ -1,0 +1,102 @@
+"""Parity at the full sizes of the five workload configurations, in the launch
+configuration the benchmark times (plans over whole stacks; the dense path for
+the prefill shapes).  Where the oracle cannot afford every output, whole layers
+and individual rows are sampled."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2602_06694_amd import binding as nq
+from paper_2602_06694_amd import synth
+from gpu_util import BAR, DECODE_TOL, Layer, rel_err, to_device
+
+pytestmark = pytest.mark.gpu
+PREFILL_TOL = 7e-4
+
+
+def build_stack(cfg, n_layers=None, batch=1):
+    import torch
+    c = synth.CONFIGS[cfg]
+    layers, xs_np, xs, ys = [], [], [], []
+    for layer, li, shp in synth.iter_config_layers(cfg, n_layers):
+        data = synth.gen_layer(cfg, layer, li, shp)
+        layers.append(Layer(shp.d_out, shp.d_in, shp.r, c.x_dtype, data=data))
+        x = synth.gen_layer_x(cfg, layer, li, shp, batch, c.x_dtype)
+        xs_np.append(x)
+        xs.append(to_device(x, c.x_dtype))
+        ys.append(torch.full((batch, shp.d_out), float("nan"), dtype=torch.float32, device="cuda"))
+    return layers, xs_np, xs, ys
+
+
+def test_config3_llama2_7b_stack_every_output():
+    import torch
+    layers, xs_np, xs, ys = build_stack(3)
+    assert len(layers) == 224
+    plan = nq.nq_plan_create([L.h for L in layers], xs, ys, 1)
+    nq.nq_plan_forward(plan)
+    torch.cuda.synchronize()
+    worst = 0.0
+    for L, x, y in zip(layers, xs_np, ys):
+        worst = max(worst, rel_err(y.cpu().numpy(), L.oracle(x)))
+    print(f"config 3: worst rel err over 224 layers {worst:.3e}")
+    assert worst <= DECODE_TOL and worst <= BAR
+    # the same stack through the cached-plan entry point gives identical bits
+    y_first = [y.clone() for y in ys]
+    nq.nq_binlr_forward_many([L.h for L in layers], xs, ys, 1)
+    torch.cuda.synchronize()
+    assert all(torch.equal(a, b) for a, b in zip(y_first, ys))
+    nq.nq_plan_destroy(plan)
+    for L in layers:
+        L.close()
+
+
+def test_config4_llama2_70b_stack_sampled():
+    import torch
+    layers, xs_np, xs, ys = build_stack(4)
+    assert len(layers) == 560
+    total_bytes = sum(nq.nq_binlr_weight_bytes(L.h) for L in layers)
+    assert abs(total_bytes / 1e9 - 4.747) < 0.01            # packed bits + fp16 scales of the whole stack
+    plan = nq.nq_plan_create([L.h for L in layers], xs, ys, 1)
+    nq.nq_plan_forward(plan)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(4)
+    worst_full, worst_rows = 0.0, 0.0
+    for i, (L, x, y) in enumerate(zip(layers, xs_np, ys)):
+        layer = i // 7
+        yh = y.cpu().numpy()
+        assert np.isfinite(yh).all()
+        if layer in (0, 41, 79):                             # whole layers against the factored oracle
+            worst_full = max(worst_full, rel_err(yh, L.oracle(x)))
+        elif layer % 8 == 3:                                 # sampled rows against the dense definition
+            rows = np.unique(np.concatenate([[0, 127, 128, L.d_out - 1], rng.integers(0, L.d_out, 2)]))
+            ref = L.oracle_rows(x, rows)
+            scale = np.abs(yh).max()
+            worst_rows = max(worst_rows, float(np.abs(yh[:, rows] - ref).max() / scale))
+    print(f"config 4: worst rel err, whole layers {worst_full:.3e}, sampled rows {worst_rows:.3e}")
+    assert worst_full <= DECODE_TOL and worst_rows <= DECODE_TOL
+    nq.nq_plan_destroy(plan)
+    for L in layers:
+        L.close()
+
+
+@pytest.mark.parametrize("batch", [512, 2048])
+def test_config5_prefill_70b_mlp(batch):
+    import torch
+    c = synth.CONFIGS[5]
+    rng = np.random.default_rng(5)
+    for li, shp in enumerate(c.block):
+        data = synth.gen_layer(5, 0, li, shp)
+        L = Layer(shp.d_out, shp.d_in, shp.r, c.x_dtype, data=data)
+        x = synth.gen_layer_x(5, 0, li, shp, batch, c.x_dtype, c.outlier_frac)
+        y = L.forward(x)
+        assert np.isfinite(y).all()
+        toks = np.unique(np.concatenate([[0, 63, 64, batch - 1], rng.integers(0, batch, 4)]))
+        ref = L.oracle(x[toks])                              # every output of the sampled tokens
+        scale = np.abs(ref).max()
+        err = float(np.abs(y[toks] - ref).max() / scale)
+        rows = np.array([0, 127, 128, shp.d_out - 1])
+        ra = L.oracle_rows(x[toks[:2]], rows)                # dense definition on a few rows
+        err_a = float(np.abs(y[toks[:2]][:, rows] - ra).max() / scale)
+        print(f"config 5 {shp.name} B={batch}: rel err {err:.3e} (dense rows {err_a:.3e})")
+        assert err <= PREFILL_TOL and err <= BAR and err_a <= PREFILL_TOL
+        L.close()

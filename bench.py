@@ -9,7 +9,7 @@ the workload, issued as ONE nq_plan_forward (four kernel launches).
 
 Default workload "cfg2": the Llama-2-7B-shaped attention projection 4096x4096, r = 1024
 (0.5 bit/weight), bf16 activations, decode batch 1 -- as a pool of distinct seeded layer
-instances whose packed weights (~0.7 GB) exceed twice the 256 MB Infinity Cache, so every
+instances whose packed weights (1.09 GB) are four times the 256 MB Infinity Cache, so every
 step streams its bits from HBM rather than from cache.  All inputs are resident in HBM
 before the timed region.
 
@@ -39,11 +39,12 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4"])
     ap.add_argument("--batch", type=int, default=1)
-    ap.add_argument("--pool", type=int, default=640, help="cfg2: number of distinct layer instances")
+    ap.add_argument("--pool", type=int, default=1024, help="cfg2: number of distinct layer instances")
     ap.add_argument("--layers", type=int, default=0, help="cfg3/cfg4: decoder layers (0 = all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target oracle time for the cpu_baseline sample")
-    ap.add_argument("--prefill", action="store_true", help="also time the config-5 prefill shapes (extra field)")
+    ap.add_argument("--quick", action="store_true",
+                    help="headline workload only: skip the extra fields (70B stack decode, config-5 prefill)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (reference for rocprofv3 --pmc byte counters)")
     return ap.parse_args()
@@ -78,27 +79,95 @@ def algorithmic_bytes(shp, batch):
     return bits + scales, bits + scales + x + y + t
 
 
+def stage_bytes(shp, batch):
+    """Algorithmic bytes of the two streaming launches for one layer:
+    stage 1 reads the V bits and the 3-byte fixed-point x', writes t (fp32);
+    stage 2 reads the U bits, the 3-byte fixed-point t and s_out (fp16), writes y (fp32)."""
+    s1 = shp.d_in * shp.r // 8 + 3 * batch * shp.d_in + 4 * batch * shp.r
+    s2 = shp.d_out * shp.r // 8 + 2 * shp.d_out + 3 * batch * shp.r + 4 * batch * shp.d_out
+    return s1, s2
+
+
 def cpu_baseline(work, batch, target_s):
-    """Oracle (Tier B, fp64, OpenMP over the host cores) on a bounded sample of the same layers."""
+    """Oracle (Tier B, fp64, OpenMP over the host cores) on a bounded sample of the same layers:
+    it walks the workload's layers in order (wrapping around) until about `target_s` seconds are spent."""
     import oracle
     from paper_2602_06694_amd import synth
-    shp, data, x = work[0]
-    xf = synth.x_as_f64(x, "bf16")
+    wbytes, n, used = 0, 0, 1
     t0 = time.perf_counter()
-    _, used = oracle.forward_factored(data.U_words, data.V_words, data.s_out, data.s_in, shp.d_out, shp.d_in, shp.r,
-                                      xf, threads=0, return_threads=True)
-    one = time.perf_counter() - t0
-    n = max(1, min(len(work), int(target_s / max(one, 1e-6))))
-    wbytes = 0
-    t0 = time.perf_counter()
-    for shp, data, x in work[:n]:
-        oracle.forward_factored(data.U_words, data.V_words, data.s_out, data.s_in, shp.d_out, shp.d_in, shp.r,
-                                synth.x_as_f64(x, "bf16"), threads=0)
+    while True:
+        shp, data, x = work[n % len(work)]
+        _, used = oracle.forward_factored(data.U_words, data.V_words, data.s_out, data.s_in, shp.d_out, shp.d_in,
+                                          shp.r, synth.x_as_f64(x, "bf16"), threads=0, return_threads=True)
         wbytes += algorithmic_bytes(shp, batch)[0]
-    dt = time.perf_counter() - t0
+        n += 1
+        dt = time.perf_counter() - t0
+        if dt >= target_s:
+            break
     return {"value": wbytes / dt / 1e9, "unit": "GB/s", "cores": int(used), "kind": "oracle",
-            "sample": f"first {n} of {len(work)} layers of the workload, fp64 factored oracle, {dt:.1f} s",
+            "sample": f"{n} layer forwards (the workload's layers in order, wrapping), fp64 factored oracle, {dt:.1f} s",
             "layers_per_s": n / dt}
+
+
+def measured_traffic(workload_name, stage):
+    """HBM bytes per launch of the given stage from the committed rocprofv3 --pmc summary of this
+    workload (FETCH_SIZE + WRITE_SIZE, each scaled by the copy-kernel calibration), or None if the
+    summary does not cover it."""
+    path = os.path.join(ROOT, "profiles", "stage_kernels_cfg2_pool_pmc.txt")
+    try:
+        want = None
+        for line in open(path):
+            if line.startswith("workload:"):
+                want = line.split(":", 1)[1].strip()
+            if line.startswith(f"traffic_bytes_per_launch_{stage}:") and want == workload_name:
+                return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def time_stack(cfg, batch, steps=10, warmup=2):
+    """Whole decoder stack of config 3 / 4 as one plan: step time, weight GB/s and per-kernel roofline."""
+    import numpy as np
+    import torch
+    from paper_2602_06694_amd import binding as nq
+    from paper_2602_06694_amd import synth
+    handles, xs, ys, wbytes, abytes, sb1, sb2 = [], [], [], 0, 0, 0, 0
+    for layer, li, shp in synth.iter_config_layers(cfg):
+        data = synth.gen_layer(cfg, layer, li, shp)
+        handles.append(nq.nq_binlr_create(shp.d_out, shp.d_in, shp.r, data.U_words, data.V_words, data.s_out,
+                                          data.s_in, nq.NQ_BF16))
+        x = synth.gen_layer_x(cfg, layer, li, shp, batch, "bf16")
+        xs.append(torch.from_numpy(x.view(np.int16).copy()).view(torch.bfloat16).cuda())
+        ys.append(torch.empty((batch, shp.d_out), dtype=torch.float32, device="cuda"))
+        wb, ab = algorithmic_bytes(shp, batch)
+        wbytes += wb
+        abytes += ab
+        sb1 += stage_bytes(shp, batch)[0]
+        sb2 += stage_bytes(shp, batch)[1]
+    plan = nq.nq_plan_create(handles, xs, ys, batch)
+    for _ in range(warmup):
+        nq.nq_plan_forward(plan)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        nq.nq_plan_forward(plan)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    pk = np.zeros(4)
+    for _ in range(5):
+        pk += np.array(nq.nq_plan_forward_timed(plan))
+    pk /= 5
+    res = {"layers": len(handles), "ms_per_step": ms, "weight_GBps": wbytes / ms / 1e6,
+           "tokens_per_s": batch / (ms * 1e-3),
+           "kernel_ms": {"quantize_x": pk[0], "stage1": pk[1], "quantize_t": pk[2], "stage2": pk[3]},
+           "stage1_GBps": sb1 / pk[1] / 1e6, "stage2_GBps": sb2 / pk[3] / 1e6,
+           "stage1_frac_of_hbm_peak": sb1 / pk[1] / 1e6 / HBM_PEAK_GBPS,
+           "stage2_frac_of_hbm_peak": sb2 / pk[3] / 1e6 / HBM_PEAK_GBPS}
+    nq.nq_plan_destroy(plan)
+    for h in handles:
+        nq.nq_binlr_destroy(h)
+    return res
 
 
 def time_prefill(args):
@@ -187,10 +256,13 @@ def main():
     for _ in range(reps):
         per_kernel += np.array(nq.nq_plan_forward_timed(plan))
     per_kernel /= reps
-    # dominant kernel: the streaming stage kernel, launched twice per step (over V^T tiles, over U tiles)
-    stage_ms = 0.5 * (per_kernel[1] + per_kernel[3])
-    stage_bytes = 0.5 * all_bytes                     # algorithmic bytes per stage launch (mean of the two)
-    achieved = stage_bytes / (stage_ms * 1e-3) / 1e9
+    # the two streaming launches; the slower one is the dominant kernel of the step
+    b1 = sum(stage_bytes(shp, batch)[0] for shp, _, _ in work)
+    b2 = sum(stage_bytes(shp, batch)[1] for shp, _, _ in work)
+    stages = {"stage1": {"algorithmic_bytes": b1, "ms": per_kernel[1], "GBps": b1 / per_kernel[1] / 1e6},
+              "stage2": {"algorithmic_bytes": b2, "ms": per_kernel[3], "GBps": b2 / per_kernel[3] / 1e6}}
+    dom = "stage1" if per_kernel[1] >= per_kernel[3] else "stage2"
+    achieved = stages[dom]["GBps"]
 
     if args.calibrate_copy:
         a = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
@@ -218,18 +290,24 @@ def main():
         "ms_per_step_hip_events": ev_ms,
         "kernel_ms": {"quantize_x": per_kernel[0], "stage1": per_kernel[1], "quantize_t": per_kernel[2],
                       "stage2": per_kernel[3]},
-        "roofline": {"bound": "hbm", "kernel": "nq::stage_kernel (mean of the stage-1 and stage-2 launch)",
+        "stages": stages,
+        "roofline": {"bound": "hbm", "kernel": f"{dom} launch (nq::stage_split_kernel / nq::stage_stream_kernel)",
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": None},
     }
-    if args.prefill:
-        out["prefill"] = time_prefill(args)
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(work, batch, args.cpu_seconds)
-
+    traffic = measured_traffic(name, dom)
+    if traffic is not None:
+        out["roofline"]["traffic"] = traffic
     nq.nq_plan_destroy(plan)
     for h in handles:
         nq.nq_binlr_destroy(h)
+    handles = []
+    del xs, ys, plan
+    if not args.quick:
+        out["extra"] = {"decode_llama2_70b_stack_b1": time_stack(4, 1), "prefill_config5": time_prefill(args)}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(work, batch, args.cpu_seconds)
+
     print(json.dumps(out))
 
 

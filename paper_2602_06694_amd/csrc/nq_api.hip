@@ -540,6 +540,40 @@ extern "C" int nq_plan_create(nq_plan* out, const nq_handle* hs, const void* con
         std::stable_sort(lists[st].begin(), lists[st].end(), [](const WorkItem& a, const WorkItem& b) {
             return (int64_t)a.n_steps * a.n_rb > (int64_t)b.n_steps * b.n_rb;
         });
+        // Workgroup i runs on XCD i % 8, each XCD with its own L2.  Deal the list into 8 queues op by
+        // op (an op's items stay together, queues stay sorted) and interleave them, so that all row
+        // blocks of a layer read that layer's activation vector through ONE L2 instead of eight.
+        if (getenv("NQ_NO_XCD_ORDER") == nullptr) {
+            constexpr int kXcds = 8;
+            std::vector<WorkItem> q[kXcds];
+            int lane = -1, last_op = -1;
+            size_t load[kXcds] = {0};
+            for (const WorkItem& w : lists[st]) {
+                if (w.op != last_op) {                       // next op goes to the least loaded queue
+                    lane = 0;
+                    for (int x = 1; x < kXcds; ++x)
+                        if (load[x] < load[lane]) lane = x;
+                    last_op = w.op;
+                }
+                q[lane].push_back(w);
+                load[lane] += (size_t)w.n_steps * w.n_rb;
+            }
+            std::vector<WorkItem> out;
+            out.reserve(lists[st].size());
+            size_t pos[kXcds] = {0};
+            while (out.size() < lists[st].size()) {
+                for (int x = 0; x < kXcds; ++x) {
+                    if (pos[x] < q[x].size()) out.push_back(q[x][pos[x]++]);
+                    else {                                   // queue ran dry: borrow from the fullest one
+                        int f = 0;
+                        for (int y = 1; y < kXcds; ++y)
+                            if (q[y].size() - pos[y] > q[f].size() - pos[f]) f = y;
+                        if (pos[f] < q[f].size()) out.push_back(q[f][pos[f]++]);
+                    }
+                }
+            }
+            lists[st].swap(out);
+        }
     }
     std::vector<WorkItem>& it1 = lists[0];
     std::vector<WorkItem>& it2 = lists[1];

@@ -260,8 +260,7 @@ prefill_gemm_kernel(GemmArgs a)
     uint32_t one2 = 0x3C003C00u;
     asm volatile("" : "+v"(one2));          // keep the constant in a vector register
     // B operands (activations of the 4 token groups) for one half step: two named register sets
-    v8h p0, p1, p2, p3;      // set P: first half (reduction offsets 0..7 of each 16)
-    v8h q0, q1, q2, q3;      // set Q: second half
+    v8h p0, p1, p2, p3;      // first half (reduction offsets 0..7 of each 16)
 #define PF_READ_B(R, BUF, H)                                                             \
     do {                                                                                 \
         const _Float16* lr = &lds_act[BUF][j * kPfLdsStride + 16 * g + 8 * (H)];         \
@@ -309,37 +308,45 @@ prefill_gemm_kernel(GemmArgs a)
     //   the second half.  Every LDS read is issued half a step before its first use.
     if (n_my > 0) {
         const int last = n_my - 1;
+        // the order in which loads are issued is pinned (scheduling barriers) and is the same in the
+        // prologue and in the loop -- activation chunks, then tile words, per step -- so that the
+        // compiler can wait for "all but the newest n" loads instead of for all of them
         PF_LOAD_ACT(a0, 0);
         wr0 = w_ptr[0];
+        __builtin_amdgcn_sched_barrier(0);
         PF_LOAD_ACT(a1, 1);
         wr1 = w_ptr[64];
+        __builtin_amdgcn_sched_barrier(0);
         PF_STORE_ACT(0, a0);
         __syncthreads();
-        PF_READ_B(p, 0, 0);
         for (int s = 0; s < n_my; s += 2) {
             {   // even step: buffer 0
                 const v4u32 w = wr0;
-                PF_READ_B(q, 0, 1);
+                PF_READ_B(p, 0, 0);
                 const int nx = min(s + 2, last);
+                __builtin_amdgcn_sched_barrier(0);
                 PF_LOAD_ACT(a0, nx);
                 wr0 = w_ptr[(size_t)nx * 64];
+                __builtin_amdgcn_sched_barrier(0);
                 PF_HALF(p, w.x, w.y);
+                PF_READ_B(p, 0, 1);
                 PF_STORE_ACT(1, a1);           // buffer 1 was last read before the previous barrier
+                PF_HALF(p, w.z, w.w);
                 __syncthreads();
-                PF_READ_B(p, 1, 0);
-                PF_HALF(q, w.z, w.w);
             }
             {   // odd step: buffer 1
                 const v4u32 w = wr1;
-                PF_READ_B(q, 1, 1);
+                PF_READ_B(p, 1, 0);
                 const int nx = min(s + 3, last);
+                __builtin_amdgcn_sched_barrier(0);
                 PF_LOAD_ACT(a1, nx);
                 wr1 = w_ptr[(size_t)nx * 64];
+                __builtin_amdgcn_sched_barrier(0);
                 PF_HALF(p, w.x, w.y);
+                PF_READ_B(p, 1, 1);
                 PF_STORE_ACT(0, a0);
+                PF_HALF(p, w.z, w.w);
                 __syncthreads();
-                PF_READ_B(p, 0, 0);
-                PF_HALF(q, w.z, w.w);
             }
         }
     }

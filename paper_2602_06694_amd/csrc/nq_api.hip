@@ -532,9 +532,19 @@ extern "C" int nq_plan_create(nq_plan* out, const nq_handle* hs, const void* con
         for (int i = 0; i < n; ++i) {
             const int nrb = (int)n_rowblocks(sd[i].M);
             const int per = w == 1 ? rbs_per_stream_item(nrb, sd[i].n_steps, total_rb, batch) : 1;
-            for (int rb = 0; rb < nrb; rb += per)
+            // runs of `per` row blocks first, then shorter and shorter ones: the sorted list ends in
+            // small items, which level out the finishing times of the waves (the hardware hands an
+            // idle slot the next item)
+            for (int rb = 0; rb < nrb;) {
+                const int rem = nrb - rb;
+                int c = 1;
+                while (c * 3 < rem) c *= 2;                   // smallest power of two >= rem / 3
+                c = std::min(std::min(c, per), rem);
+                if (getenv("NQ_UNIFORM_ITEMS")) c = std::min(per, rem);
                 lists[st].push_back(WorkItem{sd[i].tiles + (size_t)rb * sd[i].n_steps * kTileWords, sd[i].bq,
-                                             sd[i].n_steps, i, rb, std::min(per, nrb - rb)});
+                                             sd[i].n_steps, i, rb, c});
+                rb += c;
+            }
         }
         // longest items first: the hardware dispatches workgroups in order, so the short ones fill the tail
         std::stable_sort(lists[st].begin(), lists[st].end(), [](const WorkItem& a, const WorkItem& b) {

@@ -540,7 +540,6 @@ extern "C" int nq_plan_create(nq_plan* out, const nq_handle* hs, const void* con
                 int c = 1;
                 while (c * 3 < rem) c *= 2;                   // smallest power of two >= rem / 3
                 c = std::min(std::min(c, per), rem);
-                if (getenv("NQ_UNIFORM_ITEMS")) c = std::min(per, rem);
                 lists[st].push_back(WorkItem{sd[i].tiles + (size_t)rb * sd[i].n_steps * kTileWords, sd[i].bq,
                                              sd[i].n_steps, i, rb, c});
                 rb += c;
@@ -553,7 +552,7 @@ extern "C" int nq_plan_create(nq_plan* out, const nq_handle* hs, const void* con
         // Workgroup i runs on XCD i % 8, each XCD with its own L2.  Deal the list into 8 queues op by
         // op (an op's items stay together, queues stay sorted) and interleave them, so that all row
         // blocks of a layer read that layer's activation vector through ONE L2 instead of eight.
-        if (getenv("NQ_NO_XCD_ORDER") == nullptr) {
+        {
             constexpr int kXcds = 8;
             std::vector<WorkItem> q[kXcds];
             int lane = -1, last_op = -1;

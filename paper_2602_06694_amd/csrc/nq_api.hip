@@ -37,6 +37,68 @@ static size_t dtype_size(int dt) { return dt == NQ_F32 ? 4 : 2; }
 using namespace nq;
 
 // ---------------------------------------------------------------------------------------------
+// Device memory for layers comes from large slabs, not from one hipMalloc per layer: a model is
+// hundreds of layers of ~1 MB each, and the streaming kernels run measurably faster when those
+// sit back to back in a few big, contiguously mapped allocations (fewer address-translation
+// misses) than in hundreds of small ones.  A slab is released when its last layer is destroyed.
+// ---------------------------------------------------------------------------------------------
+struct Slab {
+    char* base;
+    size_t size, used;
+    int live;          // allocations handed out and not yet released
+    int device;
+    int kind;          // 0: sign tiles and scales (streamed), 1: per-layer workspaces (small, reused)
+};
+static std::mutex g_slab_mutex;
+static std::vector<Slab*> g_slabs;
+
+static size_t slab_bytes()
+{
+    size_t mb = 512;
+    if (const char* v = getenv("NQ_SLAB_MB")) {
+        long x = atol(v);
+        if (x >= 1) mb = (size_t)x;
+    }
+    return mb << 20;
+}
+
+// returns hipSuccess and (*out, *owner); the block is 4 KiB aligned
+static hipError_t slab_alloc(size_t bytes, int device, int kind, void** out, Slab** owner)
+{
+    std::lock_guard<std::mutex> lk(g_slab_mutex);
+    bytes = (bytes + 4095) / 4096 * 4096;
+    const size_t std_size = kind == 0 ? slab_bytes() : slab_bytes() / 4;
+    Slab* s = nullptr;
+    if (bytes <= std_size / 4) {
+        for (Slab* c : g_slabs)
+            if (c->device == device && c->kind == kind && c->size == std_size && c->size - c->used >= bytes) { s = c; break; }
+    }
+    if (!s) {
+        const size_t sz = bytes <= std_size / 4 ? std_size : bytes;     // big requests get a slab of their own
+        void* p = nullptr;
+        hipError_t e = hipMalloc(&p, sz);
+        if (e != hipSuccess) return e;
+        s = new Slab{(char*)p, sz, 0, 0, device, kind};
+        g_slabs.push_back(s);
+    }
+    *out = s->base + s->used;
+    s->used += bytes;
+    s->live += 1;
+    *owner = s;
+    return hipSuccess;
+}
+
+static void slab_release(Slab* s)
+{
+    if (!s) return;
+    std::lock_guard<std::mutex> lk(g_slab_mutex);
+    if (--s->live > 0) return;
+    (void)hipFree(s->base);
+    g_slabs.erase(std::find(g_slabs.begin(), g_slabs.end(), s));
+    delete s;
+}
+
+// ---------------------------------------------------------------------------------------------
 struct nq_binlr_s {
     int64_t d_out, d_in, r;
     int x_dtype, y_dtype;
@@ -44,12 +106,14 @@ struct nq_binlr_s {
     int device;
     // weights (one allocation)
     void* w_alloc;
+    Slab* w_slab;
     uint32_t* vt_tiles;   // A = V^T : M = r,     N = d_in
     uint32_t* u_tiles;    // A = U   : M = d_out, N = r
     uint16_t* s_in;
     uint16_t* s_out;
     // decode workspace (one allocation, sized for NQ_DECODE_MAX_BATCH, never reallocated)
     void* ws_alloc;
+    Slab* ws_slab;
     uint8_t* bq_x;
     uint8_t* bq_t;
     QMeta* meta_x;
@@ -178,8 +242,8 @@ static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static void free_handle(nq_handle h)
 {
     if (!h) return;
-    if (h->w_alloc) (void)hipFree(h->w_alloc);
-    if (h->ws_alloc) (void)hipFree(h->ws_alloc);
+    slab_release(h->w_slab);
+    slab_release(h->ws_slab);
     if (h->pf_alloc) (void)hipFree(h->pf_alloc);
     delete h;
 }
@@ -240,8 +304,8 @@ extern "C" int nq_binlr_create(nq_handle* out, int64_t d_out, int64_t d_in, int6
             goto done;                                                     \
         }                                                                  \
     } while (0)
-    CREATE_HIP(hipMalloc(&h->w_alloc, w_total));
-    CREATE_HIP(hipMalloc(&h->ws_alloc, ws_total));
+    CREATE_HIP(slab_alloc(w_total, h->device, 0, &h->w_alloc, &h->w_slab));
+    CREATE_HIP(slab_alloc(ws_total, h->device, 1, &h->ws_alloc, &h->ws_slab));
     CREATE_HIP(hipMalloc((void**)&d_canon, std::max(canon_u, canon_v)));
     {
         char* p = (char*)h->w_alloc;

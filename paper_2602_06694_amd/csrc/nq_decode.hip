@@ -308,7 +308,7 @@ int launch_quantize(const QuantDesc* d_descs, const QuantDesc& single, int n_ops
 // queue (the list is sorted longest first).
 // ---------------------------------------------------------------------------------------------
 #ifndef NQ_STAGE_WAVES
-#define NQ_STAGE_WAVES 4
+#define NQ_STAGE_WAVES 5
 #endif
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 typedef const __attribute__((address_space(1))) v4u* gptr_v4u;    // global (not generic) address space

@@ -137,6 +137,7 @@ struct nq_plan_s {
     WorkItem* items2;
     int n_items1, n_items2;
     int w1, w2;                     // schedule of each stage launch (see stage_schedule)
+    int max_chunks_x, max_chunks_t; // longest vector of each quantisation launch (picks its block size)
     std::vector<nq_handle> handles;
     hipEvent_t ev[5];
     bool have_events;
@@ -450,9 +451,9 @@ static int decode_once(nq_handle h, const void* x, void* y, int batch, hipStream
     const int w1 = stage_schedule(rb1, s1.n_steps, batch), w2 = stage_schedule(rb2, s2.n_steps, batch);
     const int per1 = w1 == 1 ? rbs_per_stream_item(rb1, s1.n_steps, rb1, batch) : 1;
     const int per2 = w2 == 1 ? rbs_per_stream_item(rb2, s2.n_steps, rb2, batch) : 1;
-    if ((rc = launch_quantize(nullptr, qx, 1, batch, s)) != NQ_OK) return rc;
+    if ((rc = launch_quantize(nullptr, qx, 1, qx.n_chunks, batch, s)) != NQ_OK) return rc;
     if ((rc = launch_stage(nullptr, s1, nullptr, (rb1 + per1 - 1) / per1, w1, per1, batch, s)) != NQ_OK) return rc;
-    if ((rc = launch_quantize(nullptr, qt, 1, batch, s)) != NQ_OK) return rc;
+    if ((rc = launch_quantize(nullptr, qt, 1, qt.n_chunks, batch, s)) != NQ_OK) return rc;
     return launch_stage(nullptr, s2, nullptr, (rb2 + per2 - 1) / per2, w2, per2, batch, s);
 }
 
@@ -657,6 +658,11 @@ extern "C" int nq_plan_create(nq_plan* out, const nq_handle* hs, const void* con
     p->handles.assign(hs, hs + n);
     p->n_items1 = (int)it1.size(); p->n_items2 = (int)it2.size();
     p->w1 = sched[0]; p->w2 = sched[1];
+    p->max_chunks_x = p->max_chunks_t = 0;
+    for (int i = 0; i < n; ++i) {
+        p->max_chunks_x = std::max(p->max_chunks_x, qx[i].n_chunks);
+        p->max_chunks_t = std::max(p->max_chunks_t, qt[i].n_chunks);
+    }
     const size_t qb = align_up(sizeof(QuantDesc) * n, 256), sb = align_up(sizeof(StageDesc) * n, 256);
     const size_t i1b = align_up(sizeof(WorkItem) * it1.size(), 256), i2b = align_up(sizeof(WorkItem) * it2.size(), 256);
     hipError_t e = hipMalloc(&p->alloc, 2 * qb + 2 * sb + i1b + i2b);
@@ -686,11 +692,11 @@ static int plan_run(nq_plan p, hipStream_t s, bool timed)
     const StageDesc sdummy{};
     int rc;
     if (timed) NQ_HIP(hipEventRecord(p->ev[0], s));
-    if ((rc = launch_quantize(p->qx, qdummy, p->n, p->batch, s)) != NQ_OK) return rc;
+    if ((rc = launch_quantize(p->qx, qdummy, p->n, p->max_chunks_x, p->batch, s)) != NQ_OK) return rc;
     if (timed) NQ_HIP(hipEventRecord(p->ev[1], s));
     if ((rc = launch_stage(p->s1, sdummy, p->items1, p->n_items1, p->w1, stream_max_rbs(p->batch), p->batch, s)) != NQ_OK) return rc;
     if (timed) NQ_HIP(hipEventRecord(p->ev[2], s));
-    if ((rc = launch_quantize(p->qt, qdummy, p->n, p->batch, s)) != NQ_OK) return rc;
+    if ((rc = launch_quantize(p->qt, qdummy, p->n, p->max_chunks_t, p->batch, s)) != NQ_OK) return rc;
     if (timed) NQ_HIP(hipEventRecord(p->ev[3], s));
     if ((rc = launch_stage(p->s2, sdummy, p->items2, p->n_items2, p->w2, stream_max_rbs(p->batch), p->batch, s)) != NQ_OK) return rc;
     if (timed) NQ_HIP(hipEventRecord(p->ev[4], s));

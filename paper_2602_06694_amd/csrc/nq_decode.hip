@@ -103,11 +103,11 @@ int launch_export(const uint32_t* d_tiles, int64_t wpr, bool transposed, int64_t
 
 // ---------------------------------------------------------------------------------------------
 // fixed-point quantisation of one token's vector (step a1 of the path when `scale` is given)
-// grid = (n_ops, batch), block = kQuantThreads.  A thread owns 16-element chunks (one 16-byte
+// grid = (n_ops, batch), block = NT (256 / 512 / 1024 for vectors up to 8192 / 16384 / longer: a workgroup
+// is one token, and short vectors are latency-bound).  A thread owns 16-element chunks (one 16-byte
 // group of the MFMA B operand per slice); up to kQuantHeld chunks stay in registers between the
 // max pass and the rounding pass, longer vectors are read twice.
 // ---------------------------------------------------------------------------------------------
-constexpr int kQuantThreads = 1024;
 constexpr int kQuantHeld = 2;
 
 __device__ inline void load_chunk16(const QuantDesc& d, int64_t base, int c, bool vec, float v[16])
@@ -185,6 +185,7 @@ __device__ inline long long quantize_chunk16(const float v[16], float inv_step, 
     return sum;
 }
 
+template <int kQuantThreads>
 __global__ void __launch_bounds__(kQuantThreads)
 quantize_kernel(const QuantDesc* __restrict__ descs, QuantDesc single, int batch)
 {
@@ -286,9 +287,16 @@ quantize_kernel(const QuantDesc* __restrict__ descs, QuantDesc single, int batch
     }
 }
 
-int launch_quantize(const QuantDesc* d_descs, const QuantDesc& single, int n_ops, int batch, hipStream_t s)
+// max_chunks: the largest n_chunks among the launch's vectors
+int launch_quantize(const QuantDesc* d_descs, const QuantDesc& single, int n_ops, int max_chunks, int batch,
+                    hipStream_t s)
 {
-    hipLaunchKernelGGL(quantize_kernel, dim3(n_ops, batch), dim3(kQuantThreads), 0, s, d_descs, single, batch);
+    if (max_chunks <= 256 * kQuantHeld)
+        hipLaunchKernelGGL(quantize_kernel<256>, dim3(n_ops, batch), dim3(256), 0, s, d_descs, single, batch);
+    else if (max_chunks <= 512 * kQuantHeld)
+        hipLaunchKernelGGL(quantize_kernel<512>, dim3(n_ops, batch), dim3(512), 0, s, d_descs, single, batch);
+    else
+        hipLaunchKernelGGL(quantize_kernel<1024>, dim3(n_ops, batch), dim3(1024), 0, s, d_descs, single, batch);
     NQ_HIP(hipGetLastError());
     return NQ_OK;
 }

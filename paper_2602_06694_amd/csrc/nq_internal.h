@@ -93,7 +93,8 @@ int launch_repack(const uint32_t* d_canon, int64_t wpr, bool transposed, int64_t
 int launch_export(const uint32_t* d_tiles, int64_t wpr, bool transposed, int64_t M, int64_t N,
                   uint32_t* d_canon, hipStream_t s);
 // single op (descriptor by value) or many (device arrays)
-int launch_quantize(const QuantDesc* d_descs, const QuantDesc& single, int n_ops, int batch, hipStream_t s);
+int launch_quantize(const QuantDesc* d_descs, const QuantDesc& single, int n_ops, int max_chunks, int batch,
+                    hipStream_t s);
 int stage_schedule(int n_rb_total, int mean_steps, int batch);
 int stream_target_steps();
 int stream_max_rbs(int batch);   // row blocks one stream item may chain (bounded by its LDS output buffer)

@@ -286,9 +286,8 @@ extern "C" int nq_binlr_create(nq_handle* out, int64_t d_out, int64_t d_in, int6
 
     // decode workspace
     const int mb = NQ_DECODE_MAX_BATCH;
-    const int nc = ncols_for(mb);
-    const size_t bqx_bytes = align_up((size_t)n_steps(d_in) * 4 * nc * 16, 256);
-    const size_t bqt_bytes = align_up((size_t)n_steps(r) * 4 * nc * 16, 256);
+    const size_t bqx_bytes = align_up((size_t)mb * n_steps(d_in) * 4 * kSlices * 16, 256);
+    const size_t bqt_bytes = align_up((size_t)mb * n_steps(r) * 4 * kSlices * 16, 256);
     const size_t meta_bytes = align_up(sizeof(QMeta) * mb, 256);
     h->t_stride = (int)round_up(r, kTileRows);
     const size_t t_bytes = align_up((size_t)mb * h->t_stride * 4, 256);

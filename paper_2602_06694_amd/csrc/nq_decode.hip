@@ -194,7 +194,6 @@ quantize_kernel(const QuantDesc* __restrict__ descs, QuantDesc single, int batch
     __shared__ int sm_bad;
     const QuantDesc d = descs ? descs[blockIdx.x] : single;
     const int tok = blockIdx.y;
-    const int ncols = ncols_for(batch);
     const int64_t base = (int64_t)tok * d.x_stride;
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
@@ -257,19 +256,19 @@ quantize_kernel(const QuantDesc* __restrict__ descs, QuantDesc single, int batch
 
     // pass 2: q = rint(v / step), split into three signed bytes, write the MFMA B-operand layout
     long long local_sum = 0;
-    const int c0 = col_of(tok, 0);
+    uint4* const dst = (uint4*)(d.bq) + (size_t)tok * d.n_chunks * kSlices;     // token-major: [chunk][slice]
     if (held) {
 #pragma unroll
         for (int k = 0; k < kQuantHeld; ++k) {
             const int c = tid + k * kQuantThreads;
             if (c < d.n_chunks)
-                local_sum += quantize_chunk16(hv[k], inv_step, bad, (uint4*)(d.bq) + ((size_t)c * ncols + c0));
+                local_sum += quantize_chunk16(hv[k], inv_step, bad, dst + (size_t)c * kSlices);
         }
     } else {
         for (int c = tid; c < d.n_chunks; c += kQuantThreads) {
             float v[16];
             load_chunk16(d, base, c, vec, v);
-            local_sum += quantize_chunk16(v, inv_step, bad, (uint4*)(d.bq) + ((size_t)c * ncols + c0));
+            local_sum += quantize_chunk16(v, inv_step, bad, dst + (size_t)c * kSlices);
         }
     }
     double s = (double)local_sum;               // |sum| < 2^39: exact
@@ -319,7 +318,15 @@ int launch_quantize(const QuantDesc* d_descs, const QuantDesc& single, int n_ops
 #define NQ_STAGE_WAVES 5
 #endif
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
 typedef const __attribute__((address_space(1))) v4u* gptr_v4u;    // global (not generic) address space
+// Pointers that come out of a descriptor in memory are generic to the compiler; accesses through
+// them would be flat instructions, which count on two wait counters at once and make every later
+// wait a "wait for everything".  These casts name the address space: global for vector accesses,
+// constant for wave-uniform reads (scalar loads, which the vector-memory counter does not see).
+typedef const __attribute__((address_space(1))) uint16_t* gptr_u16;
+typedef __attribute__((address_space(1))) float* gptr_f32;
+typedef const __attribute__((address_space(4))) QMeta* cptr_meta;
 
 // sign tiles are streamed once, never reused: keep them from displacing the (reused) activations
 __device__ __forceinline__ v4u load_tile_words(const char* base, uint32_t off)
@@ -327,6 +334,20 @@ __device__ __forceinline__ v4u load_tile_words(const char* base, uint32_t off)
     return __builtin_nontemporal_load((gptr_v4u)(base + off));
 }
 __device__ __forceinline__ v4u load_global_v4u(const char* base, uint32_t off) { return *(gptr_v4u)(base + off); }
+
+// Byte offset, inside an op's quantised input, of the 16 bytes lane (g, n) feeds to the MFMA as
+// rows 16g..16g+15 of column n of column group cg, at step 0.  The input is token-major
+// ([token][chunk][slice][16 bytes], a step = 4 chunks = kBqStepBytes); column n of a group is
+// slice n % 3 of the group's token n / 3.  Lanes of unused columns (n = 15, or a token beyond the
+// batch) re-read token 0: their result columns are never looked at.
+constexpr uint32_t kBqStepBytes = 4 * kSlices * 16;
+__device__ __forceinline__ uint32_t bq_lane_offset(int cg, int g, int n, int batch, int nst)
+{
+    int tok = 5 * cg + n / 3;
+    const int slice = n % 3;
+    if (n >= 15 || tok >= batch) tok = 0;
+    return (uint32_t)tok * ((uint32_t)nst * kBqStepBytes) + (uint32_t)((g * kSlices + slice) * 16);
+}
 
 // one 64-column step: eight bit planes, each one AND per register and one MFMA per column group
 template <int NB>
@@ -349,76 +370,95 @@ struct EpilogueArgs {
     int M, out_stride;
 };
 
+// LDS ints one wave needs for the epilogue: 16 columns x 64 rows
+constexpr int kEpiRegion = 16 * 64;
+// most row blocks an item of the stream kernel may chain
+constexpr int kStreamMaxRbs = 8;
+
 // raw accumulators -> LDS [col][row] -> one thread per (token, row): undo the plane weights,
 // join the three byte slices, apply 2*sum(b q) - sum(q), the step and the output scale.
+// The 128 rows x ncols results pass through LDS in pieces of 64 rows (four bit planes) x one
+// column group, so that the LDS a wave holds (and with it the number of resident waves) does not
+// grow with the batch.
 // W = 1: `lds` is this wave's private region and only the wave synchronises;
 // W > 1: `lds` is the workgroup's buffer of W regions and the partial sums of the W waves are added.
-// DEFER: the results go to `lds_out[128 * batch]` (token-major) instead of global memory; the stream
-// kernel flushes them after the item's last row block, because a pending global store in the middle
-// of the stream would force every later wait on the prefetch ring down to "wait for everything"
-// (loads and stores share one in-order counter only among their own kind).
+// DEFER: the results go to `lds_out[128 * batch]` (token-major), not yet multiplied by the output
+// scale, instead of global memory; the stream kernel scales and stores them after the item's last
+// row block.  In the middle of the stream the epilogue must issue no vector memory operation: a
+// pending store would force every later wait on the prefetch ring down to "wait for everything"
+// (loads and stores share one in-order counter only among their own kind), and waiting for a
+// freshly issued load means waiting for the whole ring issued before it.  The per-token constants
+// come through scalar loads, which that counter does not see.
 template <int NB, int W, bool DEFER>
-__device__ __forceinline__ void stage_epilogue(const v4i (&acc)[NB][8], int* lds, int wave, int lane, int ncols,
-                                               int batch, int rb, const EpilogueArgs& e, float* lds_out)
+__device__ __forceinline__ void stage_epilogue(const v4i (&acc)[NB][8], int* lds, int wave, int lane, int batch,
+                                               int rb, const EpilogueArgs& e, float* lds_out)
 {
     const int g = lane >> 4, n = lane & 15;
-    int* my_lds = (W == 1) ? lds : lds + wave * (kTileRows * ncols);
-    // accumulator layout of the 16x16 result: lane (g, n), register v  <->  D[row 4g+v][col n];
-    // the four registers of a plane are four consecutive rows: one 16-byte LDS write per plane
+    int* my_lds = (W == 1) ? lds : lds + wave * kEpiRegion;
+    const cptr_meta meta = (cptr_meta)e.meta;
 #pragma unroll
     for (int cg = 0; cg < NB; ++cg) {
-        int col = cg * 16 + n;
-        if (col < ncols) {
-            v4i* dst = (v4i*)(my_lds + col * kTileRows + 4 * g);
+        const int tg = batch - 5 * cg < 5 ? batch - 5 * cg : 5;      // tokens in this column group
 #pragma unroll
-            for (int p = 0; p < 8; ++p) dst[4 * p] = acc[cg][p];        // rows 16p + 4g .. +3
-        }
-    }
-    if (W == 1) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    } else {
-        __syncthreads();
-    }
-    constexpr int T = 64 * W;                              // threads that cooperate on the outputs
-    const int tid = (W == 1) ? lane : (int)threadIdx.x;
-    for (int o = tid; o < kTileRows * batch; o += T) {
-        int row = o & (kTileRows - 1), tok = o >> 7;
-        int c0 = col_of(tok, 0);
-        int h = 0, m = 0, l = 0;
+        for (int hf = 0; hf < 2; ++hf) {
+            // accumulator layout of the 16x16 result: lane (g, n), register v <-> D[row 4g+v][col n];
+            // the four registers of a plane are four consecutive rows: one 16-byte LDS write per plane
+            if (n < 3 * tg) {
+                v4i* dst = (v4i*)(my_lds + n * 64 + 4 * g);
 #pragma unroll
-        for (int w = 0; w < W; ++w) {
-            const int* q = lds + w * (kTileRows * ncols) + c0 * kTileRows + row;
-            h += q[0];
-            m += q[kTileRows];
-            l += q[2 * kTileRows];
+                for (int p = 0; p < 4; ++p) dst[4 * p] = acc[cg][4 * hf + p];     // rows 16p + 4g .. +3 of the half
+            }
+            if (W == 1) {
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+            } else {
+                __syncthreads();
+            }
+            // one lane per row of the half; the token is the same for the whole wave
+            const int row = lane;
+            const int r128 = 64 * hf + row;
+            const int grow = rb * kTileRows + r128;
+            // plane p holds 2^p * sum (p < 7) or -128 * sum (p = 7, the int8 sign bit): exact shifts
+            const int p = 4 * hf + (row >> 4);
+            float oscale = 1.0f;
+            if (!DEFER && e.out_scale && grow < e.M) oscale = half_bits_to_float(((gptr_u16)e.out_scale)[grow]);
+            for (int tl = wave; tl < tg; tl += W) {
+                int h = 0, m = 0, l = 0;
+#pragma unroll
+                for (int w = 0; w < W; ++w) {
+                    const int* q = lds + w * kEpiRegion + (3 * tl) * 64 + row;
+                    h += q[0];
+                    m += q[64];
+                    l += q[128];
+                }
+                h >>= p;
+                m >>= p;
+                l >>= p;
+                if (p == 7) {
+                    h = -h;
+                    m = -m;
+                    l = -l;
+                }
+                const double bsum = fma((double)h, 65536.0, fma((double)m, 256.0, (double)l));   // sum_n b_n q_n
+                const int tok = 5 * cg + tl;
+                const double sumq = meta[tok].sumq;
+                const float step = meta[tok].step;
+                double val = (2.0 * bsum - sumq) * (double)step;
+                if (DEFER) {
+                    lds_out[tok * kTileRows + r128] = (float)val;       // scaled by s_out when flushed
+                } else if (grow < e.M) {
+                    val *= (double)oscale;
+                    ((gptr_f32)e.out)[(size_t)tok * e.out_stride + grow] = (float)val;
+                }
+            }
+            if (W == 1) {
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                __builtin_amdgcn_wave_barrier();
+            } else {
+                __syncthreads();
+            }
         }
-        // plane p holds 2^p * sum (p < 7) or -128 * sum (p = 7, the int8 sign bit): exact shifts
-        int p = row >> 4;
-        h >>= p;
-        m >>= p;
-        l >>= p;
-        if (p == 7) {
-            h = -h;
-            m = -m;
-            l = -l;
-        }
-        double bsum = fma((double)h, 65536.0, fma((double)m, 256.0, (double)l));   // sum_n b_n q_n
-        QMeta mt = e.meta[tok];
-        double val = (2.0 * bsum - mt.sumq) * (double)mt.step;
-        int grow = rb * kTileRows + row;
-        if (grow < e.M) {
-            if (e.out_scale) val *= (double)half_bits_to_float(e.out_scale[grow]);
-            if (DEFER) lds_out[o] = (float)val;
-            else e.out[(size_t)tok * e.out_stride + grow] = (float)val;
-        }
-    }
-    if (W == 1) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        __builtin_amdgcn_wave_barrier();
-    } else {
-        __syncthreads();
     }
 }
 
@@ -452,8 +492,7 @@ stage_stream_kernel(const StageDesc* __restrict__ descs, StageDesc single, const
     extern __shared__ int lds[];
     const int lane = threadIdx.x;
     const int g = lane >> 4, n = lane & 15;
-    const int ncols = ncols_for(batch);
-    float* lds_out = (float*)(lds + kTileRows * ncols);     // [rbs of the item][batch][128 rows]
+    float* lds_out = (float*)(lds + kEpiRegion);            // [rbs of the item][batch][128 rows]
     for (int it = blockIdx.x; it < n_items; it += gridDim.x) {
         // descriptor fields are wave-uniform (scalar loads); what the first tile load depends on
         // comes from the work item alone
@@ -462,14 +501,10 @@ stage_stream_kernel(const StageDesc* __restrict__ descs, StageDesc single, const
         const char* a_base = (const char*)tiles;
         const char* b_base = (const char*)bq;
         uint32_t a_off = (uint32_t)(lane * 16);
-        // lanes whose column is beyond ncols re-read column 0: their result columns are never used
         uint32_t b_lane[NB];
 #pragma unroll
-        for (int cg = 0; cg < NB; ++cg) {
-            int col = cg * 16 + n;
-            b_lane[cg] = (uint32_t)((g * ncols + (col < ncols ? col : 0)) * 16);
-        }
-        const uint32_t b_inc = (uint32_t)(4 * ncols * 16);
+        for (int cg = 0; cg < NB; ++cg) b_lane[cg] = bq_lane_offset(cg, g, n, batch, nst);
+        const uint32_t b_inc = kBqStepBytes;
         int b_step = 0;                                    // step (inside its row block) of the next tile to fetch
 
         v4u wbuf[D];
@@ -517,16 +552,44 @@ stage_stream_kernel(const StageDesc* __restrict__ descs, StageDesc single, const
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
-            stage_epilogue<NB, 1, true>(acc, lds, 0, lane, ncols, batch, rb0 + u, ea,
+            stage_epilogue<NB, 1, true>(acc, lds, 0, lane, batch, rb0 + u, ea,
                                         lds_out + u * (kTileRows * batch));
         }
 #undef NQ_ISSUE
-        // flush the item's results: n_rb row blocks x batch tokens x 128 rows
+        // flush the item's results: n_rb row blocks x batch tokens x 128 rows.  The output scales
+        // of the item's rows (contiguous fp16, 16-byte loads of 8; the array is padded to whole row
+        // blocks) first go to the now idle epilogue region as floats.
+        float* lds_sc = (float*)lds;
+        static_assert(kStreamMaxRbs * kTileRows <= kEpiRegion, "scales of an item must fit the epilogue region");
+#pragma unroll
+        for (int h = 0; h < kStreamMaxRbs * kTileRows / 512; ++h) {
+            const int r0 = 512 * h + 8 * lane;
+            if (r0 < n_rb * kTileRows) {
+                float f[8];
+                if (ea.out_scale) {
+                    const v4u raw = load_global_v4u((const char*)ea.out_scale, (uint32_t)((rb0 * kTileRows + r0) * 2));
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        f[2 * i] = half_bits_to_float((uint16_t)(raw[i] & 0xffffu));
+                        f[2 * i + 1] = half_bits_to_float((uint16_t)(raw[i] >> 16));
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) f[i] = 1.0f;
+                }
+                *(v4f*)(lds_sc + r0) = v4f{f[0], f[1], f[2], f[3]};
+                *(v4f*)(lds_sc + r0 + 4) = v4f{f[4], f[5], f[6], f[7]};
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
         for (int o = lane; o < n_rb * kTileRows * batch; o += 64) {
             const int u = o / (kTileRows * batch), rem = o - u * (kTileRows * batch);
             const int tok = rem >> 7, row = rem & (kTileRows - 1);
             const int grow = (rb0 + u) * kTileRows + row;
-            if (grow < ea.M) ea.out[(size_t)tok * ea.out_stride + grow] = lds_out[o];
+            if (grow < ea.M)
+                ((gptr_f32)ea.out)[(size_t)tok * ea.out_stride + grow] = lds_out[o] * lds_sc[u * kTileRows + row];
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __builtin_amdgcn_wave_barrier();
@@ -542,7 +605,6 @@ stage_split_kernel(const StageDesc* __restrict__ descs, StageDesc single, const 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int g = lane >> 4, n = lane & 15;
-    const int ncols = ncols_for(batch);
     constexpr int rbs_per_item = 1;
     const int st0 = wave;
 
@@ -557,11 +619,8 @@ stage_split_kernel(const StageDesc* __restrict__ descs, StageDesc single, const 
         uint32_t a_off = (uint32_t)(stf * 1024 + lane * 16);
         uint32_t b_off[NB];
 #pragma unroll
-        for (int cg = 0; cg < NB; ++cg) {
-            int col = cg * 16 + n;
-            b_off[cg] = (uint32_t)(((stf * 4 + g) * ncols + (col < ncols ? col : 0)) * 16);
-        }
-        const uint32_t b_inc = (uint32_t)(W * 4 * ncols * 16);
+        for (int cg = 0; cg < NB; ++cg) b_off[cg] = (uint32_t)stf * kBqStepBytes + bq_lane_offset(cg, g, n, batch, nst);
+        const uint32_t b_inc = (uint32_t)W * kBqStepBytes;
 
         v4i acc[NB][8];
 #pragma unroll
@@ -624,7 +683,7 @@ stage_split_kernel(const StageDesc* __restrict__ descs, StageDesc single, const 
             }
         }
 #undef NQ_ISSUE
-        stage_epilogue<NB, W, false>(acc, lds, wave, lane, ncols, batch, rb0, ea, nullptr);
+        stage_epilogue<NB, W, false>(acc, lds, wave, lane, batch, rb0, ea, nullptr);
     }
 }
 #undef NQ_LOAD_ITEM
@@ -656,8 +715,7 @@ template <int NB>
 static int launch_stream_t(const StageDesc* d_descs, const StageDesc& single, const WorkItem* d_items, int n_items,
                            int rbs_per_item, int max_rbs_per_item, int batch, hipStream_t s)
 {
-    const int ncols = ncols_for(batch);
-    size_t lds_bytes = (size_t)kTileRows * ncols * sizeof(int) + (size_t)max_rbs_per_item * kTileRows * batch * sizeof(float);
+    size_t lds_bytes = (size_t)kEpiRegion * sizeof(int) + (size_t)max_rbs_per_item * kTileRows * batch * sizeof(float);
     if (n_items < 1) return NQ_OK;
     hipLaunchKernelGGL((stage_stream_kernel<NB, kRingDepth>), dim3(n_items), dim3(64), lds_bytes, s, d_descs, single,
                        d_items, n_items, rbs_per_item, batch);
@@ -669,10 +727,9 @@ template <int NB, int W>
 static int launch_split_t(const StageDesc* d_descs, const StageDesc& single, const WorkItem* d_items, int n_items,
                           int batch, hipStream_t s)
 {
-    const int ncols = ncols_for(batch);
-    size_t lds_bytes = (size_t)W * kTileRows * ncols * sizeof(int);
+    size_t lds_bytes = (size_t)W * kEpiRegion * sizeof(int);
     if (n_items < 1) return NQ_OK;
-    hipLaunchKernelGGL((stage_split_kernel<NB, W, kRingDepth>), dim3(n_items), dim3(64 * W), lds_bytes, s, d_descs,
+    hipLaunchKernelGGL((stage_split_kernel<NB, W, (NB == 1 ? kRingDepth : 2 * kRingDepth)>), dim3(n_items), dim3(64 * W), lds_bytes, s, d_descs,
                        single, d_items, n_items, batch);
     NQ_HIP(hipGetLastError());
     return NQ_OK;
@@ -700,7 +757,7 @@ int stage_schedule(int n_rb_total, int mean_steps, int batch)
 // Steps one wave of the stream kernel should see per item (several short row blocks are chained).
 int stream_target_steps() { return env_int("NQ_STREAM_STEPS", 128); }
 
-int stream_max_rbs(int batch) { return std::max(1, 8 / batch); }
+int stream_max_rbs(int batch) { return std::max(1, kStreamMaxRbs / batch); }
 
 int launch_stage(const StageDesc* d_descs, const StageDesc& single, const WorkItem* d_items, int n_items,
                  int w, int rbs_per_item, int batch, hipStream_t s)

@@ -25,11 +25,9 @@ constexpr int kTileWords = 256;
 // The streaming kernels contract exact integers.  Each token's vector v (x' = s_in (.) x for
 // stage 1, t for stage 2) is written as v_j ~= step * q_j with step a power of two chosen from
 // the token's max |v_j| so that |q_j| <= 2^22, and q_j is split into three signed bytes
-// q = 65536*hi + 256*mid + lo.  A token occupies three MFMA columns (hi, mid, lo).
-// Column of (token, slice): tokens 0..4 sit in columns 0..14, tokens 5..7 in columns 16..24.
+// q = 65536*hi + 256*mid + lo.  A token occupies three MFMA columns (hi, mid, lo) of a group of 16:
+// five tokens per group; tokens 0..4 are columns 0..14 of group 0, tokens 5..7 columns 0..8 of group 1.
 constexpr int kSlices = 3;
-__host__ __device__ inline int col_of(int token, int slice) { return (token / 5) * 16 + (token % 5) * 3 + slice; }
-__host__ __device__ inline int ncols_for(int batch) { return batch <= 5 ? 3 * batch : 16 + 3 * (batch - 5); }
 
 struct QMeta {        // per token, written by the quantisation kernel
     double sumq;      // sum_j q_j (exact)
@@ -40,7 +38,7 @@ struct QMeta {        // per token, written by the quantisation kernel
 struct QuantDesc {
     const void* x;           // device [batch][x_stride]
     const uint16_t* scale;   // device fp16 [N] or nullptr (no scaling)
-    uint8_t* bq;             // device [n_chunks][ncols][16] signed bytes
+    uint8_t* bq;             // device [batch][n_chunks][3 slices][16] signed bytes
     QMeta* meta;             // device [batch]
     int N;                   // real length
     int n_chunks;            // 16-element chunks including padding (= 4 * n_steps)

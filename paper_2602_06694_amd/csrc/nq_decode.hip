@@ -745,7 +745,7 @@ int stage_schedule(int n_rb_total, int mean_steps, int batch)
 {
     const int full = device_cu_count() * 8;
     int w;
-    if (n_rb_total >= full) w = mean_steps >= env_int("NQ_SPLIT_STEPS", 64) ? 4 : 1;
+    if (n_rb_total >= full) w = (mean_steps >= env_int("NQ_SPLIT_STEPS", 64) && batch <= 5) ? 4 : 1;
     else w = (n_rb_total * 4 >= full || batch > 2) ? 4 : 16;
     if (const char* f = getenv("NQ_FORCE_W")) {
         int fw = atoi(f);
@@ -757,7 +757,13 @@ int stage_schedule(int n_rb_total, int mean_steps, int batch)
 // Steps one wave of the stream kernel should see per item (several short row blocks are chained).
 int stream_target_steps() { return env_int("NQ_STREAM_STEPS", 128); }
 
-int stream_max_rbs(int batch) { return std::max(1, kStreamMaxRbs / batch); }
+// Row blocks an item may chain: its deferred results (128 x batch floats per row block) share the
+// CU's LDS with those of the other resident waves (20 per CU with one column group, 8 with two).
+int stream_max_rbs(int batch)
+{
+    const int per = batch <= 5 ? kStreamMaxRbs / batch : 30 / batch;
+    return std::max(1, std::min(per, kStreamMaxRbs));
+}
 
 int launch_stage(const StageDesc* d_descs, const StageDesc& single, const WorkItem* d_items, int n_items,
                  int w, int rbs_per_item, int batch, hipStream_t s)

@@ -286,8 +286,10 @@ extern "C" int nq_binlr_create(nq_handle* out, int64_t d_out, int64_t d_in, int6
 
     // decode workspace
     const int mb = NQ_DECODE_MAX_BATCH;
-    const size_t bqx_bytes = align_up((size_t)mb * n_steps(d_in) * 4 * kSlices * 16, 256);
-    const size_t bqt_bytes = align_up((size_t)mb * n_steps(r) * 4 * kSlices * 16, 256);
+    // (+1 KiB: the shared-input kernel stages whole chunks of 8 steps and may read up to 4 steps
+    // past the last token's data; what it reads there is never used)
+    const size_t bqx_bytes = align_up((size_t)mb * n_steps(d_in) * 4 * kSlices * 16 + 1024, 256);
+    const size_t bqt_bytes = align_up((size_t)mb * n_steps(r) * 4 * kSlices * 16 + 1024, 256);
     const size_t meta_bytes = align_up(sizeof(QMeta) * mb, 256);
     h->t_stride = (int)round_up(r, kTileRows);
     const size_t t_bytes = align_up((size_t)mb * h->t_stride * 4, 256);
@@ -595,6 +597,14 @@ extern "C" int nq_plan_create(nq_plan* out, const nq_handle* hs, const void* con
         sched[st] = w;
         for (int i = 0; i < n; ++i) {
             const int nrb = (int)n_rowblocks(sd[i].M);
+            if (w == kSharedSchedule) {
+                // eight waves share an op's input: items of 8 x (row blocks per wave) row blocks
+                const int group = kSharedSchedule * shared_per_wave(sd[i].n_steps, batch);
+                for (int rb = 0; rb < nrb; rb += group)
+                    lists[st].push_back(WorkItem{sd[i].tiles + (size_t)rb * sd[i].n_steps * kTileWords, sd[i].bq,
+                                                 sd[i].n_steps, i, rb, std::min(group, nrb - rb)});
+                continue;
+            }
             const int per = w == 1 ? rbs_per_stream_item(nrb, sd[i].n_steps, total_rb, batch) : 1;
             // runs of `per` row blocks first, then shorter and shorter ones: the sorted list ends in
             // small items, which level out the finishing times of the waves (the hardware hands an

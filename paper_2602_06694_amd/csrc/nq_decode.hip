@@ -462,6 +462,47 @@ __device__ __forceinline__ void stage_epilogue(const v4i (&acc)[NB][8], int* lds
     }
 }
 
+// End of an item of a streaming wave: the deferred results of its n_rb row blocks x batch tokens x
+// 128 rows are scaled and stored.  The output scales of the item's rows (contiguous fp16, 16-byte
+// loads of 8; the array is padded to whole row blocks) first go to the wave's now idle epilogue
+// region `lds` as floats.
+__device__ __forceinline__ void stream_flush(int* lds, const float* lds_out, int lane, int rb0, int n_rb, int batch,
+                                             const EpilogueArgs& ea)
+{
+    float* lds_sc = (float*)lds;
+    static_assert(kStreamMaxRbs * kTileRows <= kEpiRegion, "scales of an item must fit the epilogue region");
+#pragma unroll
+    for (int h = 0; h < kStreamMaxRbs * kTileRows / 512; ++h) {
+        const int r0 = 512 * h + 8 * lane;
+        if (r0 < n_rb * kTileRows) {
+            float f[8];
+            if (ea.out_scale) {
+                const v4u raw = load_global_v4u((const char*)ea.out_scale, (uint32_t)((rb0 * kTileRows + r0) * 2));
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    f[2 * i] = half_bits_to_float((uint16_t)(raw[i] & 0xffffu));
+                    f[2 * i + 1] = half_bits_to_float((uint16_t)(raw[i] >> 16));
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) f[i] = 1.0f;
+            }
+            *(v4f*)(lds_sc + r0) = v4f{f[0], f[1], f[2], f[3]};
+            *(v4f*)(lds_sc + r0 + 4) = v4f{f[4], f[5], f[6], f[7]};
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    for (int o = lane; o < n_rb * kTileRows * batch; o += 64) {
+        const int u = o / (kTileRows * batch), rem = o - u * (kTileRows * batch);
+        const int tok = rem >> 7, row = rem & (kTileRows - 1);
+        const int grow = (rb0 + u) * kTileRows + row;
+        if (grow < ea.M)
+            ((gptr_f32)ea.out)[(size_t)tok * ea.out_stride + grow] = lds_out[o] * lds_sc[u * kTileRows + row];
+    }
+}
+
 #define NQ_LOAD_ITEM()                                                                             \
     const uint32_t* tiles;                                                                         \
     const uint8_t* bq;                                                                             \
@@ -556,41 +597,7 @@ stage_stream_kernel(const StageDesc* __restrict__ descs, StageDesc single, const
                                         lds_out + u * (kTileRows * batch));
         }
 #undef NQ_ISSUE
-        // flush the item's results: n_rb row blocks x batch tokens x 128 rows.  The output scales
-        // of the item's rows (contiguous fp16, 16-byte loads of 8; the array is padded to whole row
-        // blocks) first go to the now idle epilogue region as floats.
-        float* lds_sc = (float*)lds;
-        static_assert(kStreamMaxRbs * kTileRows <= kEpiRegion, "scales of an item must fit the epilogue region");
-#pragma unroll
-        for (int h = 0; h < kStreamMaxRbs * kTileRows / 512; ++h) {
-            const int r0 = 512 * h + 8 * lane;
-            if (r0 < n_rb * kTileRows) {
-                float f[8];
-                if (ea.out_scale) {
-                    const v4u raw = load_global_v4u((const char*)ea.out_scale, (uint32_t)((rb0 * kTileRows + r0) * 2));
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        f[2 * i] = half_bits_to_float((uint16_t)(raw[i] & 0xffffu));
-                        f[2 * i + 1] = half_bits_to_float((uint16_t)(raw[i] >> 16));
-                    }
-                } else {
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) f[i] = 1.0f;
-                }
-                *(v4f*)(lds_sc + r0) = v4f{f[0], f[1], f[2], f[3]};
-                *(v4f*)(lds_sc + r0 + 4) = v4f{f[4], f[5], f[6], f[7]};
-            }
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-        for (int o = lane; o < n_rb * kTileRows * batch; o += 64) {
-            const int u = o / (kTileRows * batch), rem = o - u * (kTileRows * batch);
-            const int tok = rem >> 7, row = rem & (kTileRows - 1);
-            const int grow = (rb0 + u) * kTileRows + row;
-            if (grow < ea.M)
-                ((gptr_f32)ea.out)[(size_t)tok * ea.out_stride + grow] = lds_out[o] * lds_sc[u * kTileRows + row];
-        }
+        stream_flush(lds, lds_out, lane, rb0, n_rb, batch, ea);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __builtin_amdgcn_wave_barrier();
     }
@@ -686,6 +693,181 @@ stage_split_kernel(const StageDesc* __restrict__ descs, StageDesc single, const 
         stage_epilogue<NB, W, false>(acc, lds, wave, lane, batch, rb0, ea, nullptr);
     }
 }
+// ---------------------------------------------------------------------------------------------
+// Third schedule, for two column groups (batch 6..8) in launches that fill the chip: the eight
+// waves of a workgroup take row blocks of ONE op and share its quantised input through LDS.
+// With the B operand out of the registers (and off the vector-memory counter, which returns
+// loads in order) a wave affords a ring of eight tiles although the 64 accumulator registers
+// leave room for two waves per SIMD only; and the input is fetched from L2 once per eight
+// row blocks instead of once per row block.
+//   - the input is staged in chunks of 8 steps (one pass over the ring), double buffered; every
+//     wave fetches 1/8 of the next chunk at the start of a pass and writes it to LDS at the end
+//     (by then those loads are the oldest outstanding ones); one barrier per pass;
+//   - wave w owns `per` = ceil(n_rb / 8) consecutive row blocks of the item (their tiles are
+//     contiguous, the ring runs on across them); results are deferred through LDS as in the
+//     stream kernel;
+//   - a reduction that is not a multiple of 8 steps ends in half a pass, so such ops get one row
+//     block per wave (the host sees to that);
+//   - refills past the wave's last tile re-read that tile, and a wave with fewer row blocks than
+//     its siblings keeps multiplying that tile without storing anything: no branches around
+//     loads, the wait counts stay exact.
+// LDS: [2][batch][kShareTokStride] input | [8][kEpiRegion] epilogue | [8][per_max][128 * batch] results.
+// ---------------------------------------------------------------------------------------------
+constexpr int kShareWaves = 8;
+constexpr int kShareChunk = 8;
+// bytes between tokens of a staged chunk; = 48 mod 256, which spreads the 15 (token, slice)
+// operands of a 16-lane group over all LDS banks
+constexpr int kShareTokStride = kShareChunk * (int)kBqStepBytes + 48;
+static_assert(kShareTokStride % 256 == 48, "bank spread");
+
+template <int NB>
+__global__ void __launch_bounds__(64 * kShareWaves) __attribute__((amdgpu_waves_per_eu(2, 2)))
+stage_shared_kernel(const StageDesc* __restrict__ descs, const WorkItem* __restrict__ items, int n_items, int per_max,
+                    int batch)
+{
+    extern __shared__ int lds[];
+    constexpr int W = kShareWaves;
+    static_assert(kShareWaves == kSharedSchedule, "schedule code");
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4, n = lane & 15;
+    const int buf_bytes = batch * kShareTokStride;
+    char* const lds_b = (char*)lds;
+    int* const lds_epi = (int*)(lds_b + 2 * buf_bytes) + wave * kEpiRegion;
+    float* const lds_out = (float*)((int*)(lds_b + 2 * buf_bytes) + W * kEpiRegion) + wave * (per_max * kTileRows * batch);
+
+    // this lane's operand inside a staged chunk (step 0); unused columns read token 0
+    uint32_t b_lds[NB];
+#pragma unroll
+    for (int cg = 0; cg < NB; ++cg) {
+        int tok = 5 * cg + n / 3;
+        if (n >= 15 || tok >= batch) tok = 0;
+        b_lds[cg] = (uint32_t)(tok * kShareTokStride + (g * kSlices + n % 3) * 16);
+    }
+    // this thread's share of a chunk: 16-byte pieces id = i * 512 + tid < batch * 96 (i < 2);
+    // piece id -> token id / 96, offset (id % 96) * 16 inside the token's chunk.  A thread without
+    // a piece copies piece 0 as well (same bytes to the same place), which keeps the copy free of
+    // branches and the wait counts the same on every path.
+    constexpr int kPiecesPerTok = kShareChunk * (int)kBqStepBytes / 16;        // 96
+    constexpr int kShare = 2;
+    static_assert(kShare * 64 * kShareWaves >= 8 * kPiecesPerTok, "a chunk of 8 tokens in 2 pieces per thread");
+    uint32_t sh_src[kShare], sh_dst[kShare];
+#pragma unroll
+    for (int i = 0; i < kShare; ++i) {
+        const int id = i * (64 * W) + tid;
+        const int idc = id < batch * kPiecesPerTok ? id : 0;
+        const int tok = idc / kPiecesPerTok, piece = idc - tok * kPiecesPerTok;
+        sh_src[i] = (uint32_t)(piece * 16);                                   // + tok * (one token's bytes), per item
+        sh_dst[i] = (uint32_t)(tok * kShareTokStride + piece * 16);
+    }
+
+    for (int it = blockIdx.x; it < n_items; it += gridDim.x) {
+        const WorkItem* e = items + it;
+        const int nst = e->n_steps, n_rb = e->n_rb, rb_first = e->rb;
+        const char* const b_base = (const char*)e->bq;
+        const StageDesc* dp = descs + e->op;
+        EpilogueArgs ea;
+        ea.meta = dp->meta; ea.out_scale = dp->out_scale; ea.out = dp->out;
+        ea.M = dp->M; ea.out_stride = dp->out_stride;
+        const int per = (n_rb + W - 1) / W;
+        const int my0 = wave * per;
+        const int my_n = n_rb - my0 < per ? (n_rb - my0 > 0 ? n_rb - my0 : 0) : per;
+        const int passes = nst >> 3;                                    // full passes per row block
+        const int chunks = (nst + kShareChunk - 1) / kShareChunk;       // passes + the half pass, if any
+        const uint32_t tok_bytes = (uint32_t)nst * kBqStepBytes;         // one token's quantised input
+        uint32_t sh_off[kShare];
+#pragma unroll
+        for (int i = 0; i < kShare; ++i) sh_off[i] = (sh_dst[i] / kShareTokStride) * tok_bytes + sh_src[i];
+
+        // the wave's tile stream (a wave without a row block aims at the item's first tile)
+        const char* const a_base = (const char*)(e->tiles) + (size_t)(my_n > 0 ? my0 : 0) * nst * (kTileWords * 4);
+        uint32_t a_off = (uint32_t)(lane * 16);
+        const uint32_t a_last = (uint32_t)(((my_n > 0 ? my_n * nst : 1) - 1) * 1024 + lane * 16);
+        v4u wbuf[8];
+#define NQ_ISSUE(k)                                                              \
+    do {                                                                         \
+        wbuf[k] = load_tile_words(a_base, a_off);                                \
+        a_off = a_off + 1024 < a_last ? a_off + 1024 : a_last;                   \
+    } while (0)
+        // this thread's share of chunk c (the half pass stages a whole chunk too: the quantised
+        // input is padded to 4 steps and the allocation to more, see the workspace layout)
+#define NQ_SHARE_LOAD(c)                                                         \
+    _Pragma("unroll") for (int i = 0; i < kShare; ++i)                           \
+        sh[i] = load_global_v4u(b_base, sh_off[i] + (uint32_t)((c) * kShareChunk) * kBqStepBytes)
+#define NQ_SHARE_STORE(buf)                                                      \
+    _Pragma("unroll") for (int i = 0; i < kShare; ++i)                           \
+        *(v4u*)(lds_b + (buf) * buf_bytes + sh_dst[i]) = sh[i]
+        v4u sh[kShare];
+
+        __syncthreads();                                   // the previous item's readers are done with the buffers
+        int round = 0;                                     // chunks consumed so far
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            NQ_ISSUE(k);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        NQ_SHARE_LOAD(0);
+        NQ_SHARE_STORE(0);
+
+        // operands of step j of the current chunk
+#define NQ_LDSB(dst, j)                                                          \
+    _Pragma("unroll") for (int cg = 0; cg < NB; ++cg)                            \
+        dst[cg] = *(const v4u*)(bb + b_lds[cg] + (j) * (int)kBqStepBytes)
+        // `cnt` steps on ring slots 0.., operands prefetched one step ahead
+#define NQ_PASS(cnt)                                                             \
+    do {                                                                         \
+        v4u bop[2][NB];                                                          \
+        NQ_LDSB(bop[0], 0);                                                      \
+        _Pragma("unroll") for (int k = 0; k < (cnt); ++k) {                      \
+            if (k + 1 < (cnt)) NQ_LDSB(bop[(k + 1) & 1], k + 1);                 \
+            mac_tile<NB>(acc, wbuf[k], bop[k & 1]);                              \
+            NQ_ISSUE(k);                                                         \
+            __builtin_amdgcn_sched_barrier(0);                                   \
+        }                                                                        \
+    } while (0)
+
+        // one row block of this wave: full passes, then (HALF) the closing half pass
+#define NQ_ROW_BLOCK(u, HALF)                                                    \
+    do {                                                                         \
+        v4i acc[NB][8];                                                          \
+        _Pragma("unroll") for (int cg = 0; cg < NB; ++cg)                        \
+            _Pragma("unroll") for (int p = 0; p < 8; ++p) acc[cg][p] = v4i{0, 0, 0, 0}; \
+        for (int c = 0; c < passes; ++c, ++round) {                              \
+            __syncthreads();             /* chunk c is in its buffer; the other buffer is free */ \
+            const char* const bb = lds_b + (round & 1) * buf_bytes;              \
+            NQ_SHARE_LOAD(c + 1 == chunks ? 0 : c + 1);                          \
+            NQ_PASS(8);                                                          \
+            NQ_SHARE_STORE((round & 1) ^ 1);                                     \
+        }                                                                        \
+        if (HALF) {                                                              \
+            __syncthreads();                                                     \
+            const char* const bb = lds_b + (round & 1) * buf_bytes;              \
+            NQ_PASS(4);                                                          \
+            ++round;                                                             \
+        }                                                                        \
+        if ((u) < my_n)                                                          \
+            stage_epilogue<NB, 1, true>(acc, lds_epi, 0, lane, batch, rb_first + my0 + (u), ea, \
+                                        lds_out + (u) * (kTileRows * batch));    \
+    } while (0)
+
+        if (nst & 4) {
+            // the half pass leaves the ring out of phase: it must be the last thing the wave
+            // computes, so such an item has one row block per wave
+            NQ_ROW_BLOCK(0, true);
+        } else {
+            for (int u = 0; u < per; ++u) NQ_ROW_BLOCK(u, false);
+        }
+#undef NQ_ROW_BLOCK
+#undef NQ_PASS
+#undef NQ_LDSB
+#undef NQ_SHARE_STORE
+#undef NQ_SHARE_LOAD
+#undef NQ_ISSUE
+        if (my_n > 0) stream_flush(lds_epi, lds_out, lane, rb_first + my0, my_n, batch, ea);
+    }
+}
+
 #undef NQ_LOAD_ITEM
 
 static int g_cu_count = 0;
@@ -735,21 +917,66 @@ static int launch_split_t(const StageDesc* d_descs, const StageDesc& single, con
     return NQ_OK;
 }
 
+// Row blocks per wave of the shared schedule: bounded by the LDS left for deferred results.
+int shared_max_per(int batch)
+{
+    const int left = 160 * 1024 - 1024 - 2 * batch * kShareTokStride - kShareWaves * kEpiRegion * 4;
+    const int per = left / (kShareWaves * kTileRows * 4 * batch);
+    return std::max(1, std::min(per, 4));
+}
+
+// rows blocks per wave for an op with `nst` steps per row block (see stage_shared_kernel)
+int shared_per_wave(int nst, int batch)
+{
+    if (nst % 8 != 0) return 1;                       // a half pass must be the last thing a wave does
+    return std::max(1, std::min(shared_max_per(batch), stream_target_steps() / std::max(1, nst)));
+}
+
+template <int NB>
+static int launch_shared_t(const StageDesc* d_descs, const WorkItem* d_items, int n_items, int batch, hipStream_t s)
+{
+    static bool attr_set = false;
+    const int per_max = shared_max_per(batch);
+    const size_t lds_bytes = (size_t)2 * batch * kShareTokStride + (size_t)kShareWaves * kEpiRegion * 4 +
+                             (size_t)kShareWaves * per_max * kTileRows * batch * 4;
+    if (!d_items) {
+        set_error("launch_stage: the shared schedule needs a work list");
+        return NQ_E_INVALID_ARG;
+    }
+    if (n_items < 1) return NQ_OK;
+    if (!attr_set) {
+        NQ_HIP(hipFuncSetAttribute((const void*)stage_shared_kernel<NB>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   160 * 1024));
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((stage_shared_kernel<NB>), dim3(n_items), dim3(64 * kShareWaves), lds_bytes, s, d_descs, d_items,
+                       n_items, per_max, batch);
+    NQ_HIP(hipGetLastError());
+    return NQ_OK;
+}
+
 // Which schedule a launch of `n_rb_total` row blocks with (work-weighted) mean reduction length
-// `mean_steps` takes.  Returns W: 1 = stream kernel, 4 / 16 = split kernel.
+// `mean_steps` takes.  Returns W: 1 = stream kernel, 4 / 16 = split kernel, kSharedSchedule = shared-input kernel.
 //  - few row blocks (a single layer): split so that the launch still covers the chip;
-//  - many: long reductions (>= 64 steps) are split four ways, which shortens the longest serial
-//    stream and the tail of the launch; short ones run one wave per item, several row blocks in a
-//    row, where the LDS reduction and the barriers of a split would cost more than they give.
+//  - many, batch <= 5: long reductions (>= 64 steps) are split four ways, which shortens the
+//    longest serial stream and the tail of the launch; short ones run one wave per item, several
+//    row blocks in a row, where the LDS reduction and the barriers of a split would cost more
+//    than they give;
+//  - many, batch 6..8: long reductions (>= 32 steps) go to the kernel whose eight waves share the
+//    op's input through LDS, short ones again to one wave per item (a barrier per 8 steps and an
+//    epilogue per 16 do not pay).
 int stage_schedule(int n_rb_total, int mean_steps, int batch)
 {
-    const int full = device_cu_count() * 8;
+    // row blocks from which a launch counts as filling the chip (NQ_SCHEDULE_FULL overrides it,
+    // which lets small inputs exercise the schedules built for large launches)
+    const int full = env_int("NQ_SCHEDULE_FULL", device_cu_count() * 8);
     int w;
-    if (n_rb_total >= full) w = (mean_steps >= env_int("NQ_SPLIT_STEPS", 64) && batch <= 5) ? 4 : 1;
+    if (n_rb_total >= full && batch > 5) w = mean_steps >= env_int("NQ_SHARE_STEPS", 32) ? kShareWaves : 1;
+    else if (n_rb_total >= full) w = mean_steps >= env_int("NQ_SPLIT_STEPS", 64) ? 4 : 1;
     else w = (n_rb_total * 4 >= full || batch > 2) ? 4 : 16;
     if (const char* f = getenv("NQ_FORCE_W")) {
         int fw = atoi(f);
-        if (fw == 1 || fw == 4 || (fw == 16 && batch <= 2)) w = fw;
+        if (fw == 1 || fw == 4 || (fw == 16 && batch <= 2)) w = fw;     // (the shared schedule cannot be forced: it needs a work list)
     }
     return w;
 }
@@ -769,6 +996,13 @@ int launch_stage(const StageDesc* d_descs, const StageDesc& single, const WorkIt
                  int w, int rbs_per_item, int batch, hipStream_t s)
 {
     const int nb = batch <= 5 ? 1 : 2;
+    if (w == kShareWaves) {
+        if (nb != 2) {
+            set_error("launch_stage: the shared schedule is built for batch 6..8");
+            return NQ_E_INVALID_ARG;
+        }
+        return launch_shared_t<2>(d_descs, d_items, n_items, batch, s);
+    }
     if (w == 1) {
         const int mx = stream_max_rbs(batch);
         if (rbs_per_item > mx) {

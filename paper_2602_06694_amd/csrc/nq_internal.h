@@ -95,7 +95,10 @@ int launch_quantize(const QuantDesc* d_descs, const QuantDesc& single, int n_ops
                     hipStream_t s);
 int stage_schedule(int n_rb_total, int mean_steps, int batch);
 int stream_target_steps();
-int stream_max_rbs(int batch);   // row blocks one stream item may chain (bounded by its LDS output buffer)
+int stream_max_rbs(int batch);
+constexpr int kSharedSchedule = 8;     // stage_schedule()'s value for the workgroup-shared-input kernel
+int shared_per_wave(int nst, int batch);
+int shared_per_wave(int nst, int batch);   // row blocks one stream item may chain (bounded by its LDS output buffer)
 // w = 1: stream kernel (items are runs of rbs_per_item row blocks); w = 4 / 16: split kernel (one row block per item)
 int launch_stage(const StageDesc* d_descs, const StageDesc& single, const WorkItem* d_items, int n_items,
                  int w, int rbs_per_item, int batch, hipStream_t s);

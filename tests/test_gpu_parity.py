@@ -115,6 +115,48 @@ def test_integer_exact_mode_matches_bit_for_bit():
     L.close()
 
 
+@pytest.mark.parametrize("shape", [(96, 65536, 64), (65536, 96, 64), (40, 72, 65536)])
+def test_maximum_dimensions(shape):
+    # each of d_in, d_out, r at NQ_MAX_DIM, the others small; every decode batch class
+    d_out, d_in, r = shape
+    assert max(shape) == nq.NQ_MAX_DIM
+    L = Layer(d_out, d_in, r, "bf16", seed=900 + d_out % 7)
+    for batch in (1, 5, 8):
+        x = synth.gen_x(batch, d_in, 910 + batch, "bf16")
+        assert rel_err(L.forward(x), L.oracle(x)) <= DECODE_TOL, batch
+    L.close()
+
+
+def test_accumulators_at_their_extreme_values():
+    # The streaming kernels add signed bytes of the fixed-point activations, weighted by a bit
+    # plane (2^p, or -128 for plane 7), in int32.  With d_in = NQ_MAX_DIM, every sign +1 and every
+    # low byte at -128 the plane-7 sums reach 65535 * 128 * 128 = 2^30 - 2^14: the largest value the
+    # format can produce, which must still be exact.  Scales are powers of two and the inputs
+    # integers, so the fp64 oracle is exact too.
+    d_out, d_in, r = 128, nq.NQ_MAX_DIM, 64
+    ones_u = oracle.pack_signs(np.ones((d_out, r), dtype=np.int8))
+    ones_v = oracle.pack_signs(np.ones((d_in, r), dtype=np.int8))
+    s_out = np.ones(d_out, dtype=np.float16)
+    s_in = np.ones(d_in, dtype=np.float16)
+    data = synth.LayerData(synth.LinearShape("m", d_out, d_in, r), ones_u, ones_v, s_out, s_in)
+    L = Layer(d_out, d_in, r, "f32", data=data)
+    for low in (128.0, 127.0, -129.0):
+        # x_0 = 2^22 - 2^16 pins the step at 1 (|q| <= 2^22); all others have the low byte at its extreme
+        row = np.full(d_in, low, dtype=np.float64)
+        row[0] = 2.0 ** 22 - 2.0 ** 16
+        # stage 2 quantises t (all components equal the sum of the row) with a power-of-two step
+        # chosen from |t|; one element is nudged so that t is a multiple of that step
+        t = row.sum()
+        step2 = max(1.0, 2.0 ** (np.frexp(abs(t))[1] - 22))
+        row[1] -= t % step2
+        assert np.frexp(abs(row.sum()))[1] == np.frexp(abs(t))[1] and row.sum() % step2 == 0
+        x = np.stack([row, -row]).astype(np.float32)
+        y = L.forward(x)
+        ref = L.oracle(x)
+        assert np.array_equal(y.astype(np.float64), ref), low
+    L.close()
+
+
 def test_closed_forms_on_gpu():
     d_out, d_in, r = 200, 333, 77
     ones_u = oracle.pack_signs(np.ones((d_out, r), dtype=np.int8))

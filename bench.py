@@ -41,6 +41,8 @@ def parse_args():
     ap.add_argument("--batch", type=int, default=1)
     ap.add_argument("--pool", type=int, default=1024, help="cfg2: number of distinct layer instances")
     ap.add_argument("--layers", type=int, default=0, help="cfg3/cfg4: decoder layers (0 = all)")
+    ap.add_argument("--y-dtype", default="f32", choices=["f32", "bf16", "f16"],
+                    help="output type of the layers (f32 is the parity-checked default of the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target oracle time for the cpu_baseline sample")
     ap.add_argument("--quick", action="store_true",
@@ -69,22 +71,22 @@ def build_workload(args):
     return name, out
 
 
-def algorithmic_bytes(shp, batch):
+def algorithmic_bytes(shp, batch, y_size=4):
     """Bytes the method itself must move for one forward of one layer."""
     bits = shp.r * (shp.d_in + shp.d_out) // 8
     scales = 2 * (shp.d_in + shp.d_out)
     x = batch * shp.d_in * 2
-    y = batch * shp.d_out * 4
+    y = batch * shp.d_out * y_size
     t = 2 * batch * shp.r * 4      # intermediate written by stage 1 and read back for stage 2
     return bits + scales, bits + scales + x + y + t
 
 
-def stage_bytes(shp, batch):
+def stage_bytes(shp, batch, y_size=4):
     """Algorithmic bytes of the two streaming launches for one layer:
     stage 1 reads the V bits and the 3-byte fixed-point x', writes t (fp32);
-    stage 2 reads the U bits, the 3-byte fixed-point t and s_out (fp16), writes y (fp32)."""
+    stage 2 reads the U bits, the 3-byte fixed-point t and s_out (fp16), writes y (y_size bytes each)."""
     s1 = shp.d_in * shp.r // 8 + 3 * batch * shp.d_in + 4 * batch * shp.r
-    s2 = shp.d_out * shp.r // 8 + 2 * shp.d_out + 3 * batch * shp.r + 4 * batch * shp.d_out
+    s2 = shp.d_out * shp.r // 8 + 2 * shp.d_out + 3 * batch * shp.r + y_size * batch * shp.d_out
     return s1, s2
 
 
@@ -226,12 +228,14 @@ def main():
     handles, xs, ys = [], [], []
     w_bytes = 0
     all_bytes = 0
+    y_torch = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[args.y_dtype]
+    y_size = 4 if args.y_dtype == "f32" else 2
     for shp, data, x in work:
         handles.append(nq.nq_binlr_create(shp.d_out, shp.d_in, shp.r, data.U_words, data.V_words, data.s_out,
-                                          data.s_in, nq.NQ_BF16))
+                                          data.s_in, nq.NQ_BF16, nq.DTYPE_BY_NAME[args.y_dtype]))
         xs.append(torch.from_numpy(x.view(np.int16).copy()).view(torch.bfloat16).cuda())
-        ys.append(torch.empty((batch, shp.d_out), dtype=torch.float32, device="cuda"))
-        wb, ab = algorithmic_bytes(shp, batch)
+        ys.append(torch.empty((batch, shp.d_out), dtype=y_torch, device="cuda"))
+        wb, ab = algorithmic_bytes(shp, batch, y_size)
         w_bytes += wb
         all_bytes += ab
     plan = nq.nq_plan_create(handles, xs, ys, batch)
@@ -257,8 +261,8 @@ def main():
         per_kernel += np.array(nq.nq_plan_forward_timed(plan))
     per_kernel /= reps
     # the two streaming launches; the slower one is the dominant kernel of the step
-    b1 = sum(stage_bytes(shp, batch)[0] for shp, _, _ in work)
-    b2 = sum(stage_bytes(shp, batch)[1] for shp, _, _ in work)
+    b1 = sum(stage_bytes(shp, batch, y_size)[0] for shp, _, _ in work)
+    b2 = sum(stage_bytes(shp, batch, y_size)[1] for shp, _, _ in work)
     stages = {"stage1": {"algorithmic_bytes": b1, "ms": per_kernel[1], "GBps": b1 / per_kernel[1] / 1e6},
               "stage2": {"algorithmic_bytes": b2, "ms": per_kernel[3], "GBps": b2 / per_kernel[3] / 1e6}}
     dom = "stage1" if per_kernel[1] >= per_kernel[3] else "stage2"
@@ -282,7 +286,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "int8 fixed-point (3 bytes/activation) x 1-bit signs, int32 accumulate; fp32 output",
+        "dtype": "int8 fixed-point (3 bytes/activation) x 1-bit signs, int32 accumulate; " + {"f32": "fp32", "bf16": "bf16", "f16": "fp16"}[args.y_dtype] + " output",
         "data": "synthetic",
         "config": {"workload": name, "layers_per_step": len(work), "batch": batch,
                    "weight_bytes_per_step": w_bytes, "algorithmic_bytes_per_step": all_bytes},

@@ -97,7 +97,10 @@ int nq_unpack_signs(const uint32_t* words, int64_t rows, int64_t cols, int8_t* o
 /* Build a layer on the current HIP device.
  * U_words: host, canonical [d_out, ceil(r/32)];  V_words: host, canonical [d_in, ceil(r/32)];
  * s_out_fp16: host, d_out IEEE binary16 values;  s_in_fp16: host, d_in values.
- * x_dtype: NQ_F32, NQ_F16 or NQ_BF16;  y_dtype: NQ_F32 (the only output type built).
+ * x_dtype: NQ_F32, NQ_F16 or NQ_BF16;  y_dtype: NQ_F32 (default of the build's parity bar),
+ * NQ_F16 or NQ_BF16: the fp32 result rounded once more, to nearest even (a value beyond the
+ * fp16 range becomes infinity, as in IEEE conversion; the paper does not state an output
+ * type, its models run in bf16/fp16).
  * Copies everything, rearranges the bits on the GPU, and synchronises the device.
  * Any r, d_in, d_out in [1, NQ_MAX_DIM] is accepted (tails are padded inside).
  * Workspace for batch <= NQ_DECODE_MAX_BATCH is allocated here. */
@@ -111,7 +114,7 @@ int nq_binlr_create(nq_handle* out, int64_t d_out, int64_t d_in, int64_t r,
 int nq_binlr_reserve(nq_handle h, int max_batch);
 
 /* y = s_out (.) (U (V^T (s_in (.) x))) for `batch` tokens (Eq. 1).
- * x: device, [batch, d_in] of x_dtype;  y: device, [batch, d_out] float32; both 16-byte
+ * x: device, [batch, d_in] of x_dtype;  y: device, [batch, d_out] of y_dtype; both 16-byte
  * aligned, must not overlap.  Asynchronous on `stream`.  Allocates nothing when
  * batch <= the reserved batch (otherwise it reserves first, which synchronises).
  * Not re-entrant on one handle (the handle's workspace is shared); different

@@ -151,3 +151,25 @@ def forward_factored(U_words, V_words, s_out, s_in, d_out, d_in, r, x, threads: 
 
 def layer_bits(d_out: int, d_in: int, r: int) -> int:
     return int(_load().nqo_layer_bits(d_out, d_in, r))
+
+
+def round_output(y: np.ndarray, dtype: str) -> np.ndarray:
+    """The values an output of type ``dtype`` ("f32", "f16", "bf16") holds for the fp64 results ``y``:
+    rounded to fp32 first (the path's native result type), then, for the 16-bit types, once more to
+    nearest even (IEEE conversion: overflow gives infinity).  Returned as fp64.  The paper states no
+    output type (Appendix D speaks of fp16 / bf16 activations); this is the reading the tests check."""
+    y32 = np.asarray(y, dtype=np.float64).astype(np.float32)
+    if dtype == "f32":
+        return y32.astype(np.float64)
+    if dtype == "f16":
+        with np.errstate(over="ignore"):
+            return y32.astype(np.float16).astype(np.float64)
+    if dtype == "bf16":
+        bits = y32.view(np.uint32).astype(np.uint64)
+        nan = np.isnan(y32)
+        rounded = ((bits + 0x7FFF + ((bits >> 16) & 1)) & 0xFFFF0000).astype(np.uint32)
+        out = rounded.view(np.float32).astype(np.float64)
+        out[nan] = np.nan
+        return out
+    raise ValueError(f"unknown output type {dtype!r}")
+

@@ -266,9 +266,8 @@ extern "C" int nq_binlr_create(nq_handle* out, int64_t d_out, int64_t d_in, int6
     if (!U_words || !V_words || !s_out_fp16 || !s_in_fp16) return fail(NQ_E_NULL, "nq_binlr_create: NULL input");
     if (x_dtype != NQ_F32 && x_dtype != NQ_F16 && x_dtype != NQ_BF16)
         return fail(NQ_E_INVALID_ARG, "nq_binlr_create: x_dtype must be NQ_F32, NQ_F16 or NQ_BF16");
-    if (y_dtype == NQ_F16 || y_dtype == NQ_BF16)
-        return fail(NQ_E_UNSUPPORTED, "nq_binlr_create: only NQ_F32 output is built");
-    if (y_dtype != NQ_F32) return fail(NQ_E_INVALID_ARG, "nq_binlr_create: bad y_dtype");
+    if (y_dtype != NQ_F32 && y_dtype != NQ_F16 && y_dtype != NQ_BF16)
+        return fail(NQ_E_INVALID_ARG, "nq_binlr_create: y_dtype must be NQ_F32, NQ_F16 or NQ_BF16");
     if (flags & ~(NQ_FLAG_DECODE_VALU | NQ_FLAG_NO_PREFILL)) return fail(NQ_E_INVALID_ARG, "nq_binlr_create: unknown flag");
 
     nq_handle h = new (std::nothrow) nq_binlr_s();
@@ -403,7 +402,7 @@ static StageDesc make_s1(nq_handle h)
 {
     StageDesc s;
     s.tiles = h->vt_tiles; s.bq = h->bq_x; s.meta = h->meta_x; s.out_scale = nullptr; s.out = h->t;
-    s.M = (int)h->r; s.n_steps = (int)n_steps(h->d_in); s.out_stride = h->t_stride; s.reserved = 0;
+    s.M = (int)h->r; s.n_steps = (int)n_steps(h->d_in); s.out_stride = h->t_stride; s.out_dtype = NQ_F32;
     return s;
 }
 static QuantDesc make_qt(nq_handle h)
@@ -416,8 +415,8 @@ static QuantDesc make_qt(nq_handle h)
 static StageDesc make_s2(nq_handle h, void* y)
 {
     StageDesc s;
-    s.tiles = h->u_tiles; s.bq = h->bq_t; s.meta = h->meta_t; s.out_scale = h->s_out; s.out = (float*)y;
-    s.M = (int)h->d_out; s.n_steps = (int)n_steps(h->r); s.out_stride = (int)h->d_out; s.reserved = 0;
+    s.tiles = h->u_tiles; s.bq = h->bq_t; s.meta = h->meta_t; s.out_scale = h->s_out; s.out = y;
+    s.M = (int)h->d_out; s.n_steps = (int)n_steps(h->r); s.out_stride = (int)h->d_out; s.out_dtype = h->y_dtype;
     return s;
 }
 
@@ -438,11 +437,11 @@ static int decode_once(nq_handle h, const void* x, void* y, int batch, hipStream
 {
     int rc;
     if (h->flags & NQ_FLAG_DECODE_VALU) {
-        rc = launch_valu_gemv(h->vt_tiles, x, h->x_dtype, (int)h->d_in, h->s_in, nullptr, h->t, h->t_stride, h->r,
-                              h->d_in, batch, s);
+        rc = launch_valu_gemv(h->vt_tiles, x, h->x_dtype, (int)h->d_in, h->s_in, nullptr, h->t, NQ_F32, h->t_stride,
+                              h->r, h->d_in, batch, s);
         if (rc != NQ_OK) return rc;
-        return launch_valu_gemv(h->u_tiles, h->t, NQ_F32, h->t_stride, nullptr, h->s_out, (float*)y, (int)h->d_out,
-                                h->d_out, h->r, batch, s);
+        return launch_valu_gemv(h->u_tiles, h->t, NQ_F32, h->t_stride, nullptr, h->s_out, y, h->y_dtype,
+                                (int)h->d_out, h->d_out, h->r, batch, s);
     }
     QuantDesc qx = make_qx(h, x);
     StageDesc s1 = make_s1(h);
@@ -473,7 +472,8 @@ extern "C" int nq_binlr_forward(nq_handle h, const void* x, void* y, int batch, 
     if (!h) return fail(NQ_E_NULL, "nq_binlr_forward: NULL handle");
     if (batch < 1) return fail(NQ_E_INVALID_ARG, "nq_binlr_forward: batch must be >= 1");
     const size_t xs = dtype_size(h->x_dtype);
-    int rc = check_xy("nq_binlr_forward", x, y, (size_t)batch * h->d_in * xs, (size_t)batch * h->d_out * 4);
+    const size_t ys = dtype_size(h->y_dtype);
+    int rc = check_xy("nq_binlr_forward", x, y, (size_t)batch * h->d_in * xs, (size_t)batch * h->d_out * ys);
     if (rc != NQ_OK) return rc;
     hipStream_t s = (hipStream_t)stream;
     if (batch <= NQ_DECODE_MAX_BATCH) return decode_once(h, x, y, batch, s);
@@ -481,14 +481,14 @@ extern "C" int nq_binlr_forward(nq_handle h, const void* x, void* y, int batch, 
         if ((rc = ensure_prefill_workspace(h, batch)) != NQ_OK) return rc;
         PrefillArgs a;
         a.vt_tiles = h->vt_tiles; a.u_tiles = h->u_tiles; a.s_in = h->s_in; a.s_out = h->s_out;
-        a.x = x; a.y = (float*)y; a.workspace = h->pf_alloc;
-        a.d_out = h->d_out; a.d_in = h->d_in; a.r = h->r; a.batch = batch; a.x_dtype = h->x_dtype;
+        a.x = x; a.y = y; a.workspace = h->pf_alloc;
+        a.d_out = h->d_out; a.d_in = h->d_in; a.r = h->r; a.batch = batch; a.x_dtype = h->x_dtype; a.y_dtype = h->y_dtype;
         return launch_prefill(a, s);
     }
     // mid-size batches: chunks of 8 through the streaming path (each chunk re-reads the bits)
     for (int b0 = 0; b0 < batch; b0 += NQ_DECODE_MAX_BATCH) {
         int nb = std::min(NQ_DECODE_MAX_BATCH, batch - b0);
-        rc = decode_once(h, (const char*)x + (size_t)b0 * h->d_in * xs, (char*)y + (size_t)b0 * h->d_out * 4, nb, s);
+        rc = decode_once(h, (const char*)x + (size_t)b0 * h->d_in * xs, (char*)y + (size_t)b0 * h->d_out * ys, nb, s);
         if (rc != NQ_OK) return rc;
     }
     return NQ_OK;
@@ -565,7 +565,7 @@ extern "C" int nq_plan_create(nq_plan* out, const nq_handle* hs, const void* con
         if (hs[i]->flags & NQ_FLAG_DECODE_VALU) return fail(NQ_E_UNSUPPORTED, "nq_plan_create: handle uses NQ_FLAG_DECODE_VALU");
         if (hs[i]->device != hs[0]->device) return fail(NQ_E_INVALID_ARG, "nq_plan_create: handles live on different devices");
         int rc = check_xy("nq_plan_create", xs[i], ys[i], (size_t)batch * hs[i]->d_in * dtype_size(hs[i]->x_dtype),
-                          (size_t)batch * hs[i]->d_out * 4);
+                          (size_t)batch * hs[i]->d_out * dtype_size(hs[i]->y_dtype));
         if (rc != NQ_OK) return rc;
     }
     std::sort(sorted.begin(), sorted.end());

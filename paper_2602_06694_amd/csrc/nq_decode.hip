@@ -325,7 +325,6 @@ typedef const __attribute__((address_space(1))) v4u* gptr_v4u;    // global (not
 // wait a "wait for everything".  These casts name the address space: global for vector accesses,
 // constant for wave-uniform reads (scalar loads, which the vector-memory counter does not see).
 typedef const __attribute__((address_space(1))) uint16_t* gptr_u16;
-typedef __attribute__((address_space(1))) float* gptr_f32;
 typedef const __attribute__((address_space(4))) QMeta* cptr_meta;
 
 // sign tiles are streamed once, never reused: keep them from displacing the (reused) activations
@@ -366,8 +365,8 @@ __device__ __forceinline__ void mac_tile(v4i (&acc)[NB][8], const v4u w, const v
 struct EpilogueArgs {
     const QMeta* meta;
     const uint16_t* out_scale;
-    float* out;
-    int M, out_stride;
+    void* out;
+    int M, out_stride, out_dtype;
 };
 
 // LDS ints one wave needs for the epilogue: 16 columns x 64 rows
@@ -449,7 +448,7 @@ __device__ __forceinline__ void stage_epilogue(const v4i (&acc)[NB][8], int* lds
                     lds_out[tok * kTileRows + r128] = (float)val;       // scaled by s_out when flushed
                 } else if (grow < e.M) {
                     val *= (double)oscale;
-                    ((gptr_f32)e.out)[(size_t)tok * e.out_stride + grow] = (float)val;
+                    store_out(e.out, e.out_dtype, (size_t)tok * e.out_stride + grow, (float)val);
                 }
             }
             if (W == 1) {
@@ -494,13 +493,20 @@ __device__ __forceinline__ void stream_flush(int* lds, const float* lds_out, int
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    for (int o = lane; o < n_rb * kTileRows * batch; o += 64) {
-        const int u = o / (kTileRows * batch), rem = o - u * (kTileRows * batch);
-        const int tok = rem >> 7, row = rem & (kTileRows - 1);
-        const int grow = (rb0 + u) * kTileRows + row;
-        if (grow < ea.M)
-            ((gptr_f32)ea.out)[(size_t)tok * ea.out_stride + grow] = lds_out[o] * lds_sc[u * kTileRows + row];
-    }
+    // one loop per output type: the type is the same for the whole item
+    auto store_all = [&](auto store) {
+        for (int o = lane; o < n_rb * kTileRows * batch; o += 64) {
+            const int u = o / (kTileRows * batch), rem = o - u * (kTileRows * batch);
+            const int tok = rem >> 7, row = rem & (kTileRows - 1);
+            const int grow = (rb0 + u) * kTileRows + row;
+            if (grow < ea.M) store((size_t)tok * ea.out_stride + grow, lds_out[o] * lds_sc[u * kTileRows + row]);
+        }
+    };
+    typedef __attribute__((address_space(1))) float* gptr_f32;
+    typedef __attribute__((address_space(1))) uint16_t* gptr_o16;
+    if (ea.out_dtype == NQ_F32) store_all([&](size_t i, float v) { ((gptr_f32)ea.out)[i] = v; });
+    else if (ea.out_dtype == NQ_BF16) store_all([&](size_t i, float v) { ((gptr_o16)ea.out)[i] = float_to_bf16_bits(v); });
+    else store_all([&](size_t i, float v) { ((gptr_o16)ea.out)[i] = float_to_f16_bits(v); });
 }
 
 #define NQ_LOAD_ITEM()                                                                             \
@@ -513,7 +519,7 @@ __device__ __forceinline__ void stream_flush(int* lds, const float* lds_out, int
         tiles = e->tiles; bq = e->bq; nst = e->n_steps; rb0 = e->rb; n_rb = e->n_rb;               \
         const StageDesc* dp = descs + e->op;                                                       \
         ea.meta = dp->meta; ea.out_scale = dp->out_scale; ea.out = dp->out;                        \
-        ea.M = dp->M; ea.out_stride = dp->out_stride;                                              \
+        ea.M = dp->M; ea.out_stride = dp->out_stride; ea.out_dtype = dp->out_dtype;                \
     } else {                                                                                       \
         nst = single.n_steps;                                                                      \
         rb0 = it * rbs_per_item;                                                                   \
@@ -522,7 +528,7 @@ __device__ __forceinline__ void stream_flush(int* lds, const float* lds_out, int
         tiles = single.tiles + (size_t)rb0 * nst * kTileWords;                                     \
         bq = single.bq;                                                                            \
         ea.meta = single.meta; ea.out_scale = single.out_scale; ea.out = single.out;               \
-        ea.M = single.M; ea.out_stride = single.out_stride;                                        \
+        ea.M = single.M; ea.out_stride = single.out_stride; ea.out_dtype = single.out_dtype;       \
     }
 
 template <int NB, int D>
@@ -769,7 +775,7 @@ stage_shared_kernel(const StageDesc* __restrict__ descs, const WorkItem* __restr
         const StageDesc* dp = descs + e->op;
         EpilogueArgs ea;
         ea.meta = dp->meta; ea.out_scale = dp->out_scale; ea.out = dp->out;
-        ea.M = dp->M; ea.out_stride = dp->out_stride;
+        ea.M = dp->M; ea.out_stride = dp->out_stride; ea.out_dtype = dp->out_dtype;
         const int per = (n_rb + W - 1) / W;
         const int my0 = wave * per;
         const int my_n = n_rb - my0 < per ? (n_rb - my0 > 0 ? n_rb - my0 : 0) : per;
@@ -1027,7 +1033,7 @@ int launch_stage(const StageDesc* d_descs, const StageDesc& single, const WorkIt
 __global__ void __launch_bounds__(128)
 valu_gemv_kernel(const uint32_t* __restrict__ tiles, const void* __restrict__ x, int x_dtype, int x_stride,
                  const uint16_t* __restrict__ in_scale, const uint16_t* __restrict__ out_scale,
-                 float* __restrict__ out, int out_stride, int64_t M, int64_t N, int64_t nsteps)
+                 void* __restrict__ out, int out_dtype, int out_stride, int64_t M, int64_t N, int64_t nsteps)
 {
     const int rr = threadIdx.x;                     // row inside the block
     const int64_t rb = blockIdx.x, tok = blockIdx.y;
@@ -1051,16 +1057,16 @@ valu_gemv_kernel(const uint32_t* __restrict__ tiles, const void* __restrict__ x,
     }
     if (row < M) {
         if (out_scale) acc *= half_bits_to_float(out_scale[row]);
-        out[(size_t)tok * out_stride + row] = acc;
+        store_out(out, out_dtype, (size_t)tok * out_stride + row, acc);
     }
 }
 
 int launch_valu_gemv(const uint32_t* tiles, const void* x, int x_dtype, int x_stride, const uint16_t* in_scale,
-                     const uint16_t* out_scale, float* out, int out_stride, int64_t M, int64_t N, int batch,
+                     const uint16_t* out_scale, void* out, int out_dtype, int out_stride, int64_t M, int64_t N, int batch,
                      hipStream_t s)
 {
     hipLaunchKernelGGL(valu_gemv_kernel, dim3((unsigned)n_rowblocks(M), batch), dim3(128), 0, s, tiles, x, x_dtype,
-                       x_stride, in_scale, out_scale, out, out_stride, M, N, n_steps(N));
+                       x_stride, in_scale, out_scale, out, out_dtype, out_stride, M, N, n_steps(N));
     NQ_HIP(hipGetLastError());
     return NQ_OK;
 }

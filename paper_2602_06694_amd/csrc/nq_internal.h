@@ -51,11 +51,11 @@ struct StageDesc {
     const uint8_t* bq;           // quantised input of this stage
     const QMeta* meta;
     const uint16_t* out_scale;   // fp16 [M] or nullptr
-    float* out;                  // [batch][out_stride]
+    void* out;                   // [batch][out_stride] elements of out_dtype
     int M;                       // real rows
     int n_steps;                 // 64-column steps
     int out_stride;
-    int reserved;
+    int out_dtype;               // NQ_F32 (t, and y by default), NQ_F16 or NQ_BF16 (y)
 };
 
 // One unit of streaming work: a run of 128-row blocks of one op, each over its whole reduction length.
@@ -85,6 +85,30 @@ int hip_fail(hipError_t e, const char* what, const char* file, int line);
         if (e__ != hipSuccess) return ::nq::hip_fail(e__, #call, __FILE__, __LINE__); \
     } while (0)
 
+// ---- output conversion (device code) ---------------------------------------------------------
+#if defined(__HIPCC__)
+// fp32 -> bf16 bits, round to nearest even; NaN stays NaN (quiet)
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f)
+{
+    uint32_t u = __builtin_bit_cast(uint32_t, f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+// fp32 -> fp16 bits, round to nearest even (overflow gives infinity, as IEEE conversion does)
+__device__ __forceinline__ uint16_t float_to_f16_bits(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }
+__device__ __forceinline__ uint16_t float_to_out16(float f, int dtype)
+{
+    return dtype == NQ_BF16 ? float_to_bf16_bits(f) : float_to_f16_bits(f);
+}
+// element `idx` of an output array of type `dtype` in global memory
+__device__ __forceinline__ void store_out(void* base, int dtype, size_t idx, float v)
+{
+    if (dtype == NQ_F32) ((__attribute__((address_space(1))) float*)base)[idx] = v;
+    else ((__attribute__((address_space(1))) uint16_t*)base)[idx] = float_to_out16(v, dtype);
+}
+#endif
+
 // ---- launchers (nq_decode.hip) -------------------------------------------------------------
 int launch_repack(const uint32_t* d_canon, int64_t wpr, bool transposed, int64_t M, int64_t N,
                   uint32_t* d_tiles, hipStream_t s);
@@ -95,16 +119,16 @@ int launch_quantize(const QuantDesc* d_descs, const QuantDesc& single, int n_ops
                     hipStream_t s);
 int stage_schedule(int n_rb_total, int mean_steps, int batch);
 int stream_target_steps();
-int stream_max_rbs(int batch);
-constexpr int kSharedSchedule = 8;     // stage_schedule()'s value for the workgroup-shared-input kernel
-int shared_per_wave(int nst, int batch);
-int shared_per_wave(int nst, int batch);   // row blocks one stream item may chain (bounded by its LDS output buffer)
-// w = 1: stream kernel (items are runs of rbs_per_item row blocks); w = 4 / 16: split kernel (one row block per item)
+int stream_max_rbs(int batch);           // row blocks one stream item may chain (bounded by its LDS output buffer)
+constexpr int kSharedSchedule = 8;       // stage_schedule()'s value for the workgroup-shared-input kernel
+int shared_per_wave(int nst, int batch); // row blocks per wave of an item of that kernel
+// w = 1: stream kernel (items are runs of rbs_per_item row blocks); w = 4 / 16: split kernel (one row block
+// per item); w = kSharedSchedule: shared-input kernel (items of up to 8 x shared_per_wave row blocks)
 int launch_stage(const StageDesc* d_descs, const StageDesc& single, const WorkItem* d_items, int n_items,
                  int w, int rbs_per_item, int batch, hipStream_t s);
 int launch_valu_gemv(const uint32_t* tiles, const void* x, int x_dtype, int x_stride, const uint16_t* in_scale,
-                     const uint16_t* out_scale, float* out, int out_stride, int64_t M, int64_t N, int batch,
-                     hipStream_t s);
+                     const uint16_t* out_scale, void* out, int out_dtype, int out_stride, int64_t M, int64_t N,
+                     int batch, hipStream_t s);
 int device_cu_count();
 
 // ---- launchers (nq_prefill.hip) ------------------------------------------------------------
@@ -114,11 +138,11 @@ struct PrefillArgs {
     const uint16_t* s_in;
     const uint16_t* s_out;
     const void* x;
-    float* y;
+    void* y;
     void* workspace;            // device, prefill_workspace_bytes()
     int64_t d_out, d_in, r;
     int batch;
-    int x_dtype;
+    int x_dtype, y_dtype;
 };
 size_t prefill_workspace_bytes(int64_t d_out, int64_t d_in, int64_t r, int batch);
 int launch_prefill(const PrefillArgs& a, hipStream_t s);

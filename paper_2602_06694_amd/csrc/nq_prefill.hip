@@ -45,7 +45,8 @@ struct GemmArgs {
     const uint32_t* tiles;     // sign tiles of the weight: rows = outputs, columns = reduction
     float* partial;            // EPI_PARTIAL: [splits][m_pad][n_pad] raw accumulators
     _Float16* t_out;           // EPI_T: [m_pad][ldt]
-    float* y_out;              // EPI_Y: [batch][n_real]
+    void* y_out;               // EPI_Y: [batch][n_real] elements of y_dtype
+    int y_dtype;
     const float* tok_scale;    // EPI_Y: per token 1 / (2^a_b * g)
     const uint16_t* out_scale; // EPI_Y: fp16 [n_real]
     float t_scale;             // EPI_T: g
@@ -382,9 +383,9 @@ prefill_gemm_kernel(GemmArgs a)
             } else {
                 if (tok < a.batch) {
                     const float f = -a.tok_scale[tok];
-                    float* dst = a.y_out + (size_t)tok * a.n_real + n0;
+                    const size_t at = (size_t)tok * a.n_real + n0;
                     const float cv[4] = {c.x, c.y, c.z, c.w};
-                    if ((a.n_real & 3) == 0) {             // rows are 16-byte aligned: one store per lane
+                    if ((a.n_real & 3) == 0) {             // rows stay aligned: one store per lane
                         if (n0 < a.n_real) {
                             const uint2 sc = *(const uint2*)(a.out_scale + n0);
                             v4f o;
@@ -392,12 +393,19 @@ prefill_gemm_kernel(GemmArgs a)
                             o.y = cv[1] * f * h2f((uint16_t)(sc.x >> 16));
                             o.z = cv[2] * f * h2f((uint16_t)(sc.y & 0xFFFFu));
                             o.w = cv[3] * f * h2f((uint16_t)(sc.y >> 16));
-                            *(v4f*)dst = o;
+                            if (a.y_dtype == NQ_F32) {
+                                *(v4f*)((float*)a.y_out + at) = o;
+                            } else {
+                                uint2 pk;
+                                pk.x = (uint32_t)float_to_out16(o.x, a.y_dtype) | ((uint32_t)float_to_out16(o.y, a.y_dtype) << 16);
+                                pk.y = (uint32_t)float_to_out16(o.z, a.y_dtype) | ((uint32_t)float_to_out16(o.w, a.y_dtype) << 16);
+                                *(uint2*)((uint16_t*)a.y_out + at) = pk;
+                            }
                         }
                     } else {
 #pragma unroll
                         for (int v = 0; v < 4; ++v)
-                            if (n0 + v < a.n_real) dst[v] = cv[v] * f * h2f(a.out_scale[n0 + v]);
+                            if (n0 + v < a.n_real) store_out(a.y_out, a.y_dtype, at + v, cv[v] * f * h2f(a.out_scale[n0 + v]));
                     }
                 }
             }
@@ -430,7 +438,8 @@ prefill_finalize_kernel(GemmArgs a)
             const float f = -a.tok_scale[tok];
             const float cv[4] = {c.x, c.y, c.z, c.w};
             for (int v = 0; v < 4; ++v)
-                if (n0 + v < a.n_real) a.y_out[(size_t)tok * a.n_real + n0 + v] = cv[v] * f * h2f(a.out_scale[n0 + v]);
+                if (n0 + v < a.n_real)
+                    store_out(a.y_out, a.y_dtype, (size_t)tok * a.n_real + n0 + v, cv[v] * f * h2f(a.out_scale[n0 + v]));
         }
     }
 }
@@ -571,7 +580,7 @@ int launch_prefill(const PrefillArgs& p, hipStream_t s)
     }
     // gemm2: y = T U^T
     a.act = t; a.lda = L.k2; a.tiles = p.u_tiles;
-    a.y_out = p.y; a.tok_scale = tok_scale; a.out_scale = p.s_out;
+    a.y_out = p.y; a.y_dtype = p.y_dtype; a.tok_scale = tok_scale; a.out_scale = p.s_out;
     a.n_real = (int)p.d_out; a.n_rb = (int)n_rowblocks(p.d_out); a.nst = (int)n_steps(p.r);
     a.n_tiles = (a.n_rb + kPfWaves - 1) / kPfWaves;
     a.splits = L.splits2; a.steps_per_split = even_steps_per_split(a.nst, a.splits);

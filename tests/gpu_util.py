@@ -21,18 +21,49 @@ def to_device(x: np.ndarray, dtype: str):
     return torch.from_numpy(np.ascontiguousarray(x)).cuda()
 
 
+def new_output(batch: int, d_out: int, y_dtype: str = "f32"):
+    """A NaN-filled device array for y."""
+    import torch
+    tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[y_dtype]
+    return torch.full((batch, d_out), float("nan"), dtype=tdt, device="cuda")
+
+
+def output_to_numpy(y) -> np.ndarray:
+    """Device output -> numpy (fp32 stays fp32; the 16-bit types are widened exactly to fp64)."""
+    import torch
+    if y.dtype == torch.float32:
+        return y.cpu().numpy()
+    return y.cpu().to(torch.float64).numpy()
+
+
+def check_rounded(y: np.ndarray, ref: np.ndarray, y_dtype: str, tol: float) -> None:
+    """A 16-bit output against the fp64 oracle: the path's own tolerance plus one unit in the last
+    place of the output type at each element (the result is rounded once more than the fp32 one)."""
+    ulp = {"bf16": 2.0 ** -8, "f16": 2.0 ** -10}[y_dtype]
+    lim = 65504.0 if y_dtype == "f16" else np.inf
+    inside = np.abs(ref) < lim * (1 - 2.0 ** -11)
+    assert np.isfinite(y[inside]).all(), "non-finite output"
+    bound = tol * np.abs(ref).max() + ulp * np.abs(ref) + (2.0 ** -24 if y_dtype == "f16" else 0.0)
+    bad = np.abs(y - ref)[inside] > bound[inside]
+    assert not bad.any(), float((np.abs(y - ref)[inside] / bound[inside]).max())
+    # beyond the fp16 range the conversion gives infinity of the right sign (or the largest value, within rounding of the edge)
+    over = np.abs(ref) > lim * (1 + 2.0 ** -10)
+    assert np.all(np.isinf(y[over]) & (np.sign(y[over]) == np.sign(ref[over])))
+
+
 class Layer:
     """A synthetic layer resident on the GPU plus everything the oracle needs."""
 
-    def __init__(self, d_out, d_in, r, x_dtype="bf16", seed=0, flags=0, data: synth.LayerData | None = None):
-        self.d_out, self.d_in, self.r, self.x_dtype = d_out, d_in, r, x_dtype
+    def __init__(self, d_out, d_in, r, x_dtype="bf16", seed=0, flags=0, data: synth.LayerData | None = None,
+                 y_dtype="f32"):
+        self.d_out, self.d_in, self.r, self.x_dtype, self.y_dtype = d_out, d_in, r, x_dtype, y_dtype
         if data is None:
             shp = synth.LinearShape("t", d_out, d_in, r)
             data = synth.LayerData(shp, synth.gen_sign_words(d_out, r, seed + 1), synth.gen_sign_words(d_in, r, seed + 2),
                                    synth.gen_scales(d_out, seed + 3), synth.gen_scales(d_in, seed + 4))
         self.data = data
         self.h = nq.nq_binlr_create(d_out, d_in, r, data.U_words, data.V_words, data.s_out, data.s_in,
-                                    nq.DTYPE_BY_NAME[x_dtype], nq.NQ_F32, flags)
+                                    nq.DTYPE_BY_NAME[x_dtype], nq.DTYPE_BY_NAME[y_dtype], flags)
 
     def close(self):
         if self.h:
@@ -49,10 +80,10 @@ class Layer:
         import torch
         batch = x_np.shape[0]
         x = to_device(x_np, self.x_dtype)
-        y = torch.full((batch, self.d_out), float("nan"), dtype=torch.float32, device="cuda")
+        y = new_output(batch, self.d_out, self.y_dtype)
         nq.nq_binlr_forward(self.h, x, y, batch)
         torch.cuda.synchronize()
-        return y.cpu().numpy()
+        return output_to_numpy(y)
 
     def oracle(self, x_np: np.ndarray, threads=0, return_t=False):
         d = self.data

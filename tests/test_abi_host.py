@@ -94,7 +94,7 @@ def test_argument_validation_needs_no_gpu():
     assert L.nq_binlr_create(ctypes.byref(h), 4, 4, nq.NQ_MAX_DIM + 1, p(w), p(w), p(s), p(s), nq.NQ_F32, nq.NQ_F32, 0) == nq.NQ_E_SHAPE
     assert L.nq_binlr_create(ctypes.byref(h), 4, 4, 4, None, p(w), p(s), p(s), nq.NQ_F32, nq.NQ_F32, 0) == nq.NQ_E_NULL
     assert L.nq_binlr_create(ctypes.byref(h), 4, 4, 4, p(w), p(w), p(s), p(s), nq.NQ_I8, nq.NQ_F32, 0) == nq.NQ_E_INVALID_ARG
-    assert L.nq_binlr_create(ctypes.byref(h), 4, 4, 4, p(w), p(w), p(s), p(s), nq.NQ_F32, nq.NQ_BF16, 0) == nq.NQ_E_UNSUPPORTED
+    assert L.nq_binlr_create(ctypes.byref(h), 4, 4, 4, p(w), p(w), p(s), p(s), nq.NQ_F32, nq.NQ_I8, 0) == nq.NQ_E_INVALID_ARG
     assert L.nq_binlr_create(ctypes.byref(h), 4, 4, 4, p(w), p(w), p(s), p(s), nq.NQ_F32, nq.NQ_F32, 64) == nq.NQ_E_INVALID_ARG
     assert h.value is None
     assert L.nq_binlr_forward(None, None, None, 1, None) == nq.NQ_E_NULL

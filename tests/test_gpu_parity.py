@@ -7,7 +7,7 @@ import pytest
 import oracle
 from paper_2602_06694_amd import binding as nq
 from paper_2602_06694_amd import synth
-from gpu_util import BAR, DECODE_TOL, Layer, rel_err, to_device
+from gpu_util import BAR, DECODE_TOL, Layer, check_rounded, new_output, output_to_numpy, rel_err, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -310,6 +310,76 @@ def test_shared_input_schedule_batches_6_to_8(monkeypatch):
                 assert rel_err(y.cpu().numpy(), L.oracle(x)) <= DECODE_TOL, (batch, rep, L.d_out, L.d_in, L.r)
         nq.nq_plan_destroy(plan)
     for L in layers:
+        L.close()
+
+
+@pytest.mark.parametrize("y_dtype", ["bf16", "f16"])
+def test_sixteen_bit_outputs_every_path(y_dtype, monkeypatch):
+    """y as bf16 / fp16 (the fp32 result rounded once more) through every kernel that stores y:
+    split and stream kernels (single call and plan), the shared-input kernel, chunked mid batches,
+    the plain VALU kernels, and the dense path (both its direct and its split-reduction epilogue)."""
+    import torch
+    from test_gpu_prefill import PREFILL_TOL
+    shape = (777, 520, 200)
+    L = Layer(*shape, "bf16", seed=500, y_dtype=y_dtype)
+    for batch in (1, 3, 5, 6, 8, 20):
+        x = synth.gen_x(batch, shape[1], 510 + batch, "bf16")
+        check_rounded(L.forward(x), L.oracle(x), y_dtype, DECODE_TOL)
+    for batch in (64, 130):
+        x = synth.gen_x(batch, shape[1], 520 + batch, "bf16")
+        check_rounded(L.forward(x), L.oracle(x), y_dtype, PREFILL_TOL)
+    L.close()
+    # a narrow output (d_out = 96) makes the dense path split its second reduction
+    Ln = Layer(96, 2048, 1024, "bf16", seed=530, y_dtype=y_dtype)
+    x = synth.gen_x(64, 2048, 531, "bf16")
+    check_rounded(Ln.forward(x), Ln.oracle(x), y_dtype, PREFILL_TOL)
+    Ln.close()
+    Lv = Layer(*shape, "f32", seed=540, y_dtype=y_dtype, flags=nq.NQ_FLAG_DECODE_VALU)
+    x = synth.gen_x(2, shape[1], 541, "f32")
+    check_rounded(Lv.forward(x), Lv.oracle(x), y_dtype, 1e-4)
+    Lv.close()
+    # plans: stream / split schedules, then the large-launch schedules forced onto small inputs
+    shapes = [(300, 200, 100), (512, 1024, 256), (2200, 1536, 1100), (64, 4100, 70)]
+    layers = [Layer(*s, "bf16", seed=550 + i, y_dtype=y_dtype) for i, s in enumerate(shapes)]
+    hs = [l.h for l in layers]
+    for forced in (False, True):
+        if forced:
+            monkeypatch.setenv("NQ_SCHEDULE_FULL", "1")
+            monkeypatch.setenv("NQ_SHARE_STEPS", "1")
+        for batch in (1, 4, 8):
+            xs_np = [synth.gen_x(batch, s[1], 560 + i, "bf16") for i, s in enumerate(shapes)]
+            xs = [to_device(x, "bf16") for x in xs_np]
+            ys = [new_output(batch, s[0], y_dtype) for s in shapes]
+            plan = nq.nq_plan_create(hs, xs, ys, batch)
+            nq.nq_plan_forward(plan)
+            torch.cuda.synchronize()
+            for l, x, y in zip(layers, xs_np, ys):
+                check_rounded(output_to_numpy(y), l.oracle(x), y_dtype, DECODE_TOL)
+            nq.nq_plan_destroy(plan)
+    for l in layers:
+        l.close()
+
+
+def test_sixteen_bit_outputs_are_the_rounded_exact_result():
+    # integer-exact inputs (power-of-two scales, small integers): the fp32 result is exact, so the
+    # 16-bit output must be bit for bit the oracle's result rounded to that type; and fp16 saturates
+    # to infinity where the result leaves its range
+    d_out, d_in, r = 384, 520, 200
+    rng = np.random.default_rng(8)
+    U = synth.gen_sign_words(d_out, r, 81)
+    V = synth.gen_sign_words(d_in, r, 82)
+    s_out = (2.0 ** rng.integers(-3, 4, d_out)).astype(np.float16)
+    s_in = (2.0 ** rng.integers(-3, 4, d_in)).astype(np.float16)
+    data = synth.LayerData(synth.LinearShape("e", d_out, d_in, r), U, V, s_out, s_in)
+    for y_dtype in ("bf16", "f16"):
+        L = Layer(d_out, d_in, r, "f32", data=data, y_dtype=y_dtype)
+        for batch, amp in ((1, 8), (7, 8), (8, 64)):
+            x = rng.integers(-amp, amp + 1, (batch, d_in)).astype(np.float32)
+            y = L.forward(x)
+            want = oracle.round_output(L.oracle(x), y_dtype)
+            if amp == 64 and y_dtype == "f16":
+                assert np.isinf(want).any()          # the case does leave the fp16 range
+            assert np.array_equal(y, want), (y_dtype, batch, amp)
         L.close()
 
 

@@ -303,3 +303,32 @@ def test_config_bpw_values():
               (8192, 8192, 2240): 0.5508, (28672, 8192, 3520): 0.5550}
     for (n, m, r), bpw in expect.items():
         assert abs(oracle.layer_bits(n, m, r) / (n * m) - bpw) < 5e-5
+
+
+def test_output_rounding_pins():
+    # values fixed by the two 16-bit formats themselves: ties go to the even significand,
+    # fp16 overflows to infinity from 65520 on, bf16 keeps the fp32 range
+    r = oracle.round_output
+    one = 1.0
+    assert r(np.array([one + 2.0**-8]), "bf16")[0] == 1.0                       # tie -> even (1.0)
+    assert r(np.array([one + 2.0**-8 + 2.0**-20]), "bf16")[0] == one + 2.0**-7   # just above the tie
+    assert r(np.array([one + 3 * 2.0**-8]), "bf16")[0] == one + 2.0**-6          # tie -> even (1 + 2^-6)
+    assert r(np.array([-(one + 2.0**-7)]), "bf16")[0] == -(one + 2.0**-7)        # representable
+    assert np.isfinite(r(np.array([3.0e38]), "bf16")[0])
+    assert r(np.array([one + 2.0**-11]), "f16")[0] == 1.0                        # tie -> even
+    assert r(np.array([one + 3 * 2.0**-11]), "f16")[0] == one + 2.0**-9
+    assert r(np.array([65504.0]), "f16")[0] == 65504.0
+    assert r(np.array([65519.0]), "f16")[0] == 65504.0
+    assert np.isinf(r(np.array([65520.0]), "f16")[0])                            # tie -> even = infinity
+    assert r(np.array([2.0**-24]), "f16")[0] == 2.0**-24                         # smallest subnormal
+    assert r(np.array([2.0**-25]), "f16")[0] == 0.0                              # tie -> even (zero)
+    assert r(np.array([0.1]), "f32")[0] == float(np.float32(0.1))
+    assert np.isnan(r(np.array([np.nan]), "bf16")[0]) and np.isnan(r(np.array([np.nan]), "f16")[0])
+    # every bf16 value is a fixed point, and rounding is monotone
+    vals = np.random.default_rng(3).standard_normal(1000) * 100
+    once = r(vals, "bf16")
+    assert np.array_equal(r(once, "bf16"), once)
+    order = np.argsort(vals)
+    assert np.all(np.diff(once[order]) >= 0)
+    assert np.all(np.abs(once - vals) <= np.abs(vals) * 2.0**-8)
+

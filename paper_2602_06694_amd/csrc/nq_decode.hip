@@ -179,9 +179,11 @@ __device__ inline long long quantize_chunk16(const float v[16], float inv_step, 
         mid[i >> 2] |= (uint32_t)(mm & 255) << sh;
         lo[i >> 2] |= (uint32_t)(l & 255) << sh;
     }
+    // the three slices of a chunk sit 4 pieces apart (see bq_piece): consecutive threads = consecutive
+    // chunks of a step fill whole 64-byte lines with each of the three stores
     dst[0] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-    dst[1] = make_uint4(mid[0], mid[1], mid[2], mid[3]);
-    dst[2] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+    dst[4] = make_uint4(mid[0], mid[1], mid[2], mid[3]);
+    dst[8] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
     return sum;
 }
 
@@ -256,19 +258,19 @@ quantize_kernel(const QuantDesc* __restrict__ descs, QuantDesc single, int batch
 
     // pass 2: q = rint(v / step), split into three signed bytes, write the MFMA B-operand layout
     long long local_sum = 0;
-    uint4* const dst = (uint4*)(d.bq) + (size_t)tok * d.n_chunks * kSlices;     // token-major: [chunk][slice]
+    uint4* const dst = (uint4*)(d.bq) + (size_t)tok * d.n_chunks * kSlices;     // token-major, pieces ordered by bq_piece()
     if (held) {
 #pragma unroll
         for (int k = 0; k < kQuantHeld; ++k) {
             const int c = tid + k * kQuantThreads;
             if (c < d.n_chunks)
-                local_sum += quantize_chunk16(hv[k], inv_step, bad, dst + (size_t)c * kSlices);
+                local_sum += quantize_chunk16(hv[k], inv_step, bad, dst + bq_piece(c, 0));
         }
     } else {
         for (int c = tid; c < d.n_chunks; c += kQuantThreads) {
             float v[16];
             load_chunk16(d, base, c, vec, v);
-            local_sum += quantize_chunk16(v, inv_step, bad, dst + (size_t)c * kSlices);
+            local_sum += quantize_chunk16(v, inv_step, bad, dst + bq_piece(c, 0));
         }
     }
     double s = (double)local_sum;               // |sum| < 2^39: exact
@@ -336,7 +338,7 @@ __device__ __forceinline__ v4u load_global_v4u(const char* base, uint32_t off) {
 
 // Byte offset, inside an op's quantised input, of the 16 bytes lane (g, n) feeds to the MFMA as
 // rows 16g..16g+15 of column n of column group cg, at step 0.  The input is token-major
-// ([token][chunk][slice][16 bytes], a step = 4 chunks = kBqStepBytes); column n of a group is
+// ([token][step][slice][chunk of the step][16 bytes], a step = kBqStepBytes); column n of a group is
 // slice n % 3 of the group's token n / 3.  Lanes of unused columns (n = 15, or a token beyond the
 // batch) re-read token 0: their result columns are never looked at.
 constexpr uint32_t kBqStepBytes = 4 * kSlices * 16;
@@ -345,7 +347,7 @@ __device__ __forceinline__ uint32_t bq_lane_offset(int cg, int g, int n, int bat
     int tok = 5 * cg + n / 3;
     const int slice = n % 3;
     if (n >= 15 || tok >= batch) tok = 0;
-    return (uint32_t)tok * ((uint32_t)nst * kBqStepBytes) + (uint32_t)((g * kSlices + slice) * 16);
+    return (uint32_t)tok * ((uint32_t)nst * kBqStepBytes) + (uint32_t)(bq_piece(g, slice) * 16);
 }
 
 // one 64-column step: eight bit planes, each one AND per register and one MFMA per column group
@@ -765,7 +767,10 @@ stage_shared_kernel(const StageDesc* __restrict__ descs, const WorkItem* __restr
         const int idc = id < batch * kPiecesPerTok ? id : 0;
         const int tok = idc / kPiecesPerTok, piece = idc - tok * kPiecesPerTok;
         sh_src[i] = (uint32_t)(piece * 16);                                   // + tok * (one token's bytes), per item
-        sh_dst[i] = (uint32_t)(tok * kShareTokStride + piece * 16);
+        // in LDS the three slices of a chunk are adjacent (bank spread of the operand reads): piece
+        // (step, slice, g) of the global order goes to (step, g, slice)
+        const int st = piece / 12, sl = piece % 12 / 4, gg = piece % 4;
+        sh_dst[i] = (uint32_t)(tok * kShareTokStride + (st * 12 + gg * kSlices + sl) * 16);
     }
 
     for (int it = blockIdx.x; it < n_items; it += gridDim.x) {

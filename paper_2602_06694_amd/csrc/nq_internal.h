@@ -28,6 +28,9 @@ constexpr int kTileWords = 256;
 // q = 65536*hi + 256*mid + lo.  A token occupies three MFMA columns (hi, mid, lo) of a group of 16:
 // five tokens per group; tokens 0..4 are columns 0..14 of group 0, tokens 5..7 columns 0..8 of group 1.
 constexpr int kSlices = 3;
+// Position, in 16-byte pieces inside a token's quantised vector, of slice `slice` of chunk `chunk` (16
+// reduction indices): a 64-column step = 4 chunks = 12 pieces, ordered slice-major inside the step.
+__host__ __device__ inline int bq_piece(int chunk, int slice) { return (chunk >> 2) * 12 + slice * 4 + (chunk & 3); }
 
 struct QMeta {        // per token, written by the quantisation kernel
     double sumq;      // sum_j q_j (exact)
@@ -38,7 +41,7 @@ struct QMeta {        // per token, written by the quantisation kernel
 struct QuantDesc {
     const void* x;           // device [batch][x_stride]
     const uint16_t* scale;   // device fp16 [N] or nullptr (no scaling)
-    uint8_t* bq;             // device [batch][n_chunks][3 slices][16] signed bytes
+    uint8_t* bq;             // device [batch][n_steps][3 slices][4 chunks][16] signed bytes (bq_piece)
     QMeta* meta;             // device [batch]
     int N;                   // real length
     int n_chunks;            // 16-element chunks including padding (= 4 * n_steps)

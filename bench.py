@@ -71,6 +71,18 @@ def build_workload(args):
     return name, out
 
 
+def prewarm(run, seconds=0.05):
+    """The chip changes its power state a few milliseconds into a sustained load, which stalls the
+    queue for about a millisecond once; run `run` untimed until that is over (then come the W
+    warm-up steps of the contract)."""
+    import torch
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(4):
+            run()
+        torch.cuda.synchronize()
+
+
 def algorithmic_bytes(shp, batch, y_size=4):
     """Bytes the method itself must move for one forward of one layer."""
     bits = shp.r * (shp.d_in + shp.d_out) // 8
@@ -148,6 +160,7 @@ def time_stack(cfg, batch, steps=10, warmup=2):
         sb1 += stage_bytes(shp, batch)[0]
         sb2 += stage_bytes(shp, batch)[1]
     plan = nq.nq_plan_create(handles, xs, ys, batch)
+    prewarm(lambda: nq.nq_plan_forward(plan))
     for _ in range(warmup):
         nq.nq_plan_forward(plan)
     torch.cuda.synchronize()
@@ -172,6 +185,77 @@ def time_stack(cfg, batch, steps=10, warmup=2):
     return res
 
 
+def time_pool_batch(pool, batch, steps=10, warmup=2):
+    """Config 2's layer at a decode batch other than the headline's (BASELINE quotes batch 8 too):
+    the same rotating pool of distinct instances, one plan."""
+    import numpy as np
+    import torch
+    from paper_2602_06694_amd import binding as nq
+    from paper_2602_06694_amd import synth
+    shp = synth.CONFIGS[2].block[0]
+    handles, xs, ys = [], [], []
+    for i in range(pool):
+        data = synth.gen_layer(2, i, 0, shp)
+        handles.append(nq.nq_binlr_create(shp.d_out, shp.d_in, shp.r, data.U_words, data.V_words, data.s_out,
+                                          data.s_in, nq.NQ_BF16))
+        x = synth.gen_layer_x(2, i, 0, shp, batch, "bf16")
+        xs.append(torch.from_numpy(x.view(np.int16).copy()).view(torch.bfloat16).cuda())
+        ys.append(torch.empty((batch, shp.d_out), dtype=torch.float32, device="cuda"))
+    plan = nq.nq_plan_create(handles, xs, ys, batch)
+    prewarm(lambda: nq.nq_plan_forward(plan))
+    for _ in range(warmup):
+        nq.nq_plan_forward(plan)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        nq.nq_plan_forward(plan)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    pk = np.zeros(4)
+    for _ in range(5):
+        pk += np.array(nq.nq_plan_forward_timed(plan))
+    pk /= 5
+    wb, ab = algorithmic_bytes(shp, batch)
+    s1, s2 = stage_bytes(shp, batch)
+    res = {"layers": pool, "batch": batch, "ms_per_step": ms, "weight_GBps": pool * wb / ms / 1e6,
+           "algorithmic_GBps": pool * ab / ms / 1e6, "tokens_per_s_per_layer": batch * pool / (ms * 1e-3),
+           "kernel_ms": {"quantize_x": pk[0], "stage1": pk[1], "quantize_t": pk[2], "stage2": pk[3]},
+           "stage1_GBps": pool * s1 / pk[1] / 1e6, "stage2_GBps": pool * s2 / pk[3] / 1e6}
+    nq.nq_plan_destroy(plan)
+    for h in handles:
+        nq.nq_binlr_destroy(h)
+    return res
+
+
+def time_single_layer(cfg, reps=200):
+    """One layer through nq_binlr_forward, back to back (weights stay in cache): launch-bound latency."""
+    import numpy as np
+    import torch
+    from paper_2602_06694_amd import binding as nq
+    from paper_2602_06694_amd import synth
+    c = synth.CONFIGS[cfg]
+    shp = c.block[0]
+    data = synth.gen_layer(cfg, 0, 0, shp)
+    h = nq.nq_binlr_create(shp.d_out, shp.d_in, shp.r, data.U_words, data.V_words, data.s_out, data.s_in,
+                           nq.DTYPE_BY_NAME[c.x_dtype])
+    xb = synth.gen_layer_x(cfg, 0, 0, shp, 1, c.x_dtype)
+    x = torch.from_numpy(xb.view(np.int16).copy()).view(torch.bfloat16).cuda() if c.x_dtype == "bf16" \
+        else torch.from_numpy(np.ascontiguousarray(xb)).cuda()
+    y = torch.empty((1, shp.d_out), dtype=torch.float32, device="cuda")
+    prewarm(lambda: nq.nq_binlr_forward(h, x, y, 1), 0.02)
+    for _ in range(20):
+        nq.nq_binlr_forward(h, x, y, 1)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        nq.nq_binlr_forward(h, x, y, 1)
+    torch.cuda.synchronize()
+    us = (time.perf_counter() - t0) * 1e6 / reps
+    wb, _ = algorithmic_bytes(shp, 1)
+    nq.nq_binlr_destroy(h)
+    return {"shape": [shp.d_out, shp.d_in, shp.r], "us_per_forward": us, "cache_hot_weight_GBps": wb / us / 1e3}
+
+
 def time_prefill(args):
     """Config-5 shapes through nq_binlr_forward at batch 512 / 2048 (TFLOP/s = 2 B r (d_in + d_out) / time)."""
     import numpy as np
@@ -188,11 +272,9 @@ def time_prefill(args):
             xb = synth.gen_layer_x(5, 0, li, shp, B, "bf16", c.outlier_frac)
             x = torch.from_numpy(xb.view(np.int16).copy()).view(torch.bfloat16).cuda()
             y = torch.empty((B, shp.d_out), dtype=torch.float32, device="cuda")
-            for _ in range(2):
-                nq.nq_binlr_forward(h, x, y, B)
-            torch.cuda.synchronize()
+            prewarm(lambda: nq.nq_binlr_forward(h, x, y, B), 0.03)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            iters = 5
+            iters = 20
             e0.record()
             for _ in range(iters):
                 nq.nq_binlr_forward(h, x, y, B)
@@ -241,6 +323,7 @@ def main():
     plan = nq.nq_plan_create(handles, xs, ys, batch)
     torch.cuda.synchronize()
 
+    prewarm(lambda: nq.nq_plan_forward(plan))
     for _ in range(args.warmup):
         nq.nq_plan_forward(plan)
     torch.cuda.synchronize()
@@ -308,7 +391,12 @@ def main():
     handles = []
     del xs, ys, plan
     if not args.quick:
-        out["extra"] = {"decode_llama2_70b_stack_b1": time_stack(4, 1), "prefill_config5": time_prefill(args)}
+        out["extra"] = {"decode_cfg1_single_layer_b1": time_single_layer(1),
+                        "decode_cfg2_single_layer_b1": time_single_layer(2),
+                        "decode_cfg2_pool_b8": time_pool_batch(args.pool, 8),
+                        "decode_llama2_7b_stack_b1": time_stack(3, 1),
+                        "decode_llama2_70b_stack_b1": time_stack(4, 1),
+                        "prefill_config5": time_prefill(args)}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(work, batch, args.cpu_seconds)
 

@@ -437,9 +437,28 @@ prefill_finalize_kernel(GemmArgs a)
         if (tok < a.batch) {
             const float f = -a.tok_scale[tok];
             const float cv[4] = {c.x, c.y, c.z, c.w};
-            for (int v = 0; v < 4; ++v)
-                if (n0 + v < a.n_real)
-                    store_out(a.y_out, a.y_dtype, (size_t)tok * a.n_real + n0 + v, cv[v] * f * h2f(a.out_scale[n0 + v]));
+            const size_t at = (size_t)tok * a.n_real + n0;
+            if ((a.n_real & 3) == 0) {                     // rows stay aligned: one load of scales, one store
+                if (n0 < a.n_real) {
+                    const uint2 sc = *(const uint2*)(a.out_scale + n0);
+                    v4f o;
+                    o.x = cv[0] * f * h2f((uint16_t)(sc.x & 0xFFFFu));
+                    o.y = cv[1] * f * h2f((uint16_t)(sc.x >> 16));
+                    o.z = cv[2] * f * h2f((uint16_t)(sc.y & 0xFFFFu));
+                    o.w = cv[3] * f * h2f((uint16_t)(sc.y >> 16));
+                    if (a.y_dtype == NQ_F32) {
+                        *(v4f*)((float*)a.y_out + at) = o;
+                    } else {
+                        uint2 pk;
+                        pk.x = (uint32_t)float_to_out16(o.x, a.y_dtype) | ((uint32_t)float_to_out16(o.y, a.y_dtype) << 16);
+                        pk.y = (uint32_t)float_to_out16(o.z, a.y_dtype) | ((uint32_t)float_to_out16(o.w, a.y_dtype) << 16);
+                        *(uint2*)((uint16_t*)a.y_out + at) = pk;
+                    }
+                }
+            } else {
+                for (int v = 0; v < 4; ++v)
+                    if (n0 + v < a.n_real) store_out(a.y_out, a.y_dtype, at + v, cv[v] * f * h2f(a.out_scale[n0 + v]));
+            }
         }
     }
 }
@@ -461,17 +480,27 @@ struct PfLayout {
 static int choose_splits(int m_tiles, int n_tiles, int nst, int m_pad, int n_pad)
 {
     const int wgs = m_tiles * n_tiles;
-    const int cus = device_cu_count() * 2;                // two workgroups fit a CU
-    const double step_us = 0.9, hbm_bytes_per_us = 4.0e6;
+    const int cus = device_cu_count();
+    // measured on the 70B MLP shapes: one reduction step of a workgroup takes 0.73 us when it has
+    // its CU to itself and 1.17 us when two share one; a split costs the write and re-read of one
+    // set of fp32 partial sums, which mostly stay in the last-level cache (about 7.7 MB/us)
+    const double alone_us = 0.73, shared_us = 1.17, partial_bytes_per_us = 7.7e6;
     int best = 1;
     double best_cost = 1e30;
     for (int s = 1; s <= 16; ++s) {
         int per = (nst + s - 1) / s;
         per += per & 1;
         if (s > 1 && per < 8) break;
-        const int rounds = (wgs * s + cus - 1) / cus;
-        double cost = (double)rounds * per * step_us;
-        if (s > 1) cost += 2.0 * s * (double)m_pad * n_pad * 4.0 / hbm_bytes_per_us;
+        const int total = wgs * s;
+        double cost;
+        if (total <= cus) {
+            cost = per * alone_us;
+        } else {
+            const int full = total / (2 * cus), rem = total % (2 * cus);
+            cost = (double)full * per * shared_us;
+            if (rem) cost += per * (rem <= cus ? alone_us : shared_us);
+        }
+        if (s > 1) cost += s * 2.0 * (double)m_pad * n_pad * 4.0 / partial_bytes_per_us;
         if (cost < best_cost) { best_cost = cost; best = s; }
     }
     return best;
@@ -493,7 +522,7 @@ static PfLayout pf_layout(int64_t d_out, int64_t d_in, int64_t r, int batch)
     L.n1_pad = (int)n_rowblocks(r) * kTileRows;
     L.n2_pad = (int)n_rowblocks(d_out) * kTileRows;
     const int m_tiles = L.m_pad / kPfTokens;
-    L.splits1 = choose_splits(m_tiles, (int)((n_rowblocks(r) + kPfWaves - 1) / kPfWaves), (int)n_steps(d_in), L.m_pad, L.n1_pad);
+    L.splits1 = getenv("NQ_PF_SPLITS1") ? atoi(getenv("NQ_PF_SPLITS1")) : choose_splits(m_tiles, (int)((n_rowblocks(r) + kPfWaves - 1) / kPfWaves), (int)n_steps(d_in), L.m_pad, L.n1_pad);
     L.splits2 = choose_splits(m_tiles, (int)((n_rowblocks(d_out) + kPfWaves - 1) / kPfWaves), (int)n_steps(r), L.m_pad, L.n2_pad);
     size_t o = 0;
     L.off_x = o; o += al256((size_t)L.m_pad * L.k1 * 2);

@@ -577,16 +577,14 @@ stage_stream_kernel(const StageDesc* __restrict__ descs, StageDesc single, const
             __builtin_amdgcn_sched_barrier(0);             // same issue order as inside the loop
         }
         const int groups = nst / D;
-        for (int u = 0; u < n_rb; ++u) {
+        // all row blocks but the last: results deferred through LDS
+        for (int u = 0; u + 1 < n_rb; ++u) {
             v4i acc[NB][8];
 #pragma unroll
             for (int cg = 0; cg < NB; ++cg)
 #pragma unroll
                 for (int p = 0; p < 8; ++p) acc[cg][p] = v4i{0, 0, 0, 0};
-            const bool last = (u == n_rb - 1);
-            // the last row block of the item must not fetch past its own tiles
-            const int n_refill = last ? groups - 1 : groups;
-            for (int gi = 0; gi < n_refill; ++gi) {
+            for (int gi = 0; gi < groups; ++gi) {
 #pragma unroll
                 for (int k = 0; k < D; ++k) {
                     mac_tile<NB>(acc, wbuf[k], bbuf[k]);
@@ -594,18 +592,34 @@ stage_stream_kernel(const StageDesc* __restrict__ descs, StageDesc single, const
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
-            if (last) {
-#pragma unroll
-                for (int k = 0; k < D; ++k) {
-                    mac_tile<NB>(acc, wbuf[k], bbuf[k]);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
             stage_epilogue<NB, 1, true>(acc, lds, 0, lane, batch, rb0 + u, ea,
                                         lds_out + u * (kTileRows * batch));
         }
+        // the last one must not fetch past its own tiles; the ring is empty after it, so its
+        // results are scaled and stored straight from the epilogue
+        {
+            v4i acc[NB][8];
+#pragma unroll
+            for (int cg = 0; cg < NB; ++cg)
+#pragma unroll
+                for (int p = 0; p < 8; ++p) acc[cg][p] = v4i{0, 0, 0, 0};
+            for (int gi = 0; gi < groups - 1; ++gi) {
+#pragma unroll
+                for (int k = 0; k < D; ++k) {
+                    mac_tile<NB>(acc, wbuf[k], bbuf[k]);
+                    NQ_ISSUE(k);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < D; ++k) {
+                mac_tile<NB>(acc, wbuf[k], bbuf[k]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            stage_epilogue<NB, 1, false>(acc, lds, 0, lane, batch, rb0 + n_rb - 1, ea, nullptr);
+        }
 #undef NQ_ISSUE
-        stream_flush(lds, lds_out, lane, rb0, n_rb, batch, ea);
+        if (n_rb > 1) stream_flush(lds, lds_out, lane, rb0, n_rb - 1, batch, ea);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __builtin_amdgcn_wave_barrier();
     }
@@ -992,8 +1006,11 @@ int stage_schedule(int n_rb_total, int mean_steps, int batch)
     return w;
 }
 
-// Steps one wave of the stream kernel should see per item (several short row blocks are chained).
-int stream_target_steps() { return env_int("NQ_STREAM_STEPS", 128); }
+// Steps one wave of the stream kernel should see per item (row blocks shorter than this are chained).
+// Measured: beyond very short reductions chaining loses; many short items, whose epilogues and
+// stores overlap with the streaming of the other waves, beat few long ones (stage 2 of the
+// 4096x4096 r=1024 pool: 99.7 us with one 16-step row block per item, 103.5 us with eight).
+int stream_target_steps() { return env_int("NQ_STREAM_STEPS", 16); }
 
 // Row blocks an item may chain: its deferred results (128 x batch floats per row block) share the
 // CU's LDS with those of the other resident waves (20 per CU with one column group, 8 with two).

@@ -421,11 +421,11 @@ static StageDesc make_s2(nq_handle h, void* y)
 }
 
 // Row blocks chained into one item of the stream kernel for an op with `nst` steps per row block:
-// aim at stream_target_steps() steps per wave, but keep at least ~16 items per CU in the launch
+// aim at stream_target_steps(batch) steps per wave, but keep at least ~16 items per CU in the launch
 // (`total_rb` = row blocks of the whole launch).
 static int rbs_per_stream_item(int n_rb, int nst, int total_rb, int batch)
 {
-    int per = std::max(1, stream_target_steps() / std::max(1, nst));
+    int per = std::max(1, stream_target_steps(batch) / std::max(1, nst));
     per = std::min(per, stream_max_rbs(batch));
     const int want_items = device_cu_count() * 16;
     while (per > 1 && total_rb / per < want_items) per /= 2;

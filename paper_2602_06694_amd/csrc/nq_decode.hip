@@ -954,7 +954,7 @@ int shared_max_per(int batch)
 int shared_per_wave(int nst, int batch)
 {
     if (nst % 8 != 0) return 1;                       // a half pass must be the last thing a wave does
-    return std::max(1, std::min(shared_max_per(batch), stream_target_steps() / std::max(1, nst)));
+    return std::max(1, std::min(shared_max_per(batch), stream_target_steps(batch) / std::max(1, nst)));
 }
 
 template <int NB>
@@ -1010,7 +1010,9 @@ int stage_schedule(int n_rb_total, int mean_steps, int batch)
 // Measured: beyond very short reductions chaining loses; many short items, whose epilogues and
 // stores overlap with the streaming of the other waves, beat few long ones (stage 2 of the
 // 4096x4096 r=1024 pool: 99.7 us with one 16-step row block per item, 103.5 us with eight).
-int stream_target_steps() { return env_int("NQ_STREAM_STEPS", 16); }
+// With two column groups (batch 6..8, two waves per SIMD) a few chained row blocks still pay (stage 2 of the
+// same pool at batch 8: 197 us with three per item, 205 us with one).
+int stream_target_steps(int batch) { return env_int("NQ_STREAM_STEPS", batch <= 5 ? 16 : 64); }
 
 // Row blocks an item may chain: its deferred results (128 x batch floats per row block) share the
 // CU's LDS with those of the other resident waves (20 per CU with one column group, 8 with two).

@@ -121,7 +121,7 @@ int launch_export(const uint32_t* d_tiles, int64_t wpr, bool transposed, int64_t
 int launch_quantize(const QuantDesc* d_descs, const QuantDesc& single, int n_ops, int max_chunks, int batch,
                     hipStream_t s);
 int stage_schedule(int n_rb_total, int mean_steps, int batch);
-int stream_target_steps();
+int stream_target_steps(int batch);
 int stream_max_rbs(int batch);           // row blocks one stream item may chain (bounded by its LDS output buffer)
 constexpr int kSharedSchedule = 8;       // stage_schedule()'s value for the workgroup-shared-input kernel
 int shared_per_wave(int nst, int batch); // row blocks per wave of an item of that kernel

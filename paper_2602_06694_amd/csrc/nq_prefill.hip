@@ -394,7 +394,7 @@ prefill_gemm_kernel(GemmArgs a)
                             o.z = cv[2] * f * h2f((uint16_t)(sc.y & 0xFFFFu));
                             o.w = cv[3] * f * h2f((uint16_t)(sc.y >> 16));
                             if (a.y_dtype == NQ_F32) {
-                                *(v4f*)((float*)a.y_out + at) = o;
+                                __builtin_nontemporal_store(o, (v4f*)((float*)a.y_out + at));
                             } else {
                                 uint2 pk;
                                 pk.x = (uint32_t)float_to_out16(o.x, a.y_dtype) | ((uint32_t)float_to_out16(o.y, a.y_dtype) << 16);

@@ -63,10 +63,11 @@ extern "C" {
 
 /* nq_binlr_create flags */
 #define NQ_FLAG_DEFAULT      0u
-#define NQ_FLAG_DECODE_VALU  1u  /* batch < 64 runs the plain fp32 vector-ALU kernels instead of the
+#define NQ_FLAG_DECODE_VALU  1u  /* every batch runs the plain fp32 vector-ALU kernels instead of the
                                     fixed-point matrix-core kernels (slow; a second implementation
                                     kept for cross-checks and as the paper-style "mask + FMA" GEMV) */
-#define NQ_FLAG_NO_PREFILL   2u  /* never take the dense MFMA path: batch >= 64 is run as chunks of 8 */
+#define NQ_FLAG_NO_PREFILL   2u  /* never take the dense MFMA path: a batch above 8 is run as chunks of 8
+                                    through the streaming kernels (their accuracy, their cost per chunk) */
 
 typedef struct nq_binlr_s* nq_handle;   /* one factorized layer resident on one GPU */
 typedef struct nq_plan_s*  nq_plan;     /* a fixed list of independent forwards */
@@ -75,8 +76,9 @@ typedef struct nq_plan_s*  nq_plan;     /* a fixed list of independent forwards 
 #define NQ_MAX_DIM 65536
 /* Largest batch served by the streaming (decode) kernels in one pass. */
 #define NQ_DECODE_MAX_BATCH 8
-/* Batches at or above this take the dense matrix-core (prefill) path. */
-#define NQ_PREFILL_MIN_BATCH 64
+/* Batches at or above this take the dense matrix-core (prefill) path: its cost is flat up to
+ * 64 tokens (one token tile) and, measured, never above that of two streaming passes. */
+#define NQ_PREFILL_MIN_BATCH 9
 
 /* ---- packing (Algorithm 1, PackBinary; Fig. 2(c)) -- host only, no GPU needed ---- */
 
@@ -119,7 +121,8 @@ int nq_binlr_reserve(nq_handle h, int max_batch);
  * batch <= the reserved batch (otherwise it reserves first, which synchronises).
  * Not re-entrant on one handle (the handle's workspace is shared); different
  * handles may run concurrently on different streams.
- * batch <= 8: streaming kernels; 9..63: chunks of 8; >= 64: dense MFMA path. */
+ * batch <= 8: streaming kernels (exact integer accumulation); >= 9: dense MFMA path
+ * (fp16 operands, fp32 accumulation), unless the layer was created with NQ_FLAG_NO_PREFILL. */
 int nq_binlr_forward(nq_handle h, const void* x, void* y, int batch, void* stream);
 
 /* n independent forwards (same batch <= NQ_DECODE_MAX_BATCH) in four launches in total:

@@ -20,7 +20,7 @@ NQ_I8, NQ_F32, NQ_F16, NQ_BF16 = 0, 1, 2, 3
 NQ_FLAG_DEFAULT, NQ_FLAG_DECODE_VALU, NQ_FLAG_NO_PREFILL = 0, 1, 2
 NQ_MAX_DIM = 65536
 NQ_DECODE_MAX_BATCH = 8
-NQ_PREFILL_MIN_BATCH = 64
+NQ_PREFILL_MIN_BATCH = 9
 
 DTYPE_BY_NAME = {"f32": NQ_F32, "f16": NQ_F16, "bf16": NQ_BF16, "i8": NQ_I8}
 

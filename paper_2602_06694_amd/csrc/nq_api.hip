@@ -485,7 +485,7 @@ extern "C" int nq_binlr_forward(nq_handle h, const void* x, void* y, int batch, 
         a.d_out = h->d_out; a.d_in = h->d_in; a.r = h->r; a.batch = batch; a.x_dtype = h->x_dtype; a.y_dtype = h->y_dtype;
         return launch_prefill(a, s);
     }
-    // mid-size batches: chunks of 8 through the streaming path (each chunk re-reads the bits)
+    // larger batches without the dense path: chunks of 8 through the streaming path (each chunk re-reads the bits)
     for (int b0 = 0; b0 < batch; b0 += NQ_DECODE_MAX_BATCH) {
         int nb = std::min(NQ_DECODE_MAX_BATCH, batch - b0);
         rc = decode_once(h, (const char*)x + (size_t)b0 * h->d_in * xs, (char*)y + (size_t)b0 * h->d_out * ys, nb, s);

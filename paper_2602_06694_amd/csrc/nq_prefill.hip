@@ -1,4 +1,4 @@
-// Dense (prefill, batch >= 64) path of  y = s_out (.) (U (V^T (s_in (.) x)))   (Section 3.1 Eq. 1;
+// Dense (prefill, batch >= 9) path of  y = s_out (.) (U (V^T (s_in (.) x)))   (Section 3.1 Eq. 1;
 // Appendix D, "Binary GEMM"): both contractions run on the fp16 matrix cores of gfx950.
 //
 //   pre   : x'' = fp16( s_in (.) x * 2^a_b )          per token b, 2^a_b puts max|x''| in [2^12, 2^13)

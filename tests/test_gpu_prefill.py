@@ -1,4 +1,4 @@
-"""GPU parity of the dense (batch >= 64) path against the fp64 oracle."""
+"""GPU parity of the dense (batch >= 9) path against the fp64 oracle."""
 import numpy as np
 import pytest
 
@@ -18,7 +18,7 @@ PREFILL_TOL = 7e-4
 def test_prefill_small_shapes(shape, x_dtype):
     d_out, d_in, r = shape
     L = Layer(d_out, d_in, r, x_dtype, seed=3 * d_out + d_in)
-    for batch in (64, 130, 256):
+    for batch in (9, 40, 64, 130, 256):
         x = synth.gen_x(batch, d_in, 900 + batch, x_dtype, outlier_frac=0.01 if d_in >= 200 else 0.0)
         y = L.forward(x)
         ref = L.oracle(x)
@@ -69,8 +69,8 @@ def test_prefill_reserve_and_batch_changes():
     d_out, d_in, r = 700, 300, 130
     L = Layer(d_out, d_in, r, "bf16", seed=21)
     nq.nq_binlr_reserve(L.h, 512)
-    for batch in (512, 64, 300, 64, 8, 512):
+    for batch in (512, 64, 300, 17, 64, 8, 512):
         x = synth.gen_x(batch, d_in, 30 + batch, "bf16")
-        tol = PREFILL_TOL if batch >= 64 else 1e-5
+        tol = PREFILL_TOL if batch >= nq.NQ_PREFILL_MIN_BATCH else 1e-5
         assert rel_err(L.forward(x), L.oracle(x)) <= tol, batch
     L.close()

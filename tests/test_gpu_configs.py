@@ -28,6 +28,37 @@ def build_stack(cfg, n_layers=None, batch=1):
     return layers, xs_np, xs, ys
 
 
+@pytest.mark.parametrize("batch", [1, 8])
+def test_config2_pool_as_the_benchmark_runs_it(batch):
+    """Config 2's layer as a pool of distinct instances under one plan -- the benchmark's headline
+    launch configuration (at batch 8, 320 instances are enough row blocks for the schedules of
+    chip-filling launches, the shared-input kernel among them).  Every 16th instance is checked in
+    full against the oracle, and every output of every instance must be finite."""
+    import torch
+    shp = synth.CONFIGS[2].block[0]
+    n = 320
+    layers, xs_np, xs, ys = [], [], [], []
+    for i in range(n):
+        layers.append(Layer(shp.d_out, shp.d_in, shp.r, "bf16", data=synth.gen_layer(2, i, 0, shp)))
+        x = synth.gen_layer_x(2, i, 0, shp, batch, "bf16")
+        xs_np.append(x)
+        xs.append(to_device(x, "bf16"))
+        ys.append(torch.full((batch, shp.d_out), float("nan"), dtype=torch.float32, device="cuda"))
+    plan = nq.nq_plan_create([L.h for L in layers], xs, ys, batch)
+    nq.nq_plan_forward(plan)
+    nq.nq_plan_forward(plan)
+    torch.cuda.synchronize()
+    assert all(bool(torch.isfinite(y).all()) for y in ys)
+    worst = 0.0
+    for i in range(0, n, 16):
+        worst = max(worst, rel_err(ys[i].cpu().numpy(), layers[i].oracle(xs_np[i])))
+    print(f"config 2 pool, batch {batch}: worst rel err over {n // 16} checked instances {worst:.3e}")
+    assert worst <= DECODE_TOL and worst <= BAR
+    nq.nq_plan_destroy(plan)
+    for L in layers:
+        L.close()
+
+
 def test_config3_llama2_7b_stack_every_output():
     import torch
     layers, xs_np, xs, ys = build_stack(3)

@@ -94,6 +94,16 @@ int nq_pack_signs(const void* signs, int dtype, int64_t rows, int64_t cols, uint
 /* Exact inverse on the first `cols` bits of every row. out_pm1: host int8 [rows, cols]. */
 int nq_unpack_signs(const uint32_t* words, int64_t rows, int64_t cols, int8_t* out_pm1);
 
+/* The same packing on the GPU (Algorithm 1, PackBinary, for factors that already live in device
+ * memory, e.g. the latent matrices at the end of Phase 3).
+ * d_signs: device, [rows, cols] row-major of `dtype`;  d_words: device, nq_packed_words(rows, cols)
+ * words, fully overwritten with the canonical format (identical to nq_pack_signs' output).
+ * d_invalid: device int32 or NULL; incremented once for every NaN (or int8 other than +-1) met,
+ * which is packed as bit 0 -- the caller clears it before and reads it after.
+ * Asynchronous on `stream`; allocates nothing.  rows < 2^31, cols <= 65535 * 256. */
+int nq_pack_signs_device(const void* d_signs, int dtype, int64_t rows, int64_t cols,
+                         uint32_t* d_words, int32_t* d_invalid, void* stream);
+
 /* ---- layer objects ---- */
 
 /* Build a layer on the current HIP device.
@@ -110,6 +120,13 @@ int nq_binlr_create(nq_handle* out, int64_t d_out, int64_t d_in, int64_t r,
                     const uint32_t* U_words, const uint32_t* V_words,
                     const uint16_t* s_out_fp16, const uint16_t* s_in_fp16,
                     int x_dtype, int y_dtype, uint32_t flags);
+
+/* nq_binlr_create with all four inputs in device memory of the current device (canonical words as
+ * written by nq_pack_signs_device, fp16 scales); same checks, same result. */
+int nq_binlr_create_from_device(nq_handle* out, int64_t d_out, int64_t d_in, int64_t r,
+                                const uint32_t* d_U_words, const uint32_t* d_V_words,
+                                const uint16_t* d_s_out_fp16, const uint16_t* d_s_in_fp16,
+                                int x_dtype, int y_dtype, uint32_t flags);
 
 /* Grow the per-layer workspace so that forwards with batch <= max_batch allocate nothing.
  * May allocate and synchronise. */

@@ -48,6 +48,9 @@ def lib() -> ctypes.CDLL:
         L.nq_unpack_signs.argtypes = [vp, i64, i64, vp]; L.nq_unpack_signs.restype = ci
         L.nq_binlr_create.argtypes = [ctypes.POINTER(vp), i64, i64, i64, vp, vp, vp, vp, ci, ci, u32]
         L.nq_binlr_create.restype = ci
+        L.nq_pack_signs_device.argtypes = [vp, ci, i64, i64, vp, vp, vp]; L.nq_pack_signs_device.restype = ci
+        L.nq_binlr_create_from_device.argtypes = [ctypes.POINTER(vp), i64, i64, i64, vp, vp, vp, vp, ci, ci, u32]
+        L.nq_binlr_create_from_device.restype = ci
         L.nq_binlr_reserve.argtypes = [vp, ci]; L.nq_binlr_reserve.restype = ci
         L.nq_binlr_forward.argtypes = [vp, vp, vp, ci, vp]; L.nq_binlr_forward.restype = ci
         L.nq_binlr_forward_many.argtypes = [vp, vp, vp, ci, ci, vp]; L.nq_binlr_forward_many.restype = ci
@@ -149,6 +152,21 @@ def nq_binlr_create(d_out: int, d_in: int, r: int, U_words: np.ndarray, V_words:
     h = ctypes.c_void_p()
     _check(lib().nq_binlr_create(ctypes.byref(h), d_out, d_in, r, _np_ptr(U), _np_ptr(V), _np_ptr(so), _np_ptr(si),
                                  x_dtype, y_dtype, flags))
+    return h.value
+
+
+def nq_pack_signs_device(d_signs, dtype: int, rows: int, cols: int, d_words, d_invalid=None, stream=None) -> None:
+    """d_signs / d_words / d_invalid: device arrays (anything with data_ptr()) or raw addresses."""
+    _check(lib().nq_pack_signs_device(_dev_ptr(d_signs), dtype, rows, cols, _dev_ptr(d_words),
+                                      _dev_ptr(d_invalid) if d_invalid is not None else None, _stream(stream)))
+
+
+def nq_binlr_create_from_device(d_out: int, d_in: int, r: int, d_U_words, d_V_words, d_s_out, d_s_in,
+                                x_dtype: int, y_dtype: int = NQ_F32, flags: int = NQ_FLAG_DEFAULT) -> int:
+    """All four inputs are device arrays: canonical words (uint32 / int32 storage) and fp16 scales."""
+    h = ctypes.c_void_p()
+    _check(lib().nq_binlr_create_from_device(ctypes.byref(h), d_out, d_in, r, _dev_ptr(d_U_words), _dev_ptr(d_V_words),
+                                             _dev_ptr(d_s_out), _dev_ptr(d_s_in), x_dtype, y_dtype, flags))
     return h.value
 
 

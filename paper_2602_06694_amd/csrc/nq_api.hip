@@ -254,10 +254,12 @@ static nq_plan g_cached_plan = nullptr;
 static std::vector<const void*> g_cached_key;
 static void drop_cached_plan_locked();
 
-extern "C" int nq_binlr_create(nq_handle* out, int64_t d_out, int64_t d_in, int64_t r, const uint32_t* U_words,
-                               const uint32_t* V_words, const uint16_t* s_out_fp16, const uint16_t* s_in_fp16,
-                               int x_dtype, int y_dtype, uint32_t flags)
+// the inputs are host buffers (from_device = false) or device buffers of the current device
+static int create_layer(nq_handle* out, int64_t d_out, int64_t d_in, int64_t r, const uint32_t* U_words,
+                        const uint32_t* V_words, const uint16_t* s_out_fp16, const uint16_t* s_in_fp16,
+                        int x_dtype, int y_dtype, uint32_t flags, bool from_device)
 {
+    const hipMemcpyKind kind = from_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
     if (!out) return fail(NQ_E_NULL, "nq_binlr_create: out is NULL");
     *out = nullptr;
     if (d_out < 1 || d_in < 1 || r < 1) return fail(NQ_E_SHAPE, "nq_binlr_create: d_out, d_in, r must be >= 1");
@@ -322,15 +324,15 @@ extern "C" int nq_binlr_create(nq_handle* out, int64_t d_out, int64_t d_in, int6
         h->t = (float*)q;
     }
     CREATE_HIP(hipMemset(h->ws_alloc, 0, ws_total));
-    CREATE_HIP(hipMemcpy(d_canon, V_words, canon_v, hipMemcpyHostToDevice));
+    CREATE_HIP(hipMemcpy(d_canon, V_words, canon_v, kind));
     rc = launch_repack(d_canon, wpr, true, r, d_in, h->vt_tiles, nullptr);
     if (rc != NQ_OK) goto done;
     CREATE_HIP(hipDeviceSynchronize());
-    CREATE_HIP(hipMemcpy(d_canon, U_words, canon_u, hipMemcpyHostToDevice));
+    CREATE_HIP(hipMemcpy(d_canon, U_words, canon_u, kind));
     rc = launch_repack(d_canon, wpr, false, d_out, r, h->u_tiles, nullptr);
     if (rc != NQ_OK) goto done;
-    CREATE_HIP(hipMemcpy(h->s_in, s_in_fp16, (size_t)d_in * 2, hipMemcpyHostToDevice));
-    CREATE_HIP(hipMemcpy(h->s_out, s_out_fp16, (size_t)d_out * 2, hipMemcpyHostToDevice));
+    CREATE_HIP(hipMemcpy(h->s_in, s_in_fp16, (size_t)d_in * 2, kind));
+    CREATE_HIP(hipMemcpy(h->s_out, s_out_fp16, (size_t)d_out * 2, kind));
     CREATE_HIP(hipDeviceSynchronize());
 #undef CREATE_HIP
 done:
@@ -341,6 +343,34 @@ done:
     }
     *out = h;
     return NQ_OK;
+}
+
+extern "C" int nq_binlr_create(nq_handle* out, int64_t d_out, int64_t d_in, int64_t r, const uint32_t* U_words,
+                               const uint32_t* V_words, const uint16_t* s_out_fp16, const uint16_t* s_in_fp16,
+                               int x_dtype, int y_dtype, uint32_t flags)
+{
+    return create_layer(out, d_out, d_in, r, U_words, V_words, s_out_fp16, s_in_fp16, x_dtype, y_dtype, flags, false);
+}
+
+extern "C" int nq_binlr_create_from_device(nq_handle* out, int64_t d_out, int64_t d_in, int64_t r,
+                                           const uint32_t* d_U_words, const uint32_t* d_V_words,
+                                           const uint16_t* d_s_out_fp16, const uint16_t* d_s_in_fp16, int x_dtype,
+                                           int y_dtype, uint32_t flags)
+{
+    return create_layer(out, d_out, d_in, r, d_U_words, d_V_words, d_s_out_fp16, d_s_in_fp16, x_dtype, y_dtype, flags,
+                        true);
+}
+
+extern "C" int nq_pack_signs_device(const void* d_signs, int dtype, int64_t rows, int64_t cols, uint32_t* d_words,
+                                    int32_t* d_invalid, void* stream)
+{
+    if (!d_signs || !d_words) return fail(NQ_E_NULL, "nq_pack_signs_device: NULL buffer");
+    if (rows < 1 || cols < 1) return fail(NQ_E_SHAPE, "nq_pack_signs_device: rows and cols must be >= 1");
+    if (rows > 0x7fffffffLL || cols > 65535LL * 256)
+        return fail(NQ_E_SHAPE, "nq_pack_signs_device: matrix too large for one launch");
+    if (dtype != NQ_I8 && dtype != NQ_F32 && dtype != NQ_F16 && dtype != NQ_BF16)
+        return fail(NQ_E_INVALID_ARG, "nq_pack_signs_device: dtype must be NQ_I8, NQ_F32, NQ_F16 or NQ_BF16");
+    return launch_pack_signs(d_signs, dtype, rows, cols, d_words, (int*)d_invalid, (hipStream_t)stream);
 }
 
 extern "C" int nq_binlr_destroy(nq_handle h)

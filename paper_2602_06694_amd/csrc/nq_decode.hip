@@ -303,6 +303,54 @@ int launch_quantize(const QuantDesc* d_descs, const QuantDesc& single, int n_ops
 }
 
 // ---------------------------------------------------------------------------------------------
+// sign + pack on the device (Algorithm 1, PackBinary; Fig. 2(c)): latent matrix [rows][cols] ->
+// canonical words [rows][ceil(cols / 32)].  One wave per 64 consecutive columns of a row: the
+// wave-wide ballot of "value >= 0" IS two packed words.  bit = 1 iff value >= 0 (both zeros -> +1);
+// a NaN, or an int8 other than +-1, packs as bit 0 and is counted in *invalid.
+// grid = (rows, ceil(cols / 256)), block = 256 (four waves, one 64-column chunk each)
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+pack_signs_kernel(const void* __restrict__ signs, int dtype, int64_t rows, int64_t cols, int64_t wpr,
+                  uint32_t* __restrict__ words, int* __restrict__ invalid)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t chunk = (int64_t)blockIdx.y * 4 + (threadIdx.x >> 6);       // 64-column chunk of the row
+    const int64_t row = blockIdx.x;
+    const int64_t col = chunk * 64 + lane;
+    if (chunk * 64 >= cols) return;
+    bool plus = false, bad = false;
+    if (col < cols) {
+        const int64_t idx = row * cols + col;
+        if (dtype == NQ_I8) {
+            const int8_t v = ((const int8_t*)signs)[idx];
+            plus = v == 1;
+            bad = v != 1 && v != -1;
+        } else {
+            const float v = load_as_float(signs, dtype, idx);
+            plus = v >= 0.0f;
+            bad = v != v;
+        }
+    }
+    const unsigned long long mask = __ballot(plus);
+    if (bad && invalid) atomicAdd(invalid, 1);
+    if (lane == 0) {
+        words[row * wpr + chunk * 2] = (uint32_t)mask;
+        if (chunk * 2 + 1 < wpr) words[row * wpr + chunk * 2 + 1] = (uint32_t)(mask >> 32);
+    }
+}
+
+int launch_pack_signs(const void* d_signs, int dtype, int64_t rows, int64_t cols, uint32_t* d_words, int* d_invalid,
+                      hipStream_t s)
+{
+    const int64_t wpr = (cols + 31) / 32;
+    const int64_t chunks = (cols + 63) / 64;
+    hipLaunchKernelGGL(pack_signs_kernel, dim3((unsigned)rows, (unsigned)((chunks + 3) / 4)), dim3(256), 0, s, d_signs,
+                       dtype, rows, cols, wpr, d_words, d_invalid);
+    NQ_HIP(hipGetLastError());
+    return NQ_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
 // streaming sign-matrix x fixed-point-vector kernels (steps a2 and a4, with a5 fused in stage 2)
 //   NB : number of 16-column groups of the B operand (1: batch <= 5, 2: batch 6..8)
 //   D  : software prefetch ring (tiles per wave; D-1 stay in flight while one is consumed)

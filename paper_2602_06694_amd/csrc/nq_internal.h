@@ -117,6 +117,8 @@ int launch_repack(const uint32_t* d_canon, int64_t wpr, bool transposed, int64_t
                   uint32_t* d_tiles, hipStream_t s);
 int launch_export(const uint32_t* d_tiles, int64_t wpr, bool transposed, int64_t M, int64_t N,
                   uint32_t* d_canon, hipStream_t s);
+int launch_pack_signs(const void* d_signs, int dtype, int64_t rows, int64_t cols, uint32_t* d_words, int* d_invalid,
+                      hipStream_t s);
 // single op (descriptor by value) or many (device arrays)
 int launch_quantize(const QuantDesc* d_descs, const QuantDesc& single, int n_ops, int max_chunks, int batch,
                     hipStream_t s);

@@ -97,6 +97,11 @@ def test_argument_validation_needs_no_gpu():
     assert L.nq_binlr_create(ctypes.byref(h), 4, 4, 4, p(w), p(w), p(s), p(s), nq.NQ_F32, nq.NQ_I8, 0) == nq.NQ_E_INVALID_ARG
     assert L.nq_binlr_create(ctypes.byref(h), 4, 4, 4, p(w), p(w), p(s), p(s), nq.NQ_F32, nq.NQ_F32, 64) == nq.NQ_E_INVALID_ARG
     assert h.value is None
+    assert L.nq_binlr_create_from_device(ctypes.byref(h), 4, 4, 4, None, p(w), p(s), p(s), nq.NQ_F32, nq.NQ_F32, 0) == nq.NQ_E_NULL
+    assert L.nq_binlr_create_from_device(ctypes.byref(h), 4, 0, 4, p(w), p(w), p(s), p(s), nq.NQ_F32, nq.NQ_F32, 0) == nq.NQ_E_SHAPE
+    assert L.nq_pack_signs_device(None, nq.NQ_F32, 4, 4, p(w), None, None) == nq.NQ_E_NULL
+    assert L.nq_pack_signs_device(p(w), nq.NQ_F32, 0, 4, p(w), None, None) == nq.NQ_E_SHAPE
+    assert L.nq_pack_signs_device(p(w), 77, 4, 4, p(w), None, None) == nq.NQ_E_INVALID_ARG
     assert L.nq_binlr_forward(None, None, None, 1, None) == nq.NQ_E_NULL
     assert L.nq_binlr_weight_bytes(None) == 0
     assert L.nq_binlr_destroy(None) == nq.NQ_OK

@@ -96,6 +96,84 @@ def test_device_layout_round_trip_is_bit_exact():
     L.close()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16", "i8"])
+def test_device_packing_is_bit_exact(dtype):
+    """nq_pack_signs_device against the oracle's packer: ragged widths around the 32- and 64-column
+    boundaries, both zeros, infinities, denormals; NaNs are counted and packed as 0."""
+    import torch
+    rng = np.random.default_rng(11)
+    tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "i8": torch.int8}[dtype]
+    for rows, cols in [(1, 1), (3, 31), (5, 32), (4, 33), (7, 63), (2, 64), (9, 65), (130, 1000), (64, 3520), (17, 4097)]:
+        if dtype == "i8":
+            vals = rng.choice(np.array([-1, 1], dtype=np.int8), size=(rows, cols))
+            ref_in = vals
+            dev = torch.from_numpy(vals).cuda()
+        else:
+            vals = rng.standard_normal((rows, cols)).astype(np.float32)
+            flat = vals.reshape(-1)
+            special = np.array([0.0, -0.0, np.inf, -np.inf, 1e-42, -1e-42], dtype=np.float32)
+            pos = rng.choice(flat.size, size=min(flat.size, special.size), replace=False)
+            flat[pos] = special[:pos.size]
+            t = torch.from_numpy(vals).to(tdt)
+            ref_in = t.to(torch.float32).numpy()           # the values the device sees after the type's rounding
+            dev = t.cuda()
+        words = torch.full((rows, (cols + 31) // 32), -1, dtype=torch.int32, device="cuda")
+        bad = torch.zeros(1, dtype=torch.int32, device="cuda")
+        nq.nq_pack_signs_device(dev, nq.DTYPE_BY_NAME[dtype], rows, cols, words, bad)
+        torch.cuda.synchronize()
+        got = words.cpu().numpy().view(np.uint32)
+        assert np.array_equal(got, oracle.pack_signs(ref_in)), (rows, cols)
+        assert int(bad.item()) == 0
+    # invalid elements: counted, packed as bit 0
+    if dtype == "i8":
+        bad_in = np.array([[1, 0, -1, 3, 1]], dtype=np.int8)
+        want_bits, n_bad = 0b10001, 2
+        dev = torch.from_numpy(bad_in).cuda()
+    else:
+        bad_in = np.array([[1.0, np.nan, -1.0, np.nan, 2.0]], dtype=np.float32)
+        want_bits, n_bad = 0b10001, 2
+        dev = torch.from_numpy(bad_in).to(tdt).cuda()
+    words = torch.zeros((1, 1), dtype=torch.int32, device="cuda")
+    bad = torch.zeros(1, dtype=torch.int32, device="cuda")
+    nq.nq_pack_signs_device(dev, nq.DTYPE_BY_NAME[dtype], 1, 5, words, bad)
+    torch.cuda.synchronize()
+    assert int(words.item()) == want_bits and int(bad.item()) == n_bad
+    nq.nq_pack_signs_device(dev, nq.DTYPE_BY_NAME[dtype], 1, 5, words, None)      # the counter is optional
+    torch.cuda.synchronize()
+
+
+def test_layer_built_from_device_latents_matches_host_built_layer():
+    """sign + pack on the GPU, create from device buffers: same bits (exported words) and the same
+    outputs, bit for bit, as the layer built from host-packed factors."""
+    import torch
+    d_out, d_in, r = 300, 520, 200
+    rng = np.random.default_rng(12)
+    lat_u = rng.standard_normal((d_out, r)).astype(np.float32)
+    lat_v = rng.standard_normal((d_in, r)).astype(np.float32)
+    s_out = synth.gen_scales(d_out, 121)
+    s_in = synth.gen_scales(d_in, 122)
+    Uw, Vw = oracle.pack_signs(lat_u), oracle.pack_signs(lat_v)
+    host = Layer(d_out, d_in, r, "bf16", data=synth.LayerData(synth.LinearShape("h", d_out, d_in, r), Uw, Vw, s_out, s_in))
+    wpr = (r + 31) // 32
+    du = torch.empty((d_out, wpr), dtype=torch.int32, device="cuda")
+    dv = torch.empty((d_in, wpr), dtype=torch.int32, device="cuda")
+    nq.nq_pack_signs_device(torch.from_numpy(lat_u).cuda(), nq.NQ_F32, d_out, r, du)
+    nq.nq_pack_signs_device(torch.from_numpy(lat_v).cuda(), nq.NQ_F32, d_in, r, dv)
+    h = nq.nq_binlr_create_from_device(d_out, d_in, r, du, dv, torch.from_numpy(s_out).cuda(),
+                                       torch.from_numpy(s_in).cuda(), nq.NQ_BF16)
+    eu, ev = nq.nq_binlr_export_words(h, d_out, d_in, r)
+    assert np.array_equal(eu, Uw) and np.array_equal(ev, Vw)
+    for batch in (1, 8, 70):
+        x = synth.gen_x(batch, d_in, 123 + batch, "bf16")
+        xd = to_device(x, "bf16")
+        y = new_output(batch, d_out)
+        nq.nq_binlr_forward(h, xd, y, batch)
+        torch.cuda.synchronize()
+        assert np.array_equal(y.cpu().numpy(), host.forward(x)), batch
+    nq.nq_binlr_destroy(h)
+    host.close()
+
+
 def test_integer_exact_mode_matches_bit_for_bit():
     # power-of-two scales and small-integer activations: every intermediate is an exact
     # integer multiple of a power of two, so fp64 oracle and GPU must agree exactly.

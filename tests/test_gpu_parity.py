@@ -174,6 +174,22 @@ def test_layer_built_from_device_latents_matches_host_built_layer():
     host.close()
 
 
+def test_input_gradient_is_the_forward_of_the_transposed_layer():
+    # dL/dx = s_in (.) (V (U^T (s_out (.) g))): the same operator with U and V, and the two scale
+    # vectors, exchanged -- checked against plain numpy on the unpacked factors
+    d_out, d_in, r = 260, 390, 150
+    data = synth.gen_layer(7, 0, 0, synth.LinearShape("g", d_out, d_in, r))
+    swapped = synth.LayerData(synth.LinearShape("gT", d_in, d_out, r), data.V_words, data.U_words, data.s_in, data.s_out)
+    LT = Layer(d_in, d_out, r, "f32", data=swapped)
+    U = oracle.unpack_signs(data.U_words, r).astype(np.float64)
+    V = oracle.unpack_signs(data.V_words, r).astype(np.float64)
+    for batch in (1, 6):
+        g = synth.gen_x(batch, d_out, 71 + batch, "f32")
+        want = ((g.astype(np.float64) * data.s_out.astype(np.float64)) @ U @ V.T) * data.s_in.astype(np.float64)
+        assert rel_err(LT.forward(g), want) <= DECODE_TOL
+    LT.close()
+
+
 def test_integer_exact_mode_matches_bit_for_bit():
     # power-of-two scales and small-integer activations: every intermediate is an exact
     # integer multiple of a power of two, so fp64 oracle and GPU must agree exactly.

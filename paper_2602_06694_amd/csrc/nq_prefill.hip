@@ -21,6 +21,7 @@
 // middle two elements of every aligned group of four swapped, so a plain 16-byte LDS read yields
 // the matching B operand.
 #include <algorithm>
+#include <cstdio>
 #include <type_traits>
 
 #include "nq_internal.h"
@@ -33,7 +34,6 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 typedef unsigned int v4u32 __attribute__((ext_vector_type(4)));
 
 constexpr int kPfTokens = 64;           // tokens per workgroup tile (4 MFMA column groups)
-constexpr int kPfTg = kPfTokens / 16;
 constexpr int kPfWaves = 4;             // waves per workgroup, one 128-row block each
 constexpr int kPfLdsStride = 72;        // halves per token row in LDS (64 + 8: conflict-free 16-byte reads)
 constexpr int kPfThreads = 64 * kPfWaves;
@@ -197,11 +197,17 @@ __device__ __forceinline__ uint32_t bfi_sign(uint32_t x, uint32_t one2)
     return d;
 }
 
-template <int EPI>
-__global__ void __launch_bounds__(kPfThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
+// TG = token groups of 16 per workgroup tile: 4 (64 tokens) normally; 2 (32 tokens) for narrow
+// outputs at small batches, where 64-token tiles are too few to cover the chip and splitting the
+// reduction instead would cost partial sums and a finalize pass (the sign expansion is then shared
+// by half as many MFMAs: lower efficiency per workgroup, but no extra passes).
+template <int EPI, int TG>
+__global__ void __launch_bounds__(kPfThreads) __attribute__((amdgpu_waves_per_eu(2, TG == 4 ? 2 : 4)))
 prefill_gemm_kernel(GemmArgs a)
 {
-    __shared__ __attribute__((aligned(16))) _Float16 lds_act[2][kPfTokens * kPfLdsStride];
+    static_assert(TG == 2 || TG == 4, "32- or 64-token tiles");
+    constexpr int kTok = 16 * TG;
+    __shared__ __attribute__((aligned(16))) _Float16 lds_act[2][kTok * kPfLdsStride];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -224,9 +230,9 @@ prefill_gemm_kernel(GemmArgs a)
     int rb = n_tile * kPfWaves + wave;
     const bool rb_valid = rb < a.n_rb;
     if (!rb_valid) rb = a.n_rb - 1;                        // keep loading valid memory, store nothing
-    const int m0 = m_tile * kPfTokens;
+    const int m0 = m_tile * kTok;
 
-    // activation tile: 64 tokens x 64 halves = 512 chunks of 16 bytes, 2 per thread:
+    // activation tile: 64 (32) tokens x 64 halves = 512 (256) chunks of 16 bytes, 2 (1) per thread:
     // chunk c = tid + 256 i  ->  token c / 8, 16-byte column c % 8
     const int ld_tok = tid >> 3, ld_kc = tid & 7;                       // chunk i adds 32 tokens
     const _Float16* act_ptr = a.act + (size_t)(m0 + ld_tok) * a.lda + (size_t)s_begin * 64 + ld_kc * 8;
@@ -234,43 +240,45 @@ prefill_gemm_kernel(GemmArgs a)
     const int lds_off = ld_tok * kPfLdsStride + ld_kc * 8;
     const v4u32* w_ptr = (const v4u32*)a.tiles + ((size_t)rb * a.nst + s_begin) * 64 + lane;
 
-    v4f acc[8][kPfTg];
+    v4f acc[8][TG];
 #pragma unroll
     for (int p = 0; p < 8; ++p)
 #pragma unroll
-        for (int tg = 0; tg < kPfTg; ++tg) acc[p][tg] = v4f{0.f, 0.f, 0.f, 0.f};
+        for (int tg = 0; tg < TG; ++tg) acc[p][tg] = v4f{0.f, 0.f, 0.f, 0.f};
 
     // two register sets for the activation chunks and the tile words: set (s & 1) belongs to step s
     // (named registers, not arrays: arrays that are written under a condition end up in LDS)
-    uint4 a00, a01, a10, a11;
+    uint4 a00, a01 = {0, 0, 0, 0}, a10, a11 = {0, 0, 0, 0};
     v4u32 wr0, wr1;
 #define PF_LOAD_ACT(R, step)                                                             \
     do {                                                                                 \
         const _Float16* q = act_ptr + (size_t)(step) * 64;                               \
         R##0 = *(const uint4*)(q);                                                       \
-        R##1 = *(const uint4*)(q + act_i);                                               \
+        if (TG == 4) R##1 = *(const uint4*)(q + act_i);                                  \
     } while (0)
 #define PF_STORE_ACT(buf, R)                                                             \
     do {                                                                                 \
         _Float16* q = &lds_act[buf][lds_off];                                            \
         *(uint4*)(q) = R##0;                                                             \
-        *(uint4*)(q + 32 * kPfLdsStride) = R##1;                                         \
+        if (TG == 4) *(uint4*)(q + 32 * kPfLdsStride) = R##1;                            \
     } while (0)
     // one reduction step on LDS buffer CUR with tile words W; the planes are kept in program
     // order (scheduling barriers) so that only one expanded operand is alive at a time
     uint32_t one2 = 0x3C003C00u;
     asm volatile("" : "+v"(one2));          // keep the constant in a vector register
     // B operands (activations of the 4 token groups) for one half step: two named register sets
-    v8h p0, p1, p2, p3;      // first half (reduction offsets 0..7 of each 16)
+    v8h p0, p1, p2 = {}, p3 = {};      // operands of one half step (reduction offsets 0..7 or 8..15 of each 16)
 #define PF_READ_B(R, BUF, H)                                                             \
     do {                                                                                 \
         const _Float16* lr = &lds_act[BUF][j * kPfLdsStride + 16 * g + 8 * (H)];         \
         R##0 = *(const v8h*)(lr);                                                        \
         R##1 = *(const v8h*)(lr + 1 * 16 * kPfLdsStride);                                \
-        R##2 = *(const v8h*)(lr + 2 * 16 * kPfLdsStride);                                \
-        R##3 = *(const v8h*)(lr + 3 * 16 * kPfLdsStride);                                \
+        if (TG == 4) {                                                                   \
+            R##2 = *(const v8h*)(lr + 2 * 16 * kPfLdsStride);                            \
+            R##3 = *(const v8h*)(lr + 3 * 16 * kPfLdsStride);                            \
+        }                                                                                \
     } while (0)
-#define PF_MFMA(P, TG, B) acc[P][TG] = __builtin_amdgcn_mfma_f32_16x16x32_f16(aop, B, acc[P][TG], 0, 0, 0)
+#define PF_MFMA(P, G, B) acc[P][G] = __builtin_amdgcn_mfma_f32_16x16x32_f16(aop, B, acc[P][G], 0, 0, 0)
     // one half step: 8 planes x 4 token groups.  w0 / w1 are the two tile words of this half.
     // The scheduler is asked to alternate one MFMA with one vector op, so that the expansion of
     // the next plane runs in the shadow of the current plane's MFMAs.
@@ -289,10 +297,11 @@ prefill_gemm_kernel(GemmArgs a)
         _Pragma("unroll") for (int p = 0; p < 8; ++p) {                                  \
             const v8h aop = __builtin_bit_cast(v8h, au_next);                            \
             if (p < 7) PF_EXPAND(au_next, p + 1, w0, w1);                                \
-            PF_MFMA(p, 0, R##0); PF_MFMA(p, 1, R##1); PF_MFMA(p, 2, R##2); PF_MFMA(p, 3, R##3); \
-            _Pragma("unroll") for (int i = 0; i < 4; ++i) {                              \
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   /* 1 MFMA  */       \
-                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);   /* 2 VALU  */       \
+            PF_MFMA(p, 0, R##0); PF_MFMA(p, 1, R##1);                                    \
+            if (TG == 4) { PF_MFMA(p, 2, R##2); PF_MFMA(p, 3, R##3); }                   \
+            _Pragma("unroll") for (int i = 0; i < TG; ++i) {                             \
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        /* 1 MFMA */   \
+                __builtin_amdgcn_sched_group_barrier(0x002, 8 / TG, 0);   /* its share of the 8 vector ops */ \
             }                                                                            \
             __builtin_amdgcn_sched_barrier(0);                                           \
         }                                                                                \
@@ -362,7 +371,7 @@ prefill_gemm_kernel(GemmArgs a)
     // result layout: lane (g, j), register v of acc[p][tg]  <->  C[token m0 + 16 tg + j][row 128 rb + 16 p + 4 g + v]
     // (the operands were negated signs, so every factor below carries a minus)
 #pragma unroll
-    for (int tg = 0; tg < kPfTg; ++tg) {
+    for (int tg = 0; tg < TG; ++tg) {
         const int tok = m0 + tg * 16 + j;
 #pragma unroll
         for (int p = 0; p < 8; ++p) {
@@ -471,37 +480,48 @@ static size_t al256(size_t v) { return (v + 255) / 256 * 256; }
 struct PfLayout {
     int m_pad, k1, k2, n1_pad, n2_pad;
     int splits1, splits2;
+    int tg1, tg2;             // token groups of 16 per workgroup tile of the two GEMMs (4 or 2)
     size_t off_x, off_t, off_scale, off_partial, total;
 };
 
-// Split the reduction over `s` workgroups when the output alone gives too few workgroups to cover
-// the chip.  Cost model in units of one reduction step of one workgroup: rounds over the CUs times
-// steps per split, plus the write and re-read of the fp32 partial sums.
-static int choose_splits(int m_tiles, int n_tiles, int nst, int m_pad, int n_pad)
+// Tiling of one GEMM: token groups per workgroup tile (4 = 64 tokens, 2 = 32 tokens) and the number of
+// workgroups the reduction is split over, for outputs that alone give too few workgroups to
+// cover the chip.  Cost model in microseconds, constants measured on the 70B MLP shapes:
+//  - a reduction step of a 64-token workgroup takes 0.73 us when it has its CU to itself and
+//    1.17 us when two share one (two is all that fits);
+//  - a 32-token workgroup needs 0.60 us per step alone (the sign expansion is not halved), and a
+//    CU completes at most 3.9 of their steps per microsecond (up to four fit);
+//  - splitting costs a finalize launch (2 us) plus, per split, the write and re-read of one set of
+//    fp32 partial sums, not overlapped with anything: about 2.3 MB per microsecond.
+struct GemmTiling { int tg, splits; };
+static GemmTiling choose_tiling(int m_pad, int n_rb, int nst, int n_pad)
 {
-    const int wgs = m_tiles * n_tiles;
     const int cus = device_cu_count();
-    // measured on the 70B MLP shapes: one reduction step of a workgroup takes 0.73 us when it has
-    // its CU to itself and 1.17 us when two share one; a split costs the write and re-read of one
-    // set of fp32 partial sums, which mostly stay in the last-level cache (about 7.7 MB/us)
-    const double alone_us = 0.73, shared_us = 1.17, partial_bytes_per_us = 7.7e6;
-    int best = 1;
+    const int n_tiles = (n_rb + kPfWaves - 1) / kPfWaves;
+    const double partial_us = (double)m_pad * n_pad * 4.0 / 2.3e6;
+    GemmTiling best = {4, 1};
     double best_cost = 1e30;
-    for (int s = 1; s <= 16; ++s) {
-        int per = (nst + s - 1) / s;
-        per += per & 1;
-        if (s > 1 && per < 8) break;
-        const int total = wgs * s;
-        double cost;
-        if (total <= cus) {
-            cost = per * alone_us;
-        } else {
-            const int full = total / (2 * cus), rem = total % (2 * cus);
-            cost = (double)full * per * shared_us;
-            if (rem) cost += per * (rem <= cus ? alone_us : shared_us);
+    for (int tg = 4; tg >= 2; tg -= 2) {
+        const int wgs = (m_pad / (16 * tg)) * n_tiles;
+        const int per_cu = tg == 4 ? 2 : 4;
+        for (int s = 1; s <= 16; ++s) {
+            int per = (nst + s - 1) / s;
+            per += per & 1;
+            if (s > 1 && per < 8) break;
+            const int total = wgs * s;
+            // 32-token tiles were measured, and pay, only where they let an unsplit GEMM cover the chip
+            if (tg == 2 && (s > 1 || total > cus)) break;
+            // workgroups per CU in full rounds, then in the last, partial one
+            auto step_us = [&](int k) {
+                if (tg == 4) return k <= 1 ? 0.73 : 1.17;
+                return std::max(0.60, k / 3.9);
+            };
+            const int full = total / (per_cu * cus), rem = total % (per_cu * cus);
+            double cost = (double)full * per * step_us(per_cu);
+            if (rem) cost += per * step_us((rem + cus - 1) / cus);
+            if (s > 1) cost += 2.0 + s * partial_us;
+            if (cost < best_cost) { best_cost = cost; best = {tg, s}; }
         }
-        if (s > 1) cost += s * 2.0 * (double)m_pad * n_pad * 4.0 / partial_bytes_per_us;
-        if (cost < best_cost) { best_cost = cost; best = s; }
     }
     return best;
 }
@@ -521,9 +541,17 @@ static PfLayout pf_layout(int64_t d_out, int64_t d_in, int64_t r, int batch)
     L.k2 = (int)n_steps(r) * 64;
     L.n1_pad = (int)n_rowblocks(r) * kTileRows;
     L.n2_pad = (int)n_rowblocks(d_out) * kTileRows;
-    const int m_tiles = L.m_pad / kPfTokens;
-    L.splits1 = getenv("NQ_PF_SPLITS1") ? atoi(getenv("NQ_PF_SPLITS1")) : choose_splits(m_tiles, (int)((n_rowblocks(r) + kPfWaves - 1) / kPfWaves), (int)n_steps(d_in), L.m_pad, L.n1_pad);
-    L.splits2 = choose_splits(m_tiles, (int)((n_rowblocks(d_out) + kPfWaves - 1) / kPfWaves), (int)n_steps(r), L.m_pad, L.n2_pad);
+    const GemmTiling t1 = choose_tiling(L.m_pad, (int)n_rowblocks(r), (int)n_steps(d_in), L.n1_pad);
+    const GemmTiling t2 = choose_tiling(L.m_pad, (int)n_rowblocks(d_out), (int)n_steps(r), L.n2_pad);
+    L.tg1 = t1.tg; L.splits1 = t1.splits;
+    L.tg2 = t2.tg; L.splits2 = t2.splits;
+    if (getenv("NQ_PF_VERBOSE"))
+        fprintf(stderr, "prefill tiling B=%d: gemm1 tg=%d splits=%d, gemm2 tg=%d splits=%d\n", batch, L.tg1, L.splits1, L.tg2,
+                L.splits2);
+    if (getenv("NQ_PF_TG1")) L.tg1 = atoi(getenv("NQ_PF_TG1")) == 2 ? 2 : 4;
+    if (getenv("NQ_PF_TG2")) L.tg2 = atoi(getenv("NQ_PF_TG2")) == 2 ? 2 : 4;
+    if (getenv("NQ_PF_SPLITS1")) L.splits1 = std::max(1, atoi(getenv("NQ_PF_SPLITS1")));
+    if (getenv("NQ_PF_SPLITS2")) L.splits2 = std::max(1, atoi(getenv("NQ_PF_SPLITS2")));
     size_t o = 0;
     L.off_x = o; o += al256((size_t)L.m_pad * L.k1 * 2);
     L.off_t = o; o += al256((size_t)L.m_pad * L.k2 * 2);
@@ -553,16 +581,18 @@ prefill_zero_cols_kernel(_Float16* __restrict__ m, int ld, int c0, int c1, int r
 }
 
 template <int EPI>
-static int run_gemm(const GemmArgs& a, hipStream_t s)
+static int run_gemm(const GemmArgs& a, int tg, hipStream_t s)
 {
     dim3 grid(a.m_tiles * a.n_tiles, a.splits);
     if (a.splits > 1) {
-        hipLaunchKernelGGL((prefill_gemm_kernel<EPI_PARTIAL>), grid, dim3(kPfThreads), 0, s, a);
+        if (tg == 4) hipLaunchKernelGGL((prefill_gemm_kernel<EPI_PARTIAL, 4>), grid, dim3(kPfThreads), 0, s, a);
+        else hipLaunchKernelGGL((prefill_gemm_kernel<EPI_PARTIAL, 2>), grid, dim3(kPfThreads), 0, s, a);
         NQ_HIP(hipGetLastError());
         const size_t total = (size_t)a.m_pad * (a.n_pad / 4);
         hipLaunchKernelGGL((prefill_finalize_kernel<EPI>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, a);
     } else {
-        hipLaunchKernelGGL((prefill_gemm_kernel<EPI>), grid, dim3(kPfThreads), 0, s, a);
+        if (tg == 4) hipLaunchKernelGGL((prefill_gemm_kernel<EPI, 4>), grid, dim3(kPfThreads), 0, s, a);
+        else hipLaunchKernelGGL((prefill_gemm_kernel<EPI, 2>), grid, dim3(kPfThreads), 0, s, a);
     }
     NQ_HIP(hipGetLastError());
     return NQ_OK;
@@ -587,7 +617,6 @@ int launch_prefill(const PrefillArgs& p, hipStream_t s)
 
     GemmArgs a{};
     a.m_pad = L.m_pad;
-    a.m_tiles = L.m_pad / kPfTokens;
     a.batch = p.batch;
     a.partial = partial;
     // gemm1: T = X'' V
@@ -597,7 +626,8 @@ int launch_prefill(const PrefillArgs& p, hipStream_t s)
     a.n_tiles = (a.n_rb + kPfWaves - 1) / kPfWaves;
     a.splits = L.splits1; a.steps_per_split = even_steps_per_split(a.nst, a.splits);
     a.n_pad = L.n1_pad;
-    int rc = run_gemm<EPI_T>(a, s);
+    a.m_tiles = L.m_pad / (16 * L.tg1);
+    int rc = run_gemm<EPI_T>(a, L.tg1, s);
     if (rc != NQ_OK) return rc;
     if (L.k2 > L.n1_pad) {
         // columns of T beyond the last 128-row block of gemm1 are padding of gemm2's reduction:
@@ -614,7 +644,8 @@ int launch_prefill(const PrefillArgs& p, hipStream_t s)
     a.n_tiles = (a.n_rb + kPfWaves - 1) / kPfWaves;
     a.splits = L.splits2; a.steps_per_split = even_steps_per_split(a.nst, a.splits);
     a.n_pad = L.n2_pad;
-    return run_gemm<EPI_Y>(a, s);
+    a.m_tiles = L.m_pad / (16 * L.tg2);
+    return run_gemm<EPI_Y>(a, L.tg2, s);
 }
 
 }  // namespace nq

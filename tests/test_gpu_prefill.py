@@ -27,6 +27,24 @@ def test_prefill_small_shapes(shape, x_dtype):
     L.close()
 
 
+@pytest.mark.parametrize("splits", [None, "3"])
+def test_prefill_32_token_tiles_and_forced_splits(monkeypatch, splits):
+    # the tiling of the two GEMMs is chosen by a cost model; force the variants it rarely picks on
+    # small inputs: 32-token workgroup tiles, with and without a split reduction
+    monkeypatch.setenv("NQ_PF_TG1", "2")
+    monkeypatch.setenv("NQ_PF_TG2", "2")
+    if splits:
+        monkeypatch.setenv("NQ_PF_SPLITS1", splits)
+        monkeypatch.setenv("NQ_PF_SPLITS2", splits)
+    for shape in [(300, 200, 100), (640, 1500, 257), (1024, 2048, 1024)]:
+        L = Layer(*shape, "bf16", seed=61)
+        for batch in (9, 64, 100, 200):
+            x = synth.gen_x(batch, shape[1], 600 + batch, "bf16", outlier_frac=0.01)
+            err = rel_err(L.forward(x), L.oracle(x))
+            assert err <= PREFILL_TOL, (shape, batch, err)
+        L.close()
+
+
 def test_prefill_matches_streaming_path():
     d_out, d_in, r = 512, 768, 192
     x = synth.gen_x(96, d_in, 5, "bf16")

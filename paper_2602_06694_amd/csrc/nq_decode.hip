@@ -354,15 +354,18 @@ int launch_pack_signs(const void* d_signs, int dtype, int64_t rows, int64_t cols
 // streaming sign-matrix x fixed-point-vector kernels (steps a2 and a4, with a5 fused in stage 2)
 //   NB : number of 16-column groups of the B operand (1: batch <= 5, 2: batch 6..8)
 //   D  : software prefetch ring (tiles per wave; D-1 stay in flight while one is consumed)
-// Two schedules over the same tiles:
-//   stage_stream_kernel : one wave per work item.  An item is a run of consecutive 128-row blocks
-//       of one op; their tiles are contiguous in memory, so the prefetch ring keeps running across
-//       block boundaries and only the accumulators are flushed there.  For short reductions.
+// Three schedules over the same tiles:
+//   stage_stream_kernel : one wave per work item.  An item is a row block, or a run of a few
+//       consecutive short ones of one op; their tiles are contiguous in memory, so the prefetch
+//       ring keeps running across block boundaries and only the accumulators are flushed there.
+//       For short reductions.
 //   stage_split_kernel<W> : W waves of one workgroup interleave the 64-column steps of ONE row
 //       block and are summed through LDS.  For long reductions, and for launches with too few row
 //       blocks to fill the chip.
-// Either way a grid as large as the item list makes the hardware workgroup dispatcher the work
-// queue (the list is sorted longest first).
+//   stage_shared_kernel : eight waves take row blocks of one op and share its quantised input
+//       through LDS (further down).  For two column groups in launches that fill the chip.
+// In all of them a grid as large as the item list makes the hardware workgroup dispatcher the
+// work queue (the list is sorted longest first).
 // ---------------------------------------------------------------------------------------------
 #ifndef NQ_STAGE_WAVES
 #define NQ_STAGE_WAVES 5
@@ -426,7 +429,7 @@ constexpr int kStreamMaxRbs = 8;
 
 // raw accumulators -> LDS [col][row] -> one thread per (token, row): undo the plane weights,
 // join the three byte slices, apply 2*sum(b q) - sum(q), the step and the output scale.
-// The 128 rows x ncols results pass through LDS in pieces of 64 rows (four bit planes) x one
+// The 128 rows x (3 columns per token) results pass through LDS in pieces of 64 rows (four bit planes) x one
 // column group, so that the LDS a wave holds (and with it the number of resident waves) does not
 // grow with the batch.
 // W = 1: `lds` is this wave's private region and only the wave synchronises;

@@ -173,8 +173,38 @@ def time_stack(cfg, batch, steps=10, warmup=2):
     for _ in range(5):
         pk += np.array(nq.nq_plan_forward_timed(plan))
     pk /= 5
+    # the same stack as a plain loop of single-layer calls (four launches per layer on one stream),
+    # eagerly and as a HIP-graph replay of that loop
+    def loop():
+        for h, x, y in zip(handles, xs, ys):
+            nq.nq_binlr_forward(h, x, y, batch)
+    prewarm(loop, 0.02)
+    t0 = time.perf_counter()
+    for _ in range(3):
+        loop()
+    torch.cuda.synchronize()
+    ms_loop = (time.perf_counter() - t0) * 1e3 / 3
+    ms_graph = None
+    try:
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            loop()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            loop()
+        prewarm(graph.replay, 0.02)
+        t0 = time.perf_counter()
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        ms_graph = (time.perf_counter() - t0) * 1e3 / 3
+        del graph
+    except Exception as e:                     # report, do not hide
+        ms_graph = f"capture failed: {e}"
     res = {"layers": len(handles), "ms_per_step": ms, "weight_GBps": wbytes / ms / 1e6,
            "tokens_per_s": batch / (ms * 1e-3),
+           "ms_per_step_loop_of_single_calls": ms_loop, "ms_per_step_hip_graph_of_that_loop": ms_graph,
            "kernel_ms": {"quantize_x": pk[0], "stage1": pk[1], "quantize_t": pk[2], "stage2": pk[3]},
            "stage1_GBps": sb1 / pk[1] / 1e6, "stage2_GBps": sb2 / pk[3] / 1e6,
            "stage1_frac_of_hbm_peak": sb1 / pk[1] / 1e6 / HBM_PEAK_GBPS,

@@ -481,8 +481,16 @@ static int decode_once(nq_handle h, const void* x, void* y, int batch, hipStream
     const int w1 = stage_schedule(rb1, s1.n_steps, batch), w2 = stage_schedule(rb2, s2.n_steps, batch);
     const int per1 = w1 == 1 ? rbs_per_stream_item(rb1, s1.n_steps, rb1, batch) : 1;
     const int per2 = w2 == 1 ? rbs_per_stream_item(rb2, s2.n_steps, rb2, batch) : 1;
-    if ((rc = launch_quantize(nullptr, qx, 1, qx.n_chunks, batch, s)) != NQ_OK) return rc;
-    if ((rc = launch_stage(nullptr, s1, nullptr, (rb1 + per1 - 1) / per1, w1, per1, batch, s)) != NQ_OK) return rc;
+    // a lone layer is bound by launch latency: where the quantised input of a stage fits LDS, the
+    // stage quantises it itself (two launches per forward instead of four)
+    static const bool no_fuse = getenv("NQ_NO_FUSE") != nullptr;
+    if (!no_fuse && fused_fits(s1.n_steps, batch)) {
+        if ((rc = launch_fused(qx, s1, s)) != NQ_OK) return rc;
+    } else {
+        if ((rc = launch_quantize(nullptr, qx, 1, qx.n_chunks, batch, s)) != NQ_OK) return rc;
+        if ((rc = launch_stage(nullptr, s1, nullptr, (rb1 + per1 - 1) / per1, w1, per1, batch, s)) != NQ_OK) return rc;
+    }
+    if (!no_fuse && fused_fits(s2.n_steps, batch)) return launch_fused(qt, s2, s);
     if ((rc = launch_quantize(nullptr, qt, 1, qt.n_chunks, batch, s)) != NQ_OK) return rc;
     return launch_stage(nullptr, s2, nullptr, (rb2 + per2 - 1) / per2, w2, per2, batch, s);
 }

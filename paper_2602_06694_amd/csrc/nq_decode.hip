@@ -944,6 +944,134 @@ stage_shared_kernel(const StageDesc* __restrict__ descs, const WorkItem* __restr
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Fourth schedule, for ONE layer on its own at batch 1 (nq_binlr_forward): a stage and the
+// quantisation of its input in a single launch, so that a forward is two dependent launches
+// instead of four -- a lone layer is bound by launch latency (about 4 us per dependent launch),
+// not by bandwidth.  One workgroup of 16 waves per row block, as in the split kernel; every
+// workgroup quantises the whole input vector for itself (one chunk of 16 values per thread, kept
+// in registers between the max pass and the quantising pass) into LDS, in the layout of the
+// global one, while its first tiles are already in flight; the MFMA B operands then come from
+// LDS.  The arithmetic is that of quantize_kernel + stage_split_kernel, element for element, so
+// the results are bit-identical.  Only for inputs of at most 16384 elements (fused_fits()).
+// LDS: quantised input, overlaid after the reduction by [16][kEpiRegion] | scratch.
+// ---------------------------------------------------------------------------------------------
+constexpr int kFusedWaves = 16;
+constexpr int kFusedScratchInts = 64;
+
+__host__ __device__ inline size_t fused_lds_bytes(int nst)
+{
+    const size_t bq = (size_t)nst * kBqStepBytes, epi = (size_t)kFusedWaves * kEpiRegion * 4;
+    return (bq > epi ? bq : epi) + kFusedScratchInts * 4;
+}
+
+__global__ void __launch_bounds__(64 * kFusedWaves) __attribute__((amdgpu_waves_per_eu(4, 8)))
+stage_fused_kernel(QuantDesc qd, StageDesc sd)
+{
+    extern __shared__ int lds[];
+    constexpr int W = kFusedWaves;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4, n = lane & 15;
+    const int rb = blockIdx.x;
+    const int nst = sd.n_steps;
+    char* const lds_bq = (char*)lds;
+    const size_t main_bytes = fused_lds_bytes(nst) - kFusedScratchInts * 4;
+    float* const red_f = (float*)((char*)lds + main_bytes);                 // [W] partial maxima
+    int* const red_bad = (int*)(red_f + W);                                 // the token holds a non-finite value
+    double* const red_d = (double*)(red_f + W + 2);                         // [W] partial sums of q
+    static_assert((kFusedWaves + 2) * 4 + kFusedWaves * 8 <= kFusedScratchInts * 4, "scratch region");
+
+    // this wave's steps: wave, wave + W, ...; the first up to four tiles go out before anything else
+    const int cnt = (nst - wave + W - 1) / W;
+    const char* a_base = (const char*)sd.tiles + (size_t)rb * nst * (kTileWords * 4);
+    v4u wbuf[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int st = cnt > 0 ? wave + (k < cnt ? k : cnt - 1) * W : 0;
+        wbuf[k] = load_tile_words(a_base, (uint32_t)(st * 1024 + lane * 16));
+    }
+
+    // ---- quantise the input vector (as quantize_kernel does): thread tid owns chunk tid ----
+    const int esz = qd.dtype == NQ_F32 ? 4 : 2;
+    const bool vec = (((size_t)qd.x_stride * esz) & 15) == 0;
+    const bool mine = tid < qd.n_chunks;
+    float v[16];
+    float m = 0.f;
+    int bad = 0;
+    if (tid == 0) *red_bad = 0;
+    if (mine) {
+        load_chunk16(qd, 0, tid, vec, v);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const float a = fabsf(v[i]);
+            if (!(a <= 3.0e38f)) bad = 1;
+            m = fmaxf(m, a);
+        }
+    }
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    if (lane == 0) red_f[wave] = m;
+    __syncthreads();
+    if (bad) *red_bad = 1;
+    __syncthreads();
+    m = red_f[0];
+#pragma unroll
+    for (int w = 1; w < W; ++w) m = fmaxf(m, red_f[w]);
+    bad = *red_bad;
+    int e = 0;
+    float step = 1.0f;
+    if (m > 0.f && !bad) {
+        (void)frexpf(m, &e);
+        int se = e - 22;
+        se = se < -126 ? -126 : se;
+        step = ldexpf(1.0f, se);
+    }
+    const float inv_step = 1.0f / step;
+    long long local_sum = 0;
+    if (mine) local_sum = quantize_chunk16(v, inv_step, bad != 0, (uint4*)lds_bq + bq_piece(tid, 0));
+    double sum = (double)local_sum;
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+    if (lane == 0) red_d[wave] = sum;
+    __syncthreads();
+    if (tid == 0) {
+        double tot = 0.0;
+        for (int w = 0; w < W; ++w) tot += red_d[w];
+        // (the same values from every workgroup; plain member stores into global memory)
+        __attribute__((address_space(1))) QMeta* mt = (__attribute__((address_space(1))) QMeta*)qd.meta;
+        mt->sumq = tot;
+        mt->step = bad ? __builtin_nanf("") : step;
+        mt->pad = 0.f;
+    }
+    // the epilogue reads the per-token constants through scalar loads: this workgroup's own copy
+    // must have reached L2 before (workgroup-scope release = wait for the stores, no cache write-back)
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+
+    // ---- the reduction over this wave's steps, operands from LDS ----
+    const uint32_t b_lds = (uint32_t)(bq_piece(g, n < 3 ? n : 0) * 16);      // token 0; unused columns re-read slice 0
+    v4i acc[1][8];
+#pragma unroll
+    for (int p = 0; p < 8; ++p) acc[0][p] = v4i{0, 0, 0, 0};
+    for (int i0 = 0; i0 < cnt; i0 += 4) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (i0 + k < cnt) {
+                const int st = wave + (i0 + k) * W;
+                v4u b[1];
+                b[0] = *(const v4u*)(lds_bq + b_lds + st * (int)kBqStepBytes);
+                mac_tile<1>(acc, wbuf[k], b);
+                if (i0 + k + 4 < cnt) wbuf[k] = load_tile_words(a_base, (uint32_t)((st + 4 * W) * 1024 + lane * 16));
+            }
+        }
+    }
+    __syncthreads();                                       // the epilogue regions overlay the quantised input
+    EpilogueArgs ea;
+    ea.meta = sd.meta; ea.out_scale = sd.out_scale; ea.out = sd.out;
+    ea.M = sd.M; ea.out_stride = sd.out_stride; ea.out_dtype = sd.out_dtype;
+    stage_epilogue<1, W, false>(acc, lds, wave, lane, 1, rb, ea, nullptr);
+}
+
 #undef NQ_LOAD_ITEM
 
 static int g_cu_count = 0;
@@ -1027,6 +1155,22 @@ static int launch_shared_t(const StageDesc* d_descs, const WorkItem* d_items, in
     }
     hipLaunchKernelGGL((stage_shared_kernel<NB>), dim3(n_items), dim3(64 * kShareWaves), lds_bytes, s, d_descs, d_items,
                        n_items, per_max, batch);
+    NQ_HIP(hipGetLastError());
+    return NQ_OK;
+}
+
+// One stage of a lone layer at batch 1 together with the quantisation of its input (stage_fused_kernel).
+bool fused_fits(int nst, int batch) { return batch == 1 && nst * 4 <= 64 * kFusedWaves; }
+
+int launch_fused(const QuantDesc& q, const StageDesc& sd, hipStream_t s)
+{
+    static bool attr_set = false;
+    if (!attr_set) {
+        NQ_HIP(hipFuncSetAttribute((const void*)stage_fused_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(stage_fused_kernel, dim3((unsigned)n_rowblocks(sd.M)), dim3(64 * kFusedWaves),
+                       fused_lds_bytes(sd.n_steps), s, q, sd);
     NQ_HIP(hipGetLastError());
     return NQ_OK;
 }

@@ -131,6 +131,8 @@ int shared_per_wave(int nst, int batch); // row blocks per wave of an item of th
 // per item); w = kSharedSchedule: shared-input kernel (items of up to 8 x shared_per_wave row blocks)
 int launch_stage(const StageDesc* d_descs, const StageDesc& single, const WorkItem* d_items, int n_items,
                  int w, int rbs_per_item, int batch, hipStream_t s);
+bool fused_fits(int nst, int batch);     // the quantised input of a stage fits the LDS of the fused kernel
+int launch_fused(const QuantDesc& q, const StageDesc& sd, hipStream_t s);
 int launch_valu_gemv(const uint32_t* tiles, const void* x, int x_dtype, int x_stride, const uint16_t* in_scale,
                      const uint16_t* out_scale, void* out, int out_dtype, int out_stride, int64_t M, int64_t N,
                      int batch, hipStream_t s);

@@ -481,6 +481,29 @@ def test_sixteen_bit_outputs_are_the_rounded_exact_result():
         L.close()
 
 
+def test_single_call_and_plan_give_identical_bits():
+    """nq_binlr_forward runs a lone layer as two launches that quantise their input themselves;
+    plans run separate quantisation launches.  Same arithmetic, element for element: the outputs
+    (and the intermediate t) must be identical bit for bit.  The last shape is too long for the
+    fused launches' LDS and takes the four-launch path in nq_binlr_forward as well."""
+    import torch
+    for shape in [(300, 200, 100), (129, 65, 33), (4096, 4096, 1024), (640, 1500, 257), (200, 60000, 96)]:
+        L = Layer(*shape, "bf16", seed=700)
+        for batch in (1, 4, 8):
+            x_np = synth.gen_x(batch, shape[1], 710 + batch, "bf16")
+            y_single = L.forward(x_np)
+            t_single = nq.nq_binlr_read_intermediate(L.h, shape[2], batch)
+            x = to_device(x_np, "bf16")
+            y = new_output(batch, shape[0])
+            plan = nq.nq_plan_create([L.h], [x], [y], batch)
+            nq.nq_plan_forward(plan)
+            torch.cuda.synchronize()
+            assert np.array_equal(nq.nq_binlr_read_intermediate(L.h, shape[2], batch), t_single), (shape, batch)
+            assert np.array_equal(y.cpu().numpy(), y_single), (shape, batch)
+            nq.nq_plan_destroy(plan)
+        L.close()
+
+
 def test_forward_error_paths():
     import torch
     L = Layer(64, 64, 32, "bf16", seed=1)

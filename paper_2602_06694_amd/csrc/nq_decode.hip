@@ -162,22 +162,35 @@ __device__ inline void load_chunk16(const QuantDesc& d, int64_t base, int c, boo
     }
 }
 
+// byte 0 of a, b, c, d -> one word (a lowest): three byte-permute instructions
+__device__ __forceinline__ uint32_t pack_low_bytes(uint32_t a, uint32_t b, uint32_t c, uint32_t d)
+{
+    const uint32_t ab = __builtin_amdgcn_perm(b, a, 0x0c0c0400u);      // bytes: a.0, b.0, 0, 0
+    const uint32_t cd = __builtin_amdgcn_perm(d, c, 0x0c0c0400u);
+    return __builtin_amdgcn_perm(cd, ab, 0x05040100u);                 // ab.0, ab.1, cd.0, cd.1
+}
+
+// q = 65536 hi + 256 mid + lo with signed bytes: lo is the (sign-extended) low byte of q,
+// mid that of q1 = (q - lo) / 256 = (q + 128) >> 8, hi = (q1 + 128) >> 8; only the low bytes are kept
 __device__ inline long long quantize_chunk16(const float v[16], float inv_step, bool bad, uint4* dst)
 {
-    uint32_t hi[4] = {0, 0, 0, 0}, mid[4] = {0, 0, 0, 0}, lo[4] = {0, 0, 0, 0};
+    uint32_t hi[4], mid[4], lo[4];
     int sum = 0;                                            // |q| <= 2^22, 16 of them: fits
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int q = bad ? 0 : (int)rintf(v[i] * inv_step);
-        sum += q;
-        const int l = ((q + 128) & 255) - 128;
-        const int q1 = (q - l) >> 8;
-        const int mm = ((q1 + 128) & 255) - 128;
-        const int h = (q1 - mm) >> 8;
-        const int sh = 8 * (i & 3);
-        hi[i >> 2] |= (uint32_t)(h & 255) << sh;
-        mid[i >> 2] |= (uint32_t)(mm & 255) << sh;
-        lo[i >> 2] |= (uint32_t)(l & 255) << sh;
+    for (int w = 0; w < 4; ++w) {
+        uint32_t q0[4], q1[4], q2[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int q = bad ? 0 : (int)rintf(v[4 * w + i] * inv_step);
+            sum += q;
+            const int m = (q + 128) >> 8;
+            q0[i] = (uint32_t)q;
+            q1[i] = (uint32_t)m;
+            q2[i] = (uint32_t)((m + 128) >> 8);
+        }
+        lo[w] = pack_low_bytes(q0[0], q0[1], q0[2], q0[3]);
+        mid[w] = pack_low_bytes(q1[0], q1[1], q1[2], q1[3]);
+        hi[w] = pack_low_bytes(q2[0], q2[1], q2[2], q2[3]);
     }
     // the three slices of a chunk sit 4 pieces apart (see bq_piece): consecutive threads = consecutive
     // chunks of a step fill whole 64-byte lines with each of the three stores

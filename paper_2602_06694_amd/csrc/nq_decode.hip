@@ -294,9 +294,8 @@ quantize_kernel(const QuantDesc* __restrict__ descs, QuantDesc single, int batch
         QMeta mt;
         double tot = 0.0;
         for (int w = 0; w < kQuantThreads / 64; ++w) tot += smd[w];
-        mt.sumq = tot;
-        mt.step = bad ? __builtin_nanf("") : step;
-        mt.pad = 0.f;
+        mt.two_step = bad ? (double)__builtin_nanf("") : 2.0 * (double)step;
+        mt.neg_qs = -tot * (double)step;
         d.meta[tok] = mt;
     }
 }
@@ -471,7 +470,11 @@ __device__ __forceinline__ void stage_epilogue(const v4i (&acc)[NB][8], int* lds
             if (n < 3 * tg) {
                 v4i* dst = (v4i*)(my_lds + n * 64 + 4 * g);
 #pragma unroll
-                for (int p = 0; p < 4; ++p) dst[4 * p] = acc[cg][4 * hf + p];     // rows 16p + 4g .. +3 of the half
+                for (int p = 0; p < 4; ++p) {
+                    // plane 7 (the int8 sign bit) holds -128 * sum: stored negated, so that every plane p reads 2^p * sum
+                    const v4i a = acc[cg][4 * hf + p];
+                    dst[4 * p] = (4 * hf + p == 7) ? -a : a;                       // rows 16p + 4g .. +3 of the half
+                }
             }
             if (W == 1) {
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
@@ -484,11 +487,10 @@ __device__ __forceinline__ void stage_epilogue(const v4i (&acc)[NB][8], int* lds
             const int row = lane;
             const int r128 = 64 * hf + row;
             const int grow = rb * kTileRows + r128;
-            // plane p holds 2^p * sum (p < 7) or -128 * sum (p = 7, the int8 sign bit): exact shifts
-            const int p = 4 * hf + (row >> 4);
+            const int neg_p = -(4 * hf + (row >> 4));                 // this row's sums carry the weight 2^p of its plane
             float oscale = 1.0f;
             if (!DEFER && e.out_scale && grow < e.M) oscale = half_bits_to_float(((gptr_u16)e.out_scale)[grow]);
-            for (int tl = wave; tl < tg; tl += W) {
+            auto one_token = [&](int tl) {
                 int h = 0, m = 0, l = 0;
 #pragma unroll
                 for (int w = 0; w < W; ++w) {
@@ -497,26 +499,19 @@ __device__ __forceinline__ void stage_epilogue(const v4i (&acc)[NB][8], int* lds
                     m += q[64];
                     l += q[128];
                 }
-                h >>= p;
-                m >>= p;
-                l >>= p;
-                if (p == 7) {
-                    h = -h;
-                    m = -m;
-                    l = -l;
-                }
-                const double bsum = fma((double)h, 65536.0, fma((double)m, 256.0, (double)l));   // sum_n b_n q_n
+                // sum_n b_n q_n = (65536 h + 256 m + l) * 2^-p: the raw sums are below 2^30, so
+                // every step is exact in fp64, and the plane's weight rides on the token's step
+                const double raw = fma((double)h, 65536.0, fma((double)m, 256.0, (double)l));
                 const int tok = 5 * cg + tl;
-                const double sumq = meta[tok].sumq;
-                const float step = meta[tok].step;
-                double val = (2.0 * bsum - sumq) * (double)step;
+                double val = fma(raw, __builtin_ldexp(meta[tok].two_step, neg_p), meta[tok].neg_qs);   // exact; rounded once, below
                 if (DEFER) {
                     lds_out[tok * kTileRows + r128] = (float)val;       // scaled by s_out when flushed
                 } else if (grow < e.M) {
                     val *= (double)oscale;
                     store_out(e.out, e.out_dtype, (size_t)tok * e.out_stride + grow, (float)val);
                 }
-            }
+            };
+            for (int tl = wave; tl < tg; tl += W) one_token(tl);
             if (W == 1) {
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
                 __builtin_amdgcn_wave_barrier();
@@ -559,13 +554,21 @@ __device__ __forceinline__ void stream_flush(int* lds, const float* lds_out, int
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    // one loop per output type: the type is the same for the whole item
+    // one loop nest per output type (the type is the same for the whole item): a lane keeps its row
+    // of each half of a row block and walks the tokens, so that an element costs one LDS read, one
+    // multiplication and one store
     auto store_all = [&](auto store) {
-        for (int o = lane; o < n_rb * kTileRows * batch; o += 64) {
-            const int u = o / (kTileRows * batch), rem = o - u * (kTileRows * batch);
-            const int tok = rem >> 7, row = rem & (kTileRows - 1);
-            const int grow = (rb0 + u) * kTileRows + row;
-            if (grow < ea.M) store((size_t)tok * ea.out_stride + grow, lds_out[o] * lds_sc[u * kTileRows + row]);
+        for (int u = 0; u < n_rb; ++u) {
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+                const int row = 64 * hf + lane;
+                const int grow = (rb0 + u) * kTileRows + row;
+                if (grow >= ea.M) continue;
+                const float sc = lds_sc[u * kTileRows + row];
+                const float* src = lds_out + u * (kTileRows * batch) + row;
+                size_t idx = (size_t)grow;
+                for (int tok = 0; tok < batch; ++tok, idx += (size_t)ea.out_stride) store(idx, src[tok * kTileRows] * sc);
+            }
         }
     };
     typedef __attribute__((address_space(1))) float* gptr_f32;
@@ -1052,9 +1055,8 @@ stage_fused_kernel(QuantDesc qd, StageDesc sd)
         for (int w = 0; w < W; ++w) tot += red_d[w];
         // (the same values from every workgroup; plain member stores into global memory)
         __attribute__((address_space(1))) QMeta* mt = (__attribute__((address_space(1))) QMeta*)qd.meta;
-        mt->sumq = tot;
-        mt->step = bad ? __builtin_nanf("") : step;
-        mt->pad = 0.f;
+        mt->two_step = bad ? (double)__builtin_nanf("") : 2.0 * (double)step;
+        mt->neg_qs = -tot * (double)step;
     }
     // the epilogue reads the per-token constants through scalar loads: this workgroup's own copy
     // must have reached L2 before (workgroup-scope release = wait for the stores, no cache write-back)

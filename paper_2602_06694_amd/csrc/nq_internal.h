@@ -32,10 +32,13 @@ constexpr int kSlices = 3;
 // reduction indices): a 64-column step = 4 chunks = 12 pieces, ordered slice-major inside the step.
 __host__ __device__ inline int bq_piece(int chunk, int slice) { return (chunk >> 2) * 12 + slice * 4 + (chunk & 3); }
 
-struct QMeta {        // per token, written by the quantisation kernel
-    double sumq;      // sum_j q_j (exact)
-    float step;       // power of two; NaN when the token holds a non-finite value
-    float pad;
+// Per token, written by the quantisation: with step the token's power-of-two quantisation step and
+// sum_q = sum_j q_j, a stage output is  (2 sum_n b_n q_n - sum_q) step = fma(sum_n b_n q_n, two_step, neg_qs).
+// Both constants are exact (scalings of an exact integer by a power of two); two_step is NaN when
+// the token holds a non-finite value, which makes every output of the token NaN.
+struct QMeta {
+    double two_step;  // 2 step
+    double neg_qs;    // -sum_q step
 };
 
 struct QuantDesc {

@@ -14,7 +14,7 @@ step streams its bits from HBM rather than from cache.  All inputs are resident 
 before the timed region.
 
 Prints ONE JSON line.  `value` is effective weight GB/s = bytes of the stored
-factorization (r(n+m)/8 + 2(n+m) per layer, Appendix E.4) read per second.
+factorization (r(n+m)/8 + 2(n+m) per layer, Appendix F.5) read per second.
 """
 from __future__ import annotations
 
@@ -202,9 +202,46 @@ def time_stack(cfg, batch, steps=10, warmup=2):
         del graph
     except Exception as e:                     # report, do not hide
         ms_graph = f"capture failed: {e}"
+    # the stack in dependency order: per decoder layer four plans (q, k, v | o | gate, up | down), the
+    # layers of a plan reading one shared input; the plans run back to back on the stream, as they
+    # would between the attention and activation kernels of a model
+    block = synth.CONFIGS[cfg].block
+    level_plans = []
+    for base in range(0, len(handles), len(block)):
+        for group in ((0, 1, 2), (3,), (4, 5), (6,)):
+            idx = [base + g for g in group]
+            level_plans.append(nq.nq_plan_create([handles[i] for i in idx], [xs[idx[0]]] * len(idx),
+                                                 [ys[i] for i in idx], batch))
+
+    def levels():
+        for lp in level_plans:
+            nq.nq_plan_forward(lp)
+    prewarm(levels, 0.02)
+    t0 = time.perf_counter()
+    for _ in range(3):
+        levels()
+    torch.cuda.synchronize()
+    ms_levels = (time.perf_counter() - t0) * 1e3 / 3
+    try:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            levels()
+        prewarm(graph.replay, 0.02)
+        t0 = time.perf_counter()
+        for _ in range(5):
+            graph.replay()
+        torch.cuda.synchronize()
+        ms_levels_graph = (time.perf_counter() - t0) * 1e3 / 5
+        del graph
+    except Exception as e:                     # report, do not hide
+        ms_levels_graph = f"capture failed: {e}"
+    for lp in level_plans:
+        nq.nq_plan_destroy(lp)
     res = {"layers": len(handles), "ms_per_step": ms, "weight_GBps": wbytes / ms / 1e6,
            "tokens_per_s": batch / (ms * 1e-3),
            "ms_per_step_loop_of_single_calls": ms_loop, "ms_per_step_hip_graph_of_that_loop": ms_graph,
+           "ms_per_step_in_dependency_order_4_plans_per_block": ms_levels,
+           "ms_per_step_hip_graph_of_those_plans": ms_levels_graph,
            "kernel_ms": {"quantize_x": pk[0], "stage1": pk[1], "quantize_t": pk[2], "stage2": pk[3]},
            "stage1_GBps": sb1 / pk[1] / 1e6, "stage2_GBps": sb2 / pk[3] / 1e6,
            "stage1_frac_of_hbm_peak": sb1 / pk[1] / 1e6 / HBM_PEAK_GBPS,

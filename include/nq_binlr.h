@@ -3,7 +3,7 @@
  * NanoQuant low-rank binary factorized linear layer.
  *
  * Operation (quantization scheme, Section 3.1, Eq. 1; restated with diagonal
- * matrices in Appendix E.4, "NanoQuant (Ours)"):
+ * matrices in Appendix F.5, "NanoQuant (Ours)"):
  *
  *     W^ = Diag(s_out) . U . V^T . Diag(s_in),   U in {-1,+1}^{d_out x r},
  *                                                V in {-1,+1}^{d_in  x r},
@@ -145,7 +145,12 @@ int nq_binlr_forward(nq_handle h, const void* x, void* y, int batch, void* strea
 /* n independent forwards (same batch <= NQ_DECODE_MAX_BATCH) in four launches in total:
  * the streaming kernels walk a work list that covers all n layers, so small
  * layers do not pay one launch each.  hs/xs/ys: host arrays of n entries; xs[i]/ys[i]
- * device pointers as in nq_binlr_forward.  A handle may appear only once.
+ * device pointers as in nq_binlr_forward.  A handle may appear only once; several layers may
+ * read the same x (the q, k, v or the gate, up projections of a decoder block: the seven projections shown in
+ * Appendix D.3's figure), each scaling and quantising it with its own s_in.  Calls follow one another on
+ * the stream, so a later call may read what an earlier one wrote.
+ * At batch 1 a list whose launches would be short (a decoder block's few layers) runs as two
+ * launches, the stage kernels quantising their own input; results are bit-identical either way.
  * The list is compiled into an internal plan that is cached while the
  * arguments repeat (compiling allocates and synchronises; replays do not). */
 int nq_binlr_forward_many(const nq_handle* hs, const void* const* xs, void* const* ys,
@@ -158,14 +163,15 @@ int nq_plan_forward(nq_plan p, void* stream);
 /* Runs the plan once with HIP events between its kernels, waits for it, and returns the
  * duration of each kernel in milliseconds:
  * ms[0] input quantisation, ms[1] stage 1 (t = V^T x'), ms[2] quantisation of t,
- * ms[3] stage 2 (y = s_out (.) U t).  Synchronises `stream`. */
+ * ms[3] stage 2 (y = s_out (.) U t).  Synchronises `stream`.  Where a stage quantises its own
+ * input (short batch-1 lists) the quantisation entry is ~0 and the stage entry covers both. */
 int nq_plan_forward_timed(nq_plan p, void* stream, float ms[4]);
 int nq_plan_destroy(nq_plan p);
 
 int nq_binlr_destroy(nq_handle h);
 
 /* Bytes of the stored factorization: r(d_in+d_out)/8 + 2(d_in+d_out), i.e. the bit count
- * r(n+m) + 16(n+m) of Appendix E.4 divided by 8 (padding not counted). 0 for NULL. */
+ * r(n+m) + 16(n+m) of Appendix F.5 divided by 8 (padding not counted). 0 for NULL. */
 size_t nq_binlr_weight_bytes(nq_handle h);
 
 /* Debug: convert the device-resident bits back to canonical words (host buffers sized as

@@ -157,7 +157,7 @@ def round_output(y: np.ndarray, dtype: str) -> np.ndarray:
     """The values an output of type ``dtype`` ("f32", "f16", "bf16") holds for the fp64 results ``y``:
     rounded to fp32 first (the path's native result type), then, for the 16-bit types, once more to
     nearest even (IEEE conversion: overflow gives infinity).  Returned as fp64.  The paper states no
-    output type (Appendix D speaks of fp16 / bf16 activations); this is the reading the tests check."""
+    output type (Appendix E.2 speaks of fp16 / bf16 activations); this is the reading the tests check."""
     y32 = np.asarray(y, dtype=np.float64).astype(np.float32)
     if dtype == "f32":
         return y32.astype(np.float64)

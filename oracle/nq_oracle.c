@@ -6,7 +6,7 @@
  * helper with the HIP library, and the product never calls it.
  *
  * What is computed (quantization scheme, Section 3.1, Eq. 1; restated as
- * Diag(s1) U V^T Diag(s2) in Appendix E.4):
+ * Diag(s1) U V^T Diag(s2) in Appendix F.5):
  *
  *     W^[i][j] = s_out[i] * ( sum_{k<r} U[i][k] * V[j][k] ) * s_in[j]
  *     y[b][i]  = sum_{j<d_in} W^[i][j] * x[b][j]
@@ -180,7 +180,7 @@ int nqo_forward_factored(const uint32_t* U, const uint32_t* V, const double* s_o
     return used;
 }
 
-/* Storage of one factorized layer in bits: r(n+m) + 16(n+m)  (Appendix E.4) */
+/* Storage of one factorized layer in bits: r(n+m) + 16(n+m)  (Appendix F.5) */
 int64_t nqo_layer_bits(int64_t d_out, int64_t d_in, int64_t r)
 {
     return r * (d_out + d_in) + 16 * (d_out + d_in);

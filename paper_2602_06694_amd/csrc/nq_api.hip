@@ -135,8 +135,11 @@ struct nq_plan_s {
     StageDesc* s2;
     WorkItem* items1;
     WorkItem* items2;
+    FusedItem* fitems1;             // the same lists in the form of the fused schedule (empty otherwise)
+    FusedItem* fitems2;
     int n_items1, n_items2;
-    int w1, w2;                     // schedule of each stage launch (see stage_schedule)
+    int w1, w2;                     // schedule of each stage launch (see stage_schedule; kFusedSchedule: no quantisation launch)
+    int max_steps1, max_steps2;     // longest reduction of each stage launch
     int max_chunks_x, max_chunks_t; // longest vector of each quantisation launch (picks its block size)
     std::vector<nq_handle> handles;
     hipEvent_t ev[5];
@@ -588,6 +591,14 @@ static void drop_cached_plan_locked()
     }
 }
 
+static int env_int_api(const char* name, int dflt)
+{
+    const char* v = getenv(name);
+    if (!v || !*v) return dflt;
+    const int x = atoi(v);
+    return x >= 0 ? x : dflt;
+}
+
 extern "C" int nq_plan_create(nq_plan* out, const nq_handle* hs, const void* const* xs, void* const* ys, int n,
                               int batch)
 {
@@ -619,7 +630,7 @@ extern "C" int nq_plan_create(nq_plan* out, const nq_handle* hs, const void* con
         s2[i] = make_s2(hs[i], ys[i]);
     }
     // one work list per stage launch; its shape follows the schedule the launch will use
-    int sched[2];
+    int sched[2], max_steps_of[2] = {0, 0};
     std::vector<WorkItem> lists[2];
     for (int st = 0; st < 2; ++st) {
         const std::vector<StageDesc>& sd = st == 0 ? s1 : s2;
@@ -631,7 +642,18 @@ extern "C" int nq_plan_create(nq_plan* out, const nq_handle* hs, const void* con
             sq += (double)nrb * sd[i].n_steps * sd[i].n_steps;     // mean length seen by a streamed tile
             sm += (double)nrb * sd[i].n_steps;
         }
-        const int w = stage_schedule(total_rb, (int)(sq / sm), batch);
+        int w = stage_schedule(total_rb, (int)(sq / sm), batch);
+        // A short launch at batch 1 is bound by launch latency, not by bandwidth: the stage then
+        // quantises its own input (every workgroup for itself), which saves the quantisation launch.
+        {
+            int max_steps = 0;
+            for (int i = 0; i < n; ++i) max_steps = std::max(max_steps, sd[i].n_steps);
+            const double tile_mb = sm * (kTileWords * 4) / 1.0e6;
+            if (batch == 1 && !getenv("NQ_NO_FUSE") && fused_fits(max_steps, batch) &&
+                tile_mb <= (double)env_int_api("NQ_FUSE_MAX_MB", 24))
+                w = kFusedSchedule;
+            max_steps_of[st] = max_steps;
+        }
         sched[st] = w;
         for (int i = 0; i < n; ++i) {
             const int nrb = (int)n_rowblocks(sd[i].M);
@@ -705,6 +727,7 @@ extern "C" int nq_plan_create(nq_plan* out, const nq_handle* hs, const void* con
     p->handles.assign(hs, hs + n);
     p->n_items1 = (int)it1.size(); p->n_items2 = (int)it2.size();
     p->w1 = sched[0]; p->w2 = sched[1];
+    p->max_steps1 = max_steps_of[0]; p->max_steps2 = max_steps_of[1];
     p->max_chunks_x = p->max_chunks_t = 0;
     for (int i = 0; i < n; ++i) {
         p->max_chunks_x = std::max(p->max_chunks_x, qx[i].n_chunks);
@@ -712,7 +735,20 @@ extern "C" int nq_plan_create(nq_plan* out, const nq_handle* hs, const void* con
     }
     const size_t qb = align_up(sizeof(QuantDesc) * n, 256), sb = align_up(sizeof(StageDesc) * n, 256);
     const size_t i1b = align_up(sizeof(WorkItem) * it1.size(), 256), i2b = align_up(sizeof(WorkItem) * it2.size(), 256);
-    hipError_t e = hipMalloc(&p->alloc, 2 * qb + 2 * sb + i1b + i2b);
+    // stages on the fused schedule get items that carry their op's descriptors
+    std::vector<FusedItem> fit[2];
+    for (int st = 0; st < 2; ++st) {
+        if (sched[st] != kFusedSchedule) continue;
+        for (const WorkItem& w : lists[st]) {
+            FusedItem f{};
+            f.q = st == 0 ? qx[w.op] : qt[w.op];
+            f.s = st == 0 ? s1[w.op] : s2[w.op];
+            f.rb = w.rb;
+            fit[st].push_back(f);
+        }
+    }
+    const size_t f1b = align_up(sizeof(FusedItem) * fit[0].size(), 256), f2b = align_up(sizeof(FusedItem) * fit[1].size(), 256);
+    hipError_t e = hipMalloc(&p->alloc, 2 * qb + 2 * sb + i1b + i2b + f1b + f2b);
     if (e != hipSuccess) { delete p; return hip_fail(e, "hipMalloc(plan)", __FILE__, __LINE__); }
     char* c = (char*)p->alloc;
     p->qx = (QuantDesc*)c; c += qb;
@@ -720,12 +756,17 @@ extern "C" int nq_plan_create(nq_plan* out, const nq_handle* hs, const void* con
     p->s1 = (StageDesc*)c; c += sb;
     p->s2 = (StageDesc*)c; c += sb;
     p->items1 = (WorkItem*)c; c += i1b;
-    p->items2 = (WorkItem*)c;
+    p->items2 = (WorkItem*)c; c += i2b;
+    p->fitems1 = (FusedItem*)c; c += f1b;
+    p->fitems2 = (FusedItem*)c;
     const struct { void* dst; const void* src; size_t bytes; } copies[] = {
         {p->qx, qx.data(), sizeof(QuantDesc) * n}, {p->qt, qt.data(), sizeof(QuantDesc) * n},
         {p->s1, s1.data(), sizeof(StageDesc) * n}, {p->s2, s2.data(), sizeof(StageDesc) * n},
-        {p->items1, it1.data(), sizeof(WorkItem) * it1.size()}, {p->items2, it2.data(), sizeof(WorkItem) * it2.size()}};
+        {p->items1, it1.data(), sizeof(WorkItem) * it1.size()}, {p->items2, it2.data(), sizeof(WorkItem) * it2.size()},
+        {p->fitems1, fit[0].data(), sizeof(FusedItem) * fit[0].size()},
+        {p->fitems2, fit[1].data(), sizeof(FusedItem) * fit[1].size()}};
     for (const auto& cp : copies) {
+        if (cp.bytes == 0) continue;
         e = hipMemcpy(cp.dst, cp.src, cp.bytes, hipMemcpyHostToDevice);
         if (e != hipSuccess) { nq_plan_destroy(p); return hip_fail(e, "hipMemcpy(plan)", __FILE__, __LINE__); }
     }
@@ -739,13 +780,19 @@ static int plan_run(nq_plan p, hipStream_t s, bool timed)
     const StageDesc sdummy{};
     int rc;
     if (timed) NQ_HIP(hipEventRecord(p->ev[0], s));
-    if ((rc = launch_quantize(p->qx, qdummy, p->n, p->max_chunks_x, p->batch, s)) != NQ_OK) return rc;
+    if (p->w1 != kFusedSchedule &&
+        (rc = launch_quantize(p->qx, qdummy, p->n, p->max_chunks_x, p->batch, s)) != NQ_OK) return rc;
     if (timed) NQ_HIP(hipEventRecord(p->ev[1], s));
-    if ((rc = launch_stage(p->s1, sdummy, p->items1, p->n_items1, p->w1, stream_max_rbs(p->batch), p->batch, s)) != NQ_OK) return rc;
+    if (p->w1 == kFusedSchedule) rc = launch_fused_list(p->fitems1, p->n_items1, p->max_steps1, s);
+    else rc = launch_stage(p->s1, sdummy, p->items1, p->n_items1, p->w1, stream_max_rbs(p->batch), p->batch, s);
+    if (rc != NQ_OK) return rc;
     if (timed) NQ_HIP(hipEventRecord(p->ev[2], s));
-    if ((rc = launch_quantize(p->qt, qdummy, p->n, p->max_chunks_t, p->batch, s)) != NQ_OK) return rc;
+    if (p->w2 != kFusedSchedule &&
+        (rc = launch_quantize(p->qt, qdummy, p->n, p->max_chunks_t, p->batch, s)) != NQ_OK) return rc;
     if (timed) NQ_HIP(hipEventRecord(p->ev[3], s));
-    if ((rc = launch_stage(p->s2, sdummy, p->items2, p->n_items2, p->w2, stream_max_rbs(p->batch), p->batch, s)) != NQ_OK) return rc;
+    if (p->w2 == kFusedSchedule) rc = launch_fused_list(p->fitems2, p->n_items2, p->max_steps2, s);
+    else rc = launch_stage(p->s2, sdummy, p->items2, p->n_items2, p->w2, stream_max_rbs(p->batch), p->batch, s);
+    if (rc != NQ_OK) return rc;
     if (timed) NQ_HIP(hipEventRecord(p->ev[4], s));
     return NQ_OK;
 }

@@ -1,5 +1,5 @@
 // Streaming (decode, batch <= 8) kernels of the two-stage binary product
-//     t = V^T (s_in (.) x),   y = s_out (.) (U t)          (Section 3.1 Eq. 1; Appendix D, GEMV)
+//     t = V^T (s_in (.) x),   y = s_out (.) (U t)          (Section 3.1 Eq. 1; Appendix E.2, GEMV)
 // for gfx950.  Both stages are the same operation out[m] = sum_n A[m][n] v[n] with A a sign
 // matrix stored as 1 bit per entry, so one kernel serves both.
 //
@@ -110,22 +110,35 @@ int launch_export(const uint32_t* d_tiles, int64_t wpr, bool transposed, int64_t
 // ---------------------------------------------------------------------------------------------
 constexpr int kQuantHeld = 2;
 
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef const __attribute__((address_space(1))) v4u* gptr_v4u;    // global (not generic) address space
+typedef const __attribute__((address_space(1))) v4f* gptr_v4f;
+
 __device__ inline void load_chunk16(const QuantDesc& d, int64_t base, int c, bool vec, float v[16])
 {
     const int j0 = c * 16;
     if (vec && j0 + 16 <= d.N) {
+        // the scales are requested before the (type-dependent) loads of x, so that both are in flight together
+        v4u sraw[2] = {v4u{0, 0, 0, 0}, v4u{0, 0, 0, 0}};
+        if (d.scale) {
+            const gptr_v4u sp = (gptr_v4u)(d.scale + j0);
+            sraw[0] = sp[0];
+            sraw[1] = sp[1];
+        }
         if (d.dtype == NQ_F32) {
-            const float4* p = (const float4*)((const float*)d.x + base + j0);
+            // (global, not generic, address space: plain vector loads, exact wait counts)
+            const gptr_v4f p = (gptr_v4f)((const float*)d.x + base + j0);
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                float4 f = p[q];
+                const v4f f = p[q];
                 v[4 * q] = f.x; v[4 * q + 1] = f.y; v[4 * q + 2] = f.z; v[4 * q + 3] = f.w;
             }
         } else {
-            const uint4* p = (const uint4*)((const uint16_t*)d.x + base + j0);
+            const gptr_v4u p = (gptr_v4u)((const uint16_t*)d.x + base + j0);
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
-                uint4 u = p[q];
+                const v4u u = p[q];
                 uint32_t w[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
@@ -136,10 +149,9 @@ __device__ inline void load_chunk16(const QuantDesc& d, int64_t base, int c, boo
             }
         }
         if (d.scale) {
-            const uint4* sp = (const uint4*)(d.scale + j0);
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
-                uint4 u = sp[q];
+                const v4u u = sraw[q];
                 uint32_t w[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
@@ -382,9 +394,6 @@ int launch_pack_signs(const void* d_signs, int dtype, int64_t rows, int64_t cols
 #ifndef NQ_STAGE_WAVES
 #define NQ_STAGE_WAVES 5
 #endif
-typedef unsigned int v4u __attribute__((ext_vector_type(4)));
-typedef float v4f __attribute__((ext_vector_type(4)));
-typedef const __attribute__((address_space(1))) v4u* gptr_v4u;    // global (not generic) address space
 // Pointers that come out of a descriptor in memory are generic to the compiler; accesses through
 // them would be flat instructions, which count on two wait counters at once and make every later
 // wait a "wait for everything".  These casts name the address space: global for vector accesses,
@@ -453,9 +462,14 @@ constexpr int kStreamMaxRbs = 8;
 // (loads and stores share one in-order counter only among their own kind), and waiting for a
 // freshly issued load means waiting for the whole ring issued before it.  The per-token constants
 // come through scalar loads, which that counter does not see.
+// `pre_scale` (or nullptr): the output scales (fp16 bits) of this lane's two rows (row lane of each
+// half), fetched by the caller ahead of time and converted only here, so that nothing waits for them early; `own_meta` (or nullptr): the constants of token 0 when the
+// caller has just computed them itself (batch 1).  Both only shorten the chain of dependent memory
+// round trips of a launch that is bound by latency.
 template <int NB, int W, bool DEFER>
 __device__ __forceinline__ void stage_epilogue(const v4i (&acc)[NB][8], int* lds, int wave, int lane, int batch,
-                                               int rb, const EpilogueArgs& e, float* lds_out)
+                                               int rb, const EpilogueArgs& e, float* lds_out,
+                                               const uint16_t* pre_scale = nullptr, const QMeta* own_meta = nullptr)
 {
     const int g = lane >> 4, n = lane & 15;
     int* my_lds = (W == 1) ? lds : lds + wave * kEpiRegion;
@@ -489,7 +503,8 @@ __device__ __forceinline__ void stage_epilogue(const v4i (&acc)[NB][8], int* lds
             const int grow = rb * kTileRows + r128;
             const int neg_p = -(4 * hf + (row >> 4));                 // this row's sums carry the weight 2^p of its plane
             float oscale = 1.0f;
-            if (!DEFER && e.out_scale && grow < e.M) oscale = half_bits_to_float(((gptr_u16)e.out_scale)[grow]);
+            if (pre_scale) oscale = e.out_scale ? half_bits_to_float(pre_scale[hf]) : 1.0f;
+            else if (!DEFER && e.out_scale && grow < e.M) oscale = half_bits_to_float(((gptr_u16)e.out_scale)[grow]);
             auto one_token = [&](int tl) {
                 int h = 0, m = 0, l = 0;
 #pragma unroll
@@ -503,7 +518,9 @@ __device__ __forceinline__ void stage_epilogue(const v4i (&acc)[NB][8], int* lds
                 // every step is exact in fp64, and the plane's weight rides on the token's step
                 const double raw = fma((double)h, 65536.0, fma((double)m, 256.0, (double)l));
                 const int tok = 5 * cg + tl;
-                double val = fma(raw, __builtin_ldexp(meta[tok].two_step, neg_p), meta[tok].neg_qs);   // exact; rounded once, below
+                const double two_step = own_meta ? own_meta->two_step : meta[tok].two_step;
+                const double neg_qs = own_meta ? own_meta->neg_qs : meta[tok].neg_qs;
+                double val = fma(raw, __builtin_ldexp(two_step, neg_p), neg_qs);     // exact; rounded once, below
                 if (DEFER) {
                     lds_out[tok * kTileRows + r128] = (float)val;       // scaled by s_out when flushed
                 } else if (grow < e.M) {
@@ -981,8 +998,11 @@ __host__ __device__ inline size_t fused_lds_bytes(int nst)
     return (bq > epi ? bq : epi) + kFusedScratchInts * 4;
 }
 
+// LIST: workgroup i takes items[i] (a row block of some op, with that op's descriptors inside: one
+// fetch); otherwise row block i of the one op whose descriptors are the kernel arguments q1 / s1.
+template <bool LIST>
 __global__ void __launch_bounds__(64 * kFusedWaves) __attribute__((amdgpu_waves_per_eu(4, 8)))
-stage_fused_kernel(QuantDesc qd, StageDesc sd)
+stage_fused_kernel(const FusedItem* __restrict__ items, QuantDesc q1, StageDesc s1)
 {
     extern __shared__ int lds[];
     constexpr int W = kFusedWaves;
@@ -990,14 +1010,23 @@ stage_fused_kernel(QuantDesc qd, StageDesc sd)
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 4, n = lane & 15;
-    const int rb = blockIdx.x;
+    int rb = blockIdx.x;
+    QuantDesc qd = q1;
+    StageDesc sd = s1;
+    if (LIST) {
+        const FusedItem* e = items + blockIdx.x;           // uniform address of a kernel argument: scalar loads
+        rb = e->rb;
+        qd = e->q;
+        sd = e->s;
+    }
     const int nst = sd.n_steps;
     char* const lds_bq = (char*)lds;
     const size_t main_bytes = fused_lds_bytes(nst) - kFusedScratchInts * 4;
     float* const red_f = (float*)((char*)lds + main_bytes);                 // [W] partial maxima
     int* const red_bad = (int*)(red_f + W);                                 // the token holds a non-finite value
     double* const red_d = (double*)(red_f + W + 2);                         // [W] partial sums of q
-    static_assert((kFusedWaves + 2) * 4 + kFusedWaves * 8 <= kFusedScratchInts * 4, "scratch region");
+    QMeta* const own_meta = (QMeta*)(red_d + W);                            // the token's constants
+    static_assert((kFusedWaves + 2) * 4 + kFusedWaves * 8 + sizeof(QMeta) <= kFusedScratchInts * 4, "scratch region");
 
     // this wave's steps: wave, wave + W, ...; the first up to four tiles go out before anything else
     const int cnt = (nst - wave + W - 1) / W;
@@ -1007,6 +1036,17 @@ stage_fused_kernel(QuantDesc qd, StageDesc sd)
     for (int k = 0; k < 4; ++k) {
         const int st = cnt > 0 ? wave + (k < cnt ? k : cnt - 1) * W : 0;
         wbuf[k] = load_tile_words(a_base, (uint32_t)(st * 1024 + lane * 16));
+    }
+
+    // the output scales of this lane's two rows, needed last, are requested first
+    // (an unconditional load, so that the compiler finds no branch to convert -- and wait -- inside:
+    // a stage without output scales reads the start of its first tile instead and ignores it; the
+    // scale array is padded to whole row blocks)
+    uint16_t pre_scale[2];
+    {
+        const gptr_u16 sp = sd.out_scale ? (gptr_u16)sd.out_scale + rb * kTileRows : (gptr_u16)a_base;
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) pre_scale[hf] = sp[64 * hf + lane];
     }
 
     // ---- quantise the input vector (as quantize_kernel does): thread tid owns chunk tid ----
@@ -1053,15 +1093,12 @@ stage_fused_kernel(QuantDesc qd, StageDesc sd)
     if (tid == 0) {
         double tot = 0.0;
         for (int w = 0; w < W; ++w) tot += red_d[w];
-        // (the same values from every workgroup; plain member stores into global memory)
-        __attribute__((address_space(1))) QMeta* mt = (__attribute__((address_space(1))) QMeta*)qd.meta;
-        mt->two_step = bad ? (double)__builtin_nanf("") : 2.0 * (double)step;
-        mt->neg_qs = -tot * (double)step;
+        // the constants stay in the workgroup (LDS): its epilogue is their only reader
+        own_meta->two_step = bad ? (double)__builtin_nanf("") : 2.0 * (double)step;
+        own_meta->neg_qs = -tot * (double)step;
     }
-    // the epilogue reads the per-token constants through scalar loads: this workgroup's own copy
-    // must have reached L2 before (workgroup-scope release = wait for the stores, no cache write-back)
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
+    const QMeta my_meta = *own_meta;
 
     // ---- the reduction over this wave's steps, operands from LDS ----
     const uint32_t b_lds = (uint32_t)(bq_piece(g, n < 3 ? n : 0) * 16);      // token 0; unused columns re-read slice 0
@@ -1084,7 +1121,7 @@ stage_fused_kernel(QuantDesc qd, StageDesc sd)
     EpilogueArgs ea;
     ea.meta = sd.meta; ea.out_scale = sd.out_scale; ea.out = sd.out;
     ea.M = sd.M; ea.out_stride = sd.out_stride; ea.out_dtype = sd.out_dtype;
-    stage_epilogue<1, W, false>(acc, lds, wave, lane, 1, rb, ea, nullptr);
+    stage_epilogue<1, W, false>(acc, lds, wave, lane, 1, rb, ea, nullptr, pre_scale, &my_meta);
 }
 
 #undef NQ_LOAD_ITEM
@@ -1177,15 +1214,40 @@ static int launch_shared_t(const StageDesc* d_descs, const WorkItem* d_items, in
 // One stage of a lone layer at batch 1 together with the quantisation of its input (stage_fused_kernel).
 bool fused_fits(int nst, int batch) { return batch == 1 && nst * 4 <= 64 * kFusedWaves; }
 
-int launch_fused(const QuantDesc& q, const StageDesc& sd, hipStream_t s)
+static int fused_set_attr()
 {
     static bool attr_set = false;
     if (!attr_set) {
-        NQ_HIP(hipFuncSetAttribute((const void*)stage_fused_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
+        NQ_HIP(hipFuncSetAttribute((const void*)stage_fused_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
+        NQ_HIP(hipFuncSetAttribute((const void*)stage_fused_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
         attr_set = true;
     }
-    hipLaunchKernelGGL(stage_fused_kernel, dim3((unsigned)n_rowblocks(sd.M)), dim3(64 * kFusedWaves),
-                       fused_lds_bytes(sd.n_steps), s, q, sd);
+    return NQ_OK;
+}
+
+int launch_fused(const QuantDesc& q, const StageDesc& sd, hipStream_t s)
+{
+    int rc = fused_set_attr();
+    if (rc != NQ_OK) return rc;
+    hipLaunchKernelGGL(stage_fused_kernel<false>, dim3((unsigned)n_rowblocks(sd.M)), dim3(64 * kFusedWaves),
+                       fused_lds_bytes(sd.n_steps), s, nullptr, q, sd);
+    NQ_HIP(hipGetLastError());
+    return NQ_OK;
+}
+
+// The same for a list of ops: one workgroup per item; `max_steps` is the longest reduction among
+// the ops (it sizes the LDS of every workgroup).
+int launch_fused_list(const FusedItem* d_items, int n_items, int max_steps, hipStream_t s)
+{
+    if (n_items < 1) return NQ_OK;
+    if (!fused_fits(max_steps, 1)) {
+        set_error("launch_fused_list: reduction too long for the fused kernel");
+        return NQ_E_INVALID_ARG;
+    }
+    int rc = fused_set_attr();
+    if (rc != NQ_OK) return rc;
+    hipLaunchKernelGGL(stage_fused_kernel<true>, dim3((unsigned)n_items), dim3(64 * kFusedWaves),
+                       fused_lds_bytes(max_steps), s, d_items, QuantDesc{}, StageDesc{});
     NQ_HIP(hipGetLastError());
     return NQ_OK;
 }

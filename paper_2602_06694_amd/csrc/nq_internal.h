@@ -9,7 +9,7 @@ namespace nq {
 
 // ---- device bit layout ("sign tiles") ------------------------------------------------------
 // A sign matrix A[M][N] (M output rows, N = reduction length; A = V^T for stage 1, A = U for
-// stage 2 of the two-stage product of Section 3.3 / Appendix D) is cut into tiles of
+// stage 2 of the two-stage product of Section 3.3 / Appendix E.2) is cut into tiles of
 // 128 rows x 64 reduction columns = 1 KiB.  Tile (rb, st) starts at word (rb*n_steps + st)*256.
 // Inside a tile, lane l of a wavefront owns words 4l..4l+3 (one 16-byte load).  In word v of
 // lane l, bit 8*b + p  (byte b = 0..3, bit-in-byte p = 0..7) is the sign bit of
@@ -75,6 +75,15 @@ struct WorkItem {
     int n_rb;                // consecutive row blocks in the item (1 for the split schedule)
 };
 
+// One workgroup of the fused schedule: a row block of an op, with the op's descriptors copied in,
+// so that the workgroup starts after a single fetch.
+struct FusedItem {
+    QuantDesc q;
+    StageDesc s;
+    int rb;
+    int pad[3];
+};
+
 inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
 inline int64_t n_rowblocks(int64_t M) { return (M + kTileRows - 1) / kTileRows; }
 // the reduction is padded to a multiple of 4 steps (256 columns) so that the prefetch ring of the
@@ -136,6 +145,8 @@ int launch_stage(const StageDesc* d_descs, const StageDesc& single, const WorkIt
                  int w, int rbs_per_item, int batch, hipStream_t s);
 bool fused_fits(int nst, int batch);     // the quantised input of a stage fits the LDS of the fused kernel
 int launch_fused(const QuantDesc& q, const StageDesc& sd, hipStream_t s);
+constexpr int kFusedSchedule = 32;       // plan schedule code: a stage and its quantisation in one launch (batch 1)
+int launch_fused_list(const FusedItem* d_items, int n_items, int max_steps, hipStream_t s);
 int launch_valu_gemv(const uint32_t* tiles, const void* x, int x_dtype, int x_stride, const uint16_t* in_scale,
                      const uint16_t* out_scale, void* out, int out_dtype, int out_stride, int64_t M, int64_t N,
                      int batch, hipStream_t s);

@@ -1,5 +1,5 @@
 // Dense (prefill, batch >= 9) path of  y = s_out (.) (U (V^T (s_in (.) x)))   (Section 3.1 Eq. 1;
-// Appendix D, "Binary GEMM"): both contractions run on the fp16 matrix cores of gfx950.
+// Appendix E.3, "Binary GEMM Inference"): both contractions run on the fp16 matrix cores of gfx950.
 //
 //   pre   : x'' = fp16( s_in (.) x * 2^a_b )          per token b, 2^a_b puts max|x''| in [2^12, 2^13)
 //   gemm1 : T   = fp16( (X'' V) * g )                 g = power of two so that |T| <= 2^15 always

@@ -117,7 +117,7 @@ class LinearShape:
 
     @property
     def weight_bits(self) -> int:
-        # storage of the factorization, Appendix E.4: r(n+m) + 16(n+m)
+        # storage of the factorization, Appendix F.5: r(n+m) + 16(n+m)
         return self.r * (self.d_out + self.d_in) + 16 * (self.d_out + self.d_in)
 
     @property

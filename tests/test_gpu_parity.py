@@ -481,11 +481,12 @@ def test_sixteen_bit_outputs_are_the_rounded_exact_result():
         L.close()
 
 
-def test_single_call_and_plan_give_identical_bits():
-    """nq_binlr_forward runs a lone layer as two launches that quantise their input themselves;
-    plans run separate quantisation launches.  Same arithmetic, element for element: the outputs
-    (and the intermediate t) must be identical bit for bit.  The last shape is too long for the
-    fused launches' LDS and takes the four-launch path in nq_binlr_forward as well."""
+def test_single_call_and_plan_give_identical_bits(monkeypatch):
+    """nq_binlr_forward runs a lone layer at batch 1 as two launches that quantise their input
+    themselves, and so does a plan whose launches are short; larger plans (here: forced by
+    NQ_FUSE_MAX_MB=0) run separate quantisation launches.  Same arithmetic, element for element:
+    the outputs (and the intermediate t) must be identical bit for bit.  The last shape is too
+    long for the fused launches' LDS and takes the four-launch path everywhere."""
     import torch
     for shape in [(300, 200, 100), (129, 65, 33), (4096, 4096, 1024), (640, 1500, 257), (200, 60000, 96)]:
         L = Layer(*shape, "bf16", seed=700)
@@ -494,13 +495,55 @@ def test_single_call_and_plan_give_identical_bits():
             y_single = L.forward(x_np)
             t_single = nq.nq_binlr_read_intermediate(L.h, shape[2], batch)
             x = to_device(x_np, "bf16")
-            y = new_output(batch, shape[0])
-            plan = nq.nq_plan_create([L.h], [x], [y], batch)
-            nq.nq_plan_forward(plan)
+            for fuse_max_mb in (None, "0"):
+                if fuse_max_mb is None:
+                    monkeypatch.delenv("NQ_FUSE_MAX_MB", raising=False)
+                else:
+                    monkeypatch.setenv("NQ_FUSE_MAX_MB", fuse_max_mb)
+                y = new_output(batch, shape[0])
+                plan = nq.nq_plan_create([L.h], [x], [y], batch)
+                nq.nq_plan_forward(plan)
+                torch.cuda.synchronize()
+                assert np.array_equal(nq.nq_binlr_read_intermediate(L.h, shape[2], batch), t_single), (shape, batch)
+                assert np.array_equal(y.cpu().numpy(), y_single), (shape, batch, fuse_max_mb)
+                nq.nq_plan_destroy(plan)
+        L.close()
+
+
+def test_layers_that_share_one_input(monkeypatch):
+    """The projections of a decoder block that read the same activations (q, k, v; gate, up) go
+    into one forward_many call with the same x pointer: every layer scales and quantises the
+    shared input with its own s_in.  Checked against the oracle layer by layer, at batch 1 (short
+    launches that quantise in the stage kernels; also with separate quantisation launches) and
+    at batches that take the other schedules; a level that reads what the previous one wrote
+    (o after v here, fed v's output) follows in a second call on the same stream."""
+    import torch
+    d = 640
+    shapes = [(d, d, 160), (192, d, 96), (192, d, 96)]                       # q, k, v (grouped-query sizes)
+    layers = [Layer(*s, "bf16", seed=900 + i) for i, s in enumerate(shapes)]
+    o_proj = Layer(d, 192, 96, "f32", seed=950)                               # reads v's fp32 output
+    for batch in (1, 3, 8):
+        for fuse_max_mb in ((None, "0") if batch == 1 else (None,)):
+            if fuse_max_mb is None:
+                monkeypatch.delenv("NQ_FUSE_MAX_MB", raising=False)
+            else:
+                monkeypatch.setenv("NQ_FUSE_MAX_MB", fuse_max_mb)
+            x_np = synth.gen_x(batch, d, 960 + batch, "bf16")
+            x = to_device(x_np, "bf16")
+            ys = [torch.full((batch, s[0]), float("nan"), dtype=torch.float32, device="cuda") for s in shapes]
+            y_o = torch.full((batch, d), float("nan"), dtype=torch.float32, device="cuda")
+            level0 = nq.nq_plan_create([L.h for L in layers], [x, x, x], ys, batch)
+            level1 = nq.nq_plan_create([o_proj.h], [ys[2]], [y_o], batch)
+            nq.nq_plan_forward(level0)
+            nq.nq_plan_forward(level1)
             torch.cuda.synchronize()
-            assert np.array_equal(nq.nq_binlr_read_intermediate(L.h, shape[2], batch), t_single), (shape, batch)
-            assert np.array_equal(y.cpu().numpy(), y_single), (shape, batch)
-            nq.nq_plan_destroy(plan)
+            for L, y in zip(layers, ys):
+                assert rel_err(y.cpu().numpy(), L.oracle(x_np)) <= DECODE_TOL, (batch, fuse_max_mb)
+            v_out = ys[2].cpu().numpy()
+            assert rel_err(y_o.cpu().numpy(), o_proj.oracle(v_out)) <= DECODE_TOL, (batch, fuse_max_mb)
+            nq.nq_plan_destroy(level0)
+            nq.nq_plan_destroy(level1)
+    for L in layers + [o_proj]:
         L.close()
 
 

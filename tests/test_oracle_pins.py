@@ -269,7 +269,7 @@ def _model_linear_weights(block, n_layers):
 
 def test_storage_formula_and_paper_model_sizes():
     g = _golden()
-    # formula r(n+m) + 16(n+m) (Appendix E.4)
+    # formula r(n+m) + 16(n+m) (Appendix F.5)
     assert oracle.layer_bits(4096, 4096, 1024) == 1024 * 8192 + 16 * 8192
     for s in synth.llama2_70b_block():
         assert oracle.layer_bits(s.d_out, s.d_in, s.r) == s.weight_bits

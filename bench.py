@@ -5,7 +5,9 @@
 
 One "step" is one pass of the whole hot path (input quantisation, stage 1
 t = V^T (s_in . x), quantisation of t, stage 2 y = s_out . (U t)) over every layer of
-the workload, issued as ONE nq_plan_forward (four kernel launches).
+the workload, issued as ONE nq_plan_forward: four kernel launches, or two when the stage
+kernels quantise their own input (batch 1, reductions of at most 1024 / 4096 elements -- the
+default workload).
 
 Default workload "cfg2": the Llama-2-7B-shaped attention projection 4096x4096, r = 1024
 (0.5 bit/weight), bf16 activations, decode batch 1 -- as a pool of distinct seeded layer
@@ -93,13 +95,22 @@ def algorithmic_bytes(shp, batch, y_size=4):
     return bits + scales, bits + scales + x + y + t
 
 
-def stage_bytes(shp, batch, y_size=4):
+def stage_bytes(shp, batch, y_size=4, self_quantising=(False, False)):
     """Algorithmic bytes of the two streaming launches for one layer:
     stage 1 reads the V bits and the 3-byte fixed-point x', writes t (fp32);
-    stage 2 reads the U bits, the 3-byte fixed-point t and s_out (fp16), writes y (y_size bytes each)."""
-    s1 = shp.d_in * shp.r // 8 + 3 * batch * shp.d_in + 4 * batch * shp.r
-    s2 = shp.d_out * shp.r // 8 + 2 * shp.d_out + 3 * batch * shp.r + y_size * batch * shp.d_out
+    stage 2 reads the U bits, the 3-byte fixed-point t and s_out (fp16), writes y (y_size bytes each).
+    A stage that quantises its own input reads that input as it is instead (bf16 x and fp16 s_in;
+    fp32 t)."""
+    in1 = (2 * batch * shp.d_in + 2 * shp.d_in) if self_quantising[0] else 3 * batch * shp.d_in
+    in2 = 4 * batch * shp.r if self_quantising[1] else 3 * batch * shp.r
+    s1 = shp.d_in * shp.r // 8 + in1 + 4 * batch * shp.r
+    s2 = shp.d_out * shp.r // 8 + 2 * shp.d_out + in2 + y_size * batch * shp.d_out
     return s1, s2
+
+
+SCHEDULE_KERNEL = {1: "nq::stage_stream_kernel", 4: "nq::stage_split_kernel<W=4>", 16: "nq::stage_split_kernel<W=16>",
+                   8: "nq::stage_shared_kernel", 32: "nq::stage_fused_kernel", 33: "nq::stage_selfq_kernel<W=1>",
+                   34: "nq::stage_selfq_kernel<W=4>"}
 
 
 def cpu_baseline(work, batch, target_s):
@@ -411,8 +422,10 @@ def main():
         per_kernel += np.array(nq.nq_plan_forward_timed(plan))
     per_kernel /= reps
     # the two streaming launches; the slower one is the dominant kernel of the step
-    b1 = sum(stage_bytes(shp, batch, y_size)[0] for shp, _, _ in work)
-    b2 = sum(stage_bytes(shp, batch, y_size)[1] for shp, _, _ in work)
+    sched = nq.nq_plan_schedules(plan)
+    selfq = tuple(w in (32, 33, 34) for w in sched)
+    b1 = sum(stage_bytes(shp, batch, y_size, selfq)[0] for shp, _, _ in work)
+    b2 = sum(stage_bytes(shp, batch, y_size, selfq)[1] for shp, _, _ in work)
     stages = {"stage1": {"algorithmic_bytes": b1, "ms": per_kernel[1], "GBps": b1 / per_kernel[1] / 1e6},
               "stage2": {"algorithmic_bytes": b2, "ms": per_kernel[3], "GBps": b2 / per_kernel[3] / 1e6}}
     dom = "stage1" if per_kernel[1] >= per_kernel[3] else "stage2"
@@ -445,7 +458,9 @@ def main():
         "kernel_ms": {"quantize_x": per_kernel[0], "stage1": per_kernel[1], "quantize_t": per_kernel[2],
                       "stage2": per_kernel[3]},
         "stages": stages,
-        "roofline": {"bound": "hbm", "kernel": f"{dom} launch (nq::stage_split_kernel / nq::stage_stream_kernel)",
+        "stage_kernels": [SCHEDULE_KERNEL.get(w, str(w)) for w in sched],
+        "roofline": {"bound": "hbm",
+                     "kernel": f"{dom} launch ({SCHEDULE_KERNEL.get(sched[0 if dom == 'stage1' else 1], '?')})",
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": None},
     }

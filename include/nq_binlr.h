@@ -166,6 +166,11 @@ int nq_plan_forward(nq_plan p, void* stream);
  * ms[3] stage 2 (y = s_out (.) U t).  Synchronises `stream`.  Where a stage quantises its own
  * input (short batch-1 lists) the quantisation entry is ~0 and the stage entry covers both. */
 int nq_plan_forward_timed(nq_plan p, void* stream, float ms[4]);
+/* Debug: which schedule each of the plan's two stage launches uses.  w[0] stage 1, w[1] stage 2:
+ * 1 = one wave per item, 4 / 16 = that many waves share a row block, 8 = eight waves share an op's
+ * input through LDS (batch 6..8), 32 = short batch-1 launch that quantises its own input,
+ * 33 / 34 = chip-filling batch-1 launch whose waves quantise their own share (one / four waves per row block). */
+int nq_plan_schedules(nq_plan p, int w[2]);
 int nq_plan_destroy(nq_plan p);
 
 int nq_binlr_destroy(nq_handle h);

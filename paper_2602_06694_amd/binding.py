@@ -57,6 +57,7 @@ def lib() -> ctypes.CDLL:
         L.nq_plan_create.argtypes = [ctypes.POINTER(vp), vp, vp, vp, ci, ci]; L.nq_plan_create.restype = ci
         L.nq_plan_forward.argtypes = [vp, vp]; L.nq_plan_forward.restype = ci
         L.nq_plan_forward_timed.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_float)]; L.nq_plan_forward_timed.restype = ci
+        L.nq_plan_schedules.argtypes = [vp, ctypes.POINTER(ctypes.c_int)]; L.nq_plan_schedules.restype = ci
         L.nq_plan_destroy.argtypes = [vp]; L.nq_plan_destroy.restype = ci
         L.nq_binlr_destroy.argtypes = [vp]; L.nq_binlr_destroy.restype = ci
         L.nq_binlr_weight_bytes.argtypes = [vp]; L.nq_binlr_weight_bytes.restype = ctypes.c_size_t
@@ -209,6 +210,12 @@ def nq_plan_forward_timed(p: int, stream=None) -> List[float]:
     ms = (ctypes.c_float * 4)()
     _check(lib().nq_plan_forward_timed(p, _stream(stream), ms))
     return [float(v) for v in ms]
+
+
+def nq_plan_schedules(p: int) -> List[int]:
+    w = (ctypes.c_int * 2)()
+    _check(lib().nq_plan_schedules(p, w))
+    return [int(v) for v in w]
 
 
 def nq_plan_destroy(p: Optional[int]) -> None:

@@ -653,6 +653,13 @@ extern "C" int nq_plan_create(nq_plan* out, const nq_handle* hs, const void* con
                 tile_mb <= (double)env_int_api("NQ_FUSE_MAX_MB", 24))
                 w = kFusedSchedule;
             max_steps_of[st] = max_steps;
+            // A launch that fills the chip keeps its schedule, but its waves quantise their own share
+            // of the input: no quantisation launch, and the B operand comes out of LDS.
+            int min_steps = max_steps;
+            for (int i = 0; i < n; ++i) min_steps = std::min(min_steps, sd[i].n_steps);
+            if (w != kFusedSchedule && !getenv("NQ_NO_SELFQ") && total_rb >= schedule_full_rowblocks() &&
+                selfq_fits(w, max_steps, min_steps, batch))
+                w = w == 1 ? kSelfqSchedule1 : kSelfqSchedule4;
         }
         sched[st] = w;
         for (int i = 0; i < n; ++i) {
@@ -738,7 +745,7 @@ extern "C" int nq_plan_create(nq_plan* out, const nq_handle* hs, const void* con
     // stages on the fused schedule get items that carry their op's descriptors
     std::vector<FusedItem> fit[2];
     for (int st = 0; st < 2; ++st) {
-        if (sched[st] != kFusedSchedule) continue;
+        if (sched[st] != kFusedSchedule && sched[st] != kSelfqSchedule1 && sched[st] != kSelfqSchedule4) continue;
         for (const WorkItem& w : lists[st]) {
             FusedItem f{};
             f.q = st == 0 ? qx[w.op] : qt[w.op];
@@ -779,21 +786,34 @@ static int plan_run(nq_plan p, hipStream_t s, bool timed)
     const QuantDesc qdummy{};
     const StageDesc sdummy{};
     int rc;
+    // a stage on one of the self-quantising schedules has no quantisation launch
+    auto self_quantising = [](int w) { return w == kFusedSchedule || w == kSelfqSchedule1 || w == kSelfqSchedule4; };
+    auto run_stage = [&](int w, const StageDesc* sd, const WorkItem* items, const FusedItem* fitems, int n_items,
+                         int max_steps) {
+        if (w == kFusedSchedule) return launch_fused_list(fitems, n_items, max_steps, s);
+        if (w == kSelfqSchedule1 || w == kSelfqSchedule4)
+            return launch_selfq(fitems, n_items, w == kSelfqSchedule1 ? 1 : 4, max_steps, s);
+        return launch_stage(sd, sdummy, items, n_items, w, stream_max_rbs(p->batch), p->batch, s);
+    };
     if (timed) NQ_HIP(hipEventRecord(p->ev[0], s));
-    if (p->w1 != kFusedSchedule &&
+    if (!self_quantising(p->w1) &&
         (rc = launch_quantize(p->qx, qdummy, p->n, p->max_chunks_x, p->batch, s)) != NQ_OK) return rc;
     if (timed) NQ_HIP(hipEventRecord(p->ev[1], s));
-    if (p->w1 == kFusedSchedule) rc = launch_fused_list(p->fitems1, p->n_items1, p->max_steps1, s);
-    else rc = launch_stage(p->s1, sdummy, p->items1, p->n_items1, p->w1, stream_max_rbs(p->batch), p->batch, s);
-    if (rc != NQ_OK) return rc;
+    if ((rc = run_stage(p->w1, p->s1, p->items1, p->fitems1, p->n_items1, p->max_steps1)) != NQ_OK) return rc;
     if (timed) NQ_HIP(hipEventRecord(p->ev[2], s));
-    if (p->w2 != kFusedSchedule &&
+    if (!self_quantising(p->w2) &&
         (rc = launch_quantize(p->qt, qdummy, p->n, p->max_chunks_t, p->batch, s)) != NQ_OK) return rc;
     if (timed) NQ_HIP(hipEventRecord(p->ev[3], s));
-    if (p->w2 == kFusedSchedule) rc = launch_fused_list(p->fitems2, p->n_items2, p->max_steps2, s);
-    else rc = launch_stage(p->s2, sdummy, p->items2, p->n_items2, p->w2, stream_max_rbs(p->batch), p->batch, s);
-    if (rc != NQ_OK) return rc;
+    if ((rc = run_stage(p->w2, p->s2, p->items2, p->fitems2, p->n_items2, p->max_steps2)) != NQ_OK) return rc;
     if (timed) NQ_HIP(hipEventRecord(p->ev[4], s));
+    return NQ_OK;
+}
+
+extern "C" int nq_plan_schedules(nq_plan p, int w[2])
+{
+    if (!p || !w) return fail(NQ_E_NULL, "nq_plan_schedules: NULL pointer");
+    w[0] = p->w1;
+    w[1] = p->w2;
     return NQ_OK;
 }
 

@@ -469,10 +469,14 @@ constexpr int kStreamMaxRbs = 8;
 template <int NB, int W, bool DEFER>
 __device__ __forceinline__ void stage_epilogue(const v4i (&acc)[NB][8], int* lds, int wave, int lane, int batch,
                                                int rb, const EpilogueArgs& e, float* lds_out,
-                                               const uint16_t* pre_scale = nullptr, const QMeta* own_meta = nullptr)
+                                               const uint16_t* pre_scale = nullptr, const QMeta* own_meta = nullptr,
+                                               int region = kEpiRegion, bool meta_is_partial = false)
 {
+    // `region`: ints between the LDS regions of the W waves (their first kEpiRegion ints are used here).
+    // meta_is_partial: own_meta->neg_qs is this wave's share of -sum(q) step; the shares of the W
+    // waves, which the caller has put into the (otherwise unused) column 15 of their regions, are added.
     const int g = lane >> 4, n = lane & 15;
-    int* my_lds = (W == 1) ? lds : lds + wave * kEpiRegion;
+    int* my_lds = (W == 1) ? lds : lds + wave * region;
     const cptr_meta meta = (cptr_meta)e.meta;
 #pragma unroll
     for (int cg = 0; cg < NB; ++cg) {
@@ -509,7 +513,7 @@ __device__ __forceinline__ void stage_epilogue(const v4i (&acc)[NB][8], int* lds
                 int h = 0, m = 0, l = 0;
 #pragma unroll
                 for (int w = 0; w < W; ++w) {
-                    const int* q = lds + w * kEpiRegion + (3 * tl) * 64 + row;
+                    const int* q = lds + w * region + (3 * tl) * 64 + row;
                     h += q[0];
                     m += q[64];
                     l += q[128];
@@ -519,7 +523,12 @@ __device__ __forceinline__ void stage_epilogue(const v4i (&acc)[NB][8], int* lds
                 const double raw = fma((double)h, 65536.0, fma((double)m, 256.0, (double)l));
                 const int tok = 5 * cg + tl;
                 const double two_step = own_meta ? own_meta->two_step : meta[tok].two_step;
-                const double neg_qs = own_meta ? own_meta->neg_qs : meta[tok].neg_qs;
+                double neg_qs = own_meta ? own_meta->neg_qs : meta[tok].neg_qs;
+                if (own_meta && meta_is_partial && W > 1) {
+                    neg_qs = 0.0;
+#pragma unroll
+                    for (int w = 0; w < W; ++w) neg_qs += *(const double*)(lds + w * region + 15 * 64);
+                }
                 double val = fma(raw, __builtin_ldexp(two_step, neg_p), neg_qs);     // exact; rounded once, below
                 if (DEFER) {
                     lds_out[tok * kTileRows + r128] = (float)val;       // scaled by s_out when flushed
@@ -978,6 +987,171 @@ stage_shared_kernel(const StageDesc* __restrict__ descs, const WorkItem* __restr
 }
 
 // ---------------------------------------------------------------------------------------------
+// Batch 1 in launches that fill the chip: the stream / split schedules with the quantisation of
+// the input done by the waves themselves, which removes the two quantisation launches of a step
+// (19 of 205 us on the 1024-layer pool) and takes the B operand off the vector-memory path.
+// A wave requests its first D tiles, reads the chunks of its OWN steps (wave, wave + W, ...), takes
+// their maximum (with W = 4 the four waves exchange theirs through LDS: the step follows from the
+// maximum of the whole vector), quantises its chunks into its LDS region in the layout of the
+// global buffer, and streams its tiles with the B operand read from LDS one step ahead.  The
+// sum of its quantised values goes through column 15 of its epilogue region to the wave that
+// finishes the token.  After the wave's last step its region is reused for the epilogue.
+// The arithmetic is that of quantize_kernel + stage_{stream,split}_kernel element for element.
+// One item = one row block; W = 1 (short reductions) or 4 (long ones, split as in the split kernel).
+// Only for shares of at most 16 steps per wave (reductions of up to 1024 elements with W = 1, 4096
+// with W = 4): a lane then owns ONE chunk of 16 values, loaded once and kept in registers between
+// the maximum and the quantisation, and the 3 KiB of quantised input fit the epilogue region.  With
+// longer shares (chunks read twice, more LDS, fewer resident waves) the separate quantisation
+// launch measured faster: 4096x8192 r=1024 164 vs 169 us per step of a 512-layer pool, 11008x4096
+// r=1664 135 vs 143 us; the 1024-layer pool of 4096x4096 r=1024 layers gains 205 -> 191 us.
+// LDS: [W][kEpiRegion] (+ W maxima and flags when W = 4).
+// ---------------------------------------------------------------------------------------------
+template <int W, int D>
+__global__ void __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(NQ_STAGE_WAVES, 8)))
+stage_selfq_kernel(const FusedItem* __restrict__ items)
+{
+    constexpr int region = kEpiRegion;
+    extern __shared__ int lds[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int g = lane >> 4, n = lane & 15;
+    const FusedItem* e = items + blockIdx.x;               // uniform address of a kernel argument: scalar loads
+    const int rb = e->rb;
+    const QuantDesc qd = e->q;
+    const StageDesc sd = e->s;
+    const int nst = sd.n_steps;
+    char* const my_bq = (char*)(lds + wave * region);
+
+    const int cnt = (nst - wave + W - 1) / W;              // steps of this wave (may be <= 0 when W > nst)
+    const int stf = cnt > 0 ? wave : 0;
+    const char* const a_base = (const char*)sd.tiles + (size_t)rb * nst * (kTileWords * 4);
+    uint32_t a_off = (uint32_t)(stf * 1024 + lane * 16);
+
+    // ---- the wave quantises the chunks of its own steps ----
+    // lane j owns local chunk j = chunk j % 4 of the wave's step j / 4; the W waves' chunks
+    // together cover the vector (chunks past its end read as zeros).  (Requesting the input ahead
+    // of the tiles, so that the quantisation runs while the tiles are on their way, measured the same.)
+    const int esz = qd.dtype == NQ_F32 ? 4 : 2;
+    const bool vec = (((size_t)qd.x_stride * esz) & 15) == 0;
+    const int n_own = 4 * cnt;                             // <= 64 (the host checks the reduction length)
+    float hv[16];
+    float m = 0.f;
+    int bad = 0;
+    // (a lane beyond n_own reads a chunk of zeros or of another wave: harmless for the maximum)
+    const int my_chunk = 4 * (wave + (lane >> 2) * W) + (lane & 3);
+
+    v4u wbuf[D];
+#pragma unroll
+    for (int k = 0; k < D; ++k) {                          // branch-free: a short share re-reads its last tile
+        const int kk = k < cnt ? k : (cnt > 0 ? cnt - 1 : 0);
+        wbuf[k] = load_tile_words(a_base, a_off + (uint32_t)kk * (W * 1024));
+    }
+    a_off += D * W * 1024;
+    uint16_t pre_scale[2];
+    {
+        const gptr_u16 sp = sd.out_scale ? (gptr_u16)sd.out_scale + rb * kTileRows : (gptr_u16)a_base;
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf) pre_scale[hf] = sp[64 * hf + lane];
+    }
+    load_chunk16(qd, 0, my_chunk, vec, hv);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const float a = fabsf(hv[i]);
+        if (!(a <= 3.0e38f)) bad = 1;
+        m = fmaxf(m, a);
+    }
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    bad = __builtin_amdgcn_ballot_w64(bad != 0) != 0;
+    if (W > 1) {
+        // the step follows from the maximum over the whole vector: one exchange between the waves
+        float* const red_f = (float*)(lds + W * region);
+        int* const red_bad = (int*)(red_f + W);
+        if (lane == 0) {
+            red_f[wave] = m;
+            red_bad[wave] = bad;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < W; ++w) {
+            m = fmaxf(m, red_f[w]);
+            bad |= red_bad[w];
+        }
+    }
+    int ex = 0;
+    float step = 1.0f;
+    if (m > 0.f && !bad) {
+        (void)frexpf(m, &ex);
+        int se = ex - 22;
+        se = se < -126 ? -126 : se;
+        step = ldexpf(1.0f, se);
+    }
+    const float inv_step = 1.0f / step;
+    long long local_sum = 0;
+    if (lane < n_own) local_sum = quantize_chunk16(hv, inv_step, bad != 0, (uint4*)my_bq + bq_piece(lane, 0));
+    double sum = (double)local_sum;
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+    QMeta my_meta;
+    my_meta.two_step = bad ? (double)__builtin_nanf("") : 2.0 * (double)step;
+    my_meta.neg_qs = -sum * (double)step;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+
+    // ---- the reduction over this wave's steps ----
+    const char* const b_lds = my_bq + bq_piece(g, n < 3 ? n : 0) * 16;      // token 0; unused columns re-read slice 0
+    const int last = cnt > 0 ? cnt - 1 : 0;
+    v4i acc[1][8];
+#pragma unroll
+    for (int p = 0; p < 8; ++p) acc[0][p] = v4i{0, 0, 0, 0};
+#define NQ_ISSUE(k)                                                              \
+    do {                                                                         \
+        wbuf[k] = load_tile_words(a_base, a_off);                                \
+        a_off += W * 1024;                                                       \
+    } while (0)
+#define NQ_LDSB(i) (*(const v4u*)(b_lds + ((i) < last ? (i) : last) * (int)kBqStepBytes))
+    v4u bop[2][1];
+    bop[0][0] = NQ_LDSB(0);
+    int i0 = 0;
+    for (; i0 + 2 * D <= cnt; i0 += D) {
+#pragma unroll
+        for (int k = 0; k < D; ++k) {
+            bop[(k + 1) & 1][0] = NQ_LDSB(i0 + k + 1);
+            mac_tile<1>(acc, wbuf[k], bop[k & 1]);
+            NQ_ISSUE(k);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    static_assert(D % 2 == 0, "the operand double buffer is in phase at every pass over the ring");
+#pragma unroll
+    for (int k = 0; k < D; ++k) {
+        if (i0 + k < cnt) {
+            bop[(k + 1) & 1][0] = NQ_LDSB(i0 + k + 1);
+            mac_tile<1>(acc, wbuf[k], bop[k & 1]);
+            if (i0 + k + D < cnt) NQ_ISSUE(k);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < D; ++k) {
+        if (i0 + D + k < cnt) {
+            bop[(k + 1) & 1][0] = NQ_LDSB(i0 + D + k + 1);
+            mac_tile<1>(acc, wbuf[k], bop[k & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+#undef NQ_LDSB
+#undef NQ_ISSUE
+    // the region changes hands: quantised input -> epilogue (wave-local, so no workgroup barrier)
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    if (W > 1 && lane == 0) *(double*)(lds + wave * region + 15 * 64) = my_meta.neg_qs;
+    EpilogueArgs ea;
+    ea.meta = sd.meta; ea.out_scale = sd.out_scale; ea.out = sd.out;
+    ea.M = sd.M; ea.out_stride = sd.out_stride; ea.out_dtype = sd.out_dtype;
+    stage_epilogue<1, W, false>(acc, lds, wave, lane, 1, rb, ea, nullptr, pre_scale, &my_meta, region, W > 1);
+}
+
+// ---------------------------------------------------------------------------------------------
 // Fourth schedule, for ONE layer on its own at batch 1 (nq_binlr_forward): a stage and the
 // quantisation of its input in a single launch, so that a forward is two dependent launches
 // instead of four -- a lone layer is bound by launch latency (about 4 us per dependent launch),
@@ -1147,6 +1321,9 @@ static int env_int(const char* name, int dflt)
     return x > 0 ? x : dflt;
 }
 
+// tiles a wave of stage_selfq_kernel<W> keeps in flight (with the B operand in LDS a lone wave affords eight;
+// measured on the 1024-layer pool: 192-193 us per step with 8 / 4, 194-195 us with 8 / 8, 6 / 6 or four waves per SIMD)
+constexpr int kSelfqDepth1 = 8, kSelfqDepth4 = 4;
 constexpr int kRingDepth = 4;        // the tile layout pads every reduction to a multiple of this many steps
 
 template <int NB>
@@ -1252,21 +1429,40 @@ int launch_fused_list(const FusedItem* d_items, int n_items, int max_steps, hipS
     return NQ_OK;
 }
 
-// Which schedule a launch of `n_rb_total` row blocks with (work-weighted) mean reduction length
-// `mean_steps` takes.  Returns W: 1 = stream kernel, 4 / 16 = split kernel, kSharedSchedule = shared-input kernel.
-//  - few row blocks (a single layer): split so that the launch still covers the chip;
-//  - many, batch <= 5: long reductions (>= 64 steps) are split four ways, which shortens the
-//    longest serial stream and the tail of the launch; short ones run one wave per item, several
-//    row blocks in a row, where the LDS reduction and the barriers of a split would cost more
-//    than they give;
-//  - many, batch 6..8: long reductions (>= 32 steps) go to the kernel whose eight waves share the
-//    op's input through LDS, short ones again to one wave per item (a barrier per 8 steps and an
-//    epilogue per 16 do not pay).
+// Whether a batch-1 launch with schedule w (1 or 4) may quantise in the stage kernel: a wave's share
+// of every reduction must be at most 16 steps (see stage_selfq_kernel), and with one wave per row
+// block the reductions must not be so short that the stream kernel would chain row blocks.
+bool selfq_fits(int w, int max_steps, int min_steps, int batch)
+{
+    if (batch != 1 || (w != 1 && w != 4)) return false;
+    if (w == 1 && min_steps < 16) return false;
+    return max_steps <= 16 * w;
+}
+
+int launch_selfq(const FusedItem* d_items, int n_items, int w, int max_steps, hipStream_t s)
+{
+    if (n_items < 1) return NQ_OK;
+    if (!selfq_fits(w, max_steps, 16, 1)) {
+        set_error("launch_selfq: schedule or reduction length not supported");
+        return NQ_E_INVALID_ARG;
+    }
+    const size_t lds_bytes = (size_t)w * kEpiRegion * 4 + (w > 1 ? 2 * w * 4 : 0);     // + the waves' maxima and flags
+    if (w == 1)
+        hipLaunchKernelGGL((stage_selfq_kernel<1, kSelfqDepth1>), dim3((unsigned)n_items), dim3(64), lds_bytes, s, d_items);
+    else
+        hipLaunchKernelGGL((stage_selfq_kernel<4, kSelfqDepth4>), dim3((unsigned)n_items), dim3(256), lds_bytes, s, d_items);
+    NQ_HIP(hipGetLastError());
+    return NQ_OK;
+}
+
+// Row blocks from which a launch counts as filling the chip.
+int schedule_full_rowblocks() { return env_int("NQ_SCHEDULE_FULL", device_cu_count() * 8); }
+
 int stage_schedule(int n_rb_total, int mean_steps, int batch)
 {
     // row blocks from which a launch counts as filling the chip (NQ_SCHEDULE_FULL overrides it,
     // which lets small inputs exercise the schedules built for large launches)
-    const int full = env_int("NQ_SCHEDULE_FULL", device_cu_count() * 8);
+    const int full = schedule_full_rowblocks();
     int w;
     if (n_rb_total >= full && batch > 5) w = mean_steps >= env_int("NQ_SHARE_STEPS", 32) ? kShareWaves : 1;
     else if (n_rb_total >= full) w = mean_steps >= env_int("NQ_SPLIT_STEPS", 64) ? 4 : 1;

@@ -547,6 +547,71 @@ def test_layers_that_share_one_input(monkeypatch):
         L.close()
 
 
+def test_self_quantising_schedules_at_batch_1(monkeypatch):
+    """In launches that fill the chip the batch-1 stage kernels quantise their own share of the
+    input (no quantisation launch) when a wave's share of every reduction is at most 16 steps.
+    NQ_SCHEDULE_FULL=1 makes these small lists count as filling the chip.  First list: inputs of
+    64 steps (four waves per row block in stage 1), ranks of 16 steps (one wave in stage 2), as in
+    the 4096x4096 r=1024 layers, with ragged tails in every dimension; second list, with the
+    split threshold lowered so that both stages run four waves per row block: reductions of 20,
+    36 and 64 steps (waves with unequal shares), fp32 input.  The result must match the
+    four-launch path bit for bit (same arithmetic) and the oracle within the bar."""
+    import torch
+    cases = [([(4096, 4096, 1024), (300, 4090, 1000), (129, 4040, 970), (1000, 4096, 1024)], "bf16", None, [33, 34]),
+             ([(300, 1100, 1030), (129, 2000, 2050), (640, 4000, 1500)], "f32", "1", [34, 34])]
+    for shapes, x_dtype, split_steps, want in cases:
+        layers = [Layer(*s, x_dtype, seed=1200 + i) for i, s in enumerate(shapes)]
+        xs_np = [synth.gen_x(1, s[1], 1300 + i, x_dtype) for i, s in enumerate(shapes)]
+        xs = [to_device(x, x_dtype) for x in xs_np]
+        hs = [L.h for L in layers]
+        outs = {}
+        for mode in ("selfq", "four_launches"):
+            monkeypatch.setenv("NQ_SCHEDULE_FULL", "1")
+            monkeypatch.setenv("NQ_FUSE_MAX_MB", "0")
+            if split_steps:
+                monkeypatch.setenv("NQ_SPLIT_STEPS", split_steps)
+            else:
+                monkeypatch.delenv("NQ_SPLIT_STEPS", raising=False)
+            if mode == "four_launches":
+                monkeypatch.setenv("NQ_NO_SELFQ", "1")
+            else:
+                monkeypatch.delenv("NQ_NO_SELFQ", raising=False)
+            ys = [torch.full((1, s[0]), float("nan"), dtype=torch.float32, device="cuda") for s in shapes]
+            plan = nq.nq_plan_create(hs, xs, ys, 1)
+            nq.nq_plan_forward(plan)
+            nq.nq_plan_forward(plan)
+            torch.cuda.synchronize()
+            if mode == "selfq":
+                assert sorted(nq.nq_plan_schedules(plan)) == want
+            else:
+                assert all(w in (1, 4) for w in nq.nq_plan_schedules(plan))
+            outs[mode] = [y.cpu().numpy() for y in ys]
+            outs[mode + "_t"] = [nq.nq_binlr_read_intermediate(L.h, s[2], 1) for L, s in zip(layers, shapes)]
+            nq.nq_plan_destroy(plan)
+        for i, (L, x) in enumerate(zip(layers, xs_np)):
+            assert np.array_equal(outs["selfq_t"][i], outs["four_launches_t"][i]), (shapes[i], x_dtype)
+            assert np.array_equal(outs["selfq"][i], outs["four_launches"][i]), (shapes[i], x_dtype)
+            assert rel_err(outs["selfq"][i], L.oracle(x)) <= DECODE_TOL, (shapes[i], x_dtype)
+        for L in layers:
+            L.close()
+    # a token with a non-finite value: every output NaN, nothing else disturbed
+    monkeypatch.setenv("NQ_SCHEDULE_FULL", "1")
+    monkeypatch.setenv("NQ_FUSE_MAX_MB", "0")
+    monkeypatch.delenv("NQ_NO_SELFQ", raising=False)
+    monkeypatch.delenv("NQ_SPLIT_STEPS", raising=False)
+    L = Layer(300, 4090, 1000, "f32", seed=1250)
+    x_np = synth.gen_x(1, 4090, 1350, "f32")
+    x_np[0, 77] = np.inf
+    y = torch.zeros((1, 300), dtype=torch.float32, device="cuda")
+    plan = nq.nq_plan_create([L.h], [to_device(x_np, "f32")], [y], 1)
+    assert sorted(nq.nq_plan_schedules(plan)) == [33, 34]
+    nq.nq_plan_forward(plan)
+    torch.cuda.synchronize()
+    assert np.isnan(y.cpu().numpy()).all()
+    nq.nq_plan_destroy(plan)
+    L.close()
+
+
 def test_forward_error_paths():
     import torch
     L = Layer(64, 64, 32, "bf16", seed=1)

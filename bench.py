@@ -464,6 +464,14 @@ def main():
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": None},
     }
+    # what this chip attains on the two roofline resources (context for the fractions of the nominal peaks, not targets)
+    if not args.quick:
+        hbm = nq.nq_probe_hbm_read(4 << 30, 10, 50)
+        out["attainable"] = {"hbm_streaming_read_GBps": hbm,
+                             "mfma_f16_dense_TFLOPs": nq.nq_probe_mfma(nq.NQ_F16),
+                             "mfma_i8_dense_TOPs": nq.nq_probe_mfma(nq.NQ_I8),
+                             "note": "plain read-only kernel over 4 GiB; register-resident matrix-instruction loop"}
+        out["roofline"]["frac_of_attainable"] = achieved / hbm
     traffic = measured_traffic(name, dom)
     if traffic is not None:
         out["roofline"]["traffic"] = traffic

@@ -187,6 +187,21 @@ int nq_binlr_export_words(nq_handle h, uint32_t* U_words, uint32_t* V_words);
  * on this handle to host float32 [batch, r].  Synchronises the device. */
 int nq_binlr_read_intermediate(nq_handle h, float* t_host, int batch);
 
+/* ---- measurement aids (not part of the forward path) ----
+ * What this GPU attains on the two resources the roofline figures are priced against, so that a
+ * benchmark can report its results against measured as well as nominal peaks. */
+
+/* Streams a private buffer of `bytes` (>= 64 MiB; several times the 256 MB last-level cache for an
+ * HBM figure) `iters` times through a read-only kernel and returns the rate in GB/s (1e9 bytes).
+ * prewarm_ms (0..1000): about that many milliseconds of the same load run untimed first -- the chip
+ * changes its power state a few milliseconds into a sustained load, and the rate with it.
+ * Allocates and frees its buffer, runs on the default stream, synchronises. */
+int nq_probe_hbm_read(size_t bytes, int iters, int prewarm_ms, double* gb_per_s);
+/* A register-resident loop of dense matrix-core instructions on every CU: dtype NQ_F16 (fp16 operands,
+ * fp32 accumulation; the prefill path's instruction) or NQ_I8 (int8, int32 accumulation; the decode
+ * path's).  Returns 1e12 operations per second (one multiply-add = 2).  Synchronises. */
+int nq_probe_mfma(int dtype, double* tera_ops_per_s);
+
 const char* nq_status_string(int status);
 const char* nq_last_error_string(void);
 

@@ -57,6 +57,8 @@ def lib() -> ctypes.CDLL:
         L.nq_plan_create.argtypes = [ctypes.POINTER(vp), vp, vp, vp, ci, ci]; L.nq_plan_create.restype = ci
         L.nq_plan_forward.argtypes = [vp, vp]; L.nq_plan_forward.restype = ci
         L.nq_plan_forward_timed.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_float)]; L.nq_plan_forward_timed.restype = ci
+        L.nq_probe_hbm_read.argtypes = [ctypes.c_size_t, ci, ci, ctypes.POINTER(ctypes.c_double)]; L.nq_probe_hbm_read.restype = ci
+        L.nq_probe_mfma.argtypes = [ci, ctypes.POINTER(ctypes.c_double)]; L.nq_probe_mfma.restype = ci
         L.nq_plan_schedules.argtypes = [vp, ctypes.POINTER(ctypes.c_int)]; L.nq_plan_schedules.restype = ci
         L.nq_plan_destroy.argtypes = [vp]; L.nq_plan_destroy.restype = ci
         L.nq_binlr_destroy.argtypes = [vp]; L.nq_binlr_destroy.restype = ci
@@ -216,6 +218,18 @@ def nq_plan_schedules(p: int) -> List[int]:
     w = (ctypes.c_int * 2)()
     _check(lib().nq_plan_schedules(p, w))
     return [int(v) for v in w]
+
+
+def nq_probe_hbm_read(nbytes: int, iters: int = 10, prewarm_ms: int = 50) -> float:
+    out = ctypes.c_double()
+    _check(lib().nq_probe_hbm_read(nbytes, iters, prewarm_ms, ctypes.byref(out)))
+    return float(out.value)
+
+
+def nq_probe_mfma(dtype: int) -> float:
+    out = ctypes.c_double()
+    _check(lib().nq_probe_mfma(dtype, ctypes.byref(out)))
+    return float(out.value)
 
 
 def nq_plan_destroy(p: Optional[int]) -> None:

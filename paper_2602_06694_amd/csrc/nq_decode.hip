@@ -534,7 +534,7 @@ __device__ __forceinline__ void stage_epilogue(const v4i (&acc)[NB][8], int* lds
                     lds_out[tok * kTileRows + r128] = (float)val;       // scaled by s_out when flushed
                 } else if (grow < e.M) {
                     val *= (double)oscale;
-                    store_out(e.out, e.out_dtype, (size_t)tok * e.out_stride + grow, (float)val);
+                    store_out(e.out, e.out_dtype, (size_t)tok * e.out_stride + grow, (float)val, e.out_scale != nullptr);
                 }
             };
             for (int tl = wave; tl < tg; tl += W) one_token(tl);
@@ -599,9 +599,15 @@ __device__ __forceinline__ void stream_flush(int* lds, const float* lds_out, int
     };
     typedef __attribute__((address_space(1))) float* gptr_f32;
     typedef __attribute__((address_space(1))) uint16_t* gptr_o16;
-    if (ea.out_dtype == NQ_F32) store_all([&](size_t i, float v) { ((gptr_f32)ea.out)[i] = v; });
-    else if (ea.out_dtype == NQ_BF16) store_all([&](size_t i, float v) { ((gptr_o16)ea.out)[i] = float_to_bf16_bits(v); });
-    else store_all([&](size_t i, float v) { ((gptr_o16)ea.out)[i] = float_to_f16_bits(v); });
+    // (a final output -- the stage with output scales -- is stored non-temporal, see store_out)
+    if (ea.out_dtype == NQ_F32) {
+        if (ea.out_scale) store_all([&](size_t i, float v) { __builtin_nontemporal_store(v, (gptr_f32)ea.out + i); });
+        else store_all([&](size_t i, float v) { ((gptr_f32)ea.out)[i] = v; });
+    } else if (ea.out_dtype == NQ_BF16) {
+        store_all([&](size_t i, float v) { __builtin_nontemporal_store(float_to_bf16_bits(v), (gptr_o16)ea.out + i); });
+    } else {
+        store_all([&](size_t i, float v) { __builtin_nontemporal_store(float_to_f16_bits(v), (gptr_o16)ea.out + i); });
+    }
 }
 
 #define NQ_LOAD_ITEM()                                                                             \

@@ -117,10 +117,21 @@ __device__ __forceinline__ uint16_t float_to_out16(float f, int dtype)
     return dtype == NQ_BF16 ? float_to_bf16_bits(f) : float_to_f16_bits(f);
 }
 // element `idx` of an output array of type `dtype` in global memory
-__device__ __forceinline__ void store_out(void* base, int dtype, size_t idx, float v)
+// `streamed`: a final output, written once and not read back by the next launch -- stored
+// non-temporal, so that it leaves the cache while the kernel still streams instead of waiting, dirty,
+// for the write-back at the kernel's end (stage 2 of the 1024-layer pool: 100 -> 97.5 us).  The
+// intermediate t, which the next launch reads, stays a plain store.
+__device__ __forceinline__ void store_out(void* base, int dtype, size_t idx, float v, bool streamed = false)
 {
-    if (dtype == NQ_F32) ((__attribute__((address_space(1))) float*)base)[idx] = v;
-    else ((__attribute__((address_space(1))) uint16_t*)base)[idx] = float_to_out16(v, dtype);
+    typedef __attribute__((address_space(1))) float* gptr_of32;
+    typedef __attribute__((address_space(1))) uint16_t* gptr_ou16;
+    if (streamed) {
+        if (dtype == NQ_F32) __builtin_nontemporal_store(v, (gptr_of32)base + idx);
+        else __builtin_nontemporal_store(float_to_out16(v, dtype), (gptr_ou16)base + idx);
+    } else {
+        if (dtype == NQ_F32) ((gptr_of32)base)[idx] = v;
+        else ((gptr_ou16)base)[idx] = float_to_out16(v, dtype);
+    }
 }
 #endif
 

@@ -131,3 +131,19 @@ def test_config5_prefill_70b_mlp(batch):
         print(f"config 5 {shp.name} B={batch}: rel err {err:.3e} (dense rows {err_a:.3e})")
         assert err <= PREFILL_TOL and err <= BAR and err_a <= PREFILL_TOL
         L.close()
+
+
+def test_attainable_rate_probes_give_plausible_figures():
+    """The measurement aids: a streaming read must land between a third of and the whole nominal HBM
+    rate, the matrix-instruction loops between a third of and (with clock tolerance) the nominal peaks."""
+    from paper_2602_06694_amd import binding as nq
+    gbps = nq.nq_probe_hbm_read(2 << 30, 4, 20)
+    assert 2500 < gbps < 8200, gbps
+    f16 = nq.nq_probe_mfma(nq.NQ_F16)
+    i8 = nq.nq_probe_mfma(nq.NQ_I8)
+    assert 800 < f16 < 2800, f16
+    assert 1600 < i8 < 5600, i8
+    with pytest.raises(nq.NQError):
+        nq.nq_probe_mfma(nq.NQ_BF16)
+    with pytest.raises(nq.NQError):
+        nq.nq_probe_hbm_read(1 << 20, 1, 0)

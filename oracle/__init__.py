@@ -45,6 +45,11 @@ def _load():
         L.nqo_forward_factored.argtypes = [p, p, p, p, i64, i64, i64, p, i64, p, p, ci]
         L.nqo_forward_factored.restype = ci
         L.nqo_layer_bits.argtypes = [i64, i64, i64]; L.nqo_layer_bits.restype = i64
+        L.nqo_forward_dense_rows_mid.argtypes = [p, p, p, p, p, i64, i64, i64, p, i64, p, i64, p]
+        L.nqo_forward_dense_rows_mid.restype = None
+        L.nqo_forward_factored_mid.argtypes = [p, p, p, p, p, i64, i64, i64, p, i64, p, p, ci]
+        L.nqo_forward_factored_mid.restype = ci
+        L.nqo_layer_bits_mid.argtypes = [i64, i64, i64]; L.nqo_layer_bits_mid.restype = i64
         _lib = L
     return _lib
 
@@ -151,6 +156,40 @@ def forward_factored(U_words, V_words, s_out, s_in, d_out, d_in, r, x, threads: 
 
 def layer_bits(d_out: int, d_in: int, r: int) -> int:
     return int(_load().nqo_layer_bits(d_out, d_in, r))
+
+
+# ---- three-scale variant: W^ = Diag(s_out) (U Diag(s_mid) V^T) Diag(s_in)  (Appendix F.4) ----
+
+def forward_dense_rows_mid(U_words, V_words, s_out, s_mid, s_in, d_out, d_in, r, x, rows) -> np.ndarray:
+    """Tier A (the definition) on the chosen output rows."""
+    L = _load()
+    U, V = _words(U_words, d_out, r), _words(V_words, d_in, r)
+    so, sm, si = _f64(s_out, d_out), _f64(s_mid, r), _f64(s_in, d_in)
+    x = _x(x, d_in)
+    rows = np.ascontiguousarray(np.asarray(rows, dtype=np.int64))
+    assert rows.min() >= 0 and rows.max() < d_out
+    y = np.empty((x.shape[0], rows.size), dtype=np.float64)
+    L.nqo_forward_dense_rows_mid(_ptr(U), _ptr(V), _ptr(so), _ptr(sm), _ptr(si), d_out, d_in, r, _ptr(x), x.shape[0],
+                                 _ptr(rows), rows.size, _ptr(y))
+    return y
+
+
+def forward_factored_mid(U_words, V_words, s_out, s_mid, s_in, d_out, d_in, r, x, threads: int = 0,
+                         return_t: bool = False):
+    """Tier B: t = V^T (s_in . x); y = s_out . (U (s_mid . t)).  return_t gives t (before s_mid)."""
+    L = _load()
+    U, V = _words(U_words, d_out, r), _words(V_words, d_in, r)
+    so, sm, si = _f64(s_out, d_out), _f64(s_mid, r), _f64(s_in, d_in)
+    x = _x(x, d_in)
+    y = np.empty((x.shape[0], d_out), dtype=np.float64)
+    t = np.empty((x.shape[0], r), dtype=np.float64) if return_t else None
+    L.nqo_forward_factored_mid(_ptr(U), _ptr(V), _ptr(so), _ptr(sm), _ptr(si), d_out, d_in, r, _ptr(x), x.shape[0],
+                               _ptr(y), _ptr(t) if return_t else None, threads)
+    return (y, t) if return_t else y
+
+
+def layer_bits_mid(d_out: int, d_in: int, r: int) -> int:
+    return int(_load().nqo_layer_bits_mid(d_out, d_in, r))
 
 
 def round_output(y: np.ndarray, dtype: str) -> np.ndarray:

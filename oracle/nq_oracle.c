@@ -27,6 +27,13 @@
  *     x' = s_in (.) x ;  t = V^T x' ;  y = s_out (.) (U t)
  * Tier B exists because Tier A costs d_out*d_in*r operations.
  *
+ * The three-scale variant of Appendix F.4 (a rank-wise scale s_mid between the
+ * two binary products; the DBF / LittleBit format) has functions of its own at
+ * the end of the file, pinned the same way (numpy reduction, closed forms,
+ * complete enumeration, s_mid = 1 against the two-scale code); its storage
+ * formula is checked against the appendix's expression only -- the paper prints
+ * no size of such a layer with its rank, so that formula is "parity unpinned".
+ *
  * All arithmetic is IEEE double.  Inputs arrive already widened to double
  * (bf16/fp16/fp32 -> double is exact).
  */
@@ -178,6 +185,89 @@ int nqo_forward_factored(const uint32_t* U, const uint32_t* V, const double* s_o
     free(xp);
     free(t);
     return used;
+}
+
+/* ---- three-scale variant (the DBF / LittleBit format of Appendix F.4) ----
+ *     W^ = Diag(s1) ( U Diag(s_mid) V^T ) Diag(s2),   s_mid in R^r
+ * i.e. W^[i][j] = s_out[i] * ( sum_k U[i][k] * s_mid[k] * V[j][k] ) * s_in[j].
+ * Separate functions: the two-scale code above stays exactly what its pins check. */
+
+/* Tier A on chosen output rows, the definition written out */
+void nqo_forward_dense_rows_mid(const uint32_t* U, const uint32_t* V, const double* s_out, const double* s_mid,
+                                const double* s_in, int64_t d_out, int64_t d_in, int64_t r,
+                                const double* x, int64_t batch,
+                                const int64_t* rows, int64_t n_rows, double* y)
+{
+    int64_t wpr = words_per_row(r);
+    (void)d_out;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t q = 0; q < n_rows; ++q) {
+        int64_t i = rows[q];
+        double* Wrow = (double*)malloc(sizeof(double) * (size_t)d_in);
+        for (int64_t j = 0; j < d_in; ++j) {
+            double inner = 0.0;
+            for (int64_t k = 0; k < r; ++k) inner += sign_at(U, wpr, i, k) * s_mid[k] * sign_at(V, wpr, j, k);
+            Wrow[j] = s_out[i] * inner * s_in[j];
+        }
+        for (int64_t b = 0; b < batch; ++b) {
+            double acc = 0.0;
+            for (int64_t j = 0; j < d_in; ++j) acc += Wrow[j] * x[b * d_in + j];
+            y[b * n_rows + q] = acc;
+        }
+        free(Wrow);
+    }
+}
+
+/* Tier B: x' = s_in (.) x ; t = V^T x' ; t' = s_mid (.) t ; y = s_out (.) (U t').
+ * `t_out` (may be NULL) receives t (before the rank-wise scale). */
+int nqo_forward_factored_mid(const uint32_t* U, const uint32_t* V, const double* s_out, const double* s_mid,
+                             const double* s_in, int64_t d_out, int64_t d_in, int64_t r,
+                             const double* x, int64_t batch, double* y, double* t_out, int threads)
+{
+    int64_t wpr = words_per_row(r);
+    int used = 1;
+#ifdef _OPENMP
+    if (threads > 0) omp_set_num_threads(threads);
+#else
+    (void)threads;
+#endif
+    double* xp = (double*)malloc(sizeof(double) * (size_t)d_in);
+    double* t = (double*)malloc(sizeof(double) * (size_t)r);
+    double* tm = (double*)malloc(sizeof(double) * (size_t)r);
+    for (int64_t b = 0; b < batch; ++b) {
+        for (int64_t j = 0; j < d_in; ++j) xp[j] = s_in[j] * x[b * d_in + j];
+#pragma omp parallel
+        {
+#ifdef _OPENMP
+#pragma omp single
+            used = omp_get_num_threads();
+#endif
+#pragma omp for schedule(static)
+            for (int64_t k = 0; k < r; ++k) {
+                double acc = 0.0;
+                for (int64_t j = 0; j < d_in; ++j) acc += sign_at(V, wpr, j, k) * xp[j];
+                t[k] = acc;
+                tm[k] = s_mid[k] * acc;
+            }
+#pragma omp for schedule(static)
+            for (int64_t i = 0; i < d_out; ++i) {
+                double acc = 0.0;
+                for (int64_t k = 0; k < r; ++k) acc += sign_at(U, wpr, i, k) * tm[k];
+                y[b * d_out + i] = s_out[i] * acc;
+            }
+        }
+        if (t_out) for (int64_t k = 0; k < r; ++k) t_out[b * r + k] = t[k];
+    }
+    free(xp);
+    free(t);
+    free(tm);
+    return used;
+}
+
+/* Storage of the three-scale variant in bits: r(n+m) + 16(n+r+m)  (Appendix F.4) */
+int64_t nqo_layer_bits_mid(int64_t d_out, int64_t d_in, int64_t r)
+{
+    return r * (d_out + d_in) + 16 * (d_out + r + d_in);
 }
 
 /* Storage of one factorized layer in bits: r(n+m) + 16(n+m)  (Appendix F.5) */

@@ -332,3 +332,95 @@ def test_output_rounding_pins():
     assert np.all(np.diff(once[order]) >= 0)
     assert np.all(np.abs(once - vals) <= np.abs(vals) * 2.0**-8)
 
+
+
+# ---------- three-scale variant: W^ = Diag(s_out) (U Diag(s_mid) V^T) Diag(s_in)  (Appendix F.4) ----------
+
+def test_mid_scale_of_ones_is_the_two_scale_layer_bit_for_bit():
+    d_out, d_in, r, batch = 70, 130, 45, 2
+    U, V, s_out, s_in, x = small_case(d_out, d_in, r, batch, 501)
+    Uw, Vw = np_pack(U), np_pack(V)
+    ones = np.ones(r, dtype=np.float16)
+    y2, t2 = oracle.forward_factored(Uw, Vw, s_out, s_in, d_out, d_in, r, x, return_t=True)
+    y3, t3 = oracle.forward_factored_mid(Uw, Vw, s_out, ones, s_in, d_out, d_in, r, x, return_t=True)
+    assert np.array_equal(y2, y3) and np.array_equal(t2, t3)
+    rows = np.arange(d_out)
+    assert np.array_equal(oracle.forward_dense_rows(Uw, Vw, s_out, s_in, d_out, d_in, r, x, rows),
+                          oracle.forward_dense_rows_mid(Uw, Vw, s_out, ones, s_in, d_out, d_in, r, x, rows))
+
+
+@pytest.mark.parametrize("shape", [(33, 65, 31, 2), (128, 96, 64, 3), (70, 257, 100, 1)])
+def test_mid_scale_matches_numpy_matmul(shape):
+    """Independent library reduction: diag(s_out) (U diag(s_mid) V^T) diag(s_in) built with numpy."""
+    d_out, d_in, r, batch = shape
+    U, V, s_out, s_in, x = small_case(d_out, d_in, r, batch, 601 + d_out)
+    s_mid = synth.gen_scales(r, 777 + r)
+    Uw, Vw = np_pack(U), np_pack(V)
+    W = (s_out.astype(np.float64)[:, None]
+         * ((U.astype(np.float64) * s_mid.astype(np.float64)[None, :]) @ V.astype(np.float64).T)
+         * s_in.astype(np.float64)[None, :])
+    ref = x @ W.T
+    scale = np.abs(ref).max()
+    ya = oracle.forward_dense_rows_mid(Uw, Vw, s_out, s_mid, s_in, d_out, d_in, r, x, np.arange(d_out))
+    yb, t = oracle.forward_factored_mid(Uw, Vw, s_out, s_mid, s_in, d_out, d_in, r, x, return_t=True)
+    assert np.abs(ya - ref).max() <= 1e-12 * scale
+    assert np.abs(yb - ref).max() <= 1e-12 * scale
+    t_ref = (x * s_in.astype(np.float64)[None, :]) @ V.astype(np.float64)          # t is taken before s_mid
+    assert np.abs(t - t_ref).max() <= 1e-12 * np.abs(t_ref).max()
+
+
+def test_mid_scale_closed_forms():
+    d_out, d_in, r, batch = 40, 50, 37, 2
+    _, _, s_out, s_in, x = small_case(d_out, d_in, r, batch, 701)
+    s_mid = synth.gen_scales(r, 702)
+    so, sm, si = (a.astype(np.float64) for a in (s_out, s_mid, s_in))
+    # all signs +1:  y_i = s_out_i (sum_k s_mid_k) (sum_j s_in_j x_j)
+    ones_u, ones_v = np.ones((d_out, r), np.int8), np.ones((d_in, r), np.int8)
+    y = oracle.forward_factored_mid(np_pack(ones_u), np_pack(ones_v), s_out, s_mid, s_in, d_out, d_in, r, x)
+    expect = so[None, :] * sm.sum() * (x * si[None, :]).sum(axis=1)[:, None]
+    assert np.abs(y - expect).max() <= 1e-12 * np.abs(expect).max()
+    # s_mid = e_k selects rank k:  y_i = s_out_i U_ik sum_j V_jk s_in_j x_j
+    U = synth.gen_signs_pm1(d_out, r, 703)
+    V = synth.gen_signs_pm1(d_in, r, 704)
+    for k in (0, 17, r - 1):
+        e = np.zeros(r, dtype=np.float16)
+        e[k] = 1
+        y = oracle.forward_factored_mid(np_pack(U), np_pack(V), s_out, e, s_in, d_out, d_in, r, x)
+        expect = so[None, :] * U[:, k].astype(np.float64)[None, :] * ((x * si[None, :]) @ V[:, k].astype(np.float64))[:, None]
+        assert np.abs(y - expect).max() <= 1e-12 * np.abs(expect).max()
+        ya = oracle.forward_dense_rows_mid(np_pack(U), np_pack(V), s_out, e, s_in, d_out, d_in, r, x, np.arange(d_out))
+        assert np.abs(ya - expect).max() <= 1e-12 * np.abs(expect).max()
+    # a negative entry of s_mid is a sign flip of that column of U (or of V)
+    s_neg = s_mid.copy()
+    s_neg[5] = -s_neg[5]
+    U2 = U.copy()
+    U2[:, 5] = -U2[:, 5]
+    assert np.array_equal(oracle.forward_factored_mid(np_pack(U), np_pack(V), s_out, s_neg, s_in, d_out, d_in, r, x),
+                          oracle.forward_factored_mid(np_pack(U2), np_pack(V), s_out, s_mid, s_in, d_out, d_in, r, x))
+
+
+def test_mid_scale_brute_force_exact_integers():
+    """Every sign pattern of a (2, 2, 2) layer with small-integer scales: results are exact integers."""
+    d_out, d_in, r = 2, 2, 2
+    s_out = np.array([1, 3], dtype=np.float16)
+    s_mid = np.array([2, 5], dtype=np.float16)
+    s_in = np.array([2, 1], dtype=np.float16)
+    x = np.array([[3, -2], [-1, 4]], dtype=np.float64)
+    for ubits in itertools.product((-1, 1), repeat=d_out * r):
+        U = np.array(ubits, dtype=np.int8).reshape(d_out, r)
+        for vbits in itertools.product((-1, 1), repeat=d_in * r):
+            V = np.array(vbits, dtype=np.int8).reshape(d_in, r)
+            expect = [[int(s_out[i]) * sum(sum(int(U[i, k]) * int(s_mid[k]) * int(V[j, k]) for k in range(r))
+                                            * int(s_in[j]) * int(x[b, j]) for j in range(d_in))
+                       for i in range(d_out)] for b in range(2)]
+            Uw, Vw = oracle.pack_signs(U), oracle.pack_signs(V)
+            ya = oracle.forward_dense_rows_mid(Uw, Vw, s_out, s_mid, s_in, d_out, d_in, r, x, np.arange(d_out))
+            yb = oracle.forward_factored_mid(Uw, Vw, s_out, s_mid, s_in, d_out, d_in, r, x)
+            assert ya.tolist() == expect and yb.tolist() == expect
+
+
+def test_mid_scale_storage_formula():
+    """r(n+m) + 16(n+r+m) bits (Appendix F.4): 16 r more than the two-scale layer."""
+    for d_out, d_in, r in [(4096, 4096, 1024), (11008, 4096, 1664), (1, 1, 1)]:
+        assert oracle.layer_bits_mid(d_out, d_in, r) == oracle.layer_bits(d_out, d_in, r) + 16 * r
+        assert oracle.layer_bits_mid(d_out, d_in, r) == r * (d_out + d_in) + 16 * (d_out + r + d_in)

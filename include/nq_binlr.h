@@ -128,6 +128,17 @@ int nq_binlr_create_from_device(nq_handle* out, int64_t d_out, int64_t d_in, int
                                 const uint16_t* d_s_out_fp16, const uint16_t* d_s_in_fp16,
                                 int x_dtype, int y_dtype, uint32_t flags);
 
+/* Three-scale variant -- the format of the low-rank binary methods the paper compares with
+ * (DBF, LittleBit; Appendix F.4):
+ *     W^ = Diag(s_out) . U . Diag(s_mid) . V^T . Diag(s_in),
+ *     y  = s_out (.) ( U ( s_mid (.) ( V^T ( s_in (.) x ) ) ) ),     s_mid: r rank-wise scales.
+ * s_mid_fp16: host, r IEEE binary16 values (finite, any sign), copied; NULL removes the scale again
+ * (back to the two-scale layer of Eq. 1).  Every path applies it: the streaming kernels while they
+ * quantise t, the dense path when it stores T.  Synchronises the device.  Call it before plans are
+ * built on the handle (a plan keeps the layer's descriptors; the cached plan of
+ * nq_binlr_forward_many is dropped here).  nq_binlr_weight_bytes then counts the 2r bytes too. */
+int nq_binlr_set_mid_scale(nq_handle h, const uint16_t* s_mid_fp16);
+
 /* Grow the per-layer workspace so that forwards with batch <= max_batch allocate nothing.
  * May allocate and synchronise. */
 int nq_binlr_reserve(nq_handle h, int max_batch);
@@ -176,7 +187,8 @@ int nq_plan_destroy(nq_plan p);
 int nq_binlr_destroy(nq_handle h);
 
 /* Bytes of the stored factorization: r(d_in+d_out)/8 + 2(d_in+d_out), i.e. the bit count
- * r(n+m) + 16(n+m) of Appendix F.5 divided by 8 (padding not counted). 0 for NULL. */
+ * r(n+m) + 16(n+m) of Appendix F.5 divided by 8 (padding not counted); with a rank-wise scale
+ * 2r bytes more (r(n+m) + 16(n+r+m) bits, Appendix F.4). 0 for NULL. */
 size_t nq_binlr_weight_bytes(nq_handle h);
 
 /* Debug: convert the device-resident bits back to canonical words (host buffers sized as

@@ -57,6 +57,7 @@ def lib() -> ctypes.CDLL:
         L.nq_plan_create.argtypes = [ctypes.POINTER(vp), vp, vp, vp, ci, ci]; L.nq_plan_create.restype = ci
         L.nq_plan_forward.argtypes = [vp, vp]; L.nq_plan_forward.restype = ci
         L.nq_plan_forward_timed.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_float)]; L.nq_plan_forward_timed.restype = ci
+        L.nq_binlr_set_mid_scale.argtypes = [vp, vp]; L.nq_binlr_set_mid_scale.restype = ci
         L.nq_probe_hbm_read.argtypes = [ctypes.c_size_t, ci, ci, ctypes.POINTER(ctypes.c_double)]; L.nq_probe_hbm_read.restype = ci
         L.nq_probe_mfma.argtypes = [ci, ctypes.POINTER(ctypes.c_double)]; L.nq_probe_mfma.restype = ci
         L.nq_plan_schedules.argtypes = [vp, ctypes.POINTER(ctypes.c_int)]; L.nq_plan_schedules.restype = ci
@@ -171,6 +172,19 @@ def nq_binlr_create_from_device(d_out: int, d_in: int, r: int, d_U_words, d_V_wo
     _check(lib().nq_binlr_create_from_device(ctypes.byref(h), d_out, d_in, r, _dev_ptr(d_U_words), _dev_ptr(d_V_words),
                                              _dev_ptr(d_s_out), _dev_ptr(d_s_in), x_dtype, y_dtype, flags))
     return h.value
+
+
+def nq_binlr_set_mid_scale(h: int, s_mid: Optional[np.ndarray]) -> None:
+    """s_mid: r fp16 values (numpy float16 or their uint16 bits), or None to remove the scale."""
+    if s_mid is None:
+        _check(lib().nq_binlr_set_mid_scale(h, None))
+        return
+    a = np.ascontiguousarray(s_mid)
+    if a.dtype == np.float16:
+        a = a.view(np.uint16)
+    if a.dtype != np.uint16:
+        raise TypeError("s_mid must be float16 (or uint16 bits)")
+    _check(lib().nq_binlr_set_mid_scale(h, a.ctypes.data_as(ctypes.c_void_p)))
 
 
 def nq_binlr_reserve(h: int, max_batch: int) -> None:

@@ -111,6 +111,8 @@ struct nq_binlr_s {
     uint32_t* u_tiles;    // A = U   : M = d_out, N = r
     uint16_t* s_in;
     uint16_t* s_out;
+    uint16_t* s_mid;      // rank-wise scale of the three-scale variant, fp16 [r padded to 128], or nullptr
+    int mid_exp;          // ceil(log2(max |s_mid|)): keeps the dense path's fp16 intermediate in range
     // decode workspace (one allocation, sized for NQ_DECODE_MAX_BATCH, never reallocated)
     void* ws_alloc;
     Slab* ws_slab;
@@ -249,6 +251,7 @@ static void free_handle(nq_handle h)
     slab_release(h->w_slab);
     slab_release(h->ws_slab);
     if (h->pf_alloc) (void)hipFree(h->pf_alloc);
+    if (h->s_mid) (void)hipFree(h->s_mid);
     delete h;
 }
 
@@ -390,7 +393,41 @@ extern "C" int nq_binlr_destroy(nq_handle h)
 extern "C" size_t nq_binlr_weight_bytes(nq_handle h)
 {
     if (!h) return 0;
-    return (size_t)(h->r * (h->d_in + h->d_out) + 7) / 8 + 2 * (size_t)(h->d_in + h->d_out);
+    return (size_t)(h->r * (h->d_in + h->d_out) + 7) / 8 + 2 * (size_t)(h->d_in + h->d_out) +
+           (h->s_mid ? 2 * (size_t)h->r : 0);
+}
+
+extern "C" int nq_binlr_set_mid_scale(nq_handle h, const uint16_t* s_mid_fp16)
+{
+    if (!h) return fail(NQ_E_NULL, "nq_binlr_set_mid_scale: NULL handle");
+    {
+        std::lock_guard<std::mutex> lk(g_cache_mutex);
+        drop_cached_plan_locked();                       // its descriptors hold the old pointer
+    }
+    NQ_HIP(hipDeviceSynchronize());
+    if (!s_mid_fp16) {
+        if (h->s_mid) NQ_HIP(hipFree(h->s_mid));
+        h->s_mid = nullptr;
+        h->mid_exp = 0;
+        return NQ_OK;
+    }
+    float mx = 0.f;
+    for (int64_t k = 0; k < h->r; ++k) {
+        const float v = half_to_float_host(s_mid_fp16[k]);
+        if (!(std::fabs(v) <= 65504.f)) return fail(NQ_E_INVALID_ARG, "nq_binlr_set_mid_scale: non-finite scale");
+        mx = std::max(mx, std::fabs(v));
+    }
+    int e = 0;
+    if (mx > 0.f) {
+        (void)std::frexp(mx, &e);                          // mx = f 2^e, f in [0.5, 1)  ->  mx <= 2^e
+        e = std::max(-8, std::min(16, e));
+    }
+    const size_t bytes = (size_t)round_up(h->r, kTileRows) * 2;
+    if (!h->s_mid) NQ_HIP(hipMalloc((void**)&h->s_mid, bytes));
+    NQ_HIP(hipMemset(h->s_mid, 0, bytes));
+    NQ_HIP(hipMemcpy(h->s_mid, s_mid_fp16, (size_t)h->r * 2, hipMemcpyHostToDevice));
+    h->mid_exp = e;
+    return NQ_OK;
 }
 
 static int ensure_prefill_workspace(nq_handle h, int batch)
@@ -441,7 +478,7 @@ static StageDesc make_s1(nq_handle h)
 static QuantDesc make_qt(nq_handle h)
 {
     QuantDesc q;
-    q.x = h->t; q.scale = nullptr; q.bq = h->bq_t; q.meta = h->meta_t;
+    q.x = h->t; q.scale = h->s_mid; q.bq = h->bq_t; q.meta = h->meta_t;
     q.N = (int)h->r; q.n_chunks = (int)n_steps(h->r) * 4; q.x_stride = h->t_stride; q.dtype = NQ_F32;
     return q;
 }
@@ -473,7 +510,7 @@ static int decode_once(nq_handle h, const void* x, void* y, int batch, hipStream
         rc = launch_valu_gemv(h->vt_tiles, x, h->x_dtype, (int)h->d_in, h->s_in, nullptr, h->t, NQ_F32, h->t_stride,
                               h->r, h->d_in, batch, s);
         if (rc != NQ_OK) return rc;
-        return launch_valu_gemv(h->u_tiles, h->t, NQ_F32, h->t_stride, nullptr, h->s_out, y, h->y_dtype,
+        return launch_valu_gemv(h->u_tiles, h->t, NQ_F32, h->t_stride, h->s_mid, h->s_out, y, h->y_dtype,
                                 (int)h->d_out, h->d_out, h->r, batch, s);
     }
     QuantDesc qx = make_qx(h, x);
@@ -522,6 +559,7 @@ extern "C" int nq_binlr_forward(nq_handle h, const void* x, void* y, int batch, 
         if ((rc = ensure_prefill_workspace(h, batch)) != NQ_OK) return rc;
         PrefillArgs a;
         a.vt_tiles = h->vt_tiles; a.u_tiles = h->u_tiles; a.s_in = h->s_in; a.s_out = h->s_out;
+        a.s_mid = h->s_mid; a.mid_exp = h->mid_exp;
         a.x = x; a.y = y; a.workspace = h->pf_alloc;
         a.d_out = h->d_out; a.d_in = h->d_in; a.r = h->r; a.batch = batch; a.x_dtype = h->x_dtype; a.y_dtype = h->y_dtype;
         return launch_prefill(a, s);

@@ -175,6 +175,8 @@ struct PrefillArgs {
     const uint32_t* u_tiles;    // stage-2 sign tiles (A = U)
     const uint16_t* s_in;
     const uint16_t* s_out;
+    const uint16_t* s_mid;      // rank-wise scale (fp16, padded to whole row blocks with zeros) or nullptr
+    int mid_exp;                // |s_mid| <= 2^mid_exp
     const void* x;
     void* y;
     void* workspace;            // device, prefill_workspace_bytes()

@@ -50,6 +50,7 @@ struct GemmArgs {
     const float* tok_scale;    // EPI_Y: per token 1 / (2^a_b * g)
     const uint16_t* out_scale; // EPI_Y: fp16 [n_real]
     float t_scale;             // EPI_T: g
+    const uint16_t* mid_scale; // EPI_T: rank-wise scale fp16 [n_pad] (zeros beyond n_real) or nullptr
     int lda, ldt;
     int n_real;                // real output rows
     int n_rb;                  // row blocks of the weight
@@ -195,6 +196,28 @@ __device__ __forceinline__ uint32_t bfi_sign(uint32_t x, uint32_t one2)
     const uint32_t mask = 0x80008000u;
     asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(d) : "s"(mask), "v"(x), "v"(one2));
     return d;
+}
+
+// One lane's four results of gemm 1 (rows n0 .. n0 + 3 of token `tok`, raw accumulators of negated
+// signs) -> fp16 T: times g, times the rank-wise scale of the three-scale variant where there is
+// one (its own power of two is folded into g), rows beyond the real rank exact zeros (they are
+// padding of the next reduction); stored in the swizzled order 0, 2, 1, 3.
+__device__ __forceinline__ void store_t(const GemmArgs& a, int tok, int n0, const v4f c)
+{
+    float f[4] = {-a.t_scale, -a.t_scale, -a.t_scale, -a.t_scale};
+    if (a.mid_scale) {
+        const uint2 m = *(const uint2*)(a.mid_scale + n0);
+        f[0] *= h2f((uint16_t)(m.x & 0xFFFFu));
+        f[1] *= h2f((uint16_t)(m.x >> 16));
+        f[2] *= h2f((uint16_t)(m.y & 0xFFFFu));
+        f[3] *= h2f((uint16_t)(m.y >> 16));
+    }
+    v4h o;
+    o.x = (_Float16)(n0 + 0 < a.n_real ? c.x * f[0] : 0.f);
+    o.y = (_Float16)(n0 + 2 < a.n_real ? c.z * f[2] : 0.f);
+    o.z = (_Float16)(n0 + 1 < a.n_real ? c.y * f[1] : 0.f);
+    o.w = (_Float16)(n0 + 3 < a.n_real ? c.w * f[3] : 0.f);
+    *(v4h*)(a.t_out + (size_t)tok * a.ldt + n0) = o;
 }
 
 // TG = token groups of 16 per workgroup tile: 4 (64 tokens) normally; 2 (32 tokens) for narrow
@@ -381,14 +404,7 @@ prefill_gemm_kernel(GemmArgs a)
                 float* dst = a.partial + ((size_t)split * a.m_pad + tok) * a.n_pad + n0;
                 *(v4f*)dst = c;
             } else if (EPI == EPI_T) {
-                const float f = -a.t_scale;
-                v4h o;
-                // rows >= n_real are padding of the next reduction: exact zeros
-                o.x = (_Float16)(n0 + 0 < a.n_real ? c.x * f : 0.f);
-                o.y = (_Float16)(n0 + 2 < a.n_real ? c.z * f : 0.f);     // swizzled order 0,2,1,3
-                o.z = (_Float16)(n0 + 1 < a.n_real ? c.y * f : 0.f);
-                o.w = (_Float16)(n0 + 3 < a.n_real ? c.w * f : 0.f);
-                *(v4h*)(a.t_out + (size_t)tok * a.ldt + n0) = o;
+                store_t(a, tok, n0, c);
             } else {
                 if (tok < a.batch) {
                     const float f = -a.tok_scale[tok];
@@ -435,13 +451,7 @@ prefill_finalize_kernel(GemmArgs a)
     v4f c = {0.f, 0.f, 0.f, 0.f};
     for (int s = 0; s < a.splits; ++s) c += *(const v4f*)(a.partial + ((size_t)s * a.m_pad + tok) * a.n_pad + n0);
     if (EPI == EPI_T) {
-        const float f = -a.t_scale;
-        v4h o;
-        o.x = (_Float16)(n0 + 0 < a.n_real ? c.x * f : 0.f);
-        o.y = (_Float16)(n0 + 2 < a.n_real ? c.z * f : 0.f);
-        o.z = (_Float16)(n0 + 1 < a.n_real ? c.y * f : 0.f);
-        o.w = (_Float16)(n0 + 3 < a.n_real ? c.w * f : 0.f);
-        *(v4h*)(a.t_out + (size_t)tok * a.ldt + n0) = o;
+        store_t(a, tok, n0, c);
     } else {
         if (tok < a.batch) {
             const float f = -a.tok_scale[tok];
@@ -609,7 +619,8 @@ int launch_prefill(const PrefillArgs& p, hipStream_t s)
     // |x''| < 2^13, so |t''| < d_in * 2^13; g brings that to <= 2^15 (fp16 range 65504)
     int lg = 0;
     while (((int64_t)1 << lg) < p.d_in) ++lg;
-    const float g_t = ldexpf(1.0f, -(lg > 2 ? lg - 2 : 0));
+    // (with a rank-wise scale, |s_mid| <= 2^mid_exp, T = X''V g s_mid stays within the same bound)
+    const float g_t = ldexpf(1.0f, -(lg > 2 ? lg - 2 : 0) - (p.s_mid ? p.mid_exp : 0));
 
     hipLaunchKernelGGL(prefill_prescale_kernel, dim3(p.batch), dim3(kPreThreads), 0, s, p.x, p.x_dtype, p.s_in, (int)p.d_in,
                        L.k1, g_t, xs, tok_scale);
@@ -621,7 +632,7 @@ int launch_prefill(const PrefillArgs& p, hipStream_t s)
     a.partial = partial;
     // gemm1: T = X'' V
     a.act = xs; a.lda = L.k1; a.tiles = p.vt_tiles;
-    a.t_out = t; a.ldt = L.k2; a.t_scale = g_t;
+    a.t_out = t; a.ldt = L.k2; a.t_scale = g_t; a.mid_scale = p.s_mid;
     a.n_real = (int)p.r; a.n_rb = (int)n_rowblocks(p.r); a.nst = (int)n_steps(p.d_in);
     a.n_tiles = (a.n_rb + kPfWaves - 1) / kPfWaves;
     a.splits = L.splits1; a.steps_per_split = even_steps_per_split(a.nst, a.splits);

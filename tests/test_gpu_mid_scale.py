@@ -1,0 +1,132 @@
+"""GPU parity of the three-scale variant  y = s_out . (U (s_mid . (V^T (s_in . x))))  (the DBF /
+LittleBit format of Appendix F.4) against the fp64 oracle, through the C ABI, on every path."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2602_06694_amd import binding as nq
+from paper_2602_06694_amd import synth
+from gpu_util import DECODE_TOL, Layer, rel_err, to_device
+
+pytestmark = pytest.mark.gpu
+PREFILL_TOL = 7e-4
+
+
+def mid_scales(r, seed, signed=True):
+    """fp16 rank-wise scales |N(0,1)| + 0.1 (the recipe of the other scales), every fifth negative."""
+    s = synth.gen_scales(r, seed).astype(np.float16)
+    if signed:
+        s[::5] = -s[::5]
+    return s
+
+
+def mid_oracle(L, s_mid, x_np, return_t=False):
+    d = L.data
+    return oracle.forward_factored_mid(d.U_words, d.V_words, d.s_out, s_mid, d.s_in, L.d_out, L.d_in, L.r,
+                                       synth.x_as_f64(x_np, L.x_dtype), return_t=return_t)
+
+
+@pytest.mark.parametrize("shape", [(300, 200, 100), (129, 65, 33), (1024, 1024, 256), (640, 1500, 257)])
+def test_decode_batches_match_oracle(shape):
+    d_out, d_in, r = shape
+    L = Layer(d_out, d_in, r, "bf16", seed=2000 + r)
+    s_mid = mid_scales(r, 2100 + r)
+    nq.nq_binlr_set_mid_scale(L.h, s_mid)
+    assert nq.nq_binlr_weight_bytes(L.h) == oracle.layer_bits_mid(d_out, d_in, r) // 8 + (1 if oracle.layer_bits_mid(d_out, d_in, r) % 8 else 0)
+    for batch in (1, 2, 5, 8):
+        x = synth.gen_x(batch, d_in, 2200 + batch, "bf16")
+        ref, t_ref = mid_oracle(L, s_mid, x, return_t=True)
+        y = L.forward(x)
+        assert rel_err(y, ref) <= DECODE_TOL, (shape, batch)
+        # the intermediate is t before the rank-wise scale
+        t = nq.nq_binlr_read_intermediate(L.h, r, batch)
+        assert rel_err(t, t_ref) <= DECODE_TOL, (shape, batch)
+    # sampled rows against the definition (Tier A)
+    x = synth.gen_x(2, d_in, 2300, "bf16")
+    rows = np.array([0, d_out // 2, d_out - 1])
+    ref_rows = oracle.forward_dense_rows_mid(L.data.U_words, L.data.V_words, L.data.s_out, s_mid, L.data.s_in,
+                                             d_out, d_in, r, synth.x_as_f64(x, "bf16"), rows)
+    y = L.forward(x)
+    assert np.abs(y[:, rows] - ref_rows).max() <= DECODE_TOL * np.abs(ref_rows).max()
+    # removing the scale gives the two-scale layer again
+    nq.nq_binlr_set_mid_scale(L.h, None)
+    assert rel_err(L.forward(x), L.oracle(x)) <= DECODE_TOL
+    L.close()
+
+
+def test_mid_scale_of_ones_changes_no_bit():
+    import torch
+    L = Layer(512, 1024, 256, "bf16", seed=2400)
+    for batch in (1, 4, 8):
+        x = synth.gen_x(batch, 1024, 2410 + batch, "bf16")
+        y0 = L.forward(x)
+        nq.nq_binlr_set_mid_scale(L.h, np.ones(256, dtype=np.float16))
+        y1 = L.forward(x)
+        nq.nq_binlr_set_mid_scale(L.h, None)
+        assert np.array_equal(y0, y1), batch
+    L.close()
+
+
+def test_plans_and_every_schedule(monkeypatch):
+    """Plans (short fused launches, self-quantising chip-filling launches, separate quantisation
+    launches) and the plain vector-ALU kernels all apply the rank-wise scale."""
+    import torch
+    shapes = [(4096, 4096, 1024), (300, 4090, 1000), (129, 4040, 970)]
+    layers = [Layer(*s, "bf16", seed=2500 + i) for i, s in enumerate(shapes)]
+    mids = [mid_scales(s[2], 2600 + i) for i, s in enumerate(shapes)]
+    for L, m in zip(layers, mids):
+        nq.nq_binlr_set_mid_scale(L.h, m)
+    xs_np = [synth.gen_x(1, s[1], 2700 + i, "bf16") for i, s in enumerate(shapes)]
+    xs = [to_device(x, "bf16") for x in xs_np]
+    refs = [mid_oracle(L, m, x) for L, m, x in zip(layers, mids, xs_np)]
+    hs = [L.h for L in layers]
+    for env, want in (({}, {32}), ({"NQ_FUSE_MAX_MB": "0"}, {4, 16, 1}),
+                      ({"NQ_FUSE_MAX_MB": "0", "NQ_SCHEDULE_FULL": "1"}, {33, 34})):
+        for k in ("NQ_FUSE_MAX_MB", "NQ_SCHEDULE_FULL"):
+            monkeypatch.delenv(k, raising=False)
+        for k, v in env.items():
+            monkeypatch.setenv(k, v)
+        ys = [torch.full((1, s[0]), float("nan"), dtype=torch.float32, device="cuda") for s in shapes]
+        plan = nq.nq_plan_create(hs, xs, ys, 1)
+        assert set(nq.nq_plan_schedules(plan)) <= want, (env, nq.nq_plan_schedules(plan))
+        nq.nq_plan_forward(plan)
+        torch.cuda.synchronize()
+        for y, ref, s in zip(ys, refs, shapes):
+            assert rel_err(y.cpu().numpy(), ref) <= DECODE_TOL, (env, s)
+        nq.nq_plan_destroy(plan)
+    for L in layers:
+        L.close()
+    # vector-ALU kernels
+    L = Layer(300, 200, 100, "f32", seed=2800, flags=nq.NQ_FLAG_DECODE_VALU)
+    m = mid_scales(100, 2801)
+    nq.nq_binlr_set_mid_scale(L.h, m)
+    x = synth.gen_x(3, 200, 2802, "f32")
+    assert rel_err(L.forward(x), mid_oracle(L, m, x)) <= 1e-5
+    L.close()
+
+
+@pytest.mark.parametrize("shape,batch", [((1024, 2048, 512), 64), ((300, 1100, 1030), 40), ((4096, 1024, 3520), 130)])
+def test_dense_path_matches_oracle(shape, batch):
+    """Batches that take the dense matrix-core path; scales up to 16 and down to 1/64 exercise the
+    power of two that keeps the fp16 intermediate in range."""
+    d_out, d_in, r = shape
+    L = Layer(d_out, d_in, r, "bf16", seed=2900 + r)
+    x = synth.gen_x(batch, d_in, 2950 + batch, "bf16")
+    for gain in (1.0, 16.0, 1.0 / 64):
+        s_mid = (mid_scales(r, 2960 + r).astype(np.float32) * gain).astype(np.float16)
+        nq.nq_binlr_set_mid_scale(L.h, s_mid)
+        err = rel_err(L.forward(x), mid_oracle(L, s_mid, x))
+        assert err <= PREFILL_TOL, (shape, batch, gain, err)
+    L.close()
+
+
+def test_argument_checks():
+    L = Layer(64, 64, 32, "bf16", seed=2990)
+    bad = np.ones(32, dtype=np.float16)
+    bad[3] = np.inf
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_binlr_set_mid_scale(L.h, bad)
+    assert e.value.status == nq.NQ_E_INVALID_ARG
+    with pytest.raises(nq.NQError):
+        nq.nq_binlr_set_mid_scale(None, np.ones(32, dtype=np.float16))
+    L.close()

@@ -162,8 +162,9 @@ int nq_binlr_forward(nq_handle h, const void* x, void* y, int batch, void* strea
  * the stream, so a later call may read what an earlier one wrote.
  * At batch 1 a list whose launches would be short (a decoder block's few layers) runs as two
  * launches, the stage kernels quantising their own input; results are bit-identical either way.
- * The list is compiled into an internal plan that is cached while the
- * arguments repeat (compiling allocates and synchronises; replays do not). */
+ * The list is compiled into an internal plan; the plans of the 32 most recently used argument lists
+ * are kept (compiling allocates and synchronises; replays do not), so a model may call this once per
+ * group of layers.  The cache is emptied when a handle is destroyed or its rank-wise scale changed. */
 int nq_binlr_forward_many(const nq_handle* hs, const void* const* xs, void* const* ys,
                           int n, int batch, void* stream);
 

@@ -256,8 +256,14 @@ static void free_handle(nq_handle h)
 }
 
 static std::mutex g_cache_mutex;
-static nq_plan g_cached_plan = nullptr;
-static std::vector<const void*> g_cached_key;
+// plans compiled by nq_binlr_forward_many, most recently used first (a decoder block calls it with a
+// handful of different lists in turn: q, k, v | o | gate, up | down)
+struct CachedPlan {
+    std::vector<const void*> key;
+    nq_plan plan;
+};
+static std::vector<CachedPlan> g_plan_cache;
+constexpr size_t kPlanCacheSize = 32;
 static void drop_cached_plan_locked();
 
 // the inputs are host buffers (from_device = false) or device buffers of the current device
@@ -619,14 +625,13 @@ extern "C" int nq_plan_destroy(nq_plan p)
     return NQ_OK;
 }
 
+// every cached plan goes (a handle one of them may use is being destroyed or changed)
 static void drop_cached_plan_locked()
 {
-    if (g_cached_plan) {
-        (void)hipDeviceSynchronize();
-        nq_plan_destroy(g_cached_plan);
-        g_cached_plan = nullptr;
-        g_cached_key.clear();
-    }
+    if (g_plan_cache.empty()) return;
+    (void)hipDeviceSynchronize();
+    for (CachedPlan& c : g_plan_cache) nq_plan_destroy(c.plan);
+    g_plan_cache.clear();
 }
 
 static int env_int_api(const char* name, int dflt)
@@ -886,13 +891,20 @@ extern "C" int nq_binlr_forward_many(const nq_handle* hs, const void* const* xs,
     key.push_back((const void*)(intptr_t)batch);
     for (int i = 0; i < n; ++i) { key.push_back(hs[i]); key.push_back(xs[i]); key.push_back(ys[i]); }
     std::lock_guard<std::mutex> lk(g_cache_mutex);
-    if (!g_cached_plan || key != g_cached_key) {
-        drop_cached_plan_locked();
+    size_t at = 0;
+    while (at < g_plan_cache.size() && g_plan_cache[at].key != key) ++at;
+    if (at == g_plan_cache.size()) {
         nq_plan p = nullptr;
         int rc = nq_plan_create(&p, hs, xs, ys, n, batch);
         if (rc != NQ_OK) return rc;
-        g_cached_plan = p;
-        g_cached_key = key;
+        if (g_plan_cache.size() >= kPlanCacheSize) {          // the least recently used one makes room
+            (void)hipDeviceSynchronize();
+            nq_plan_destroy(g_plan_cache.back().plan);
+            g_plan_cache.pop_back();
+        }
+        g_plan_cache.push_back(CachedPlan{key, p});
+        at = g_plan_cache.size() - 1;
     }
-    return plan_run(g_cached_plan, (hipStream_t)stream, false);
+    if (at != 0) std::rotate(g_plan_cache.begin(), g_plan_cache.begin() + at, g_plan_cache.begin() + at + 1);
+    return plan_run(g_plan_cache.front().plan, (hipStream_t)stream, false);
 }

@@ -627,3 +627,86 @@ def test_forward_error_paths():
     with pytest.raises(nq.NQError):
         nq.nq_binlr_read_intermediate(L.h, 32, 9)
     L.close()
+
+
+def test_forward_many_keeps_several_lists_compiled():
+    """A decoder block calls forward_many with a handful of different lists in turn; their plans are
+    cached (most recently used first, 32 at most).  Correct results over alternating lists, over more
+    lists than the cache holds, and after a handle of a cached list has been destroyed."""
+    import torch
+    d = 256
+    layers = [Layer(d, d, 64, "bf16", seed=3000 + i) for i in range(6)]
+    groups = [[0, 1, 2], [3], [4, 5], [0, 3], [1], [2, 4]]
+    x_np = synth.gen_x(1, d, 3050, "bf16")
+    x = to_device(x_np, "bf16")
+    refs = [L.oracle(x_np) for L in layers]
+    outs = [[torch.zeros((1, d), dtype=torch.float32, device="cuda") for _ in layers] for _ in range(40)]
+    for rnd in range(3):
+        for gi, g in enumerate(groups):
+            ys = [outs[0][i] for i in g]
+            for y in ys:
+                y.fill_(float("nan"))
+            nq.nq_binlr_forward_many([layers[i].h for i in g], [x] * len(g), ys, 1)
+            torch.cuda.synchronize()
+            for i, y in zip(g, ys):
+                assert rel_err(y.cpu().numpy(), refs[i]) <= DECODE_TOL, (rnd, gi, i)
+    # 40 distinct lists (distinct output buffers): more than the cache holds
+    for k in range(40):
+        nq.nq_binlr_forward_many([layers[0].h, layers[1].h], [x, x], [outs[k][0], outs[k][1]], 1)
+    torch.cuda.synchronize()
+    for k in (0, 7, 39):
+        assert rel_err(outs[k][0].cpu().numpy(), refs[0]) <= DECODE_TOL
+        assert rel_err(outs[k][1].cpu().numpy(), refs[1]) <= DECODE_TOL
+    layers[5].close()                                   # empties the cache; the other lists compile again
+    y = torch.zeros((1, d), dtype=torch.float32, device="cuda")
+    nq.nq_binlr_forward_many([layers[3].h], [x], [y], 1)
+    torch.cuda.synchronize()
+    assert rel_err(y.cpu().numpy(), refs[3]) <= DECODE_TOL
+    for L in layers[:5]:
+        L.close()
+
+
+def test_plans_replay_correctly_from_a_hip_graph(monkeypatch):
+    """Launch-bound sequences of plans are meant to be captured into HIP graphs.  Every schedule is
+    captured (a short fused list, a chip-filling self-quantising list, a four-launch list at batch 3,
+    the two-column-group kernels at batch 8) and the graph is replayed several times with new inputs
+    and eager work in between; every replay must reproduce the eager result bit for bit."""
+    import torch
+    shapes = [(512, 4096, 1024), (300, 4090, 1000)]
+    cases = [({}, 1), ({"NQ_FUSE_MAX_MB": "0", "NQ_SCHEDULE_FULL": "1"}, 1), ({}, 3), ({"NQ_SCHEDULE_FULL": "1"}, 8)]
+    for env, batch in cases:
+        for k in ("NQ_FUSE_MAX_MB", "NQ_SCHEDULE_FULL"):
+            monkeypatch.delenv(k, raising=False)
+        for k, v in env.items():
+            monkeypatch.setenv(k, v)
+        layers = [Layer(*s, "bf16", seed=3100 + i) for i, s in enumerate(shapes)]
+        xs = [torch.zeros((batch, s[1]), dtype=torch.bfloat16, device="cuda") for s in shapes]
+        ys = [torch.zeros((batch, s[0]), dtype=torch.float32, device="cuda") for s in shapes]
+        plan = nq.nq_plan_create([L.h for L in layers], xs, ys, batch)
+
+        def new_inputs(seed):
+            for i, (x, s) in enumerate(zip(xs, shapes)):
+                x.copy_(to_device(synth.gen_x(batch, s[1], seed + i, "bf16"), "bf16"))
+
+        new_inputs(3200)
+        nq.nq_plan_forward(plan)                      # warm up outside the capture
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            nq.nq_plan_forward(plan)
+        for rep in range(4):
+            new_inputs(3300 + 10 * rep)
+            nq.nq_plan_forward(plan)                  # eager
+            torch.cuda.synchronize()
+            eager = [y.clone() for y in ys]
+            for y in ys:
+                y.fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for y, e in zip(ys, eager):
+                assert torch.equal(y, e), (env, batch, rep)
+        del graph
+        nq.nq_plan_destroy(plan)
+        for L in layers:
+            L.close()

@@ -212,3 +212,27 @@ def round_output(y: np.ndarray, dtype: str) -> np.ndarray:
         return out
     raise ValueError(f"unknown output type {dtype!r}")
 
+
+
+# ---- gradients with respect to the two scale vectors, signs frozen (Section 3.4; Algorithm 1, Phase 3) ----
+
+def scale_grads(U_words, V_words, s_out, s_in, d_out, d_in, r, x, g):
+    """For a loss L of the layer output y = W^ x with upstream gradient g = dL/dy ([batch, d_out]):
+        dL/ds_out_i = sum_b g_bi * sum_j (U V^T)_ij s_in_j x_bj
+        dL/ds_in_j  = sum_b x_bj * sum_i g_bi s_out_i (U V^T)_ij
+    (Eq. 1 differentiated; the packed signs are constants).  Plain fp64 numpy on the unpacked
+    factors; returns (ds_out [d_out], ds_in [d_in])."""
+    U = unpack_signs(_words(U_words, d_out, r), r).astype(np.float64)
+    V = unpack_signs(_words(V_words, d_in, r), r).astype(np.float64)
+    so, si = _f64(s_out, d_out), _f64(s_in, d_in)
+    x = _x(x, d_in)
+    g = np.ascontiguousarray(np.asarray(g, dtype=np.float64))
+    assert g.shape == (x.shape[0], d_out)
+    ds_out = np.zeros(d_out)
+    ds_in = np.zeros(d_in)
+    for b in range(x.shape[0]):
+        z = U @ (V.T @ (si * x[b]))                      # U V^T (s_in . x_b)
+        ds_out += g[b] * z
+        w = V @ (U.T @ (so * g[b]))                      # V U^T (s_out . g_b)
+        ds_in += x[b] * w
+    return ds_out, ds_in

@@ -424,3 +424,44 @@ def test_mid_scale_storage_formula():
     for d_out, d_in, r in [(4096, 4096, 1024), (11008, 4096, 1664), (1, 1, 1)]:
         assert oracle.layer_bits_mid(d_out, d_in, r) == oracle.layer_bits(d_out, d_in, r) + 16 * r
         assert oracle.layer_bits_mid(d_out, d_in, r) == r * (d_out + d_in) + 16 * (d_out + r + d_in)
+
+
+# ---------- gradients of the scale vectors (signs frozen: Section 3.4; Algorithm 1, Phase 3) ----------
+
+def test_scale_gradients_are_exact_differences_of_the_forward():
+    """y is linear in each scale entry, so dL/ds_i of L = sum(g * y) equals L(s + e_i) - L(s) exactly
+    (up to fp64 rounding): the gradient formulas are pinned to the forward oracle, entry by entry."""
+    d_out, d_in, r, batch = 23, 37, 19, 3
+    U, V, s_out, s_in, x = small_case(d_out, d_in, r, batch, 901)
+    Uw, Vw = np_pack(U), np_pack(V)
+    g = np.random.default_rng(902).standard_normal((batch, d_out))
+    so, si = s_out.astype(np.float64), s_in.astype(np.float64)
+
+    def loss(so_, si_):
+        return float((g * oracle.forward_factored(Uw, Vw, so_, si_, d_out, d_in, r, x)).sum())
+
+    ds_out, ds_in = oracle.scale_grads(Uw, Vw, s_out, s_in, d_out, d_in, r, x, g)
+    base = loss(so, si)
+    scale = max(np.abs(ds_out).max(), np.abs(ds_in).max())
+    for i in range(d_out):
+        e = so.copy()
+        e[i] += 1.0
+        assert abs((loss(e, si) - base) - ds_out[i]) <= 1e-9 * scale, i
+    for j in range(d_in):
+        e = si.copy()
+        e[j] += 1.0
+        assert abs((loss(so, e) - base) - ds_in[j]) <= 1e-9 * scale, j
+
+
+def test_scale_gradients_closed_form_all_plus_one():
+    """All signs +1: (U V^T)_ij = r, so ds_out_i = r sum_b g_bi (s_in . x_b) and ds_in_j = r sum_b x_bj (s_out . g_b)."""
+    d_out, d_in, r, batch = 12, 9, 7, 2
+    _, _, s_out, s_in, x = small_case(d_out, d_in, r, batch, 911)
+    g = np.random.default_rng(912).standard_normal((batch, d_out))
+    Uw, Vw = np_pack(np.ones((d_out, r), np.int8)), np_pack(np.ones((d_in, r), np.int8))
+    ds_out, ds_in = oracle.scale_grads(Uw, Vw, s_out, s_in, d_out, d_in, r, x, g)
+    so, si = s_out.astype(np.float64), s_in.astype(np.float64)
+    e_out = r * (g * (x @ si)[:, None]).sum(axis=0)
+    e_in = r * (x * (g @ so)[:, None]).sum(axis=0)
+    assert np.abs(ds_out - e_out).max() <= 1e-12 * np.abs(e_out).max()
+    assert np.abs(ds_in - e_in).max() <= 1e-12 * np.abs(e_in).max()

@@ -153,6 +153,25 @@ int nq_binlr_reserve(nq_handle h, int max_batch);
  * (fp16 operands, fp32 accumulation), unless the layer was created with NQ_FLAG_NO_PREFILL. */
 int nq_binlr_forward(nq_handle h, const void* x, void* y, int batch, void* stream);
 
+/* ---- scale gradients with the packed signs frozen (Section 3.4; Algorithm 1, Phase 3) ----
+ * For a loss L with upstream gradient g = dL/dy ([batch, d_out]):
+ *     dL/ds_out = sum_b g_b (.) z_b,                 z = U (V^T (s_in (.) x))        (the forward without s_out)
+ *     dL/ds_in  = sum_b x_b (.) w_b,                 w = V (U^T (s_out (.) g))
+ * z comes from nq_binlr_forward_unscaled on the layer; w from the same call on the transposed layer
+ * (nq_binlr_create with U and V, and s_out and s_in, exchanged: its forward without output scale
+ * is V (U^T (s_out (.) g))); nq_scale_grad does the products and the sum over the batch. */
+
+/* z = U (V^T (s_in (.) x)) [(.) s_mid where set]: the forward without its output scale.  Pointers
+ * and types as in nq_binlr_forward (z has y_dtype).  Any batch, run as passes of up to 8 tokens through the
+ * streaming kernels (exact integer accumulation).  Asynchronous on `stream`. */
+int nq_binlr_forward_unscaled(nq_handle h, const void* x, void* z, int batch, void* stream);
+
+/* out[j] = sum_{b < batch} a[b][j] * b[b][j], j < n.  a, b: device, [batch, n] row-major of a_dtype /
+ * b_dtype (NQ_F32, NQ_F16, NQ_BF16); out: device float [n].  fp64 accumulation, one rounding.
+ * Asynchronous on `stream`; allocates nothing. */
+int nq_scale_grad(const void* a, int a_dtype, const void* b, int b_dtype, int batch, int64_t n, float* out,
+                  void* stream);
+
 /* n independent forwards (same batch <= NQ_DECODE_MAX_BATCH) in four launches in total:
  * the streaming kernels walk a work list that covers all n layers, so small
  * layers do not pay one launch each.  hs/xs/ys: host arrays of n entries; xs[i]/ys[i]

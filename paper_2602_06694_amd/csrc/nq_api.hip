@@ -508,21 +508,22 @@ static int rbs_per_stream_item(int n_rb, int nst, int total_rb, int batch)
     return std::min(per, std::max(1, n_rb));
 }
 
-// one pass of the streaming path for batch <= 8
-static int decode_once(nq_handle h, const void* x, void* y, int batch, hipStream_t s)
+// one pass of the streaming path for batch <= 8; `unscaled`: without the output scale (z = U t)
+static int decode_once(nq_handle h, const void* x, void* y, int batch, hipStream_t s, bool unscaled = false)
 {
     int rc;
     if (h->flags & NQ_FLAG_DECODE_VALU) {
         rc = launch_valu_gemv(h->vt_tiles, x, h->x_dtype, (int)h->d_in, h->s_in, nullptr, h->t, NQ_F32, h->t_stride,
                               h->r, h->d_in, batch, s);
         if (rc != NQ_OK) return rc;
-        return launch_valu_gemv(h->u_tiles, h->t, NQ_F32, h->t_stride, h->s_mid, h->s_out, y, h->y_dtype,
+        return launch_valu_gemv(h->u_tiles, h->t, NQ_F32, h->t_stride, h->s_mid, unscaled ? nullptr : h->s_out, y, h->y_dtype,
                                 (int)h->d_out, h->d_out, h->r, batch, s);
     }
     QuantDesc qx = make_qx(h, x);
     StageDesc s1 = make_s1(h);
     QuantDesc qt = make_qt(h);
     StageDesc s2 = make_s2(h, y);
+    if (unscaled) s2.out_scale = nullptr;
     const int rb1 = (int)n_rowblocks(h->r), rb2 = (int)n_rowblocks(h->d_out);
     const int w1 = stage_schedule(rb1, s1.n_steps, batch), w2 = stage_schedule(rb2, s2.n_steps, batch);
     const int per1 = w1 == 1 ? rbs_per_stream_item(rb1, s1.n_steps, rb1, batch) : 1;
@@ -878,6 +879,33 @@ extern "C" int nq_plan_forward_timed(nq_plan p, void* stream, float ms[4])
     NQ_HIP(hipEventSynchronize(p->ev[4]));
     for (int i = 0; i < 4; ++i) NQ_HIP(hipEventElapsedTime(&ms[i], p->ev[i], p->ev[i + 1]));
     return NQ_OK;
+}
+
+// z = U (V^T (s_in (.) x)): the forward without its output scale, any batch, in passes of up to 8 tokens
+extern "C" int nq_binlr_forward_unscaled(nq_handle h, const void* x, void* z, int batch, void* stream)
+{
+    if (!h) return fail(NQ_E_NULL, "nq_binlr_forward_unscaled: NULL handle");
+    if (batch < 1) return fail(NQ_E_INVALID_ARG, "nq_binlr_forward_unscaled: batch must be >= 1");
+    const size_t xs = dtype_size(h->x_dtype), ys = dtype_size(h->y_dtype);
+    int rc = check_xy("nq_binlr_forward_unscaled", x, z, (size_t)batch * h->d_in * xs, (size_t)batch * h->d_out * ys);
+    if (rc != NQ_OK) return rc;
+    for (int b0 = 0; b0 < batch; b0 += NQ_DECODE_MAX_BATCH) {
+        const int nb = std::min(NQ_DECODE_MAX_BATCH, batch - b0);
+        rc = decode_once(h, (const char*)x + (size_t)b0 * h->d_in * xs, (char*)z + (size_t)b0 * h->d_out * ys, nb,
+                         (hipStream_t)stream, true);
+        if (rc != NQ_OK) return rc;
+    }
+    return NQ_OK;
+}
+
+extern "C" int nq_scale_grad(const void* a, int a_dtype, const void* b, int b_dtype, int batch, int64_t n, float* out,
+                             void* stream)
+{
+    if (!a || !b || !out) return fail(NQ_E_NULL, "nq_scale_grad: NULL pointer");
+    if (batch < 1 || n < 1) return fail(NQ_E_INVALID_ARG, "nq_scale_grad: batch and n must be >= 1");
+    for (int dt : {a_dtype, b_dtype})
+        if (dt != NQ_F32 && dt != NQ_F16 && dt != NQ_BF16) return fail(NQ_E_INVALID_ARG, "nq_scale_grad: dtype must be NQ_F32, NQ_F16 or NQ_BF16");
+    return launch_scale_grad(a, a_dtype, b, b_dtype, batch, n, out, (hipStream_t)stream);
 }
 
 extern "C" int nq_binlr_forward_many(const nq_handle* hs, const void* const* xs, void* const* ys, int n, int batch,

@@ -1540,6 +1540,30 @@ int launch_stage(const StageDesc* d_descs, const StageDesc& single, const WorkIt
 }
 
 // ---------------------------------------------------------------------------------------------
+// out[j] = sum_b a[b][j] * b[b][j]: the reduction over the batch that turns an upstream gradient
+// and an unscaled product into the gradient of a scale vector (Section 3.4: the scales are tuned
+// with the packed signs frozen).  One thread per column, fp64 accumulation, one rounding.
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+scale_grad_kernel(const void* __restrict__ a, int a_dtype, const void* __restrict__ b, int b_dtype, int batch, int64_t n,
+                  float* __restrict__ out)
+{
+    const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= n) return;
+    double acc = 0.0;
+    for (int t = 0; t < batch; ++t)
+        acc += (double)load_as_float(a, a_dtype, (int64_t)t * n + j) * (double)load_as_float(b, b_dtype, (int64_t)t * n + j);
+    out[j] = (float)acc;
+}
+
+int launch_scale_grad(const void* a, int a_dtype, const void* b, int b_dtype, int batch, int64_t n, float* out, hipStream_t s)
+{
+    hipLaunchKernelGGL(scale_grad_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, a, a_dtype, b, b_dtype, batch, n, out);
+    NQ_HIP(hipGetLastError());
+    return NQ_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
 // plain vector-ALU GEMV on the same sign tiles: one thread per output row, fp32 accumulate,
 // bit -> sign by mask and select (the paper-style "lightweight mask + FMA" kernel).
 // grid = (row blocks, batch), block = 128

@@ -163,6 +163,8 @@ int launch_fused_list(const FusedItem* d_items, int n_items, int max_steps, hipS
 constexpr int kSelfqSchedule1 = 33, kSelfqSchedule4 = 34;
 bool selfq_fits(int w, int max_steps, int min_steps, int batch);
 int launch_selfq(const FusedItem* d_items, int n_items, int w, int max_steps, hipStream_t s);
+int launch_scale_grad(const void* a, int a_dtype, const void* b, int b_dtype, int batch, int64_t n, float* out,
+                      hipStream_t s);
 int launch_valu_gemv(const uint32_t* tiles, const void* x, int x_dtype, int x_stride, const uint16_t* in_scale,
                      const uint16_t* out_scale, void* out, int out_dtype, int out_stride, int64_t M, int64_t N,
                      int batch, hipStream_t s);

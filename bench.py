@@ -109,7 +109,7 @@ def stage_bytes(shp, batch, y_size=4, self_quantising=(False, False)):
 
 
 SCHEDULE_KERNEL = {1: "nq::stage_stream_kernel", 4: "nq::stage_split_kernel<W=4>", 16: "nq::stage_split_kernel<W=16>",
-                   8: "nq::stage_shared_kernel", 32: "nq::stage_fused_kernel", 33: "nq::stage_selfq_kernel<W=1>",
+                   8: "nq::stage_shared_kernel", 9: "nq::stage_shared_kernel<resident input>", 32: "nq::stage_fused_kernel", 33: "nq::stage_selfq_kernel<W=1>",
                    34: "nq::stage_selfq_kernel<W=4>"}
 
 

@@ -199,7 +199,8 @@ int nq_plan_forward(nq_plan p, void* stream);
 int nq_plan_forward_timed(nq_plan p, void* stream, float ms[4]);
 /* Debug: which schedule each of the plan's two stage launches uses.  w[0] stage 1, w[1] stage 2:
  * 1 = one wave per item, 4 / 16 = that many waves share a row block, 8 = eight waves share an op's
- * input through LDS (batch 6..8), 32 = short batch-1 launch that quantises its own input,
+ * input through LDS (batch 6..8), 9 = the same with the whole input resident in LDS (reductions of at
+ * most 16 steps), 32 = short batch-1 launch that quantises its own input,
  * 33 / 34 = chip-filling batch-1 launch whose waves quantise their own share (one / four waves per row block). */
 int nq_plan_schedules(nq_plan p, int w[2]);
 int nq_plan_destroy(nq_plan p);

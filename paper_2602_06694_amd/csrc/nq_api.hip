@@ -701,6 +701,9 @@ extern "C" int nq_plan_create(nq_plan* out, const nq_handle* hs, const void* con
             // of the input: no quantisation launch, and the B operand comes out of LDS.
             int min_steps = max_steps;
             for (int i = 0; i < n; ++i) min_steps = std::min(min_steps, sd[i].n_steps);
+            // batch 6..8, short reductions: the shared-input kernel with the whole input resident in LDS
+            if (w == 1 && batch > 5 && max_steps <= 16 && total_rb >= schedule_full_rowblocks() && !getenv("NQ_NO_RESIDENT"))
+                w = kSharedResidentSchedule;
             if (w != kFusedSchedule && !getenv("NQ_NO_SELFQ") && total_rb >= schedule_full_rowblocks() &&
                 selfq_fits(w, max_steps, min_steps, batch))
                 w = w == 1 ? kSelfqSchedule1 : kSelfqSchedule4;
@@ -708,7 +711,7 @@ extern "C" int nq_plan_create(nq_plan* out, const nq_handle* hs, const void* con
         sched[st] = w;
         for (int i = 0; i < n; ++i) {
             const int nrb = (int)n_rowblocks(sd[i].M);
-            if (w == kSharedSchedule) {
+            if (w == kSharedSchedule || w == kSharedResidentSchedule) {
                 // eight waves share an op's input: items of 8 x (row blocks per wave) row blocks
                 const int group = kSharedSchedule * shared_per_wave(sd[i].n_steps, batch);
                 for (int rb = 0; rb < nrb; rb += group)

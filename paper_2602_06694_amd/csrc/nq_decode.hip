@@ -857,7 +857,10 @@ constexpr int kShareChunk = 8;
 constexpr int kShareTokStride = kShareChunk * (int)kBqStepBytes + 48;
 static_assert(kShareTokStride % 256 == 48, "bank spread");
 
-template <int NB>
+// RESIDENT: for reductions of at most 16 steps the whole quantised input (two chunks) is staged once
+// per item and stays in its two buffers; the row blocks then need neither refills nor barriers, and
+// the eight waves drift apart freely.
+template <int NB, bool RESIDENT>
 __global__ void __launch_bounds__(64 * kShareWaves) __attribute__((amdgpu_waves_per_eu(2, 2)))
 stage_shared_kernel(const StageDesc* __restrict__ descs, const WorkItem* __restrict__ items, int n_items, int per_max,
                     int batch)
@@ -949,6 +952,11 @@ stage_shared_kernel(const StageDesc* __restrict__ descs, const WorkItem* __restr
         }
         NQ_SHARE_LOAD(0);
         NQ_SHARE_STORE(0);
+        if (RESIDENT) {
+            NQ_SHARE_LOAD(chunks > 1 ? 1 : 0);             // (a one-chunk input is copied twice: no branch around loads)
+            NQ_SHARE_STORE(1);
+            __syncthreads();
+        }
 
         // operands of step j of the current chunk
 #define NQ_LDSB(dst, j)                                                          \
@@ -973,18 +981,29 @@ stage_shared_kernel(const StageDesc* __restrict__ descs, const WorkItem* __restr
         v4i acc[NB][8];                                                          \
         _Pragma("unroll") for (int cg = 0; cg < NB; ++cg)                        \
             _Pragma("unroll") for (int p = 0; p < 8; ++p) acc[cg][p] = v4i{0, 0, 0, 0}; \
-        for (int c = 0; c < passes; ++c, ++round) {                              \
-            __syncthreads();             /* chunk c is in its buffer; the other buffer is free */ \
-            const char* const bb = lds_b + (round & 1) * buf_bytes;              \
-            NQ_SHARE_LOAD(c + 1 == chunks ? 0 : c + 1);                          \
-            NQ_PASS(8);                                                          \
-            NQ_SHARE_STORE((round & 1) ^ 1);                                     \
-        }                                                                        \
-        if (HALF) {                                                              \
-            __syncthreads();                                                     \
-            const char* const bb = lds_b + (round & 1) * buf_bytes;              \
-            NQ_PASS(4);                                                          \
-            ++round;                                                             \
+        if (RESIDENT) {                                                          \
+            for (int c = 0; c < passes; ++c) {                                   \
+                const char* const bb = lds_b + c * buf_bytes;                    \
+                NQ_PASS(8);                                                      \
+            }                                                                    \
+            if (HALF) {                                                          \
+                const char* const bb = lds_b + passes * buf_bytes;               \
+                NQ_PASS(4);                                                      \
+            }                                                                    \
+        } else {                                                                 \
+            for (int c = 0; c < passes; ++c, ++round) {                          \
+                __syncthreads();         /* chunk c is in its buffer; the other buffer is free */ \
+                const char* const bb = lds_b + (round & 1) * buf_bytes;          \
+                NQ_SHARE_LOAD(c + 1 == chunks ? 0 : c + 1);                      \
+                NQ_PASS(8);                                                      \
+                NQ_SHARE_STORE((round & 1) ^ 1);                                 \
+            }                                                                    \
+            if (HALF) {                                                          \
+                __syncthreads();                                                 \
+                const char* const bb = lds_b + (round & 1) * buf_bytes;          \
+                NQ_PASS(4);                                                      \
+                ++round;                                                         \
+            }                                                                    \
         }                                                                        \
         if ((u) < my_n)                                                          \
             stage_epilogue<NB, 1, true>(acc, lds_epi, 0, lane, batch, rb_first + my0 + (u), ea, \
@@ -1387,7 +1406,7 @@ int shared_per_wave(int nst, int batch)
     return std::max(1, std::min(shared_max_per(batch), stream_target_steps(batch) / std::max(1, nst)));
 }
 
-template <int NB>
+template <int NB, bool RESIDENT>
 static int launch_shared_t(const StageDesc* d_descs, const WorkItem* d_items, int n_items, int batch, hipStream_t s)
 {
     static bool attr_set = false;
@@ -1400,11 +1419,11 @@ static int launch_shared_t(const StageDesc* d_descs, const WorkItem* d_items, in
     }
     if (n_items < 1) return NQ_OK;
     if (!attr_set) {
-        NQ_HIP(hipFuncSetAttribute((const void*)stage_shared_kernel<NB>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        NQ_HIP(hipFuncSetAttribute((const void*)stage_shared_kernel<NB, RESIDENT>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                    160 * 1024));
         attr_set = true;
     }
-    hipLaunchKernelGGL((stage_shared_kernel<NB>), dim3(n_items), dim3(64 * kShareWaves), lds_bytes, s, d_descs, d_items,
+    hipLaunchKernelGGL((stage_shared_kernel<NB, RESIDENT>), dim3(n_items), dim3(64 * kShareWaves), lds_bytes, s, d_descs, d_items,
                        n_items, per_max, batch);
     NQ_HIP(hipGetLastError());
     return NQ_OK;
@@ -1516,12 +1535,13 @@ int launch_stage(const StageDesc* d_descs, const StageDesc& single, const WorkIt
                  int w, int rbs_per_item, int batch, hipStream_t s)
 {
     const int nb = batch <= 5 ? 1 : 2;
-    if (w == kShareWaves) {
+    if (w == kShareWaves || w == kSharedResidentSchedule) {
         if (nb != 2) {
             set_error("launch_stage: the shared schedule is built for batch 6..8");
             return NQ_E_INVALID_ARG;
         }
-        return launch_shared_t<2>(d_descs, d_items, n_items, batch, s);
+        if (w == kShareWaves) return launch_shared_t<2, false>(d_descs, d_items, n_items, batch, s);
+        return launch_shared_t<2, true>(d_descs, d_items, n_items, batch, s);
     }
     if (w == 1) {
         const int mx = stream_max_rbs(batch);

@@ -149,6 +149,7 @@ int stage_schedule(int n_rb_total, int mean_steps, int batch);
 int stream_target_steps(int batch);
 int stream_max_rbs(int batch);           // row blocks one stream item may chain (bounded by its LDS output buffer)
 constexpr int kSharedSchedule = 8;       // stage_schedule()'s value for the workgroup-shared-input kernel
+constexpr int kSharedResidentSchedule = 9;   // the same kernel with the whole input resident in LDS (reductions <= 16 steps)
 int shared_per_wave(int nst, int batch); // row blocks per wave of an item of that kernel
 // w = 1: stream kernel (items are runs of rbs_per_item row blocks); w = 4 / 16: split kernel (one row block
 // per item); w = kSharedSchedule: shared-input kernel (items of up to 8 x shared_per_wave row blocks)

@@ -710,3 +710,28 @@ def test_plans_replay_correctly_from_a_hip_graph(monkeypatch):
         nq.nq_plan_destroy(plan)
         for L in layers:
             L.close()
+
+
+def test_resident_input_schedule_batches_6_to_8(monkeypatch):
+    """Batch 6..8 with reductions of at most 16 steps in launches that fill the chip: the eight waves
+    of a workgroup stage the op's whole quantised input in LDS once and stream their row blocks
+    without further barriers.  Reductions of 4, 8, 12 and 16 steps (one or two chunks, with and
+    without the closing half pass), items of more and fewer than eight row blocks, ragged rows."""
+    import torch
+    monkeypatch.setenv("NQ_SCHEDULE_FULL", "1")
+    shapes = [(4096, 1024, 1024), (300, 200, 100), (129, 700, 513), (1000, 520, 260), (2100, 1000, 700)]
+    layers = [Layer(*s, "bf16", seed=5000 + i) for i, s in enumerate(shapes)]
+    for batch in (6, 7, 8):
+        xs_np = [synth.gen_x(batch, s[1], 5100 + 10 * batch + i, "bf16") for i, s in enumerate(shapes)]
+        xs = [to_device(x, "bf16") for x in xs_np]
+        ys = [torch.full((batch, s[0]), float("nan"), dtype=torch.float32, device="cuda") for s in shapes]
+        plan = nq.nq_plan_create([L.h for L in layers], xs, ys, batch)
+        assert nq.nq_plan_schedules(plan) == [9, 9]
+        nq.nq_plan_forward(plan)
+        nq.nq_plan_forward(plan)
+        torch.cuda.synchronize()
+        for L, x, y, s in zip(layers, xs_np, ys, shapes):
+            assert rel_err(y.cpu().numpy(), L.oracle(x)) <= DECODE_TOL, (s, batch)
+        nq.nq_plan_destroy(plan)
+    for L in layers:
+        L.close()

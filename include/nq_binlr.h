@@ -200,8 +200,10 @@ int nq_plan_forward_timed(nq_plan p, void* stream, float ms[4]);
 /* Debug: which schedule each of the plan's two stage launches uses.  w[0] stage 1, w[1] stage 2:
  * 1 = one wave per item, 4 / 16 = that many waves share a row block, 8 = eight waves share an op's
  * input through LDS (batch 6..8), 9 = the same with the whole input resident in LDS (reductions of at
- * most 16 steps), 32 = short batch-1 launch that quantises its own input,
- * 33 / 34 = chip-filling batch-1 launch whose waves quantise their own share (one / four waves per row block). */
+ * most 16 steps), 32 = short batch-1 launch with reductions of 4097..16384 elements in which every
+ * workgroup (16 waves per row block) quantises the input for itself,
+ * 33 / 34 = batch-1 launch whose waves quantise their own share of the input (one / four waves per
+ * row block; reductions of at most 1024 / 4096 elements). */
 int nq_plan_schedules(nq_plan p, int w[2]);
 int nq_plan_destroy(nq_plan p);
 

@@ -530,13 +530,20 @@ static int decode_once(nq_handle h, const void* x, void* y, int batch, hipStream
     const int per2 = w2 == 1 ? rbs_per_stream_item(rb2, s2.n_steps, rb2, batch) : 1;
     // a lone layer is bound by launch latency: where the quantised input of a stage fits LDS, the
     // stage quantises it itself (two launches per forward instead of four)
-    static const bool no_fuse = getenv("NQ_NO_FUSE") != nullptr;
-    if (!no_fuse && fused_fits(s1.n_steps, batch)) {
+    // (reductions of up to 4096 elements by the waves of the one- or four-wave kernel, longer ones
+    // up to 16384 by the 16-wave kernel)
+    const bool no_fuse = getenv("NQ_NO_FUSE") != nullptr, no_selfq = getenv("NQ_NO_SELFQ") != nullptr;
+    const int sq1 = no_selfq ? 0 : selfq_width(s1.n_steps, s1.n_steps, batch);
+    const int sq2 = no_selfq ? 0 : selfq_width(s2.n_steps, s2.n_steps, batch);
+    if (sq1) {
+        if ((rc = launch_selfq(nullptr, rb1, qx, s1, sq1, s1.n_steps, s)) != NQ_OK) return rc;
+    } else if (!no_fuse && fused_fits(s1.n_steps, batch)) {
         if ((rc = launch_fused(qx, s1, s)) != NQ_OK) return rc;
     } else {
         if ((rc = launch_quantize(nullptr, qx, 1, qx.n_chunks, batch, s)) != NQ_OK) return rc;
         if ((rc = launch_stage(nullptr, s1, nullptr, (rb1 + per1 - 1) / per1, w1, per1, batch, s)) != NQ_OK) return rc;
     }
+    if (sq2) return launch_selfq(nullptr, rb2, qt, s2, sq2, s2.n_steps, s);
     if (!no_fuse && fused_fits(s2.n_steps, batch)) return launch_fused(qt, s2, s);
     if ((rc = launch_quantize(nullptr, qt, 1, qt.n_chunks, batch, s)) != NQ_OK) return rc;
     return launch_stage(nullptr, s2, nullptr, (rb2 + per2 - 1) / per2, w2, per2, batch, s);
@@ -688,24 +695,30 @@ extern "C" int nq_plan_create(nq_plan* out, const nq_handle* hs, const void* con
         }
         int w = stage_schedule(total_rb, (int)(sq / sm), batch);
         // A short launch at batch 1 is bound by launch latency, not by bandwidth: the stage then
-        // quantises its own input (every workgroup for itself), which saves the quantisation launch.
+        // quantises its own input, which saves the quantisation launch -- by the waves of the one- or
+        // four-wave kernel where the reductions are short enough for it (measured faster than the
+        // 16-wave kernel at every size: 4 layers of 4096x4096 r=1024 11.6 vs 13.0 us, 32 layers 13.8
+        // vs 29.5), else by the 16-wave kernel, every workgroup for itself, up to NQ_FUSE_MAX_MB of tiles.
         {
             int max_steps = 0;
             for (int i = 0; i < n; ++i) max_steps = std::max(max_steps, sd[i].n_steps);
             const double tile_mb = sm * (kTileWords * 4) / 1.0e6;
-            if (batch == 1 && !getenv("NQ_NO_FUSE") && fused_fits(max_steps, batch) &&
-                tile_mb <= (double)env_int_api("NQ_FUSE_MAX_MB", 24))
+            int min_steps = max_steps;
+            for (int i = 0; i < n; ++i) min_steps = std::min(min_steps, sd[i].n_steps);
+            const bool full = total_rb >= schedule_full_rowblocks();
+            const int sq = full || getenv("NQ_NO_SELFQ") ? 0 : selfq_width(max_steps, min_steps, batch);
+            if (sq)
+                w = sq == 1 ? kSelfqSchedule1 : kSelfqSchedule4;
+            else if (batch == 1 && !getenv("NQ_NO_FUSE") && fused_fits(max_steps, batch) &&
+                     tile_mb <= (double)env_int_api("NQ_FUSE_MAX_MB", 24))
                 w = kFusedSchedule;
             max_steps_of[st] = max_steps;
             // A launch that fills the chip keeps its schedule, but its waves quantise their own share
             // of the input: no quantisation launch, and the B operand comes out of LDS.
-            int min_steps = max_steps;
-            for (int i = 0; i < n; ++i) min_steps = std::min(min_steps, sd[i].n_steps);
             // batch 6..8, short reductions: the shared-input kernel with the whole input resident in LDS
             if (w == 1 && batch > 5 && max_steps <= 16 && total_rb >= schedule_full_rowblocks() && !getenv("NQ_NO_RESIDENT"))
                 w = kSharedResidentSchedule;
-            if (w != kFusedSchedule && !getenv("NQ_NO_SELFQ") && total_rb >= schedule_full_rowblocks() &&
-                selfq_fits(w, max_steps, min_steps, batch))
+            if ((w == 1 || w == 4) && !getenv("NQ_NO_SELFQ") && full && selfq_fits(w, max_steps, min_steps, batch))
                 w = w == 1 ? kSelfqSchedule1 : kSelfqSchedule4;
         }
         sched[st] = w;
@@ -839,7 +852,7 @@ static int plan_run(nq_plan p, hipStream_t s, bool timed)
                          int max_steps) {
         if (w == kFusedSchedule) return launch_fused_list(fitems, n_items, max_steps, s);
         if (w == kSelfqSchedule1 || w == kSelfqSchedule4)
-            return launch_selfq(fitems, n_items, w == kSelfqSchedule1 ? 1 : 4, max_steps, s);
+            return launch_selfq(fitems, n_items, qdummy, sdummy, w == kSelfqSchedule1 ? 1 : 4, max_steps, s);
         return launch_stage(sd, sdummy, items, n_items, w, stream_max_rbs(p->batch), p->batch, s);
     };
     if (timed) NQ_HIP(hipEventRecord(p->ev[0], s));

@@ -1028,9 +1028,10 @@ stage_shared_kernel(const StageDesc* __restrict__ descs, const WorkItem* __restr
 }
 
 // ---------------------------------------------------------------------------------------------
-// Batch 1 in launches that fill the chip: the stream / split schedules with the quantisation of
-// the input done by the waves themselves, which removes the two quantisation launches of a step
-// (19 of 205 us on the 1024-layer pool) and takes the B operand off the vector-memory path.
+// Batch 1: the stream / split schedules with the quantisation of the input done by the waves
+// themselves, which removes the two quantisation launches of a step (19 of 205 us on the
+// 1024-layer pool; 4 of a lone layer's dependent launch latencies become 2) and takes the B
+// operand off the vector-memory path.
 // A wave requests its first D tiles, reads the chunks of its OWN steps (wave, wave + W, ...), takes
 // their maximum (with W = 4 the four waves exchange theirs through LDS: the step follows from the
 // maximum of the whole vector), quantises its chunks into its LDS region in the layout of the
@@ -1046,20 +1047,26 @@ stage_shared_kernel(const StageDesc* __restrict__ descs, const WorkItem* __restr
 // launch measured faster: 4096x8192 r=1024 164 vs 169 us per step of a 512-layer pool, 11008x4096
 // r=1664 135 vs 143 us; the 1024-layer pool of 4096x4096 r=1024 layers gains 205 -> 191 us.
 // LDS: [W][kEpiRegion] (+ W maxima and flags when W = 4).
+// LIST: workgroup i takes items[i]; otherwise row block i of the one op in the kernel arguments q1 / s1.
 // ---------------------------------------------------------------------------------------------
-template <int W, int D>
+template <int W, int D, bool LIST>
 __global__ void __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(NQ_STAGE_WAVES, 8)))
-stage_selfq_kernel(const FusedItem* __restrict__ items)
+stage_selfq_kernel(const FusedItem* __restrict__ items, QuantDesc q1, StageDesc s1)
 {
     constexpr int region = kEpiRegion;
     extern __shared__ int lds[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int g = lane >> 4, n = lane & 15;
-    const FusedItem* e = items + blockIdx.x;               // uniform address of a kernel argument: scalar loads
-    const int rb = e->rb;
-    const QuantDesc qd = e->q;
-    const StageDesc sd = e->s;
+    int rb = blockIdx.x;
+    QuantDesc qd = q1;
+    StageDesc sd = s1;
+    if (LIST) {
+        const FusedItem* e = items + blockIdx.x;           // uniform address of a kernel argument: scalar loads
+        rb = e->rb;
+        qd = e->q;
+        sd = e->s;
+    }
     const int nst = sd.n_steps;
     char* const my_bq = (char*)(lds + wave * region);
 
@@ -1480,7 +1487,20 @@ bool selfq_fits(int w, int max_steps, int min_steps, int batch)
     return max_steps <= 16 * w;
 }
 
-int launch_selfq(const FusedItem* d_items, int n_items, int w, int max_steps, hipStream_t s)
+// Waves per row block (1 or 4) with which a batch-1 launch that does NOT fill the chip quantises in
+// the stage kernel, 0 if its reductions are too long for that.  Such a launch is bound by the
+// latency of its dependent launches and of a wave's chain of steps, so every length that fits is
+// taken (short ones too), with four waves unless every reduction is exactly one wave's 16 steps.
+int selfq_width(int max_steps, int min_steps, int batch)
+{
+    if (batch != 1) return 0;
+    if (max_steps <= 16 && min_steps >= 16) return 1;
+    return max_steps <= 64 ? 4 : 0;
+}
+
+// d_items == nullptr: the n_items row blocks of the one op (q1, s1).
+int launch_selfq(const FusedItem* d_items, int n_items, const QuantDesc& q1, const StageDesc& s1, int w, int max_steps,
+                 hipStream_t s)
 {
     if (n_items < 1) return NQ_OK;
     if (!selfq_fits(w, max_steps, 16, 1)) {
@@ -1488,10 +1508,15 @@ int launch_selfq(const FusedItem* d_items, int n_items, int w, int max_steps, hi
         return NQ_E_INVALID_ARG;
     }
     const size_t lds_bytes = (size_t)w * kEpiRegion * 4 + (w > 1 ? 2 * w * 4 : 0);     // + the waves' maxima and flags
-    if (w == 1)
-        hipLaunchKernelGGL((stage_selfq_kernel<1, kSelfqDepth1>), dim3((unsigned)n_items), dim3(64), lds_bytes, s, d_items);
+    const dim3 grid((unsigned)n_items);
+    if (w == 1 && d_items)
+        hipLaunchKernelGGL((stage_selfq_kernel<1, kSelfqDepth1, true>), grid, dim3(64), lds_bytes, s, d_items, q1, s1);
+    else if (w == 1)
+        hipLaunchKernelGGL((stage_selfq_kernel<1, kSelfqDepth1, false>), grid, dim3(64), lds_bytes, s, d_items, q1, s1);
+    else if (d_items)
+        hipLaunchKernelGGL((stage_selfq_kernel<4, kSelfqDepth4, true>), grid, dim3(256), lds_bytes, s, d_items, q1, s1);
     else
-        hipLaunchKernelGGL((stage_selfq_kernel<4, kSelfqDepth4>), dim3((unsigned)n_items), dim3(256), lds_bytes, s, d_items);
+        hipLaunchKernelGGL((stage_selfq_kernel<4, kSelfqDepth4, false>), grid, dim3(256), lds_bytes, s, d_items, q1, s1);
     NQ_HIP(hipGetLastError());
     return NQ_OK;
 }

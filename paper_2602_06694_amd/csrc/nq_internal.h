@@ -159,11 +159,13 @@ bool fused_fits(int nst, int batch);     // the quantised input of a stage fits 
 int launch_fused(const QuantDesc& q, const StageDesc& sd, hipStream_t s);
 constexpr int kFusedSchedule = 32;       // plan schedule code: a stage and its quantisation in one launch (batch 1)
 int launch_fused_list(const FusedItem* d_items, int n_items, int max_steps, hipStream_t s);
-// plan schedule codes: batch-1 launches that fill the chip, with the quantisation done by the waves
-// of the stage kernel themselves (stage_selfq_kernel<1> / <4>)
+// plan schedule codes: batch-1 launches with the quantisation done by the waves of the stage kernel
+// themselves (stage_selfq_kernel<1> / <4>: one or four waves per row block)
 constexpr int kSelfqSchedule1 = 33, kSelfqSchedule4 = 34;
 bool selfq_fits(int w, int max_steps, int min_steps, int batch);
-int launch_selfq(const FusedItem* d_items, int n_items, int w, int max_steps, hipStream_t s);
+int selfq_width(int max_steps, int min_steps, int batch);    // for launches that do not fill the chip; 0: none
+int launch_selfq(const FusedItem* d_items, int n_items, const QuantDesc& q1, const StageDesc& s1, int w, int max_steps,
+                 hipStream_t s);
 int launch_scale_grad(const void* a, int a_dtype, const void* b, int b_dtype, int batch, int64_t n, float* out,
                       hipStream_t s);
 int launch_valu_gemv(const uint32_t* tiles, const void* x, int x_dtype, int x_stride, const uint16_t* in_scale,

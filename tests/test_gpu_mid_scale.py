@@ -68,8 +68,8 @@ def test_mid_scale_of_ones_changes_no_bit():
 
 
 def test_plans_and_every_schedule(monkeypatch):
-    """Plans (short fused launches, self-quantising chip-filling launches, separate quantisation
-    launches) and the plain vector-ALU kernels all apply the rank-wise scale."""
+    """Plans (self-quantising launches, short and chip-filling; the 16-wave fused launches; separate
+    quantisation launches) and the plain vector-ALU kernels all apply the rank-wise scale."""
     import torch
     shapes = [(4096, 4096, 1024), (300, 4090, 1000), (129, 4040, 970)]
     layers = [Layer(*s, "bf16", seed=2500 + i) for i, s in enumerate(shapes)]
@@ -80,9 +80,10 @@ def test_plans_and_every_schedule(monkeypatch):
     xs = [to_device(x, "bf16") for x in xs_np]
     refs = [mid_oracle(L, m, x) for L, m, x in zip(layers, mids, xs_np)]
     hs = [L.h for L in layers]
-    for env, want in (({}, {32}), ({"NQ_FUSE_MAX_MB": "0"}, {4, 16, 1}),
+    for env, want in (({}, {33, 34}), ({"NQ_NO_SELFQ": "1"}, {32}),
+                      ({"NQ_NO_SELFQ": "1", "NQ_FUSE_MAX_MB": "0"}, {4, 16, 1}),
                       ({"NQ_FUSE_MAX_MB": "0", "NQ_SCHEDULE_FULL": "1"}, {33, 34})):
-        for k in ("NQ_FUSE_MAX_MB", "NQ_SCHEDULE_FULL"):
+        for k in ("NQ_FUSE_MAX_MB", "NQ_SCHEDULE_FULL", "NQ_NO_SELFQ"):
             monkeypatch.delenv(k, raising=False)
         for k, v in env.items():
             monkeypatch.setenv(k, v)

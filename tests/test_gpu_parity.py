@@ -482,31 +482,47 @@ def test_sixteen_bit_outputs_are_the_rounded_exact_result():
 
 
 def test_single_call_and_plan_give_identical_bits(monkeypatch):
-    """nq_binlr_forward runs a lone layer at batch 1 as two launches that quantise their input
-    themselves, and so does a plan whose launches are short; larger plans (here: forced by
-    NQ_FUSE_MAX_MB=0) run separate quantisation launches.  Same arithmetic, element for element:
-    the outputs (and the intermediate t) must be identical bit for bit.  The last shape is too
-    long for the fused launches' LDS and takes the four-launch path everywhere."""
+    """At batch 1 a lone layer (nq_binlr_forward) and a plan whose launches are short run two
+    launches that quantise their input themselves: by the waves of the one- or four-wave kernel
+    for reductions of up to 4096 elements, by the 16-wave kernel up to 16384 (NQ_NO_SELFQ=1 sends
+    the short ones there too); with NQ_FUSE_MAX_MB=0 as well, and for longer inputs, the
+    quantisation is a launch of its own.  Same arithmetic, element for element: the outputs (and
+    the intermediate t) must be identical bit for bit over all of these, single call and plan."""
     import torch
-    for shape in [(300, 200, 100), (129, 65, 33), (4096, 4096, 1024), (640, 1500, 257), (200, 60000, 96)]:
+    modes = ({}, {"NQ_NO_SELFQ": "1"}, {"NQ_NO_SELFQ": "1", "NQ_FUSE_MAX_MB": "0", "NQ_NO_FUSE": "1"})
+    for shape in [(300, 200, 100), (129, 65, 33), (4096, 4096, 1024), (640, 1500, 257), (300, 9000, 4100),
+                  (200, 60000, 96)]:
         L = Layer(*shape, "bf16", seed=700)
         for batch in (1, 4, 8):
             x_np = synth.gen_x(batch, shape[1], 710 + batch, "bf16")
-            y_single = L.forward(x_np)
-            t_single = nq.nq_binlr_read_intermediate(L.h, shape[2], batch)
             x = to_device(x_np, "bf16")
-            for fuse_max_mb in (None, "0"):
-                if fuse_max_mb is None:
-                    monkeypatch.delenv("NQ_FUSE_MAX_MB", raising=False)
-                else:
-                    monkeypatch.setenv("NQ_FUSE_MAX_MB", fuse_max_mb)
+            first = None
+            for env in modes:
+                for k in ("NQ_NO_SELFQ", "NQ_FUSE_MAX_MB", "NQ_NO_FUSE"):
+                    monkeypatch.delenv(k, raising=False)
+                for k, v in env.items():
+                    monkeypatch.setenv(k, v)
+                y_single = L.forward(x_np)
+                t_single = nq.nq_binlr_read_intermediate(L.h, shape[2], batch)
                 y = new_output(batch, shape[0])
                 plan = nq.nq_plan_create([L.h], [x], [y], batch)
+                if batch == 1 and shape == (4096, 4096, 1024):
+                    want = {0: [34, 33], 1: [32, 32], 3: None}[len(env)]
+                    if want:
+                        assert nq.nq_plan_schedules(plan) == want, env
+                    else:
+                        assert all(w in (1, 4, 16) for w in nq.nq_plan_schedules(plan)), env
                 nq.nq_plan_forward(plan)
                 torch.cuda.synchronize()
-                assert np.array_equal(nq.nq_binlr_read_intermediate(L.h, shape[2], batch), t_single), (shape, batch)
-                assert np.array_equal(y.cpu().numpy(), y_single), (shape, batch, fuse_max_mb)
+                t_plan = nq.nq_binlr_read_intermediate(L.h, shape[2], batch)
+                y_plan = y.cpu().numpy()
                 nq.nq_plan_destroy(plan)
+                if first is None:
+                    first = (y_single, t_single)
+                for got_y, got_t in ((y_single, t_single), (y_plan, t_plan)):
+                    assert np.array_equal(got_t, first[1]), (shape, batch, env)
+                    assert np.array_equal(got_y, first[0]), (shape, batch, env)
+            assert rel_err(first[0], L.oracle(x_np)) <= DECODE_TOL, (shape, batch)
         L.close()
 
 

@@ -574,7 +574,9 @@ struct PfLayout {
 
 // Tiling of one GEMM: token groups per workgroup tile (4 = 64 tokens, 2 = 32 tokens) and the number of
 // workgroups the reduction is split over, for outputs that alone give too few workgroups to
-// cover the chip.  Cost model in microseconds, constants measured on the 70B MLP shapes:
+// cover the chip.  Cost model in microseconds, constants measured on the 70B MLP shapes (with the
+// first version of the kernel; the kernel has since gained a few per cent everywhere, and sweeps
+// over splits and tile sizes on those shapes still land on the choices this model makes):
 //  - a reduction step of a 64-token workgroup takes 0.73 us when it has its CU to itself and
 //    1.17 us when two share one (two is all that fits);
 //  - a 32-token workgroup needs 0.60 us per step alone (the sign expansion is not halved), and a

@@ -92,3 +92,32 @@ def test_prefill_reserve_and_batch_changes():
         tol = PREFILL_TOL if batch >= nq.NQ_PREFILL_MIN_BATCH else 1e-5
         assert rel_err(L.forward(x), L.oracle(x)) <= tol, batch
     L.close()
+
+
+def test_prefill_activations_with_a_large_mean_and_uniform_sign_columns():
+    """The dense kernels accumulate P = the sum of the activations under the +1 weights and form
+    the signed sum as 2P - S (S = the plain sum).  That cancels most where the activations share
+    a large offset (S far above the signed sums), and it must be exact-ish where a column of V is
+    all +1 (P = S) or all -1 (P = 0): long reduction, all-positive inputs, constant inputs, and a V
+    whose first columns are uniform.  Same bar as every other dense case."""
+    d_out, d_in, r = 640, 8192, 384
+    rng = np.random.default_rng(77)
+    U = synth.gen_sign_words(d_out, r, 771)
+    V = synth.gen_sign_words(d_in, r, 772)
+    V[:, 0] |= np.uint32(0x0000FFFF)          # rank columns 0..15 all +1
+    V[:, 0] &= np.uint32(0x0000FFFF)          # rank columns 16..31 all -1
+    s_out = synth.gen_scales(d_out, 773)
+    s_in = np.full(d_in, 1.0, dtype=np.float16)           # keep the offset of x intact in x'
+    data = synth.LayerData(synth.LinearShape("m", d_out, d_in, r), U, V, s_out, s_in)
+    L = Layer(d_out, d_in, r, "f32", data=data)
+    batch = 80
+    x = (np.abs(rng.standard_normal((batch, d_in))) + 3.0).astype(np.float32)
+    x[1] = 2.5                                  # a constant token
+    x[2] = -x[2]                                # an all-negative one
+    x[3, ::2] = 0.0                             # half of the inputs zero
+    err = rel_err(L.forward(x), L.oracle(x))
+    assert err <= PREFILL_TOL, err
+    for b in range(4):
+        y, ref = L.forward(x)[b], L.oracle(x)[b]
+        assert np.abs(y - ref).max() <= PREFILL_TOL * np.abs(ref).max(), b
+    L.close()

@@ -725,8 +725,8 @@ extern "C" int nq_plan_create(nq_plan* out, const nq_handle* hs, const void* con
         for (int i = 0; i < n; ++i) {
             const int nrb = (int)n_rowblocks(sd[i].M);
             if (w == kSharedSchedule || w == kSharedResidentSchedule) {
-                // eight waves share an op's input: items of 8 x (row blocks per wave) row blocks
-                const int group = kSharedSchedule * shared_per_wave(sd[i].n_steps, batch);
+                // the waves of a workgroup share an op's input: items of kShareWaves x (row blocks per wave) row blocks
+                const int group = kShareWaves * shared_per_wave(sd[i].n_steps, batch);
                 for (int rb = 0; rb < nrb; rb += group)
                     lists[st].push_back(WorkItem{sd[i].tiles + (size_t)rb * sd[i].n_steps * kTileWords, sd[i].bq,
                                                  sd[i].n_steps, i, rb, std::min(group, nrb - rb)});

@@ -324,10 +324,92 @@ quantize_kernel(const QuantDesc* __restrict__ descs, QuantDesc single, int batch
     }
 }
 
+// The same for short vectors (at most 64 * H chunks): ONE WAVE per (vector, token), its chunks
+// held in registers between the two passes, reductions by shuffles only -- no workgroup barrier,
+// no LDS; a workgroup is four independent waves.  A launch of many short vectors is a chain of
+// latencies, not a stream: the 8192 (layer, token) pairs of 1024 ranks of 1024 at batch 8 took
+// 22 us as workgroups of 256 threads of which 64 had a chunk, three barriers each, and take 14 us
+// this way (13 -> 9 us at batch 4).  Taken for vectors of up to 1024 elements (H = 1); with more
+// chunks per lane (H = 2, 4: vectors of up to 4096) it measured the same as the workgroup kernel
+// or slower.  Same arithmetic element for element: identical bytes and constants.
+template <int H, bool STREAMED>
+__global__ void __launch_bounds__(256)
+quantize_wave_kernel(const QuantDesc* __restrict__ descs, QuantDesc single, int n_ops, int batch)
+{
+    const int lane = threadIdx.x & 63;
+    const int task = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+    if (task >= n_ops * batch) return;                      // whole waves leave; nothing below synchronises
+    const int op = task / batch, tok = task - op * batch;
+    const QuantDesc d = descs ? descs[op] : single;
+    const int64_t base = (int64_t)tok * d.x_stride;
+    const int esz = d.dtype == NQ_F32 ? 4 : 2;
+    const bool vec = (((size_t)d.x_stride * esz) & 15) == 0;
+
+    float hv[H][16];
+    float m = 0.f;
+    int bad = 0;
+#pragma unroll
+    for (int k = 0; k < H; ++k) {
+        // (a lane past the end re-reads the vector's first chunk: no branch around the loads, and
+        // the maximum does not change)
+        const int c = lane + 64 * k;
+        load_chunk16(d, base, c < d.n_chunks ? c : 0, vec, hv[k]);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const float a = fabsf(hv[k][i]);
+            if (!(a <= 3.0e38f)) bad = 1;
+            m = fmaxf(m, a);
+        }
+    }
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    bad = __builtin_amdgcn_ballot_w64(bad != 0) != 0;
+
+    int e = 0;
+    float step = 1.0f;
+    if (m > 0.f && !bad) {
+        (void)frexpf(m, &e);
+        int se = e - 22;
+        se = se < -126 ? -126 : se;
+        step = ldexpf(1.0f, se);
+    }
+    const float inv_step = 1.0f / step;
+
+    long long local_sum = 0;
+    uint4* const dst = (uint4*)(d.bq) + (size_t)tok * d.n_chunks * kSlices;
+#pragma unroll
+    for (int k = 0; k < H; ++k) {
+        const int c = lane + 64 * k;
+        if (c < d.n_chunks) local_sum += quantize_chunk16<STREAMED>(hv[k], inv_step, bad != 0, dst + bq_piece(c, 0));
+    }
+    double sum = (double)local_sum;
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+    if (lane == 0) {
+        QMeta mt;
+        mt.two_step = bad ? (double)__builtin_nanf("") : 2.0 * (double)step;
+        mt.neg_qs = -sum * (double)step;
+        d.meta[tok] = mt;
+    }
+}
+
 // max_chunks: the largest n_chunks among the launch's vectors
 int launch_quantize(const QuantDesc* d_descs, const QuantDesc& single, int n_ops, int max_chunks, int batch,
                     hipStream_t s)
 {
+    const bool no_wave = getenv("NQ_NO_QUANT_WAVE") != nullptr;
+    // several short vectors: one wave each (a lone short vector keeps the workgroup kernel, whose
+    // threads share it)
+    if (!no_wave && max_chunks <= 64 && (size_t)n_ops * batch >= 64) {
+        const dim3 wgrid((unsigned)(((size_t)n_ops * batch + 3) / 4));
+#define NQ_LAUNCH_QWAVE(H)                                                                              \
+    do {                                                                                                \
+        if (batch <= 5) hipLaunchKernelGGL((quantize_wave_kernel<H, true>), wgrid, dim3(256), 0, s, d_descs, single, n_ops, batch); \
+        else hipLaunchKernelGGL((quantize_wave_kernel<H, false>), wgrid, dim3(256), 0, s, d_descs, single, n_ops, batch);           \
+    } while (0)
+        NQ_LAUNCH_QWAVE(1);
+#undef NQ_LAUNCH_QWAVE
+        NQ_HIP(hipGetLastError());
+        return NQ_OK;
+    }
     const dim3 grid(n_ops, batch);
 #define NQ_LAUNCH_QUANT(T)                                                                              \
     do {                                                                                                \
@@ -402,7 +484,7 @@ int launch_pack_signs(const void* d_signs, int dtype, int64_t rows, int64_t cols
 //   stage_split_kernel<W> : W waves of one workgroup interleave the 64-column steps of ONE row
 //       block and are summed through LDS.  For long reductions, and for launches with too few row
 //       blocks to fill the chip.
-//   stage_shared_kernel : eight waves take row blocks of one op and share its quantised input
+//   stage_shared_kernel : the waves of a workgroup take row blocks of one op and share its quantised input
 //       through LDS (further down).  For two column groups in launches that fill the chip.
 // In all of them a grid as large as the item list makes the hardware workgroup dispatcher the
 // work queue (the list is sorted longest first).
@@ -831,16 +913,19 @@ stage_split_kernel(const StageDesc* __restrict__ descs, StageDesc single, const 
     }
 }
 // ---------------------------------------------------------------------------------------------
-// Third schedule, for two column groups (batch 6..8) in launches that fill the chip: the eight
-// waves of a workgroup take row blocks of ONE op and share its quantised input through LDS.
-// With the B operand out of the registers (and off the vector-memory counter, which returns
+// Third schedule, for two column groups (batch 6..8) in launches that fill the chip: the W =
+// kShareWaves waves of a workgroup take row blocks of ONE op and share its quantised input through
+// LDS.  With the B operand out of the registers (and off the vector-memory counter, which returns
 // loads in order) a wave affords a ring of eight tiles although the 64 accumulator registers
-// leave room for two waves per SIMD only; and the input is fetched from L2 once per eight
-// row blocks instead of once per row block.
+// leave room for two waves per SIMD only; and the input is fetched from L2 once per W or more
+// row blocks instead of once per row block.  W = 4, so that TWO workgroups share a CU and one
+// streams while the other stages its input, waits at a barrier or flushes its results: with W = 8
+// (one workgroup per CU, nothing to overlap with) the 1024-layer pool of 4096x4096 r=1024 layers
+// took 377 us per step at batch 8, with W = 4 it takes 349 (stage 1 139 -> 129, stage 2 188 -> 168).
 //   - the input is staged in chunks of 8 steps (one pass over the ring), double buffered; every
-//     wave fetches 1/8 of the next chunk at the start of a pass and writes it to LDS at the end
+//     wave fetches 1/W of the next chunk at the start of a pass and writes it to LDS at the end
 //     (by then those loads are the oldest outstanding ones); one barrier per pass;
-//   - wave w owns `per` = ceil(n_rb / 8) consecutive row blocks of the item (their tiles are
+//   - wave w owns `per` = ceil(n_rb / W) consecutive row blocks of the item (their tiles are
 //     contiguous, the ring runs on across them); results are deferred through LDS as in the
 //     stream kernel;
 //   - a reduction that is not a multiple of 8 steps ends in half a pass, so such ops get one row
@@ -848,9 +933,8 @@ stage_split_kernel(const StageDesc* __restrict__ descs, StageDesc single, const 
 //   - refills past the wave's last tile re-read that tile, and a wave with fewer row blocks than
 //     its siblings keeps multiplying that tile without storing anything: no branches around
 //     loads, the wait counts stay exact.
-// LDS: [2][batch][kShareTokStride] input | [8][kEpiRegion] epilogue | [8][per_max][128 * batch] results.
+// LDS: [2][batch][kShareTokStride] input | [W][kEpiRegion] epilogue | [W][per_max][128 * batch] results.
 // ---------------------------------------------------------------------------------------------
-constexpr int kShareWaves = 8;
 constexpr int kShareChunk = 8;
 // bytes between tokens of a staged chunk; = 48 mod 256, which spreads the 15 (token, slice)
 // operands of a 16-lane group over all LDS banks
@@ -859,7 +943,7 @@ static_assert(kShareTokStride % 256 == 48, "bank spread");
 
 // RESIDENT: for reductions of at most 16 steps the whole quantised input (two chunks) is staged once
 // per item and stays in its two buffers; the row blocks then need neither refills nor barriers, and
-// the eight waves drift apart freely.
+// the waves drift apart freely.
 template <int NB, bool RESIDENT>
 __global__ void __launch_bounds__(64 * kShareWaves) __attribute__((amdgpu_waves_per_eu(2, 2)))
 stage_shared_kernel(const StageDesc* __restrict__ descs, const WorkItem* __restrict__ items, int n_items, int per_max,
@@ -867,7 +951,6 @@ stage_shared_kernel(const StageDesc* __restrict__ descs, const WorkItem* __restr
 {
     extern __shared__ int lds[];
     constexpr int W = kShareWaves;
-    static_assert(kShareWaves == kSharedSchedule, "schedule code");
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -890,8 +973,8 @@ stage_shared_kernel(const StageDesc* __restrict__ descs, const WorkItem* __restr
     // a piece copies piece 0 as well (same bytes to the same place), which keeps the copy free of
     // branches and the wait counts the same on every path.
     constexpr int kPiecesPerTok = kShareChunk * (int)kBqStepBytes / 16;        // 96
-    constexpr int kShare = 2;
-    static_assert(kShare * 64 * kShareWaves >= 8 * kPiecesPerTok, "a chunk of 8 tokens in 2 pieces per thread");
+    constexpr int kShare = (8 * kPiecesPerTok + 64 * kShareWaves - 1) / (64 * kShareWaves);
+    static_assert(kShare * 64 * kShareWaves >= 8 * kPiecesPerTok, "a chunk of 8 tokens in kShare pieces per thread");
     uint32_t sh_src[kShare], sh_dst[kShare];
 #pragma unroll
     for (int i = 0; i < kShare; ++i) {
@@ -1401,7 +1484,7 @@ static int launch_split_t(const StageDesc* d_descs, const StageDesc& single, con
 // Row blocks per wave of the shared schedule: bounded by the LDS left for deferred results.
 int shared_max_per(int batch)
 {
-    const int left = 160 * 1024 - 1024 - 2 * batch * kShareTokStride - kShareWaves * kEpiRegion * 4;
+    const int left = kShareLdsBytes - 2 * batch * kShareTokStride - kShareWaves * kEpiRegion * 4;
     const int per = left / (kShareWaves * kTileRows * 4 * batch);
     return std::max(1, std::min(per, 4));
 }
@@ -1530,7 +1613,7 @@ int stage_schedule(int n_rb_total, int mean_steps, int batch)
     // which lets small inputs exercise the schedules built for large launches)
     const int full = schedule_full_rowblocks();
     int w;
-    if (n_rb_total >= full && batch > 5) w = mean_steps >= env_int("NQ_SHARE_STEPS", 32) ? kShareWaves : 1;
+    if (n_rb_total >= full && batch > 5) w = mean_steps >= env_int("NQ_SHARE_STEPS", 32) ? kSharedSchedule : 1;
     else if (n_rb_total >= full) w = mean_steps >= env_int("NQ_SPLIT_STEPS", 64) ? 4 : 1;
     else w = (n_rb_total * 4 >= full || batch > 2) ? 4 : 16;
     if (const char* f = getenv("NQ_FORCE_W")) {
@@ -1560,12 +1643,12 @@ int launch_stage(const StageDesc* d_descs, const StageDesc& single, const WorkIt
                  int w, int rbs_per_item, int batch, hipStream_t s)
 {
     const int nb = batch <= 5 ? 1 : 2;
-    if (w == kShareWaves || w == kSharedResidentSchedule) {
+    if (w == kSharedSchedule || w == kSharedResidentSchedule) {
         if (nb != 2) {
             set_error("launch_stage: the shared schedule is built for batch 6..8");
             return NQ_E_INVALID_ARG;
         }
-        if (w == kShareWaves) return launch_shared_t<2, false>(d_descs, d_items, n_items, batch, s);
+        if (w == kSharedSchedule) return launch_shared_t<2, false>(d_descs, d_items, n_items, batch, s);
         return launch_shared_t<2, true>(d_descs, d_items, n_items, batch, s);
     }
     if (w == 1) {

@@ -148,11 +148,18 @@ int launch_quantize(const QuantDesc* d_descs, const QuantDesc& single, int n_ops
 int stage_schedule(int n_rb_total, int mean_steps, int batch);
 int stream_target_steps(int batch);
 int stream_max_rbs(int batch);           // row blocks one stream item may chain (bounded by its LDS output buffer)
+#ifndef NQ_SHARE_WAVES
+#define NQ_SHARE_WAVES 4
+#endif
+constexpr int kShareWaves = NQ_SHARE_WAVES;    // waves of a workgroup of the shared-input kernel
+// LDS one such workgroup may take: with four waves two workgroups share a CU (one streams while
+// the other stages its input or flushes its results), with eight a workgroup has the CU to itself
+constexpr int kShareLdsBytes = (kShareWaves <= 4 ? 80 : 160) * 1024 - 1024;
 constexpr int kSharedSchedule = 8;       // stage_schedule()'s value for the workgroup-shared-input kernel
 constexpr int kSharedResidentSchedule = 9;   // the same kernel with the whole input resident in LDS (reductions <= 16 steps)
 int shared_per_wave(int nst, int batch); // row blocks per wave of an item of that kernel
 // w = 1: stream kernel (items are runs of rbs_per_item row blocks); w = 4 / 16: split kernel (one row block
-// per item); w = kSharedSchedule: shared-input kernel (items of up to 8 x shared_per_wave row blocks)
+// per item); w = kSharedSchedule: shared-input kernel (items of up to kShareWaves x shared_per_wave row blocks)
 int launch_stage(const StageDesc* d_descs, const StageDesc& single, const WorkItem* d_items, int n_items,
                  int w, int rbs_per_item, int batch, hipStream_t s);
 bool fused_fits(int nst, int batch);     // the quantised input of a stage fits the LDS of the fused kernel

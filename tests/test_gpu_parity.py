@@ -751,3 +751,41 @@ def test_resident_input_schedule_batches_6_to_8(monkeypatch):
         nq.nq_plan_destroy(plan)
     for L in layers:
         L.close()
+
+
+def test_wave_per_vector_quantiser_matches_workgroup_quantiser(monkeypatch):
+    """Launches of many short vectors (at most 1024 elements each, 64 or more (vector, token)
+    pairs) quantise with one wave per pair instead of one workgroup; NQ_NO_QUANT_WAVE=1 keeps the
+    workgroup kernel.  Same arithmetic: the outputs must be identical bit for bit, with ragged
+    lengths (1 element, 1000, 1024), fp32 and bf16 inputs, a non-finite token, batches 3 and 8
+    (non-temporal and plain stores of the quantised bytes)."""
+    import torch
+    for x_dtype in ("bf16", "f32"):
+        shapes = [(200, 1, 1000), (129, 1000, 1024), (300, 1024, 70), (64, 517, 333)] * 6
+        layers = [Layer(*s, x_dtype, seed=3100 + i) for i, s in enumerate(shapes)]
+        hs = [L.h for L in layers]
+        for batch in (3, 8):
+            xs_np = [synth.gen_x(batch, s[1], 3200 + i, x_dtype) for i, s in enumerate(shapes)]
+            xs_np[5][batch - 1, 3] = np.uint16(0x7F80) if x_dtype == "bf16" else np.inf       # +infinity
+            xs = [to_device(x, x_dtype) for x in xs_np]
+            outs = {}
+            for mode in ("wave", "workgroup"):
+                if mode == "workgroup":
+                    monkeypatch.setenv("NQ_NO_QUANT_WAVE", "1")
+                else:
+                    monkeypatch.delenv("NQ_NO_QUANT_WAVE", raising=False)
+                ys = [new_output(batch, s[0]) for s in shapes]
+                plan = nq.nq_plan_create(hs, xs, ys, batch)
+                nq.nq_plan_forward(plan)
+                torch.cuda.synchronize()
+                outs[mode] = [y.cpu().numpy() for y in ys]
+                nq.nq_plan_destroy(plan)
+            for i, (L, x) in enumerate(zip(layers, xs_np)):
+                assert np.array_equal(outs["wave"][i], outs["workgroup"][i], equal_nan=True), (shapes[i], batch, x_dtype)
+                if i == 5:
+                    assert np.isnan(outs["wave"][i][batch - 1]).all()
+                    assert rel_err(outs["wave"][i][:batch - 1], L.oracle(x[:batch - 1])) <= DECODE_TOL
+                else:
+                    assert rel_err(outs["wave"][i], L.oracle(x)) <= DECODE_TOL, (shapes[i], batch, x_dtype)
+        for L in layers:
+            L.close()

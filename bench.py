@@ -264,7 +264,7 @@ def time_stack(cfg, batch, steps=10, warmup=2):
 
 
 def time_pool_batch(pool, batch, steps=10, warmup=2):
-    """Config 2's layer at a decode batch other than the headline's (BASELINE quotes batch 8 too):
+    """Config 2's layer at a decode batch other than the headline's (the metric is quoted at batch 8 too):
     the same rotating pool of distinct instances, one plan."""
     import numpy as np
     import torch

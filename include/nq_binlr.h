@@ -199,7 +199,7 @@ int nq_plan_forward(nq_plan p, void* stream);
 int nq_plan_forward_timed(nq_plan p, void* stream, float ms[4]);
 /* Debug: which schedule each of the plan's two stage launches uses.  w[0] stage 1, w[1] stage 2:
  * 1 = one wave per item, 4 / 16 = that many waves share a row block, 8 = the waves of a workgroup share an op's
- * input through LDS (batch 6..8), 9 = the same with the whole input resident in LDS (reductions of at
+ * input through LDS (batch 4..8), 9 = the same with the whole input resident in LDS (reductions of at
  * most 16 steps), 32 = short batch-1 launch with reductions of 4097..16384 elements in which every
  * workgroup (16 waves per row block) quantises the input for itself,
  * 33 / 34 = batch-1 launch whose waves quantise their own share of the input (one / four waves per

@@ -913,7 +913,8 @@ stage_split_kernel(const StageDesc* __restrict__ descs, StageDesc single, const 
     }
 }
 // ---------------------------------------------------------------------------------------------
-// Third schedule, for two column groups (batch 6..8) in launches that fill the chip: the W =
+// Third schedule, for batch 6..8 (two column groups) and the long reductions of batch 4..5, in
+// launches that fill the chip: the W =
 // kShareWaves waves of a workgroup take row blocks of ONE op and share its quantised input through
 // LDS.  With the B operand out of the registers (and off the vector-memory counter, which returns
 // loads in order) a wave affords a ring of eight tiles although the 64 accumulator registers
@@ -945,7 +946,7 @@ static_assert(kShareTokStride % 256 == 48, "bank spread");
 // per item and stays in its two buffers; the row blocks then need neither refills nor barriers, and
 // the waves drift apart freely.
 template <int NB, bool RESIDENT>
-__global__ void __launch_bounds__(64 * kShareWaves) __attribute__((amdgpu_waves_per_eu(2, 2)))
+__global__ void __launch_bounds__(64 * kShareWaves) __attribute__((amdgpu_waves_per_eu(NB == 2 ? 2 : 3, NB == 2 ? 2 : 8)))
 stage_shared_kernel(const StageDesc* __restrict__ descs, const WorkItem* __restrict__ items, int n_items, int per_max,
                     int batch)
 {
@@ -1484,7 +1485,8 @@ static int launch_split_t(const StageDesc* d_descs, const StageDesc& single, con
 // Row blocks per wave of the shared schedule: bounded by the LDS left for deferred results.
 int shared_max_per(int batch)
 {
-    const int left = kShareLdsBytes - 2 * batch * kShareTokStride - kShareWaves * kEpiRegion * 4;
+    const int budget = batch > 5 ? kShareLdsBytes : (batch == 5 ? 52 : 39) * 1024;      // 2, 3 or 4 workgroups per CU
+    const int left = budget - 2 * batch * kShareTokStride - kShareWaves * kEpiRegion * 4;
     const int per = left / (kShareWaves * kTileRows * 4 * batch);
     return std::max(1, std::min(per, 4));
 }
@@ -1607,13 +1609,19 @@ int launch_selfq(const FusedItem* d_items, int n_items, const QuantDesc& q1, con
 // Row blocks from which a launch counts as filling the chip.
 int schedule_full_rowblocks() { return env_int("NQ_SCHEDULE_FULL", device_cu_count() * 8); }
 
+// Smallest batch whose long reductions take the shared-input kernel in launches that fill the chip.
+// With one column group (batch <= 5) it pays from batch 4 on (stage 1 of the 4096x4096 r=1024 pool:
+// 121 -> 116 us at batch 4, 130 -> 120 us at batch 5; batch 3 the same, batch 2 slower); short
+// reductions (the resident variant) stay with the stream kernel below batch 6 (115 against 119 us).
+int shared_min_batch() { return env_int("NQ_SHARE_MIN_BATCH", 4); }
+
 int stage_schedule(int n_rb_total, int mean_steps, int batch)
 {
     // row blocks from which a launch counts as filling the chip (NQ_SCHEDULE_FULL overrides it,
     // which lets small inputs exercise the schedules built for large launches)
     const int full = schedule_full_rowblocks();
     int w;
-    if (n_rb_total >= full && batch > 5) w = mean_steps >= env_int("NQ_SHARE_STEPS", 32) ? kSharedSchedule : 1;
+    if (n_rb_total >= full && batch >= shared_min_batch()) w = mean_steps >= env_int("NQ_SHARE_STEPS", 32) ? kSharedSchedule : 1;
     else if (n_rb_total >= full) w = mean_steps >= env_int("NQ_SPLIT_STEPS", 64) ? 4 : 1;
     else w = (n_rb_total * 4 >= full || batch > 2) ? 4 : 16;
     if (const char* f = getenv("NQ_FORCE_W")) {
@@ -1644,9 +1652,9 @@ int launch_stage(const StageDesc* d_descs, const StageDesc& single, const WorkIt
 {
     const int nb = batch <= 5 ? 1 : 2;
     if (w == kSharedSchedule || w == kSharedResidentSchedule) {
-        if (nb != 2) {
-            set_error("launch_stage: the shared schedule is built for batch 6..8");
-            return NQ_E_INVALID_ARG;
+        if (nb == 1) {
+            if (w == kSharedSchedule) return launch_shared_t<1, false>(d_descs, d_items, n_items, batch, s);
+            return launch_shared_t<1, true>(d_descs, d_items, n_items, batch, s);
         }
         if (w == kSharedSchedule) return launch_shared_t<2, false>(d_descs, d_items, n_items, batch, s);
         return launch_shared_t<2, true>(d_descs, d_items, n_items, batch, s);

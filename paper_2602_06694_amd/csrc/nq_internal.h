@@ -179,7 +179,8 @@ int launch_valu_gemv(const uint32_t* tiles, const void* x, int x_dtype, int x_st
                      const uint16_t* out_scale, void* out, int out_dtype, int out_stride, int64_t M, int64_t N,
                      int batch, hipStream_t s);
 int device_cu_count();
-int schedule_full_rowblocks();            // row blocks from which a launch counts as filling the chip
+int schedule_full_rowblocks();
+int shared_min_batch();          // smallest batch that takes the shared-input kernel in launches that fill the chip            // row blocks from which a launch counts as filling the chip
 
 // ---- launchers (nq_prefill.hip) ------------------------------------------------------------
 struct PrefillArgs {

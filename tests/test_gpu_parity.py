@@ -378,9 +378,10 @@ def test_forward_many_and_plan_match_oracle():
             L.close()
 
 
-def test_shared_input_schedule_batches_6_to_8(monkeypatch):
-    """Large launches at batch 6..8 run the kernel whose eight waves share an op's quantised
-    input through LDS; NQ_SCHEDULE_FULL=1 makes these small launches take that schedule.
+def test_shared_input_schedule_batches_4_to_8(monkeypatch):
+    """Large launches at batch 4..8 run the kernel in which the waves of a workgroup share an op's
+    quantised input through LDS (one column group at batch 4 and 5, two from 6 on);
+    NQ_SCHEDULE_FULL=1 makes these small launches take that schedule.
     Shapes cover: reductions of 4 steps only, an odd number of half passes (68, 20 steps), items
     of more and fewer than eight row blocks, several row blocks per wave, ragged rows."""
     import torch
@@ -390,11 +391,12 @@ def test_shared_input_schedule_batches_6_to_8(monkeypatch):
               (2200, 1536, 1100), (4096, 512, 1024), (1500, 3072, 2300)]
     layers = [Layer(*s, "bf16", seed=300 + i) for i, s in enumerate(shapes)]
     hs = [L.h for L in layers]
-    for batch in (6, 7, 8):
+    for batch in (4, 5, 6, 7, 8):
         xs_np = [synth.gen_x(batch, s[1], 400 + i, "bf16") for i, s in enumerate(shapes)]
         xs = [to_device(x, "bf16") for x in xs_np]
         ys = [torch.full((batch, s[0]), float("nan"), dtype=torch.float32, device="cuda") for s in shapes]
         plan = nq.nq_plan_create(hs, xs, ys, batch)
+        assert nq.nq_plan_schedules(plan) == [8, 8], batch
         for rep in range(2):
             for y in ys:
                 y.fill_(float("nan"))

@@ -27,12 +27,14 @@ def test_prefill_small_shapes(shape, x_dtype):
     L.close()
 
 
-@pytest.mark.parametrize("splits", [None, "3"])
-def test_prefill_32_token_tiles_and_forced_splits(monkeypatch, splits):
+@pytest.mark.parametrize("tg,splits", [("2", None), ("2", "3"), ("2", "16"), (None, "5")])
+def test_prefill_32_token_tiles_and_forced_splits(monkeypatch, tg, splits):
     # the tiling of the two GEMMs is chosen by a cost model; force the variants it rarely picks on
-    # small inputs: 32-token workgroup tiles, with and without a split reduction
-    monkeypatch.setenv("NQ_PF_TG1", "2")
-    monkeypatch.setenv("NQ_PF_TG2", "2")
+    # small inputs: 32-token workgroup tiles, with and without a split reduction, 64-token tiles
+    # with one, and more splits than the reduction has groups of four steps (empty splits)
+    if tg:
+        monkeypatch.setenv("NQ_PF_TG1", tg)
+        monkeypatch.setenv("NQ_PF_TG2", tg)
     if splits:
         monkeypatch.setenv("NQ_PF_SPLITS1", splits)
         monkeypatch.setenv("NQ_PF_SPLITS2", splits)

@@ -37,6 +37,7 @@ typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef _Float16 v4h __attribute__((ext_vector_type(4)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef unsigned int v4u32 __attribute__((ext_vector_type(4)));
+typedef const __attribute__((address_space(1))) v4u32* gp_v4u32;
 
 constexpr int kPfTokens = 64;           // tokens per workgroup tile (4 MFMA column groups)
 constexpr int kPfWaves = 4;             // waves per workgroup, one 128-row block each
@@ -127,21 +128,73 @@ __device__ __forceinline__ void pf_store8(_Float16* dst, const float v[8], float
     *(v8h*)dst = o;
 }
 
+// DT: the element type of x (a template parameter, so that the loads of the fast path sit in
+// straight-line code: all of a thread's chunks are requested back to back, then converted).
+template <int DT>
 __global__ void __launch_bounds__(kPreThreads)
-prefill_prescale_kernel(const void* __restrict__ x, int x_dtype, const uint16_t* __restrict__ s_in, int d_in, int lda,
+prefill_prescale_kernel(const void* __restrict__ x, const uint16_t* __restrict__ s_in, int d_in, int lda,
                         float g_t, _Float16* __restrict__ xs, float* __restrict__ tok_scale)
 {
     __shared__ float sm[kPreThreads / 64];
+    constexpr int x_dtype = DT;
     const int tok = blockIdx.x;
     const int tid = threadIdx.x;
     const int64_t base = (int64_t)tok * d_in;
-    const int esz = x_dtype == NQ_F32 ? 4 : 2;
+    constexpr int esz = DT == NQ_F32 ? 4 : 2;
     const bool vec = (((size_t)d_in * esz) & 15) == 0;      // every token row starts 16-byte aligned
     const int n8 = lda / 8;
     const bool held = n8 <= kPreThreads * kPreHeld;
+    // rows of whole, aligned chunks (every model shape): no branch around a load.  A thread's chunk
+    // past the end of the row re-reads chunk 0 and counts as zeros.
+    const bool fast = held && vec && (d_in & 7) == 0;
     float hv[kPreHeld][8];
     float m = 0.f;
-    if (held) {
+    if (fast) {
+        const int n_in = d_in / 8;
+        typedef const __attribute__((address_space(1))) v4f* gp_v4f;
+        v4u32 xr0[kPreHeld], sr[kPreHeld];
+        v4f xf0[kPreHeld], xf1[kPreHeld];
+        const char* const xrow = (const char*)x + (size_t)base * esz;
+#pragma unroll
+        for (int k = 0; k < kPreHeld; ++k) {
+            const int c = tid + k * kPreThreads;
+            const uint32_t cc = (uint32_t)(c < n_in ? c : 0);
+            if (DT == NQ_F32) {
+                xf0[k] = *(gp_v4f)(xrow + cc * 32u);
+                xf1[k] = *(gp_v4f)(xrow + cc * 32u + 16u);
+            } else {
+                xr0[k] = *(gp_v4u32)(xrow + cc * 16u);
+            }
+            sr[k] = *(gp_v4u32)((const char*)s_in + cc * 16u);
+        }
+#pragma unroll
+        for (int k = 0; k < kPreHeld; ++k) {
+            const bool valid = tid + k * kPreThreads < n_in;
+            float xv[8];
+            if (DT == NQ_F32) {
+                const v4f a = xf0[k], b = xf1[k];
+                xv[0] = a.x; xv[1] = a.y; xv[2] = a.z; xv[3] = a.w;
+                xv[4] = b.x; xv[5] = b.y; xv[6] = b.z; xv[7] = b.w;
+            } else {
+                const uint32_t w[4] = {xr0[k].x, xr0[k].y, xr0[k].z, xr0[k].w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint16_t lo = (uint16_t)(w[i] & 0xFFFFu), hi = (uint16_t)(w[i] >> 16);
+                    xv[2 * i] = DT == NQ_F16 ? h2f(lo) : __builtin_bit_cast(float, (uint32_t)lo << 16);
+                    xv[2 * i + 1] = DT == NQ_F16 ? h2f(hi) : __builtin_bit_cast(float, (uint32_t)hi << 16);
+                }
+            }
+            const uint32_t sw[4] = {sr[k].x, sr[k].y, sr[k].z, sr[k].w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float v0 = xv[2 * i] * h2f((uint16_t)(sw[i] & 0xFFFFu));
+                const float v1 = xv[2 * i + 1] * h2f((uint16_t)(sw[i] >> 16));
+                hv[k][2 * i] = valid ? v0 : 0.f;
+                hv[k][2 * i + 1] = valid ? v1 : 0.f;
+                m = fmaxf(m, fmaxf(fabsf(hv[k][2 * i]), fabsf(hv[k][2 * i + 1])));
+            }
+        }
+    } else if (held) {
 #pragma unroll
         for (int k = 0; k < kPreHeld; ++k) {
             const int c = tid + k * kPreThreads;
@@ -198,10 +251,13 @@ prefill_prescale_kernel(const void* __restrict__ x, int x_dtype, const uint16_t*
 // acc + the sum of the eight fp16 values of a 16-byte chunk (each times `ones`): four v_dot2_f32_f16
 __device__ __forceinline__ float pf_sum8(const uint4& c, half2v ones, float acc)
 {
-    acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, c.x), ones, acc, false);
-    acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, c.y), ones, acc, false);
-    acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, c.z), ones, acc, false);
-    return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, c.w), ones, acc, false);
+    // (the words are copied out first: a bit cast applied directly to an element of a vector
+    // type may read the vector's first element instead)
+    const uint32_t w0 = c.x, w1 = c.y, w2 = c.z, w3 = c.w;
+    acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, w0), ones, acc, false);
+    acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, w1), ones, acc, false);
+    acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, w2), ones, acc, false);
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, w3), ones, acc, false);
 }
 
 // One lane's four results of gemm 1 (rows n0 .. n0 + 3 of token `tok`, raw accumulators of negated
@@ -701,8 +757,15 @@ int launch_prefill(const PrefillArgs& p, hipStream_t s)
     // (with a rank-wise scale, |s_mid| <= 2^mid_exp, T = X''V g s_mid stays within the same bound)
     const float g_t = ldexpf(1.0f, -(lg > 2 ? lg - 2 : 0) - (p.s_mid ? p.mid_exp : 0));
 
-    hipLaunchKernelGGL(prefill_prescale_kernel, dim3(p.batch), dim3(kPreThreads), 0, s, p.x, p.x_dtype, p.s_in, (int)p.d_in,
-                       L.k1, g_t, xs, tok_scale);
+    if (p.x_dtype == NQ_F32)
+        hipLaunchKernelGGL(prefill_prescale_kernel<NQ_F32>, dim3(p.batch), dim3(kPreThreads), 0, s, p.x, p.s_in, (int)p.d_in,
+                           L.k1, g_t, xs, tok_scale);
+    else if (p.x_dtype == NQ_F16)
+        hipLaunchKernelGGL(prefill_prescale_kernel<NQ_F16>, dim3(p.batch), dim3(kPreThreads), 0, s, p.x, p.s_in, (int)p.d_in,
+                           L.k1, g_t, xs, tok_scale);
+    else
+        hipLaunchKernelGGL(prefill_prescale_kernel<NQ_BF16>, dim3(p.batch), dim3(kPreThreads), 0, s, p.x, p.s_in, (int)p.d_in,
+                           L.k1, g_t, xs, tok_scale);
     NQ_HIP(hipGetLastError());
 
     GemmArgs a{};

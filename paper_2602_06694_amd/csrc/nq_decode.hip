@@ -543,6 +543,9 @@ struct EpilogueArgs {
 
 // LDS ints one wave needs for the epilogue: 16 columns x 64 rows
 constexpr int kEpiRegion = 16 * 64;
+// LDS ints a wave of stage_selfq_kernel needs: its quantised share (16 steps of 192 bytes per chunk
+// a lane holds), later its epilogue region
+constexpr int selfq_region_ints(int chunks_per_lane) { return chunks_per_lane * 16 * 192 / 4 > kEpiRegion ? chunks_per_lane * 16 * 192 / 4 : kEpiRegion; }
 // most row blocks an item of the stream kernel may chain
 constexpr int kStreamMaxRbs = 8;
 
@@ -1144,11 +1147,14 @@ stage_shared_kernel(const StageDesc* __restrict__ descs, const WorkItem* __restr
 // LDS: [W][kEpiRegion] (+ W maxima and flags when W = 4).
 // LIST: workgroup i takes items[i]; otherwise row block i of the one op in the kernel arguments q1 / s1.
 // ---------------------------------------------------------------------------------------------
-template <int W, int D, bool LIST>
-__global__ void __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(NQ_STAGE_WAVES, 8)))
+// C: chunks of 16 values a lane holds (1: shares of at most 16 steps; 2: up to 32, with one wave per
+// row block only -- the quantised share then takes 6 KiB of LDS per wave instead of 3).
+template <int W, int D, bool LIST, int C = 1>
+__global__ void __launch_bounds__(64 * W) __attribute__((amdgpu_waves_per_eu(C == 1 ? NQ_STAGE_WAVES : 4, 8)))
 stage_selfq_kernel(const FusedItem* __restrict__ items, QuantDesc q1, StageDesc s1)
 {
-    constexpr int region = kEpiRegion;
+    static_assert(C == 1 || W == 1, "two chunks per lane only with one wave per row block");
+    constexpr int region = selfq_region_ints(C);
     extern __shared__ int lds[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -1176,12 +1182,12 @@ stage_selfq_kernel(const FusedItem* __restrict__ items, QuantDesc q1, StageDesc 
     // of the tiles, so that the quantisation runs while the tiles are on their way, measured the same.)
     const int esz = qd.dtype == NQ_F32 ? 4 : 2;
     const bool vec = (((size_t)qd.x_stride * esz) & 15) == 0;
-    const int n_own = 4 * cnt;                             // <= 64 (the host checks the reduction length)
-    float hv[16];
+    const int n_own = 4 * cnt;                             // <= 64 C (the host checks the reduction length)
+    float hv[C][16];
     float m = 0.f;
     int bad = 0;
     // (a lane beyond n_own reads a chunk of zeros or of another wave: harmless for the maximum)
-    const int my_chunk = 4 * (wave + (lane >> 2) * W) + (lane & 3);
+    const int my_chunk = 4 * (wave + (lane >> 2) * W) + (lane & 3);     // the c-th chunk of a lane: + 64 c W
 
     v4u wbuf[D];
 #pragma unroll
@@ -1196,13 +1202,16 @@ stage_selfq_kernel(const FusedItem* __restrict__ items, QuantDesc q1, StageDesc 
 #pragma unroll
         for (int hf = 0; hf < 2; ++hf) pre_scale[hf] = sp[64 * hf + lane];
     }
-    load_chunk16(qd, 0, my_chunk, vec, hv);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const float a = fabsf(hv[i]);
-        if (!(a <= 3.0e38f)) bad = 1;
-        m = fmaxf(m, a);
-    }
+    for (int c = 0; c < C; ++c) load_chunk16(qd, 0, my_chunk + 64 * c * W, vec, hv[c]);
+#pragma unroll
+    for (int c = 0; c < C; ++c)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const float a = fabsf(hv[c][i]);
+            if (!(a <= 3.0e38f)) bad = 1;
+            m = fmaxf(m, a);
+        }
     for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
     bad = __builtin_amdgcn_ballot_w64(bad != 0) != 0;
     if (W > 1) {
@@ -1230,7 +1239,10 @@ stage_selfq_kernel(const FusedItem* __restrict__ items, QuantDesc q1, StageDesc 
     }
     const float inv_step = 1.0f / step;
     long long local_sum = 0;
-    if (lane < n_own) local_sum = quantize_chunk16(hv, inv_step, bad != 0, (uint4*)my_bq + bq_piece(lane, 0));
+#pragma unroll
+    for (int c = 0; c < C; ++c)
+        if (lane + 64 * c < n_own)
+            local_sum += quantize_chunk16(hv[c], inv_step, bad != 0, (uint4*)my_bq + bq_piece(lane + 64 * c, 0));
     double sum = (double)local_sum;
     for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
     QMeta my_meta;
@@ -1574,12 +1586,13 @@ int launch_fused_list(const FusedItem* d_items, int n_items, int max_steps, hipS
 }
 
 // Whether a batch-1 launch with schedule w (1 or 4) may quantise in the stage kernel: a wave's share
-// of every reduction must be at most 16 steps (see stage_selfq_kernel), and with one wave per row
-// block the reductions must not be so short that the stream kernel would chain row blocks.
+// of every reduction must be at most 16 steps (see stage_selfq_kernel; 32 with one wave per row block,
+// whose lanes then hold two chunks), and with one wave per row block the reductions must not be so
+// short that the stream kernel would chain row blocks.
 bool selfq_fits(int w, int max_steps, int min_steps, int batch)
 {
     if (batch != 1 || (w != 1 && w != 4)) return false;
-    if (w == 1 && min_steps < 16) return false;
+    if (w == 1) return min_steps >= 16 && max_steps <= (getenv("NQ_NO_SELFQ_C2") ? 16 : 32);    // (two chunks per lane beyond 16)
     return max_steps <= 16 * w;
 }
 
@@ -1603,9 +1616,14 @@ int launch_selfq(const FusedItem* d_items, int n_items, const QuantDesc& q1, con
         set_error("launch_selfq: schedule or reduction length not supported");
         return NQ_E_INVALID_ARG;
     }
-    const size_t lds_bytes = (size_t)w * kEpiRegion * 4 + (w > 1 ? 2 * w * 4 : 0);     // + the waves' maxima and flags
+    const int c = (w == 1 && max_steps > 16) ? 2 : 1;       // chunks a lane holds
+    const size_t lds_bytes = (size_t)w * selfq_region_ints(c) * 4 + (w > 1 ? 2 * w * 4 : 0);     // + the waves' maxima and flags
     const dim3 grid((unsigned)n_items);
-    if (w == 1 && d_items)
+    if (w == 1 && c == 2 && d_items)
+        hipLaunchKernelGGL((stage_selfq_kernel<1, kSelfqDepth1, true, 2>), grid, dim3(64), lds_bytes, s, d_items, q1, s1);
+    else if (w == 1 && c == 2)
+        hipLaunchKernelGGL((stage_selfq_kernel<1, kSelfqDepth1, false, 2>), grid, dim3(64), lds_bytes, s, d_items, q1, s1);
+    else if (w == 1 && d_items)
         hipLaunchKernelGGL((stage_selfq_kernel<1, kSelfqDepth1, true>), grid, dim3(64), lds_bytes, s, d_items, q1, s1);
     else if (w == 1)
         hipLaunchKernelGGL((stage_selfq_kernel<1, kSelfqDepth1, false>), grid, dim3(64), lds_bytes, s, d_items, q1, s1);

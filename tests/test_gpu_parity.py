@@ -572,11 +572,15 @@ def test_self_quantising_schedules_at_batch_1(monkeypatch):
     64 steps (four waves per row block in stage 1), ranks of 16 steps (one wave in stage 2), as in
     the 4096x4096 r=1024 layers, with ragged tails in every dimension; second list, with the
     split threshold lowered so that both stages run four waves per row block: reductions of 20,
-    36 and 64 steps (waves with unequal shares), fp32 input.  The result must match the
+    36 and 64 steps (waves with unequal shares), fp32 input; third and fourth: reductions of 17 to
+    32 steps on one wave per row block, whose lanes then hold two chunks each.  The result must match the
     four-launch path bit for bit (same arithmetic) and the oracle within the bar."""
     import torch
     cases = [([(4096, 4096, 1024), (300, 4090, 1000), (129, 4040, 970), (1000, 4096, 1024)], "bf16", None, [33, 34]),
-             ([(300, 1100, 1030), (129, 2000, 2050), (640, 4000, 1500)], "f32", "1", [34, 34])]
+             ([(300, 1100, 1030), (129, 2000, 2050), (640, 4000, 1500)], "f32", "1", [34, 34]),
+             # ranks of 17 .. 32 steps next to one of 16: one wave per row block holding two chunks per lane
+             ([(4096, 4096, 1664), (300, 4090, 2048), (129, 4040, 1030), (1000, 4096, 1024)], "bf16", None, [33, 34]),
+             ([(640, 1100, 1500), (129, 2000, 2048)], "f32", None, [33, 33])]
     for shapes, x_dtype, split_steps, want in cases:
         layers = [Layer(*s, x_dtype, seed=1200 + i) for i, s in enumerate(shapes)]
         xs_np = [synth.gen_x(1, s[1], 1300 + i, x_dtype) for i, s in enumerate(shapes)]

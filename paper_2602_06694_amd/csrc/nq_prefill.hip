@@ -286,20 +286,29 @@ __device__ __forceinline__ void store_t(const GemmArgs& a, int tok, int n0, cons
 // outputs at small batches, where 64-token tiles are too few to cover the chip and splitting the
 // reduction instead would cost partial sums and a finalize pass (the sign expansion is then shared
 // by half as many MFMAs: lower efficiency per workgroup, but no extra passes).
-template <int EPI, int TG>
-__global__ void __launch_bounds__(kPfThreads) __attribute__((amdgpu_waves_per_eu(2, TG == 4 ? 2 : 4)))
+// KS = 2: eight waves; waves 4..7 take the same rows and tokens as waves 0..3 but the second half of
+// the workgroup's part of the reduction (with activation buffers of their own), and hand their
+// accumulators to their partners through LDS before the epilogue.  For GEMMs whose tiles (times
+// splits) number no more than the CUs: such a workgroup fills its CU by itself (two waves per
+// SIMD), and the reduction is halved without partial sums in memory.
+template <int EPI, int TG, int KS = 1>
+__global__ void __launch_bounds__(kPfThreads * KS) __attribute__((amdgpu_waves_per_eu(2, TG == 4 ? 2 : 4)))
 prefill_gemm_kernel(GemmArgs a)
 {
     static_assert(TG == 2 || TG == 4, "32- or 64-token tiles");
+    static_assert(KS == 1 || (KS == 2 && TG == 4), "the in-workgroup split is built for 64-token tiles");
     constexpr int kTok = 16 * TG;
-    // four activation buffers; after the reduction the same memory serves the epilogue
+    // four activation buffers (per half of the workgroup); after the reduction the same memory serves
+    // the exchange of accumulators and the epilogue
     constexpr int kActBuf = kTok * kPfLdsStride;                            // halves per buffer
-    constexpr int kLdsBytes = 4 * kActBuf * 2 > kPfWaves * 16 * kPfTrStride * 4 ? 4 * kActBuf * 2 : kPfWaves * 16 * kPfTrStride * 4;
+    constexpr int kLdsBytes = KS * 4 * kActBuf * 2 > kPfWaves * 16 * kPfTrStride * 4 ? KS * 4 * kActBuf * 2 : kPfWaves * 16 * kPfTrStride * 4;
+    static_assert(KS == 1 || kLdsBytes >= kPfWaves * 2 * 8 * 64 * 16, "exchange of two token groups per round");
     __shared__ __attribute__((aligned(16))) char lds_raw[kLdsBytes];
-    _Float16 (*const lds_act)[kActBuf] = (_Float16 (*)[kActBuf])lds_raw;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x & (kPfThreads - 1);                     // thread within its half
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave8 = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int wave = wave8 & (kPfWaves - 1), grp = wave8 / kPfWaves;
+    _Float16 (*const lds_act)[kActBuf] = (_Float16 (*)[kActBuf])lds_raw + 4 * grp;
     const int g = lane >> 4, j = lane & 15;
 
     // workgroups that share a token tile run on the same XCD (ids are dealt round-robin to the
@@ -312,9 +321,12 @@ prefill_gemm_kernel(GemmArgs a)
     }
     const int m_tile = id / a.n_tiles, n_tile = id - m_tile * a.n_tiles;
     const int split = blockIdx.y;
-    const int s_begin = split * a.steps_per_split;
-    const int s_end = min(a.nst, s_begin + a.steps_per_split);
-    const int n_my = s_end - s_begin;
+    // (with KS = 2 the host makes the workgroup's part a multiple of eight steps: equal halves, both
+    // multiples of four, so that all eight waves pass the same barriers)
+    const int wg_begin = split * a.steps_per_split;
+    const int wg_steps = max(0, min(a.nst, wg_begin + a.steps_per_split) - wg_begin);
+    const int n_my = wg_steps / KS;
+    const int s_begin = wg_begin + grp * n_my;
 
     int rb = n_tile * kPfWaves + wave;
     const bool rb_valid = rb < a.n_rb;
@@ -480,14 +492,40 @@ prefill_gemm_kernel(GemmArgs a)
     if (TG == 4) { ssum1 += __shfl_xor(ssum1, 1); ssum1 += __shfl_xor(ssum1, 2); ssum1 += __shfl_xor(ssum1, 4); }
     __syncthreads();
     if (ld_kc == 0) {
-        lds_f[ld_tok] = ssum0;
-        if (TG == 4) lds_f[ld_tok + 32] = ssum1;
+        lds_f[grp * 64 + ld_tok] = ssum0;
+        if (TG == 4) lds_f[grp * 64 + ld_tok + 32] = ssum1;
     }
     __syncthreads();
     float s_tok[TG];
 #pragma unroll
-    for (int tg = 0; tg < TG; ++tg) s_tok[tg] = lds_f[tg * 16 + j];
+    for (int tg = 0; tg < TG; ++tg) {
+        s_tok[tg] = lds_f[tg * 16 + j];
+        if (KS == 2) s_tok[tg] += lds_f[64 + tg * 16 + j];
+    }
     __syncthreads();                                       // the sums are read: LDS changes hands once more
+    if (KS == 2) {
+        // waves 4..7 hand their accumulators to waves 0..3, two token groups per round: a lane's 16
+        // registers of a token group go to the same lane of the partner (no transposition here).
+        // Every wave adds what it reads (the second half's sums are not used any further): no
+        // branch around a write to the accumulators.
+        float* const xr = lds_f + wave * (2 * 8 * 64 * 4);
+#pragma unroll
+        for (int round = 0; round < 2; ++round) {
+            if (grp == 1) {
+#pragma unroll
+                for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+                    for (int p = 0; p < 8; ++p) *(v4f*)(xr + ((tl * 8 + p) * 64 + lane) * 4) = acc[p][2 * round + tl];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int tl = 0; tl < 2; ++tl)
+#pragma unroll
+                for (int p = 0; p < 8; ++p) acc[p][2 * round + tl] += *(const v4f*)(xr + ((tl * 8 + p) * 64 + lane) * 4);
+            __syncthreads();
+        }
+        if (grp == 1) return;
+    }
     if (!rb_valid) return;
 
     // Result layout: lane (g, j), register v of acc[p][tg]  <->  C[token m0 + 16 tg + j][row 128 rb + 16 p + 4 g + v],
@@ -625,6 +663,7 @@ struct PfLayout {
     int m_pad, k1, k2, n1_pad, n2_pad;
     int splits1, splits2;
     int tg1, tg2;             // token groups of 16 per workgroup tile of the two GEMMs (4 or 2)
+    int ks1, ks2;             // halves of the reduction taken inside a workgroup (1, or 2: eight waves)
     size_t off_x, off_t, off_scale, off_partial, total;
 };
 
@@ -639,20 +678,21 @@ struct PfLayout {
 //    CU completes at most 3.9 of their steps per microsecond (up to four fit);
 //  - splitting costs a finalize launch (2 us) plus, per split, the write and re-read of one set of
 //    fp32 partial sums, not overlapped with anything: about 2.3 MB per microsecond.
-// steps per split, rounded up to a multiple of 4 (as nst itself is): the kernel's loop body is four steps
-static int steps_per_split4(int nst, int splits)
+// steps per split, rounded up to a multiple of 4 (as nst itself is): the kernel's loop body is four
+// steps; of 8 where the workgroup halves its part once more (ks = 2: nst is then a multiple of 8 too)
+static int steps_per_split4(int nst, int splits, int ks = 1)
 {
-    const int per = (nst + splits - 1) / splits;
-    return (per + 3) / 4 * 4;
+    const int per = (nst + splits - 1) / splits, q = 4 * ks;
+    return (per + q - 1) / q * q;
 }
 
-struct GemmTiling { int tg, splits; };
+struct GemmTiling { int tg, splits, ks; };
 static GemmTiling choose_tiling(int m_pad, int n_rb, int nst, int n_pad)
 {
     const int cus = device_cu_count();
     const int n_tiles = (n_rb + kPfWaves - 1) / kPfWaves;
     const double partial_us = (double)m_pad * n_pad * 4.0 / 2.3e6;
-    GemmTiling best = {4, 1};
+    GemmTiling best = {4, 1, 1};
     double best_cost = 1e30;
     for (int tg = 4; tg >= 2; tg -= 2) {
         const int wgs = (m_pad / (16 * tg)) * n_tiles;
@@ -672,9 +712,17 @@ static GemmTiling choose_tiling(int m_pad, int n_rb, int nst, int n_pad)
             double cost = (double)full * per * step_us(per_cu);
             if (rem) cost += per * step_us((rem + cus - 1) / cus);
             if (s > 1) cost += 2.0 + s * partial_us;
-            if (cost < best_cost) { best_cost = cost; best = {tg, s}; }
+            if (cost < best_cost) { best_cost = cost; best = {tg, s, 1}; }
         }
     }
+    // A long reduction whose 64-token tiles number no more than the CUs and that the model leaves
+    // (nearly) unsplit: eight-wave workgroups, each filling its CU and halving its reduction through
+    // LDS, without partial sums in memory.  Measured on the 70B MLP shapes at 2048 tokens: gemm 1 of
+    // the gate layer (224 tiles, 128 steps) 106 -> 99 us, of the down layer (224 tiles, 448 steps,
+    // split in two before) 300 -> 284 us including the finalize pass it no longer needs; with more
+    // splits (512 tokens: 56 tiles) the eight-wave workgroups gain nothing.
+    const int wgs4 = (m_pad / 64) * n_tiles;
+    if (best.tg == 4 && best.splits <= 2 && wgs4 <= cus && nst % 8 == 0 && nst >= 64) best = {4, 1, 2};
     return best;
 }
 
@@ -688,15 +736,20 @@ static PfLayout pf_layout(int64_t d_out, int64_t d_in, int64_t r, int batch)
     L.n2_pad = (int)n_rowblocks(d_out) * kTileRows;
     const GemmTiling t1 = choose_tiling(L.m_pad, (int)n_rowblocks(r), (int)n_steps(d_in), L.n1_pad);
     const GemmTiling t2 = choose_tiling(L.m_pad, (int)n_rowblocks(d_out), (int)n_steps(r), L.n2_pad);
-    L.tg1 = t1.tg; L.splits1 = t1.splits;
-    L.tg2 = t2.tg; L.splits2 = t2.splits;
+    L.tg1 = t1.tg; L.splits1 = t1.splits; L.ks1 = t1.ks;
+    L.tg2 = t2.tg; L.splits2 = t2.splits; L.ks2 = t2.ks;
     if (getenv("NQ_PF_VERBOSE"))
-        fprintf(stderr, "prefill tiling B=%d: gemm1 tg=%d splits=%d, gemm2 tg=%d splits=%d\n", batch, L.tg1, L.splits1, L.tg2,
-                L.splits2);
+        fprintf(stderr, "prefill tiling B=%d: gemm1 tg=%d splits=%d ks=%d, gemm2 tg=%d splits=%d ks=%d\n", batch, L.tg1, L.splits1,
+                t1.ks, L.tg2, L.splits2, t2.ks);
     if (getenv("NQ_PF_TG1")) L.tg1 = atoi(getenv("NQ_PF_TG1")) == 2 ? 2 : 4;
     if (getenv("NQ_PF_TG2")) L.tg2 = atoi(getenv("NQ_PF_TG2")) == 2 ? 2 : 4;
     if (getenv("NQ_PF_SPLITS1")) L.splits1 = std::max(1, atoi(getenv("NQ_PF_SPLITS1")));
     if (getenv("NQ_PF_SPLITS2")) L.splits2 = std::max(1, atoi(getenv("NQ_PF_SPLITS2")));
+    if (getenv("NQ_PF_KS1")) L.ks1 = atoi(getenv("NQ_PF_KS1")) == 2 ? 2 : 1;
+    if (getenv("NQ_PF_KS2")) L.ks2 = atoi(getenv("NQ_PF_KS2")) == 2 ? 2 : 1;
+    // the in-workgroup split needs 64-token tiles and a reduction of whole groups of eight steps
+    if (L.tg1 != 4 || n_steps(d_in) % 8 != 0) L.ks1 = 1;
+    if (L.tg2 != 4 || n_steps(r) % 8 != 0) L.ks2 = 1;
     size_t o = 0;
     L.off_x = o; o += al256((size_t)L.m_pad * L.k1 * 2);
     L.off_t = o; o += al256((size_t)L.m_pad * L.k2 * 2);
@@ -726,17 +779,23 @@ prefill_zero_cols_kernel(_Float16* __restrict__ m, int ld, int c0, int c1, int r
 }
 
 template <int EPI>
-static int run_gemm(const GemmArgs& a, int tg, hipStream_t s)
+static int run_gemm(const GemmArgs& a, int tg, int ks, hipStream_t s)
 {
     dim3 grid(a.m_tiles * a.n_tiles, a.splits);
+    if (ks == 2 && (tg != 4 || a.nst % 8 != 0 || a.steps_per_split % 8 != 0)) {
+        set_error("prefill: the in-workgroup split needs 64-token tiles and parts of whole groups of eight steps");
+        return NQ_E_INVALID_ARG;
+    }
     if (a.splits > 1) {
-        if (tg == 4) hipLaunchKernelGGL((prefill_gemm_kernel<EPI_PARTIAL, 4>), grid, dim3(kPfThreads), 0, s, a);
+        if (ks == 2) hipLaunchKernelGGL((prefill_gemm_kernel<EPI_PARTIAL, 4, 2>), grid, dim3(2 * kPfThreads), 0, s, a);
+        else if (tg == 4) hipLaunchKernelGGL((prefill_gemm_kernel<EPI_PARTIAL, 4>), grid, dim3(kPfThreads), 0, s, a);
         else hipLaunchKernelGGL((prefill_gemm_kernel<EPI_PARTIAL, 2>), grid, dim3(kPfThreads), 0, s, a);
         NQ_HIP(hipGetLastError());
         const size_t total = (size_t)a.m_pad * (a.n_pad / 4);
         hipLaunchKernelGGL((prefill_finalize_kernel<EPI>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, a);
     } else {
-        if (tg == 4) hipLaunchKernelGGL((prefill_gemm_kernel<EPI, 4>), grid, dim3(kPfThreads), 0, s, a);
+        if (ks == 2) hipLaunchKernelGGL((prefill_gemm_kernel<EPI, 4, 2>), grid, dim3(2 * kPfThreads), 0, s, a);
+        else if (tg == 4) hipLaunchKernelGGL((prefill_gemm_kernel<EPI, 4>), grid, dim3(kPfThreads), 0, s, a);
         else hipLaunchKernelGGL((prefill_gemm_kernel<EPI, 2>), grid, dim3(kPfThreads), 0, s, a);
     }
     NQ_HIP(hipGetLastError());
@@ -777,10 +836,10 @@ int launch_prefill(const PrefillArgs& p, hipStream_t s)
     a.t_out = t; a.ldt = L.k2; a.t_scale = g_t; a.mid_scale = p.s_mid;
     a.n_real = (int)p.r; a.n_rb = (int)n_rowblocks(p.r); a.nst = (int)n_steps(p.d_in);
     a.n_tiles = (a.n_rb + kPfWaves - 1) / kPfWaves;
-    a.splits = L.splits1; a.steps_per_split = steps_per_split4(a.nst, a.splits);
+    a.splits = L.splits1; a.steps_per_split = steps_per_split4(a.nst, a.splits, L.ks1);
     a.n_pad = L.n1_pad;
     a.m_tiles = L.m_pad / (16 * L.tg1);
-    int rc = run_gemm<EPI_T>(a, L.tg1, s);
+    int rc = run_gemm<EPI_T>(a, L.tg1, L.ks1, s);
     if (rc != NQ_OK) return rc;
     if (L.k2 > L.n1_pad) {
         // columns of T beyond the last 128-row block of gemm1 are padding of gemm2's reduction:
@@ -795,10 +854,10 @@ int launch_prefill(const PrefillArgs& p, hipStream_t s)
     a.y_out = p.y; a.y_dtype = p.y_dtype; a.tok_scale = tok_scale; a.out_scale = p.s_out;
     a.n_real = (int)p.d_out; a.n_rb = (int)n_rowblocks(p.d_out); a.nst = (int)n_steps(p.r);
     a.n_tiles = (a.n_rb + kPfWaves - 1) / kPfWaves;
-    a.splits = L.splits2; a.steps_per_split = steps_per_split4(a.nst, a.splits);
+    a.splits = L.splits2; a.steps_per_split = steps_per_split4(a.nst, a.splits, L.ks2);
     a.n_pad = L.n2_pad;
     a.m_tiles = L.m_pad / (16 * L.tg2);
-    return run_gemm<EPI_Y>(a, L.tg2, s);
+    return run_gemm<EPI_Y>(a, L.tg2, L.ks2, s);
 }
 
 }  // namespace nq

@@ -27,11 +27,17 @@ def test_prefill_small_shapes(shape, x_dtype):
     L.close()
 
 
-@pytest.mark.parametrize("tg,splits", [("2", None), ("2", "3"), ("2", "16"), (None, "5")])
-def test_prefill_32_token_tiles_and_forced_splits(monkeypatch, tg, splits):
+@pytest.mark.parametrize("tg,splits,ks", [("2", None, None), ("2", "3", None), ("2", "16", None), (None, "5", None),
+                                          (None, "1", "2"), (None, "2", "2")])
+def test_prefill_32_token_tiles_and_forced_splits(monkeypatch, tg, splits, ks):
     # the tiling of the two GEMMs is chosen by a cost model; force the variants it rarely picks on
     # small inputs: 32-token workgroup tiles, with and without a split reduction, 64-token tiles
-    # with one, and more splits than the reduction has groups of four steps (empty splits)
+    # with one, more splits than the reduction has groups of four steps (empty splits), and
+    # eight-wave workgroups that halve their part of the reduction through LDS (taken where the
+    # reduction is a whole number of groups of eight steps: the second and third shape)
+    if ks:
+        monkeypatch.setenv("NQ_PF_KS1", ks)
+        monkeypatch.setenv("NQ_PF_KS2", ks)
     if tg:
         monkeypatch.setenv("NQ_PF_TG1", tg)
         monkeypatch.setenv("NQ_PF_TG2", tg)

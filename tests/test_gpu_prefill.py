@@ -129,3 +129,29 @@ def test_prefill_activations_with_a_large_mean_and_uniform_sign_columns():
         y, ref = L.forward(x)[b], L.oracle(x)[b]
         assert np.abs(y - ref).max() <= PREFILL_TOL * np.abs(ref).max(), b
     L.close()
+
+
+def test_prefill_eight_wave_workgroups_by_default(monkeypatch):
+    """A first GEMM with a long reduction whose 64-token tiles number no more than the CUs, but too many
+    for 32-token tiles to take over (here 7 x 20 tiles of 64 steps) runs eight-wave workgroups that halve the reduction through LDS; NQ_PF_KS1=1
+    switches that off.  Both against the oracle on sampled tokens (first, last, tile edges, random),
+    and against each other within the dense tolerance."""
+    d_out, d_in, r, batch = 256, 4096, 3584, 1280
+    L = Layer(d_out, d_in, r, "bf16", seed=4100)
+    x = synth.gen_x(batch, d_in, 4101, "bf16", outlier_frac=0.01)
+    rng = np.random.default_rng(4102)
+    idx = np.unique(np.concatenate([[0, 63, 64, 127, 1215, 1216, batch - 1], rng.integers(0, batch, 40)]))
+    ref = L.oracle(x[idx])
+    outs = {}
+    for ks in (None, "1"):
+        if ks:
+            monkeypatch.setenv("NQ_PF_KS1", ks)
+        else:
+            monkeypatch.delenv("NQ_PF_KS1", raising=False)
+        y = L.forward(x)
+        outs[ks] = y
+        for k, b in enumerate(idx):
+            assert np.abs(y[b] - ref[k]).max() <= PREFILL_TOL * np.abs(ref[k]).max(), (ks, int(b))
+    assert not np.array_equal(outs[None], outs["1"])       # different summation orders: the two paths did run
+    assert rel_err(outs[None], outs["1"]) <= PREFILL_TOL
+    L.close()

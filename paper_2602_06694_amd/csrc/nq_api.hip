@@ -718,7 +718,12 @@ extern "C" int nq_plan_create(nq_plan* out, const nq_handle* hs, const void* con
             // batch 6..8, short reductions: the shared-input kernel with the whole input resident in LDS
             if (w == 1 && batch > 5 && max_steps <= 16 && total_rb >= schedule_full_rowblocks() && !getenv("NQ_NO_RESIDENT"))
                 w = kSharedResidentSchedule;
-            if ((w == 1 || w == 4) && !getenv("NQ_NO_SELFQ") && full && selfq_fits(w, max_steps, min_steps, batch))
+            // (with four waves per row block only where every reduction has 48 steps or more: for shorter
+            // ones the split kernel with its quantisation launch measured the same or faster -- 35 steps:
+            // 62 against 66 us, 55 steps: 85 against 85 -- and a mixed list, as stage 2 of the 70B stack
+            // with its 8-step ranks, 442 + 9 against 476 us)
+            if ((w == 1 || (w == 4 && min_steps >= env_int_api("NQ_SELFQ4_MIN_STEPS", 48))) && !getenv("NQ_NO_SELFQ") && full &&
+                selfq_fits(w, max_steps, min_steps, batch))
                 w = w == 1 ? kSelfqSchedule1 : kSelfqSchedule4;
         }
         sched[st] = w;

@@ -1651,7 +1651,9 @@ int stage_schedule(int n_rb_total, int mean_steps, int batch)
     const int full = schedule_full_rowblocks();
     int w;
     if (n_rb_total >= full && batch >= shared_min_batch()) w = mean_steps >= env_int("NQ_SHARE_STEPS", 32) ? kSharedSchedule : 1;
-    else if (n_rb_total >= full) w = mean_steps >= env_int("NQ_SPLIT_STEPS", 64) ? 4 : 1;
+    // (batch 1 splits from 33 steps on: stage 2 of the 70B stack, 35 and 55 steps, 452 -> 442 us; pools
+    // of 35- and 55-step reductions 64 -> 62 and 91 -> 85 us including the quantisation launch)
+    else if (n_rb_total >= full) w = mean_steps >= env_int("NQ_SPLIT_STEPS", batch == 1 ? 33 : 64) ? 4 : 1;
     else w = (n_rb_total * 4 >= full || batch > 2) ? 4 : 16;
     if (const char* f = getenv("NQ_FORCE_W")) {
         int fw = atoi(f);

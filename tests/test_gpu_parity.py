@@ -591,9 +591,12 @@ def test_self_quantising_schedules_at_batch_1(monkeypatch):
             monkeypatch.setenv("NQ_SCHEDULE_FULL", "1")
             monkeypatch.setenv("NQ_FUSE_MAX_MB", "0")
             if split_steps:
+                # (short and unequal shares take four self-quantising waves only when asked to)
                 monkeypatch.setenv("NQ_SPLIT_STEPS", split_steps)
+                monkeypatch.setenv("NQ_SELFQ4_MIN_STEPS", "1")
             else:
                 monkeypatch.delenv("NQ_SPLIT_STEPS", raising=False)
+                monkeypatch.delenv("NQ_SELFQ4_MIN_STEPS", raising=False)
             if mode == "four_launches":
                 monkeypatch.setenv("NQ_NO_SELFQ", "1")
             else:
@@ -621,6 +624,7 @@ def test_self_quantising_schedules_at_batch_1(monkeypatch):
     monkeypatch.setenv("NQ_FUSE_MAX_MB", "0")
     monkeypatch.delenv("NQ_NO_SELFQ", raising=False)
     monkeypatch.delenv("NQ_SPLIT_STEPS", raising=False)
+    monkeypatch.delenv("NQ_SELFQ4_MIN_STEPS", raising=False)
     L = Layer(300, 4090, 1000, "f32", seed=1250)
     x_np = synth.gen_x(1, 4090, 1350, "f32")
     x_np[0, 77] = np.inf

@@ -716,13 +716,19 @@ static GemmTiling choose_tiling(int m_pad, int n_rb, int nst, int n_pad)
         }
     }
     // A long reduction whose 64-token tiles number no more than the CUs and that the model leaves
-    // (nearly) unsplit: eight-wave workgroups, each filling its CU and halving its reduction through
-    // LDS, without partial sums in memory.  Measured on the 70B MLP shapes at 2048 tokens: gemm 1 of
-    // the gate layer (224 tiles, 128 steps) 106 -> 99 us, of the down layer (224 tiles, 448 steps,
-    // split in two before) 300 -> 284 us including the finalize pass it no longer needs; with more
-    // splits (512 tokens: 56 tiles) the eight-wave workgroups gain nothing.
+    // unsplit, or splits no further than into one part per CU: eight-wave workgroups, one per CU,
+    // each halving its part of the reduction through LDS -- half the partial sums in memory, or none.
+    // Measured on the 70B MLP shapes: gemm 1 of the gate layer at 2048 tokens (224 tiles, 128 steps)
+    // 106 -> 99 us, of the down layer (224 tiles, 448 steps, split in two before) 300 -> 284 us
+    // including the finalize pass it no longer needs; gate layer at 1024 tokens (112 tiles, two
+    // parts per tile) 244 -> 213 us per forward, at 512 tokens (56 tiles, four parts) 115 -> 113 us.
     const int wgs4 = (m_pad / 64) * n_tiles;
-    if (best.tg == 4 && best.splits <= 2 && wgs4 <= cus && nst % 8 == 0 && nst >= 64) best = {4, 1, 2};
+    if (best.tg == 4 && wgs4 <= cus && nst % 8 == 0) {
+        const int s_fill = std::max(1, cus / wgs4);
+        // (a half of at least 16 steps; of 32 where the tile is not split otherwise: 28-step halves of
+        // an unsplit second GEMM measured 2 % slower than four-wave workgroups)
+        if (best.splits <= 2 * s_fill && nst / (2 * s_fill) >= (s_fill == 1 ? 32 : 16)) best = {4, s_fill, 2};
+    }
     return best;
 }
 

@@ -727,7 +727,10 @@ static GemmTiling choose_tiling(int m_pad, int n_rb, int nst, int n_pad)
         const int s_fill = std::max(1, cus / wgs4);
         // (a half of at least 16 steps; of 32 where the tile is not split otherwise: 28-step halves of
         // an unsplit second GEMM measured 2 % slower than four-wave workgroups)
-        if (best.splits <= 2 * s_fill && nst / (2 * s_fill) >= (s_fill == 1 ? 32 : 16)) best = {4, s_fill, 2};
+        // and parts of equal length (three unequal parts of 128 steps at 768 tokens: 194 against 174 us
+        // per forward with four-wave workgroups)
+        if (best.splits <= 2 * s_fill && nst % (8 * s_fill) == 0 && nst / (2 * s_fill) >= (s_fill == 1 ? 32 : 16))
+            best = {4, s_fill, 2};
     }
     return best;
 }

@@ -139,9 +139,13 @@ int nq_binlr_create_from_device(nq_handle* out, int64_t d_out, int64_t d_in, int
  * nq_binlr_forward_many is dropped here).  nq_binlr_weight_bytes then counts the 2r bytes too. */
 int nq_binlr_set_mid_scale(nq_handle h, const uint16_t* s_mid_fp16);
 
-/* Grow the per-layer workspace so that forwards with batch <= max_batch allocate nothing.
+/* Grow the per-layer workspace so that forwards with ANY batch <= max_batch allocate nothing
+ * (the dense path's need is not monotone in the batch; the largest need up to max_batch is taken).
  * May allocate and synchronise. */
 int nq_binlr_reserve(nq_handle h, int max_batch);
+/* What has been reserved: the largest batch that allocates nothing, and the bytes of the dense
+ * path's workspace held by the layer.  Either pointer may be NULL. */
+int nq_binlr_reserved(nq_handle h, int* max_batch, size_t* workspace_bytes);
 
 /* y = s_out (.) (U (V^T (s_in (.) x))) for `batch` tokens (Eq. 1).
  * x: device, [batch, d_in] of x_dtype;  y: device, [batch, d_out] of y_dtype; both 16-byte
@@ -152,6 +156,13 @@ int nq_binlr_reserve(nq_handle h, int max_batch);
  * batch <= 8: streaming kernels (exact integer accumulation); >= 9: dense MFMA path
  * (fp16 operands, fp32 accumulation), unless the layer was created with NQ_FLAG_NO_PREFILL. */
 int nq_binlr_forward(nq_handle h, const void* x, void* y, int batch, void* stream);
+
+/* The same product for ANY batch through the streaming kernels only, in passes of up to 8 tokens
+ * (exact integer accumulation of 24-bit fixed-point activations: the accuracy of a batch <= 8
+ * forward, at the cost of one pass over the bits per 8 tokens) -- the per-call way to ask for the
+ * exact path above batch 8, where nq_binlr_forward takes the fp16-operand dense path.
+ * Pointers, types and stream as in nq_binlr_forward; allocates nothing. */
+int nq_binlr_forward_exact(nq_handle h, const void* x, void* y, int batch, void* stream);
 
 /* ---- scale gradients with the packed signs frozen (Section 3.4; Algorithm 1, Phase 3) ----
  * For a loss L with upstream gradient g = dL/dy ([batch, d_out]):
@@ -236,6 +247,21 @@ int nq_probe_hbm_read(size_t bytes, int iters, int prewarm_ms, double* gb_per_s)
  * fp32 accumulation; the prefill path's instruction) or NQ_I8 (int8, int32 accumulation; the decode
  * path's).  Returns 1e12 operations per second (one multiply-add = 2).  Synchronises. */
 int nq_probe_mfma(int dtype, double* tera_ops_per_s);
+
+/* ---- tuning options (process-wide) ----
+ * Integers that steer the library's choice of schedules and tilings; every one has a measured
+ * default and none changes a result beyond the documented tolerances.  Names: "slab_mb",
+ * "force_w", "split_steps", "selfq4_min_steps", "share_steps", "share_min_batch", "stream_steps",
+ * "schedule_full", "fuse_max_mb", "no_fuse", "no_selfq", "no_selfq_c2", "no_resident",
+ * "no_quant_wave", "pf_splits1", "pf_splits2", "pf_tg1", "pf_tg2", "pf_ks1", "pf_ks2", "pf_verbose",
+ * "exec_spin_limit" (see the source for the meaning of each).  value < 0 restores the default.
+ * The environment variable NQ_<NAME IN CAPITALS> gives an option its initial value; it is read once,
+ * when the library first consults an option, never on a launch path.  Plans keep the schedules
+ * chosen when they were created.  Not thread-safe against forwards running at the same time.
+ * Unknown name -> NQ_E_INVALID_ARG. */
+int nq_set_option(const char* name, int value);
+/* *value = the option's current value, -1 when it is unset (built-in default applies). */
+int nq_get_option(const char* name, int* value);
 
 const char* nq_status_string(int status);
 const char* nq_last_error_string(void);

@@ -52,7 +52,11 @@ def lib() -> ctypes.CDLL:
         L.nq_binlr_create_from_device.argtypes = [ctypes.POINTER(vp), i64, i64, i64, vp, vp, vp, vp, ci, ci, u32]
         L.nq_binlr_create_from_device.restype = ci
         L.nq_binlr_reserve.argtypes = [vp, ci]; L.nq_binlr_reserve.restype = ci
+        L.nq_binlr_reserved.argtypes = [vp, ctypes.POINTER(ci), ctypes.POINTER(ctypes.c_size_t)]; L.nq_binlr_reserved.restype = ci
         L.nq_binlr_forward.argtypes = [vp, vp, vp, ci, vp]; L.nq_binlr_forward.restype = ci
+        L.nq_binlr_forward_exact.argtypes = [vp, vp, vp, ci, vp]; L.nq_binlr_forward_exact.restype = ci
+        L.nq_set_option.argtypes = [ctypes.c_char_p, ci]; L.nq_set_option.restype = ci
+        L.nq_get_option.argtypes = [ctypes.c_char_p, ctypes.POINTER(ci)]; L.nq_get_option.restype = ci
         L.nq_binlr_forward_many.argtypes = [vp, vp, vp, ci, ci, vp]; L.nq_binlr_forward_many.restype = ci
         L.nq_plan_create.argtypes = [ctypes.POINTER(vp), vp, vp, vp, ci, ci]; L.nq_plan_create.restype = ci
         L.nq_plan_forward.argtypes = [vp, vp]; L.nq_plan_forward.restype = ci
@@ -193,8 +197,30 @@ def nq_binlr_reserve(h: int, max_batch: int) -> None:
     _check(lib().nq_binlr_reserve(h, max_batch))
 
 
+def nq_binlr_reserved(h: int):
+    """(largest batch that allocates nothing, bytes of the dense path's workspace)."""
+    b, n = ctypes.c_int(), ctypes.c_size_t()
+    _check(lib().nq_binlr_reserved(h, ctypes.byref(b), ctypes.byref(n)))
+    return int(b.value), int(n.value)
+
+
 def nq_binlr_forward(h: int, x, y, batch: int, stream=None) -> None:
     _check(lib().nq_binlr_forward(h, _dev_ptr(x), _dev_ptr(y), batch, _stream(stream)))
+
+
+def nq_binlr_forward_exact(h: int, x, y, batch: int, stream=None) -> None:
+    _check(lib().nq_binlr_forward_exact(h, _dev_ptr(x), _dev_ptr(y), batch, _stream(stream)))
+
+
+def nq_set_option(name: str, value: Optional[int]) -> None:
+    """value None (or negative) restores the option's default."""
+    _check(lib().nq_set_option(name.encode(), -1 if value is None else int(value)))
+
+
+def nq_get_option(name: str) -> int:
+    v = ctypes.c_int()
+    _check(lib().nq_get_option(name.encode(), ctypes.byref(v)))
+    return int(v.value)
 
 
 def nq_binlr_forward_unscaled(h: int, x, z, batch: int, stream=None) -> None:

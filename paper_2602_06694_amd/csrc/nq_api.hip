@@ -1,5 +1,6 @@
 // C ABI of libnq_binlr: host-side packing, layer handles, plans.  See include/nq_binlr.h.
 #include <algorithm>
+#include <cctype>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -30,6 +31,38 @@ static int fail(int code, const char* msg)
 
 static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
+// ---- tuning options: one table, filled once from the environment, then only through nq_set_option ----
+struct OptEntry { const char* name; bool flag; };
+static const OptEntry kOptTable[OPT_COUNT] = {
+    {"slab_mb", false}, {"force_w", false}, {"split_steps", false}, {"selfq4_min_steps", false}, {"share_steps", false},
+    {"share_min_batch", false}, {"stream_steps", false}, {"schedule_full", false}, {"fuse_max_mb", false},
+    {"no_fuse", true}, {"no_selfq", true}, {"no_selfq_c2", true}, {"no_resident", true}, {"no_quant_wave", true},
+    {"pf_splits1", false}, {"pf_splits2", false}, {"pf_tg1", false}, {"pf_tg2", false}, {"pf_ks1", false}, {"pf_ks2", false},
+    {"pf_verbose", true},
+};
+static int g_opt[OPT_COUNT];
+static std::once_flag g_opt_once;
+
+static void options_from_environment()
+{
+    for (int i = 0; i < OPT_COUNT; ++i) {
+        g_opt[i] = -1;
+        std::string env = "NQ_";
+        for (const char* c = kOptTable[i].name; *c; ++c) env += (char)toupper((unsigned char)*c);
+        const char* v = getenv(env.c_str());
+        if (!v || !*v) continue;
+        const int x = atoi(v);
+        if (kOptTable[i].flag) g_opt[i] = (v[0] == '0' && v[1] == 0) ? 0 : 1;
+        else if (x >= 0) g_opt[i] = x;
+    }
+}
+
+int opt(Opt o)
+{
+    std::call_once(g_opt_once, options_from_environment);
+    return g_opt[o];
+}
+
 static size_t dtype_size(int dt) { return dt == NQ_F32 ? 4 : 2; }
 
 }  // namespace nq
@@ -54,12 +87,7 @@ static std::vector<Slab*> g_slabs;
 
 static size_t slab_bytes()
 {
-    size_t mb = 512;
-    if (const char* v = getenv("NQ_SLAB_MB")) {
-        long x = atol(v);
-        if (x >= 1) mb = (size_t)x;
-    }
-    return mb << 20;
+    return (size_t)std::max(1, opt_or(OPT_SLAB_MB, 512)) << 20;
 }
 
 // returns hipSuccess and (*out, *owner); the block is 4 KiB aligned
@@ -239,6 +267,31 @@ extern "C" const char* nq_status_string(int status)
 }
 
 extern "C" const char* nq_last_error_string(void) { return g_last_error.c_str(); }
+
+static int find_option(const char* name)
+{
+    if (!name) return -1;
+    for (int i = 0; i < OPT_COUNT; ++i)
+        if (strcmp(name, kOptTable[i].name) == 0) return i;
+    return -1;
+}
+
+extern "C" int nq_set_option(const char* name, int value)
+{
+    const int i = find_option(name);
+    if (i < 0) return fail(NQ_E_INVALID_ARG, "nq_set_option: unknown option name");
+    (void)opt((Opt)i);                                   // the environment is read before the first override, not after it
+    g_opt[i] = value < 0 ? -1 : (kOptTable[i].flag ? (value != 0) : value);
+    return NQ_OK;
+}
+
+extern "C" int nq_get_option(const char* name, int* value)
+{
+    const int i = find_option(name);
+    if (i < 0 || !value) return fail(i < 0 ? NQ_E_INVALID_ARG : NQ_E_NULL, "nq_get_option: unknown option name or NULL pointer");
+    *value = opt((Opt)i);
+    return NQ_OK;
+}
 
 // ---------------------------------------------------------------------------------------------
 // handles
@@ -436,9 +489,9 @@ extern "C" int nq_binlr_set_mid_scale(nq_handle h, const uint16_t* s_mid_fp16)
     return NQ_OK;
 }
 
-static int ensure_prefill_workspace(nq_handle h, int batch)
+// grows the dense path's workspace to `need` bytes (never shrinks it)
+static int grow_prefill_workspace(nq_handle h, size_t need)
 {
-    const size_t need = prefill_workspace_bytes(h->d_out, h->d_in, h->r, batch);
     if (need <= h->pf_bytes) return NQ_OK;
     NQ_HIP(hipDeviceSynchronize());
     if (h->pf_alloc) NQ_HIP(hipFree(h->pf_alloc));
@@ -451,19 +504,36 @@ static int ensure_prefill_workspace(nq_handle h, int batch)
     return NQ_OK;
 }
 
+static int ensure_prefill_workspace(nq_handle h, int batch)
+{
+    return grow_prefill_workspace(h, prefill_workspace_bytes(h->d_out, h->d_in, h->r, batch));
+}
+
 extern "C" int nq_binlr_reserve(nq_handle h, int max_batch)
 {
     if (!h) return fail(NQ_E_NULL, "nq_binlr_reserve: NULL handle");
     if (max_batch < 1) return fail(NQ_E_INVALID_ARG, "nq_binlr_reserve: max_batch must be >= 1");
     if (max_batch < NQ_PREFILL_MIN_BATCH || (h->flags & (NQ_FLAG_NO_PREFILL | NQ_FLAG_DECODE_VALU))) return NQ_OK;   // decode workspace is fixed
-    // the dense path's workspace need is not monotone in the batch (small batches split the
-    // reduction and keep partial sums): size it for every power of two up to max_batch
-    for (int b = NQ_PREFILL_MIN_BATCH; ; b *= 2) {
-        int rc = ensure_prefill_workspace(h, std::min(b, max_batch));
-        if (rc != NQ_OK) return rc;
+    // The dense path's need is not monotone in the batch: smaller batches split the reduction
+    // over more workgroups and keep more partial sums.  It depends on the batch only through its
+    // padding to whole 64-token tiles, so the maximum over every padding up to max_batch's is taken.
+    size_t need = 0;
+    for (int64_t b = 64; ; b += 64) {
+        const int bb = (int)std::min<int64_t>(b, max_batch);
+        need = std::max(need, prefill_workspace_bytes(h->d_out, h->d_in, h->r, bb));
         if (b >= max_batch) break;
     }
+    int rc = grow_prefill_workspace(h, need);
+    if (rc != NQ_OK) return rc;
     h->pf_batch = std::max(h->pf_batch, max_batch);
+    return NQ_OK;
+}
+
+extern "C" int nq_binlr_reserved(nq_handle h, int* max_batch, size_t* workspace_bytes)
+{
+    if (!h) return fail(NQ_E_NULL, "nq_binlr_reserved: NULL handle");
+    if (max_batch) *max_batch = std::max(h->pf_batch, (int)NQ_DECODE_MAX_BATCH);
+    if (workspace_bytes) *workspace_bytes = h->pf_bytes;
     return NQ_OK;
 }
 
@@ -532,7 +602,7 @@ static int decode_once(nq_handle h, const void* x, void* y, int batch, hipStream
     // stage quantises it itself (two launches per forward instead of four)
     // (reductions of up to 4096 elements by the waves of the one- or four-wave kernel, longer ones
     // up to 16384 by the 16-wave kernel)
-    const bool no_fuse = getenv("NQ_NO_FUSE") != nullptr, no_selfq = getenv("NQ_NO_SELFQ") != nullptr;
+    const bool no_fuse = opt_flag(OPT_NO_FUSE), no_selfq = opt_flag(OPT_NO_SELFQ);
     const int sq1 = no_selfq ? 0 : selfq_width(s1.n_steps, s1.n_steps, batch);
     const int sq2 = no_selfq ? 0 : selfq_width(s2.n_steps, s2.n_steps, batch);
     if (sq1) {
@@ -642,14 +712,6 @@ static void drop_cached_plan_locked()
     g_plan_cache.clear();
 }
 
-static int env_int_api(const char* name, int dflt)
-{
-    const char* v = getenv(name);
-    if (!v || !*v) return dflt;
-    const int x = atoi(v);
-    return x >= 0 ? x : dflt;
-}
-
 extern "C" int nq_plan_create(nq_plan* out, const nq_handle* hs, const void* const* xs, void* const* ys, int n,
                               int batch)
 {
@@ -706,23 +768,23 @@ extern "C" int nq_plan_create(nq_plan* out, const nq_handle* hs, const void* con
             int min_steps = max_steps;
             for (int i = 0; i < n; ++i) min_steps = std::min(min_steps, sd[i].n_steps);
             const bool full = total_rb >= schedule_full_rowblocks();
-            const int sq = full || getenv("NQ_NO_SELFQ") ? 0 : selfq_width(max_steps, min_steps, batch);
+            const int sq = full || opt_flag(OPT_NO_SELFQ) ? 0 : selfq_width(max_steps, min_steps, batch);
             if (sq)
                 w = sq == 1 ? kSelfqSchedule1 : kSelfqSchedule4;
-            else if (batch == 1 && !getenv("NQ_NO_FUSE") && fused_fits(max_steps, batch) &&
-                     tile_mb <= (double)env_int_api("NQ_FUSE_MAX_MB", 24))
+            else if (batch == 1 && !opt_flag(OPT_NO_FUSE) && fused_fits(max_steps, batch) &&
+                     tile_mb <= (double)opt_or(OPT_FUSE_MAX_MB, 24))
                 w = kFusedSchedule;
             max_steps_of[st] = max_steps;
             // A launch that fills the chip keeps its schedule, but its waves quantise their own share
             // of the input: no quantisation launch, and the B operand comes out of LDS.
             // batch 6..8, short reductions: the shared-input kernel with the whole input resident in LDS
-            if (w == 1 && batch > 5 && max_steps <= 16 && total_rb >= schedule_full_rowblocks() && !getenv("NQ_NO_RESIDENT"))
+            if (w == 1 && batch > 5 && max_steps <= 16 && total_rb >= schedule_full_rowblocks() && !opt_flag(OPT_NO_RESIDENT))
                 w = kSharedResidentSchedule;
             // (with four waves per row block only where every reduction has 48 steps or more: for shorter
             // ones the split kernel with its quantisation launch measured the same or faster -- 35 steps:
             // 62 against 66 us, 55 steps: 85 against 85 -- and a mixed list, as stage 2 of the 70B stack
             // with its 8-step ranks, 442 + 9 against 476 us)
-            if ((w == 1 || (w == 4 && min_steps >= env_int_api("NQ_SELFQ4_MIN_STEPS", 48))) && !getenv("NQ_NO_SELFQ") && full &&
+            if ((w == 1 || (w == 4 && min_steps >= opt_or(OPT_SELFQ4_MIN_STEPS, 48))) && !opt_flag(OPT_NO_SELFQ) && full &&
                 selfq_fits(w, max_steps, min_steps, batch))
                 w = w == 1 ? kSelfqSchedule1 : kSelfqSchedule4;
         }
@@ -902,21 +964,32 @@ extern "C" int nq_plan_forward_timed(nq_plan p, void* stream, float ms[4])
     return NQ_OK;
 }
 
-// z = U (V^T (s_in (.) x)): the forward without its output scale, any batch, in passes of up to 8 tokens
-extern "C" int nq_binlr_forward_unscaled(nq_handle h, const void* x, void* z, int batch, void* stream)
+// any batch through the streaming kernels, in passes of up to 8 tokens; `unscaled`: z = U (V^T (s_in (.) x))
+static int forward_in_passes(const char* who, nq_handle h, const void* x, void* y, int batch, void* stream, bool unscaled)
 {
-    if (!h) return fail(NQ_E_NULL, "nq_binlr_forward_unscaled: NULL handle");
-    if (batch < 1) return fail(NQ_E_INVALID_ARG, "nq_binlr_forward_unscaled: batch must be >= 1");
+    char buf[96];
+    if (!h) { snprintf(buf, sizeof buf, "%s: NULL handle", who); return fail(NQ_E_NULL, buf); }
+    if (batch < 1) { snprintf(buf, sizeof buf, "%s: batch must be >= 1", who); return fail(NQ_E_INVALID_ARG, buf); }
     const size_t xs = dtype_size(h->x_dtype), ys = dtype_size(h->y_dtype);
-    int rc = check_xy("nq_binlr_forward_unscaled", x, z, (size_t)batch * h->d_in * xs, (size_t)batch * h->d_out * ys);
+    int rc = check_xy(who, x, y, (size_t)batch * h->d_in * xs, (size_t)batch * h->d_out * ys);
     if (rc != NQ_OK) return rc;
     for (int b0 = 0; b0 < batch; b0 += NQ_DECODE_MAX_BATCH) {
         const int nb = std::min(NQ_DECODE_MAX_BATCH, batch - b0);
-        rc = decode_once(h, (const char*)x + (size_t)b0 * h->d_in * xs, (char*)z + (size_t)b0 * h->d_out * ys, nb,
-                         (hipStream_t)stream, true);
+        rc = decode_once(h, (const char*)x + (size_t)b0 * h->d_in * xs, (char*)y + (size_t)b0 * h->d_out * ys, nb,
+                         (hipStream_t)stream, unscaled);
         if (rc != NQ_OK) return rc;
     }
     return NQ_OK;
+}
+
+extern "C" int nq_binlr_forward_unscaled(nq_handle h, const void* x, void* z, int batch, void* stream)
+{
+    return forward_in_passes("nq_binlr_forward_unscaled", h, x, z, batch, stream, true);
+}
+
+extern "C" int nq_binlr_forward_exact(nq_handle h, const void* x, void* y, int batch, void* stream)
+{
+    return forward_in_passes("nq_binlr_forward_exact", h, x, y, batch, stream, false);
 }
 
 extern "C" int nq_scale_grad(const void* a, int a_dtype, const void* b, int b_dtype, int batch, int64_t n, float* out,

@@ -395,7 +395,7 @@ quantize_wave_kernel(const QuantDesc* __restrict__ descs, QuantDesc single, int 
 int launch_quantize(const QuantDesc* d_descs, const QuantDesc& single, int n_ops, int max_chunks, int batch,
                     hipStream_t s)
 {
-    const bool no_wave = getenv("NQ_NO_QUANT_WAVE") != nullptr;
+    const bool no_wave = opt_flag(OPT_NO_QUANT_WAVE);
     // several short vectors: one wave each (a lone short vector keeps the workgroup kernel, whose
     // threads share it)
     if (!no_wave && max_chunks <= 64 && (size_t)n_ops * batch >= 64) {
@@ -1468,14 +1468,6 @@ int device_cu_count()
     return g_cu_count;
 }
 
-static int env_int(const char* name, int dflt)
-{
-    const char* v = getenv(name);
-    if (!v || !*v) return dflt;
-    int x = atoi(v);
-    return x > 0 ? x : dflt;
-}
-
 // tiles a wave of stage_selfq_kernel<W> keeps in flight (with the B operand in LDS a lone wave affords eight;
 // measured on the 1024-layer pool: 192-193 us per step with 8 / 4, 194-195 us with 8 / 8, 6 / 6 or four waves per SIMD)
 constexpr int kSelfqDepth1 = 8, kSelfqDepth4 = 4;
@@ -1592,7 +1584,7 @@ int launch_fused_list(const FusedItem* d_items, int n_items, int max_steps, hipS
 bool selfq_fits(int w, int max_steps, int min_steps, int batch)
 {
     if (batch != 1 || (w != 1 && w != 4)) return false;
-    if (w == 1) return min_steps >= 16 && max_steps <= (getenv("NQ_NO_SELFQ_C2") ? 16 : 32);    // (two chunks per lane beyond 16)
+    if (w == 1) return min_steps >= 16 && max_steps <= (opt_flag(OPT_NO_SELFQ_C2) ? 16 : 32);    // (two chunks per lane beyond 16)
     return max_steps <= 16 * w;
 }
 
@@ -1636,13 +1628,17 @@ int launch_selfq(const FusedItem* d_items, int n_items, const QuantDesc& q1, con
 }
 
 // Row blocks from which a launch counts as filling the chip.
-int schedule_full_rowblocks() { return env_int("NQ_SCHEDULE_FULL", device_cu_count() * 8); }
+int schedule_full_rowblocks()
+{
+    const int v = opt(OPT_SCHEDULE_FULL);
+    return v > 0 ? v : device_cu_count() * 8;
+}
 
 // Smallest batch whose long reductions take the shared-input kernel in launches that fill the chip.
 // With one column group (batch <= 5) it pays from batch 4 on (stage 1 of the 4096x4096 r=1024 pool:
 // 121 -> 116 us at batch 4, 130 -> 120 us at batch 5; batch 3 the same, batch 2 slower); short
 // reductions (the resident variant) stay with the stream kernel below batch 6 (115 against 119 us).
-int shared_min_batch() { return env_int("NQ_SHARE_MIN_BATCH", 4); }
+int shared_min_batch() { return std::max(1, opt_or(OPT_SHARE_MIN_BATCH, 4)); }
 
 int stage_schedule(int n_rb_total, int mean_steps, int batch)
 {
@@ -1650,13 +1646,13 @@ int stage_schedule(int n_rb_total, int mean_steps, int batch)
     // which lets small inputs exercise the schedules built for large launches)
     const int full = schedule_full_rowblocks();
     int w;
-    if (n_rb_total >= full && batch >= shared_min_batch()) w = mean_steps >= env_int("NQ_SHARE_STEPS", 32) ? kSharedSchedule : 1;
+    if (n_rb_total >= full && batch >= shared_min_batch()) w = mean_steps >= std::max(1, opt_or(OPT_SHARE_STEPS, 32)) ? kSharedSchedule : 1;
     // (batch 1 splits from 33 steps on: stage 2 of the 70B stack, 35 and 55 steps, 452 -> 442 us; pools
     // of 35- and 55-step reductions 64 -> 62 and 91 -> 85 us including the quantisation launch)
-    else if (n_rb_total >= full) w = mean_steps >= env_int("NQ_SPLIT_STEPS", batch == 1 ? 33 : 64) ? 4 : 1;
+    else if (n_rb_total >= full) w = mean_steps >= std::max(1, opt_or(OPT_SPLIT_STEPS, batch == 1 ? 33 : 64)) ? 4 : 1;
     else w = (n_rb_total * 4 >= full || batch > 2) ? 4 : 16;
-    if (const char* f = getenv("NQ_FORCE_W")) {
-        int fw = atoi(f);
+    {
+        const int fw = opt(OPT_FORCE_W);
         if (fw == 1 || fw == 4 || (fw == 16 && batch <= 2)) w = fw;     // (the shared schedule cannot be forced: it needs a work list)
     }
     return w;
@@ -1668,7 +1664,7 @@ int stage_schedule(int n_rb_total, int mean_steps, int batch)
 // 4096x4096 r=1024 pool: 99.7 us with one 16-step row block per item, 103.5 us with eight).
 // With two column groups (batch 6..8, two waves per SIMD) a few chained row blocks still pay (stage 2 of the
 // same pool at batch 8: 197 us with three per item, 205 us with one).
-int stream_target_steps(int batch) { return env_int("NQ_STREAM_STEPS", batch <= 5 ? 16 : 64); }
+int stream_target_steps(int batch) { return std::max(1, opt_or(OPT_STREAM_STEPS, batch <= 5 ? 16 : 64)); }
 
 // Row blocks an item may chain: its deferred results (128 x batch floats per row block) share the
 // CU's LDS with those of the other resident waves (20 per CU with one column group, 8 with two).

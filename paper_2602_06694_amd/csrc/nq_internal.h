@@ -91,6 +91,37 @@ inline int64_t n_rowblocks(int64_t M) { return (M + kTileRows - 1) / kTileRows; 
 inline int64_t n_steps(int64_t N) { return (N + 4 * kTileCols - 1) / (4 * kTileCols) * 4; }
 inline size_t tile_words(int64_t M, int64_t N) { return (size_t)n_rowblocks(M) * n_steps(N) * kTileWords; }
 
+// ---- tuning options ------------------------------------------------------------------------
+// Process-wide integers that steer the choice of schedules and tilings (the tests use them to run
+// schedules built for large launches on small inputs; the defaults are the measured choices).
+// An option is "unset" (-1: the built-in default applies) until nq_set_option gives it a value;
+// the NQ_<NAME> environment variables are read ONCE, when the library first looks at an option, and
+// never on a launch path.
+enum Opt {
+    OPT_SLAB_MB,            // size of the device slabs layers are carved from (default 512)
+    OPT_FORCE_W,            // 1 / 4 / 16: schedule of the stage launches
+    OPT_SPLIT_STEPS,        // reduction length from which a launch is split four ways (33 at batch 1, 64 above)
+    OPT_SELFQ4_MIN_STEPS,   // shortest reduction of a launch whose four-wave row blocks quantise their own input (48)
+    OPT_SHARE_STEPS,        // reduction length from which the shared-input kernel is taken (32)
+    OPT_SHARE_MIN_BATCH,    // smallest batch that takes it (4)
+    OPT_STREAM_STEPS,       // steps a stream item chains (16; 64 with two column groups)
+    OPT_SCHEDULE_FULL,      // row blocks from which a launch counts as filling the chip (8 per CU)
+    OPT_FUSE_MAX_MB,        // tile megabytes up to which a batch-1 plan launch takes the 16-wave fused kernel (24; 0: never)
+    OPT_NO_FUSE,            // flag: no launch takes the 16-wave fused kernel
+    OPT_NO_SELFQ,           // flag: no launch takes the one- and four-wave self-quantising kernels
+    OPT_NO_SELFQ_C2,        // flag: one wave per row block quantises its own input only up to 16 steps
+    OPT_NO_RESIDENT,        // flag: batch 6..8 never takes the resident-input variant of the shared kernel
+    OPT_NO_QUANT_WAVE,      // flag: short vectors are quantised by the workgroup kernel too
+    OPT_PF_SPLITS1, OPT_PF_SPLITS2,     // split count of the two prefill GEMMs
+    OPT_PF_TG1, OPT_PF_TG2,             // token groups per workgroup tile (2 or 4)
+    OPT_PF_KS1, OPT_PF_KS2,             // halves of the reduction taken inside a workgroup (1 or 2)
+    OPT_PF_VERBOSE,         // flag: print the chosen prefill tiling
+    OPT_COUNT
+};
+int opt(Opt o);                                        // -1 when unset
+inline int opt_or(Opt o, int dflt) { const int v = opt(o); return v >= 0 ? v : dflt; }
+inline bool opt_flag(Opt o) { return opt(o) > 0; }
+
 // ---- error plumbing ------------------------------------------------------------------------
 void set_error(const std::string& msg);
 int hip_fail(hipError_t e, const char* what, const char* file, int line);

@@ -747,16 +747,16 @@ static PfLayout pf_layout(int64_t d_out, int64_t d_in, int64_t r, int batch)
     const GemmTiling t2 = choose_tiling(L.m_pad, (int)n_rowblocks(d_out), (int)n_steps(r), L.n2_pad);
     L.tg1 = t1.tg; L.splits1 = t1.splits; L.ks1 = t1.ks;
     L.tg2 = t2.tg; L.splits2 = t2.splits; L.ks2 = t2.ks;
-    if (getenv("NQ_PF_TG1")) L.tg1 = atoi(getenv("NQ_PF_TG1")) == 2 ? 2 : 4;
-    if (getenv("NQ_PF_TG2")) L.tg2 = atoi(getenv("NQ_PF_TG2")) == 2 ? 2 : 4;
-    if (getenv("NQ_PF_SPLITS1")) L.splits1 = std::max(1, atoi(getenv("NQ_PF_SPLITS1")));
-    if (getenv("NQ_PF_SPLITS2")) L.splits2 = std::max(1, atoi(getenv("NQ_PF_SPLITS2")));
-    if (getenv("NQ_PF_KS1")) L.ks1 = atoi(getenv("NQ_PF_KS1")) == 2 ? 2 : 1;
-    if (getenv("NQ_PF_KS2")) L.ks2 = atoi(getenv("NQ_PF_KS2")) == 2 ? 2 : 1;
+    if (opt(OPT_PF_TG1) >= 0) L.tg1 = opt(OPT_PF_TG1) == 2 ? 2 : 4;
+    if (opt(OPT_PF_TG2) >= 0) L.tg2 = opt(OPT_PF_TG2) == 2 ? 2 : 4;
+    if (opt(OPT_PF_SPLITS1) >= 0) L.splits1 = std::max(1, opt(OPT_PF_SPLITS1));
+    if (opt(OPT_PF_SPLITS2) >= 0) L.splits2 = std::max(1, opt(OPT_PF_SPLITS2));
+    if (opt(OPT_PF_KS1) >= 0) L.ks1 = opt(OPT_PF_KS1) == 2 ? 2 : 1;
+    if (opt(OPT_PF_KS2) >= 0) L.ks2 = opt(OPT_PF_KS2) == 2 ? 2 : 1;
     // the in-workgroup split needs 64-token tiles and a reduction of whole groups of eight steps
     if (L.tg1 != 4 || n_steps(d_in) % 8 != 0) L.ks1 = 1;
     if (L.tg2 != 4 || n_steps(r) % 8 != 0) L.ks2 = 1;
-    if (getenv("NQ_PF_VERBOSE"))
+    if (opt_flag(OPT_PF_VERBOSE))
         fprintf(stderr, "prefill tiling B=%d: gemm1 tg=%d splits=%d ks=%d, gemm2 tg=%d splits=%d ks=%d\n", batch, L.tg1, L.splits1,
                 L.ks1, L.tg2, L.splits2, L.ks2);
     size_t o = 0;

@@ -26,3 +26,33 @@ def pytest_collection_modifyitems(config, items):
     for it in items:
         if "gpu" in it.keywords:
             it.add_marker(skip)
+
+
+class _Options:
+    """Sets tuning options of the library for one test and restores the defaults afterwards."""
+
+    def __init__(self):
+        self.touched = set()
+
+    def set(self, name, value):
+        """name: the option's name (an "NQ_" prefix and capitals are accepted); value: int, its decimal
+        string, or None for the default."""
+        from paper_2602_06694_amd import binding as nq
+        name = name[3:].lower() if name.startswith("NQ_") else name
+        nq.nq_set_option(name, None if value is None else int(value))
+        self.touched.add(name)
+
+    def unset(self, name):
+        self.set(name, None)
+
+    def restore(self):
+        from paper_2602_06694_amd import binding as nq
+        for name in self.touched:
+            nq.nq_set_option(name, None)
+
+
+@pytest.fixture
+def nqopt():
+    o = _Options()
+    yield o
+    o.restore()

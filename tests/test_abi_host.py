@@ -108,3 +108,34 @@ def test_argument_validation_needs_no_gpu():
     assert L.nq_plan_destroy(None) == nq.NQ_OK
     assert L.nq_plan_forward(None, None) == nq.NQ_E_NULL
     assert nq.nq_status_string(nq.NQ_E_ALIGN) == "pointer not 16-byte aligned"
+
+
+def test_tuning_options_are_set_read_and_restored_without_a_gpu():
+    """The options are plain integers behind nq_set_option / nq_get_option: unset (-1) until given a
+    value, flags are normalised to 0 / 1, a negative value restores the default, unknown names are errors."""
+    assert nq.nq_get_option("schedule_full") == -1
+    nq.nq_set_option("schedule_full", 1)
+    assert nq.nq_get_option("schedule_full") == 1
+    nq.nq_set_option("fuse_max_mb", 0)
+    assert nq.nq_get_option("fuse_max_mb") == 0                 # 0 is a value (never fuse), not "unset"
+    nq.nq_set_option("no_selfq", 7)
+    assert nq.nq_get_option("no_selfq") == 1
+    for name in ("schedule_full", "fuse_max_mb", "no_selfq"):
+        nq.nq_set_option(name, None)
+        assert nq.nq_get_option(name) == -1
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_set_option("no_such_option", 1)
+    assert e.value.status == nq.NQ_E_INVALID_ARG
+    with pytest.raises(nq.NQError):
+        nq.nq_get_option("NQ_SCHEDULE_FULL")                    # the environment's spelling is not an option name
+
+
+def test_no_environment_lookup_on_a_launch_path():
+    """The library reads the environment in one place only (the options table's initialiser)."""
+    import glob
+    hits = []
+    for f in glob.glob(os.path.join(ROOT, "paper_2602_06694_amd", "csrc", "*")):
+        for i, line in enumerate(open(f), 1):
+            if "getenv" in line and not line.lstrip().startswith("//"):
+                hits.append((os.path.basename(f), i))
+    assert len(hits) == 1 and hits[0][0] == "nq_api.hip", hits

@@ -32,8 +32,8 @@ def build_stack(cfg, n_layers=None, batch=1):
 def test_config2_pool_as_the_benchmark_runs_it(batch):
     """Config 2's layer as a pool of distinct instances under one plan -- the benchmark's headline
     launch configuration (at batch 8, 320 instances are enough row blocks for the schedules of
-    chip-filling launches, the shared-input kernel among them).  Every 16th instance is checked in
-    full against the oracle, and every output of every instance must be finite."""
+    chip-filling launches, the shared-input kernel among them).  Every output of every instance is
+    checked against the factored oracle."""
     import torch
     shp = synth.CONFIGS[2].block[0]
     n = 320
@@ -50,9 +50,9 @@ def test_config2_pool_as_the_benchmark_runs_it(batch):
     torch.cuda.synchronize()
     assert all(bool(torch.isfinite(y).all()) for y in ys)
     worst = 0.0
-    for i in range(0, n, 16):
+    for i in range(n):
         worst = max(worst, rel_err(ys[i].cpu().numpy(), layers[i].oracle(xs_np[i])))
-    print(f"config 2 pool, batch {batch}: worst rel err over {n // 16} checked instances {worst:.3e}")
+    print(f"config 2 pool, batch {batch}: worst rel err over all {n} instances {worst:.3e}")
     assert worst <= DECODE_TOL and worst <= BAR
     nq.nq_plan_destroy(plan)
     for L in layers:
@@ -81,7 +81,10 @@ def test_config3_llama2_7b_stack_every_output():
         L.close()
 
 
-def test_config4_llama2_70b_stack_sampled():
+def test_config4_llama2_70b_stack_every_output():
+    """All 560 layers of the 70B-shaped stack under one plan: every output of every layer against the
+    factored oracle (the layers sit at different offsets of ten 512 MiB slabs, which is what varies
+    between them), and sampled rows of every eighth decoder layer against the dense definition."""
     import torch
     layers, xs_np, xs, ys = build_stack(4)
     assert len(layers) == 560
@@ -91,19 +94,21 @@ def test_config4_llama2_70b_stack_sampled():
     nq.nq_plan_forward(plan)
     torch.cuda.synchronize()
     rng = np.random.default_rng(4)
-    worst_full, worst_rows = 0.0, 0.0
+    worst_full, worst_rows, at = 0.0, 0.0, -1
     for i, (L, x, y) in enumerate(zip(layers, xs_np, ys)):
         layer = i // 7
         yh = y.cpu().numpy()
-        assert np.isfinite(yh).all()
-        if layer in (0, 41, 79):                             # whole layers against the factored oracle
-            worst_full = max(worst_full, rel_err(yh, L.oracle(x)))
-        elif layer % 8 == 3:                                 # sampled rows against the dense definition
+        e = rel_err(yh, L.oracle(x))
+        if e > worst_full:
+            worst_full, at = e, i
+        if layer % 8 == 3:                                   # sampled rows against the dense definition
             rows = np.unique(np.concatenate([[0, 127, 128, L.d_out - 1], rng.integers(0, L.d_out, 2)]))
             ref = L.oracle_rows(x, rows)
             scale = np.abs(yh).max()
             worst_rows = max(worst_rows, float(np.abs(yh[:, rows] - ref).max() / scale))
-    print(f"config 4: worst rel err, whole layers {worst_full:.3e}, sampled rows {worst_rows:.3e}")
+        if i % 70 == 69:
+            print(f"config 4: {i + 1} of 560 layers checked, worst so far {worst_full:.3e}", flush=True)
+    print(f"config 4: worst rel err over all 560 layers {worst_full:.3e} (op {at}), sampled dense rows {worst_rows:.3e}")
     assert worst_full <= DECODE_TOL and worst_rows <= DECODE_TOL
     nq.nq_plan_destroy(plan)
     for L in layers:
@@ -112,6 +117,9 @@ def test_config4_llama2_70b_stack_sampled():
 
 @pytest.mark.parametrize("batch", [512, 2048])
 def test_config5_prefill_70b_mlp(batch):
+    """The dense path at the prefill sizes: every token at 512; at 2048 one token of every 64-token tile
+    (the unit of the workgroup remap and of the eight-wave split) plus 256 random ones -- every output
+    of those tokens against the factored oracle, a few rows against the dense definition."""
     import torch
     c = synth.CONFIGS[5]
     rng = np.random.default_rng(5)
@@ -121,15 +129,27 @@ def test_config5_prefill_70b_mlp(batch):
         x = synth.gen_layer_x(5, 0, li, shp, batch, c.x_dtype, c.outlier_frac)
         y = L.forward(x)
         assert np.isfinite(y).all()
-        toks = np.unique(np.concatenate([[0, 63, 64, batch - 1], rng.integers(0, batch, 4)]))
-        ref = L.oracle(x[toks])                              # every output of the sampled tokens
-        scale = np.abs(ref).max()
-        err = float(np.abs(y[toks] - ref).max() / scale)
+        if batch <= 512:
+            toks = np.arange(batch)
+        else:
+            per_tile = np.arange(0, batch, 64) + rng.integers(0, 64, batch // 64)
+            toks = np.unique(np.concatenate([[0, 63, 64, batch - 1], per_tile, rng.integers(0, batch, 256)]))
+            assert len(set(toks // 64)) == batch // 64
+        worst_abs, ref_max, per_token = 0.0, 0.0, 0.0
+        for t0 in range(0, len(toks), 64):                   # in pieces, so that the run shows progress
+            sel = toks[t0:t0 + 64]
+            ref = L.oracle(x[sel])                           # every output of these tokens
+            d = np.abs(y[sel] - ref)
+            worst_abs, ref_max = max(worst_abs, float(d.max())), max(ref_max, float(np.abs(ref).max()))
+            per_token = max(per_token, float((d.max(axis=1) / np.abs(ref).max(axis=1)).max()))
+            print(f"config 5 {shp.name} B={batch}: {min(t0 + 64, len(toks))} of {len(toks)} tokens", flush=True)
+        err = worst_abs / ref_max                            # the bar's measure: over the whole output of the call
         rows = np.array([0, 127, 128, shp.d_out - 1])
         ra = L.oracle_rows(x[toks[:2]], rows)                # dense definition on a few rows
-        err_a = float(np.abs(y[toks[:2]][:, rows] - ra).max() / scale)
-        print(f"config 5 {shp.name} B={batch}: rel err {err:.3e} (dense rows {err_a:.3e})")
-        assert err <= PREFILL_TOL and err <= BAR and err_a <= PREFILL_TOL
+        err_a = float(np.abs(y[toks[:2]][:, rows] - ra).max() / ref_max)
+        print(f"config 5 {shp.name} B={batch}: rel err over {len(toks)} tokens {err:.3e} (worst token relative to "
+              f"its own largest output {per_token:.3e}; dense rows {err_a:.3e})")
+        assert err <= PREFILL_TOL and err <= BAR and err_a <= PREFILL_TOL and per_token <= BAR
         L.close()
 
 

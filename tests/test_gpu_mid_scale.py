@@ -67,7 +67,7 @@ def test_mid_scale_of_ones_changes_no_bit():
     L.close()
 
 
-def test_plans_and_every_schedule(monkeypatch):
+def test_plans_and_every_schedule(nqopt):
     """Plans (self-quantising launches, short and chip-filling; the 16-wave fused launches; separate
     quantisation launches) and the plain vector-ALU kernels all apply the rank-wise scale."""
     import torch
@@ -84,9 +84,9 @@ def test_plans_and_every_schedule(monkeypatch):
                       ({"NQ_NO_SELFQ": "1", "NQ_FUSE_MAX_MB": "0"}, {4, 16, 1}),
                       ({"NQ_FUSE_MAX_MB": "0", "NQ_SCHEDULE_FULL": "1"}, {33, 34})):
         for k in ("NQ_FUSE_MAX_MB", "NQ_SCHEDULE_FULL", "NQ_NO_SELFQ"):
-            monkeypatch.delenv(k, raising=False)
+            nqopt.unset(k)
         for k, v in env.items():
-            monkeypatch.setenv(k, v)
+            nqopt.set(k, v)
         ys = [torch.full((1, s[0]), float("nan"), dtype=torch.float32, device="cuda") for s in shapes]
         plan = nq.nq_plan_create(hs, xs, ys, 1)
         assert set(nq.nq_plan_schedules(plan)) <= want, (env, nq.nq_plan_schedules(plan))

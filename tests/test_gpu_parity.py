@@ -378,15 +378,15 @@ def test_forward_many_and_plan_match_oracle():
             L.close()
 
 
-def test_shared_input_schedule_batches_4_to_8(monkeypatch):
+def test_shared_input_schedule_batches_4_to_8(nqopt):
     """Large launches at batch 4..8 run the kernel in which the waves of a workgroup share an op's
     quantised input through LDS (one column group at batch 4 and 5, two from 6 on);
     NQ_SCHEDULE_FULL=1 makes these small launches take that schedule.
     Shapes cover: reductions of 4 steps only, an odd number of half passes (68, 20 steps), items
     of more and fewer than eight row blocks, several row blocks per wave, ragged rows."""
     import torch
-    monkeypatch.setenv("NQ_SCHEDULE_FULL", "1")
-    monkeypatch.setenv("NQ_SHARE_STEPS", "1")
+    nqopt.set("schedule_full", "1")
+    nqopt.set("share_steps", "1")
     shapes = [(300, 200, 100), (129, 65, 33), (512, 1024, 256), (64, 4100, 70), (1, 1, 1),
               (2200, 1536, 1100), (4096, 512, 1024), (1500, 3072, 2300)]
     layers = [Layer(*s, "bf16", seed=300 + i) for i, s in enumerate(shapes)]
@@ -410,7 +410,7 @@ def test_shared_input_schedule_batches_4_to_8(monkeypatch):
 
 
 @pytest.mark.parametrize("y_dtype", ["bf16", "f16"])
-def test_sixteen_bit_outputs_every_path(y_dtype, monkeypatch):
+def test_sixteen_bit_outputs_every_path(y_dtype, nqopt):
     """y as bf16 / fp16 (the fp32 result rounded once more) through every kernel that stores y:
     split and stream kernels (single call and plan), the shared-input kernel, chunked mid batches,
     the plain VALU kernels, and the dense path (both its direct and its split-reduction epilogue)."""
@@ -444,8 +444,8 @@ def test_sixteen_bit_outputs_every_path(y_dtype, monkeypatch):
     hs = [l.h for l in layers]
     for forced in (False, True):
         if forced:
-            monkeypatch.setenv("NQ_SCHEDULE_FULL", "1")
-            monkeypatch.setenv("NQ_SHARE_STEPS", "1")
+            nqopt.set("schedule_full", "1")
+            nqopt.set("share_steps", "1")
         for batch in (1, 4, 8):
             xs_np = [synth.gen_x(batch, s[1], 560 + i, "bf16") for i, s in enumerate(shapes)]
             xs = [to_device(x, "bf16") for x in xs_np]
@@ -483,7 +483,7 @@ def test_sixteen_bit_outputs_are_the_rounded_exact_result():
         L.close()
 
 
-def test_single_call_and_plan_give_identical_bits(monkeypatch):
+def test_single_call_and_plan_give_identical_bits(nqopt):
     """At batch 1 a lone layer (nq_binlr_forward) and a plan whose launches are short run two
     launches that quantise their input themselves: by the waves of the one- or four-wave kernel
     for reductions of up to 4096 elements, by the 16-wave kernel up to 16384 (NQ_NO_SELFQ=1 sends
@@ -501,9 +501,9 @@ def test_single_call_and_plan_give_identical_bits(monkeypatch):
             first = None
             for env in modes:
                 for k in ("NQ_NO_SELFQ", "NQ_FUSE_MAX_MB", "NQ_NO_FUSE"):
-                    monkeypatch.delenv(k, raising=False)
+                    nqopt.unset(k)
                 for k, v in env.items():
-                    monkeypatch.setenv(k, v)
+                    nqopt.set(k, v)
                 y_single = L.forward(x_np)
                 t_single = nq.nq_binlr_read_intermediate(L.h, shape[2], batch)
                 y = new_output(batch, shape[0])
@@ -528,7 +528,7 @@ def test_single_call_and_plan_give_identical_bits(monkeypatch):
         L.close()
 
 
-def test_layers_that_share_one_input(monkeypatch):
+def test_layers_that_share_one_input(nqopt):
     """The projections of a decoder block that read the same activations (q, k, v; gate, up) go
     into one forward_many call with the same x pointer: every layer scales and quantises the
     shared input with its own s_in.  Checked against the oracle layer by layer, at batch 1 (short
@@ -543,9 +543,9 @@ def test_layers_that_share_one_input(monkeypatch):
     for batch in (1, 3, 8):
         for fuse_max_mb in ((None, "0") if batch == 1 else (None,)):
             if fuse_max_mb is None:
-                monkeypatch.delenv("NQ_FUSE_MAX_MB", raising=False)
+                nqopt.unset("fuse_max_mb")
             else:
-                monkeypatch.setenv("NQ_FUSE_MAX_MB", fuse_max_mb)
+                nqopt.set("fuse_max_mb", fuse_max_mb)
             x_np = synth.gen_x(batch, d, 960 + batch, "bf16")
             x = to_device(x_np, "bf16")
             ys = [torch.full((batch, s[0]), float("nan"), dtype=torch.float32, device="cuda") for s in shapes]
@@ -565,7 +565,7 @@ def test_layers_that_share_one_input(monkeypatch):
         L.close()
 
 
-def test_self_quantising_schedules_at_batch_1(monkeypatch):
+def test_self_quantising_schedules_at_batch_1(nqopt):
     """In launches that fill the chip the batch-1 stage kernels quantise their own share of the
     input (no quantisation launch) when a wave's share of every reduction is at most 16 steps.
     NQ_SCHEDULE_FULL=1 makes these small lists count as filling the chip.  First list: inputs of
@@ -588,19 +588,19 @@ def test_self_quantising_schedules_at_batch_1(monkeypatch):
         hs = [L.h for L in layers]
         outs = {}
         for mode in ("selfq", "four_launches"):
-            monkeypatch.setenv("NQ_SCHEDULE_FULL", "1")
-            monkeypatch.setenv("NQ_FUSE_MAX_MB", "0")
+            nqopt.set("schedule_full", "1")
+            nqopt.set("fuse_max_mb", "0")
             if split_steps:
                 # (short and unequal shares take four self-quantising waves only when asked to)
-                monkeypatch.setenv("NQ_SPLIT_STEPS", split_steps)
-                monkeypatch.setenv("NQ_SELFQ4_MIN_STEPS", "1")
+                nqopt.set("split_steps", split_steps)
+                nqopt.set("selfq4_min_steps", "1")
             else:
-                monkeypatch.delenv("NQ_SPLIT_STEPS", raising=False)
-                monkeypatch.delenv("NQ_SELFQ4_MIN_STEPS", raising=False)
+                nqopt.unset("split_steps")
+                nqopt.unset("selfq4_min_steps")
             if mode == "four_launches":
-                monkeypatch.setenv("NQ_NO_SELFQ", "1")
+                nqopt.set("no_selfq", "1")
             else:
-                monkeypatch.delenv("NQ_NO_SELFQ", raising=False)
+                nqopt.unset("no_selfq")
             ys = [torch.full((1, s[0]), float("nan"), dtype=torch.float32, device="cuda") for s in shapes]
             plan = nq.nq_plan_create(hs, xs, ys, 1)
             nq.nq_plan_forward(plan)
@@ -620,11 +620,11 @@ def test_self_quantising_schedules_at_batch_1(monkeypatch):
         for L in layers:
             L.close()
     # a token with a non-finite value: every output NaN, nothing else disturbed
-    monkeypatch.setenv("NQ_SCHEDULE_FULL", "1")
-    monkeypatch.setenv("NQ_FUSE_MAX_MB", "0")
-    monkeypatch.delenv("NQ_NO_SELFQ", raising=False)
-    monkeypatch.delenv("NQ_SPLIT_STEPS", raising=False)
-    monkeypatch.delenv("NQ_SELFQ4_MIN_STEPS", raising=False)
+    nqopt.set("schedule_full", "1")
+    nqopt.set("fuse_max_mb", "0")
+    nqopt.unset("no_selfq")
+    nqopt.unset("split_steps")
+    nqopt.unset("selfq4_min_steps")
     L = Layer(300, 4090, 1000, "f32", seed=1250)
     x_np = synth.gen_x(1, 4090, 1350, "f32")
     x_np[0, 77] = np.inf
@@ -692,7 +692,7 @@ def test_forward_many_keeps_several_lists_compiled():
         L.close()
 
 
-def test_plans_replay_correctly_from_a_hip_graph(monkeypatch):
+def test_plans_replay_correctly_from_a_hip_graph(nqopt):
     """Launch-bound sequences of plans are meant to be captured into HIP graphs.  Every schedule is
     captured (a short fused list, a chip-filling self-quantising list, a four-launch list at batch 3,
     the two-column-group kernels at batch 8) and the graph is replayed several times with new inputs
@@ -702,9 +702,9 @@ def test_plans_replay_correctly_from_a_hip_graph(monkeypatch):
     cases = [({}, 1), ({"NQ_FUSE_MAX_MB": "0", "NQ_SCHEDULE_FULL": "1"}, 1), ({}, 3), ({"NQ_SCHEDULE_FULL": "1"}, 8)]
     for env, batch in cases:
         for k in ("NQ_FUSE_MAX_MB", "NQ_SCHEDULE_FULL"):
-            monkeypatch.delenv(k, raising=False)
+            nqopt.unset(k)
         for k, v in env.items():
-            monkeypatch.setenv(k, v)
+            nqopt.set(k, v)
         layers = [Layer(*s, "bf16", seed=3100 + i) for i, s in enumerate(shapes)]
         xs = [torch.zeros((batch, s[1]), dtype=torch.bfloat16, device="cuda") for s in shapes]
         ys = [torch.zeros((batch, s[0]), dtype=torch.float32, device="cuda") for s in shapes]
@@ -738,13 +738,13 @@ def test_plans_replay_correctly_from_a_hip_graph(monkeypatch):
             L.close()
 
 
-def test_resident_input_schedule_batches_6_to_8(monkeypatch):
+def test_resident_input_schedule_batches_6_to_8(nqopt):
     """Batch 6..8 with reductions of at most 16 steps in launches that fill the chip: the eight waves
     of a workgroup stage the op's whole quantised input in LDS once and stream their row blocks
     without further barriers.  Reductions of 4, 8, 12 and 16 steps (one or two chunks, with and
     without the closing half pass), items of more and fewer than eight row blocks, ragged rows."""
     import torch
-    monkeypatch.setenv("NQ_SCHEDULE_FULL", "1")
+    nqopt.set("schedule_full", "1")
     shapes = [(4096, 1024, 1024), (300, 200, 100), (129, 700, 513), (1000, 520, 260), (2100, 1000, 700)]
     layers = [Layer(*s, "bf16", seed=5000 + i) for i, s in enumerate(shapes)]
     for batch in (6, 7, 8):
@@ -763,7 +763,7 @@ def test_resident_input_schedule_batches_6_to_8(monkeypatch):
         L.close()
 
 
-def test_wave_per_vector_quantiser_matches_workgroup_quantiser(monkeypatch):
+def test_wave_per_vector_quantiser_matches_workgroup_quantiser(nqopt):
     """Launches of many short vectors (at most 1024 elements each, 64 or more (vector, token)
     pairs) quantise with one wave per pair instead of one workgroup; NQ_NO_QUANT_WAVE=1 keeps the
     workgroup kernel.  Same arithmetic: the outputs must be identical bit for bit, with ragged
@@ -781,9 +781,9 @@ def test_wave_per_vector_quantiser_matches_workgroup_quantiser(monkeypatch):
             outs = {}
             for mode in ("wave", "workgroup"):
                 if mode == "workgroup":
-                    monkeypatch.setenv("NQ_NO_QUANT_WAVE", "1")
+                    nqopt.set("no_quant_wave", "1")
                 else:
-                    monkeypatch.delenv("NQ_NO_QUANT_WAVE", raising=False)
+                    nqopt.unset("no_quant_wave")
                 ys = [new_output(batch, s[0]) for s in shapes]
                 plan = nq.nq_plan_create(hs, xs, ys, batch)
                 nq.nq_plan_forward(plan)

@@ -4,7 +4,7 @@ import pytest
 
 from paper_2602_06694_amd import binding as nq
 from paper_2602_06694_amd import synth
-from gpu_util import BAR, Layer, rel_err
+from gpu_util import BAR, Layer, rel_err, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -29,21 +29,21 @@ def test_prefill_small_shapes(shape, x_dtype):
 
 @pytest.mark.parametrize("tg,splits,ks", [("2", None, None), ("2", "3", None), ("2", "16", None), (None, "5", None),
                                           (None, "1", "2"), (None, "2", "2")])
-def test_prefill_32_token_tiles_and_forced_splits(monkeypatch, tg, splits, ks):
+def test_prefill_32_token_tiles_and_forced_splits(nqopt, tg, splits, ks):
     # the tiling of the two GEMMs is chosen by a cost model; force the variants it rarely picks on
     # small inputs: 32-token workgroup tiles, with and without a split reduction, 64-token tiles
     # with one, more splits than the reduction has groups of four steps (empty splits), and
     # eight-wave workgroups that halve their part of the reduction through LDS (taken where the
     # reduction is a whole number of groups of eight steps: the second and third shape)
     if ks:
-        monkeypatch.setenv("NQ_PF_KS1", ks)
-        monkeypatch.setenv("NQ_PF_KS2", ks)
+        nqopt.set("pf_ks1", ks)
+        nqopt.set("pf_ks2", ks)
     if tg:
-        monkeypatch.setenv("NQ_PF_TG1", tg)
-        monkeypatch.setenv("NQ_PF_TG2", tg)
+        nqopt.set("pf_tg1", tg)
+        nqopt.set("pf_tg2", tg)
     if splits:
-        monkeypatch.setenv("NQ_PF_SPLITS1", splits)
-        monkeypatch.setenv("NQ_PF_SPLITS2", splits)
+        nqopt.set("pf_splits1", splits)
+        nqopt.set("pf_splits2", splits)
     for shape in [(300, 200, 100), (640, 1500, 257), (1024, 2048, 1024)]:
         L = Layer(*shape, "bf16", seed=61)
         for batch in (9, 64, 100, 200):
@@ -131,7 +131,7 @@ def test_prefill_activations_with_a_large_mean_and_uniform_sign_columns():
     L.close()
 
 
-def test_prefill_eight_wave_workgroups_by_default(monkeypatch):
+def test_prefill_eight_wave_workgroups_by_default(nqopt):
     """A first GEMM with a long reduction whose 64-token tiles number no more than the CUs, but too many
     for 32-token tiles to take over (here 7 x 20 tiles of 64 steps) runs eight-wave workgroups that halve the reduction through LDS; NQ_PF_KS1=1
     switches that off.  Both against the oracle on sampled tokens (first, last, tile edges, random),
@@ -145,13 +145,52 @@ def test_prefill_eight_wave_workgroups_by_default(monkeypatch):
     outs = {}
     for ks in (None, "1"):
         if ks:
-            monkeypatch.setenv("NQ_PF_KS1", ks)
+            nqopt.set("pf_ks1", ks)
         else:
-            monkeypatch.delenv("NQ_PF_KS1", raising=False)
+            nqopt.unset("pf_ks1")
         y = L.forward(x)
         outs[ks] = y
         for k, b in enumerate(idx):
             assert np.abs(y[b] - ref[k]).max() <= PREFILL_TOL * np.abs(ref[k]).max(), (ks, int(b))
     assert not np.array_equal(outs[None], outs["1"])       # different summation orders: the two paths did run
     assert rel_err(outs[None], outs["1"]) <= PREFILL_TOL
+    L.close()
+
+
+def test_reserve_covers_every_batch_up_to_the_reserved_one():
+    """The dense path's workspace need is not monotone in the batch (small batches split the reduction
+    and keep partial sums).  After nq_binlr_reserve(h, 2048) a forward at ANY batch <= 2048 must leave
+    the workspace as it is (no reallocation, hence no synchronisation on the stream)."""
+    import torch
+    for shape in [(2048, 7168, 880), (7168, 2048, 880)]:     # the 70B MLP shapes at a quarter of their size
+        L = Layer(*shape, "bf16", seed=5200)
+        nq.nq_binlr_reserve(L.h, 2048)
+        b0, bytes0 = nq.nq_binlr_reserved(L.h)
+        assert b0 == 2048 and bytes0 > 0
+        x = torch.zeros((2048, shape[1]), dtype=torch.bfloat16, device="cuda")
+        y = torch.empty((2048, shape[0]), dtype=torch.float32, device="cuda")
+        for batch in (9, 64, 65, 449, 833, 1473, 1793, 2048):
+            nq.nq_binlr_forward(L.h, x, y, batch)
+            assert nq.nq_binlr_reserved(L.h) == (b0, bytes0), batch
+        torch.cuda.synchronize()
+        L.close()
+
+
+def test_exact_path_above_batch_8_on_request():
+    """nq_binlr_forward_exact: any batch through the streaming kernels (their accuracy), bit-identical to
+    passes of 8 through nq_binlr_forward."""
+    import torch
+    d_out, d_in, r, batch = 384, 1000, 200, 21
+    L = Layer(d_out, d_in, r, "bf16", seed=5300)
+    x_np = synth.gen_x(batch, d_in, 5301, "bf16")
+    x = to_device(x_np, "bf16")
+    y = torch.full((batch, d_out), float("nan"), dtype=torch.float32, device="cuda")
+    nq.nq_binlr_forward_exact(L.h, x, y, batch)
+    parts = torch.full((batch, d_out), float("nan"), dtype=torch.float32, device="cuda")
+    for b0 in range(0, batch, 8):
+        nb = min(8, batch - b0)
+        nq.nq_binlr_forward(L.h, x[b0:b0 + nb], parts[b0:b0 + nb], nb)
+    torch.cuda.synchronize()
+    assert torch.equal(y, parts)
+    assert rel_err(y.cpu().numpy(), L.oracle(x_np)) <= 1e-5
     L.close()

@@ -420,10 +420,35 @@ def test_mid_scale_brute_force_exact_integers():
 
 
 def test_mid_scale_storage_formula():
-    """r(n+m) + 16(n+r+m) bits (Appendix F.4): 16 r more than the two-scale layer."""
-    for d_out, d_in, r in [(4096, 4096, 1024), (11008, 4096, 1664), (1, 1, 1)]:
-        assert oracle.layer_bits_mid(d_out, d_in, r) == oracle.layer_bits(d_out, d_in, r) + 16 * r
-        assert oracle.layer_bits_mid(d_out, d_in, r) == r * (d_out + d_in) + 16 * (d_out + r + d_in)
+    """Storage of the three-scale layer (Appendix F.4: r(n+m) + 16(n+r+m) bits), pinned three ways that
+    do not retype the oracle's expression: totals worked by hand, a layer counted bit by bit from the
+    arrays that would be stored, and the size the paper prints for a 1.00-bit model in this format."""
+    # worked by hand: 1024 * 8192 = 8388608 sign bits, 16 * 9216 = 147456 scale bits; 1664 * 15104 = 25133056, 16 * 16768 = 268288
+    assert oracle.layer_bits_mid(4096, 4096, 1024) == 8536064
+    assert oracle.layer_bits_mid(11008, 4096, 1664) == 25401344
+    assert oracle.layer_bits_mid(1, 1, 1) == 50                      # 2 sign bits + three fp16 scales
+    # the operands are not interchangeable: a swapped or dropped term changes one of these
+    assert oracle.layer_bits_mid(3, 5, 7) == 7 * 8 + 16 * 15 == 296
+    assert oracle.layer_bits_mid(5, 7, 3) == 3 * 12 + 16 * 15 == 276
+    assert oracle.layer_bits_mid(7, 3, 5) == 5 * 10 + 16 * 15 == 290
+    # counted from the arrays a layer of this format stores: one bit per sign, 16 per fp16 scale
+    for d_out, d_in, r in [(6, 9, 4), (33, 17, 40), (128, 64, 65)]:
+        U = np.ones((d_out, r), np.int8)
+        V = np.ones((d_in, r), np.int8)
+        scales = [np.ones(d_out, np.float16), np.ones(r, np.float16), np.ones(d_in, np.float16)]
+        counted = U.size + V.size + sum(8 * a.nbytes for a in scales)
+        assert oracle.layer_bits_mid(d_out, d_in, r) == counted
+        assert oracle.layer_bits_mid(d_out, d_in, r) - oracle.layer_bits(d_out, d_in, r) == 8 * scales[1].nbytes
+    # Table 1 prints 1.33 GB for Llama-2-7B at 1.00 bit in this format (the DBF row): the largest rank
+    # with at most one bit per weight in every layer, plus the 16-bit embedding and output head
+    g = _golden()
+    bits = 0
+    for s in synth.llama2_7b_block():
+        r = (s.d_out * s.d_in - 16 * (s.d_out + s.d_in)) // (s.d_out + s.d_in + 16)
+        assert oracle.layer_bits_mid(s.d_out, s.d_in, r) <= s.d_out * s.d_in < oracle.layer_bits_mid(s.d_out, s.d_in, r + 1)
+        bits += 32 * oracle.layer_bits_mid(s.d_out, s.d_in, r)
+    v, tol = g["llama2_7b_1bit_three_scale_gb"]
+    assert abs((bits / 8 + 2 * 32000 * 4096 * 2) / 1e9 - v) <= tol
 
 
 # ---------- gradients of the scale vectors (signs frozen: Section 3.4; Algorithm 1, Phase 3) ----------

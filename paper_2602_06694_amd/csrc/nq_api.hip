@@ -127,6 +127,41 @@ static void slab_release(Slab* s)
 }
 
 // ---------------------------------------------------------------------------------------------
+// What the streaming kernels of one layer need beyond its inputs and outputs: the fixed-point copies
+// of x' and t, their per-token constants, and the intermediate t.
+struct DecodeWorkspace {
+    uint8_t* bq_x;
+    uint8_t* bq_t;
+    QMeta* meta_x;
+    QMeta* meta_t;
+    float* t;             // [batch][t_stride]
+    int t_stride;
+};
+
+// Carves a DecodeWorkspace for `batch` tokens of a (d_in, r) layer out of `base` (256-byte aligned);
+// returns the bytes it takes (base == nullptr: only the size).
+static size_t carve_workspace(DecodeWorkspace* w, char* base, int64_t d_in, int64_t r, int batch)
+{
+    auto al = [](size_t v) { return (v + 255) / 256 * 256; };
+    // (+1 KiB: the shared-input kernel stages whole chunks of 8 steps and may read up to 4 steps
+    // past the last token's data; what it reads there meets 0 bits only and is never used)
+    const size_t bqx_bytes = al((size_t)batch * n_steps(d_in) * 4 * kSlices * 16 + 1024);
+    const size_t bqt_bytes = al((size_t)batch * n_steps(r) * 4 * kSlices * 16 + 1024);
+    const size_t meta_bytes = al(sizeof(QMeta) * batch);
+    const int t_stride = (int)round_up(r, kTileRows);
+    const size_t t_bytes = al((size_t)batch * t_stride * 4);
+    if (w) {
+        char* q = base;
+        w->bq_x = (uint8_t*)q; q += bqx_bytes;
+        w->bq_t = (uint8_t*)q; q += bqt_bytes;
+        w->meta_x = (QMeta*)q; q += meta_bytes;
+        w->meta_t = (QMeta*)q; q += meta_bytes;
+        w->t = (float*)q;
+        w->t_stride = t_stride;
+    }
+    return bqx_bytes + bqt_bytes + 2 * meta_bytes + t_bytes;
+}
+
 struct nq_binlr_s {
     int64_t d_out, d_in, r;
     int x_dtype, y_dtype;
@@ -144,12 +179,7 @@ struct nq_binlr_s {
     // decode workspace (one allocation, sized for NQ_DECODE_MAX_BATCH, never reallocated)
     void* ws_alloc;
     Slab* ws_slab;
-    uint8_t* bq_x;
-    uint8_t* bq_t;
-    QMeta* meta_x;
-    QMeta* meta_t;
-    float* t;             // [8][t_stride]
-    int t_stride;
+    DecodeWorkspace ws;
     // prefill workspace (grown by reserve)
     void* pf_alloc;
     size_t pf_bytes;
@@ -351,15 +381,7 @@ static int create_layer(nq_handle* out, int64_t d_out, int64_t d_in, int64_t r, 
     const size_t w_total = vt_bytes + u_bytes + sin_bytes + sout_bytes;
 
     // decode workspace
-    const int mb = NQ_DECODE_MAX_BATCH;
-    // (+1 KiB: the shared-input kernel stages whole chunks of 8 steps and may read up to 4 steps
-    // past the last token's data; what it reads there is never used)
-    const size_t bqx_bytes = align_up((size_t)mb * n_steps(d_in) * 4 * kSlices * 16 + 1024, 256);
-    const size_t bqt_bytes = align_up((size_t)mb * n_steps(r) * 4 * kSlices * 16 + 1024, 256);
-    const size_t meta_bytes = align_up(sizeof(QMeta) * mb, 256);
-    h->t_stride = (int)round_up(r, kTileRows);
-    const size_t t_bytes = align_up((size_t)mb * h->t_stride * 4, 256);
-    const size_t ws_total = bqx_bytes + bqt_bytes + 2 * meta_bytes + t_bytes;
+    const size_t ws_total = carve_workspace(nullptr, nullptr, d_in, r, NQ_DECODE_MAX_BATCH);
 
     uint32_t* d_canon = nullptr;
     const size_t canon_u = (size_t)d_out * wpr * 4, canon_v = (size_t)d_in * wpr * 4;
@@ -381,12 +403,7 @@ static int create_layer(nq_handle* out, int64_t d_out, int64_t d_in, int64_t r, 
         h->u_tiles = (uint32_t*)p; p += u_bytes;
         h->s_in = (uint16_t*)p; p += sin_bytes;
         h->s_out = (uint16_t*)p;
-        char* q = (char*)h->ws_alloc;
-        h->bq_x = (uint8_t*)q; q += bqx_bytes;
-        h->bq_t = (uint8_t*)q; q += bqt_bytes;
-        h->meta_x = (QMeta*)q; q += meta_bytes;
-        h->meta_t = (QMeta*)q; q += meta_bytes;
-        h->t = (float*)q;
+        (void)carve_workspace(&h->ws, (char*)h->ws_alloc, d_in, r, NQ_DECODE_MAX_BATCH);
     }
     CREATE_HIP(hipMemset(h->ws_alloc, 0, ws_total));
     CREATE_HIP(hipMemcpy(d_canon, V_words, canon_v, kind));
@@ -537,31 +554,31 @@ extern "C" int nq_binlr_reserved(nq_handle h, int* max_batch, size_t* workspace_
     return NQ_OK;
 }
 
-static QuantDesc make_qx(nq_handle h, const void* x)
+static QuantDesc make_qx(nq_handle h, const DecodeWorkspace& w, const void* x)
 {
     QuantDesc q;
-    q.x = x; q.scale = h->s_in; q.bq = h->bq_x; q.meta = h->meta_x;
+    q.x = x; q.scale = h->s_in; q.bq = w.bq_x; q.meta = w.meta_x;
     q.N = (int)h->d_in; q.n_chunks = (int)n_steps(h->d_in) * 4; q.x_stride = (int)h->d_in; q.dtype = h->x_dtype;
     return q;
 }
-static StageDesc make_s1(nq_handle h)
+static StageDesc make_s1(nq_handle h, const DecodeWorkspace& w)
 {
     StageDesc s;
-    s.tiles = h->vt_tiles; s.bq = h->bq_x; s.meta = h->meta_x; s.out_scale = nullptr; s.out = h->t;
-    s.M = (int)h->r; s.n_steps = (int)n_steps(h->d_in); s.out_stride = h->t_stride; s.out_dtype = NQ_F32;
+    s.tiles = h->vt_tiles; s.bq = w.bq_x; s.meta = w.meta_x; s.out_scale = nullptr; s.out = w.t;
+    s.M = (int)h->r; s.n_steps = (int)n_steps(h->d_in); s.out_stride = w.t_stride; s.out_dtype = NQ_F32;
     return s;
 }
-static QuantDesc make_qt(nq_handle h)
+static QuantDesc make_qt(nq_handle h, const DecodeWorkspace& w)
 {
     QuantDesc q;
-    q.x = h->t; q.scale = h->s_mid; q.bq = h->bq_t; q.meta = h->meta_t;
-    q.N = (int)h->r; q.n_chunks = (int)n_steps(h->r) * 4; q.x_stride = h->t_stride; q.dtype = NQ_F32;
+    q.x = w.t; q.scale = h->s_mid; q.bq = w.bq_t; q.meta = w.meta_t;
+    q.N = (int)h->r; q.n_chunks = (int)n_steps(h->r) * 4; q.x_stride = w.t_stride; q.dtype = NQ_F32;
     return q;
 }
-static StageDesc make_s2(nq_handle h, void* y)
+static StageDesc make_s2(nq_handle h, const DecodeWorkspace& w, void* y)
 {
     StageDesc s;
-    s.tiles = h->u_tiles; s.bq = h->bq_t; s.meta = h->meta_t; s.out_scale = h->s_out; s.out = y;
+    s.tiles = h->u_tiles; s.bq = w.bq_t; s.meta = w.meta_t; s.out_scale = h->s_out; s.out = y;
     s.M = (int)h->d_out; s.n_steps = (int)n_steps(h->r); s.out_stride = (int)h->d_out; s.out_dtype = h->y_dtype;
     return s;
 }
@@ -579,20 +596,22 @@ static int rbs_per_stream_item(int n_rb, int nst, int total_rb, int batch)
 }
 
 // one pass of the streaming path for batch <= 8; `unscaled`: without the output scale (z = U t)
-static int decode_once(nq_handle h, const void* x, void* y, int batch, hipStream_t s, bool unscaled = false)
+// (`w`: the workspace the kernels use -- the layer's own, or one carved out of the static scratch array)
+static int decode_once(nq_handle h, const DecodeWorkspace& w, const void* x, void* y, int batch, hipStream_t s,
+                       bool unscaled = false)
 {
     int rc;
     if (h->flags & NQ_FLAG_DECODE_VALU) {
-        rc = launch_valu_gemv(h->vt_tiles, x, h->x_dtype, (int)h->d_in, h->s_in, nullptr, h->t, NQ_F32, h->t_stride,
+        rc = launch_valu_gemv(h->vt_tiles, x, h->x_dtype, (int)h->d_in, h->s_in, nullptr, w.t, NQ_F32, w.t_stride,
                               h->r, h->d_in, batch, s);
         if (rc != NQ_OK) return rc;
-        return launch_valu_gemv(h->u_tiles, h->t, NQ_F32, h->t_stride, h->s_mid, unscaled ? nullptr : h->s_out, y, h->y_dtype,
+        return launch_valu_gemv(h->u_tiles, w.t, NQ_F32, w.t_stride, h->s_mid, unscaled ? nullptr : h->s_out, y, h->y_dtype,
                                 (int)h->d_out, h->d_out, h->r, batch, s);
     }
-    QuantDesc qx = make_qx(h, x);
-    StageDesc s1 = make_s1(h);
-    QuantDesc qt = make_qt(h);
-    StageDesc s2 = make_s2(h, y);
+    QuantDesc qx = make_qx(h, w, x);
+    StageDesc s1 = make_s1(h, w);
+    QuantDesc qt = make_qt(h, w);
+    StageDesc s2 = make_s2(h, w, y);
     if (unscaled) s2.out_scale = nullptr;
     const int rb1 = (int)n_rowblocks(h->r), rb2 = (int)n_rowblocks(h->d_out);
     const int w1 = stage_schedule(rb1, s1.n_steps, batch), w2 = stage_schedule(rb2, s2.n_steps, batch);
@@ -638,7 +657,7 @@ extern "C" int nq_binlr_forward(nq_handle h, const void* x, void* y, int batch, 
     int rc = check_xy("nq_binlr_forward", x, y, (size_t)batch * h->d_in * xs, (size_t)batch * h->d_out * ys);
     if (rc != NQ_OK) return rc;
     hipStream_t s = (hipStream_t)stream;
-    if (batch <= NQ_DECODE_MAX_BATCH) return decode_once(h, x, y, batch, s);
+    if (batch <= NQ_DECODE_MAX_BATCH) return decode_once(h, h->ws, x, y, batch, s);
     if (batch >= NQ_PREFILL_MIN_BATCH && !(h->flags & (NQ_FLAG_NO_PREFILL | NQ_FLAG_DECODE_VALU))) {
         if ((rc = ensure_prefill_workspace(h, batch)) != NQ_OK) return rc;
         PrefillArgs a;
@@ -651,7 +670,7 @@ extern "C" int nq_binlr_forward(nq_handle h, const void* x, void* y, int batch, 
     // larger batches without the dense path: chunks of 8 through the streaming path (each chunk re-reads the bits)
     for (int b0 = 0; b0 < batch; b0 += NQ_DECODE_MAX_BATCH) {
         int nb = std::min(NQ_DECODE_MAX_BATCH, batch - b0);
-        rc = decode_once(h, (const char*)x + (size_t)b0 * h->d_in * xs, (char*)y + (size_t)b0 * h->d_out * ys, nb, s);
+        rc = decode_once(h, h->ws, (const char*)x + (size_t)b0 * h->d_in * xs, (char*)y + (size_t)b0 * h->d_out * ys, nb, s);
         if (rc != NQ_OK) return rc;
     }
     return NQ_OK;
@@ -685,7 +704,7 @@ extern "C" int nq_binlr_read_intermediate(nq_handle h, float* t_host, int batch)
     if (!h || !t_host) return fail(NQ_E_NULL, "nq_binlr_read_intermediate: NULL pointer");
     if (batch < 1 || batch > NQ_DECODE_MAX_BATCH) return fail(NQ_E_INVALID_ARG, "nq_binlr_read_intermediate: batch must be 1..8");
     NQ_HIP(hipDeviceSynchronize());
-    NQ_HIP(hipMemcpy2D(t_host, (size_t)h->r * 4, h->t, (size_t)h->t_stride * 4, (size_t)h->r * 4, batch,
+    NQ_HIP(hipMemcpy2D(t_host, (size_t)h->r * 4, h->ws.t, (size_t)h->ws.t_stride * 4, (size_t)h->r * 4, batch,
                        hipMemcpyDeviceToHost));
     return NQ_OK;
 }
@@ -737,10 +756,10 @@ extern "C" int nq_plan_create(nq_plan* out, const nq_handle* hs, const void* con
     std::vector<QuantDesc> qx(n), qt(n);
     std::vector<StageDesc> s1(n), s2(n);
     for (int i = 0; i < n; ++i) {
-        qx[i] = make_qx(hs[i], xs[i]);
-        s1[i] = make_s1(hs[i]);
-        qt[i] = make_qt(hs[i]);
-        s2[i] = make_s2(hs[i], ys[i]);
+        qx[i] = make_qx(hs[i], hs[i]->ws, xs[i]);
+        s1[i] = make_s1(hs[i], hs[i]->ws);
+        qt[i] = make_qt(hs[i], hs[i]->ws);
+        s2[i] = make_s2(hs[i], hs[i]->ws, ys[i]);
     }
     // one work list per stage launch; its shape follows the schedule the launch will use
     int sched[2], max_steps_of[2] = {0, 0};
@@ -975,7 +994,7 @@ static int forward_in_passes(const char* who, nq_handle h, const void* x, void* 
     if (rc != NQ_OK) return rc;
     for (int b0 = 0; b0 < batch; b0 += NQ_DECODE_MAX_BATCH) {
         const int nb = std::min(NQ_DECODE_MAX_BATCH, batch - b0);
-        rc = decode_once(h, (const char*)x + (size_t)b0 * h->d_in * xs, (char*)y + (size_t)b0 * h->d_out * ys, nb,
+        rc = decode_once(h, h->ws, (const char*)x + (size_t)b0 * h->d_in * xs, (char*)y + (size_t)b0 * h->d_out * ys, nb,
                          (hipStream_t)stream, unscaled);
         if (rc != NQ_OK) return rc;
     }

@@ -35,7 +35,7 @@ def is_stale() -> bool:
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    deps = sources() + [os.path.join(CSRC, "nq_internal.h"), os.path.join(ROOT, "include", "nq_binlr.h")]
+    deps = sources() + [os.path.join(CSRC, "nq_internal.h"), os.path.join(CSRC, "nq_device.h"), os.path.join(ROOT, "include", "nq_binlr.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 

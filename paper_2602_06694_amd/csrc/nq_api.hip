@@ -127,17 +127,6 @@ static void slab_release(Slab* s)
 }
 
 // ---------------------------------------------------------------------------------------------
-// What the streaming kernels of one layer need beyond its inputs and outputs: the fixed-point copies
-// of x' and t, their per-token constants, and the intermediate t.
-struct DecodeWorkspace {
-    uint8_t* bq_x;
-    uint8_t* bq_t;
-    QMeta* meta_x;
-    QMeta* meta_t;
-    float* t;             // [batch][t_stride]
-    int t_stride;
-};
-
 // Carves a DecodeWorkspace for `batch` tokens of a (d_in, r) layer out of `base` (256-byte aligned);
 // returns the bytes it takes (base == nullptr: only the size).
 static size_t carve_workspace(DecodeWorkspace* w, char* base, int64_t d_in, int64_t r, int batch)
@@ -161,30 +150,6 @@ static size_t carve_workspace(DecodeWorkspace* w, char* base, int64_t d_in, int6
     }
     return bqx_bytes + bqt_bytes + 2 * meta_bytes + t_bytes;
 }
-
-struct nq_binlr_s {
-    int64_t d_out, d_in, r;
-    int x_dtype, y_dtype;
-    uint32_t flags;
-    int device;
-    // weights (one allocation)
-    void* w_alloc;
-    Slab* w_slab;
-    uint32_t* vt_tiles;   // A = V^T : M = r,     N = d_in
-    uint32_t* u_tiles;    // A = U   : M = d_out, N = r
-    uint16_t* s_in;
-    uint16_t* s_out;
-    uint16_t* s_mid;      // rank-wise scale of the three-scale variant, fp16 [r padded to 128], or nullptr
-    int mid_exp;          // ceil(log2(max |s_mid|)): keeps the dense path's fp16 intermediate in range
-    // decode workspace (one allocation, sized for NQ_DECODE_MAX_BATCH, never reallocated)
-    void* ws_alloc;
-    Slab* ws_slab;
-    DecodeWorkspace ws;
-    // prefill workspace (grown by reserve)
-    void* pf_alloc;
-    size_t pf_bytes;
-    int pf_batch;
-};
 
 struct nq_plan_s {
     int n, batch, device;

@@ -157,6 +157,21 @@ int nq_binlr_reserved(nq_handle h, int* max_batch, size_t* workspace_bytes);
  * (fp16 operands, fp32 accumulation), unless the layer was created with NQ_FLAG_NO_PREFILL. */
 int nq_binlr_forward(nq_handle h, const void* x, void* y, int batch, void* stream);
 
+/* nq_binlr_forward for callers that cannot allocate device memory or rely on a workspace the
+ * library allocated for them: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same kernels and bit-identical results for batch <=
+ * NQ_DECODE_MAX_BATCH (larger batches: NQ_E_UNSUPPORTED), but the kernels' scratch memory (the
+ * fixed-point copies of x' and t, the token constants, the intermediate t) is a static array of
+ * NQ_STATIC_SCRATCH_BYTES inside the library, one copy per GPU, held until the process ends,
+ * instead of the layer's own workspace.  A layer and batch that need more (about
+ * batch * 3.2 * (d_in + r) bytes: any BASELINE shape at batch 8 fits) -> NQ_E_SHAPE.  The call
+ * allocates and frees nothing and clears nothing (every byte read was written earlier in the
+ * same call).  Every call on one GPU uses that GPU's one array: calls that overlap in time on one
+ * GPU (two streams, two threads) race; calls on one stream follow one another safely.
+ * nq_binlr_read_intermediate does not see this call's t. */
+#define NQ_STATIC_SCRATCH_BYTES (2u << 20)
+int nq_binlr_forward_static(nq_handle h, const void* x, void* y, int batch, void* stream);
+
 /* The same product for ANY batch through the streaming kernels only, in passes of up to 8 tokens
  * (exact integer accumulation of 24-bit fixed-point activations: the accuracy of a batch <= 8
  * forward, at the cost of one pass over the bits per 8 tokens) -- the per-call way to ask for the

@@ -21,6 +21,7 @@ NQ_FLAG_DEFAULT, NQ_FLAG_DECODE_VALU, NQ_FLAG_NO_PREFILL = 0, 1, 2
 NQ_MAX_DIM = 65536
 NQ_DECODE_MAX_BATCH = 8
 NQ_PREFILL_MIN_BATCH = 9
+NQ_STATIC_SCRATCH_BYTES = 2 << 20
 
 DTYPE_BY_NAME = {"f32": NQ_F32, "f16": NQ_F16, "bf16": NQ_BF16, "i8": NQ_I8}
 
@@ -54,6 +55,7 @@ def lib() -> ctypes.CDLL:
         L.nq_binlr_reserve.argtypes = [vp, ci]; L.nq_binlr_reserve.restype = ci
         L.nq_binlr_reserved.argtypes = [vp, ctypes.POINTER(ci), ctypes.POINTER(ctypes.c_size_t)]; L.nq_binlr_reserved.restype = ci
         L.nq_binlr_forward.argtypes = [vp, vp, vp, ci, vp]; L.nq_binlr_forward.restype = ci
+        L.nq_binlr_forward_static.argtypes = [vp, vp, vp, ci, vp]; L.nq_binlr_forward_static.restype = ci
         L.nq_binlr_forward_exact.argtypes = [vp, vp, vp, ci, vp]; L.nq_binlr_forward_exact.restype = ci
         L.nq_set_option.argtypes = [ctypes.c_char_p, ci]; L.nq_set_option.restype = ci
         L.nq_get_option.argtypes = [ctypes.c_char_p, ctypes.POINTER(ci)]; L.nq_get_option.restype = ci
@@ -206,6 +208,10 @@ def nq_binlr_reserved(h: int):
 
 def nq_binlr_forward(h: int, x, y, batch: int, stream=None) -> None:
     _check(lib().nq_binlr_forward(h, _dev_ptr(x), _dev_ptr(y), batch, _stream(stream)))
+
+
+def nq_binlr_forward_static(h: int, x, y, batch: int, stream=None) -> None:
+    _check(lib().nq_binlr_forward_static(h, _dev_ptr(x), _dev_ptr(y), batch, _stream(stream)))
 
 
 def nq_binlr_forward_exact(h: int, x, y, batch: int, stream=None) -> None:

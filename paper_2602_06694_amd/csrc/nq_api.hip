@@ -641,6 +641,63 @@ extern "C" int nq_binlr_forward(nq_handle h, const void* x, void* y, int batch, 
     return NQ_OK;
 }
 
+// ---------------------------------------------------------------------------------------------
+// nq_binlr_forward for callers that must not allocate: the kernels' scratch memory (fixed-point
+// x' and t, token constants, the intermediate t) is carved out of one file-scope device array
+// instead of the layer's workspace.  Every GPU the library runs on holds its own copy of the array
+// (at its own address) until the process ends.  The array's name is only a host-side stand-in: its
+// device address is looked up once per device and that pointer is what the kernels receive.
+// ---------------------------------------------------------------------------------------------
+constexpr size_t kStaticScratchBytes = NQ_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mutex;
+
+// the address of the current device's copy of `scratch` (the current device must be `device`)
+static int static_scratch(int device, char** out)
+{
+    if (device < 0 || device >= kMaxDevices) return fail(NQ_E_UNSUPPORTED, "nq_binlr_forward_static: device index beyond 63");
+    std::lock_guard<std::mutex> lk(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* p = nullptr;
+        NQ_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(NQ_E_HIP, "nq_binlr_forward_static: hipGetSymbolAddress returned no address");
+        g_scratch_ptr[device] = p;
+    }
+    *out = (char*)g_scratch_ptr[device];
+    return NQ_OK;
+}
+
+extern "C" int nq_binlr_forward_static(nq_handle h, const void* x, void* y, int batch, void* stream)
+{
+    if (!h) return fail(NQ_E_NULL, "nq_binlr_forward_static: NULL handle");
+    if (batch < 1) return fail(NQ_E_INVALID_ARG, "nq_binlr_forward_static: batch must be >= 1");
+    if (batch > NQ_DECODE_MAX_BATCH)
+        return fail(NQ_E_UNSUPPORTED, "nq_binlr_forward_static: batch must be <= NQ_DECODE_MAX_BATCH (the streaming kernels)");
+    int rc = check_xy("nq_binlr_forward_static", x, y, (size_t)batch * h->d_in * dtype_size(h->x_dtype),
+                      (size_t)batch * h->d_out * dtype_size(h->y_dtype));
+    if (rc != NQ_OK) return rc;
+    const size_t need = carve_workspace(nullptr, nullptr, h->d_in, h->r, batch);
+    if (need > kStaticScratchBytes) {
+        char buf[200];
+        snprintf(buf, sizeof buf, "nq_binlr_forward_static: batch %d of this layer needs %zu bytes of scratch, the static array holds %zu",
+                 batch, need, kStaticScratchBytes);
+        return fail(NQ_E_SHAPE, buf);
+    }
+    int dev = -1;
+    NQ_HIP(hipGetDevice(&dev));
+    if (dev != h->device) return fail(NQ_E_INVALID_ARG, "nq_binlr_forward_static: the layer lives on another device than the current one");
+    char* base = nullptr;
+    if ((rc = static_scratch(dev, &base)) != NQ_OK) return rc;
+    // Nothing in the array has to start at zero: every byte a kernel reads from it was written
+    // earlier in the same call (the quantiser writes the padding of the fixed-point vectors too; the
+    // bytes past the last token that the shared-input kernel may touch only ever meet 0 bits).
+    DecodeWorkspace w;
+    (void)carve_workspace(&w, base, h->d_in, h->r, batch);
+    return decode_once(h, w, x, y, batch, (hipStream_t)stream);
+}
+
 extern "C" int nq_binlr_export_words(nq_handle h, uint32_t* U_words, uint32_t* V_words)
 {
     if (!h) return fail(NQ_E_NULL, "nq_binlr_export_words: NULL handle");

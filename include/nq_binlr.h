@@ -54,6 +54,7 @@ extern "C" {
 #define NQ_E_NULL        (-4)  /* a required pointer is NULL */
 #define NQ_E_UNSUPPORTED (-5)  /* valid request that this build does not implement */
 #define NQ_E_HIP         (-6)  /* a HIP runtime call failed (see nq_last_error_string) */
+#define NQ_E_TIMEOUT     (-7)  /* a bounded wait inside a kernel ran into its limit (nq_exec_status) */
 
 /* element types */
 #define NQ_I8   0   /* int8, values must be exactly -1 or +1 (pack input only) */
@@ -71,6 +72,7 @@ extern "C" {
 
 typedef struct nq_binlr_s* nq_handle;   /* one factorized layer resident on one GPU */
 typedef struct nq_plan_s*  nq_plan;     /* a fixed list of independent forwards */
+typedef struct nq_exec_s*  nq_exec;     /* a fixed list of layers run in dependency order by one launch */
 
 /* Largest d_in, d_out or r accepted (exactness of the 32-bit accumulators). */
 #define NQ_MAX_DIM 65536
@@ -233,6 +235,41 @@ int nq_plan_forward_timed(nq_plan p, void* stream, float ms[4]);
 int nq_plan_schedules(nq_plan p, int w[2]);
 int nq_plan_destroy(nq_plan p);
 
+/* ---- layers in dependency order, one launch (batch 1) ----
+ * A decoder block -- the seven projections of Appendix D.3's figure, called in the order of the decode
+ * harness of Appendix D.1: q, k, v | o | gate, up | down -- or a whole stack of blocks, run by ONE
+ * persistent kernel: one workgroup per CU walks its share of the 2 x levels phases (stage 1 and stage 2
+ * of every level) and hands t and y from phase to phase through device memory, without a launch or
+ * a grid-wide barrier in between.  Results are bit-identical to nq_binlr_forward called layer by layer.
+ *
+ * hs / xs / ys: host arrays of n entries, layers listed level by level; level_of[i] >= 0, non-decreasing.
+ * xs[i] (device, d_in elements of the layer's x_dtype) is EITHER memory that no layer of the list writes
+ * OR exactly ys[j] of a layer j of an earlier level (same pointer, d_in(i) = d_out(j), x_dtype(i) =
+ * y_dtype(j)): then layer i waits for layer j's output.  No other ordering exists: layers that do not
+ * depend on one another through such a buffer may run in any order or together, whatever their level.
+ * ys[i] (device, d_out elements of y_dtype) must not overlap one another nor any input except as said.
+ * 16-byte alignment as in nq_binlr_forward; d_in, r <= 32768; a handle may appear once.
+ * nq_exec_create allocates (descriptors, task lists, the hand-over buffers) and synchronises;
+ * nq_exec_forward only enqueues one launch on `stream` and allocates nothing; it may be captured in a HIP
+ * graph and replayed.  Launches of one executor must follow one another on one stream.
+ * Every wait inside the kernel is bounded (option "exec_spin_limit_us", default 2 s): should the
+ * grid ever not be resident as a whole (another kernel holding CUs), waits give up, every workgroup
+ * leaves, and nq_exec_status -- which synchronises `stream` -- returns NQ_E_TIMEOUT once; the outputs
+ * of that launch are then incomplete. */
+int nq_exec_create(nq_exec* out, const nq_handle* hs, const void* const* xs, void* const* ys,
+                   const int* level_of, int n);
+int nq_exec_forward(nq_exec e, void* stream);
+int nq_exec_status(nq_exec e, void* stream);
+/* Debug: workgroups of the launch, tasks in their lists, LDS bytes per workgroup.  Pointers may be NULL. */
+int nq_exec_info(nq_exec e, int* n_workgroups, int* n_tasks, size_t* lds_bytes);
+int nq_exec_destroy(nq_exec e);
+/* Host only (no GPU needed): the task lists nq_exec_create would build for layers of these shapes on
+ * n_workgroups workgroups.  tasks_out: host, capacity x 7 int32 -- workgroup, phase (2 level + stage),
+ * layer, stage (0: t = V^T x', 1: y = U t), first row block, row blocks, waves per row block -- in
+ * phase order; NULL to only count.  *n_tasks = number of tasks. */
+int nq_exec_plan_tasks(const int64_t* d_out, const int64_t* d_in, const int64_t* r, const int* level_of, int n,
+                       int n_workgroups, int32_t* tasks_out, int capacity, int* n_tasks);
+
 int nq_binlr_destroy(nq_handle h);
 
 /* Bytes of the stored factorization: r(d_in+d_out)/8 + 2(d_in+d_out), i.e. the bit count
@@ -269,7 +306,7 @@ int nq_probe_mfma(int dtype, double* tera_ops_per_s);
  * "force_w", "split_steps", "selfq4_min_steps", "share_steps", "share_min_batch", "stream_steps",
  * "schedule_full", "fuse_max_mb", "no_fuse", "no_selfq", "no_selfq_c2", "no_resident",
  * "no_quant_wave", "pf_splits1", "pf_splits2", "pf_tg1", "pf_tg2", "pf_ks1", "pf_ks2", "pf_verbose",
- * "exec_spin_limit" (see the source for the meaning of each).  value < 0 restores the default.
+ * "exec_spin_limit_us" (see the source for the meaning of each).  value < 0 restores the default.
  * The environment variable NQ_<NAME IN CAPITALS> gives an option its initial value; it is read once,
  * when the library first consults an option, never on a launch path.  Plans keep the schedules
  * chosen when they were created.  Not thread-safe against forwards running at the same time.

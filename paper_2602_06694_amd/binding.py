@@ -15,7 +15,7 @@ from typing import List, Optional, Sequence
 import numpy as np
 
 NQ_OK = 0
-NQ_E_INVALID_ARG, NQ_E_SHAPE, NQ_E_ALIGN, NQ_E_NULL, NQ_E_UNSUPPORTED, NQ_E_HIP = -1, -2, -3, -4, -5, -6
+NQ_E_INVALID_ARG, NQ_E_SHAPE, NQ_E_ALIGN, NQ_E_NULL, NQ_E_UNSUPPORTED, NQ_E_HIP, NQ_E_TIMEOUT = -1, -2, -3, -4, -5, -6, -7
 NQ_I8, NQ_F32, NQ_F16, NQ_BF16 = 0, 1, 2, 3
 NQ_FLAG_DEFAULT, NQ_FLAG_DECODE_VALU, NQ_FLAG_NO_PREFILL = 0, 1, 2
 NQ_MAX_DIM = 65536
@@ -74,6 +74,12 @@ def lib() -> ctypes.CDLL:
         L.nq_binlr_weight_bytes.argtypes = [vp]; L.nq_binlr_weight_bytes.restype = ctypes.c_size_t
         L.nq_binlr_export_words.argtypes = [vp, vp, vp]; L.nq_binlr_export_words.restype = ci
         L.nq_binlr_read_intermediate.argtypes = [vp, vp, ci]; L.nq_binlr_read_intermediate.restype = ci
+        L.nq_exec_create.argtypes = [ctypes.POINTER(vp), vp, vp, vp, vp, ci]; L.nq_exec_create.restype = ci
+        L.nq_exec_forward.argtypes = [vp, vp]; L.nq_exec_forward.restype = ci
+        L.nq_exec_status.argtypes = [vp, vp]; L.nq_exec_status.restype = ci
+        L.nq_exec_info.argtypes = [vp, ctypes.POINTER(ci), ctypes.POINTER(ci), ctypes.POINTER(ctypes.c_size_t)]; L.nq_exec_info.restype = ci
+        L.nq_exec_destroy.argtypes = [vp]; L.nq_exec_destroy.restype = ci
+        L.nq_exec_plan_tasks.argtypes = [vp, vp, vp, vp, ci, ci, vp, ci, ctypes.POINTER(ci)]; L.nq_exec_plan_tasks.restype = ci
         L.nq_status_string.argtypes = [ci]; L.nq_status_string.restype = ctypes.c_char_p
         L.nq_last_error_string.argtypes = []; L.nq_last_error_string.restype = ctypes.c_char_p
         _lib = L
@@ -258,6 +264,52 @@ def nq_plan_create(hs: Sequence[int], xs: Sequence, ys: Sequence, batch: int) ->
     _check(lib().nq_plan_create(ctypes.byref(p), _ptr_array(list(hs)), _ptr_array([_dev_ptr(x) for x in xs]),
                                 _ptr_array([_dev_ptr(y) for y in ys]), n, batch))
     return p.value
+
+
+def nq_exec_create(hs: Sequence[int], xs: Sequence, ys: Sequence, level_of: Sequence[int]) -> int:
+    n = len(hs)
+    if len(xs) != n or len(ys) != n or len(level_of) != n:
+        raise ValueError("hs, xs, ys, level_of must have the same length")
+    e = ctypes.c_void_p()
+    lv = (ctypes.c_int * n)(*[int(v) for v in level_of])
+    _check(lib().nq_exec_create(ctypes.byref(e), _ptr_array(list(hs)), _ptr_array([_dev_ptr(x) for x in xs]),
+                                _ptr_array([_dev_ptr(y) for y in ys]), lv, n))
+    return e.value
+
+
+def nq_exec_forward(e: int, stream=None) -> None:
+    _check(lib().nq_exec_forward(e, _stream(stream)))
+
+
+def nq_exec_status(e: int, stream=None) -> None:
+    """Waits for the stream; raises NQError(NQ_E_TIMEOUT) if a wait inside a launch gave up."""
+    _check(lib().nq_exec_status(e, _stream(stream)))
+
+
+def nq_exec_info(e: int):
+    """(workgroups, tasks, LDS bytes per workgroup)."""
+    a, b, c = ctypes.c_int(), ctypes.c_int(), ctypes.c_size_t()
+    _check(lib().nq_exec_info(e, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)))
+    return int(a.value), int(b.value), int(c.value)
+
+
+def nq_exec_destroy(e: Optional[int]) -> None:
+    _check(lib().nq_exec_destroy(e))
+
+
+def nq_exec_plan_tasks(d_out: Sequence[int], d_in: Sequence[int], r: Sequence[int], level_of: Sequence[int],
+                       n_workgroups: int) -> np.ndarray:
+    """Host only: int32 [n_tasks, 7] = workgroup, phase, layer, stage, first row block, row blocks, waves per row block."""
+    n = len(d_out)
+    a = [np.ascontiguousarray(v, dtype=np.int64) for v in (d_out, d_in, r)]
+    lv = np.ascontiguousarray(level_of, dtype=np.int32)
+    cnt = ctypes.c_int()
+    _check(lib().nq_exec_plan_tasks(_np_ptr(a[0]), _np_ptr(a[1]), _np_ptr(a[2]), _np_ptr(lv), n, n_workgroups, None, 0,
+                                    ctypes.byref(cnt)))
+    out = np.zeros((cnt.value, 7), dtype=np.int32)
+    _check(lib().nq_exec_plan_tasks(_np_ptr(a[0]), _np_ptr(a[1]), _np_ptr(a[2]), _np_ptr(lv), n, n_workgroups, _np_ptr(out),
+                                    cnt.value, ctypes.byref(cnt)))
+    return out
 
 
 def nq_plan_forward(p: int, stream=None) -> None:

@@ -38,7 +38,7 @@ static const OptEntry kOptTable[OPT_COUNT] = {
     {"share_min_batch", false}, {"stream_steps", false}, {"schedule_full", false}, {"fuse_max_mb", false},
     {"no_fuse", true}, {"no_selfq", true}, {"no_selfq_c2", true}, {"no_resident", true}, {"no_quant_wave", true},
     {"pf_splits1", false}, {"pf_splits2", false}, {"pf_tg1", false}, {"pf_tg2", false}, {"pf_ks1", false}, {"pf_ks2", false},
-    {"pf_verbose", true},
+    {"pf_verbose", true}, {"exec_spin_limit_us", false},
 };
 static int g_opt[OPT_COUNT];
 static std::once_flag g_opt_once;
@@ -257,6 +257,7 @@ extern "C" const char* nq_status_string(int status)
         case NQ_E_NULL: return "null pointer";
         case NQ_E_UNSUPPORTED: return "unsupported";
         case NQ_E_HIP: return "HIP runtime error";
+        case NQ_E_TIMEOUT: return "a bounded wait on the device ran into its limit";
         default: return "unknown status";
     }
 }

@@ -23,6 +23,67 @@ typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef const __attribute__((address_space(1))) v4u* gptr_v4u;    // global (not generic) address space
 typedef const __attribute__((address_space(1))) v4f* gptr_v4f;
+typedef const __attribute__((address_space(1))) uint16_t* gptr_u16;
+
+// chunk c (16 consecutive elements) of token row `base` of the vector d describes, times its scale
+__device__ inline void load_chunk16(const QuantDesc& d, int64_t base, int c, bool vec, float v[16])
+{
+    const int j0 = c * 16;
+    if (vec && j0 + 16 <= d.N) {
+        // the scales are requested before the (type-dependent) loads of x, so that both are in flight together
+        v4u sraw[2] = {v4u{0, 0, 0, 0}, v4u{0, 0, 0, 0}};
+        if (d.scale) {
+            const gptr_v4u sp = (gptr_v4u)(d.scale + j0);
+            sraw[0] = sp[0];
+            sraw[1] = sp[1];
+        }
+        if (d.dtype == NQ_F32) {
+            // (global, not generic, address space: plain vector loads, exact wait counts)
+            const gptr_v4f p = (gptr_v4f)((const float*)d.x + base + j0);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const v4f f = p[q];
+                v[4 * q] = f.x; v[4 * q + 1] = f.y; v[4 * q + 2] = f.z; v[4 * q + 3] = f.w;
+            }
+        } else {
+            const gptr_v4u p = (gptr_v4u)((const uint16_t*)d.x + base + j0);
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const v4u u = p[q];
+                uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    uint16_t lo = (uint16_t)(w[i] & 0xFFFFu), hi = (uint16_t)(w[i] >> 16);
+                    v[8 * q + 2 * i] = d.dtype == NQ_F16 ? half_bits_to_float(lo) : bf16_bits_to_float(lo);
+                    v[8 * q + 2 * i + 1] = d.dtype == NQ_F16 ? half_bits_to_float(hi) : bf16_bits_to_float(hi);
+                }
+            }
+        }
+        if (d.scale) {
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const v4u u = sraw[q];
+                uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    v[8 * q + 2 * i] *= half_bits_to_float((uint16_t)(w[i] & 0xFFFFu));
+                    v[8 * q + 2 * i + 1] *= half_bits_to_float((uint16_t)(w[i] >> 16));
+                }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int j = j0 + i;
+            float f = 0.f;                                  // padding beyond N contributes nothing
+            if (j < d.N) {
+                f = load_as_float(d.x, d.dtype, base + j);
+                if (d.scale) f *= half_bits_to_float(d.scale[j]);
+            }
+            v[i] = f;
+        }
+    }
+}
 
 // byte 0 of a, b, c, d -> one word (a lowest): three byte-permute instructions
 __device__ __forceinline__ uint32_t pack_low_bytes(uint32_t a, uint32_t b, uint32_t c, uint32_t d)

@@ -1,0 +1,708 @@
+// Dependent layers in ONE launch: a decoder block (or a stack of them) run level by level
+// (q, k, v | o | gate, up | down -- the seven projections of Appendix D.3's figure, in the order the
+// decode harness of Appendix D.1 calls them) by a persistent grid, batch 1.
+//
+// A layer forward is two sign-matrix x vector products (Section 3.1 Eq. 1; Appendix E.2), so a
+// stack of L levels is 2 L phases, each depending on ALL outputs of the one before.  Run as
+// launches, a phase costs a launch-to-launch latency (about 7 us measured) for well under 1 us of
+// streaming.  Here one workgroup of 16 waves sits on every CU and walks its own list of tasks; a
+// task is a run of 128-row blocks of one phase's sign matrix.  Nothing is ever waited for except data:
+//
+//  - every value that crosses from one phase to the next (t of stage 1; y where a later layer of
+//    the same call reads it) is stored as a 64-bit pair (fp32 bits, epoch) with ONE device-scope
+//    store, and read with device-scope loads; a consumer accepts a pair only if it carries the
+//    epoch of this launch, else it reads again.  A pair is written by a single 8-byte store, so it
+//    is seen whole or not at all: no flag, no counter, no fence, no ordering between stores.  The
+//    epoch lives in device memory and is advanced by the last workgroup to leave, so a replay of a
+//    captured launch gets a fresh one.
+//  - every wait is bounded by a wall-clock limit; a workgroup that gives up sets an error word
+//    and leaves, the others see the word (or run into their own limit) and leave too: the grid
+//    always drains.
+//  - a workgroup requests the first sign tiles of its next task BEFORE it waits for that task's
+//    input, so the weights stream while the dependency chain is being walked.
+//
+// The arithmetic is that of the streaming kernels element for element (same fixed-point split, same
+// exact integer sums, same single roundings), so results are bit-identical to a sequence of
+// nq_binlr_forward calls.
+#include <algorithm>
+#include <mutex>
+#include <vector>
+
+#include "nq_internal.h"
+#include "nq_device.h"
+
+namespace nq {
+
+constexpr int kExecWaves = 16;
+constexpr int kExecThreads = 64 * kExecWaves;
+constexpr int kExecRing = 8;                       // sign tiles a wave keeps in flight
+constexpr int kExecMaxSteps = 512;                 // longest reduction: 32768 elements (96 KiB of LDS as fixed point)
+constexpr int kExecEpiInts = 3 * kTileRows;        // per wave: the three slice columns x 128 rows
+
+// one stage of one layer, as the kernel sees it
+struct ExecOp {
+    const uint32_t* tiles;          // sign tiles of A (V^T or U)
+    const void* in;                 // the input vector: plain elements of in_dtype, or pairs (in_ll)
+    const uint16_t* in_scale;       // fp16 [N] or nullptr
+    const uint16_t* out_scale;      // fp16 [M rounded up to whole row blocks] or nullptr
+    void* out;                      // plain output [M] of out_dtype, or nullptr
+    unsigned long long* out_ll;     // pairs [M] for the stages that read this output in the same launch, or nullptr
+    int M, N, n_steps, in_dtype, out_dtype, in_ll;
+    int pad[2];
+};
+
+// a run of row blocks of one stage, done by one workgroup: W waves share a row block, 16 / W row
+// blocks are worked on side by side
+struct ExecTask {
+    int op, rb0, n_rb, wl;          // W = 1 << wl
+};
+
+struct ExecState {                  // device words shared by the launches of one executor
+    unsigned int epoch;             // of the NEXT launch (never 0: a cleared pair is never valid)
+    unsigned int done;              // workgroups of the running launch that have left
+    int error;                      // sticky: a wait ran into its limit
+    int pad;
+};
+
+typedef __attribute__((address_space(1))) unsigned long long* gptr_u64;
+
+__device__ __forceinline__ void ll_store(unsigned long long* p, float v, unsigned int epoch)
+{
+    const unsigned long long pair = (unsigned long long)__builtin_bit_cast(unsigned int, v) | ((unsigned long long)epoch << 32);
+    __hip_atomic_store(p, pair, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// ---------------------------------------------------------------------------------------------
+// LDS: [bq_bytes] the task's input as fixed point (layout of the global buffers of the streaming
+// kernels) | [16][3][128] raw sums of the waves | [16] maxima | [16] sums of q | flags
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kExecThreads)
+exec_kernel(const ExecOp* __restrict__ ops, const ExecTask* __restrict__ tasks, const int* __restrict__ task_begin,
+            ExecState* __restrict__ state, int bq_bytes, unsigned long long spin_ticks)
+{
+    extern __shared__ int lds[];
+    constexpr int D = kExecRing;
+    char* const lds_bq = (char*)lds;
+    int* const lds_epi = (int*)(lds_bq + bq_bytes);
+    float* const red_f = (float*)(lds_epi + kExecWaves * kExecEpiInts);
+    double* const red_d = (double*)(red_f + kExecWaves);
+    int* const red_bad = (int*)(red_d + kExecWaves);
+    int* const lds_abort = red_bad + kExecWaves;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4, n = lane & 15;
+    const unsigned int epoch = state->epoch;                // written by the previous launch (or the host)
+    int ti = task_begin[blockIdx.x];
+    const int t_end = task_begin[blockIdx.x + 1];
+    if (tid == 0) *lds_abort = 0;
+    __syncthreads();
+
+    v4u wbuf[D];
+    // the wave's tile stream of one (task, group of row blocks)
+    const char* a_base = nullptr;
+    uint32_t a_off = 0;
+    int cnt = 0, part = 0, w_of = 1;
+    // requests the first D tiles of group `grp` of task `t` (branch-free: a short share re-reads its last tile)
+#define NQ_PRIME(t, grp)                                                                           \
+    do {                                                                                           \
+        const int nst_ = ops[(t).op].n_steps;                                                      \
+        const int wl_ = (t).wl;                                                                    \
+        const int sub_ = wave >> wl_;                                                              \
+        part = wave - (sub_ << wl_);                                                               \
+        w_of = 1 << wl_;                                                                           \
+        const int rb_ = (t).rb0 + (grp) * (kExecWaves >> wl_) + sub_;                              \
+        const bool act_ = rb_ < (t).rb0 + (t).n_rb;                                                \
+        cnt = act_ ? (nst_ - part + w_of - 1) >> wl_ : 0;                                          \
+        cnt = cnt < 0 ? 0 : cnt;                                                                   \
+        a_base = (const char*)ops[(t).op].tiles +                                                  \
+                 (size_t)(act_ ? rb_ : (t).rb0) * nst_ * (kTileWords * 4);                         \
+        a_off = (uint32_t)((cnt > 0 ? part : 0) * 1024 + lane * 16);                               \
+        _Pragma("unroll") for (int k = 0; k < D; ++k) {                                            \
+            const int kk = k < cnt ? k : (cnt > 0 ? cnt - 1 : 0);                                  \
+            wbuf[k] = load_tile_words(a_base, a_off + (uint32_t)kk * (uint32_t)(w_of * 1024));     \
+        }                                                                                          \
+        a_off += (uint32_t)(D * w_of * 1024);                                                      \
+    } while (0)
+
+    ExecTask tk{0, 0, 0, 0};
+    if (ti < t_end) {
+        tk = tasks[ti];
+        NQ_PRIME(tk, 0);
+    }
+
+    while (ti < t_end) {
+        const ExecOp op = ops[tk.op];                       // wave-uniform: scalar loads
+        const int nst = op.n_steps;
+        const int n_chunks = 4 * nst;
+
+        // ---- the task's input: load (waiting for this launch's epoch where another stage writes it), scale, quantise ----
+        // A thread owns chunk tid of 16 elements; inputs of up to 16384 elements are so held in registers
+        // between the maximum and the rounding.  Longer ones (up to 32768) are walked twice, a chunk at a time.
+        const bool held = n_chunks <= kExecThreads;
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)op.in, 0, op.in_ll ? ((op.N + 1) & ~1) * 8 : 0, 0x00020000);   // (whole 16-byte loads; the arrays are padded)
+        QuantDesc qd;
+        qd.x = op.in; qd.scale = op.in_scale; qd.bq = nullptr; qd.meta = nullptr;
+        qd.N = op.N; qd.n_chunks = n_chunks; qd.x_stride = op.N; qd.dtype = op.in_dtype;
+        const unsigned long long t0 = __builtin_amdgcn_s_memrealtime();
+        int gave_up = 0;
+        // chunk ch of a paired input -> v; false while a pair of it does not carry this launch's epoch yet
+        auto load_pairs = [&](int ch, float v[16]) {
+            const int j0 = ch * 16;
+            asm volatile("" ::: "memory");                  // another workgroup writes this memory: load again on every call
+            // (device-scope loads, all eight requested before any is looked at; beyond the array the buffer returns zeros)
+            v4u pr[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) pr[q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (j0 + 2 * q) * 8, 0, 16);
+            unsigned int ok = 1u;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int j = j0 + 2 * q;
+                const unsigned int e0 = pr[q][1], e1 = pr[q][3];
+                ok &= (unsigned int)(j >= op.N) | (unsigned int)(e0 == epoch);
+                ok &= (unsigned int)(j + 1 >= op.N) | (unsigned int)(e1 == epoch);
+                const unsigned int b0 = j < op.N ? pr[q][0] : 0u, b1 = j + 1 < op.N ? pr[q][2] : 0u;
+                v[2 * q] = __builtin_bit_cast(float, b0);
+                v[2 * q + 1] = __builtin_bit_cast(float, b1);
+            }
+            return ok != 0u;
+        };
+        // the same, repeated until the whole wave has its chunks (or the time is up: gave_up)
+        auto wait_pairs = [&](int ch, float v[16]) {
+            unsigned int spins = 0;
+            const int j_wave = (ch - lane) * 16;            // first element of this wave's share
+            for (;;) {
+                const bool ok = load_pairs(ch, v);
+                if (__builtin_amdgcn_ballot_w64(!ok) == 0) return;
+                // Not all there yet.  Until the wave's first pair carries this launch's epoch the wave
+                // polls that one pair only (one transaction per round, all lanes the same address),
+                // so that workgroups waiting far ahead of the running phase leave the memory system alone.
+                bool stop = false;
+                for (;;) {
+                    typedef unsigned int v2u __attribute__((ext_vector_type(2)));
+                    asm volatile("" ::: "memory");
+                    const v2u pr = __builtin_amdgcn_raw_buffer_load_b64(rsrc, j_wave * 8, 0, 16);
+                    if (j_wave >= op.N || pr.y == epoch) break;
+                    ++spins;
+                    stop = __builtin_amdgcn_s_memrealtime() - t0 > spin_ticks ||
+                           ((spins & 15u) == 0 &&
+                            __hip_atomic_load(&state->error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0);
+                    if (stop) break;
+                    __builtin_amdgcn_s_sleep(8);
+                }
+                if (stop || __builtin_amdgcn_s_memrealtime() - t0 > spin_ticks) {
+                    gave_up = 1;
+                    return;
+                }
+            }
+        };
+        // v *= the input scale of chunk ch (as the quantiser of the streaming path does: one fp32 product)
+        auto scale_chunk = [&](int ch, float v[16]) {
+            if (!op.in_scale) return;
+            const int j0 = ch * 16;
+            if (j0 + 16 <= op.N) {
+                const gptr_v4u sp = (gptr_v4u)(op.in_scale + j0);
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const v4u u = sp[q];
+                    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        v[8 * q + 2 * i] *= half_bits_to_float((uint16_t)(w[i] & 0xFFFFu));
+                        v[8 * q + 2 * i + 1] *= half_bits_to_float((uint16_t)(w[i] >> 16));
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    if (j0 + i < op.N) v[i] *= half_bits_to_float(((gptr_u16)op.in_scale)[j0 + i]);
+            }
+        };
+        auto max_of = [&](const float v[16], float& m, int& bad) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float a = fabsf(v[i]);
+                if (!(a <= 3.0e38f)) bad = 1;
+                m = fmaxf(m, a);
+            }
+        };
+        float hv[16];
+        float m = 0.f;
+        int bad = 0;
+        if (held) {
+            if (op.in_ll) {
+                wait_pairs(tid, hv);
+                scale_chunk(tid, hv);
+            } else if (tid < n_chunks) {
+                load_chunk16(qd, 0, tid, true, hv);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) hv[i] = 0.f;
+            }
+            max_of(hv, m, bad);
+        } else {
+            for (int c0 = 0; c0 < n_chunks; c0 += kExecThreads) {            // (whole waves: n_chunks is a multiple of 64... of 16)
+                const int ch = c0 + tid;
+                if (op.in_ll) {
+                    wait_pairs(ch, hv);                                        // (chunks past the end read as zeros)
+                    scale_chunk(ch, hv);
+                } else if (ch < n_chunks) {
+                    load_chunk16(qd, 0, ch, true, hv);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) hv[i] = 0.f;
+                }
+                max_of(hv, m, bad);
+                if (gave_up) break;
+            }
+        }
+        for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+        bad = __builtin_amdgcn_ballot_w64(bad != 0) != 0;
+        if (lane == 0) {
+            red_f[wave] = m;
+            red_bad[wave] = bad;
+        }
+        if (gave_up) *lds_abort = 1;
+        __syncthreads();
+        if (*lds_abort) break;                              // the whole workgroup leaves (same LDS word for all)
+#pragma unroll
+        for (int w = 0; w < kExecWaves; ++w) {
+            m = fmaxf(m, red_f[w]);
+            bad |= red_bad[w];
+        }
+        int ex = 0;
+        float step = 1.0f;
+        if (m > 0.f && !bad) {
+            (void)frexpf(m, &ex);
+            int se = ex - 22;
+            se = se < -126 ? -126 : se;
+            step = ldexpf(1.0f, se);
+        }
+        const float inv_step = 1.0f / step;
+        long long local_sum = 0;
+        if (held) {
+            if (tid < n_chunks) local_sum = quantize_chunk16(hv, inv_step, bad != 0, (uint4*)lds_bq + bq_piece(tid, 0));
+        } else {
+            for (int c0 = 0; c0 < n_chunks; c0 += kExecThreads) {
+                const int ch = c0 + tid;
+                if (ch >= n_chunks) break;
+                if (op.in_ll) {
+                    (void)load_pairs(ch, hv);                                  // this thread has seen these pairs valid already
+                    scale_chunk(ch, hv);
+                } else {
+                    load_chunk16(qd, 0, ch, true, hv);
+                }
+                local_sum += quantize_chunk16(hv, inv_step, bad != 0, (uint4*)lds_bq + bq_piece(ch, 0));
+            }
+        }
+        double sum = (double)local_sum;
+        for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+        if (lane == 0) red_d[wave] = sum;
+        __syncthreads();
+        double tot = 0.0;
+#pragma unroll
+        for (int w = 0; w < kExecWaves; ++w) tot += red_d[w];
+        const double two_step = bad ? (double)__builtin_nanf("") : 2.0 * (double)step;
+        const double neg_qs = -tot * (double)step;
+
+        // ---- the task's row blocks, 16 / W at a time ----
+        const int per = kExecWaves >> tk.wl;
+        const int n_grp = (tk.n_rb + per - 1) / per;
+        const uint32_t b_lane = (uint32_t)(bq_piece(g, n < 3 ? n : 0) * 16);     // unused columns re-read slice 0
+        ExecTask nxt = tk;
+        const bool more = ti + 1 < t_end;
+        if (more) nxt = tasks[ti + 1];
+        for (int grp = 0; grp < n_grp; ++grp) {
+            // the output scales of the rows this thread will finish: requested now, used last
+            uint16_t ps[2] = {0, 0};
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int idx = tid + u * kExecThreads;
+                const int rb = tk.rb0 + grp * per + (idx >> 7);
+                if (op.out_scale && idx < per * kTileRows && rb < tk.rb0 + tk.n_rb)
+                    ps[u] = ((gptr_u16)op.out_scale)[rb * kTileRows + (idx & 127)];
+            }
+            v4i acc[1][8];
+#pragma unroll
+            for (int p = 0; p < 8; ++p) acc[0][p] = v4i{0, 0, 0, 0};
+            const int last = cnt > 0 ? cnt - 1 : 0;
+            const int w_steps = w_of;
+#define NQ_ISSUE(k)                                                              \
+    do {                                                                         \
+        wbuf[k] = load_tile_words(a_base, a_off);                                \
+        a_off += (uint32_t)(w_steps * 1024);                                     \
+    } while (0)
+#define NQ_LDSB(i) (*(const v4u*)(lds_bq + b_lane + (part + ((i) < last ? (i) : last) * w_steps) * (int)kBqStepBytes))
+            v4u bop[2][1];
+            bop[0][0] = NQ_LDSB(0);
+            int i0 = 0;
+            for (; i0 + 2 * D <= cnt; i0 += D) {
+#pragma unroll
+                for (int k = 0; k < D; ++k) {
+                    bop[(k + 1) & 1][0] = NQ_LDSB(i0 + k + 1);
+                    mac_tile<1>(acc, wbuf[k], bop[k & 1]);
+                    NQ_ISSUE(k);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < D; ++k) {
+                if (i0 + k < cnt) {
+                    bop[(k + 1) & 1][0] = NQ_LDSB(i0 + k + 1);
+                    mac_tile<1>(acc, wbuf[k], bop[k & 1]);
+                    if (i0 + k + D < cnt) NQ_ISSUE(k);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < D; ++k) {
+                if (i0 + D + k < cnt) {
+                    bop[(k + 1) & 1][0] = NQ_LDSB(i0 + D + k + 1);
+                    mac_tile<1>(acc, wbuf[k], bop[k & 1]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+#undef NQ_LDSB
+#undef NQ_ISSUE
+            // the ring is empty: the next group's (or the next task's) first tiles go out before the
+            // epilogue, and long before that task's input is waited for
+            const int w_cur = 1 << tk.wl;
+            if (grp + 1 < n_grp) NQ_PRIME(tk, grp + 1);
+            else if (more) NQ_PRIME(nxt, 0);
+
+            // ---- epilogue: raw sums -> LDS, added over the W waves of a row block, scaled, stored ----
+            __syncthreads();                                // the regions (and, after the last group, the input) are free
+            if (n < 3) {
+                v4i* dst = (v4i*)(lds_epi + wave * kExecEpiInts + n * kTileRows) + g;
+#pragma unroll
+                for (int p = 0; p < 8; ++p) dst[4 * p] = p == 7 ? -acc[0][p] : acc[0][p];    // rows 16p + 4g .. +3; plane 7 holds -128 * sum
+            }
+            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int idx = tid + u * kExecThreads;
+                const int sub = idx >> 7, row = idx & 127;
+                const int rb = tk.rb0 + grp * per + sub;
+                const int grow = rb * kTileRows + row;
+                if (idx < per * kTileRows && rb < tk.rb0 + tk.n_rb && grow < op.M) {
+                    int h = 0, mm = 0, l = 0;
+                    const int* q = lds_epi + sub * w_cur * kExecEpiInts + row;
+                    for (int w = 0; w < w_cur; ++w, q += kExecEpiInts) {
+                        h += q[0];
+                        mm += q[kTileRows];
+                        l += q[2 * kTileRows];
+                    }
+                    const double raw = fma((double)h, 65536.0, fma((double)mm, 256.0, (double)l));
+                    double val = fma(raw, __builtin_ldexp(two_step, -(row >> 4)), neg_qs);    // exact; rounded once, below
+                    if (op.out_scale) val *= (double)half_bits_to_float(ps[u]);
+                    float f = (float)val;
+                    if (op.out) store_out(op.out, op.out_dtype, (size_t)grow, f, op.out_scale != nullptr);
+                    if (op.out_ll) {
+                        // what a reader of the stored output would see: the value after its rounding to the output type
+                        if (op.out_dtype == NQ_BF16) f = bf16_bits_to_float(float_to_bf16_bits(f));
+                        else if (op.out_dtype == NQ_F16) f = half_bits_to_float(float_to_f16_bits(f));
+                        ll_store(op.out_ll + grow, f, epoch);
+                    }
+                }
+            }
+        }
+        ++ti;
+        tk = nxt;
+    }
+#undef NQ_PRIME
+
+    // ---- leave: report a missed deadline; the last workgroup out advances the epoch ----
+    __syncthreads();
+    if (tid == 0) {
+        if (*lds_abort) __hip_atomic_store(&state->error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned int left = __hip_atomic_fetch_add(&state->done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (left + 1 == gridDim.x) {
+            __hip_atomic_store(&state->done, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const unsigned int e = epoch + 1;
+            __hip_atomic_store(&state->epoch, e == 0 ? 1u : e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// host: the task lists
+// ---------------------------------------------------------------------------------------------
+struct PlannedTask {
+    int wg, phase, layer, stage, rb0, n_rb, W;
+};
+
+// Levels are run as 2 phases each (stage 1 of every layer of the level, then stage 2).  Inside a
+// phase the row blocks are dealt to the workgroups in runs of 16 / W with the largest W (waves per row
+// block) for which every run finds a workgroup of its own; consecutive phases start where the one
+// before stopped, so a workgroup's next task usually lies several phases ahead and its first tiles
+// are in registers long before its input exists.  Every workgroup's list is in phase order, which
+// is what makes the grid deadlock-free: the earliest unfinished phase depends on finished ones only.
+static void plan_tasks(const int64_t* d_out, const int64_t* d_in, const int64_t* r, const int* level_of, int n,
+                       int n_wg, std::vector<PlannedTask>& out)
+{
+    out.clear();
+    int start = 0;
+    for (int i0 = 0; i0 < n;) {
+        int i1 = i0;
+        while (i1 < n && level_of[i1] == level_of[i0]) ++i1;
+        for (int stage = 0; stage < 2; ++stage) {
+            const int phase = 2 * level_of[i0] + stage;
+            std::vector<int> nrb(i1 - i0);
+            for (int i = i0; i < i1; ++i) nrb[i - i0] = (int)n_rowblocks(stage == 0 ? r[i] : d_out[i]);
+            int W = kExecWaves;
+            auto runs = [&](int w) {
+                int u = 0;
+                for (int v : nrb) u += (v + kExecWaves / w - 1) / (kExecWaves / w);
+                return u;
+            };
+            while (W > 1 && runs(W) > n_wg) W /= 2;
+            const int per = kExecWaves / W;
+            const int total = runs(W);
+            // runs per workgroup when even one wave per row block leaves more runs than workgroups
+            const int each = (total + n_wg - 1) / n_wg;
+            int run = 0;
+            for (int i = i0; i < i1; ++i) {
+                for (int rb = 0; rb < nrb[i - i0]; rb += per, ++run) {
+                    const int wg = (start + run / each) % n_wg;
+                    const int cnt = std::min(per, nrb[i - i0] - rb);
+                    if (!out.empty() && out.back().wg == wg && out.back().phase == phase && out.back().layer == i &&
+                        out.back().rb0 + out.back().n_rb == rb)
+                        out.back().n_rb += cnt;                 // the same workgroup goes on with the same layer
+                    else
+                        out.push_back(PlannedTask{wg, phase, i, stage, rb, cnt, W});
+                }
+            }
+            start = (start + (total + each - 1) / each) % n_wg;
+        }
+        i0 = i1;
+    }
+}
+
+}  // namespace nq
+
+using namespace nq;
+
+struct nq_exec_s {
+    int n, n_wg, device;
+    std::vector<nq_handle> handles;
+    void* alloc;                    // ops | tasks | task_begin | state | pairs
+    ExecOp* ops;
+    ExecTask* tasks;
+    int* task_begin;
+    ExecState* state;
+    int bq_bytes;
+    size_t lds_bytes;
+    int n_tasks;
+};
+
+static int exec_fail(int code, const char* msg)
+{
+    set_error(msg);
+    return code;
+}
+
+extern "C" int nq_exec_plan_tasks(const int64_t* d_out, const int64_t* d_in, const int64_t* r, const int* level_of, int n,
+                                  int n_workgroups, int32_t* tasks_out, int capacity, int* n_tasks)
+{
+    if (!d_out || !d_in || !r || !level_of || !n_tasks) return exec_fail(NQ_E_NULL, "nq_exec_plan_tasks: NULL pointer");
+    if (n < 1 || n_workgroups < 1) return exec_fail(NQ_E_INVALID_ARG, "nq_exec_plan_tasks: n and n_workgroups must be >= 1");
+    for (int i = 0; i < n; ++i) {
+        if (d_out[i] < 1 || d_in[i] < 1 || r[i] < 1) return exec_fail(NQ_E_SHAPE, "nq_exec_plan_tasks: dimensions must be >= 1");
+        if (level_of[i] < 0 || (i > 0 && level_of[i] < level_of[i - 1]))
+            return exec_fail(NQ_E_INVALID_ARG, "nq_exec_plan_tasks: levels must be >= 0 and listed in order");
+    }
+    std::vector<PlannedTask> t;
+    plan_tasks(d_out, d_in, r, level_of, n, n_workgroups, t);
+    *n_tasks = (int)t.size();
+    if (tasks_out) {
+        if ((int)t.size() > capacity) return exec_fail(NQ_E_INVALID_ARG, "nq_exec_plan_tasks: tasks_out too small");
+        for (size_t k = 0; k < t.size(); ++k) {
+            int32_t* o = tasks_out + 7 * k;
+            o[0] = t[k].wg; o[1] = t[k].phase; o[2] = t[k].layer; o[3] = t[k].stage; o[4] = t[k].rb0; o[5] = t[k].n_rb; o[6] = t[k].W;
+        }
+    }
+    return NQ_OK;
+}
+
+extern "C" int nq_exec_destroy(nq_exec e)
+{
+    if (!e) return NQ_OK;
+    (void)hipDeviceSynchronize();
+    if (e->alloc) (void)hipFree(e->alloc);
+    delete e;
+    return NQ_OK;
+}
+
+extern "C" int nq_exec_create(nq_exec* out, const nq_handle* hs, const void* const* xs, void* const* ys,
+                              const int* level_of, int n)
+{
+    if (!out) return exec_fail(NQ_E_NULL, "nq_exec_create: out is NULL");
+    *out = nullptr;
+    if (!hs || !xs || !ys || !level_of) return exec_fail(NQ_E_NULL, "nq_exec_create: NULL array");
+    if (n < 1) return exec_fail(NQ_E_INVALID_ARG, "nq_exec_create: n must be >= 1");
+    std::vector<int> src(n, -1);
+    std::vector<char> consumed(n, 0);
+    for (int i = 0; i < n; ++i) {
+        nq_handle h = hs[i];
+        if (!h) return exec_fail(NQ_E_NULL, "nq_exec_create: NULL handle in list");
+        if (h->flags & NQ_FLAG_DECODE_VALU) return exec_fail(NQ_E_UNSUPPORTED, "nq_exec_create: handle uses NQ_FLAG_DECODE_VALU");
+        if (h->device != hs[0]->device) return exec_fail(NQ_E_INVALID_ARG, "nq_exec_create: handles live on different devices");
+        if (n_steps(h->d_in) > kExecMaxSteps || n_steps(h->r) > kExecMaxSteps)
+            return exec_fail(NQ_E_SHAPE, "nq_exec_create: d_in and r must be <= 32768");
+        if (level_of[i] < 0 || (i > 0 && level_of[i] < level_of[i - 1]))
+            return exec_fail(NQ_E_INVALID_ARG, "nq_exec_create: levels must be >= 0 and listed in order");
+        if (!xs[i] || !ys[i]) return exec_fail(NQ_E_NULL, "nq_exec_create: x or y is NULL");
+        if (((uintptr_t)xs[i] | (uintptr_t)ys[i]) & 15u) return exec_fail(NQ_E_ALIGN, "nq_exec_create: x and y must be 16-byte aligned");
+        for (int j = 0; j < i; ++j)
+            if (hs[j] == h) return exec_fail(NQ_E_INVALID_ARG, "nq_exec_create: a handle appears twice");
+    }
+    // data flow: an input is either outside memory, or exactly the output of a layer of an earlier level
+    auto bytes_x = [&](int i) { return (size_t)hs[i]->d_in * (hs[i]->x_dtype == NQ_F32 ? 4 : 2); };
+    auto bytes_y = [&](int i) { return (size_t)hs[i]->d_out * (hs[i]->y_dtype == NQ_F32 ? 4 : 2); };
+    auto overlap = [](const void* a, size_t na, const void* b, size_t nb) {
+        return (const char*)a < (const char*)b + nb && (const char*)b < (const char*)a + na;
+    };
+    for (int i = 0; i < n; ++i) {
+        for (int j = 0; j < n; ++j) {
+            if (j != i && overlap(ys[i], bytes_y(i), ys[j], bytes_y(j)))
+                return exec_fail(NQ_E_INVALID_ARG, "nq_exec_create: two outputs overlap");
+            if (!overlap(xs[i], bytes_x(i), ys[j], bytes_y(j))) continue;
+            const bool same = xs[i] == ys[j] && hs[i]->d_in == hs[j]->d_out && hs[i]->x_dtype == hs[j]->y_dtype;
+            if (!same || level_of[j] >= level_of[i])
+                return exec_fail(NQ_E_INVALID_ARG,
+                                 "nq_exec_create: an input may overlap an output only by BEING the output (same pointer, "
+                                 "length and type) of a layer of an earlier level");
+            src[i] = j;
+            consumed[j] = 1;
+        }
+    }
+
+    nq_exec e = new (std::nothrow) nq_exec_s();
+    if (!e) return exec_fail(NQ_E_HIP, "nq_exec_create: out of host memory");
+    e->n = n; e->device = hs[0]->device; e->alloc = nullptr;
+    e->handles.assign(hs, hs + n);
+    // one workgroup per CU, and only as many as can be resident together
+    int per_cu = 0;
+    std::vector<int64_t> d_out(n), d_in(n), r(n);
+    int max_steps = 4;
+    for (int i = 0; i < n; ++i) {
+        d_out[i] = hs[i]->d_out; d_in[i] = hs[i]->d_in; r[i] = hs[i]->r;
+        max_steps = std::max(max_steps, (int)std::max(n_steps(d_in[i]), n_steps(r[i])));
+    }
+    e->bq_bytes = max_steps * (int)kBqStepBytes;
+    e->lds_bytes = (size_t)e->bq_bytes + (size_t)kExecWaves * kExecEpiInts * 4 + kExecWaves * (4 + 8 + 4) + 16;
+    hipError_t he = hipFuncSetAttribute((const void*)exec_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (he == hipSuccess)
+        he = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)exec_kernel, kExecThreads, e->lds_bytes);
+    if (he != hipSuccess) { delete e; return hip_fail(he, "occupancy query (executor)", __FILE__, __LINE__); }
+    if (per_cu < 1) { delete e; return exec_fail(NQ_E_UNSUPPORTED, "nq_exec_create: the executor's workgroup does not fit a CU"); }
+    e->n_wg = device_cu_count();
+
+    std::vector<PlannedTask> planned;
+    plan_tasks(d_out.data(), d_in.data(), r.data(), level_of, n, e->n_wg, planned);
+    // per workgroup, in phase order (plan_tasks emits phases in order: a stable sort by workgroup keeps it)
+    std::stable_sort(planned.begin(), planned.end(), [](const PlannedTask& a, const PlannedTask& b) { return a.wg < b.wg; });
+    std::vector<ExecTask> tasks(planned.size());
+    std::vector<int> begin(e->n_wg + 1, 0);
+    for (size_t k = 0; k < planned.size(); ++k) {
+        int wl = 0;
+        while ((1 << wl) < planned[k].W) ++wl;
+        tasks[k] = ExecTask{2 * planned[k].layer + planned[k].stage, planned[k].rb0, planned[k].n_rb, wl};
+        begin[planned[k].wg + 1] += 1;
+    }
+    for (int w = 0; w < e->n_wg; ++w) begin[w + 1] += begin[w];
+    e->n_tasks = (int)tasks.size();
+
+    auto al = [](size_t v) { return (v + 255) / 256 * 256; };
+    const size_t ops_b = al(sizeof(ExecOp) * 2 * n), tasks_b = al(sizeof(ExecTask) * tasks.size()),
+                 begin_b = al(sizeof(int) * begin.size()), state_b = al(sizeof(ExecState));
+    size_t pairs = 0;
+    std::vector<size_t> t_off(n), y_off(n);
+    for (int i = 0; i < n; ++i) {
+        t_off[i] = pairs; pairs += al((size_t)hs[i]->r * 8);
+        y_off[i] = pairs; if (consumed[i]) pairs += al((size_t)hs[i]->d_out * 8);
+    }
+    const size_t total = ops_b + tasks_b + begin_b + state_b + pairs;
+    he = hipMalloc(&e->alloc, total);
+    if (he != hipSuccess) { delete e; return hip_fail(he, "hipMalloc(executor)", __FILE__, __LINE__); }
+    char* c = (char*)e->alloc;
+    e->ops = (ExecOp*)c; c += ops_b;
+    e->tasks = (ExecTask*)c; c += tasks_b;
+    e->task_begin = (int*)c; c += begin_b;
+    e->state = (ExecState*)c; c += state_b;
+    char* pair_base = c;
+    std::vector<ExecOp> ops(2 * n);
+    for (int i = 0; i < n; ++i) {
+        nq_handle h = hs[i];
+        ExecOp& a = ops[2 * i];
+        a = ExecOp{};
+        a.tiles = h->vt_tiles;
+        a.in = src[i] >= 0 ? (const void*)(pair_base + y_off[src[i]]) : xs[i];
+        a.in_ll = src[i] >= 0;
+        a.in_scale = h->s_in; a.out_scale = nullptr;
+        a.out = h->ws.t;                                   // (so that nq_binlr_read_intermediate sees it)
+        a.out_ll = (unsigned long long*)(pair_base + t_off[i]);
+        a.M = (int)h->r; a.N = (int)h->d_in; a.n_steps = (int)n_steps(h->d_in);
+        a.in_dtype = h->x_dtype; a.out_dtype = NQ_F32;
+        ExecOp& b = ops[2 * i + 1];
+        b = ExecOp{};
+        b.tiles = h->u_tiles;
+        b.in = pair_base + t_off[i]; b.in_ll = 1;
+        b.in_scale = h->s_mid; b.out_scale = h->s_out;
+        b.out = ys[i];
+        b.out_ll = consumed[i] ? (unsigned long long*)(pair_base + y_off[i]) : nullptr;
+        b.M = (int)h->d_out; b.N = (int)h->r; b.n_steps = (int)n_steps(h->r);
+        b.in_dtype = NQ_F32; b.out_dtype = h->y_dtype;
+    }
+    ExecState st0{1u, 0u, 0, 0};
+    he = hipMemset(e->alloc, 0, total);
+    if (he == hipSuccess) he = hipMemcpy(e->ops, ops.data(), sizeof(ExecOp) * ops.size(), hipMemcpyHostToDevice);
+    if (he == hipSuccess && !tasks.empty()) he = hipMemcpy(e->tasks, tasks.data(), sizeof(ExecTask) * tasks.size(), hipMemcpyHostToDevice);
+    if (he == hipSuccess) he = hipMemcpy(e->task_begin, begin.data(), sizeof(int) * begin.size(), hipMemcpyHostToDevice);
+    if (he == hipSuccess) he = hipMemcpy(e->state, &st0, sizeof st0, hipMemcpyHostToDevice);
+    if (he == hipSuccess) he = hipDeviceSynchronize();
+    if (he != hipSuccess) {
+        (void)hipFree(e->alloc);
+        delete e;
+        return hip_fail(he, "upload (executor)", __FILE__, __LINE__);
+    }
+    *out = e;
+    return NQ_OK;
+}
+
+extern "C" int nq_exec_forward(nq_exec e, void* stream)
+{
+    if (!e) return exec_fail(NQ_E_NULL, "nq_exec_forward: NULL executor");
+    // wall-clock limit of every wait, in ticks of the 100 MHz constant clock (default 2 s)
+    const int us = opt(OPT_EXEC_SPIN_LIMIT_US);
+    const unsigned long long ticks = us >= 0 ? (unsigned long long)us * 100ull : 200000000ull;
+    hipLaunchKernelGGL(exec_kernel, dim3(e->n_wg), dim3(kExecThreads), e->lds_bytes, (hipStream_t)stream, e->ops, e->tasks,
+                       e->task_begin, e->state, e->bq_bytes, ticks);
+    NQ_HIP(hipGetLastError());
+    return NQ_OK;
+}
+
+extern "C" int nq_exec_status(nq_exec e, void* stream)
+{
+    if (!e) return exec_fail(NQ_E_NULL, "nq_exec_status: NULL executor");
+    NQ_HIP(hipStreamSynchronize((hipStream_t)stream));
+    ExecState st;
+    NQ_HIP(hipMemcpy(&st, e->state, sizeof st, hipMemcpyDeviceToHost));
+    if (st.error) {
+        // clear the word (and the count of a launch that may have been cut short cannot be off: every workgroup leaves through it)
+        int zero = 0;
+        NQ_HIP(hipMemcpy(&e->state->error, &zero, sizeof zero, hipMemcpyHostToDevice));
+        return exec_fail(NQ_E_TIMEOUT, "nq_exec_status: a wait inside the executor ran into its time limit; outputs of that launch are incomplete");
+    }
+    return NQ_OK;
+}
+
+extern "C" int nq_exec_info(nq_exec e, int* n_workgroups, int* n_tasks, size_t* lds_bytes)
+{
+    if (!e) return exec_fail(NQ_E_NULL, "nq_exec_info: NULL executor");
+    if (n_workgroups) *n_workgroups = e->n_wg;
+    if (n_tasks) *n_tasks = e->n_tasks;
+    if (lds_bytes) *lds_bytes = e->lds_bytes;
+    return NQ_OK;
+}

@@ -116,6 +116,7 @@ enum Opt {
     OPT_PF_TG1, OPT_PF_TG2,             // token groups per workgroup tile (2 or 4)
     OPT_PF_KS1, OPT_PF_KS2,             // halves of the reduction taken inside a workgroup (1 or 2)
     OPT_PF_VERBOSE,         // flag: print the chosen prefill tiling
+    OPT_EXEC_SPIN_LIMIT_US, // wall-clock limit, in microseconds, of every wait inside the dependent-layer executor (2 s)
     OPT_COUNT
 };
 int opt(Opt o);                                        // -1 when unset

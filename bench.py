@@ -85,6 +85,57 @@ def prewarm(run, seconds=0.05):
         torch.cuda.synchronize()
 
 
+def timed_windows(run, steps, windows=5):
+    """Times `windows` back-to-back windows of `steps` calls of run() (wall clock around a device
+    synchronisation each); returns per-step milliseconds of every window."""
+    import torch
+    out = []
+    for _ in range(windows):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            run()
+        torch.cuda.synchronize()
+        out.append((time.perf_counter() - t0) * 1e3 / steps)
+    return out
+
+
+def window_stats(ms):
+    s = sorted(ms)
+    return {"median": s[len(s) // 2], "min": s[0], "max": s[-1], "windows": len(s)}
+
+
+class ClockSampler:
+    """Observed engine / memory clocks while a load runs: rocm-smi is started in the background just
+    before a timed region and read afterwards (clocks are left at their defaults)."""
+
+    def __init__(self):
+        import shutil
+        import subprocess
+        self.proc = None
+        exe = shutil.which("rocm-smi") or "/opt/rocm/bin/rocm-smi"
+        try:
+            self.proc = subprocess.Popen(["bash", "-c", f"sleep 0.3; {exe} --showclocks"], stdout=subprocess.PIPE,
+                                         stderr=subprocess.DEVNULL, text=True)
+        except OSError:
+            self.proc = None
+
+    def read(self):
+        import re
+        if self.proc is None:
+            return None
+        try:
+            text = self.proc.communicate(timeout=20)[0]
+        except Exception:
+            return None
+        out = {}
+        for name in ("sclk", "mclk", "fclk"):
+            m = re.search(rf"{name} clock level: \d+: \((\d+)Mhz\)", text)
+            if m:
+                out[name + "_MHz"] = int(m.group(1))
+        return out or None
+
+
 def algorithmic_bytes(shp, batch, y_size=4):
     """Bytes the method itself must move for one forward of one layer."""
     bits = shp.r * (shp.d_in + shp.d_out) // 8
@@ -166,7 +217,8 @@ def measured_traffic(workload_name, stage):
 
 
 def time_stack(cfg, batch, steps=10, warmup=2):
-    """Whole decoder stack of config 3 / 4 as one plan: step time, weight GB/s and per-kernel roofline."""
+    """Whole decoder stack of config 3 / 4 as one plan of independent layers: step time (median of five
+    windows), weight GB/s and per-kernel roofline; and the same stack as a loop of single-layer calls."""
     import numpy as np
     import torch
     from paper_2602_06694_amd import binding as nq
@@ -188,85 +240,21 @@ def time_stack(cfg, batch, steps=10, warmup=2):
     prewarm(lambda: nq.nq_plan_forward(plan))
     for _ in range(warmup):
         nq.nq_plan_forward(plan)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        nq.nq_plan_forward(plan)
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3 / steps
+    win = timed_windows(lambda: nq.nq_plan_forward(plan), steps)
+    ms = window_stats(win)["median"]
     pk = np.zeros(4)
     for _ in range(5):
         pk += np.array(nq.nq_plan_forward_timed(plan))
     pk /= 5
-    # the same stack as a plain loop of single-layer calls (four launches per layer on one stream),
-    # eagerly and as a HIP-graph replay of that loop
+    # the same stack as a plain loop of single-layer calls (two to four launches per layer on one stream)
     def loop():
         for h, x, y in zip(handles, xs, ys):
             nq.nq_binlr_forward(h, x, y, batch)
     prewarm(loop, 0.02)
-    t0 = time.perf_counter()
-    for _ in range(3):
-        loop()
-    torch.cuda.synchronize()
-    ms_loop = (time.perf_counter() - t0) * 1e3 / 3
-    ms_graph = None
-    try:
-        side = torch.cuda.Stream()
-        with torch.cuda.stream(side):
-            loop()
-        torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            loop()
-        prewarm(graph.replay, 0.02)
-        t0 = time.perf_counter()
-        for _ in range(3):
-            graph.replay()
-        torch.cuda.synchronize()
-        ms_graph = (time.perf_counter() - t0) * 1e3 / 3
-        del graph
-    except Exception as e:                     # report, do not hide
-        ms_graph = f"capture failed: {e}"
-    # the stack in dependency order: per decoder layer four plans (q, k, v | o | gate, up | down), the
-    # layers of a plan reading one shared input; the plans run back to back on the stream, as they
-    # would between the attention and activation kernels of a model
-    block = synth.CONFIGS[cfg].block
-    level_plans = []
-    for base in range(0, len(handles), len(block)):
-        for group in ((0, 1, 2), (3,), (4, 5), (6,)):
-            idx = [base + g for g in group]
-            level_plans.append(nq.nq_plan_create([handles[i] for i in idx], [xs[idx[0]]] * len(idx),
-                                                 [ys[i] for i in idx], batch))
-
-    def levels():
-        for lp in level_plans:
-            nq.nq_plan_forward(lp)
-    prewarm(levels, 0.02)
-    t0 = time.perf_counter()
-    for _ in range(3):
-        levels()
-    torch.cuda.synchronize()
-    ms_levels = (time.perf_counter() - t0) * 1e3 / 3
-    try:
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            levels()
-        prewarm(graph.replay, 0.02)
-        t0 = time.perf_counter()
-        for _ in range(5):
-            graph.replay()
-        torch.cuda.synchronize()
-        ms_levels_graph = (time.perf_counter() - t0) * 1e3 / 5
-        del graph
-    except Exception as e:                     # report, do not hide
-        ms_levels_graph = f"capture failed: {e}"
-    for lp in level_plans:
-        nq.nq_plan_destroy(lp)
-    res = {"layers": len(handles), "ms_per_step": ms, "weight_GBps": wbytes / ms / 1e6,
-           "tokens_per_s": batch / (ms * 1e-3),
-           "ms_per_step_loop_of_single_calls": ms_loop, "ms_per_step_hip_graph_of_that_loop": ms_graph,
-           "ms_per_step_in_dependency_order_4_plans_per_block": ms_levels,
-           "ms_per_step_hip_graph_of_those_plans": ms_levels_graph,
+    ms_loop = window_stats(timed_windows(loop, 2, 3))["median"]
+    res = {"layers": len(handles), "ms_per_step": ms, "ms_per_step_windows": window_stats(win),
+           "weight_GBps": wbytes / ms / 1e6, "tokens_per_s": batch / (ms * 1e-3),
+           "ms_per_step_loop_of_single_calls": ms_loop,
            "kernel_ms": {"quantize_x": pk[0], "stage1": pk[1], "quantize_t": pk[2], "stage2": pk[3]},
            "stage1_GBps": sb1 / pk[1] / 1e6, "stage2_GBps": sb2 / pk[3] / 1e6,
            "stage1_frac_of_hbm_peak": sb1 / pk[1] / 1e6 / HBM_PEAK_GBPS,
@@ -275,6 +263,74 @@ def time_stack(cfg, batch, steps=10, warmup=2):
     for h in handles:
         nq.nq_binlr_destroy(h)
     return res
+
+
+def time_stack_in_dependency_order(cfg, steps=10):
+    """The stack of config 3 / 4 at batch 1 with every layer reading the output of the layer before it
+    (q -> o -> gate -> down -> the next block's q, k, v; k, v and up are computed as well): each of the
+    2 x 4 x blocks stages waits for all of the one before.  Scales are multiplied by powers of two so that
+    the chain keeps a magnitude near one (synth.gen_chained_stack).  Three ways to run it: the executor
+    (one persistent launch per token), four plans per block back to back on the stream, single calls."""
+    import numpy as np
+    import torch
+    from paper_2602_06694_amd import binding as nq
+    from paper_2602_06694_amd import synth
+    c = synth.CONFIGS[cfg]
+    layers = synth.gen_chained_stack(cfg)
+    n = len(layers)
+    level, src = synth.chain_spec(n // 7)
+    hs, ys, wbytes = [], [], 0
+    for i, d in enumerate(layers):
+        shp = d.shape
+        hs.append(nq.nq_binlr_create(shp.d_out, shp.d_in, shp.r, d.U_words, d.V_words, d.s_out, d.s_in,
+                                     nq.NQ_BF16 if src[i] < 0 else nq.NQ_F32))
+        ys.append(torch.zeros((1, shp.d_out), dtype=torch.float32, device="cuda"))
+        wbytes += algorithmic_bytes(shp, 1)[0]
+    x0n = synth.gen_x(1, c.block[0].d_in, synth.seed_for(cfg, 0, 0, synth.T_X), "bf16")
+    x0 = torch.from_numpy(x0n.view(np.int16).copy()).view(torch.bfloat16).cuda()
+    xs = [x0 if s < 0 else ys[s] for s in src]
+
+    def single():
+        for h, x, y in zip(hs, xs, ys):
+            nq.nq_binlr_forward(h, x, y, 1)
+    single()
+    torch.cuda.synchronize()
+    ref = [y.clone() for y in ys]
+    ex = nq.nq_exec_create(hs, xs, ys, level)
+    for y in ys:
+        y.zero_()
+    nq.nq_exec_forward(ex)
+    nq.nq_exec_status(ex)
+    identical = all(torch.equal(a, b) for a, b in zip(ys, ref))
+    prewarm(lambda: nq.nq_exec_forward(ex))
+    win = timed_windows(lambda: nq.nq_exec_forward(ex), steps)
+    nq.nq_exec_status(ex)
+    ms = window_stats(win)["median"]
+    n_wg, n_tasks, lds = nq.nq_exec_info(ex)
+    # four plans per block (q, k, v | o | gate, up | down), each two launches, back to back on the stream
+    plans = []
+    for base in range(0, n, 7):
+        for group in ((0, 1, 2), (3,), (4, 5), (6,)):
+            idx = [base + g for g in group]
+            plans.append(nq.nq_plan_create([hs[i] for i in idx], [xs[i] for i in idx], [ys[i] for i in idx], 1))
+
+    def levels():
+        for lp in plans:
+            nq.nq_plan_forward(lp)
+    prewarm(levels, 0.02)
+    ms_levels = window_stats(timed_windows(levels, 3, 3))["median"]
+    ms_single = window_stats(timed_windows(single, 2, 3))["median"]
+    for lp in plans:
+        nq.nq_plan_destroy(lp)
+    nq.nq_exec_destroy(ex)
+    for h in hs:
+        nq.nq_binlr_destroy(h)
+    phases = 2 * (level[-1] + 1)
+    return {"layers": n, "dependent_stages": phases, "executor_ms_per_step": ms, "executor_windows": window_stats(win),
+            "executor_us_per_stage": ms * 1e3 / phases, "executor_weight_GBps": wbytes / ms / 1e6,
+            "executor_bit_identical_to_single_calls": bool(identical),
+            "executor_workgroups": n_wg, "executor_tasks": n_tasks, "executor_lds_bytes": lds,
+            "four_plans_per_block_ms_per_step": ms_levels, "single_calls_ms_per_step": ms_single}
 
 
 def time_pool_batch(pool, batch, steps=10, warmup=2):
@@ -297,19 +353,16 @@ def time_pool_batch(pool, batch, steps=10, warmup=2):
     prewarm(lambda: nq.nq_plan_forward(plan))
     for _ in range(warmup):
         nq.nq_plan_forward(plan)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        nq.nq_plan_forward(plan)
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3 / steps
+    win = timed_windows(lambda: nq.nq_plan_forward(plan), steps)
+    ms = window_stats(win)["median"]
     pk = np.zeros(4)
     for _ in range(5):
         pk += np.array(nq.nq_plan_forward_timed(plan))
     pk /= 5
     wb, ab = algorithmic_bytes(shp, batch)
     s1, s2 = stage_bytes(shp, batch)
-    res = {"layers": pool, "batch": batch, "ms_per_step": ms, "weight_GBps": pool * wb / ms / 1e6,
+    res = {"layers": pool, "batch": batch, "ms_per_step": ms, "ms_per_step_windows": window_stats(win),
+           "schedules": nq.nq_plan_schedules(plan), "weight_GBps": pool * wb / ms / 1e6,
            "algorithmic_GBps": pool * ab / ms / 1e6, "tokens_per_s_per_layer": batch * pool / (ms * 1e-3),
            "kernel_ms": {"quantize_x": pk[0], "stage1": pk[1], "quantize_t": pk[2], "stage2": pk[3]},
            "stage1_GBps": pool * s1 / pk[1] / 1e6, "stage2_GBps": pool * s2 / pk[3] / 1e6}
@@ -337,12 +390,8 @@ def time_single_layer(cfg, reps=200):
     prewarm(lambda: nq.nq_binlr_forward(h, x, y, 1), 0.02)
     for _ in range(20):
         nq.nq_binlr_forward(h, x, y, 1)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(reps):
-        nq.nq_binlr_forward(h, x, y, 1)
-    torch.cuda.synchronize()
-    us = (time.perf_counter() - t0) * 1e6 / reps
+    win = timed_windows(lambda: nq.nq_binlr_forward(h, x, y, 1), reps)
+    us = window_stats(win)["median"] * 1e3
     wb, _ = algorithmic_bytes(shp, 1)
     nq.nq_binlr_destroy(h)
     return {"shape": [shp.d_out, shp.d_in, shp.r], "us_per_forward": us, "cache_hot_weight_GBps": wb / us / 1e3}
@@ -365,16 +414,19 @@ def time_prefill(args):
             x = torch.from_numpy(xb.view(np.int16).copy()).view(torch.bfloat16).cuda()
             y = torch.empty((B, shp.d_out), dtype=torch.float32, device="cuda")
             prewarm(lambda: nq.nq_binlr_forward(h, x, y, B), 0.03)
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            iters = 20
-            e0.record()
-            for _ in range(iters):
-                nq.nq_binlr_forward(h, x, y, B)
-            e1.record()
-            torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / iters
+            win = []
+            for _ in range(5):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                iters = 10
+                e0.record()
+                for _ in range(iters):
+                    nq.nq_binlr_forward(h, x, y, B)
+                e1.record()
+                torch.cuda.synchronize()
+                win.append(e0.elapsed_time(e1) / iters)
+            ms = window_stats(win)["median"]
             flops = 2.0 * B * shp.r * (shp.d_in + shp.d_out)
-            res[f"{shp.name}_{shp.d_out}x{shp.d_in}_B{B}"] = {"ms": ms, "TFLOP/s": flops / ms / 1e9,
+            res[f"{shp.name}_{shp.d_out}x{shp.d_in}_B{B}"] = {"ms": ms, "ms_windows": window_stats(win), "TFLOP/s": flops / ms / 1e9,
                                                              "frac_of_f16_mfma_peak": flops / ms / 1e9 / MFMA_F16_PEAK_TFLOPS}
             del x, y
         nq.nq_binlr_destroy(h)
@@ -419,6 +471,9 @@ def main():
     for _ in range(args.warmup):
         nq.nq_plan_forward(plan)
     torch.cuda.synchronize()
+    # EXACTLY `steps` steps are timed for the headline value (window 0); four more windows of the same
+    # length follow, and the line also carries their median, minimum and maximum
+    clocks = ClockSampler()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     e0.record()
@@ -428,6 +483,12 @@ def main():
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
     ev_ms = e0.elapsed_time(e1) / args.steps
+    more_windows = [wall_ms] + timed_windows(lambda: nq.nq_plan_forward(plan), args.steps, 4)
+    while clocks.proc is not None and clocks.proc.poll() is None:      # keep the load up until the clocks have been read
+        for _ in range(50):
+            nq.nq_plan_forward(plan)
+        torch.cuda.synchronize()
+    observed_clocks = clocks.read()
 
     # per-kernel durations (HIP events recorded between the four launches, on the same stream)
     reps = max(3, min(args.steps, 20))
@@ -469,6 +530,8 @@ def main():
                    "weight_bytes_per_step": w_bytes, "algorithmic_bytes_per_step": all_bytes},
         "tokens_per_s_per_layer": batch * len(work) / (wall_ms * 1e-3),
         "ms_per_step_hip_events": ev_ms,
+        "ms_per_step_windows": window_stats(more_windows),
+        "observed_clocks": observed_clocks,
         "kernel_ms": {"quantize_x": per_kernel[0], "stage1": per_kernel[1], "quantize_t": per_kernel[2],
                       "stage2": per_kernel[3]},
         "stages": stages,
@@ -489,6 +552,8 @@ def main():
     traffic = measured_traffic(name, dom)
     if traffic is not None:
         out["roofline"]["traffic"] = traffic
+        out["roofline"]["traffic_source"] = ("profiles/stage_kernels_cfg2_pool_pmc.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of "
+                                             "this workload in a separate run (not measured in this one)")
     nq.nq_plan_destroy(plan)
     for h in handles:
         nq.nq_binlr_destroy(h)
@@ -500,6 +565,8 @@ def main():
                         "decode_cfg2_pool_b8": time_pool_batch(args.pool, 8),
                         "decode_llama2_7b_stack_b1": time_stack(3, 1),
                         "decode_llama2_70b_stack_b1": time_stack(4, 1),
+                        "decode_llama2_7b_in_dependency_order_b1": time_stack_in_dependency_order(3),
+                        "decode_llama2_70b_in_dependency_order_b1": time_stack_in_dependency_order(4),
                         "prefill_config5": time_prefill(args)}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(work, batch, args.cpu_seconds)

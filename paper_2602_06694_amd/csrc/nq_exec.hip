@@ -26,6 +26,7 @@
 // nq_binlr_forward calls.
 #include <algorithm>
 #include <mutex>
+#include <type_traits>
 #include <vector>
 
 #include "nq_internal.h"
@@ -39,8 +40,11 @@ constexpr int kExecRing = 8;                       // sign tiles a wave keeps in
 constexpr int kExecMaxSteps = 512;                 // longest reduction: 32768 elements (96 KiB of LDS as fixed point)
 constexpr int kExecEpiInts = 3 * kTileRows;        // per wave: the three slice columns x 128 rows
 
-// one stage of one layer, as the kernel sees it
-struct ExecOp {
+// One task of one workgroup: a run of row blocks of one stage of one layer, with everything the
+// kernel needs to know about that stage in the record itself -- a workgroup's records are
+// consecutive in memory, so the next one is a neighbouring cache line, requested a task ahead.
+// W = 1 << wl waves share a row block, 16 / W row blocks are worked on side by side.
+struct ExecTask {
     const uint32_t* tiles;          // sign tiles of A (V^T or U)
     const void* in;                 // the input vector: plain elements of in_dtype, or pairs (in_ll)
     const uint16_t* in_scale;       // fp16 [N] or nullptr
@@ -48,14 +52,10 @@ struct ExecOp {
     void* out;                      // plain output [M] of out_dtype, or nullptr
     unsigned long long* out_ll;     // pairs [M] for the stages that read this output in the same launch, or nullptr
     int M, N, n_steps, in_dtype, out_dtype, in_ll;
-    int pad[2];
+    int rb0, n_rb, wl;
+    int pad[3];
 };
-
-// a run of row blocks of one stage, done by one workgroup: W waves share a row block, 16 / W row
-// blocks are worked on side by side
-struct ExecTask {
-    int op, rb0, n_rb, wl;          // W = 1 << wl
-};
+static_assert(sizeof(ExecTask) == 96, "task record");
 
 struct ExecState {                  // device words shared by the launches of one executor
     unsigned int epoch;             // of the NEXT launch (never 0: a cleared pair is never valid)
@@ -66,28 +66,74 @@ struct ExecState {                  // device words shared by the launches of on
 
 typedef __attribute__((address_space(1))) unsigned long long* gptr_u64;
 
+
 __device__ __forceinline__ void ll_store(unsigned long long* p, float v, unsigned int epoch)
 {
     const unsigned long long pair = (unsigned long long)__builtin_bit_cast(unsigned int, v) | ((unsigned long long)epoch << 32);
     __hip_atomic_store(p, pair, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Reductions over a wavefront on the data-parallel-primitive path of the vector unit (no LDS traffic):
+// quad exchanges, mirrored halves of a 16-lane row, then the four rows through scalar registers.
+// The result is the same in every lane.
+template <class T, class Op>
+__device__ __forceinline__ T wave_reduce32(T v, Op op)
+{
+    static_assert(sizeof(T) == 4, "32-bit values");
+    auto dpp = [](T x, auto ctrl) {
+        return __builtin_bit_cast(T, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, x), decltype(ctrl)::value, 0xf, 0xf, true));
+    };
+    v = op(v, dpp(v, std::integral_constant<int, 0xB1>{}));      // quad_perm [1, 0, 3, 2]
+    v = op(v, dpp(v, std::integral_constant<int, 0x4E>{}));      // quad_perm [2, 3, 0, 1]
+    v = op(v, dpp(v, std::integral_constant<int, 0x141>{}));     // row_half_mirror
+    v = op(v, dpp(v, std::integral_constant<int, 0x140>{}));     // row_mirror
+    const int b = __builtin_bit_cast(int, v);
+    const T r0 = __builtin_bit_cast(T, __builtin_amdgcn_readlane(b, 0)), r1 = __builtin_bit_cast(T, __builtin_amdgcn_readlane(b, 16));
+    const T r2 = __builtin_bit_cast(T, __builtin_amdgcn_readlane(b, 32)), r3 = __builtin_bit_cast(T, __builtin_amdgcn_readlane(b, 48));
+    return op(op(r0, r1), op(r2, r3));
+}
+
+// sum of a 64-bit integer over the wavefront (the halves travel separately, the additions are 64-bit)
+__device__ __forceinline__ long long wave_sum64(long long v)
+{
+    auto dpp = [](long long x, auto ctrl) {
+        const int lo = __builtin_amdgcn_mov_dpp((int)(unsigned int)(unsigned long long)x, decltype(ctrl)::value, 0xf, 0xf, true);
+        const int hi = __builtin_amdgcn_mov_dpp((int)(unsigned int)((unsigned long long)x >> 32), decltype(ctrl)::value, 0xf, 0xf, true);
+        return (long long)(((unsigned long long)(unsigned int)hi << 32) | (unsigned int)lo);
+    };
+    v += dpp(v, std::integral_constant<int, 0xB1>{});
+    v += dpp(v, std::integral_constant<int, 0x4E>{});
+    v += dpp(v, std::integral_constant<int, 0x141>{});
+    v += dpp(v, std::integral_constant<int, 0x140>{});
+    long long t = 0;
+#pragma unroll
+    for (int r = 0; r < 64; r += 16) {
+        const unsigned int lo = (unsigned int)__builtin_amdgcn_readlane((int)(unsigned int)(unsigned long long)v, r);
+        const unsigned int hi = (unsigned int)__builtin_amdgcn_readlane((int)(unsigned int)((unsigned long long)v >> 32), r);
+        t += (long long)(((unsigned long long)hi << 32) | lo);
+    }
+    return t;
+}
+
 // ---------------------------------------------------------------------------------------------
 // LDS: [bq_bytes] the task's input as fixed point (layout of the global buffers of the streaming
-// kernels) | [16][3][128] raw sums of the waves | [16] maxima | [16] sums of q | flags
+// kernels) | [16][3][128] raw sums of the waves | sum of q, largest magnitude, flags
 // ---------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(kExecThreads)
-exec_kernel(const ExecOp* __restrict__ ops, const ExecTask* __restrict__ tasks, const int* __restrict__ task_begin,
+exec_kernel(const ExecTask* __restrict__ tasks, const int* __restrict__ task_begin,
             ExecState* __restrict__ state, int bq_bytes, unsigned long long spin_ticks)
 {
     extern __shared__ int lds[];
     constexpr int D = kExecRing;
     char* const lds_bq = (char*)lds;
     int* const lds_epi = (int*)(lds_bq + bq_bytes);
-    float* const red_f = (float*)(lds_epi + kExecWaves * kExecEpiInts);
-    double* const red_d = (double*)(red_f + kExecWaves);
-    int* const red_bad = (int*)(red_d + kExecWaves);
-    int* const lds_abort = red_bad + kExecWaves;
+    // reductions over the workgroup go through LDS atomics (one instruction per wave each, no shuffle
+    // chains): the sum of the quantised values, the largest magnitude (as the bits of a non-negative
+    // float), "a value is not finite", "a wait gave up"
+    unsigned long long* const lds_sum = (unsigned long long*)(lds_epi + kExecWaves * kExecEpiInts);
+    unsigned int* const lds_max = (unsigned int*)(lds_sum + 1);
+    int* const lds_bad = (int*)(lds_max + 1);
+    int* const lds_abort = lds_bad + 1;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -96,7 +142,12 @@ exec_kernel(const ExecOp* __restrict__ ops, const ExecTask* __restrict__ tasks, 
     const unsigned int epoch = state->epoch;                // written by the previous launch (or the host)
     int ti = task_begin[blockIdx.x];
     const int t_end = task_begin[blockIdx.x + 1];
-    if (tid == 0) *lds_abort = 0;
+    if (tid == 0) {
+        *lds_abort = 0;
+        *lds_sum = 0;
+        *lds_max = 0;
+        *lds_bad = 0;
+    }
     __syncthreads();
 
     v4u wbuf[D];
@@ -107,7 +158,7 @@ exec_kernel(const ExecOp* __restrict__ ops, const ExecTask* __restrict__ tasks, 
     // requests the first D tiles of group `grp` of task `t` (branch-free: a short share re-reads its last tile)
 #define NQ_PRIME(t, grp)                                                                           \
     do {                                                                                           \
-        const int nst_ = ops[(t).op].n_steps;                                                      \
+        const int nst_ = (t).n_steps;                                                      \
         const int wl_ = (t).wl;                                                                    \
         const int sub_ = wave >> wl_;                                                              \
         part = wave - (sub_ << wl_);                                                               \
@@ -116,7 +167,7 @@ exec_kernel(const ExecOp* __restrict__ ops, const ExecTask* __restrict__ tasks, 
         const bool act_ = rb_ < (t).rb0 + (t).n_rb;                                                \
         cnt = act_ ? (nst_ - part + w_of - 1) >> wl_ : 0;                                          \
         cnt = cnt < 0 ? 0 : cnt;                                                                   \
-        a_base = (const char*)ops[(t).op].tiles +                                                  \
+        a_base = (const char*)(t).tiles +                                                  \
                  (size_t)(act_ ? rb_ : (t).rb0) * nst_ * (kTileWords * 4);                         \
         a_off = (uint32_t)((cnt > 0 ? part : 0) * 1024 + lane * 16);                               \
         _Pragma("unroll") for (int k = 0; k < D; ++k) {                                            \
@@ -126,21 +177,49 @@ exec_kernel(const ExecOp* __restrict__ ops, const ExecTask* __restrict__ tasks, 
         a_off += (uint32_t)(D * w_of * 1024);                                                      \
     } while (0)
 
-    ExecTask tk{0, 0, 0, 0};
+    // With the first tiles of a task go the scales it will need (static data, usually cold in the caches:
+    // a round trip to memory each): the input scales of the chunk this thread owns -- where the input is
+    // handed over by another stage and fits one chunk per thread -- and the output scales of the rows this
+    // thread finishes in the task's first group.  All of them are requested before the task's input is
+    // waited for and converted only when they are used.
+    v4u sraw[2] = {v4u{0, 0, 0, 0}, v4u{0, 0, 0, 0}};
+    uint16_t ps[2] = {0, 0};
+#define NQ_PREFETCH_SCALES(t)                                                                      \
+    do {                                                                                           \
+        const uint16_t* const is_ = (t).in_scale;                                          \
+        const int n_ = (t).N;                                                              \
+        if (is_ && (t).in_ll && tid * 16 + 16 <= n_) {                                     \
+            const gptr_v4u sp_ = (gptr_v4u)(is_ + tid * 16);                                       \
+            sraw[0] = sp_[0];                                                                      \
+            sraw[1] = sp_[1];                                                                      \
+        }                                                                                          \
+        const uint16_t* const os_ = (t).out_scale;                                         \
+        const int per_ = kExecWaves >> (t).wl;                                                     \
+        _Pragma("unroll") for (int u = 0; u < 2; ++u) {                                            \
+            const int idx_ = tid + u * kExecThreads;                                               \
+            const int rb_ = (t).rb0 + (idx_ >> 7);                                                 \
+            if (os_ && idx_ < per_ * kTileRows && rb_ < (t).rb0 + (t).n_rb)                        \
+                ps[u] = ((gptr_u16)os_)[rb_ * kTileRows + (idx_ & 127)];                           \
+        }                                                                                          \
+    } while (0)
+
+    ExecTask tk{};
     if (ti < t_end) {
         tk = tasks[ti];
         NQ_PRIME(tk, 0);
+        NQ_PREFETCH_SCALES(tk);
     }
 
     while (ti < t_end) {
-        const ExecOp op = ops[tk.op];                       // wave-uniform: scalar loads
+        const ExecTask& op = tk;                            // (wave-uniform: the record came through scalar loads)
+        // the next record is requested now, a whole task before its fields are needed
+        ExecTask nxt = tk;
+        const bool more = ti + 1 < t_end;
+        if (more) nxt = tasks[ti + 1];
         const int nst = op.n_steps;
         const int n_chunks = 4 * nst;
 
         // ---- the task's input: load (waiting for this launch's epoch where another stage writes it), scale, quantise ----
-        // A thread owns chunk tid of 16 elements; inputs of up to 16384 elements are so held in registers
-        // between the maximum and the rounding.  Longer ones (up to 32768) are walked twice, a chunk at a time.
-        const bool held = n_chunks <= kExecThreads;
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)op.in, 0, op.in_ll ? ((op.N + 1) & ~1) * 8 : 0, 0x00020000);   // (whole 16-byte loads; the arrays are padded)
         QuantDesc qd;
         qd.x = op.in; qd.scale = op.in_scale; qd.bq = nullptr; qd.meta = nullptr;
@@ -155,39 +234,43 @@ exec_kernel(const ExecOp* __restrict__ ops, const ExecTask* __restrict__ tasks, 
             v4u pr[8];
 #pragma unroll
             for (int q = 0; q < 8; ++q) pr[q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (j0 + 2 * q) * 8, 0, 16);
-            unsigned int ok = 1u;
+            unsigned int ok = 1u, any = 0u;                 // all pairs of the chunk carry the epoch / at least one does
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
                 const int j = j0 + 2 * q;
                 const unsigned int e0 = pr[q][1], e1 = pr[q][3];
                 ok &= (unsigned int)(j >= op.N) | (unsigned int)(e0 == epoch);
                 ok &= (unsigned int)(j + 1 >= op.N) | (unsigned int)(e1 == epoch);
+                any |= (unsigned int)(j < op.N) & (unsigned int)(e0 == epoch);
                 const unsigned int b0 = j < op.N ? pr[q][0] : 0u, b1 = j + 1 < op.N ? pr[q][2] : 0u;
                 v[2 * q] = __builtin_bit_cast(float, b0);
                 v[2 * q + 1] = __builtin_bit_cast(float, b1);
             }
-            return ok != 0u;
+            return ok | (any << 1);
         };
         // the same, repeated until the whole wave has its chunks (or the time is up: gave_up)
         auto wait_pairs = [&](int ch, float v[16]) {
             unsigned int spins = 0;
             const int j_wave = (ch - lane) * 16;            // first element of this wave's share
             for (;;) {
-                const bool ok = load_pairs(ch, v);
-                if (__builtin_amdgcn_ballot_w64(!ok) == 0) return;
-                // Not all there yet.  Until the wave's first pair carries this launch's epoch the wave
-                // polls that one pair only (one transaction per round, all lanes the same address),
-                // so that workgroups waiting far ahead of the running phase leave the memory system alone.
+                const unsigned int got = load_pairs(ch, v);
+                if (__builtin_amdgcn_ballot_w64((got & 1u) == 0u) == 0) return;
+                // Not all there yet.  If part of the wave's share is, the producing phase is under way:
+                // the wave asks again at once.  If nothing is, the wave polls its first pair only (one
+                // transaction per round, all lanes the same address) until that one carries this launch's
+                // epoch, so that workgroups waiting far ahead of the running phase leave the memory system alone.
                 bool stop = false;
-                for (;;) {
+                const bool some = __builtin_amdgcn_ballot_w64((got & 2u) != 0u) != 0;
+                for (; !some;) {
                     typedef unsigned int v2u __attribute__((ext_vector_type(2)));
                     asm volatile("" ::: "memory");
                     const v2u pr = __builtin_amdgcn_raw_buffer_load_b64(rsrc, j_wave * 8, 0, 16);
                     if (j_wave >= op.N || pr.y == epoch) break;
                     ++spins;
-                    stop = __builtin_amdgcn_s_memrealtime() - t0 > spin_ticks ||
-                           ((spins & 15u) == 0 &&
-                            __hip_atomic_load(&state->error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0);
+                    // (the clock and the error word are looked at every 16th round, and on the first: a limit of zero gives up at once)
+                    if ((spins & 15u) == 1u)
+                        stop = __builtin_amdgcn_s_memrealtime() - t0 > spin_ticks ||
+                               __hip_atomic_load(&state->error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0;
                     if (stop) break;
                     __builtin_amdgcn_s_sleep(8);
                 }
@@ -227,22 +310,42 @@ exec_kernel(const ExecOp* __restrict__ ops, const ExecTask* __restrict__ tasks, 
                 m = fmaxf(m, a);
             }
         };
+        // A thread owns chunk tid of 16 elements; inputs of up to 16384 elements are so held in registers
+        // between the maximum and the rounding.  Longer ones (up to 32768) are walked twice, a chunk at a time.
+        const bool held = n_chunks <= kExecThreads;
         float hv[16];
         float m = 0.f;
         int bad = 0;
+        // (a wave none of whose lanes owns a chunk goes straight to the barrier: the vector units of the CU
+        // are shared, and what the idle waves would compute on zeros delays the ones that matter)
+        const bool wave_works = !held || tid - lane < n_chunks;
         if (held) {
-            if (op.in_ll) {
-                wait_pairs(tid, hv);
-                scale_chunk(tid, hv);
-            } else if (tid < n_chunks) {
-                load_chunk16(qd, 0, tid, true, hv);
-            } else {
+            if (wave_works) {
+                if (op.in_ll) {
+                    wait_pairs(tid, hv);
+                    if (op.in_scale && tid * 16 + 16 <= op.N) {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) hv[i] = 0.f;
+                        for (int q = 0; q < 2; ++q) {
+                            const uint32_t w[4] = {sraw[q].x, sraw[q].y, sraw[q].z, sraw[q].w};
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                hv[8 * q + 2 * i] *= half_bits_to_float((uint16_t)(w[i] & 0xFFFFu));
+                                hv[8 * q + 2 * i + 1] *= half_bits_to_float((uint16_t)(w[i] >> 16));
+                            }
+                        }
+                    } else {
+                        scale_chunk(tid, hv);
+                    }
+                } else if (tid < n_chunks) {
+                    load_chunk16(qd, 0, tid, true, hv);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) hv[i] = 0.f;
+                }
+                max_of(hv, m, bad);
             }
-            max_of(hv, m, bad);
         } else {
-            for (int c0 = 0; c0 < n_chunks; c0 += kExecThreads) {            // (whole waves: n_chunks is a multiple of 64... of 16)
+            for (int c0 = 0; c0 < n_chunks; c0 += kExecThreads) {
                 const int ch = c0 + tid;
                 if (op.in_ll) {
                     wait_pairs(ch, hv);                                        // (chunks past the end read as zeros)
@@ -257,20 +360,19 @@ exec_kernel(const ExecOp* __restrict__ ops, const ExecTask* __restrict__ tasks, 
                 if (gave_up) break;
             }
         }
-        for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-        bad = __builtin_amdgcn_ballot_w64(bad != 0) != 0;
-        if (lane == 0) {
-            red_f[wave] = m;
-            red_bad[wave] = bad;
+        if (wave_works) {
+            m = wave_reduce32(m, [](float a, float b) { return fmaxf(a, b); });
+            bad = __builtin_amdgcn_ballot_w64(bad != 0) != 0;
+            if (lane == 0) {                                // one LDS atomic per wave
+                atomicMax(lds_max, __builtin_bit_cast(unsigned int, m));      // m >= 0: its bits order like the value
+                if (bad) atomicOr(lds_bad, 1);
+            }
+            if (gave_up) *lds_abort = 1;
         }
-        if (gave_up) *lds_abort = 1;
         __syncthreads();
         if (*lds_abort) break;                              // the whole workgroup leaves (same LDS word for all)
-#pragma unroll
-        for (int w = 0; w < kExecWaves; ++w) {
-            m = fmaxf(m, red_f[w]);
-            bad |= red_bad[w];
-        }
+        m = __builtin_bit_cast(float, *lds_max);
+        bad = *lds_bad;
         int ex = 0;
         float step = 1.0f;
         if (m > 0.f && !bad) {
@@ -280,29 +382,28 @@ exec_kernel(const ExecOp* __restrict__ ops, const ExecTask* __restrict__ tasks, 
             step = ldexpf(1.0f, se);
         }
         const float inv_step = 1.0f / step;
-        long long local_sum = 0;
-        if (held) {
-            if (tid < n_chunks) local_sum = quantize_chunk16(hv, inv_step, bad != 0, (uint4*)lds_bq + bq_piece(tid, 0));
-        } else {
-            for (int c0 = 0; c0 < n_chunks; c0 += kExecThreads) {
-                const int ch = c0 + tid;
-                if (ch >= n_chunks) break;
-                if (op.in_ll) {
-                    (void)load_pairs(ch, hv);                                  // this thread has seen these pairs valid already
-                    scale_chunk(ch, hv);
-                } else {
-                    load_chunk16(qd, 0, ch, true, hv);
+        if (wave_works) {
+            long long local_sum = 0;
+            if (held) {
+                if (tid < n_chunks) local_sum = quantize_chunk16(hv, inv_step, bad != 0, (uint4*)lds_bq + bq_piece(tid, 0));
+            } else {
+                for (int c0 = 0; c0 < n_chunks; c0 += kExecThreads) {
+                    const int ch = c0 + tid;
+                    if (ch >= n_chunks) break;
+                    if (op.in_ll) {
+                        (void)load_pairs(ch, hv);                              // (this thread has seen these pairs valid already)
+                        scale_chunk(ch, hv);
+                    } else {
+                        load_chunk16(qd, 0, ch, true, hv);
+                    }
+                    local_sum += quantize_chunk16(hv, inv_step, bad != 0, (uint4*)lds_bq + bq_piece(ch, 0));
                 }
-                local_sum += quantize_chunk16(hv, inv_step, bad != 0, (uint4*)lds_bq + bq_piece(ch, 0));
             }
+            local_sum = wave_sum64(local_sum);
+            if (lane == 0) atomicAdd(lds_sum, (unsigned long long)local_sum);  // |sum| < 2^39: exact, whatever the order
         }
-        double sum = (double)local_sum;
-        for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
-        if (lane == 0) red_d[wave] = sum;
         __syncthreads();
-        double tot = 0.0;
-#pragma unroll
-        for (int w = 0; w < kExecWaves; ++w) tot += red_d[w];
+        const double tot = (double)(long long)*lds_sum;
         const double two_step = bad ? (double)__builtin_nanf("") : 2.0 * (double)step;
         const double neg_qs = -tot * (double)step;
 
@@ -310,19 +411,18 @@ exec_kernel(const ExecOp* __restrict__ ops, const ExecTask* __restrict__ tasks, 
         const int per = kExecWaves >> tk.wl;
         const int n_grp = (tk.n_rb + per - 1) / per;
         const uint32_t b_lane = (uint32_t)(bq_piece(g, n < 3 ? n : 0) * 16);     // unused columns re-read slice 0
-        ExecTask nxt = tk;
-        const bool more = ti + 1 < t_end;
-        if (more) nxt = tasks[ti + 1];
         for (int grp = 0; grp < n_grp; ++grp) {
-            // the output scales of the rows this thread will finish: requested now, used last
-            uint16_t ps[2] = {0, 0};
+            // (the output scales of the first group came with the task's first tiles; a later group requests its own now)
+            if (grp > 0) {
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const int idx = tid + u * kExecThreads;
-                const int rb = tk.rb0 + grp * per + (idx >> 7);
-                if (op.out_scale && idx < per * kTileRows && rb < tk.rb0 + tk.n_rb)
-                    ps[u] = ((gptr_u16)op.out_scale)[rb * kTileRows + (idx & 127)];
+                for (int u = 0; u < 2; ++u) {
+                    const int idx = tid + u * kExecThreads;
+                    const int rb = tk.rb0 + grp * per + (idx >> 7);
+                    if (op.out_scale && idx < per * kTileRows && rb < tk.rb0 + tk.n_rb)
+                        ps[u] = ((gptr_u16)op.out_scale)[rb * kTileRows + (idx & 127)];
+                }
             }
+            const uint16_t ps_now[2] = {ps[0], ps[1]};
             v4i acc[1][8];
 #pragma unroll
             for (int p = 0; p < 8; ++p) acc[0][p] = v4i{0, 0, 0, 0};
@@ -336,66 +436,61 @@ exec_kernel(const ExecOp* __restrict__ ops, const ExecTask* __restrict__ tasks, 
 #define NQ_LDSB(i) (*(const v4u*)(lds_bq + b_lane + (part + ((i) < last ? (i) : last) * w_steps) * (int)kBqStepBytes))
             v4u bop[2][1];
             bop[0][0] = NQ_LDSB(0);
-            int i0 = 0;
-            for (; i0 + 2 * D <= cnt; i0 += D) {
+            for (int i0 = 0; i0 < cnt; i0 += D) {
 #pragma unroll
                 for (int k = 0; k < D; ++k) {
-                    bop[(k + 1) & 1][0] = NQ_LDSB(i0 + k + 1);
-                    mac_tile<1>(acc, wbuf[k], bop[k & 1]);
-                    NQ_ISSUE(k);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
-#pragma unroll
-            for (int k = 0; k < D; ++k) {
-                if (i0 + k < cnt) {
-                    bop[(k + 1) & 1][0] = NQ_LDSB(i0 + k + 1);
-                    mac_tile<1>(acc, wbuf[k], bop[k & 1]);
-                    if (i0 + k + D < cnt) NQ_ISSUE(k);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
-#pragma unroll
-            for (int k = 0; k < D; ++k) {
-                if (i0 + D + k < cnt) {
-                    bop[(k + 1) & 1][0] = NQ_LDSB(i0 + D + k + 1);
-                    mac_tile<1>(acc, wbuf[k], bop[k & 1]);
-                    __builtin_amdgcn_sched_barrier(0);
+                    if (i0 + k < cnt) {
+                        bop[(k + 1) & 1][0] = NQ_LDSB(i0 + k + 1);
+                        mac_tile<1>(acc, wbuf[k], bop[k & 1]);
+                        if (i0 + k + D < cnt) NQ_ISSUE(k);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                 }
             }
 #undef NQ_LDSB
 #undef NQ_ISSUE
-            // the ring is empty: the next group's (or the next task's) first tiles go out before the
-            // epilogue, and long before that task's input is waited for
+            // the ring is empty: the next group's first tiles go out before the epilogue
             const int w_cur = 1 << tk.wl;
             if (grp + 1 < n_grp) NQ_PRIME(tk, grp + 1);
-            else if (more) NQ_PRIME(nxt, 0);
 
             // ---- epilogue: raw sums -> LDS, added over the W waves of a row block, scaled, stored ----
-            __syncthreads();                                // the regions (and, after the last group, the input) are free
+            __syncthreads();
+            if (tid == 0 && grp == 0) {                     // every thread has read them; the next task starts from zero
+                *lds_sum = 0;
+                *lds_max = 0;
+                *lds_bad = 0;
+            }                                // the regions (and, after the last group, the input) are free
             if (n < 3) {
                 v4i* dst = (v4i*)(lds_epi + wave * kExecEpiInts + n * kTileRows) + g;
 #pragma unroll
                 for (int p = 0; p < 8; ++p) dst[4 * p] = p == 7 ? -acc[0][p] : acc[0][p];    // rows 16p + 4g .. +3; plane 7 holds -128 * sum
             }
             __syncthreads();
-#pragma unroll
+#pragma unroll 1
             for (int u = 0; u < 2; ++u) {
                 const int idx = tid + u * kExecThreads;
+                if (idx >= per * kTileRows) break;          // (whole waves: per * 128 is a multiple of 64)
                 const int sub = idx >> 7, row = idx & 127;
                 const int rb = tk.rb0 + grp * per + sub;
                 const int grow = rb * kTileRows + row;
                 if (idx < per * kTileRows && rb < tk.rb0 + tk.n_rb && grow < op.M) {
                     int h = 0, mm = 0, l = 0;
                     const int* q = lds_epi + sub * w_cur * kExecEpiInts + row;
-                    for (int w = 0; w < w_cur; ++w, q += kExecEpiInts) {
-                        h += q[0];
-                        mm += q[kTileRows];
-                        l += q[2 * kTileRows];
+                    // (eight waves' sums requested at a time; a wave beyond the row block's W reads wave 0's region again and is not added)
+#pragma unroll 1
+                    for (int w0 = 0; w0 < w_cur; w0 += 8) {
+#pragma unroll
+                        for (int w = 0; w < 8; ++w) {
+                            const int* qw = q + (w0 + w < w_cur ? w0 + w : 0) * kExecEpiInts;
+                            const int a0 = qw[0], a1 = qw[kTileRows], a2 = qw[2 * kTileRows];
+                            h += w0 + w < w_cur ? a0 : 0;
+                            mm += w0 + w < w_cur ? a1 : 0;
+                            l += w0 + w < w_cur ? a2 : 0;
+                        }
                     }
                     const double raw = fma((double)h, 65536.0, fma((double)mm, 256.0, (double)l));
                     double val = fma(raw, __builtin_ldexp(two_step, -(row >> 4)), neg_qs);    // exact; rounded once, below
-                    if (op.out_scale) val *= (double)half_bits_to_float(ps[u]);
+                    if (op.out_scale) val *= (double)half_bits_to_float(u ? ps_now[1] : ps_now[0]);
                     float f = (float)val;
                     if (op.out) store_out(op.out, op.out_dtype, (size_t)grow, f, op.out_scale != nullptr);
                     if (op.out_ll) {
@@ -407,10 +502,18 @@ exec_kernel(const ExecOp* __restrict__ ops, const ExecTask* __restrict__ tasks, 
                 }
             }
         }
+        // The next task's first tiles and scales go out now, behind this task's stores and ahead of the wait
+        // for that task's input.  (Not earlier: vector memory returns in order, so anything this task still
+        // had to wait for -- a scale, a spilled register -- would have waited for those tiles as well.)
+        if (more) {
+            NQ_PRIME(nxt, 0);
+            NQ_PREFETCH_SCALES(nxt);
+        }
         ++ti;
         tk = nxt;
     }
 #undef NQ_PRIME
+#undef NQ_PREFETCH_SCALES
 
     // ---- leave: report a missed deadline; the last workgroup out advances the epoch ----
     __syncthreads();
@@ -486,8 +589,7 @@ using namespace nq;
 struct nq_exec_s {
     int n, n_wg, device;
     std::vector<nq_handle> handles;
-    void* alloc;                    // ops | tasks | task_begin | state | pairs
-    ExecOp* ops;
+    void* alloc;                    // tasks | task_begin | state | pairs
     ExecTask* tasks;
     int* task_begin;
     ExecState* state;
@@ -591,7 +693,7 @@ extern "C" int nq_exec_create(nq_exec* out, const nq_handle* hs, const void* con
         max_steps = std::max(max_steps, (int)std::max(n_steps(d_in[i]), n_steps(r[i])));
     }
     e->bq_bytes = max_steps * (int)kBqStepBytes;
-    e->lds_bytes = (size_t)e->bq_bytes + (size_t)kExecWaves * kExecEpiInts * 4 + kExecWaves * (4 + 8 + 4) + 16;
+    e->lds_bytes = (size_t)e->bq_bytes + (size_t)kExecWaves * kExecEpiInts * 4 + 32;
     hipError_t he = hipFuncSetAttribute((const void*)exec_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (he == hipSuccess)
         he = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)exec_kernel, kExecThreads, e->lds_bytes);
@@ -603,40 +705,34 @@ extern "C" int nq_exec_create(nq_exec* out, const nq_handle* hs, const void* con
     plan_tasks(d_out.data(), d_in.data(), r.data(), level_of, n, e->n_wg, planned);
     // per workgroup, in phase order (plan_tasks emits phases in order: a stable sort by workgroup keeps it)
     std::stable_sort(planned.begin(), planned.end(), [](const PlannedTask& a, const PlannedTask& b) { return a.wg < b.wg; });
-    std::vector<ExecTask> tasks(planned.size());
     std::vector<int> begin(e->n_wg + 1, 0);
-    for (size_t k = 0; k < planned.size(); ++k) {
-        int wl = 0;
-        while ((1 << wl) < planned[k].W) ++wl;
-        tasks[k] = ExecTask{2 * planned[k].layer + planned[k].stage, planned[k].rb0, planned[k].n_rb, wl};
-        begin[planned[k].wg + 1] += 1;
-    }
+    for (size_t k = 0; k < planned.size(); ++k) begin[planned[k].wg + 1] += 1;
     for (int w = 0; w < e->n_wg; ++w) begin[w + 1] += begin[w];
-    e->n_tasks = (int)tasks.size();
+    e->n_tasks = (int)planned.size();
 
     auto al = [](size_t v) { return (v + 255) / 256 * 256; };
-    const size_t ops_b = al(sizeof(ExecOp) * 2 * n), tasks_b = al(sizeof(ExecTask) * tasks.size()),
-                 begin_b = al(sizeof(int) * begin.size()), state_b = al(sizeof(ExecState));
+    const size_t tasks_b = al(sizeof(ExecTask) * planned.size()), begin_b = al(sizeof(int) * begin.size()),
+                 state_b = al(sizeof(ExecState));
     size_t pairs = 0;
     std::vector<size_t> t_off(n), y_off(n);
     for (int i = 0; i < n; ++i) {
         t_off[i] = pairs; pairs += al((size_t)hs[i]->r * 8);
         y_off[i] = pairs; if (consumed[i]) pairs += al((size_t)hs[i]->d_out * 8);
     }
-    const size_t total = ops_b + tasks_b + begin_b + state_b + pairs;
+    const size_t total = tasks_b + begin_b + state_b + pairs;
     he = hipMalloc(&e->alloc, total);
     if (he != hipSuccess) { delete e; return hip_fail(he, "hipMalloc(executor)", __FILE__, __LINE__); }
     char* c = (char*)e->alloc;
-    e->ops = (ExecOp*)c; c += ops_b;
     e->tasks = (ExecTask*)c; c += tasks_b;
     e->task_begin = (int*)c; c += begin_b;
     e->state = (ExecState*)c; c += state_b;
     char* pair_base = c;
-    std::vector<ExecOp> ops(2 * n);
+    // the two stages of every layer
+    std::vector<ExecTask> ops(2 * n);
     for (int i = 0; i < n; ++i) {
         nq_handle h = hs[i];
-        ExecOp& a = ops[2 * i];
-        a = ExecOp{};
+        ExecTask& a = ops[2 * i];
+        a = ExecTask{};
         a.tiles = h->vt_tiles;
         a.in = src[i] >= 0 ? (const void*)(pair_base + y_off[src[i]]) : xs[i];
         a.in_ll = src[i] >= 0;
@@ -645,8 +741,8 @@ extern "C" int nq_exec_create(nq_exec* out, const nq_handle* hs, const void* con
         a.out_ll = (unsigned long long*)(pair_base + t_off[i]);
         a.M = (int)h->r; a.N = (int)h->d_in; a.n_steps = (int)n_steps(h->d_in);
         a.in_dtype = h->x_dtype; a.out_dtype = NQ_F32;
-        ExecOp& b = ops[2 * i + 1];
-        b = ExecOp{};
+        ExecTask& b = ops[2 * i + 1];
+        b = ExecTask{};
         b.tiles = h->u_tiles;
         b.in = pair_base + t_off[i]; b.in_ll = 1;
         b.in_scale = h->s_mid; b.out_scale = h->s_out;
@@ -655,10 +751,18 @@ extern "C" int nq_exec_create(nq_exec* out, const nq_handle* hs, const void* con
         b.M = (int)h->d_out; b.N = (int)h->r; b.n_steps = (int)n_steps(h->r);
         b.in_dtype = NQ_F32; b.out_dtype = h->y_dtype;
     }
+    std::vector<ExecTask> tasks(planned.size());
+    for (size_t k = 0; k < planned.size(); ++k) {
+        tasks[k] = ops[2 * planned[k].layer + planned[k].stage];
+        tasks[k].rb0 = planned[k].rb0;
+        tasks[k].n_rb = planned[k].n_rb;
+        int wl = 0;
+        while ((1 << wl) < planned[k].W) ++wl;
+        tasks[k].wl = wl;
+    }
     ExecState st0{1u, 0u, 0, 0};
     he = hipMemset(e->alloc, 0, total);
-    if (he == hipSuccess) he = hipMemcpy(e->ops, ops.data(), sizeof(ExecOp) * ops.size(), hipMemcpyHostToDevice);
-    if (he == hipSuccess && !tasks.empty()) he = hipMemcpy(e->tasks, tasks.data(), sizeof(ExecTask) * tasks.size(), hipMemcpyHostToDevice);
+    if (he == hipSuccess) he = hipMemcpy(e->tasks, tasks.data(), sizeof(ExecTask) * tasks.size(), hipMemcpyHostToDevice);
     if (he == hipSuccess) he = hipMemcpy(e->task_begin, begin.data(), sizeof(int) * begin.size(), hipMemcpyHostToDevice);
     if (he == hipSuccess) he = hipMemcpy(e->state, &st0, sizeof st0, hipMemcpyHostToDevice);
     if (he == hipSuccess) he = hipDeviceSynchronize();
@@ -677,7 +781,7 @@ extern "C" int nq_exec_forward(nq_exec e, void* stream)
     // wall-clock limit of every wait, in ticks of the 100 MHz constant clock (default 2 s)
     const int us = opt(OPT_EXEC_SPIN_LIMIT_US);
     const unsigned long long ticks = us >= 0 ? (unsigned long long)us * 100ull : 200000000ull;
-    hipLaunchKernelGGL(exec_kernel, dim3(e->n_wg), dim3(kExecThreads), e->lds_bytes, (hipStream_t)stream, e->ops, e->tasks,
+    hipLaunchKernelGGL(exec_kernel, dim3(e->n_wg), dim3(kExecThreads), e->lds_bytes, (hipStream_t)stream, e->tasks,
                        e->task_begin, e->state, e->bq_bytes, ticks);
     NQ_HIP(hipGetLastError());
     return NQ_OK;

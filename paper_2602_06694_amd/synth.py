@@ -195,3 +195,50 @@ def iter_config_layers(cfg: int, max_layers: int | None = None) -> Iterator[Tupl
     for layer in range(n):
         for li, shp in enumerate(c.block):
             yield layer, li, shp
+
+
+# ---- a decoder stack whose layers feed one another --------------------------------------------
+# The seven projections of a block in the order a decoder calls them, as levels of mutually
+# independent layers, and which layer's output each one reads when the stack is run as a chain
+# (the attention, normalisation and activation kernels that sit in between in a real model are
+# not part of this path): o reads q's output, gate and up read o's, down reads gate's, and the q, k,
+# v of the next block read down's.
+BLOCK_LEVEL = (0, 0, 0, 1, 2, 2, 3)
+BLOCK_SOURCE = (-1, -1, -1, 0, 3, 3, 4)       # index inside the block; -1: the previous block's down (or the stack's input)
+
+
+def chain_spec(n_blocks: int):
+    """(level, source) of every layer of n_blocks chained blocks; source -1 = the stack's input."""
+    level, src = [], []
+    for b in range(n_blocks):
+        for li in range(7):
+            level.append(4 * b + BLOCK_LEVEL[li])
+            src.append(7 * b + BLOCK_SOURCE[li] if BLOCK_SOURCE[li] >= 0 else (7 * b - 1 if b else -1))
+    return level, src
+
+
+def gen_chained_stack(cfg: int, n_blocks: int | None = None) -> List[LayerData]:
+    """The layers of config 3 / 4 with their scale vectors multiplied by powers of two (exact in fp16)
+    such that activations keep a magnitude near one along the chain q -> o -> gate -> down -> q ...:
+    a layer with i.i.d. signs multiplies the rms of its input by about 1.17 sqrt(r d_in), which a real
+    model's normalisation layers would absorb.  Only the data changes; the operator is the same."""
+    import math
+    c = CONFIGS[cfg]
+    n_blocks = c.n_layers if n_blocks is None else n_blocks
+    out: List[LayerData] = []
+    carry = {}                                   # log2 of the rms at each layer's output, relative to the stack's input
+    _, src = chain_spec(n_blocks)
+    for b in range(n_blocks):
+        for li, shp in enumerate(c.block):
+            i = 7 * b + li
+            d = gen_layer(cfg, b, li, shp)
+            at_input = carry[src[i]] if src[i] >= 0 else 0.0
+            gain = math.log2(1.17 * math.sqrt(shp.r * shp.d_in))
+            k = int(round(at_input + gain))      # bring the output back to about one
+            k = max(0, min(k, 18))               # (the scales stay normal fp16 numbers: 0.1 * 2^-9 > 6.1e-5)
+            k_in = k // 2
+            s_in = (d.s_in.astype(np.float32) * np.float32(2.0 ** -k_in)).astype(np.float16)
+            s_out = (d.s_out.astype(np.float32) * np.float32(2.0 ** -(k - k_in))).astype(np.float16)
+            carry[i] = at_input + gain - k
+            out.append(LayerData(shp, d.U_words, d.V_words, s_out, s_in))
+    return out

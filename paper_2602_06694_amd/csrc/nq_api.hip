@@ -38,7 +38,7 @@ static const OptEntry kOptTable[OPT_COUNT] = {
     {"share_min_batch", false}, {"stream_steps", false}, {"schedule_full", false}, {"fuse_max_mb", false},
     {"no_fuse", true}, {"no_selfq", true}, {"no_selfq_c2", true}, {"no_resident", true}, {"no_quant_wave", true},
     {"pf_splits1", false}, {"pf_splits2", false}, {"pf_tg1", false}, {"pf_tg2", false}, {"pf_ks1", false}, {"pf_ks2", false},
-    {"pf_verbose", true}, {"exec_spin_limit_us", false},
+    {"pf_verbose", true}, {"exec_spin_limit_us", false}, {"no_small_layer", true}, {"small_layer_kb", false},
 };
 static int g_opt[OPT_COUNT];
 static std::once_flag g_opt_once;
@@ -574,6 +574,8 @@ static int decode_once(nq_handle h, const DecodeWorkspace& w, const void* x, voi
         return launch_valu_gemv(h->u_tiles, w.t, NQ_F32, w.t_stride, h->s_mid, unscaled ? nullptr : h->s_out, y, h->y_dtype,
                                 (int)h->d_out, h->d_out, h->r, batch, s);
     }
+    // a small layer on its own: one workgroup runs both stages in one launch, t staying in LDS
+    if (small_layer_fits(h, batch)) return launch_small_layer(h, w, x, y, unscaled, s);
     QuantDesc qx = make_qx(h, w, x);
     StageDesc s1 = make_s1(h, w);
     QuantDesc qt = make_qt(h, w);

@@ -34,11 +34,12 @@
 
 namespace nq {
 
-constexpr int kExecWaves = 16;
+constexpr int kExecWaves = 8;                      // two per SIMD
 constexpr int kExecThreads = 64 * kExecWaves;
 constexpr int kExecRing = 8;                       // sign tiles a wave keeps in flight
 constexpr int kExecMaxSteps = 512;                 // longest reduction: 32768 elements (96 KiB of LDS as fixed point)
 constexpr int kExecEpiInts = 3 * kTileRows;        // per wave: the three slice columns x 128 rows
+constexpr int kExecHeld = 4;                       // 16-element chunks of the input a thread keeps in registers (inputs of up to 16384 elements)
 
 // One task of one workgroup: a run of row blocks of one stage of one layer, with everything the
 // kernel needs to know about that stage in the record itself -- a workgroup's records are
@@ -46,14 +47,15 @@ constexpr int kExecEpiInts = 3 * kTileRows;        // per wave: the three slice 
 // W = 1 << wl waves share a row block, 16 / W row blocks are worked on side by side.
 struct ExecTask {
     const uint32_t* tiles;          // sign tiles of A (V^T or U)
-    const void* in;                 // the input vector: plain elements of in_dtype, or pairs (in_ll)
+    const void* in;                 // the input vector: plain elements of in_dtype (in_ll 0), pairs (1), or none: the LDS array (2)
     const uint16_t* in_scale;       // fp16 [N] or nullptr
     const uint16_t* out_scale;      // fp16 [M rounded up to whole row blocks] or nullptr
     void* out;                      // plain output [M] of out_dtype, or nullptr
     unsigned long long* out_ll;     // pairs [M] for the stages that read this output in the same launch, or nullptr
     int M, N, n_steps, in_dtype, out_dtype, in_ll;
     int rb0, n_rb, wl;
-    int pad[3];
+    int out_lds;                    // the (fp32) output also goes to the workgroup's LDS array, for its next task (in_ll == 2)
+    int pad[2];
 };
 static_assert(sizeof(ExecTask) == 96, "task record");
 
@@ -119,9 +121,9 @@ __device__ __forceinline__ long long wave_sum64(long long v)
 // LDS: [bq_bytes] the task's input as fixed point (layout of the global buffers of the streaming
 // kernels) | [16][3][128] raw sums of the waves | sum of q, largest magnitude, flags
 // ---------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(kExecThreads)
-exec_kernel(const ExecTask* __restrict__ tasks, const int* __restrict__ task_begin,
-            ExecState* __restrict__ state, int bq_bytes, unsigned long long spin_ticks)
+// tasks[ti .. t_end) of this workgroup; state == nullptr: a lone workgroup whose tasks hand over through LDS only
+__device__ __forceinline__ void exec_body(const ExecTask* __restrict__ tasks, int ti, const int t_end,
+                                          ExecState* __restrict__ state, int bq_bytes, unsigned long long spin_ticks)
 {
     extern __shared__ int lds[];
     constexpr int D = kExecRing;
@@ -134,14 +136,13 @@ exec_kernel(const ExecTask* __restrict__ tasks, const int* __restrict__ task_beg
     unsigned int* const lds_max = (unsigned int*)(lds_sum + 1);
     int* const lds_bad = (int*)(lds_max + 1);
     int* const lds_abort = lds_bad + 1;
+    float* const lds_t = (float*)(lds_sum + 4);             // (past the 32 bytes of words above) an output kept in LDS for the next task of this workgroup
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 4, n = lane & 15;
-    const unsigned int epoch = state->epoch;                // written by the previous launch (or the host)
-    int ti = task_begin[blockIdx.x];
-    const int t_end = task_begin[blockIdx.x + 1];
+    const unsigned int epoch = state ? state->epoch : 0u;   // written by the previous launch (or the host)
     if (tid == 0) {
         *lds_abort = 0;
         *lds_sum = 0;
@@ -182,16 +183,21 @@ exec_kernel(const ExecTask* __restrict__ tasks, const int* __restrict__ task_beg
     // handed over by another stage and fits one chunk per thread -- and the output scales of the rows this
     // thread finishes in the task's first group.  All of them are requested before the task's input is
     // waited for and converted only when they are used.
-    v4u sraw[2] = {v4u{0, 0, 0, 0}, v4u{0, 0, 0, 0}};
+    v4u sraw[kExecHeld][2];
+#pragma unroll
+    for (int c = 0; c < kExecHeld; ++c) sraw[c][0] = sraw[c][1] = v4u{0, 0, 0, 0};
     uint16_t ps[2] = {0, 0};
 #define NQ_PREFETCH_SCALES(t)                                                                      \
     do {                                                                                           \
-        const uint16_t* const is_ = (t).in_scale;                                          \
-        const int n_ = (t).N;                                                              \
-        if (is_ && (t).in_ll && tid * 16 + 16 <= n_) {                                     \
-            const gptr_v4u sp_ = (gptr_v4u)(is_ + tid * 16);                                       \
-            sraw[0] = sp_[0];                                                                      \
-            sraw[1] = sp_[1];                                                                      \
+        const uint16_t* const is_ = (t).in_scale;                                                  \
+        const int n_ = (t).N;                                                                      \
+        _Pragma("unroll") for (int c_ = 0; c_ < kExecHeld; ++c_) {                                 \
+            const int j_ = (tid + c_ * kExecThreads) * 16;                                         \
+            if (is_ && (t).in_ll && j_ + 16 <= n_) {                                               \
+                const gptr_v4u sp_ = (gptr_v4u)(is_ + j_);                                         \
+                sraw[c_][0] = sp_[0];                                                              \
+                sraw[c_][1] = sp_[1];                                                              \
+            }                                                                                      \
         }                                                                                          \
         const uint16_t* const os_ = (t).out_scale;                                         \
         const int per_ = kExecWaves >> (t).wl;                                                     \
@@ -310,54 +316,58 @@ exec_kernel(const ExecTask* __restrict__ tasks, const int* __restrict__ task_beg
                 m = fmaxf(m, a);
             }
         };
-        // A thread owns chunk tid of 16 elements; inputs of up to 16384 elements are so held in registers
-        // between the maximum and the rounding.  Longer ones (up to 32768) are walked twice, a chunk at a time.
-        const bool held = n_chunks <= kExecThreads;
-        float hv[16];
+        // A thread owns chunks tid, tid + 256, ...; inputs of up to 16384 elements (four chunks per thread) stay in
+        // registers between the maximum and the rounding, longer ones (up to 32768) are fetched twice.
+        const int n_c = (n_chunks + kExecThreads - 1) / kExecThreads;           // chunks per thread
+        const bool held = n_c <= kExecHeld;
+        if (op.in_ll == 2) __syncthreads();                 // the LDS array of this workgroup's previous task is complete
+        float hv[kExecHeld][16];
         float m = 0.f;
         int bad = 0;
-        // (a wave none of whose lanes owns a chunk goes straight to the barrier: the vector units of the CU
-        // are shared, and what the idle waves would compute on zeros delays the ones that matter)
-        const bool wave_works = !held || tid - lane < n_chunks;
-        if (held) {
-            if (wave_works) {
-                if (op.in_ll) {
-                    wait_pairs(tid, hv);
-                    if (op.in_scale && tid * 16 + 16 <= op.N) {
+        // chunk ch of the input, scaled, wherever it comes from (c: which of the thread's chunks, for the prefetched scales)
+        auto fetch = [&](int ch, int c, float v[16]) {
+            if (op.in_ll == 0) {
+                if (ch < n_chunks) load_chunk16(qd, 0, ch, true, v);
+                else {
 #pragma unroll
-                        for (int q = 0; q < 2; ++q) {
-                            const uint32_t w[4] = {sraw[q].x, sraw[q].y, sraw[q].z, sraw[q].w};
-#pragma unroll
-                            for (int i = 0; i < 4; ++i) {
-                                hv[8 * q + 2 * i] *= half_bits_to_float((uint16_t)(w[i] & 0xFFFFu));
-                                hv[8 * q + 2 * i + 1] *= half_bits_to_float((uint16_t)(w[i] >> 16));
-                            }
-                        }
-                    } else {
-                        scale_chunk(tid, hv);
-                    }
-                } else if (tid < n_chunks) {
-                    load_chunk16(qd, 0, tid, true, hv);
-                } else {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) hv[i] = 0.f;
+                    for (int i = 0; i < 16; ++i) v[i] = 0.f;
                 }
-                max_of(hv, m, bad);
+                return;
+            }
+            if (op.in_ll == 1) {
+                wait_pairs(ch, v);                          // (a chunk past the end reads as zeros)
+            } else {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) v[i] = ch * 16 + i < op.N ? lds_t[ch * 16 + i] : 0.f;
+            }
+            if (c < kExecHeld && op.in_scale && ch * 16 + 16 <= op.N) {
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const uint32_t w[4] = {sraw[c][q].x, sraw[c][q].y, sraw[c][q].z, sraw[c][q].w};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        v[8 * q + 2 * i] *= half_bits_to_float((uint16_t)(w[i] & 0xFFFFu));
+                        v[8 * q + 2 * i + 1] *= half_bits_to_float((uint16_t)(w[i] >> 16));
+                    }
+                }
+            } else {
+                scale_chunk(ch, v);
+            }
+        };
+        // (a wave none of whose lanes owns a chunk goes straight to the barrier)
+        const bool wave_works = tid - lane < n_chunks;
+        if (held) {
+#pragma unroll
+            for (int c = 0; c < kExecHeld; ++c) {
+                if (c < n_c && tid - lane + c * kExecThreads < n_chunks) {
+                    fetch(tid + c * kExecThreads, c, hv[c]);
+                    max_of(hv[c], m, bad);
+                }
             }
         } else {
-            for (int c0 = 0; c0 < n_chunks; c0 += kExecThreads) {
-                const int ch = c0 + tid;
-                if (op.in_ll) {
-                    wait_pairs(ch, hv);                                        // (chunks past the end read as zeros)
-                    scale_chunk(ch, hv);
-                } else if (ch < n_chunks) {
-                    load_chunk16(qd, 0, ch, true, hv);
-                } else {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) hv[i] = 0.f;
-                }
-                max_of(hv, m, bad);
-                if (gave_up) break;
+            for (int c = 0; c < n_c && !gave_up; ++c) {
+                fetch(tid + c * kExecThreads, kExecHeld, hv[0]);
+                max_of(hv[0], m, bad);
             }
         }
         if (wave_works) {
@@ -385,18 +395,17 @@ exec_kernel(const ExecTask* __restrict__ tasks, const int* __restrict__ task_beg
         if (wave_works) {
             long long local_sum = 0;
             if (held) {
-                if (tid < n_chunks) local_sum = quantize_chunk16(hv, inv_step, bad != 0, (uint4*)lds_bq + bq_piece(tid, 0));
+#pragma unroll
+                for (int c = 0; c < kExecHeld; ++c) {
+                    const int ch = tid + c * kExecThreads;
+                    if (c < n_c && ch < n_chunks)
+                        local_sum += quantize_chunk16(hv[c], inv_step, bad != 0, (uint4*)lds_bq + bq_piece(ch, 0));
+                }
             } else {
-                for (int c0 = 0; c0 < n_chunks; c0 += kExecThreads) {
-                    const int ch = c0 + tid;
-                    if (ch >= n_chunks) break;
-                    if (op.in_ll) {
-                        (void)load_pairs(ch, hv);                              // (this thread has seen these pairs valid already)
-                        scale_chunk(ch, hv);
-                    } else {
-                        load_chunk16(qd, 0, ch, true, hv);
-                    }
-                    local_sum += quantize_chunk16(hv, inv_step, bad != 0, (uint4*)lds_bq + bq_piece(ch, 0));
+                for (int c = 0; c < n_c; ++c) {
+                    const int ch = tid + c * kExecThreads;
+                    fetch(ch, kExecHeld, hv[0]);            // (pairs this thread has already seen valid)
+                    if (ch < n_chunks) local_sum += quantize_chunk16(hv[0], inv_step, bad != 0, (uint4*)lds_bq + bq_piece(ch, 0));
                 }
             }
             local_sum = wave_sum64(local_sum);
@@ -476,11 +485,11 @@ exec_kernel(const ExecTask* __restrict__ tasks, const int* __restrict__ task_beg
                 if (idx < per * kTileRows && rb < tk.rb0 + tk.n_rb && grow < op.M) {
                     int h = 0, mm = 0, l = 0;
                     const int* q = lds_epi + sub * w_cur * kExecEpiInts + row;
-                    // (eight waves' sums requested at a time; a wave beyond the row block's W reads wave 0's region again and is not added)
+                    // (the waves' sums requested together; a wave beyond the row block's W reads wave 0's region again and is not added)
 #pragma unroll 1
-                    for (int w0 = 0; w0 < w_cur; w0 += 8) {
+                    for (int w0 = 0; w0 < w_cur; w0 += kExecWaves) {
 #pragma unroll
-                        for (int w = 0; w < 8; ++w) {
+                        for (int w = 0; w < kExecWaves; ++w) {
                             const int* qw = q + (w0 + w < w_cur ? w0 + w : 0) * kExecEpiInts;
                             const int a0 = qw[0], a1 = qw[kTileRows], a2 = qw[2 * kTileRows];
                             h += w0 + w < w_cur ? a0 : 0;
@@ -493,6 +502,7 @@ exec_kernel(const ExecTask* __restrict__ tasks, const int* __restrict__ task_beg
                     if (op.out_scale) val *= (double)half_bits_to_float(u ? ps_now[1] : ps_now[0]);
                     float f = (float)val;
                     if (op.out) store_out(op.out, op.out_dtype, (size_t)grow, f, op.out_scale != nullptr);
+                    if (op.out_lds) lds_t[grow] = f;
                     if (op.out_ll) {
                         // what a reader of the stored output would see: the value after its rounding to the output type
                         if (op.out_dtype == NQ_BF16) f = bf16_bits_to_float(float_to_bf16_bits(f));
@@ -517,7 +527,7 @@ exec_kernel(const ExecTask* __restrict__ tasks, const int* __restrict__ task_beg
 
     // ---- leave: report a missed deadline; the last workgroup out advances the epoch ----
     __syncthreads();
-    if (tid == 0) {
+    if (tid == 0 && state) {
         if (*lds_abort) __hip_atomic_store(&state->error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const unsigned int left = __hip_atomic_fetch_add(&state->done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (left + 1 == gridDim.x) {
@@ -526,6 +536,25 @@ exec_kernel(const ExecTask* __restrict__ tasks, const int* __restrict__ task_beg
             __hip_atomic_store(&state->epoch, e == 0 ? 1u : e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
+}
+
+__global__ void __launch_bounds__(kExecThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
+exec_kernel(const ExecTask* __restrict__ tasks, const int* __restrict__ task_begin,
+            ExecState* __restrict__ state, int bq_bytes, unsigned long long spin_ticks)
+{
+    exec_body(tasks, task_begin[blockIdx.x], task_begin[blockIdx.x + 1], state, bq_bytes, spin_ticks);
+}
+
+// One small layer, both stages, by ONE workgroup in one launch: t stays in LDS between the stages
+// (the two-stage GEMV of Appendix E.2 with its intermediate in shared memory).  The two task records are
+// kernel arguments.
+struct ExecPair {
+    ExecTask t[2];
+};
+__global__ void __launch_bounds__(kExecThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
+exec_small_kernel(ExecPair pair, int bq_bytes)
+{
+    exec_body(pair.t, 0, 2, nullptr, bq_bytes, 0ull);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -627,6 +656,61 @@ extern "C" int nq_exec_plan_tasks(const int64_t* d_out, const int64_t* d_in, con
     return NQ_OK;
 }
 
+// ---------------------------------------------------------------------------------------------
+// a lone small layer at batch 1: both stages in one launch by one workgroup (see exec_small_kernel)
+// ---------------------------------------------------------------------------------------------
+namespace nq {
+
+// Off by default: measured on config 1 (1024 x 1024, r = 256, 66 KB of bits) one workgroup doing all ten row
+// blocks of the two stages in turn takes 13.3 us per forward where the two launches that spread them over ten
+// CUs take 10.2 us -- on this chip the latency of a stage is a wave's instruction stream, not the launch, and a
+// lone workgroup serialises what the CUs do side by side.  The option "small_layer_kb" gives the packed size
+// (both factors, KiB) up to which a lone layer at batch 1 takes this path.
+constexpr int kSmallLayerKiB = 0;
+
+bool small_layer_fits(nq_handle h, int batch)
+{
+    if (batch != 1 || opt_flag(OPT_NO_SMALL_LAYER)) return false;
+    if (h->d_in > 16384 || h->r > 8192) return false;       // one chunk per thread; t in LDS
+    const size_t tile_bytes = (tile_words(h->r, h->d_in) + tile_words(h->d_out, h->r)) * 4;
+    return tile_bytes <= (size_t)opt_or(OPT_SMALL_LAYER_KB, kSmallLayerKiB) * 1024;
+}
+
+int launch_small_layer(nq_handle h, const DecodeWorkspace& w, const void* x, void* y, bool unscaled, hipStream_t s)
+{
+    static bool attr_set = false;
+    ExecPair p{};
+    // waves per row block: as many as leave every row block of the stage a place in ONE round (else one wave each, several rounds)
+    auto wl_for = [](int64_t n_rb) {
+        int W = kExecWaves;
+        while (W > 1 && n_rb * W > kExecWaves) W /= 2;
+        int wl = 0;
+        while ((1 << wl) < W) ++wl;
+        return wl;
+    };
+    ExecTask& a = p.t[0];
+    a.tiles = h->vt_tiles; a.in = x; a.in_ll = 0; a.in_scale = h->s_in; a.out_scale = nullptr;
+    a.out = w.t; a.out_ll = nullptr; a.out_lds = 1;
+    a.M = (int)h->r; a.N = (int)h->d_in; a.n_steps = (int)n_steps(h->d_in); a.in_dtype = h->x_dtype; a.out_dtype = NQ_F32;
+    a.rb0 = 0; a.n_rb = (int)n_rowblocks(h->r); a.wl = wl_for(a.n_rb);
+    ExecTask& b = p.t[1];
+    b.tiles = h->u_tiles; b.in = nullptr; b.in_ll = 2; b.in_scale = h->s_mid; b.out_scale = unscaled ? nullptr : h->s_out;
+    b.out = y; b.out_ll = nullptr; b.out_lds = 0;
+    b.M = (int)h->d_out; b.N = (int)h->r; b.n_steps = (int)n_steps(h->r); b.in_dtype = NQ_F32; b.out_dtype = h->y_dtype;
+    b.rb0 = 0; b.n_rb = (int)n_rowblocks(h->d_out); b.wl = wl_for(b.n_rb);
+    const int bq_bytes = (int)std::max(n_steps(h->d_in), n_steps(h->r)) * (int)kBqStepBytes;
+    const size_t lds_bytes = (size_t)bq_bytes + (size_t)kExecWaves * kExecEpiInts * 4 + 32 + (size_t)round_up(h->r, 16) * 4;
+    if (!attr_set) {
+        NQ_HIP(hipFuncSetAttribute((const void*)exec_small_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(exec_small_kernel, dim3(1), dim3(kExecThreads), lds_bytes, s, p, bq_bytes);
+    NQ_HIP(hipGetLastError());
+    return NQ_OK;
+}
+
+}  // namespace nq
+
 extern "C" int nq_exec_destroy(nq_exec e)
 {
     if (!e) return NQ_OK;
@@ -684,7 +768,7 @@ extern "C" int nq_exec_create(nq_exec* out, const nq_handle* hs, const void* con
     if (!e) return exec_fail(NQ_E_HIP, "nq_exec_create: out of host memory");
     e->n = n; e->device = hs[0]->device; e->alloc = nullptr;
     e->handles.assign(hs, hs + n);
-    // one workgroup per CU, and only as many as can be resident together
+    // up to two workgroups per CU, and only as many as can be resident together
     int per_cu = 0;
     std::vector<int64_t> d_out(n), d_in(n), r(n);
     int max_steps = 4;
@@ -699,7 +783,7 @@ extern "C" int nq_exec_create(nq_exec* out, const nq_handle* hs, const void* con
         he = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)exec_kernel, kExecThreads, e->lds_bytes);
     if (he != hipSuccess) { delete e; return hip_fail(he, "occupancy query (executor)", __FILE__, __LINE__); }
     if (per_cu < 1) { delete e; return exec_fail(NQ_E_UNSUPPORTED, "nq_exec_create: the executor's workgroup does not fit a CU"); }
-    e->n_wg = device_cu_count();
+    e->n_wg = device_cu_count() * std::min(per_cu, 2);
 
     std::vector<PlannedTask> planned;
     plan_tasks(d_out.data(), d_in.data(), r.data(), level_of, n, e->n_wg, planned);

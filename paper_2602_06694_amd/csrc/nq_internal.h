@@ -117,6 +117,8 @@ enum Opt {
     OPT_PF_KS1, OPT_PF_KS2,             // halves of the reduction taken inside a workgroup (1 or 2)
     OPT_PF_VERBOSE,         // flag: print the chosen prefill tiling
     OPT_EXEC_SPIN_LIMIT_US, // wall-clock limit, in microseconds, of every wait inside the dependent-layer executor (2 s)
+    OPT_NO_SMALL_LAYER,     // flag: a lone small layer at batch 1 never takes the one-workgroup, one-launch kernel
+    OPT_SMALL_LAYER_KB,     // packed size (KiB, both factors) up to which it does (160)
     OPT_COUNT
 };
 int opt(Opt o);                                        // -1 when unset
@@ -255,6 +257,10 @@ int launch_valu_gemv(const uint32_t* tiles, const void* x, int x_dtype, int x_st
 int device_cu_count();
 int schedule_full_rowblocks();
 int shared_min_batch();          // smallest batch that takes the shared-input kernel in launches that fill the chip            // row blocks from which a launch counts as filling the chip
+
+// ---- launchers (nq_exec.hip) ---------------------------------------------------------------
+bool small_layer_fits(nq_handle h, int batch);
+int launch_small_layer(nq_handle h, const DecodeWorkspace& w, const void* x, void* y, bool unscaled, hipStream_t s);
 
 // ---- launchers (nq_prefill.hip) ------------------------------------------------------------
 struct PrefillArgs {

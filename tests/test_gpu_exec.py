@@ -225,3 +225,51 @@ def test_executor_argument_checks():
         nq.nq_exec_create(hs[:3] + [wrong.h] + hs[4:], c.xs, c.ys, list(LEVELS))
     wrong.close()
     c.close()
+
+
+@pytest.mark.parametrize("shape", [(1024, 1024, 256), (300, 131, 33), (1, 1, 1), (2048, 200, 64), (128, 16000, 8), (129, 65, 4000)])
+def test_small_layer_in_one_launch_matches_the_two_launch_path(shape, nqopt):
+    """A lone small layer at batch 1 can run both stages in ONE launch by one workgroup, t staying in LDS (an
+    option: off by default): same arithmetic, so bit-identical to the two-launch path, t included; also with a
+    rank-wise scale, a 16-bit output and without the output scale."""
+    import torch
+    d_out, d_in, r = shape
+    for y_dtype, mid in (("f32", False), ("bf16", True)):
+        L = Layer(d_out, d_in, r, "bf16", seed=9100 + d_out, y_dtype=y_dtype)
+        if mid:
+            nq.nq_binlr_set_mid_scale(L.h, (np.random.default_rng(9101).standard_normal(r) * 0.5 + 1.0).astype(np.float16))
+        x_np = synth.gen_x(1, d_in, 9102, "bf16")
+        x = to_device(x_np, "bf16")
+        outs = {}
+        for small in (True, False):
+            nqopt.set("small_layer_kb", 4096 if small else 0)
+            tdt = torch.float32 if y_dtype == "f32" else torch.bfloat16
+            y = torch.full((1, d_out), float("nan"), dtype=tdt, device="cuda")
+            z = torch.full((1, d_out), float("nan"), dtype=tdt, device="cuda")
+            nq.nq_binlr_forward(L.h, x, y, 1)
+            torch.cuda.synchronize()
+            t = nq.nq_binlr_read_intermediate(L.h, r, 1)
+            nq.nq_binlr_forward_unscaled(L.h, x, z, 1)
+            torch.cuda.synchronize()
+            outs[small] = (y.view(torch.int16 if y_dtype != "f32" else torch.int32).cpu().numpy(), t.view(np.int32).copy(),
+                           z.view(torch.int16 if y_dtype != "f32" else torch.int32).cpu().numpy())
+        for a, b in zip(outs[True], outs[False]):
+            assert np.array_equal(a, b), (shape, y_dtype)
+        if not mid:
+            nqopt.set("small_layer_kb", 4096)
+            assert rel_err(L.forward(x_np), L.oracle(x_np)) <= DECODE_TOL
+        L.close()
+
+
+def test_small_layer_path_is_an_option_and_changes_no_result(nqopt):
+    """The one-launch path is off by default (it measured slower than two launches that spread the row blocks
+    over many CUs); the option that sets its size limit switches it on, and results stay the same either way."""
+    import torch
+    L = Layer(1024, 1024, 256, "bf16", seed=9200)
+    x_np = synth.gen_x(1, 1024, 9201, "bf16")
+    ref = L.forward(x_np)                                    # default: two launches
+    nqopt.set("small_layer_kb", 1)                           # 66 KiB of bits do not fit 1 KiB: still two launches
+    assert np.array_equal(L.forward(x_np), ref)
+    nqopt.set("small_layer_kb", 128)                         # now one launch by one workgroup
+    assert np.array_equal(L.forward(x_np), ref)
+    L.close()

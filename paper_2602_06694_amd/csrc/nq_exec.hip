@@ -72,7 +72,8 @@ typedef __attribute__((address_space(1))) unsigned long long* gptr_u64;
 __device__ __forceinline__ void ll_store(unsigned long long* p, float v, unsigned int epoch)
 {
     const unsigned long long pair = (unsigned long long)__builtin_bit_cast(unsigned int, v) | ((unsigned long long)epoch << 32);
-    __hip_atomic_store(p, pair, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // (global, not generic, address space: a flat store would count on both wait counters)
+    __hip_atomic_store((gptr_u64)p, pair, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Reductions over a wavefront on the data-parallel-primitive path of the vector unit (no LDS traffic):
@@ -125,7 +126,7 @@ __device__ __forceinline__ long long wave_sum64(long long v)
 __device__ __forceinline__ void exec_body(const ExecTask* __restrict__ tasks, int ti, const int t_end,
                                           ExecState* __restrict__ state, int bq_bytes, unsigned long long spin_ticks)
 {
-    extern __shared__ int lds[];
+    extern __shared__ __align__(16) int lds[];
     constexpr int D = kExecRing;
     char* const lds_bq = (char*)lds;
     int* const lds_epi = (int*)(lds_bq + bq_bytes);

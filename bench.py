@@ -49,6 +49,9 @@ def parse_args():
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target oracle time for the cpu_baseline sample")
     ap.add_argument("--quick", action="store_true",
                     help="headline workload only: skip the extra fields (70B stack decode, config-5 prefill)")
+    ap.add_argument("--case", default="",
+                    help="run ONE of the side workloads only and print its JSON (for profiling a single case): "
+                         "prefill:<gate|down>:<batch> | pool_b8 | stack3 | stack4 | chain3 | chain4")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (reference for rocprofv3 --pmc byte counters)")
     return ap.parse_args()
@@ -397,7 +400,7 @@ def time_single_layer(cfg, reps=200):
     return {"shape": [shp.d_out, shp.d_in, shp.r], "us_per_forward": us, "cache_hot_weight_GBps": wb / us / 1e3}
 
 
-def time_prefill(args):
+def time_prefill(args, only_layer=None, only_batch=None):
     """Config-5 shapes through nq_binlr_forward at batch 512 / 2048 (TFLOP/s = 2 B r (d_in + d_out) / time)."""
     import numpy as np
     import torch
@@ -406,9 +409,11 @@ def time_prefill(args):
     res = {}
     c = synth.CONFIGS[5]
     for li, shp in enumerate(c.block):
+        if only_layer and shp.name != only_layer:
+            continue
         data = synth.gen_layer(5, 0, li, shp)
         h = nq.nq_binlr_create(shp.d_out, shp.d_in, shp.r, data.U_words, data.V_words, data.s_out, data.s_in, nq.NQ_BF16)
-        for B in c.batches:
+        for B in ((only_batch,) if only_batch else c.batches):
             nq.nq_binlr_reserve(h, B)
             xb = synth.gen_layer_x(5, 0, li, shp, B, "bf16", c.outlier_frac)
             x = torch.from_numpy(xb.view(np.int16).copy()).view(torch.bfloat16).cuda()
@@ -448,6 +453,26 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     nq.lib()
+    if args.case:
+        kind = args.case.split(":")
+        if kind[0] == "prefill":
+            res = time_prefill(args, kind[1], int(kind[2]))
+        elif kind[0] == "pool_b8":
+            res = time_pool_batch(args.pool, 8)
+        elif kind[0] in ("stack3", "stack4"):
+            res = time_stack(int(kind[0][-1]), 1)
+        elif kind[0] in ("chain3", "chain4"):
+            res = time_stack_in_dependency_order(int(kind[0][-1]))
+        else:
+            print(f"bench.py: unknown --case {args.case}", file=sys.stderr)
+            sys.exit(2)
+        if args.calibrate_copy:
+            a = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+            b = torch.empty_like(a)
+            b.copy_(a)
+            torch.cuda.synchronize()
+        print(json.dumps({"case": args.case, "result": res}))
+        return
     batch = args.batch
     name, work = build_workload(args)
 

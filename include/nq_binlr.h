@@ -277,6 +277,9 @@ int nq_binlr_destroy(nq_handle h);
  * 2r bytes more (r(n+m) + 16(n+r+m) bits, Appendix F.4). 0 for NULL. */
 size_t nq_binlr_weight_bytes(nq_handle h);
 
+/* Debug: number of device slabs (the large allocations layers are carved from) the library holds now. */
+int nq_debug_slab_count(void);
+
 /* Debug: convert the device-resident bits back to canonical words (host buffers sized as
  * in nq_binlr_create).  Synchronises.  Either pointer may be NULL to skip that factor. */
 int nq_binlr_export_words(nq_handle h, uint32_t* U_words, uint32_t* V_words);

@@ -80,6 +80,7 @@ def lib() -> ctypes.CDLL:
         L.nq_exec_info.argtypes = [vp, ctypes.POINTER(ci), ctypes.POINTER(ci), ctypes.POINTER(ctypes.c_size_t)]; L.nq_exec_info.restype = ci
         L.nq_exec_destroy.argtypes = [vp]; L.nq_exec_destroy.restype = ci
         L.nq_exec_plan_tasks.argtypes = [vp, vp, vp, vp, ci, ci, vp, ci, ctypes.POINTER(ci)]; L.nq_exec_plan_tasks.restype = ci
+        L.nq_debug_slab_count.argtypes = []; L.nq_debug_slab_count.restype = ci
         L.nq_status_string.argtypes = [ci]; L.nq_status_string.restype = ctypes.c_char_p
         L.nq_last_error_string.argtypes = []; L.nq_last_error_string.restype = ctypes.c_char_p
         _lib = L
@@ -346,6 +347,10 @@ def nq_plan_destroy(p: Optional[int]) -> None:
 
 def nq_binlr_destroy(h: Optional[int]) -> None:
     _check(lib().nq_binlr_destroy(h))
+
+
+def nq_debug_slab_count() -> int:
+    return int(lib().nq_debug_slab_count())
 
 
 def nq_binlr_weight_bytes(h: Optional[int]) -> int:

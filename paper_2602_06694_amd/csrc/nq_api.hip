@@ -81,6 +81,7 @@ struct Slab {
     int live;          // allocations handed out and not yet released
     int device;
     int kind;          // 0: sign tiles and scales (streamed), 1: per-layer workspaces (small, reused)
+    std::vector<std::pair<size_t, size_t>> free_ranges;    // (offset, bytes) of released blocks, sorted by offset, neighbours merged
 };
 static std::mutex g_slab_mutex;
 static std::vector<Slab*> g_slabs;
@@ -90,7 +91,9 @@ static size_t slab_bytes()
     return (size_t)std::max(1, opt_or(OPT_SLAB_MB, 512)) << 20;
 }
 
-// returns hipSuccess and (*out, *owner); the block is 4 KiB aligned
+// returns hipSuccess and (*out, *owner); the block is 4 KiB aligned.  Released blocks are reused (first
+// fit) before a slab grows, so a process that keeps rebuilding layers beside a long-lived one does not
+// take a new slab every time.
 static hipError_t slab_alloc(size_t bytes, int device, int kind, void** out, Slab** owner)
 {
     std::lock_guard<std::mutex> lk(g_slab_mutex);
@@ -98,6 +101,19 @@ static hipError_t slab_alloc(size_t bytes, int device, int kind, void** out, Sla
     const size_t std_size = kind == 0 ? slab_bytes() : slab_bytes() / 4;
     Slab* s = nullptr;
     if (bytes <= std_size / 4) {
+        for (Slab* c : g_slabs) {
+            if (c->device != device || c->kind != kind || c->size != std_size) continue;
+            for (size_t i = 0; i < c->free_ranges.size(); ++i) {
+                if (c->free_ranges[i].second < bytes) continue;
+                *out = c->base + c->free_ranges[i].first;
+                c->free_ranges[i].first += bytes;
+                c->free_ranges[i].second -= bytes;
+                if (c->free_ranges[i].second == 0) c->free_ranges.erase(c->free_ranges.begin() + i);
+                c->live += 1;
+                *owner = c;
+                return hipSuccess;
+            }
+        }
         for (Slab* c : g_slabs)
             if (c->device == device && c->kind == kind && c->size == std_size && c->size - c->used >= bytes) { s = c; break; }
     }
@@ -106,7 +122,7 @@ static hipError_t slab_alloc(size_t bytes, int device, int kind, void** out, Sla
         void* p = nullptr;
         hipError_t e = hipMalloc(&p, sz);
         if (e != hipSuccess) return e;
-        s = new Slab{(char*)p, sz, 0, 0, device, kind};
+        s = new Slab{(char*)p, sz, 0, 0, device, kind, {}};
         g_slabs.push_back(s);
     }
     *out = s->base + s->used;
@@ -116,14 +132,40 @@ static hipError_t slab_alloc(size_t bytes, int device, int kind, void** out, Sla
     return hipSuccess;
 }
 
-static void slab_release(Slab* s)
+// gives the block [p, p + bytes) back to its slab; the slab itself is freed when its last block goes
+static void slab_release(Slab* s, void* p, size_t bytes)
 {
     if (!s) return;
     std::lock_guard<std::mutex> lk(g_slab_mutex);
-    if (--s->live > 0) return;
+    if (--s->live > 0) {
+        bytes = (bytes + 4095) / 4096 * 4096;
+        const size_t off = (size_t)((char*)p - s->base);
+        auto it = s->free_ranges.begin();
+        while (it != s->free_ranges.end() && it->first < off) ++it;
+        it = s->free_ranges.insert(it, std::make_pair(off, bytes));
+        if (it + 1 != s->free_ranges.end() && it->first + it->second == (it + 1)->first) {      // merge with the next
+            it->second += (it + 1)->second;
+            s->free_ranges.erase(it + 1);
+        }
+        if (it != s->free_ranges.begin() && (it - 1)->first + (it - 1)->second == it->first) {  // and with the previous
+            (it - 1)->second += it->second;
+            it = s->free_ranges.erase(it) - 1;
+        }
+        if (it->first + it->second == s->used) {                  // the tail of the slab: plain unused space again
+            s->used = it->first;
+            s->free_ranges.erase(it);
+        }
+        return;
+    }
     (void)hipFree(s->base);
     g_slabs.erase(std::find(g_slabs.begin(), g_slabs.end(), s));
     delete s;
+}
+
+extern "C" int nq_debug_slab_count(void)
+{
+    std::lock_guard<std::mutex> lk(g_slab_mutex);
+    return (int)g_slabs.size();
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -297,8 +339,8 @@ static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static void free_handle(nq_handle h)
 {
     if (!h) return;
-    slab_release(h->w_slab);
-    slab_release(h->ws_slab);
+    slab_release(h->w_slab, h->w_alloc, h->w_bytes);
+    slab_release(h->ws_slab, h->ws_alloc, h->ws_bytes);
     if (h->pf_alloc) (void)hipFree(h->pf_alloc);
     if (h->s_mid) (void)hipFree(h->s_mid);
     delete h;
@@ -360,6 +402,8 @@ static int create_layer(nq_handle* out, int64_t d_out, int64_t d_in, int64_t r, 
             goto done;                                                     \
         }                                                                  \
     } while (0)
+    h->w_bytes = w_total;
+    h->ws_bytes = ws_total;
     CREATE_HIP(slab_alloc(w_total, h->device, 0, &h->w_alloc, &h->w_slab));
     CREATE_HIP(slab_alloc(ws_total, h->device, 1, &h->ws_alloc, &h->ws_slab));
     CREATE_HIP(hipMalloc((void**)&d_canon, std::max(canon_u, canon_v)));

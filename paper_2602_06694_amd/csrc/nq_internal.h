@@ -191,6 +191,7 @@ struct nq_binlr_s {
     int device;
     // weights (one allocation)
     void* w_alloc;
+    size_t w_bytes;
     Slab* w_slab;
     uint32_t* vt_tiles;   // A = V^T : M = r,     N = d_in
     uint32_t* u_tiles;    // A = U   : M = d_out, N = r
@@ -200,6 +201,7 @@ struct nq_binlr_s {
     int mid_exp;          // ceil(log2(max |s_mid|)): keeps the dense path's fp16 intermediate in range
     // decode workspace (one allocation, sized for NQ_DECODE_MAX_BATCH, never reallocated)
     void* ws_alloc;
+    size_t ws_bytes;
     Slab* ws_slab;
     nq::DecodeWorkspace ws;
     // prefill workspace (grown by reserve)

@@ -799,3 +799,23 @@ def test_wave_per_vector_quantiser_matches_workgroup_quantiser(nqopt):
                     assert rel_err(outs["wave"][i], L.oracle(x)) <= DECODE_TOL, (shapes[i], batch, x_dtype)
         for L in layers:
             L.close()
+
+
+def test_layers_rebuilt_beside_a_long_lived_one_do_not_grow_device_memory(nqopt):
+    """Creating and destroying layers while another layer of the same slab stays alive (a layer rebuilt after
+    every sign update, the use of the device-side packing) must reuse the released blocks: the number of
+    slabs stays what it was after the first round, and the rebuilt layers still compute the right thing."""
+    nqopt.set("slab_mb", 8)                                  # small slabs, so that a leak would show within a few rounds
+    keeper = Layer(512, 512, 128, "bf16", seed=6100)
+    x_np = synth.gen_x(2, 512, 6101, "bf16")
+    counts = []
+    for it in range(40):
+        L = Layer(1024, 1024, 256, "bf16", seed=6200 + it)   # 66 KB of tiles + workspace: many fit one slab
+        if it % 13 == 0:
+            xl = synth.gen_x(2, 1024, 6300 + it, "bf16")
+            assert rel_err(L.forward(xl), L.oracle(xl)) <= DECODE_TOL
+        L.close()
+        counts.append(nq.nq_debug_slab_count())
+    assert max(counts) == counts[0], counts
+    assert rel_err(keeper.forward(x_np), keeper.oracle(x_np)) <= DECODE_TOL
+    keeper.close()

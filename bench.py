@@ -117,6 +117,10 @@ class ClockSampler:
         import subprocess
         self.proc = None
         exe = shutil.which("rocm-smi") or "/opt/rocm/bin/rocm-smi"
+        # under a profiler every child process is itself instrumented (and initialises the GPU before it can start
+        # another program): no side process is started then, and the clocks are reported as null
+        if any(k.startswith(("ROCPROF", "ROCP_")) for k in os.environ) or "rocprof" in os.environ.get("LD_PRELOAD", ""):
+            return
         try:
             self.proc = subprocess.Popen(["bash", "-c", f"sleep 0.3; {exe} --showclocks"], stdout=subprocess.PIPE,
                                          stderr=subprocess.DEVNULL, text=True)

@@ -81,6 +81,13 @@ def lib() -> ctypes.CDLL:
         L.nq_exec_destroy.argtypes = [vp]; L.nq_exec_destroy.restype = ci
         L.nq_exec_plan_tasks.argtypes = [vp, vp, vp, vp, ci, ci, vp, ci, ctypes.POINTER(ci)]; L.nq_exec_plan_tasks.restype = ci
         L.nq_debug_slab_count.argtypes = []; L.nq_debug_slab_count.restype = ci
+        dbl, szp = ctypes.c_double, ctypes.POINTER(ctypes.c_size_t)
+        L.nq_lb_admm_workspace_bytes.argtypes = [i64, i64, i64, szp]; L.nq_lb_admm_workspace_bytes.restype = ci
+        L.nq_lb_admm.argtypes = [vp, i64, i64, i64, vp, vp, ci, dbl, dbl, dbl, ci, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.nq_lb_admm.restype = ci
+        L.nq_lb_admm_balance.argtypes = [vp, vp, i64, vp, vp, i64, i64, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.nq_lb_admm_balance.restype = ci
+        L.nq_dgemm.argtypes = [ci, ci, i64, i64, i64, dbl, vp, i64, vp, i64, dbl, vp, i64, vp]; L.nq_dgemm.restype = ci
         L.nq_status_string.argtypes = [ci]; L.nq_status_string.restype = ctypes.c_char_p
         L.nq_last_error_string.argtypes = []; L.nq_last_error_string.restype = ctypes.c_char_p
         _lib = L
@@ -369,3 +376,34 @@ def nq_binlr_read_intermediate(h: int, r: int, batch: int) -> np.ndarray:
     t = np.empty((batch, r), dtype=np.float32)
     _check(lib().nq_binlr_read_intermediate(h, _np_ptr(t), batch))
     return t
+
+
+# ---- latent-binary ADMM (include/nq_lb_admm.h) ----
+
+NQ_ADMM_MAX_RANK = 8192
+NQ_ADMM_MAX_DIM = 65536
+
+
+def nq_lb_admm_workspace_bytes(n: int, m: int, r: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().nq_lb_admm_workspace_bytes(n, m, r, ctypes.byref(out)))
+    return out.value
+
+
+def nq_lb_admm(W, n: int, m: int, r: int, U0, V0, n_iters: int, rho_start: float, rho_end: float, lam: float, power_iters: int,
+               U, V, Z_U, Z_V, Lambda_U, Lambda_V, workspace, workspace_bytes: int, stream=None) -> None:
+    _check(lib().nq_lb_admm(_dev_ptr(W), n, m, r, _dev_ptr(U0), _dev_ptr(V0), n_iters, rho_start, rho_end, lam, power_iters,
+                            _dev_ptr(U), _dev_ptr(V), _dev_ptr(Z_U), _dev_ptr(Z_V), _dev_ptr(Lambda_U), _dev_ptr(Lambda_V),
+                            _dev_ptr(workspace), workspace_bytes, _stream(stream)))
+
+
+def nq_lb_admm_balance(U, Lambda_U, n: int, V, Lambda_V, m: int, r: int, U_words, V_words, s1, s2, eta, workspace,
+                       workspace_bytes: int, stream=None) -> None:
+    _check(lib().nq_lb_admm_balance(_dev_ptr(U), _dev_ptr(Lambda_U), n, _dev_ptr(V), _dev_ptr(Lambda_V), m, r, _dev_ptr(U_words),
+                                    _dev_ptr(V_words), _dev_ptr(s1), _dev_ptr(s2), _dev_ptr(eta), _dev_ptr(workspace), workspace_bytes,
+                                    _stream(stream)))
+
+
+def nq_dgemm(trans_a: int, trans_b: int, M: int, N: int, K: int, alpha: float, A, lda: int, B, ldb: int, beta: float, C, ldc: int,
+             stream=None) -> None:
+    _check(lib().nq_dgemm(trans_a, trans_b, M, N, K, alpha, _dev_ptr(A), lda, _dev_ptr(B), ldb, beta, _dev_ptr(C), ldc, _stream(stream)))

@@ -1,0 +1,684 @@
+// Latent-binary ADMM on one matrix in binary64 (Section 3.2 Step 2-2 and 2-3; Appendix B): the dense
+// products on the fp64 matrix cores, a blocked Cholesky with its inverse, the SVID proxy update by power
+// iteration, the dual update and the magnitude balancing.  Host code only sequences launches.
+#include "nq_internal.h"
+#include "nq_lb_admm.h"
+
+#include <math.h>
+#include <mutex>
+
+namespace nq {
+
+typedef double v4d __attribute__((ext_vector_type(4)));
+
+// ============================================================================================
+//  C = alpha op(A) op(B) + beta Cin + diag I   [, C2 = C + E]        (batched along blockIdx.z)
+// ============================================================================================
+struct GemmArgs {
+    const double* A;
+    const double* B;
+    const double* Cin;     // read only when beta != 0 (may be C)
+    double* C;
+    const double* E;       // optional second output C2 = C + E (both with ldc)
+    double* C2;
+    int M, N, K;
+    int lda, ldb, ldcin, ldc;
+    long long sA, sB, sC;  // elements between batch members (Cin, C share sC)
+    int trans_a;           // 0: A stored [M][K];  1: stored [K][M]
+    int trans_b;           // 0: B stored [K][N];  1: stored [N][K]
+    double alpha, beta, diag;
+    int lower_only;        // tiles that lie entirely above the diagonal are skipped
+    int k_from_max;        // the reduction starts at max(first row, first column) of the tile: both operands
+                           // are lower triangular in the sense  op(A)[i][k] = 0 for k < i,  op(B)[k][j] = 0 for k < j
+};
+
+constexpr int kGemmThreads = 256;
+constexpr int kBK = 16;        // reduction depth of one LDS tile = four 16x16x4 matrix instructions
+
+// A workgroup of four waves (2 x 2) owns a BM x BN tile of C; each wave (BM/2) x (BN/2) of it as
+// 16 x 16 accumulator tiles.  v_mfma_f64_16x16x4_f64: lane l supplies A[l & 15][l >> 4] and B[l >> 4][l & 15],
+// and holds C[4 v + (l >> 4)][l & 15] in element v of its four accumulators.  Operand tiles go through LDS as
+// [k][i] and [k][j] (row pitch BM + 16: the four k rows a wave reads at once fall on different bank halves),
+// double buffered: the global loads of tile kt + 1 are in flight while tile kt is multiplied.
+template <int BM, int BN>
+__global__ __launch_bounds__(kGemmThreads) void dgemm_kernel(GemmArgs g)
+{
+    constexpr int PA = BM + 16, PB = BN + 16;
+    constexpr int TM = BM / 32, TN = BN / 32;
+    constexpr int LA = BM * kBK / kGemmThreads, LB = BN * kBK / kGemmThreads;
+    extern __shared__ __align__(16) double lds_gemm[];
+    double (*As)[kBK][PA] = reinterpret_cast<double (*)[kBK][PA]>(lds_gemm);
+    double (*Bs)[kBK][PB] = reinterpret_cast<double (*)[kBK][PB]>(lds_gemm + 2 * kBK * PA);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i0 = blockIdx.y * BM, j0 = blockIdx.x * BN;
+    if (g.lower_only && j0 > i0 + BM - 1) return;
+    const double* A = g.A + (size_t)blockIdx.z * g.sA;
+    const double* B = g.B + (size_t)blockIdx.z * g.sB;
+    const int k_begin = g.k_from_max ? ((i0 > j0 ? i0 : j0) / kBK) * kBK : 0;
+    const int n_kt = g.K > k_begin ? (g.K - k_begin + kBK - 1) / kBK : 0;
+    const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
+
+    double ra[LA], rb[LB];
+    auto fetch = [&](int kt) {
+        const int k0 = k_begin + kt * kBK;
+#pragma unroll
+        for (int p = 0; p < LA; ++p) {
+            const int idx = p * kGemmThreads + tid;
+            const int i = g.trans_a ? idx % BM : idx / kBK, k = g.trans_a ? idx / BM : idx % kBK;
+            const int gi = i0 + i, gk = k0 + k;
+            double v = 0.0;
+            if (gi < g.M && gk < g.K) v = g.trans_a ? A[(size_t)gk * g.lda + gi] : A[(size_t)gi * g.lda + gk];
+            ra[p] = v;
+        }
+#pragma unroll
+        for (int p = 0; p < LB; ++p) {
+            const int idx = p * kGemmThreads + tid;
+            const int j = g.trans_b ? idx / kBK : idx % BN, k = g.trans_b ? idx % kBK : idx / BN;
+            const int gj = j0 + j, gk = k0 + k;
+            double v = 0.0;
+            if (gj < g.N && gk < g.K) v = g.trans_b ? B[(size_t)gj * g.ldb + gk] : B[(size_t)gk * g.ldb + gj];
+            rb[p] = v;
+        }
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int p = 0; p < LA; ++p) {
+            const int idx = p * kGemmThreads + tid;
+            const int i = g.trans_a ? idx % BM : idx / kBK, k = g.trans_a ? idx / BM : idx % kBK;
+            As[buf][k][i] = ra[p];
+        }
+#pragma unroll
+        for (int p = 0; p < LB; ++p) {
+            const int idx = p * kGemmThreads + tid;
+            const int j = g.trans_b ? idx / kBK : idx % BN, k = g.trans_b ? idx % kBK : idx / BN;
+            Bs[buf][k][j] = rb[p];
+        }
+    };
+
+    v4d acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b) acc[a][b] = v4d{0.0, 0.0, 0.0, 0.0};
+
+    if (n_kt > 0) {
+        fetch(0);
+        stash(0);
+    }
+    __syncthreads();
+    for (int kt = 0; kt < n_kt; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < n_kt) fetch(kt + 1);
+#pragma unroll
+        for (int k4 = 0; k4 < kBK / 4; ++k4) {
+            double a[TM], b[TN];
+            const int kk = k4 * 4 + (lane >> 4);
+#pragma unroll
+            for (int t = 0; t < TM; ++t) a[t] = As[buf][kk][wm0 + t * 16 + (lane & 15)];
+#pragma unroll
+            for (int t = 0; t < TN; ++t) b[t] = Bs[buf][kk][wn0 + t * 16 + (lane & 15)];
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[tm], b[tn], acc[tm][tn], 0, 0, 0);
+        }
+        if (kt + 1 < n_kt) stash(buf ^ 1);
+        __syncthreads();
+    }
+
+    const double* Cin = g.Cin ? g.Cin + (size_t)blockIdx.z * g.sC : nullptr;
+    double* C = g.C + (size_t)blockIdx.z * g.sC;
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int i = i0 + wm0 + tm * 16 + 4 * v + (lane >> 4);
+                const int j = j0 + wn0 + tn * 16 + (lane & 15);
+                if (i < g.M && j < g.N) {
+                    double val = g.alpha * acc[tm][tn][v];
+                    if (g.beta != 0.0) val = fma(g.beta, Cin[(size_t)i * g.ldcin + j], val);
+                    if (i == j) val += g.diag;
+                    C[(size_t)i * g.ldc + j] = val;
+                    if (g.C2) g.C2[(size_t)i * g.ldc + j] = val + g.E[(size_t)i * g.ldc + j];
+                }
+            }
+}
+
+template <int BM, int BN> constexpr size_t gemm_lds_bytes() { return (size_t)2 * kBK * ((BM + 16) + (BN + 16)) * sizeof(double); }
+
+static int launch_gemm(const GemmArgs& g, int batch, hipStream_t s)
+{
+    if (g.M < 1 || g.N < 1 || batch < 1) return NQ_OK;
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [] {
+        attr_err = hipFuncSetAttribute((const void*)dgemm_kernel<128, 128>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)gemm_lds_bytes<128, 128>());
+    });
+    NQ_HIP(attr_err);
+    const long long tiles128 = (long long)((g.M + 127) / 128) * ((g.N + 127) / 128) * batch;
+    if (tiles128 >= 192) {
+        dim3 grid((g.N + 127) / 128, (g.M + 127) / 128, batch);
+        const size_t lds = gemm_lds_bytes<128, 128>();
+        hipLaunchKernelGGL((dgemm_kernel<128, 128>), grid, dim3(kGemmThreads), lds, s, g);
+    } else {
+        dim3 grid((g.N + 63) / 64, (g.M + 63) / 64, batch);
+        const size_t lds = gemm_lds_bytes<64, 64>();
+        hipLaunchKernelGGL((dgemm_kernel<64, 64>), grid, dim3(kGemmThreads), lds, s, g);
+    }
+    NQ_HIP(hipGetLastError());
+    return NQ_OK;
+}
+
+static GemmArgs gemm_args(int ta, int tb, int M, int N, int K, double alpha, const double* A, int lda, const double* B, int ldb,
+                          double beta, const double* Cin, int ldcin, double* C, int ldc)
+{
+    GemmArgs g{};
+    g.A = A; g.B = B; g.Cin = Cin; g.C = C; g.E = nullptr; g.C2 = nullptr;
+    g.M = M; g.N = N; g.K = K; g.lda = lda; g.ldb = ldb; g.ldcin = ldcin; g.ldc = ldc;
+    g.sA = g.sB = g.sC = 0;
+    g.trans_a = ta; g.trans_b = tb; g.alpha = alpha; g.beta = beta; g.diag = 0.0;
+    g.lower_only = 0; g.k_from_max = 0;
+    return g;
+}
+
+// ============================================================================================
+//  Cholesky of one 64 x 64 diagonal block and the inverse of its factor (one workgroup)
+// ============================================================================================
+constexpr int kNB = 64;
+
+// 256 threads as 16 x 16, thread (ty, tx) keeps the 4 x 4 sub-blocks of the matrix (a) and of the running right-hand
+// side of L X = I (b, starts as the identity) in registers.  Step j of the right-looking elimination needs column j
+// of the current matrix and row j of the current right-hand side: their owners publish them in LDS at the end of
+// step j - 1 (double buffered), so a step costs one barrier.  Every thread derives the pivot's square root and the
+// scaled column entries it needs itself.  H (lower part) is overwritten by L; the block of Linv receives L^-1 with
+// an exactly zero upper part.  A pivot that is not > 0 sets *status (the results are then meaningless, every thread
+// still finishes).
+__global__ __launch_bounds__(256) void potrf_inv64_kernel(double* H, int ldh, double* Linv, int ldi, int o, int* status)
+{
+    __shared__ double colraw[2][kNB];
+    __shared__ double brow[2][kNB];
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    double a[4][4], b[4][4];
+#pragma unroll
+    for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) {
+            a[ii][cc] = H[(size_t)(o + 4 * ty + ii) * ldh + o + 4 * tx + cc];
+            b[ii][cc] = (4 * ty + ii == 4 * tx + cc) ? 1.0 : 0.0;
+        }
+    if (tx == 0)
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii) colraw[0][4 * ty + ii] = a[ii][0];
+    if (ty == 0)
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) brow[0][4 * tx + cc] = b[0][cc];
+    __syncthreads();
+    bool bad = false;
+    for (int j = 0; j < kNB; ++j) {
+        const int cur = j & 1, jb = j >> 2, jj = j & 3;
+        const double piv = colraw[cur][j];
+        if (!(piv > 0.0)) bad = true;
+        const double d = sqrt(piv);
+        const double inv = 1.0 / d;
+        double lrow[4], lcol[4], x[4];
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii) lrow[ii] = (4 * ty + ii > j) ? colraw[cur][4 * ty + ii] * inv : 0.0;
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) {
+            lcol[cc] = (4 * tx + cc > j) ? colraw[cur][4 * tx + cc] * inv : 0.0;
+            x[cc] = brow[cur][4 * tx + cc] * inv;
+        }
+        if (tx == jb)                                   // column j of L
+#pragma unroll
+            for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+                for (int cc = 0; cc < 4; ++cc)
+                    if (cc == jj) a[ii][cc] = (4 * ty + ii == j) ? d : lrow[ii];
+        if (ty == jb)                                   // row j of X = L^-1
+#pragma unroll
+            for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+                for (int cc = 0; cc < 4; ++cc)
+                    if (ii == jj) b[ii][cc] = x[cc];
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+            for (int cc = 0; cc < 4; ++cc) {
+                a[ii][cc] = fma(-lrow[ii], lcol[cc], a[ii][cc]);     // lrow = 0 at and above row j, lcol = 0 up to column j
+                b[ii][cc] = fma(-lrow[ii], x[cc], b[ii][cc]);
+            }
+        if (j + 1 < kNB) {
+            const int nb = (j + 1) >> 2, nj = (j + 1) & 3;
+            if (tx == nb)
+#pragma unroll
+                for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+                    for (int cc = 0; cc < 4; ++cc)
+                        if (cc == nj) colraw[cur ^ 1][4 * ty + ii] = a[ii][cc];
+            if (ty == nb)
+#pragma unroll
+                for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+                    for (int cc = 0; cc < 4; ++cc)
+                        if (ii == nj) brow[cur ^ 1][4 * tx + cc] = b[ii][cc];
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) {
+            const int i = 4 * ty + ii, c = 4 * tx + cc;
+            if (c <= i) H[(size_t)(o + i) * ldh + o + c] = a[ii][cc];
+            Linv[(size_t)(o + i) * ldi + o + c] = (c <= i) ? b[ii][cc] : 0.0;
+        }
+    if (bad && threadIdx.x == 0) *status = 1;
+}
+
+// Identity outside the leading r x r part of a [rp][rp] matrix (the padding that keeps the block algorithms
+// exact: an identity block factorises and inverts to itself); `zero_inside` also clears the leading part.
+__global__ void pad_identity_kernel(double* A, int rp, int r, int zero_inside)
+{
+    const size_t n = (size_t)rp * rp;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += (size_t)gridDim.x * blockDim.x) {
+        const int i = (int)(e / rp), j = (int)(e % rp);
+        if (i >= r || j >= r) A[e] = (i == j) ? 1.0 : 0.0;
+        else if (zero_inside) A[e] = 0.0;
+    }
+}
+
+// ============================================================================================
+//  SVID: power iteration on |P| and the proxy / dual update
+// ============================================================================================
+constexpr int kRowsPerWg = 16;
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    return v;
+}
+
+// Sum over the workgroup of one value per thread (256 threads); every thread gets the result.
+__device__ __forceinline__ double block_sum(double v, double* scratch4)
+{
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) scratch4[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return (scratch4[0] + scratch4[1]) + (scratch4[2] + scratch4[3]);
+}
+
+// One round of the power iteration in one pass over P [n][r]: for the 16 rows of this workgroup
+//     a_i = sum_k |P[i][k]| b_k          with b = w / ||w||   (w: the unnormalised vector of the round before)
+// and, unless `rows_only`, this workgroup's part of the next unnormalised vector  w'_k = sum_i |P[i][k]| a_i
+// (partial[g][k]; a second kernel adds the parts in a fixed order).  `ones`: a_i = 1 instead (the start vector;
+// its scale does not matter, the next round normalises).
+__global__ __launch_bounds__(256) void power_pass_kernel(const double* P, int n, int r, const double* w, int ones, int rows_only,
+                                                          double* a_out, double* partial)
+{
+    __shared__ double red[4];
+    __shared__ double a_s[kRowsPerWg];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int row0 = blockIdx.x * kRowsPerWg;
+    if (!ones) {
+        double q = 0.0;
+        for (int k = tid; k < r; k += 256) q = fma(w[k], w[k], q);
+        const double inv = 1.0 / sqrt(block_sum(q, red));
+        for (int rr = 0; rr < kRowsPerWg / 4; ++rr) {
+            const int i = row0 + wave * (kRowsPerWg / 4) + rr;
+            double d = 0.0;
+            if (i < n)
+                for (int k = lane; k < r; k += 64) d = fma(fabs(P[(size_t)i * r + k]), w[k], d);
+            d = wave_sum(d) * inv;
+            if (lane == 0) {
+                a_s[wave * (kRowsPerWg / 4) + rr] = d;
+                if (i < n) a_out[i] = d;
+            }
+        }
+    } else if (tid < kRowsPerWg) {
+        a_s[tid] = 1.0;
+    }
+    __syncthreads();
+    if (rows_only) return;
+    for (int k = tid; k < r; k += 256) {
+        double c = 0.0;
+#pragma unroll 4
+        for (int rr = 0; rr < kRowsPerWg; ++rr) {
+            const int i = row0 + rr;
+            if (i < n) c = fma(fabs(P[(size_t)i * r + k]), a_s[rr], c);
+        }
+        partial[(size_t)blockIdx.x * r + k] = c;
+    }
+}
+
+// w[k] = sum_g partial[g][k], parts added in index order (four interleaved partial sums, then a fixed tree).
+__global__ __launch_bounds__(256) void power_reduce_kernel(const double* partial, int n_parts, int r, double* w)
+{
+    __shared__ double s[4][64];
+    const int c = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int k = blockIdx.x * 64 + c;
+    double acc = 0.0;
+    if (k < r)
+        for (int g = q; g < n_parts; g += 4) acc += partial[(size_t)g * r + k];
+    s[q][c] = acc;
+    __syncthreads();
+    if (q == 0 && k < r) w[k] = (s[0][c] + s[1][c]) + (s[2][c] + s[3][c]);
+}
+
+// Z = sign(P) (.) (a b^T) with b = w / ||w||  (power_iters = 0: the constant sum(w) / (n r), w = |P|^T 1),
+// and the dual update in its two forms:  first = 0:  Lambda = P - Z  (P = X + Lambda_old, so this is
+// Lambda_old + X - Z),  D = Z - Lambda;   first = 1 (initial state):  Lambda = 0,  D = Z.
+__global__ __launch_bounds__(256) void svid_finish_kernel(const double* P, int n, int r, const double* a, const double* w, int zero_rounds,
+                                                           int first, double* Z, double* Lambda, double* D)
+{
+    __shared__ double red[4];
+    const int tid = threadIdx.x;
+    double q = 0.0;
+    for (int k = tid; k < r; k += 256) q = zero_rounds ? q + w[k] : fma(w[k], w[k], q);
+    const double tot = block_sum(q, red);
+    const double scale = zero_rounds ? tot / ((double)n * (double)r) : 1.0 / sqrt(tot);
+    const int row0 = blockIdx.x * kRowsPerWg;
+    for (int rr = 0; rr < kRowsPerWg; ++rr) {
+        const int i = row0 + rr;
+        if (i >= n) break;
+        const double ai = zero_rounds ? 1.0 : a[i];
+        for (int k = tid; k < r; k += 256) {
+            const size_t e = (size_t)i * r + k;
+            const double p = P[e];
+            const double mag = zero_rounds ? scale : ai * (w[k] * scale);
+            const double z = (p >= 0.0) ? mag : -mag;
+            Z[e] = z;
+            const double lam = first ? 0.0 : p - z;
+            Lambda[e] = lam;
+            D[e] = z - lam;
+        }
+    }
+}
+
+// ============================================================================================
+//  Magnitude balancing (Step 2-3)
+// ============================================================================================
+__global__ __launch_bounds__(256) void sumsq_kernel(const double* X, const double* L, size_t count, double* partial)
+{
+    __shared__ double red[4];
+    double q = 0.0;
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < count; e += (size_t)gridDim.x * 256) {
+        const double p = X[e] + L[e];
+        q = fma(p, p, q);
+    }
+    const double t = block_sum(q, red);
+    if (threadIdx.x == 0) partial[blockIdx.x] = t;
+}
+
+constexpr int kSumParts = 256;
+
+// One wave per row: scale[i] = mean_k |f p_ik| with f = eta (which = 0) or 1 / eta (which = 1), p = X + L, and the
+// packed sign bits of the row (bit = 1 iff p >= 0; a NaN packs as 0).
+__global__ __launch_bounds__(256) void balance_rows_kernel(const double* X, const double* L, int rows, int r, const double* parts_u,
+                                                            const double* parts_v, int which, uint32_t* words, double* scale, double* eta_out)
+{
+    __shared__ double red[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const double su = block_sum(parts_u[tid], red);
+    const double sv = block_sum(parts_v[tid], red);
+    const double eta = sqrt(sqrt(sv) / sqrt(su));
+    if (eta_out && blockIdx.x == 0 && tid == 0) *eta_out = eta;
+    const double f = which == 0 ? eta : 1.0 / eta;
+    const int i = blockIdx.x * 4 + wave;
+    if (i >= rows) return;
+    const int n_words = (r + 31) / 32;
+    double acc = 0.0;
+    for (int c = 0; c * 64 < r; ++c) {
+        const int k = c * 64 + lane;
+        double p = -1.0;
+        if (k < r) {
+            p = X[(size_t)i * r + k] + L[(size_t)i * r + k];
+            acc += fabs(f * p);
+        }
+        const unsigned long long bits = __ballot(k < r && p >= 0.0);
+        if (lane == 0) {
+            words[(size_t)i * n_words + 2 * c] = (uint32_t)bits;
+            if (2 * c + 1 < n_words) words[(size_t)i * n_words + 2 * c + 1] = (uint32_t)(bits >> 32);
+        }
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) scale[i] = acc / (double)r;
+}
+
+// ============================================================================================
+//  Host side: workspace layout and the sequence of launches
+// ============================================================================================
+static int64_t next_pow2(int64_t v) { int64_t p = 1; while (p < v) p <<= 1; return p; }
+static size_t up256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+struct AdmmWs {
+    int rp;            // padded side of the r x r matrices: 64 * 2^ceil(log2(ceil(r/64)))
+    int rr;            // 64 * ceil(r/64): the part the factorisation touches
+    double *H, *Linv, *Hinv, *T, *RHS, *P, *DU, *DV, *a, *w, *partial, *parts_u, *parts_v;
+    int* status;
+    size_t bytes;
+};
+
+static AdmmWs carve(void* base, int64_t n, int64_t m, int64_t r)
+{
+    AdmmWs ws{};
+    const int64_t q = (r + kNB - 1) / kNB;
+    ws.rr = (int)(q * kNB);
+    ws.rp = (int)(next_pow2(q) * kNB);
+    const int64_t big = n > m ? n : m;
+    size_t off = 0;
+    auto take = [&](size_t count) { double* p = base ? (double*)((char*)base + off) : nullptr; off += up256(count * sizeof(double)); return p; };
+    const size_t sq = (size_t)ws.rp * ws.rp;
+    ws.H = take(sq); ws.Linv = take(sq); ws.Hinv = take(sq); ws.T = take(sq);
+    ws.RHS = take((size_t)big * r); ws.P = take((size_t)big * r);
+    ws.DU = take((size_t)n * r); ws.DV = take((size_t)m * r);
+    ws.a = take(big); ws.w = take(r);
+    ws.partial = take((size_t)((big + kRowsPerWg - 1) / kRowsPerWg) * r);
+    ws.parts_u = take(kSumParts); ws.parts_v = take(kSumParts);
+    ws.status = (int*)take(32);
+    ws.bytes = off;
+    return ws;
+}
+
+// SVID of P [rows][r] by `iters` rounds of power iteration; writes Z, Lambda and D = Z - Lambda.
+static int svid(const AdmmWs& ws, const double* P, int rows, int r, int iters, int first, double* Z, double* Lambda, double* D, hipStream_t s)
+{
+    const int n_wg = (rows + kRowsPerWg - 1) / kRowsPerWg;
+    const int red_wg = (r + 63) / 64;
+    // w = |P|^T 1
+    hipLaunchKernelGGL(power_pass_kernel, dim3(n_wg), dim3(256), 0, s, P, rows, r, (const double*)nullptr, 1, 0, ws.a, ws.partial);
+    hipLaunchKernelGGL(power_reduce_kernel, dim3(red_wg), dim3(256), 0, s, ws.partial, n_wg, r, ws.w);
+    for (int it = 0; it < iters; ++it) {
+        // a = |P| b with b = w / ||w||; and, except in the last round, the next w = |P|^T a
+        const int last = it + 1 == iters;
+        hipLaunchKernelGGL(power_pass_kernel, dim3(n_wg), dim3(256), 0, s, P, rows, r, (const double*)ws.w, 0, last, ws.a, ws.partial);
+        if (!last) hipLaunchKernelGGL(power_reduce_kernel, dim3(red_wg), dim3(256), 0, s, ws.partial, n_wg, r, ws.w);
+    }
+    hipLaunchKernelGGL(svid_finish_kernel, dim3(n_wg), dim3(256), 0, s, P, rows, r, (const double*)ws.a, (const double*)ws.w, iters == 0 ? 1 : 0, first,
+                       Z, Lambda, D);
+    NQ_HIP(hipGetLastError());
+    return NQ_OK;
+}
+
+// H (leading rr x rr of [rp][rp], lower part) -> L in place, Linv = L^-1, Hinv = L^-T L^-1.
+static int factor_and_invert(const AdmmWs& ws, hipStream_t s)
+{
+    const int rp = ws.rp, rr = ws.rr, q = rr / kNB;
+    for (int k = 0; k < q; ++k) {
+        const int o = k * kNB;
+        hipLaunchKernelGGL(potrf_inv64_kernel, dim3(1), dim3(256), 0, s, ws.H, rp, ws.Linv, rp, o, ws.status);
+        const int rem = rr - o - kNB;
+        if (rem <= 0) break;
+        double* A21 = ws.H + (size_t)(o + kNB) * rp + o;
+        // panel: L21 = A21 L11^-T, in place (a workgroup reads all of its rows before it writes them)
+        GemmArgs p = gemm_args(0, 1, rem, kNB, kNB, 1.0, A21, rp, ws.Linv + (size_t)o * rp + o, rp, 0.0, nullptr, 0, A21, rp);
+        int rc = launch_gemm(p, 1, s);
+        if (rc != NQ_OK) return rc;
+        // trailing update: A22 -= L21 L21^T (lower tiles only)
+        double* A22 = ws.H + (size_t)(o + kNB) * rp + o + kNB;
+        GemmArgs u = gemm_args(0, 1, rem, rem, kNB, -1.0, A21, rp, A21, rp, 1.0, A22, rp, A22, rp);
+        u.lower_only = 1;
+        rc = launch_gemm(u, 1, s);
+        if (rc != NQ_OK) return rc;
+    }
+    // L^-1 block-recursively: with the halves of a diagonal block inverted (X11, X22), the block below the
+    // diagonal of its inverse is  -X22 L21 X11;  all pairs of one level run as one batched launch.
+    for (int b = kNB; b < rr; b *= 2) {
+        const int pairs = (rr - b + 2 * b - 1) / (2 * b);       // pairs whose lower half holds real rows
+        const long long stride = (long long)2 * b * rp + 2 * b;
+        GemmArgs t = gemm_args(0, 0, b, b, b, 1.0, ws.H + (size_t)b * rp, rp, ws.Linv, rp, 0.0, nullptr, 0, ws.T + (size_t)b * rp, rp);
+        t.sA = t.sB = t.sC = stride;
+        int rc = launch_gemm(t, pairs, s);
+        if (rc != NQ_OK) return rc;
+        GemmArgs x = gemm_args(0, 0, b, b, b, -1.0, ws.Linv + (size_t)b * rp + b, rp, ws.T + (size_t)b * rp, rp, 0.0, nullptr, 0,
+                               ws.Linv + (size_t)b * rp, rp);
+        x.sA = x.sB = x.sC = stride;
+        rc = launch_gemm(x, pairs, s);
+        if (rc != NQ_OK) return rc;
+    }
+    GemmArgs h = gemm_args(1, 0, rr, rr, rr, 1.0, ws.Linv, rp, ws.Linv, rp, 0.0, nullptr, 0, ws.Hinv, rp);
+    h.k_from_max = 1;
+    return launch_gemm(h, 1, s);
+}
+
+// One factor update of Eq. 5 and Eq. 6 for X [rows][r] given the other factor O [cols][r]:
+//   op(W) is [rows][cols] (w_trans = 1: W is stored [cols][rows]).
+static int factor_step(const AdmmWs& ws, const double* W, int w_trans, int ldw, int rows, int cols, int r, const double* O, double rho, double lam,
+                       int power_iters, double* X, double* Z, double* Lambda, double* D, hipStream_t s)
+{
+    // H = O^T O + (rho + lambda) I   (lower tiles)
+    GemmArgs gh = gemm_args(1, 0, r, r, cols, 1.0, O, r, O, r, 0.0, nullptr, 0, ws.H, ws.rp);
+    gh.diag = rho + lam;
+    gh.lower_only = 1;
+    int rc = launch_gemm(gh, 1, s);
+    if (rc != NQ_OK) return rc;
+    rc = factor_and_invert(ws, s);
+    if (rc != NQ_OK) return rc;
+    // RHS = op(W) O + rho (Z - Lambda)
+    GemmArgs gr = gemm_args(w_trans, 0, rows, r, cols, 1.0, W, ldw, O, r, rho, D, r, ws.RHS, r);
+    rc = launch_gemm(gr, 1, s);
+    if (rc != NQ_OK) return rc;
+    // X = RHS H^-1,  P = X + Lambda
+    GemmArgs gx = gemm_args(0, 0, rows, r, r, 1.0, ws.RHS, r, ws.Hinv, ws.rp, 0.0, nullptr, 0, X, r);
+    gx.E = Lambda;
+    gx.C2 = ws.P;
+    rc = launch_gemm(gx, 1, s);
+    if (rc != NQ_OK) return rc;
+    return svid(ws, ws.P, rows, r, power_iters, 0, Z, Lambda, D, s);
+}
+
+static int fail(int code, const char* msg)
+{
+    set_error(msg);
+    return code;
+}
+
+static bool aligned8(const void* p) { return ((uintptr_t)p & 7u) == 0; }
+
+static int check_shape(int64_t n, int64_t m, int64_t r)
+{
+    if (n < 1 || m < 1 || r < 1) return fail(NQ_E_SHAPE, "lb_admm: n, m, r must be >= 1");
+    if (n > NQ_ADMM_MAX_DIM || m > NQ_ADMM_MAX_DIM || r > NQ_ADMM_MAX_RANK) return fail(NQ_E_SHAPE, "lb_admm: n, m or r beyond the supported size");
+    if ((uint64_t)n * (uint64_t)m >= (1ull << 40)) return fail(NQ_E_SHAPE, "lb_admm: n * m too large");
+    return NQ_OK;
+}
+
+}  // namespace nq
+
+using namespace nq;
+
+extern "C" int nq_lb_admm_workspace_bytes(int64_t n, int64_t m, int64_t r, size_t* bytes)
+{
+    if (!bytes) return fail(NQ_E_NULL, "lb_admm_workspace_bytes: bytes is NULL");
+    const int rc = check_shape(n, m, r);
+    if (rc != NQ_OK) return rc;
+    *bytes = carve(nullptr, n, m, r).bytes;
+    return NQ_OK;
+}
+
+extern "C" int nq_lb_admm(const double* W, int64_t n, int64_t m, int64_t r, const double* U0, const double* V0, int n_iters, double rho_start,
+                          double rho_end, double lambda, int power_iters, double* U, double* V, double* Z_U, double* Z_V, double* Lambda_U,
+                          double* Lambda_V, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!W || !U0 || !V0 || !U || !V || !Z_U || !Z_V || !Lambda_U || !Lambda_V || !workspace) return fail(NQ_E_NULL, "lb_admm: NULL pointer");
+    int rc = check_shape(n, m, r);
+    if (rc != NQ_OK) return rc;
+    const void* ptrs[] = {W, U0, V0, U, V, Z_U, Z_V, Lambda_U, Lambda_V};
+    for (const void* p : ptrs)
+        if (!aligned8(p)) return fail(NQ_E_ALIGN, "lb_admm: a matrix pointer is not 8-byte aligned");
+    if (((uintptr_t)workspace & 255u) != 0) return fail(NQ_E_ALIGN, "lb_admm: workspace is not 256-byte aligned");
+    if (n_iters < 0 || power_iters < 0) return fail(NQ_E_INVALID_ARG, "lb_admm: n_iters and power_iters must be >= 0");
+    if (!isfinite(rho_start) || !isfinite(rho_end) || !isfinite(lambda)) return fail(NQ_E_INVALID_ARG, "lb_admm: rho and lambda must be finite");
+    const AdmmWs ws = carve(workspace, n, m, r);
+    if (workspace_bytes < ws.bytes) return fail(NQ_E_INVALID_ARG, "lb_admm: workspace smaller than nq_lb_admm_workspace_bytes");
+    hipStream_t s = (hipStream_t)stream;
+    const int N = (int)n, M = (int)m, R = (int)r;
+
+    NQ_HIP(hipMemsetAsync(ws.status, 0, 256, s));
+    hipLaunchKernelGGL(pad_identity_kernel, dim3(256), dim3(256), 0, s, ws.H, ws.rp, R, 0);
+    hipLaunchKernelGGL(pad_identity_kernel, dim3(256), dim3(256), 0, s, ws.Linv, ws.rp, R, 1);
+    NQ_HIP(hipGetLastError());
+    if (U != U0) NQ_HIP(hipMemcpyAsync(U, U0, (size_t)n * r * sizeof(double), hipMemcpyDeviceToDevice, s));
+    if (V != V0) NQ_HIP(hipMemcpyAsync(V, V0, (size_t)m * r * sizeof(double), hipMemcpyDeviceToDevice, s));
+    // initial state: Z = SVID of the start factors, Lambda = 0
+    rc = svid(ws, U, N, R, power_iters, 1, Z_U, Lambda_U, ws.DU, s);
+    if (rc != NQ_OK) return rc;
+    rc = svid(ws, V, M, R, power_iters, 1, Z_V, Lambda_V, ws.DV, s);
+    if (rc != NQ_OK) return rc;
+    for (int k = 0; k < n_iters; ++k) {
+        const double rho = n_iters <= 1 ? rho_start : rho_start + (rho_end - rho_start) * (double)k / (double)(n_iters - 1);
+        rc = factor_step(ws, W, 0, M, N, M, R, V, rho, lambda, power_iters, U, Z_U, Lambda_U, ws.DU, s);
+        if (rc != NQ_OK) return rc;
+        rc = factor_step(ws, W, 1, M, M, N, R, U, rho, lambda, power_iters, V, Z_V, Lambda_V, ws.DV, s);
+        if (rc != NQ_OK) return rc;
+    }
+    int status = 0;
+    NQ_HIP(hipMemcpyAsync(&status, ws.status, sizeof(int), hipMemcpyDeviceToHost, s));
+    NQ_HIP(hipStreamSynchronize(s));
+    if (status != 0) return fail(NQ_E_INVALID_ARG, "lb_admm: a pivot of the Cholesky factorisation was not positive (rho + lambda <= 0, or NaN in the input)");
+    return NQ_OK;
+}
+
+extern "C" int nq_lb_admm_balance(const double* U, const double* Lambda_U, int64_t n, const double* V, const double* Lambda_V, int64_t m, int64_t r,
+                                  uint32_t* U_words, uint32_t* V_words, double* s1, double* s2, double* eta, void* workspace,
+                                  size_t workspace_bytes, void* stream)
+{
+    if (!U || !Lambda_U || !V || !Lambda_V || !U_words || !V_words || !s1 || !s2 || !eta || !workspace) return fail(NQ_E_NULL, "lb_admm_balance: NULL pointer");
+    const int rc = check_shape(n, m, r);
+    if (rc != NQ_OK) return rc;
+    const void* ptrs[] = {U, Lambda_U, V, Lambda_V, s1, s2, eta};
+    for (const void* p : ptrs)
+        if (!aligned8(p)) return fail(NQ_E_ALIGN, "lb_admm_balance: a pointer is not 8-byte aligned");
+    if (((uintptr_t)U_words & 3u) || ((uintptr_t)V_words & 3u)) return fail(NQ_E_ALIGN, "lb_admm_balance: word pointers must be 4-byte aligned");
+    if (((uintptr_t)workspace & 255u) != 0) return fail(NQ_E_ALIGN, "lb_admm_balance: workspace is not 256-byte aligned");
+    const AdmmWs ws = carve(workspace, n, m, r);
+    if (workspace_bytes < ws.bytes) return fail(NQ_E_INVALID_ARG, "lb_admm_balance: workspace smaller than nq_lb_admm_workspace_bytes");
+    hipStream_t s = (hipStream_t)stream;
+    hipLaunchKernelGGL(sumsq_kernel, dim3(kSumParts), dim3(256), 0, s, U, Lambda_U, (size_t)n * r, ws.parts_u);
+    hipLaunchKernelGGL(sumsq_kernel, dim3(kSumParts), dim3(256), 0, s, V, Lambda_V, (size_t)m * r, ws.parts_v);
+    hipLaunchKernelGGL(balance_rows_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, s, U, Lambda_U, (int)n, (int)r, (const double*)ws.parts_u,
+                       (const double*)ws.parts_v, 0, U_words, s1, eta);
+    hipLaunchKernelGGL(balance_rows_kernel, dim3((unsigned)((m + 3) / 4)), dim3(256), 0, s, V, Lambda_V, (int)m, (int)r, (const double*)ws.parts_u,
+                       (const double*)ws.parts_v, 1, V_words, s2, (double*)nullptr);
+    NQ_HIP(hipGetLastError());
+    return NQ_OK;
+}
+
+extern "C" int nq_dgemm(int trans_a, int trans_b, int64_t M, int64_t N, int64_t K, double alpha, const double* A, int64_t lda, const double* B,
+                        int64_t ldb, double beta, double* C, int64_t ldc, void* stream)
+{
+    if (!A || !B || !C) return fail(NQ_E_NULL, "dgemm: NULL pointer");
+    if (M < 1 || N < 1 || K < 1 || M > NQ_ADMM_MAX_DIM || N > NQ_ADMM_MAX_DIM || K > NQ_ADMM_MAX_DIM) return fail(NQ_E_SHAPE, "dgemm: M, N, K must be in [1, 65536]");
+    if ((trans_a | trans_b) & ~1) return fail(NQ_E_INVALID_ARG, "dgemm: trans flags are 0 or 1");
+    if (lda < (trans_a ? M : K) || ldb < (trans_b ? K : N) || ldc < N || lda > INT32_MAX || ldb > INT32_MAX || ldc > INT32_MAX)
+        return fail(NQ_E_SHAPE, "dgemm: a leading dimension is smaller than its row length");
+    if (!aligned8(A) || !aligned8(B) || !aligned8(C)) return fail(NQ_E_ALIGN, "dgemm: a pointer is not 8-byte aligned");
+    GemmArgs g = gemm_args(trans_a, trans_b, (int)M, (int)N, (int)K, alpha, A, (int)lda, B, (int)ldb, beta, C, (int)ldc, C, (int)ldc);
+    return launch_gemm(g, 1, (hipStream_t)stream);
+}

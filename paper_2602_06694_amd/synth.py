@@ -242,3 +242,18 @@ def gen_chained_stack(cfg: int, n_blocks: int | None = None) -> List[LayerData]:
             carry[i] = at_input + gain - k
             out.append(LayerData(shp, d.U_words, d.V_words, s_out, s_in))
     return out
+
+
+def gen_admm_problem(n: int, m: int, r: int, seed: int) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Inputs of the latent-binary factorisation of one matrix (no arithmetic of the method here): a target
+    W [n, m] shaped like a trained weight matrix (a decaying low-rank part plus dense noise, standard deviation
+    about 0.02) and start factors U0 [n, r], V0 [m, r] (i.i.d. normal, scaled so that U0 V0^T has W's scale)."""
+    g = _rng(seed)
+    k = max(1, min(n, m) // 8)
+    decay = 1.0 / np.sqrt(1.0 + np.arange(k))
+    low = (g.standard_normal((n, k)) * decay) @ g.standard_normal((k, m))
+    w = 0.02 * (0.7 * low / np.sqrt((decay ** 2).sum()) + 0.7 * g.standard_normal((n, m)))
+    s = np.sqrt(0.02 / np.sqrt(r))
+    u0 = s * g.standard_normal((n, r))
+    v0 = s * g.standard_normal((m, r))
+    return w, u0, v0

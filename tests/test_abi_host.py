@@ -16,9 +16,13 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_functions():
-    src = open(os.path.join(ROOT, "include", "nq_binlr.h")).read()
-    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(nq_[a-z0-9_]+)\s*\(", src)))
+    import glob
+    names = set()
+    for path in sorted(glob.glob(os.path.join(ROOT, "include", "*.h"))):
+        src = open(path).read()
+        src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+        names |= set(re.findall(r"\b(nq_[a-z0-9_]+)\s*\(", src))
+    return sorted(names)
 
 
 def test_library_loads_and_exports_every_declared_symbol():
@@ -26,7 +30,7 @@ def test_library_loads_and_exports_every_declared_symbol():
     names = declared_functions()
     assert len(names) >= 17, names
     for n in names:
-        assert hasattr(L, n), f"{n} declared in include/nq_binlr.h but not exported"
+        assert hasattr(L, n), f"{n} declared in include/*.h but not exported"
 
 
 def test_binding_has_every_declared_name():
@@ -139,3 +143,21 @@ def test_no_environment_lookup_on_a_launch_path():
             if "getenv" in line and not line.lstrip().startswith("//"):
                 hits.append((os.path.basename(f), i))
     assert len(hits) == 1 and hits[0][0] == "nq_api.hip", hits
+
+
+def test_lb_admm_host_checks():
+    """Argument checks of the LB-ADMM entry points that need no GPU."""
+    b = nq.nq_lb_admm_workspace_bytes(4096, 4096, 1024)
+    # four padded r x r matrices and four n x r ones at least, in binary64
+    assert b >= 8 * (4 * 1024 * 1024 + 4 * 4096 * 1024) and b % 256 == 0
+    assert nq.nq_lb_admm_workspace_bytes(100, 70, 65) >= 8 * 4 * 128 * 128
+    for bad in ((0, 4, 4), (4, 0, 4), (4, 4, 0), (nq.NQ_ADMM_MAX_DIM + 1, 4, 4), (4, 4, nq.NQ_ADMM_MAX_RANK + 1)):
+        with pytest.raises(nq.NQError) as e:
+            nq.nq_lb_admm_workspace_bytes(*bad)
+        assert e.value.status == nq.NQ_E_SHAPE
+    L = nq.lib()
+    assert L.nq_lb_admm(None, 4, 4, 2, None, None, 1, 1.0, 1.0, 0.0, 1, None, None, None, None, None, None, None, 0, None) == nq.NQ_E_NULL
+    assert L.nq_dgemm(0, 0, 4, 4, 4, 1.0, None, 4, None, 4, 0.0, None, 4, None) == nq.NQ_E_NULL
+    assert L.nq_dgemm(0, 0, 4, 4, 4, 1.0, 8, 3, 8, 4, 0.0, 8, 4, None) == nq.NQ_E_SHAPE      # lda < K
+    assert L.nq_dgemm(2, 0, 4, 4, 4, 1.0, 8, 4, 8, 4, 0.0, 8, 4, None) == nq.NQ_E_INVALID_ARG
+    assert L.nq_dgemm(0, 0, 4, 4, 4, 1.0, 12, 4, 8, 4, 0.0, 8, 4, None) == nq.NQ_E_ALIGN

@@ -51,7 +51,7 @@ def parse_args():
                     help="headline workload only: skip the extra fields (70B stack decode, config-5 prefill)")
     ap.add_argument("--case", default="",
                     help="run ONE of the side workloads only and print its JSON (for profiling a single case): "
-                         "prefill:<gate|down>:<batch> | pool_b8 | stack3 | stack4 | chain3 | chain4")
+                         "prefill:<gate|down>:<batch> | pool_b8 | stack3 | stack4 | chain3 | chain4 | admm")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (reference for rocprofv3 --pmc byte counters)")
     return ap.parse_args()
@@ -404,6 +404,62 @@ def time_single_layer(cfg, reps=200):
     return {"shape": [shp.d_out, shp.d_in, shp.r], "us_per_forward": us, "cache_hot_weight_GBps": wb / us / 1e3}
 
 
+def time_lb_admm(n=4096, m=4096, r=1024, iters=10, power_iters=8, with_oracle=False):
+    """LB-ADMM (Section 3.2 Step 2-2) on one synthetic matrix of config 2's shape: time per iteration, the
+    binary64 GEMM behind it on the iteration's three product shapes, and (optionally) one oracle iteration."""
+    import torch
+    from paper_2602_06694_amd import binding as nq
+    from paper_2602_06694_amd import synth
+    w, u0, v0 = synth.gen_admm_problem(n, m, r, seed=42)
+    dev = lambda a: torch.from_numpy(a).cuda()
+    dw, du0, dv0 = dev(w), dev(u0), dev(v0)
+    nbytes = nq.nq_lb_admm_workspace_bytes(n, m, r)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    out = [torch.empty((n if i % 2 == 0 else m, r), dtype=torch.float64, device="cuda") for i in range(6)]
+
+    def run(k):
+        nq.nq_lb_admm(dw, n, m, r, du0, dv0, k, 0.02, 0.3, 1e-3, power_iters, out[0], out[1], out[2], out[3], out[4], out[5], ws, nbytes)
+    run(2)
+    torch.cuda.synchronize()
+    win = []
+    for _ in range(5):
+        t0 = time.perf_counter(); run(0); torch.cuda.synchronize(); t_init = time.perf_counter() - t0
+        t0 = time.perf_counter(); run(iters); torch.cuda.synchronize(); t_all = time.perf_counter() - t0
+        win.append((t_all - t_init) * 1e3 / iters)
+    ms = window_stats(win)["median"]
+    # algorithmic flops of one iteration: two products with W, two symmetric Gram matrices, two Cholesky
+    # factorisations, and two triangular solves for every row of U and of V
+    flops = 2 * (2.0 * n * m * r) + (m + n) * float(r) * r + 2 * r ** 3 / 3.0 + 2.0 * (n + m) * r * r
+    res = {"shape": [n, m, r], "iterations_timed": iters, "power_iters": power_iters, "ms_per_iteration": ms,
+           "ms_per_iteration_windows": window_stats(win), "algorithmic_GFLOP_per_iteration": flops / 1e9,
+           "TFLOPs_algorithmic": flops / ms / 1e9, "frac_of_fp64_matrix_peak": flops / ms / 1e9 / 78.6, "dgemm": {}}
+    for name, ta, tb, M, N, K in (("W.V", 0, 0, n, r, m), ("W^T.U", 1, 0, m, r, n), ("V^T.V", 1, 0, r, r, m), ("RHS.Hinv", 0, 0, n, r, r)):
+        a = torch.randn((K, M) if ta else (M, K), dtype=torch.float64, device="cuda")
+        b = torch.randn((K, N), dtype=torch.float64, device="cuda")
+        c = torch.empty((M, N), dtype=torch.float64, device="cuda")
+        f = lambda: nq.nq_dgemm(ta, tb, M, N, K, 1.0, a, a.shape[1], b, N, 0.0, c, N)
+        prewarm(f, 0.03)
+        gw = []
+        for _ in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(10):
+                f()
+            e1.record()
+            torch.cuda.synchronize()
+            gw.append(e0.elapsed_time(e1) / 10)
+        g_ms = window_stats(gw)["median"]
+        res["dgemm"][name] = {"M": M, "N": N, "K": K, "ms": g_ms, "TFLOPs": 2.0 * M * N * K / g_ms / 1e9,
+                              "frac_of_fp64_matrix_peak": 2.0 * M * N * K / g_ms / 1e9 / 78.6}
+    if with_oracle:
+        from oracle import lb_admm as O
+        t0 = time.perf_counter()
+        O.lb_admm(w, u0, v0, 1, 0.02, 0.3, 1e-3, power_iters)
+        res["oracle_s_per_iteration"] = time.perf_counter() - t0
+        res["oracle_cores"] = os.cpu_count()
+    return res
+
+
 def time_prefill(args, only_layer=None, only_batch=None):
     """Config-5 shapes through nq_binlr_forward at batch 512 / 2048 (TFLOP/s = 2 B r (d_in + d_out) / time)."""
     import numpy as np
@@ -467,6 +523,8 @@ def main():
             res = time_stack(int(kind[0][-1]), 1)
         elif kind[0] in ("chain3", "chain4"):
             res = time_stack_in_dependency_order(int(kind[0][-1]))
+        elif kind[0] == "admm":
+            res = time_lb_admm(with_oracle=not args.no_cpu_baseline)
         else:
             print(f"bench.py: unknown --case {args.case}", file=sys.stderr)
             sys.exit(2)
@@ -596,7 +654,8 @@ def main():
                         "decode_llama2_70b_stack_b1": time_stack(4, 1),
                         "decode_llama2_7b_in_dependency_order_b1": time_stack_in_dependency_order(3),
                         "decode_llama2_70b_in_dependency_order_b1": time_stack_in_dependency_order(4),
-                        "prefill_config5": time_prefill(args)}
+                        "prefill_config5": time_prefill(args),
+                        "lb_admm_cfg2_shape_f64": time_lb_admm(iters=5, with_oracle=not args.no_cpu_baseline)}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(work, batch, args.cpu_seconds)
 

@@ -61,6 +61,7 @@ extern "C" {
 #define NQ_F32  1
 #define NQ_F16  2   /* IEEE binary16 */
 #define NQ_BF16 3
+#define NQ_F64  4   /* IEEE binary64: nq_lb_admm.h and nq_probe_mfma only */
 
 /* nq_binlr_create flags */
 #define NQ_FLAG_DEFAULT      0u
@@ -300,7 +301,8 @@ int nq_binlr_read_intermediate(nq_handle h, float* t_host, int batch);
 int nq_probe_hbm_read(size_t bytes, int iters, int prewarm_ms, double* gb_per_s);
 /* A register-resident loop of dense matrix-core instructions on every CU: dtype NQ_F16 (fp16 operands,
  * fp32 accumulation; the prefill path's instruction) or NQ_I8 (int8, int32 accumulation; the decode
- * path's).  Returns 1e12 operations per second (one multiply-add = 2).  Synchronises. */
+ * path's) or NQ_F64 (binary64, the LB-ADMM products').  Returns 1e12 operations per second (one
+ * multiply-add = 2).  Synchronises. */
 int nq_probe_mfma(int dtype, double* tera_ops_per_s);
 
 /* ---- tuning options (process-wide) ----
@@ -309,7 +311,7 @@ int nq_probe_mfma(int dtype, double* tera_ops_per_s);
  * "force_w", "split_steps", "selfq4_min_steps", "share_steps", "share_min_batch", "stream_steps",
  * "schedule_full", "fuse_max_mb", "no_fuse", "no_selfq", "no_selfq_c2", "no_resident",
  * "no_quant_wave", "pf_splits1", "pf_splits2", "pf_tg1", "pf_tg2", "pf_ks1", "pf_ks2", "pf_verbose",
- * "exec_spin_limit_us", "no_small_layer", "small_layer_kb" (see the source for the meaning of each).  value < 0 restores the default.
+ * "exec_spin_limit_us", "no_small_layer", "small_layer_kb", "dgemm_tile", "admm_no_overlap" (see the source for the meaning of each).  value < 0 restores the default.
  * The environment variable NQ_<NAME IN CAPITALS> gives an option its initial value; it is read once,
  * when the library first consults an option, never on a launch path.  Plans keep the schedules
  * chosen when they were created.  Not thread-safe against forwards running at the same time.

@@ -16,7 +16,7 @@ import numpy as np
 
 NQ_OK = 0
 NQ_E_INVALID_ARG, NQ_E_SHAPE, NQ_E_ALIGN, NQ_E_NULL, NQ_E_UNSUPPORTED, NQ_E_HIP, NQ_E_TIMEOUT = -1, -2, -3, -4, -5, -6, -7
-NQ_I8, NQ_F32, NQ_F16, NQ_BF16 = 0, 1, 2, 3
+NQ_I8, NQ_F32, NQ_F16, NQ_BF16, NQ_F64 = 0, 1, 2, 3, 4
 NQ_FLAG_DEFAULT, NQ_FLAG_DECODE_VALU, NQ_FLAG_NO_PREFILL = 0, 1, 2
 NQ_MAX_DIM = 65536
 NQ_DECODE_MAX_BATCH = 8

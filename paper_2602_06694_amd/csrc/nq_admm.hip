@@ -37,18 +37,24 @@ constexpr int kBK = 16;        // reduction depth of one LDS tile = four 16x16x4
 
 // A workgroup of four waves (2 x 2) owns a BM x BN tile of C; each wave (BM/2) x (BN/2) of it as
 // 16 x 16 accumulator tiles.  v_mfma_f64_16x16x4_f64: lane l supplies A[l & 15][l >> 4] and B[l >> 4][l & 15],
-// and holds C[4 v + (l >> 4)][l & 15] in element v of its four accumulators.  Operand tiles go through LDS as
-// [k][i] and [k][j] (row pitch BM + 16: the four k rows a wave reads at once fall on different bank halves),
-// double buffered: the global loads of tile kt + 1 are in flight while tile kt is multiplied.
+// and holds C[4 v + (l >> 4)][l & 15] in element v of its four accumulators.  Operand tiles go through LDS, double
+// buffered: the global loads of tile kt + 1 are in flight while tile kt is multiplied.  The LDS layout of an
+// operand follows the memory layout of its source, so that both the staging stores and the operand reads are
+// free of bank conflicts: a source that is contiguous along the reduction (A stored [M][K], B stored [N][K]) is kept
+// as [i][k] with a row pitch of 17 doubles, one that is contiguous along the tile's rows or columns as [k][i] with
+// a pitch of BM + 16.  Two workgroups fit a CU (registers and LDS), so one's staging overlaps the other's products.
 template <int BM, int BN>
-__global__ __launch_bounds__(kGemmThreads) void dgemm_kernel(GemmArgs g)
+__global__ __launch_bounds__(kGemmThreads, 2) void dgemm_kernel(GemmArgs g)
 {
+    constexpr int PK = kBK + 1;
     constexpr int PA = BM + 16, PB = BN + 16;
+    constexpr int SA = BM * PK > kBK * PA ? BM * PK : kBK * PA;
+    constexpr int SB = BN * PK > kBK * PB ? BN * PK : kBK * PB;
     constexpr int TM = BM / 32, TN = BN / 32;
     constexpr int LA = BM * kBK / kGemmThreads, LB = BN * kBK / kGemmThreads;
     extern __shared__ __align__(16) double lds_gemm[];
-    double (*As)[kBK][PA] = reinterpret_cast<double (*)[kBK][PA]>(lds_gemm);
-    double (*Bs)[kBK][PB] = reinterpret_cast<double (*)[kBK][PB]>(lds_gemm + 2 * kBK * PA);
+    double* As = lds_gemm;                 // [2][SA]
+    double* Bs = lds_gemm + 2 * SA;        // [2][SB]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i0 = blockIdx.y * BM, j0 = blockIdx.x * BN;
@@ -58,6 +64,7 @@ __global__ __launch_bounds__(kGemmThreads) void dgemm_kernel(GemmArgs g)
     const int k_begin = g.k_from_max ? ((i0 > j0 ? i0 : j0) / kBK) * kBK : 0;
     const int n_kt = g.K > k_begin ? (g.K - k_begin + kBK - 1) / kBK : 0;
     const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
+    const bool ta = g.trans_a != 0, tb = g.trans_b != 0;
 
     double ra[LA], rb[LB];
     auto fetch = [&](int kt) {
@@ -65,19 +72,19 @@ __global__ __launch_bounds__(kGemmThreads) void dgemm_kernel(GemmArgs g)
 #pragma unroll
         for (int p = 0; p < LA; ++p) {
             const int idx = p * kGemmThreads + tid;
-            const int i = g.trans_a ? idx % BM : idx / kBK, k = g.trans_a ? idx / BM : idx % kBK;
+            const int i = ta ? idx % BM : idx / kBK, k = ta ? idx / BM : idx % kBK;
             const int gi = i0 + i, gk = k0 + k;
             double v = 0.0;
-            if (gi < g.M && gk < g.K) v = g.trans_a ? A[(size_t)gk * g.lda + gi] : A[(size_t)gi * g.lda + gk];
+            if (gi < g.M && gk < g.K) v = ta ? A[(size_t)gk * g.lda + gi] : A[(size_t)gi * g.lda + gk];
             ra[p] = v;
         }
 #pragma unroll
         for (int p = 0; p < LB; ++p) {
             const int idx = p * kGemmThreads + tid;
-            const int j = g.trans_b ? idx / kBK : idx % BN, k = g.trans_b ? idx % kBK : idx / BN;
+            const int j = tb ? idx / kBK : idx % BN, k = tb ? idx % kBK : idx / BN;
             const int gj = j0 + j, gk = k0 + k;
             double v = 0.0;
-            if (gj < g.N && gk < g.K) v = g.trans_b ? B[(size_t)gj * g.ldb + gk] : B[(size_t)gk * g.ldb + gj];
+            if (gj < g.N && gk < g.K) v = tb ? B[(size_t)gj * g.ldb + gk] : B[(size_t)gk * g.ldb + gj];
             rb[p] = v;
         }
     };
@@ -85,14 +92,14 @@ __global__ __launch_bounds__(kGemmThreads) void dgemm_kernel(GemmArgs g)
 #pragma unroll
         for (int p = 0; p < LA; ++p) {
             const int idx = p * kGemmThreads + tid;
-            const int i = g.trans_a ? idx % BM : idx / kBK, k = g.trans_a ? idx / BM : idx % kBK;
-            As[buf][k][i] = ra[p];
+            const int i = ta ? idx % BM : idx / kBK, k = ta ? idx / BM : idx % kBK;
+            As[buf * SA + (ta ? k * PA + i : i * PK + k)] = ra[p];
         }
 #pragma unroll
         for (int p = 0; p < LB; ++p) {
             const int idx = p * kGemmThreads + tid;
-            const int j = g.trans_b ? idx / kBK : idx % BN, k = g.trans_b ? idx % kBK : idx / BN;
-            Bs[buf][k][j] = rb[p];
+            const int j = tb ? idx / kBK : idx % BN, k = tb ? idx % kBK : idx / BN;
+            Bs[buf * SB + (tb ? j * PK + k : k * PB + j)] = rb[p];
         }
     };
 
@@ -102,6 +109,12 @@ __global__ __launch_bounds__(kGemmThreads) void dgemm_kernel(GemmArgs g)
 #pragma unroll
         for (int b = 0; b < TN; ++b) acc[a][b] = v4d{0.0, 0.0, 0.0, 0.0};
 
+    // per-lane offsets of the operand reads: element (row l & 15 of a 16-row group, depth l >> 4 of a group of four)
+    const int a_off = ta ? (lane >> 4) * PA + wm0 + (lane & 15) : (wm0 + (lane & 15)) * PK + (lane >> 4);
+    const int a_dk = ta ? 4 * PA : 4, a_dt = ta ? 16 : 16 * PK;
+    const int b_off = tb ? (wn0 + (lane & 15)) * PK + (lane >> 4) : (lane >> 4) * PB + wn0 + (lane & 15);
+    const int b_dk = tb ? 4 : 4 * PB, b_dt = tb ? 16 * PK : 16;
+
     if (n_kt > 0) {
         fetch(0);
         stash(0);
@@ -110,14 +123,15 @@ __global__ __launch_bounds__(kGemmThreads) void dgemm_kernel(GemmArgs g)
     for (int kt = 0; kt < n_kt; ++kt) {
         const int buf = kt & 1;
         if (kt + 1 < n_kt) fetch(kt + 1);
+        const double* Ab = As + buf * SA + a_off;
+        const double* Bb = Bs + buf * SB + b_off;
 #pragma unroll
         for (int k4 = 0; k4 < kBK / 4; ++k4) {
             double a[TM], b[TN];
-            const int kk = k4 * 4 + (lane >> 4);
 #pragma unroll
-            for (int t = 0; t < TM; ++t) a[t] = As[buf][kk][wm0 + t * 16 + (lane & 15)];
+            for (int t = 0; t < TM; ++t) a[t] = Ab[k4 * a_dk + t * a_dt];
 #pragma unroll
-            for (int t = 0; t < TN; ++t) b[t] = Bs[buf][kk][wn0 + t * 16 + (lane & 15)];
+            for (int t = 0; t < TN; ++t) b[t] = Bb[k4 * b_dk + t * b_dt];
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
@@ -148,30 +162,41 @@ __global__ __launch_bounds__(kGemmThreads) void dgemm_kernel(GemmArgs g)
             }
 }
 
-template <int BM, int BN> constexpr size_t gemm_lds_bytes() { return (size_t)2 * kBK * ((BM + 16) + (BN + 16)) * sizeof(double); }
+template <int BM, int BN> constexpr size_t gemm_lds_bytes()
+{
+    constexpr int PK = kBK + 1;
+    constexpr int SA = BM * PK > kBK * (BM + 16) ? BM * PK : kBK * (BM + 16);
+    constexpr int SB = BN * PK > kBK * (BN + 16) ? BN * PK : kBK * (BN + 16);
+    return (size_t)2 * (SA + SB) * sizeof(double);
+}
 
+template <int BM, int BN> static int launch_gemm_tile(const GemmArgs& g, int batch, hipStream_t s)
+{
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    constexpr size_t lds = gemm_lds_bytes<BM, BN>();
+    std::call_once(once, [] {
+        if (lds > 65536)
+            attr_err = hipFuncSetAttribute((const void*)dgemm_kernel<BM, BN>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    });
+    NQ_HIP(attr_err);
+    dim3 grid((g.N + BN - 1) / BN, (g.M + BM - 1) / BM, batch);
+    hipLaunchKernelGGL((dgemm_kernel<BM, BN>), grid, dim3(kGemmThreads), lds, s, g);
+    NQ_HIP(hipGetLastError());
+    return NQ_OK;
+}
+
+// Tile choice: the largest tile that still gives every CU two workgroups; the option "dgemm_tile" (1: 128 x 128,
+// 2: 128 x 64, 3: 64 x 64) overrides it.
 static int launch_gemm(const GemmArgs& g, int batch, hipStream_t s)
 {
     if (g.M < 1 || g.N < 1 || batch < 1) return NQ_OK;
-    static std::once_flag once;
-    static hipError_t attr_err = hipSuccess;
-    std::call_once(once, [] {
-        attr_err = hipFuncSetAttribute((const void*)dgemm_kernel<128, 128>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)gemm_lds_bytes<128, 128>());
-    });
-    NQ_HIP(attr_err);
-    const long long tiles128 = (long long)((g.M + 127) / 128) * ((g.N + 127) / 128) * batch;
-    if (tiles128 >= 192) {
-        dim3 grid((g.N + 127) / 128, (g.M + 127) / 128, batch);
-        const size_t lds = gemm_lds_bytes<128, 128>();
-        hipLaunchKernelGGL((dgemm_kernel<128, 128>), grid, dim3(kGemmThreads), lds, s, g);
-    } else {
-        dim3 grid((g.N + 63) / 64, (g.M + 63) / 64, batch);
-        const size_t lds = gemm_lds_bytes<64, 64>();
-        hipLaunchKernelGGL((dgemm_kernel<64, 64>), grid, dim3(kGemmThreads), lds, s, g);
-    }
-    NQ_HIP(hipGetLastError());
-    return NQ_OK;
+    auto tiles = [&](int bm, int bn) { return (long long)((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn) * batch; };
+    int choice = opt_or(OPT_DGEMM_TILE, 0);
+    if (choice < 1 || choice > 3) choice = tiles(128, 128) >= 512 ? 1 : tiles(128, 64) >= 384 ? 2 : 3;
+    if (choice == 1) return launch_gemm_tile<128, 128>(g, batch, s);
+    if (choice == 2) return launch_gemm_tile<128, 64>(g, batch, s);
+    return launch_gemm_tile<64, 64>(g, batch, s);
 }
 
 static GemmArgs gemm_args(int ta, int tb, int M, int N, int K, double alpha, const double* A, int lda, const double* B, int ldb,
@@ -191,18 +216,32 @@ static GemmArgs gemm_args(int ta, int tb, int M, int N, int K, double alpha, con
 // ============================================================================================
 constexpr int kNB = 64;
 
-// 256 threads as 16 x 16, thread (ty, tx) keeps the 4 x 4 sub-blocks of the matrix (a) and of the running right-hand
-// side of L X = I (b, starts as the identity) in registers.  Step j of the right-looking elimination needs column j
-// of the current matrix and row j of the current right-hand side: their owners publish them in LDS at the end of
-// step j - 1 (double buffered), so a step costs one barrier.  Every thread derives the pivot's square root and the
-// scaled column entries it needs itself.  H (lower part) is overwritten by L; the block of Linv receives L^-1 with
-// an exactly zero upper part.  A pivot that is not > 0 sets *status (the results are then meaningless, every thread
-// still finishes).
+__device__ __forceinline__ double readlane_f64(double v, int lane)
+{
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), lane);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), lane);
+    return __hiloint2double(hi, lo);
+}
+
+// 256 threads as 16 column groups x 16 row groups (the 16 row groups of a column group are 16 adjacent lanes of one
+// wave); a thread keeps the 4 x 4 sub-blocks of the matrix (a) and of the running right-hand side of L X = I (b, starts
+// as the identity) in registers.  The elimination advances by panels of four columns:
+//   * the wave that holds the panel factorises it on its own: pivot and multipliers travel by lane reads, the square
+//     root and its reciprocal come from the hardware's reciprocal-square-root estimate refined by two coupled Newton
+//     steps and a residual correction (ten dependent operations; within an ulp or two); it then publishes the four
+//     scaled columns (zero at and above their pivot) and the reciprocal pivots in LDS;
+//   * after ONE barrier everybody applies the rank-4 update to its blocks right of the panel, the threads that hold
+//     rows of the panel finish those rows of X with the panel's 4 x 4 triangle, hand them to their column group by
+//     lane shuffles, and the rows below get their rank-4 update of b.
+// LDS buffers alternate between panels, so the next panel's columns never overwrite ones still being read.
+// H (lower part) is overwritten by L; the block of Linv receives L^-1 with an exactly zero upper part.  A pivot that is
+// not > 0 sets *status (the results are then meaningless, every thread still finishes).
 __global__ __launch_bounds__(256) void potrf_inv64_kernel(double* H, int ldh, double* Linv, int ldi, int o, int* status)
 {
-    __shared__ double colraw[2][kNB];
-    __shared__ double brow[2][kNB];
-    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    __shared__ double colL[2][4][kNB];
+    __shared__ double dinv[2][4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int tx = threadIdx.x >> 4, ty = threadIdx.x & 15;
     double a[4][4], b[4][4];
 #pragma unroll
     for (int ii = 0; ii < 4; ++ii)
@@ -211,63 +250,88 @@ __global__ __launch_bounds__(256) void potrf_inv64_kernel(double* H, int ldh, do
             a[ii][cc] = H[(size_t)(o + 4 * ty + ii) * ldh + o + 4 * tx + cc];
             b[ii][cc] = (4 * ty + ii == 4 * tx + cc) ? 1.0 : 0.0;
         }
-    if (tx == 0)
-#pragma unroll
-        for (int ii = 0; ii < 4; ++ii) colraw[0][4 * ty + ii] = a[ii][0];
-    if (ty == 0)
-#pragma unroll
-        for (int cc = 0; cc < 4; ++cc) brow[0][4 * tx + cc] = b[0][cc];
-    __syncthreads();
     bool bad = false;
-    for (int j = 0; j < kNB; ++j) {
-        const int cur = j & 1, jb = j >> 2, jj = j & 3;
-        const double piv = colraw[cur][j];
-        if (!(piv > 0.0)) bad = true;
-        const double d = sqrt(piv);
-        const double inv = 1.0 / d;
-        double lrow[4], lcol[4], x[4];
+    for (int jb = 0; jb < kNB / 4; ++jb) {
+        const int buf = jb & 1;
+        if (wave == (jb >> 2)) {
+            const int src = 16 * (jb & 3) + jb;            // lane of the thread that holds the panel's diagonal block
+            const bool mine = tx == jb;
 #pragma unroll
-        for (int ii = 0; ii < 4; ++ii) lrow[ii] = (4 * ty + ii > j) ? colraw[cur][4 * ty + ii] * inv : 0.0;
+            for (int jj = 0; jj < 4; ++jj) {
+                const int j = 4 * jb + jj;
+                const double piv = readlane_f64(a[jj][jj], src);
+                if (!(piv > 0.0)) bad = true;
+                const double y = __builtin_amdgcn_rsq(piv);
+                double g = piv * y, h = 0.5 * y;
+                double e = fma(-h, g, 0.5);
+                g = fma(g, e, g);
+                h = fma(h, e, h);
+                e = fma(-h, g, 0.5);
+                g = fma(g, e, g);
+                h = fma(h, e, h);
+                e = fma(-g, g, piv);
+                g = fma(e, h, g);
+                const double d = g, inv = 2.0 * h;
+                double l[4];
 #pragma unroll
-        for (int cc = 0; cc < 4; ++cc) {
-            lcol[cc] = (4 * tx + cc > j) ? colraw[cur][4 * tx + cc] * inv : 0.0;
-            x[cc] = brow[cur][4 * tx + cc] * inv;
-        }
-        if (tx == jb)                                   // column j of L
+                for (int ii = 0; ii < 4; ++ii) {
+                    const int row = 4 * ty + ii;
+                    l[ii] = row > j ? a[ii][jj] * inv : 0.0;
+                    if (mine && row >= j) a[ii][jj] = row == j ? d : l[ii];
+                }
 #pragma unroll
-            for (int ii = 0; ii < 4; ++ii)
+                for (int cc = jj + 1; cc < 4; ++cc) {
+                    const double lc = readlane_f64(a[cc][jj], src);       // L[4 jb + cc][j]
+                    if (mine)
 #pragma unroll
-                for (int cc = 0; cc < 4; ++cc)
-                    if (cc == jj) a[ii][cc] = (4 * ty + ii == j) ? d : lrow[ii];
-        if (ty == jb)                                   // row j of X = L^-1
+                        for (int ii = 0; ii < 4; ++ii) a[ii][cc] = fma(-l[ii], lc, a[ii][cc]);
+                }
+                if (mine)
 #pragma unroll
-            for (int ii = 0; ii < 4; ++ii)
-#pragma unroll
-                for (int cc = 0; cc < 4; ++cc)
-                    if (ii == jj) b[ii][cc] = x[cc];
-#pragma unroll
-        for (int ii = 0; ii < 4; ++ii)
-#pragma unroll
-            for (int cc = 0; cc < 4; ++cc) {
-                a[ii][cc] = fma(-lrow[ii], lcol[cc], a[ii][cc]);     // lrow = 0 at and above row j, lcol = 0 up to column j
-                b[ii][cc] = fma(-lrow[ii], x[cc], b[ii][cc]);
+                    for (int ii = 0; ii < 4; ++ii) colL[buf][jj][4 * ty + ii] = l[ii];
+                if (lane == src) dinv[buf][jj] = inv;
             }
-        if (j + 1 < kNB) {
-            const int nb = (j + 1) >> 2, nj = (j + 1) & 3;
-            if (tx == nb)
-#pragma unroll
-                for (int ii = 0; ii < 4; ++ii)
-#pragma unroll
-                    for (int cc = 0; cc < 4; ++cc)
-                        if (cc == nj) colraw[cur ^ 1][4 * ty + ii] = a[ii][cc];
-            if (ty == nb)
-#pragma unroll
-                for (int ii = 0; ii < 4; ++ii)
-#pragma unroll
-                    for (int cc = 0; cc < 4; ++cc)
-                        if (ii == nj) brow[cur ^ 1][4 * tx + cc] = b[ii][cc];
         }
         __syncthreads();
+        double lr[4][4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int ii = 0; ii < 4; ++ii) lr[q][ii] = colL[buf][q][4 * ty + ii];
+        if (tx > jb) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int cc = 0; cc < 4; ++cc) {
+                    const double lc = colL[buf][q][4 * tx + cc];
+#pragma unroll
+                    for (int ii = 0; ii < 4; ++ii) a[ii][cc] = fma(-lr[q][ii], lc, a[ii][cc]);
+                }
+        }
+        if (ty == jb) {                                    // rows 4 jb .. 4 jb + 3 of X
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int cc = 0; cc < 4; ++cc) {
+                    double acc = b[q][cc];
+#pragma unroll
+                    for (int p = 0; p < q; ++p) acc = fma(-colL[buf][p][4 * jb + q], b[p][cc], acc);
+                    b[q][cc] = acc * dinv[buf][q];
+                }
+        }
+        double xs[4][4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int cc = 0; cc < 4; ++cc) xs[q][cc] = __shfl(b[q][cc], (lane & 48) | jb);
+        if (ty > jb) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+                    for (int cc = 0; cc < 4; ++cc) b[ii][cc] = fma(-lr[q][ii], xs[q][cc], b[ii][cc]);
+        }
     }
 #pragma unroll
     for (int ii = 0; ii < 4; ++ii)
@@ -277,7 +341,7 @@ __global__ __launch_bounds__(256) void potrf_inv64_kernel(double* H, int ldh, do
             if (c <= i) H[(size_t)(o + i) * ldh + o + c] = a[ii][cc];
             Linv[(size_t)(o + i) * ldi + o + c] = (c <= i) ? b[ii][cc] : 0.0;
         }
-    if (bad && threadIdx.x == 0) *status = 1;
+    if (bad) *status = 1;
 }
 
 // Identity outside the leading r x r part of a [rp][rp] matrix (the padding that keeps the block algorithms
@@ -314,84 +378,116 @@ __device__ __forceinline__ double block_sum(double v, double* scratch4)
     return (scratch4[0] + scratch4[1]) + (scratch4[2] + scratch4[3]);
 }
 
+constexpr int kWParts = 8;      // the vector of a round is kept as eight partial vectors, added in a fixed order by its readers
+
+__device__ __forceinline__ double w_at(const double* w8, int r, int k)
+{
+    return ((w8[k] + w8[r + k]) + (w8[2 * r + k] + w8[3 * r + k])) + ((w8[4 * r + k] + w8[5 * r + k]) + (w8[6 * r + k] + w8[7 * r + k]));
+}
+
 // One round of the power iteration in one pass over P [n][r]: for the 16 rows of this workgroup
 //     a_i = sum_k |P[i][k]| b_k          with b = w / ||w||   (w: the unnormalised vector of the round before)
 // and, unless `rows_only`, this workgroup's part of the next unnormalised vector  w'_k = sum_i |P[i][k]| a_i
 // (partial[g][k]; a second kernel adds the parts in a fixed order).  `ones`: a_i = 1 instead (the start vector;
-// its scale does not matter, the next round normalises).
-__global__ __launch_bounds__(256) void power_pass_kernel(const double* P, int n, int r, const double* w, int ones, int rows_only,
+// its scale does not matter, the next round normalises).  w is staged in LDS (dynamic, r doubles).
+__global__ __launch_bounds__(256) void power_pass_kernel(const double* P, int n, int r, const double* w8, int ones, int rows_only,
                                                           double* a_out, double* partial)
 {
+    extern __shared__ __align__(16) double w_s[];
     __shared__ double red[4];
     __shared__ double a_s[kRowsPerWg];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int row0 = blockIdx.x * kRowsPerWg;
     if (!ones) {
         double q = 0.0;
-        for (int k = tid; k < r; k += 256) q = fma(w[k], w[k], q);
-        const double inv = 1.0 / sqrt(block_sum(q, red));
-        for (int rr = 0; rr < kRowsPerWg / 4; ++rr) {
-            const int i = row0 + wave * (kRowsPerWg / 4) + rr;
-            double d = 0.0;
-            if (i < n)
-                for (int k = lane; k < r; k += 64) d = fma(fabs(P[(size_t)i * r + k]), w[k], d);
-            d = wave_sum(d) * inv;
+        for (int k = tid; k < r; k += 256) {
+            const double v = w_at(w8, r, k);
+            w_s[k] = v;
+            q = fma(v, v, q);
+        }
+        const double inv = 1.0 / sqrt(block_sum(q, red));           // its barriers also publish w_s
+        constexpr int RW = kRowsPerWg / 4;                          // rows per wave, taken together
+        double d[RW];
+        const double* rowp[RW];
+#pragma unroll
+        for (int rr = 0; rr < RW; ++rr) {
+            const int i = row0 + wave * RW + rr;
+            d[rr] = 0.0;
+            rowp[rr] = P + (size_t)(i < n ? i : n - 1) * r;        // a row beyond the end reads the last row, its result is dropped
+        }
+#pragma unroll 2
+        for (int k = lane; k < r; k += 64) {
+            const double wk = w_s[k];
+#pragma unroll
+            for (int rr = 0; rr < RW; ++rr) d[rr] = fma(fabs(rowp[rr][k]), wk, d[rr]);
+        }
+#pragma unroll
+        for (int rr = 0; rr < RW; ++rr) {
+            const int i = row0 + wave * RW + rr;
+            const double v = wave_sum(d[rr]) * inv;
             if (lane == 0) {
-                a_s[wave * (kRowsPerWg / 4) + rr] = d;
-                if (i < n) a_out[i] = d;
+                a_s[wave * RW + rr] = i < n ? v : 0.0;
+                if (i < n) a_out[i] = v;
             }
         }
     } else if (tid < kRowsPerWg) {
-        a_s[tid] = 1.0;
+        a_s[tid] = row0 + tid < n ? 1.0 : 0.0;
     }
     __syncthreads();
     if (rows_only) return;
     for (int k = tid; k < r; k += 256) {
         double c = 0.0;
-#pragma unroll 4
+#pragma unroll
         for (int rr = 0; rr < kRowsPerWg; ++rr) {
             const int i = row0 + rr;
-            if (i < n) c = fma(fabs(P[(size_t)i * r + k]), a_s[rr], c);
+            c = fma(fabs(P[(size_t)(i < n ? i : n - 1) * r + k]), a_s[rr], c);      // a_s = 0 beyond the end
         }
         partial[(size_t)blockIdx.x * r + k] = c;
     }
 }
 
-// w[k] = sum_g partial[g][k], parts added in index order (four interleaved partial sums, then a fixed tree).
-__global__ __launch_bounds__(256) void power_reduce_kernel(const double* partial, int n_parts, int r, double* w)
+// w8[q][k] = sum over the parts g = q, q + 8, q + 16, ... of partial[g][k], added in index order by four threads per
+// column whose results are combined in a fixed tree.
+__global__ __launch_bounds__(256) void power_reduce_kernel(const double* partial, int n_parts, int r, double* w8)
 {
     __shared__ double s[4][64];
-    const int c = threadIdx.x & 63, q = threadIdx.x >> 6;
-    const int k = blockIdx.x * 64 + c;
+    const int c = threadIdx.x & 63, t = threadIdx.x >> 6;
+    const int k = blockIdx.x * 64 + c, q = blockIdx.y;
     double acc = 0.0;
     if (k < r)
-        for (int g = q; g < n_parts; g += 4) acc += partial[(size_t)g * r + k];
-    s[q][c] = acc;
+        for (int g = q + kWParts * t; g < n_parts; g += kWParts * 4) acc += partial[(size_t)g * r + k];
+    s[t][c] = acc;
     __syncthreads();
-    if (q == 0 && k < r) w[k] = (s[0][c] + s[1][c]) + (s[2][c] + s[3][c]);
+    if (t == 0 && k < r) w8[(size_t)q * r + k] = (s[0][c] + s[1][c]) + (s[2][c] + s[3][c]);
 }
 
 // Z = sign(P) (.) (a b^T) with b = w / ||w||  (power_iters = 0: the constant sum(w) / (n r), w = |P|^T 1),
 // and the dual update in its two forms:  first = 0:  Lambda = P - Z  (P = X + Lambda_old, so this is
 // Lambda_old + X - Z),  D = Z - Lambda;   first = 1 (initial state):  Lambda = 0,  D = Z.
-__global__ __launch_bounds__(256) void svid_finish_kernel(const double* P, int n, int r, const double* a, const double* w, int zero_rounds,
+__global__ __launch_bounds__(256) void svid_finish_kernel(const double* P, int n, int r, const double* a, const double* w8, int zero_rounds,
                                                            int first, double* Z, double* Lambda, double* D)
 {
+    extern __shared__ __align__(16) double w_s[];
     __shared__ double red[4];
     const int tid = threadIdx.x;
     double q = 0.0;
-    for (int k = tid; k < r; k += 256) q = zero_rounds ? q + w[k] : fma(w[k], w[k], q);
+    for (int k = tid; k < r; k += 256) {
+        const double v = w_at(w8, r, k);
+        w_s[k] = v;
+        q = zero_rounds ? q + v : fma(v, v, q);
+    }
     const double tot = block_sum(q, red);
     const double scale = zero_rounds ? tot / ((double)n * (double)r) : 1.0 / sqrt(tot);
     const int row0 = blockIdx.x * kRowsPerWg;
-    for (int rr = 0; rr < kRowsPerWg; ++rr) {
-        const int i = row0 + rr;
-        if (i >= n) break;
-        const double ai = zero_rounds ? 1.0 : a[i];
-        for (int k = tid; k < r; k += 256) {
+    for (int k = tid; k < r; k += 256) {
+        const double bk = zero_rounds ? scale : w_s[k] * scale;
+#pragma unroll 4
+        for (int rr = 0; rr < kRowsPerWg; ++rr) {
+            const int i = row0 + rr;
+            if (i >= n) break;
             const size_t e = (size_t)i * r + k;
             const double p = P[e];
-            const double mag = zero_rounds ? scale : ai * (w[k] * scale);
+            const double mag = zero_rounds ? scale : a[i] * bk;
             const double z = (p >= 0.0) ? mag : -mag;
             Z[e] = z;
             const double lam = first ? 0.0 : p - z;
@@ -478,7 +574,7 @@ static AdmmWs carve(void* base, int64_t n, int64_t m, int64_t r)
     ws.H = take(sq); ws.Linv = take(sq); ws.Hinv = take(sq); ws.T = take(sq);
     ws.RHS = take((size_t)big * r); ws.P = take((size_t)big * r);
     ws.DU = take((size_t)n * r); ws.DV = take((size_t)m * r);
-    ws.a = take(big); ws.w = take(r);
+    ws.a = take(big); ws.w = take((size_t)kWParts * r);
     ws.partial = take((size_t)((big + kRowsPerWg - 1) / kRowsPerWg) * r);
     ws.parts_u = take(kSumParts); ws.parts_v = take(kSumParts);
     ws.status = (int*)take(32);
@@ -490,17 +586,26 @@ static AdmmWs carve(void* base, int64_t n, int64_t m, int64_t r)
 static int svid(const AdmmWs& ws, const double* P, int rows, int r, int iters, int first, double* Z, double* Lambda, double* D, hipStream_t s)
 {
     const int n_wg = (rows + kRowsPerWg - 1) / kRowsPerWg;
-    const int red_wg = (r + 63) / 64;
+    const dim3 red_grid((r + 63) / 64, kWParts);
+    const size_t lds = (size_t)r * sizeof(double);
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [] {        // r doubles of dynamic LDS plus the kernels' own few words can pass 64 KiB at the largest rank
+        const int most = NQ_ADMM_MAX_RANK * (int)sizeof(double);
+        attr_err = hipFuncSetAttribute((const void*)power_pass_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, most);
+        if (attr_err == hipSuccess) attr_err = hipFuncSetAttribute((const void*)svid_finish_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, most);
+    });
+    NQ_HIP(attr_err);
     // w = |P|^T 1
-    hipLaunchKernelGGL(power_pass_kernel, dim3(n_wg), dim3(256), 0, s, P, rows, r, (const double*)nullptr, 1, 0, ws.a, ws.partial);
-    hipLaunchKernelGGL(power_reduce_kernel, dim3(red_wg), dim3(256), 0, s, ws.partial, n_wg, r, ws.w);
+    hipLaunchKernelGGL(power_pass_kernel, dim3(n_wg), dim3(256), lds, s, P, rows, r, (const double*)nullptr, 1, 0, ws.a, ws.partial);
+    hipLaunchKernelGGL(power_reduce_kernel, red_grid, dim3(256), 0, s, ws.partial, n_wg, r, ws.w);
     for (int it = 0; it < iters; ++it) {
         // a = |P| b with b = w / ||w||; and, except in the last round, the next w = |P|^T a
         const int last = it + 1 == iters;
-        hipLaunchKernelGGL(power_pass_kernel, dim3(n_wg), dim3(256), 0, s, P, rows, r, (const double*)ws.w, 0, last, ws.a, ws.partial);
-        if (!last) hipLaunchKernelGGL(power_reduce_kernel, dim3(red_wg), dim3(256), 0, s, ws.partial, n_wg, r, ws.w);
+        hipLaunchKernelGGL(power_pass_kernel, dim3(n_wg), dim3(256), lds, s, P, rows, r, (const double*)ws.w, 0, last, ws.a, ws.partial);
+        if (!last) hipLaunchKernelGGL(power_reduce_kernel, red_grid, dim3(256), 0, s, ws.partial, n_wg, r, ws.w);
     }
-    hipLaunchKernelGGL(svid_finish_kernel, dim3(n_wg), dim3(256), 0, s, P, rows, r, (const double*)ws.a, (const double*)ws.w, iters == 0 ? 1 : 0, first,
+    hipLaunchKernelGGL(svid_finish_kernel, dim3(n_wg), dim3(256), lds, s, P, rows, r, (const double*)ws.a, (const double*)ws.w, iters == 0 ? 1 : 0, first,
                        Z, Lambda, D);
     NQ_HIP(hipGetLastError());
     return NQ_OK;
@@ -547,23 +652,53 @@ static int factor_and_invert(const AdmmWs& ws, hipStream_t s)
     return launch_gemm(h, 1, s);
 }
 
+// A second stream and two events, created once: the product with W does not depend on the factorisation, so it runs
+// beside it (the factorisation is a chain of small launches that leaves most of the chip idle).
+struct SideStream {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+    hipError_t err = hipSuccess;
+};
+
+static SideStream& side_stream()
+{
+    static SideStream ss;
+    static std::once_flag once;
+    std::call_once(once, [] {
+        ss.err = hipStreamCreateWithFlags(&ss.stream, hipStreamNonBlocking);
+        if (ss.err == hipSuccess) ss.err = hipEventCreateWithFlags(&ss.fork, hipEventDisableTiming);
+        if (ss.err == hipSuccess) ss.err = hipEventCreateWithFlags(&ss.join, hipEventDisableTiming);
+    });
+    return ss;
+}
+
 // One factor update of Eq. 5 and Eq. 6 for X [rows][r] given the other factor O [cols][r]:
 //   op(W) is [rows][cols] (w_trans = 1: W is stored [cols][rows]).
 static int factor_step(const AdmmWs& ws, const double* W, int w_trans, int ldw, int rows, int cols, int r, const double* O, double rho, double lam,
                        int power_iters, double* X, double* Z, double* Lambda, double* D, hipStream_t s)
 {
-    // H = O^T O + (rho + lambda) I   (lower tiles)
+    const bool overlap = !opt_flag(OPT_ADMM_NO_OVERLAP);
+    SideStream& ss = side_stream();
+    NQ_HIP(ss.err);
+    // RHS = op(W) O + rho (Z - Lambda), on the side stream
+    hipStream_t rs = overlap ? ss.stream : s;
+    if (overlap) {
+        NQ_HIP(hipEventRecord(ss.fork, s));
+        NQ_HIP(hipStreamWaitEvent(ss.stream, ss.fork, 0));
+    }
+    GemmArgs gr = gemm_args(w_trans, 0, rows, r, cols, 1.0, W, ldw, O, r, rho, D, r, ws.RHS, r);
+    int rc = launch_gemm(gr, 1, rs);
+    if (rc != NQ_OK) return rc;
+    if (overlap) NQ_HIP(hipEventRecord(ss.join, ss.stream));
+    // H = O^T O + (rho + lambda) I   (lower tiles), its factor and inverse
     GemmArgs gh = gemm_args(1, 0, r, r, cols, 1.0, O, r, O, r, 0.0, nullptr, 0, ws.H, ws.rp);
     gh.diag = rho + lam;
     gh.lower_only = 1;
-    int rc = launch_gemm(gh, 1, s);
+    rc = launch_gemm(gh, 1, s);
     if (rc != NQ_OK) return rc;
     rc = factor_and_invert(ws, s);
     if (rc != NQ_OK) return rc;
-    // RHS = op(W) O + rho (Z - Lambda)
-    GemmArgs gr = gemm_args(w_trans, 0, rows, r, cols, 1.0, W, ldw, O, r, rho, D, r, ws.RHS, r);
-    rc = launch_gemm(gr, 1, s);
-    if (rc != NQ_OK) return rc;
+    if (overlap) NQ_HIP(hipStreamWaitEvent(s, ss.join, 0));
     // X = RHS H^-1,  P = X + Lambda
     GemmArgs gx = gemm_args(0, 0, rows, r, r, 1.0, ws.RHS, r, ws.Hinv, ws.rp, 0.0, nullptr, 0, X, r);
     gx.E = Lambda;

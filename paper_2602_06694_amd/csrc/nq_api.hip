@@ -39,6 +39,7 @@ static const OptEntry kOptTable[OPT_COUNT] = {
     {"no_fuse", true}, {"no_selfq", true}, {"no_selfq_c2", true}, {"no_resident", true}, {"no_quant_wave", true},
     {"pf_splits1", false}, {"pf_splits2", false}, {"pf_tg1", false}, {"pf_tg2", false}, {"pf_ks1", false}, {"pf_ks2", false},
     {"pf_verbose", true}, {"exec_spin_limit_us", false}, {"no_small_layer", true}, {"small_layer_kb", false},
+    {"dgemm_tile", false}, {"admm_no_overlap", true},
 };
 static int g_opt[OPT_COUNT];
 static std::once_flag g_opt_once;

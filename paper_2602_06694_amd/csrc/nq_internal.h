@@ -119,6 +119,8 @@ enum Opt {
     OPT_EXEC_SPIN_LIMIT_US, // wall-clock limit, in microseconds, of every wait inside the dependent-layer executor (2 s)
     OPT_NO_SMALL_LAYER,     // flag: a lone small layer at batch 1 never takes the one-workgroup, one-launch kernel
     OPT_SMALL_LAYER_KB,     // packed size (KiB, both factors) up to which it does (160)
+    OPT_DGEMM_TILE,         // tile of the binary64 product: 1 = 128 x 128, 2 = 128 x 64, 3 = 64 x 64 (default: by size)
+    OPT_ADMM_NO_OVERLAP,    // flag: LB-ADMM runs the product with W on the caller's stream instead of beside the factorisation
     OPT_COUNT
 };
 int opt(Opt o);                                        // -1 when unset

@@ -74,6 +74,24 @@ __global__ void __launch_bounds__(256) probe_mfma_kernel(float* __restrict__ sin
     if (s == 123.456f) sink[threadIdx.x] = s;
 }
 
+typedef double pv4d __attribute__((ext_vector_type(4)));
+
+// The same loop with the binary64 instruction (16 x 16 x 4, 2048 operations each).  Eight accumulators, two rounds
+// per iteration: with sixteen the same loop measured a quarter slower.
+__global__ __launch_bounds__(256) void probe_mfma_f64_kernel(float* sink, int iters)
+{
+    pv4d acc[8];
+    for (int i = 0; i < 8; ++i) acc[i] = pv4d{0, 0, 0, 0};
+    const double a = threadIdx.x * 0.001 + 1.0, b = 1.0 + threadIdx.x * 0.5;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i & 7] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc[i & 7], 0, 0, 0);
+    }
+    double s = 0.0;
+    for (int i = 0; i < 8; ++i) s += acc[i].x + acc[i].y;
+    if (s == 123.456) sink[threadIdx.x] = (float)s;
+}
+
 }  // namespace nq
 
 using namespace nq;
@@ -134,21 +152,22 @@ done:
 extern "C" int nq_probe_mfma(int dtype, double* tera_ops_per_s)
 {
     if (!tera_ops_per_s) return fail(NQ_E_NULL, "nq_probe_mfma: NULL result pointer");
-    if (dtype != NQ_F16 && dtype != NQ_I8) return fail(NQ_E_INVALID_ARG, "nq_probe_mfma: dtype must be NQ_F16 or NQ_I8");
+    if (dtype != NQ_F16 && dtype != NQ_I8 && dtype != NQ_F64) return fail(NQ_E_INVALID_ARG, "nq_probe_mfma: dtype must be NQ_F16, NQ_I8 or NQ_F64");
     int rc = NQ_OK;
     float* sink = nullptr;
     hipEvent_t e0 = nullptr, e1 = nullptr;
-    const int iters = 4000, reps = 3;
+    const int iters = dtype == NQ_F64 ? 1000 : 4000, reps = 3;
     const int blocks = device_cu_count() * 2;                 // 4 waves each: two waves per SIMD
     float ms = 0.f;
     // one instruction = 16 x 16 x K multiply-adds, K = 32 (fp16) or 64 (int8)
-    const double ops_per_launch = (double)blocks * 4 * iters * 16 * (dtype == NQ_F16 ? 16384.0 : 32768.0);
+    const double ops_per_launch = (double)blocks * 4 * iters * 16 * (dtype == NQ_F16 ? 16384.0 : dtype == NQ_I8 ? 32768.0 : 2048.0);
     PROBE_HIP(hipMalloc((void**)&sink, 256 * 4));
     PROBE_HIP(hipEventCreate(&e0));
     PROBE_HIP(hipEventCreate(&e1));
     for (int i = 0; i < reps + 1; ++i) {
         if (i == 1) PROBE_HIP(hipEventRecord(e0, nullptr));
-        if (dtype == NQ_F16) hipLaunchKernelGGL(probe_mfma_kernel<false>, dim3(blocks), dim3(256), 0, nullptr, sink, iters);
+        if (dtype == NQ_F64) hipLaunchKernelGGL(probe_mfma_f64_kernel, dim3(blocks), dim3(256), 0, nullptr, sink, iters);
+        else if (dtype == NQ_F16) hipLaunchKernelGGL(probe_mfma_kernel<false>, dim3(blocks), dim3(256), 0, nullptr, sink, iters);
         else hipLaunchKernelGGL(probe_mfma_kernel<true>, dim3(blocks), dim3(256), 0, nullptr, sink, iters);
     }
     PROBE_HIP(hipEventRecord(e1, nullptr));

@@ -451,6 +451,18 @@ def time_lb_admm(n=4096, m=4096, r=1024, iters=10, power_iters=8, with_oracle=Fa
         g_ms = window_stats(gw)["median"]
         res["dgemm"][name] = {"M": M, "N": N, "K": K, "ms": g_ms, "TFLOPs": 2.0 * M * N * K / g_ms / 1e9,
                               "frac_of_fp64_matrix_peak": 2.0 * M * N * K / g_ms / 1e9 / 78.6}
+    # what a register-resident loop of the same instruction reaches on this chip, and the clocks under that product
+    res["mfma_f64_loop_TFLOPs"] = nq.nq_probe_mfma(nq.NQ_F64)
+    a = torch.randn((n, m), dtype=torch.float64, device="cuda")
+    b = torch.randn((m, r), dtype=torch.float64, device="cuda")
+    c = torch.empty((n, r), dtype=torch.float64, device="cuda")
+    clocks = ClockSampler()
+    t0 = time.perf_counter()
+    while clocks.proc is not None and clocks.proc.poll() is None and time.perf_counter() - t0 < 20.0:
+        for _ in range(20):
+            nq.nq_dgemm(0, 0, n, r, m, 1.0, a, m, b, r, 0.0, c, r)
+        torch.cuda.synchronize()
+    res["observed_clocks_under_dgemm"] = clocks.read()
     if with_oracle:
         from oracle import lb_admm as O
         t0 = time.perf_counter()

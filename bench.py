@@ -51,7 +51,7 @@ def parse_args():
                     help="headline workload only: skip the extra fields (70B stack decode, config-5 prefill)")
     ap.add_argument("--case", default="",
                     help="run ONE of the side workloads only and print its JSON (for profiling a single case): "
-                         "prefill:<gate|down>:<batch> | pool_b8 | stack3 | stack4 | chain3 | chain4 | admm")
+                         "prefill:<gate|down>:<batch> | pool_b<1..8> | stack3 | stack4 | chain3 | chain4 | admm")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (reference for rocprofv3 --pmc byte counters)")
     return ap.parse_args()
@@ -529,8 +529,8 @@ def main():
         kind = args.case.split(":")
         if kind[0] == "prefill":
             res = time_prefill(args, kind[1], int(kind[2]))
-        elif kind[0] == "pool_b8":
-            res = time_pool_batch(args.pool, 8)
+        elif kind[0].startswith("pool_b") and kind[0][6:].isdigit():
+            res = time_pool_batch(args.pool, int(kind[0][6:]))
         elif kind[0] in ("stack3", "stack4"):
             res = time_stack(int(kind[0][-1]), 1)
         elif kind[0] in ("chain3", "chain4"):

@@ -186,14 +186,23 @@ int nq_binlr_forward_exact(nq_handle h, const void* x, void* y, int batch, void*
  * For a loss L with upstream gradient g = dL/dy ([batch, d_out]):
  *     dL/ds_out = sum_b g_b (.) z_b,                 z = U (V^T (s_in (.) x))        (the forward without s_out)
  *     dL/ds_in  = sum_b x_b (.) w_b,                 w = V (U^T (s_out (.) g))
- * z comes from nq_binlr_forward_unscaled on the layer; w from the same call on the transposed layer
- * (nq_binlr_create with U and V, and s_out and s_in, exchanged: its forward without output scale
- * is V (U^T (s_out (.) g))); nq_scale_grad does the products and the sum over the batch. */
+ * z comes from nq_binlr_forward_unscaled, w from nq_binlr_forward_transposed_unscaled on the SAME
+ * layer object (the transposed products read the resident bits; no second copy of the weights);
+ * nq_scale_grad does the products and the sum over the batch. */
 
 /* z = U (V^T (s_in (.) x)) [(.) s_mid where set]: the forward without its output scale.  Pointers
  * and types as in nq_binlr_forward (z has y_dtype).  Any batch, run as passes of up to 8 tokens through the
  * streaming kernels (exact integer accumulation).  Asynchronous on `stream`. */
 int nq_binlr_forward_unscaled(nq_handle h, const void* x, void* z, int batch, void* stream);
+
+/* w = V (s_mid (.) (U^T (s_out (.) g))): the layer's transpose applied to g without the input scale
+ * (s_mid only where nq_binlr_set_mid_scale has set one).
+ * g: device, [batch, d_out] row-major of the layer's y_dtype;  w: device, [batch, d_in] floats.
+ * Any batch (passes of up to 8 tokens).  Sign products are exact and added in binary64 on the vector
+ * ALU, each result is rounded once to fp32 (u = U^T(..) between the two products likewise).  The first
+ * call on a layer allocates its workspace (and synchronises the device then); afterwards the call is
+ * asynchronous on `stream`.  g and w must be 16-byte aligned. */
+int nq_binlr_forward_transposed_unscaled(nq_handle h, const void* g, float* w, int batch, void* stream);
 
 /* out[j] = sum_{b < batch} a[b][j] * b[b][j], j < n.  a, b: device, [batch, n] row-major of a_dtype /
  * b_dtype (NQ_F32, NQ_F16, NQ_BF16); out: device float [n].  fp64 accumulation, one rounding.

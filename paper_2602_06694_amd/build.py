@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libnq_binlr.so")
-SOURCES = ["nq_api.hip", "nq_admm.hip", "nq_decode.hip", "nq_exec.hip", "nq_prefill.hip", "nq_probe.hip"]
+SOURCES = ["nq_api.hip", "nq_admm.hip", "nq_decode.hip", "nq_exec.hip", "nq_prefill.hip", "nq_probe.hip", "nq_transposed.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -343,6 +343,7 @@ static void free_handle(nq_handle h)
     slab_release(h->w_slab, h->w_alloc, h->w_bytes);
     slab_release(h->ws_slab, h->ws_alloc, h->ws_bytes);
     if (h->pf_alloc) (void)hipFree(h->pf_alloc);
+    if (h->tp_alloc) (void)hipFree(h->tp_alloc);
     if (h->s_mid) (void)hipFree(h->s_mid);
     delete h;
 }
@@ -1079,6 +1080,44 @@ extern "C" int nq_binlr_forward_unscaled(nq_handle h, const void* x, void* z, in
 extern "C" int nq_binlr_forward_exact(nq_handle h, const void* x, void* y, int batch, void* stream)
 {
     return forward_in_passes("nq_binlr_forward_exact", h, x, y, batch, stream, false);
+}
+
+extern "C" int nq_binlr_forward_transposed_unscaled(nq_handle h, const void* g, float* w, int batch, void* stream)
+{
+    if (!h) return fail(NQ_E_NULL, "nq_binlr_forward_transposed_unscaled: NULL handle");
+    if (batch < 1) return fail(NQ_E_INVALID_ARG, "nq_binlr_forward_transposed_unscaled: batch must be >= 1");
+    const size_t gs = dtype_size(h->y_dtype);
+    int rc = check_xy("nq_binlr_forward_transposed_unscaled", g, w, (size_t)batch * h->d_out * gs, (size_t)batch * h->d_in * sizeof(float));
+    if (rc != NQ_OK) return rc;
+    // workspace for passes of up to 8 tokens: the intermediate u = s_mid (.) U^T (s_out (.) g) [8][r padded], then the
+    // partial sums of the larger of the two products
+    const int nb_max = NQ_DECODE_MAX_BATCH;
+    const size_t r_pad = (size_t)n_steps(h->r) * kTileCols;
+    const size_t u_bytes = align_up(nb_max * r_pad * sizeof(float), 256);
+    const size_t need = u_bytes + std::max(gemv_t_partial_bytes(h->d_out, h->r, nb_max), gemv_t_partial_bytes(h->r, h->d_in, nb_max));
+    if (h->tp_bytes < need) {
+        NQ_HIP(hipDeviceSynchronize());
+        if (h->tp_alloc) NQ_HIP(hipFree(h->tp_alloc));
+        h->tp_alloc = nullptr;
+        h->tp_bytes = 0;
+        NQ_HIP(hipMalloc(&h->tp_alloc, need));
+        h->tp_bytes = need;
+    }
+    float* u = (float*)h->tp_alloc;
+    double* partial = (double*)((char*)h->tp_alloc + u_bytes);
+    hipStream_t s = (hipStream_t)stream;
+    for (int b0 = 0; b0 < batch; b0 += nb_max) {
+        const int nb = std::min(nb_max, batch - b0);
+        // u = s_mid (.) U^T (s_out (.) g): the tiles of U ([d_out][r]) read along their columns
+        rc = launch_gemv_t(h->u_tiles, h->d_out, h->r, (const char*)g + (size_t)b0 * h->d_out * gs, h->y_dtype, (int)h->d_out, h->s_out,
+                           h->s_mid, u, NQ_F32, (int)r_pad, nb, partial, s);
+        if (rc != NQ_OK) return rc;
+        // w = V u: the tiles of V^T ([r][d_in]) read along their columns
+        rc = launch_gemv_t(h->vt_tiles, h->r, h->d_in, u, NQ_F32, (int)r_pad, nullptr, nullptr, w + (size_t)b0 * h->d_in, NQ_F32,
+                           (int)h->d_in, nb, partial, s);
+        if (rc != NQ_OK) return rc;
+    }
+    return NQ_OK;
 }
 
 extern "C" int nq_scale_grad(const void* a, int a_dtype, const void* b, int b_dtype, int batch, int64_t n, float* out,

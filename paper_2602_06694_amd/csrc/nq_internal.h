@@ -210,6 +210,9 @@ struct nq_binlr_s {
     void* pf_alloc;
     size_t pf_bytes;
     int pf_batch;
+    // workspace of the transposed products (allocated by their first call)
+    void* tp_alloc;
+    size_t tp_bytes;
 };
 
 
@@ -261,6 +264,11 @@ int launch_valu_gemv(const uint32_t* tiles, const void* x, int x_dtype, int x_st
 int device_cu_count();
 int schedule_full_rowblocks();
 int shared_min_batch();          // smallest batch that takes the shared-input kernel in launches that fill the chip            // row blocks from which a launch counts as filling the chip
+
+// ---- launchers (nq_transposed.hip) -----------------------------------------------------------
+size_t gemv_t_partial_bytes(int64_t M, int64_t N, int batch);
+int launch_gemv_t(const uint32_t* tiles, int64_t M, int64_t N, const void* in, int in_dtype, int in_stride, const uint16_t* in_scale,
+                  const uint16_t* out_scale, void* out, int out_dtype, int out_stride, int batch, double* partial, hipStream_t s);
 
 // ---- launchers (nq_exec.hip) ---------------------------------------------------------------
 bool small_layer_fits(nq_handle h, int batch);

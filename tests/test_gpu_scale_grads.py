@@ -1,6 +1,6 @@
 """GPU parity of the scale gradients with frozen signs (Section 3.4; Algorithm 1, Phase 3) against the
-fp64 oracle, through the C ABI: unscaled forwards of the layer and of its transpose, then the reduction
-over the batch."""
+fp64 oracle, through the C ABI: the unscaled forward of the layer, the unscaled transposed product from the SAME
+layer object (no second copy of the bits), then the reduction over the batch."""
 import numpy as np
 import pytest
 
@@ -18,8 +18,7 @@ def test_scale_gradients_match_oracle(shape, batch):
     d_out, d_in, r = shape
     L = Layer(d_out, d_in, r, "f32", seed=4000 + r)
     d = L.data
-    # the transposed layer: factors and scale vectors exchanged
-    T = nq.nq_binlr_create(d_in, d_out, r, d.V_words, d.U_words, d.s_in, d.s_out, nq.NQ_F32, nq.NQ_F32, 0)
+    weight_bytes = nq.nq_binlr_weight_bytes(L.h)
     x_np = synth.gen_x(batch, d_in, 4100 + batch, "f32")
     g_np = synth.gen_x(batch, d_out, 4200 + batch, "f32")
     x, g = to_device(x_np, "f32"), to_device(g_np, "f32")
@@ -28,7 +27,8 @@ def test_scale_gradients_match_oracle(shape, batch):
     ds_out = torch.zeros(d_out, dtype=torch.float32, device="cuda")
     ds_in = torch.zeros(d_in, dtype=torch.float32, device="cuda")
     nq.nq_binlr_forward_unscaled(L.h, x, z, batch)
-    nq.nq_binlr_forward_unscaled(T, g, w, batch)
+    nq.nq_binlr_forward_transposed_unscaled(L.h, g, w, batch)
+    assert nq.nq_binlr_weight_bytes(L.h) == weight_bytes
     nq.nq_scale_grad(g, nq.NQ_F32, z, nq.NQ_F32, batch, d_out, ds_out)
     nq.nq_scale_grad(x, nq.NQ_F32, w, nq.NQ_F32, batch, d_in, ds_in)
     torch.cuda.synchronize()
@@ -40,8 +40,47 @@ def test_scale_gradients_match_oracle(shape, batch):
                                          x_np.astype(np.float64), g_np.astype(np.float64))
     assert np.abs(ds_out.cpu().numpy() - ref_out).max() <= 1e-5 * np.abs(ref_out).max(), (shape, batch)
     assert np.abs(ds_in.cpu().numpy() - ref_in).max() <= 1e-5 * np.abs(ref_in).max(), (shape, batch)
+    # w itself against the definition: V (U^T (s_out (.) g)) with the signs unpacked on the host
+    U = nq.nq_unpack_signs(d.U_words, r).astype(np.float64)
+    V = nq.nq_unpack_signs(d.V_words, r).astype(np.float64)
+    w_ref = ((g_np.astype(np.float64) * d.s_out.astype(np.float64)) @ U) @ V.T
+    assert rel_err(w.cpu().numpy(), w_ref) <= 1e-6
+    # and against the old route: a second layer object built from the exchanged factors
+    T = nq.nq_binlr_create(d_in, d_out, r, d.V_words, d.U_words, d.s_in, d.s_out, nq.NQ_F32, nq.NQ_F32, 0)
+    w2 = torch.full((batch, d_in), float("nan"), dtype=torch.float32, device="cuda")
+    nq.nq_binlr_forward_unscaled(T, g, w2, batch)
+    torch.cuda.synchronize()
+    assert rel_err(w2.cpu().numpy(), w_ref) <= 1e-5
     nq.nq_binlr_destroy(T)
     L.close()
+
+
+def test_transposed_product_types_mid_scale_and_checks():
+    import torch
+    d_out, d_in, r, batch = 260, 130, 70, 11
+    for y_dtype in ("f32", "bf16", "f16"):
+        L = Layer(d_out, d_in, r, "bf16", seed=4400, y_dtype=y_dtype)
+        d = L.data
+        s_mid = (np.random.default_rng(4401).standard_normal(r) * 0.5 + 1.0).astype(np.float16)
+        g_np = synth.gen_x(batch, d_out, 4402, y_dtype)
+        g = to_device(g_np, y_dtype)
+        w = torch.full((batch, d_in), float("nan"), dtype=torch.float32, device="cuda")
+        U = nq.nq_unpack_signs(d.U_words, r).astype(np.float64)
+        V = nq.nq_unpack_signs(d.V_words, r).astype(np.float64)
+        g64 = synth.x_as_f64(g_np, y_dtype)
+        for mid in (None, s_mid):
+            nq.nq_binlr_set_mid_scale(L.h, mid)
+            nq.nq_binlr_forward_transposed_unscaled(L.h, g, w, batch)
+            torch.cuda.synchronize()
+            u = (g64 * d.s_out.astype(np.float64)) @ U
+            if mid is not None:
+                u = u * mid.astype(np.float64)
+            assert rel_err(w.cpu().numpy(), u @ V.T) <= 1e-6, (y_dtype, mid is not None)
+        with pytest.raises(nq.NQError):
+            nq.nq_binlr_forward_transposed_unscaled(L.h, g, w, 0)
+        with pytest.raises(nq.NQError):
+            nq.nq_binlr_forward_transposed_unscaled(L.h, None, w, 1)
+        L.close()
 
 
 def test_batch_reduction_kernel_types_and_checks():

@@ -484,29 +484,32 @@ def time_prefill(args, only_layer=None, only_batch=None):
         if only_layer and shp.name != only_layer:
             continue
         data = synth.gen_layer(5, 0, li, shp)
-        h = nq.nq_binlr_create(shp.d_out, shp.d_in, shp.r, data.U_words, data.V_words, data.s_out, data.s_in, nq.NQ_BF16)
-        for B in ((only_batch,) if only_batch else c.batches):
-            nq.nq_binlr_reserve(h, B)
-            xb = synth.gen_layer_x(5, 0, li, shp, B, "bf16", c.outlier_frac)
-            x = torch.from_numpy(xb.view(np.int16).copy()).view(torch.bfloat16).cuda()
-            y = torch.empty((B, shp.d_out), dtype=torch.float32, device="cuda")
-            prewarm(lambda: nq.nq_binlr_forward(h, x, y, B), 0.03)
-            win = []
-            for _ in range(5):
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                iters = 10
-                e0.record()
-                for _ in range(iters):
-                    nq.nq_binlr_forward(h, x, y, B)
-                e1.record()
-                torch.cuda.synchronize()
-                win.append(e0.elapsed_time(e1) / iters)
-            ms = window_stats(win)["median"]
-            flops = 2.0 * B * shp.r * (shp.d_in + shp.d_out)
-            res[f"{shp.name}_{shp.d_out}x{shp.d_in}_B{B}"] = {"ms": ms, "ms_windows": window_stats(win), "TFLOP/s": flops / ms / 1e9,
-                                                             "frac_of_f16_mfma_peak": flops / ms / 1e9 / MFMA_F16_PEAK_TFLOPS}
-            del x, y
-        nq.nq_binlr_destroy(h)
+        # fp32 outputs (the parity bar's type) and bf16 outputs (what a bf16 model consumes; the fp32 result rounded once more)
+        for y_name, y_code, y_torch in (("f32", nq.NQ_F32, torch.float32), ("bf16", nq.NQ_BF16, torch.bfloat16)):
+            h = nq.nq_binlr_create(shp.d_out, shp.d_in, shp.r, data.U_words, data.V_words, data.s_out, data.s_in, nq.NQ_BF16, y_code)
+            for B in ((only_batch,) if only_batch else c.batches):
+                nq.nq_binlr_reserve(h, B)
+                xb = synth.gen_layer_x(5, 0, li, shp, B, "bf16", c.outlier_frac)
+                x = torch.from_numpy(xb.view(np.int16).copy()).view(torch.bfloat16).cuda()
+                y = torch.empty((B, shp.d_out), dtype=y_torch, device="cuda")
+                prewarm(lambda: nq.nq_binlr_forward(h, x, y, B), 0.03)
+                win = []
+                for _ in range(5):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    iters = 10
+                    e0.record()
+                    for _ in range(iters):
+                        nq.nq_binlr_forward(h, x, y, B)
+                    e1.record()
+                    torch.cuda.synchronize()
+                    win.append(e0.elapsed_time(e1) / iters)
+                ms = window_stats(win)["median"]
+                flops = 2.0 * B * shp.r * (shp.d_in + shp.d_out)
+                key = f"{shp.name}_{shp.d_out}x{shp.d_in}_B{B}" + ("" if y_name == "f32" else "_y_" + y_name)
+                res[key] = {"ms": ms, "ms_windows": window_stats(win), "TFLOP/s": flops / ms / 1e9,
+                            "frac_of_f16_mfma_peak": flops / ms / 1e9 / MFMA_F16_PEAK_TFLOPS}
+                del x, y
+            nq.nq_binlr_destroy(h)
     return res
 
 

@@ -16,13 +16,13 @@ iterates, for U (and, with the roles of U and V exchanged and W transposed, for 
 
 Readings taken where the paper is silent:
   * SVID(P) = sign(P) (.) (a b^T): the signs of P times the best rank-one approximation a b^T of |P|
-    ("rank-1 approximation that preserves the sign structure"); sign(0) = +1.  a b^T = sigma u v^T, the leading
+    (Eq. 6 asks for the rank-one approximant whose signs are those of P); sign(0) = +1.  a b^T = sigma u v^T, the leading
     singular triplet of |P|, is found by `power_iters` rounds of power iteration started from the
     all-ones vector (|P| is non-negative, so its leading vectors are too and the start is never orthogonal
     to them); the count is an input, both implementations run exactly that many rounds.
   * order inside one iteration: U-step, Z_U, Lambda_U, then the same for V with the NEW U.
-  * the penalty rho follows a linear schedule from rho_start to rho_end over the K iterations (Appendix C:
-    "a linear ADMM penalty scheduler"); K = 1 uses rho_start.
+  * the penalty rho follows a linear schedule from rho_start to rho_end over the K iterations (Appendix C
+    names the scheduler as linear, over 400 steps, without its end points); K = 1 uses rho_start.
   * initial state: U and V are inputs (random numbers are drawn by the caller), Z = SVID(U), Lambda = 0.
   * magnitude balancing (Step 2-3) with identity preconditioners: P_U = U + Lambda_U, P_V = V + Lambda_V of the
     last iteration, eta = sqrt(||P_V||_F / ||P_U||_F), s1_i = mean_k |eta P_U[i, k]|, s2_j = mean_k |P_V[j, k] / eta|,

@@ -1584,7 +1584,7 @@ int launch_scale_grad(const void* a, int a_dtype, const void* b, int b_dtype, in
 
 // ---------------------------------------------------------------------------------------------
 // plain vector-ALU GEMV on the same sign tiles: one thread per output row, fp32 accumulate,
-// bit -> sign by mask and select (the paper-style "lightweight mask + FMA" kernel).
+// bit -> sign by mask and select, then a multiply-add: the plain vector-ALU form of the two-stage product that Appendix E.2 describes.
 // grid = (row blocks, batch), block = 128
 // ---------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(128)

@@ -5,6 +5,7 @@
 #include "nq_lb_admm.h"
 
 #include <math.h>
+#include <algorithm>
 #include <mutex>
 
 namespace nq {
@@ -30,6 +31,9 @@ struct GemmArgs {
     int lower_only;        // tiles that lie entirely above the diagonal are skipped
     int k_from_max;        // the reduction starts at max(first row, first column) of the tile: both operands
                            // are lower triangular in the sense  op(A)[i][k] = 0 for k < i,  op(B)[k][j] = 0 for k < j
+    int k_parts;           // > 1 (unbatched only): blockIdx.z takes the reduction range [z, z + 1) * k_per_part and
+    int k_per_part;        // writes its partial product to Cp[z]; beta, Cin and diag apply to part 0 only
+    double* Cp[4];
 };
 
 constexpr int kGemmThreads = 256;
@@ -43,7 +47,9 @@ constexpr int kBK = 16;        // reduction depth of one LDS tile = four 16x16x4
 // free of bank conflicts: a source that is contiguous along the reduction (A stored [M][K], B stored [N][K]) is kept
 // as [i][k] with a row pitch of 17 doubles, one that is contiguous along the tile's rows or columns as [k][i] with
 // a pitch of BM + 16.  Two workgroups fit a CU (registers and LDS), so one's staging overlaps the other's products.
-template <int BM, int BN>
+// PF: tiles held in registers ahead of the one being multiplied (1 for the large tiles; 4 for the 64 x 64 tile, whose
+// launches are mostly short reductions that would otherwise wait a full memory latency per 16 columns).
+template <int BM, int BN, int PF>
 __global__ __launch_bounds__(kGemmThreads, 2) void dgemm_kernel(GemmArgs g)
 {
     constexpr int PK = kBK + 1;
@@ -59,15 +65,18 @@ __global__ __launch_bounds__(kGemmThreads, 2) void dgemm_kernel(GemmArgs g)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i0 = blockIdx.y * BM, j0 = blockIdx.x * BN;
     if (g.lower_only && j0 > i0 + BM - 1) return;
-    const double* A = g.A + (size_t)blockIdx.z * g.sA;
-    const double* B = g.B + (size_t)blockIdx.z * g.sB;
-    const int k_begin = g.k_from_max ? ((i0 > j0 ? i0 : j0) / kBK) * kBK : 0;
-    const int n_kt = g.K > k_begin ? (g.K - k_begin + kBK - 1) / kBK : 0;
+    const double* A = g.A + (size_t)(g.k_parts > 1 ? 0 : blockIdx.z) * g.sA;
+    const double* B = g.B + (size_t)(g.k_parts > 1 ? 0 : blockIdx.z) * g.sB;
+    const int part = g.k_parts > 1 ? (int)blockIdx.z : 0;
+    const int zb = g.k_parts > 1 ? 0 : (int)blockIdx.z;
+    const int k_begin = g.k_from_max ? ((i0 > j0 ? i0 : j0) / kBK) * kBK : part * g.k_per_part;
+    const int k_end = g.k_parts > 1 && k_begin + g.k_per_part < g.K ? k_begin + g.k_per_part : g.K;
+    const int n_kt = k_end > k_begin ? (k_end - k_begin + kBK - 1) / kBK : 0;
     const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
     const bool ta = g.trans_a != 0, tb = g.trans_b != 0;
 
-    double ra[LA], rb[LB];
-    auto fetch = [&](int kt) {
+    double ra[PF][LA], rb[PF][LB];
+    auto fetch = [&](int kt, double (&ra)[LA], double (&rb)[LB]) {
         const int k0 = k_begin + kt * kBK;
 #pragma unroll
         for (int p = 0; p < LA; ++p) {
@@ -75,7 +84,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void dgemm_kernel(GemmArgs g)
             const int i = ta ? idx % BM : idx / kBK, k = ta ? idx / BM : idx % kBK;
             const int gi = i0 + i, gk = k0 + k;
             double v = 0.0;
-            if (gi < g.M && gk < g.K) v = ta ? A[(size_t)gk * g.lda + gi] : A[(size_t)gi * g.lda + gk];
+            if (gi < g.M && gk < k_end) v = ta ? A[(size_t)gk * g.lda + gi] : A[(size_t)gi * g.lda + gk];
             ra[p] = v;
         }
 #pragma unroll
@@ -84,11 +93,11 @@ __global__ __launch_bounds__(kGemmThreads, 2) void dgemm_kernel(GemmArgs g)
             const int j = tb ? idx / kBK : idx % BN, k = tb ? idx % kBK : idx / BN;
             const int gj = j0 + j, gk = k0 + k;
             double v = 0.0;
-            if (gj < g.N && gk < g.K) v = tb ? B[(size_t)gj * g.ldb + gk] : B[(size_t)gk * g.ldb + gj];
+            if (gj < g.N && gk < k_end) v = tb ? B[(size_t)gj * g.ldb + gk] : B[(size_t)gk * g.ldb + gj];
             rb[p] = v;
         }
     };
-    auto stash = [&](int buf) {
+    auto stash = [&](int buf, const double (&ra)[LA], const double (&rb)[LB]) {
 #pragma unroll
         for (int p = 0; p < LA; ++p) {
             const int idx = p * kGemmThreads + tid;
@@ -115,35 +124,43 @@ __global__ __launch_bounds__(kGemmThreads, 2) void dgemm_kernel(GemmArgs g)
     const int b_off = tb ? (wn0 + (lane & 15)) * PK + (lane >> 4) : (lane >> 4) * PB + wn0 + (lane & 15);
     const int b_dk = tb ? 4 : 4 * PB, b_dt = tb ? 16 * PK : 16;
 
-    if (n_kt > 0) {
-        fetch(0);
-        stash(0);
-    }
+#pragma unroll
+    for (int t = 0; t < PF; ++t)
+        if (t < n_kt) fetch(t, ra[t], rb[t]);
+    if (n_kt > 0) stash(0, ra[0], rb[0]);
     __syncthreads();
-    for (int kt = 0; kt < n_kt; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < n_kt) fetch(kt + 1);
-        const double* Ab = As + buf * SA + a_off;
-        const double* Bb = Bs + buf * SB + b_off;
+    for (int kt0 = 0; kt0 < n_kt; kt0 += PF) {
 #pragma unroll
-        for (int k4 = 0; k4 < kBK / 4; ++k4) {
-            double a[TM], b[TN];
+        for (int sl = 0; sl < PF; ++sl) {
+            const int kt = kt0 + sl;
+            if (kt < n_kt) {
+                const int buf = kt & 1;
+                // slot sl went to LDS one tile ago: refill it with the tile PF ahead, multiply tile kt, then stage tile kt + 1
+                if (kt + PF < n_kt) fetch(kt + PF, ra[sl], rb[sl]);
+                const double* Ab = As + buf * SA + a_off;
+                const double* Bb = Bs + buf * SB + b_off;
 #pragma unroll
-            for (int t = 0; t < TM; ++t) a[t] = Ab[k4 * a_dk + t * a_dt];
+                for (int k4 = 0; k4 < kBK / 4; ++k4) {
+                    double a[TM], b[TN];
 #pragma unroll
-            for (int t = 0; t < TN; ++t) b[t] = Bb[k4 * b_dk + t * b_dt];
+                    for (int t = 0; t < TM; ++t) a[t] = Ab[k4 * a_dk + t * a_dt];
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
+                    for (int t = 0; t < TN; ++t) b[t] = Bb[k4 * b_dk + t * b_dt];
 #pragma unroll
-                for (int tn = 0; tn < TN; ++tn)
-                    acc[tm][tn] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[tm], b[tn], acc[tm][tn], 0, 0, 0);
+                    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                        for (int tn = 0; tn < TN; ++tn)
+                            acc[tm][tn] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[tm], b[tn], acc[tm][tn], 0, 0, 0);
+                }
+                if (kt + 1 < n_kt) stash(buf ^ 1, ra[(sl + 1) % PF], rb[(sl + 1) % PF]);
+                __syncthreads();
+            }
         }
-        if (kt + 1 < n_kt) stash(buf ^ 1);
-        __syncthreads();
     }
 
-    const double* Cin = g.Cin ? g.Cin + (size_t)blockIdx.z * g.sC : nullptr;
-    double* C = g.C + (size_t)blockIdx.z * g.sC;
+    const bool first = part == 0;
+    const double* Cin = g.Cin && first ? g.Cin + (size_t)zb * g.sC : nullptr;
+    double* C = g.k_parts > 1 ? g.Cp[part] : g.C + (size_t)zb * g.sC;
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
@@ -154,8 +171,8 @@ __global__ __launch_bounds__(kGemmThreads, 2) void dgemm_kernel(GemmArgs g)
                 const int j = j0 + wn0 + tn * 16 + (lane & 15);
                 if (i < g.M && j < g.N) {
                     double val = g.alpha * acc[tm][tn][v];
-                    if (g.beta != 0.0) val = fma(g.beta, Cin[(size_t)i * g.ldcin + j], val);
-                    if (i == j) val += g.diag;
+                    if (g.beta != 0.0 && first) val = fma(g.beta, Cin[(size_t)i * g.ldcin + j], val);
+                    if (i == j && first) val += g.diag;
                     C[(size_t)i * g.ldc + j] = val;
                     if (g.C2) g.C2[(size_t)i * g.ldc + j] = val + g.E[(size_t)i * g.ldc + j];
                 }
@@ -170,18 +187,18 @@ template <int BM, int BN> constexpr size_t gemm_lds_bytes()
     return (size_t)2 * (SA + SB) * sizeof(double);
 }
 
-template <int BM, int BN> static int launch_gemm_tile(const GemmArgs& g, int batch, hipStream_t s)
+template <int BM, int BN, int PF> static int launch_gemm_tile(const GemmArgs& g, int batch, hipStream_t s)
 {
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     constexpr size_t lds = gemm_lds_bytes<BM, BN>();
     std::call_once(once, [] {
         if (lds > 65536)
-            attr_err = hipFuncSetAttribute((const void*)dgemm_kernel<BM, BN>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            attr_err = hipFuncSetAttribute((const void*)dgemm_kernel<BM, BN, PF>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     });
     NQ_HIP(attr_err);
     dim3 grid((g.N + BN - 1) / BN, (g.M + BM - 1) / BM, batch);
-    hipLaunchKernelGGL((dgemm_kernel<BM, BN>), grid, dim3(kGemmThreads), lds, s, g);
+    hipLaunchKernelGGL((dgemm_kernel<BM, BN, PF>), grid, dim3(kGemmThreads), lds, s, g);
     NQ_HIP(hipGetLastError());
     return NQ_OK;
 }
@@ -191,12 +208,17 @@ template <int BM, int BN> static int launch_gemm_tile(const GemmArgs& g, int bat
 static int launch_gemm(const GemmArgs& g, int batch, hipStream_t s)
 {
     if (g.M < 1 || g.N < 1 || batch < 1) return NQ_OK;
-    auto tiles = [&](int bm, int bn) { return (long long)((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn) * batch; };
+    auto tiles = [&](int bm, int bn) {            // workgroups that do work (with lower_only: those not entirely above the diagonal)
+        const int tr = (g.M + bm - 1) / bm, tc = (g.N + bn - 1) / bn;
+        long long n = 0;
+        for (int i = 0; i < tr; ++i) n += g.lower_only ? std::min(tc, (i * bm + bm - 1) / bn + 1) : tc;
+        return n * batch;
+    };
     int choice = opt_or(OPT_DGEMM_TILE, 0);
     if (choice < 1 || choice > 3) choice = tiles(128, 128) >= 512 ? 1 : tiles(128, 64) >= 384 ? 2 : 3;
-    if (choice == 1) return launch_gemm_tile<128, 128>(g, batch, s);
-    if (choice == 2) return launch_gemm_tile<128, 64>(g, batch, s);
-    return launch_gemm_tile<64, 64>(g, batch, s);
+    if (choice == 1) return launch_gemm_tile<128, 128, 1>(g, batch, s);
+    if (choice == 2) return launch_gemm_tile<128, 64, 1>(g, batch, s);
+    return launch_gemm_tile<64, 64, 4>(g, batch, s);
 }
 
 static GemmArgs gemm_args(int ta, int tb, int M, int N, int K, double alpha, const double* A, int lda, const double* B, int ldb,
@@ -208,6 +230,8 @@ static GemmArgs gemm_args(int ta, int tb, int M, int N, int K, double alpha, con
     g.sA = g.sB = g.sC = 0;
     g.trans_a = ta; g.trans_b = tb; g.alpha = alpha; g.beta = beta; g.diag = 0.0;
     g.lower_only = 0; g.k_from_max = 0;
+    g.k_parts = 1; g.k_per_part = 0;
+    for (double*& c : g.Cp) c = nullptr;
     return g;
 }
 
@@ -342,6 +366,15 @@ __global__ __launch_bounds__(256) void potrf_inv64_kernel(double* H, int ldh, do
             Linv[(size_t)(o + i) * ldi + o + c] = (c <= i) ? b[ii][cc] : 0.0;
         }
     if (bad) *status = 1;
+}
+
+// A += B + C on the leading r x r part of [rp][rp] matrices (the partial Gram products of a split reduction).
+__global__ void add_parts_kernel(double* A, const double* B, const double* C, int rp, int r)
+{
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= r) return;
+    const size_t at = (size_t)blockIdx.y * rp + j;
+    A[at] = (A[at] + B[at]) + C[at];
 }
 
 // Identity outside the leading r x r part of a [rp][rp] matrix (the padding that keeps the block algorithms
@@ -694,8 +727,20 @@ static int factor_step(const AdmmWs& ws, const double* W, int w_trans, int ldw, 
     GemmArgs gh = gemm_args(1, 0, r, r, cols, 1.0, O, r, O, r, 0.0, nullptr, 0, ws.H, ws.rp);
     gh.diag = rho + lam;
     gh.lower_only = 1;
-    rc = launch_gemm(gh, 1, s);
+    // a long reduction over few tiles: three parts of the reduction side by side (into H and two buffers that are free
+    // at this point), then added in a fixed order
+    const int parts = cols >= 768 ? 3 : 1;
+    if (parts > 1) {
+        gh.k_parts = parts;
+        gh.k_per_part = ((cols + parts - 1) / parts + kBK - 1) / kBK * kBK;
+        gh.Cp[0] = ws.H; gh.Cp[1] = ws.T; gh.Cp[2] = ws.Hinv;
+    }
+    rc = launch_gemm(gh, parts, s);
     if (rc != NQ_OK) return rc;
+    if (parts > 1) {
+        hipLaunchKernelGGL(add_parts_kernel, dim3((r + 255) / 256, r), dim3(256), 0, s, ws.H, (const double*)ws.T, (const double*)ws.Hinv, ws.rp, r);
+        NQ_HIP(hipGetLastError());
+    }
     rc = factor_and_invert(ws, s);
     if (rc != NQ_OK) return rc;
     if (overlap) NQ_HIP(hipStreamWaitEvent(s, ss.join, 0));

@@ -152,6 +152,41 @@ def test_balancing_matches_the_oracle_bit_for_bit_in_the_signs():
     assert np.array_equal(nq.nq_pack_signs(su.astype(np.int8)).reshape(-1), uw.cpu().numpy().view(np.uint32).reshape(-1))
 
 
+def test_factorised_matrix_runs_as_a_layer():
+    """From a target matrix to a resident layer without leaving the GPU: LB-ADMM, balancing, the packed signs and the
+    scales (rounded to fp16 by the caller) into nq_binlr_create_from_device, one forward; checked against the oracle's
+    reconstruction W^ = Diag(s1) sign(P_U) sign(P_V)^T Diag(s2) applied to x, and W^ against the target."""
+    import torch
+    n, m, r = 256, 192, 96
+    w, u0, v0 = synth.gen_admm_problem(n, m, r, seed=33)
+    outs, ws, nbytes = run_gpu(w, u0, v0, 30, 0.02, 0.3, 1e-3, 6)
+    nw = (r + 31) // 32
+    uw = torch.empty((n, nw), dtype=torch.int32, device="cuda")
+    vw = torch.empty((m, nw), dtype=torch.int32, device="cuda")
+    s1 = torch.empty(n, dtype=torch.float64, device="cuda")
+    s2 = torch.empty(m, dtype=torch.float64, device="cuda")
+    eta = torch.empty(1, dtype=torch.float64, device="cuda")
+    nq.nq_lb_admm_balance(outs["U"], outs["Lambda_U"], n, outs["V"], outs["Lambda_V"], m, r, uw, vw, s1, s2, eta, ws, nbytes)
+    s1h, s2h = s1.to(torch.float16).contiguous(), s2.to(torch.float16).contiguous()
+    h = nq.nq_binlr_create_from_device(n, m, r, uw, vw, s1h, s2h, nq.NQ_F32, nq.NQ_F32, 0)
+    x_np = synth.gen_x(3, m, 3301, "f32")
+    y = torch.empty((3, n), dtype=torch.float32, device="cuda")
+    nq.nq_binlr_forward(h, dev(x_np), y, 3)
+    torch.cuda.synchronize()
+    # the oracle's balancing of the oracle's own run, with the scales rounded to fp16 the same way
+    ref_state = O.lb_admm(w, u0, v0, 30, 0.02, 0.3, 1e-3, 6)
+    su, sv, r1, r2, _ = O.balance(ref_state)
+    w_hat = O.reconstruction(su, sv, r1.astype(np.float16).astype(np.float64), r2.astype(np.float16).astype(np.float64))
+    y_ref = x_np.astype(np.float64) @ w_hat.T
+    assert np.abs(y.cpu().numpy() - y_ref).max() <= 1e-5 * np.abs(y_ref).max()
+    # the factorisation is an approximation of the target at about one bit per weight: it must at least beat the
+    # sign-only rank-r start by a clear margin
+    rel = np.linalg.norm(w - w_hat) / np.linalg.norm(w)
+    print("relative reconstruction error of the binary factorisation", rel, flush=True)
+    assert rel < 0.9
+    nq.nq_binlr_destroy(h)
+
+
 def test_a_failed_factorisation_is_reported():
     w, u0, v0 = synth.gen_admm_problem(96, 80, 70, seed=2)
     with pytest.raises(nq.NQError) as e:

@@ -204,6 +204,11 @@ int nq_binlr_forward_unscaled(nq_handle h, const void* x, void* z, int batch, vo
  * asynchronous on `stream`.  g and w must be 16-byte aligned. */
 int nq_binlr_forward_transposed_unscaled(nq_handle h, const void* g, float* w, int batch, void* stream);
 
+/* The gradient of a loss with respect to the layer's input, dL/dx = W^T g = s_in (.) w with w as above
+ * (the layer is linear in x; Section 3.4 back-propagates through the frozen packed layers).
+ * Same pointers, types, workspace and stream behaviour as nq_binlr_forward_transposed_unscaled. */
+int nq_binlr_backward_input(nq_handle h, const void* g, float* dx, int batch, void* stream);
+
 /* out[j] = sum_{b < batch} a[b][j] * b[b][j], j < n.  a, b: device, [batch, n] row-major of a_dtype /
  * b_dtype (NQ_F32, NQ_F16, NQ_BF16); out: device float [n].  fp64 accumulation, one rounding.
  * Asynchronous on `stream`; allocates nothing. */

@@ -65,6 +65,7 @@ def lib() -> ctypes.CDLL:
         L.nq_plan_forward_timed.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_float)]; L.nq_plan_forward_timed.restype = ci
         L.nq_binlr_forward_unscaled.argtypes = [vp, vp, vp, ci, vp]; L.nq_binlr_forward_unscaled.restype = ci
         L.nq_binlr_forward_transposed_unscaled.argtypes = [vp, vp, vp, ci, vp]; L.nq_binlr_forward_transposed_unscaled.restype = ci
+        L.nq_binlr_backward_input.argtypes = [vp, vp, vp, ci, vp]; L.nq_binlr_backward_input.restype = ci
         L.nq_scale_grad.argtypes = [vp, ci, vp, ci, ci, ctypes.c_int64, vp, vp]; L.nq_scale_grad.restype = ci
         L.nq_binlr_set_mid_scale.argtypes = [vp, vp]; L.nq_binlr_set_mid_scale.restype = ci
         L.nq_probe_hbm_read.argtypes = [ctypes.c_size_t, ci, ci, ctypes.POINTER(ctypes.c_double)]; L.nq_probe_hbm_read.restype = ci
@@ -250,6 +251,10 @@ def nq_binlr_forward_unscaled(h: int, x, z, batch: int, stream=None) -> None:
 
 def nq_binlr_forward_transposed_unscaled(h: int, g, w, batch: int, stream=None) -> None:
     _check(lib().nq_binlr_forward_transposed_unscaled(h, _dev_ptr(g), _dev_ptr(w), batch, _stream(stream)))
+
+
+def nq_binlr_backward_input(h: int, g, dx, batch: int, stream=None) -> None:
+    _check(lib().nq_binlr_backward_input(h, _dev_ptr(g), _dev_ptr(dx), batch, _stream(stream)))
 
 
 def nq_scale_grad(a, a_dtype: int, b, b_dtype: int, batch: int, n: int, out, stream=None) -> None:

@@ -1082,12 +1082,14 @@ extern "C" int nq_binlr_forward_exact(nq_handle h, const void* x, void* y, int b
     return forward_in_passes("nq_binlr_forward_exact", h, x, y, batch, stream, false);
 }
 
-extern "C" int nq_binlr_forward_transposed_unscaled(nq_handle h, const void* g, float* w, int batch, void* stream)
+// w = [s_in (.)] V (s_mid (.) (U^T (s_out (.) g))) from the resident tiles
+static int transposed_forward(const char* who, nq_handle h, const void* g, float* w, int batch, void* stream, bool with_s_in)
 {
-    if (!h) return fail(NQ_E_NULL, "nq_binlr_forward_transposed_unscaled: NULL handle");
-    if (batch < 1) return fail(NQ_E_INVALID_ARG, "nq_binlr_forward_transposed_unscaled: batch must be >= 1");
+    char buf[96];
+    if (!h) { snprintf(buf, sizeof buf, "%s: NULL handle", who); return fail(NQ_E_NULL, buf); }
+    if (batch < 1) { snprintf(buf, sizeof buf, "%s: batch must be >= 1", who); return fail(NQ_E_INVALID_ARG, buf); }
     const size_t gs = dtype_size(h->y_dtype);
-    int rc = check_xy("nq_binlr_forward_transposed_unscaled", g, w, (size_t)batch * h->d_out * gs, (size_t)batch * h->d_in * sizeof(float));
+    int rc = check_xy(who, g, w, (size_t)batch * h->d_out * gs, (size_t)batch * h->d_in * sizeof(float));
     if (rc != NQ_OK) return rc;
     // workspace for passes of up to 8 tokens: the intermediate u = s_mid (.) U^T (s_out (.) g) [8][r padded], then the
     // partial sums of the larger of the two products
@@ -1113,11 +1115,21 @@ extern "C" int nq_binlr_forward_transposed_unscaled(nq_handle h, const void* g, 
                            h->s_mid, u, NQ_F32, (int)r_pad, nb, partial, s);
         if (rc != NQ_OK) return rc;
         // w = V u: the tiles of V^T ([r][d_in]) read along their columns
-        rc = launch_gemv_t(h->vt_tiles, h->r, h->d_in, u, NQ_F32, (int)r_pad, nullptr, nullptr, w + (size_t)b0 * h->d_in, NQ_F32,
-                           (int)h->d_in, nb, partial, s);
+        rc = launch_gemv_t(h->vt_tiles, h->r, h->d_in, u, NQ_F32, (int)r_pad, nullptr, with_s_in ? h->s_in : nullptr,
+                           w + (size_t)b0 * h->d_in, NQ_F32, (int)h->d_in, nb, partial, s);
         if (rc != NQ_OK) return rc;
     }
     return NQ_OK;
+}
+
+extern "C" int nq_binlr_forward_transposed_unscaled(nq_handle h, const void* g, float* w, int batch, void* stream)
+{
+    return transposed_forward("nq_binlr_forward_transposed_unscaled", h, g, w, batch, stream, false);
+}
+
+extern "C" int nq_binlr_backward_input(nq_handle h, const void* g, float* dx, int batch, void* stream)
+{
+    return transposed_forward("nq_binlr_backward_input", h, g, dx, batch, stream, true);
 }
 
 extern "C" int nq_scale_grad(const void* a, int a_dtype, const void* b, int b_dtype, int batch, int64_t n, float* out,

@@ -76,6 +76,11 @@ def test_transposed_product_types_mid_scale_and_checks():
             if mid is not None:
                 u = u * mid.astype(np.float64)
             assert rel_err(w.cpu().numpy(), u @ V.T) <= 1e-6, (y_dtype, mid is not None)
+            # the input gradient is the same product times s_in: W^T g with W the dense matrix of Eq. 1
+            nq.nq_binlr_backward_input(L.h, g, w, batch)
+            torch.cuda.synchronize()
+            dx_ref = (u @ V.T) * d.s_in.astype(np.float64)
+            assert rel_err(w.cpu().numpy(), dx_ref) <= 1e-6, (y_dtype, mid is not None)
         with pytest.raises(nq.NQError):
             nq.nq_binlr_forward_transposed_unscaled(L.h, g, w, 0)
         with pytest.raises(nq.NQError):

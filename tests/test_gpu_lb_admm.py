@@ -73,7 +73,7 @@ def test_dgemm_against_numpy(ta, tb, M, N, K):
     assert np.abs(dn.cpu().numpy() - (a.T if ta else a) @ (b.T if tb else b)).max() <= 4e-16 * (K + 4) * max(1.0, np.abs(ref).max())
 
 
-SHAPES = [(96, 80, 24), (130, 70, 65), (200, 150, 130), (300, 260, 200), (70, 310, 64), (513, 257, 321)]
+SHAPES = [(96, 80, 24), (130, 70, 65), (200, 150, 130), (300, 260, 200), (70, 310, 64), (513, 257, 321), (20, 30, 70), (1100, 40, 33)]
 
 
 @pytest.mark.parametrize("n,m,r", SHAPES)

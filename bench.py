@@ -433,7 +433,8 @@ def time_lb_admm(n=4096, m=4096, r=1024, iters=10, power_iters=8, with_oracle=Fa
     res = {"shape": [n, m, r], "iterations_timed": iters, "power_iters": power_iters, "ms_per_iteration": ms,
            "ms_per_iteration_windows": window_stats(win), "algorithmic_GFLOP_per_iteration": flops / 1e9,
            "TFLOPs_algorithmic": flops / ms / 1e9, "frac_of_fp64_matrix_peak": flops / ms / 1e9 / 78.6, "dgemm": {}}
-    for name, ta, tb, M, N, K in (("W.V", 0, 0, n, r, m), ("W^T.U", 1, 0, m, r, n), ("V^T.V", 1, 0, r, r, m), ("RHS.Hinv", 0, 0, n, r, r)):
+    for name, ta, tb, M, N, K in (("W.V", 0, 0, n, r, m), ("W^T.U", 1, 0, m, r, n), ("V^T.V", 1, 0, r, r, m), ("RHS.Hinv", 0, 0, n, r, r),
+                                  ("4096^3", 0, 0, 4096, 4096, 4096)):
         a = torch.randn((K, M) if ta else (M, K), dtype=torch.float64, device="cuda")
         b = torch.randn((K, N), dtype=torch.float64, device="cuda")
         c = torch.empty((M, N), dtype=torch.float64, device="cuda")

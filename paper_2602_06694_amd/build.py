@@ -43,8 +43,13 @@ def is_stale() -> bool:
     return any(os.path.getmtime(d) > t for d in sources() + HEADERS)
 
 
+# per-source additions: the matrix-core probe loops keep their accumulators in ordinary vector registers (left to itself
+# the compiler moves them between the two register files in every iteration of those loops)
+EXTRA_FLAGS = {"nq_probe.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+
+
 def _compile_one(src: str, obj: str, verbose: bool) -> str:
-    cmd = [HIPCC] + [f for f in FLAGS if f != "-shared"] + ["-c", src, "-o", obj]
+    cmd = [HIPCC] + [f for f in FLAGS if f != "-shared"] + EXTRA_FLAGS.get(os.path.basename(src), []) + ["-c", src, "-o", obj]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)

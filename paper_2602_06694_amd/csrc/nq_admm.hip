@@ -49,7 +49,8 @@ constexpr int kBK = 16;        // reduction depth of one LDS tile = four 16x16x4
 // a pitch of BM + 16.  Two workgroups fit a CU (registers and LDS), so one's staging overlaps the other's products.
 // PF: tiles held in registers ahead of the one being multiplied (1 for the large tiles; 4 for the 64 x 64 tile, whose
 // launches are mostly short reductions that would otherwise wait a full memory latency per 16 columns).
-template <int BM, int BN, int PF>
+// TA, TB: the transpose flags as compile-time constants (LDS offsets become immediates of the LDS instructions).
+template <int BM, int BN, int PF, bool TA, bool TB>
 __global__ __launch_bounds__(kGemmThreads, 2) void dgemm_kernel(GemmArgs g)
 {
     constexpr int PK = kBK + 1;
@@ -73,43 +74,74 @@ __global__ __launch_bounds__(kGemmThreads, 2) void dgemm_kernel(GemmArgs g)
     const int k_end = g.k_parts > 1 && k_begin + g.k_per_part < g.K ? k_begin + g.k_per_part : g.K;
     const int n_kt = k_end > k_begin ? (k_end - k_begin + kBK - 1) / kBK : 0;
     const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
-    const bool ta = g.trans_a != 0, tb = g.trans_b != 0;
+    constexpr bool ta = TA, tb = TB;
+    // a tile that lies inside the matrix needs no masking of rows or columns
+    const bool interior = i0 + BM <= g.M && j0 + BN <= g.N;
 
+    // What a thread fetches does not change from tile to tile except for the reduction offset: the pointers (rows and
+    // columns beyond the matrix are clamped to its last one and their values replaced by zero), the element's depth
+    // inside a tile and its place in LDS are set up once; the loop only advances the pointers.  Tiles are fetched in
+    // ascending order, one call per tile.
     double ra[PF][LA], rb[PF][LB];
+    const double* pa[LA];
+    const double* pb[LB];
+    bool va[LA], vb[LB];
+    int ka[LA], kb[LB], sa[LA], sb[LB];
+    const size_t step_a = ta ? (size_t)kBK * g.lda : kBK, step_b = tb ? kBK : (size_t)kBK * g.ldb;
+#pragma unroll
+    for (int p = 0; p < LA; ++p) {
+        const int idx = p * kGemmThreads + tid;
+        const int i = ta ? idx % BM : idx / kBK, k = ta ? idx / BM : idx % kBK;
+        const int gi = i0 + i < g.M ? i0 + i : g.M - 1;
+        va[p] = i0 + i < g.M;
+        ka[p] = k;
+        sa[p] = ta ? k * PA + i : i * PK + k;
+        pa[p] = ta ? A + (size_t)(k_begin + k) * g.lda + gi : A + (size_t)gi * g.lda + k_begin + k;
+    }
+#pragma unroll
+    for (int p = 0; p < LB; ++p) {
+        const int idx = p * kGemmThreads + tid;
+        const int j = tb ? idx / kBK : idx % BN, k = tb ? idx % kBK : idx / BN;
+        const int gj = j0 + j < g.N ? j0 + j : g.N - 1;
+        vb[p] = j0 + j < g.N;
+        kb[p] = k;
+        sb[p] = tb ? j * PK + k : k * PB + j;
+        pb[p] = tb ? B + (size_t)gj * g.ldb + k_begin + k : B + (size_t)(k_begin + k) * g.ldb + gj;
+    }
     auto fetch = [&](int kt, double (&ra)[LA], double (&rb)[LB]) {
-        const int k0 = k_begin + kt * kBK;
+        const int krem = k_end - (k_begin + kt * kBK);        // depth left, >= 1
+        if (krem >= kBK && interior) {
 #pragma unroll
-        for (int p = 0; p < LA; ++p) {
-            const int idx = p * kGemmThreads + tid;
-            const int i = ta ? idx % BM : idx / kBK, k = ta ? idx / BM : idx % kBK;
-            const int gi = i0 + i, gk = k0 + k;
-            double v = 0.0;
-            if (gi < g.M && gk < k_end) v = ta ? A[(size_t)gk * g.lda + gi] : A[(size_t)gi * g.lda + gk];
-            ra[p] = v;
+            for (int p = 0; p < LA; ++p) ra[p] = *pa[p];
+#pragma unroll
+            for (int p = 0; p < LB; ++p) rb[p] = *pb[p];
+        } else if (krem >= kBK) {                             // a whole tile: every address is inside the matrix
+#pragma unroll
+            for (int p = 0; p < LA; ++p) {
+                const double v = *pa[p];
+                ra[p] = va[p] ? v : 0.0;
+            }
+#pragma unroll
+            for (int p = 0; p < LB; ++p) {
+                const double v = *pb[p];
+                rb[p] = vb[p] ? v : 0.0;
+            }
+        } else {                                              // the ragged last tile
+#pragma unroll
+            for (int p = 0; p < LA; ++p) ra[p] = (va[p] && ka[p] < krem) ? *pa[p] : 0.0;
+#pragma unroll
+            for (int p = 0; p < LB; ++p) rb[p] = (vb[p] && kb[p] < krem) ? *pb[p] : 0.0;
         }
 #pragma unroll
-        for (int p = 0; p < LB; ++p) {
-            const int idx = p * kGemmThreads + tid;
-            const int j = tb ? idx / kBK : idx % BN, k = tb ? idx % kBK : idx / BN;
-            const int gj = j0 + j, gk = k0 + k;
-            double v = 0.0;
-            if (gj < g.N && gk < k_end) v = tb ? B[(size_t)gj * g.ldb + gk] : B[(size_t)gk * g.ldb + gj];
-            rb[p] = v;
-        }
+        for (int p = 0; p < LA; ++p) pa[p] += step_a;
+#pragma unroll
+        for (int p = 0; p < LB; ++p) pb[p] += step_b;
     };
     auto stash = [&](int buf, const double (&ra)[LA], const double (&rb)[LB]) {
 #pragma unroll
-        for (int p = 0; p < LA; ++p) {
-            const int idx = p * kGemmThreads + tid;
-            const int i = ta ? idx % BM : idx / kBK, k = ta ? idx / BM : idx % kBK;
-            As[buf * SA + (ta ? k * PA + i : i * PK + k)] = ra[p];
-        }
+        for (int p = 0; p < LA; ++p) As[buf * SA + sa[p]] = ra[p];
 #pragma unroll
-        for (int p = 0; p < LB; ++p) {
-            const int idx = p * kGemmThreads + tid;
-            const int j = tb ? idx / kBK : idx % BN, k = tb ? idx % kBK : idx / BN;
-            Bs[buf * SB + (tb ? j * PK + k : k * PB + j)] = rb[p];
-        }
+        for (int p = 0; p < LB; ++p) Bs[buf * SB + sb[p]] = rb[p];
     };
 
     v4d acc[TM][TN];
@@ -120,9 +152,9 @@ __global__ __launch_bounds__(kGemmThreads, 2) void dgemm_kernel(GemmArgs g)
 
     // per-lane offsets of the operand reads: element (row l & 15 of a 16-row group, depth l >> 4 of a group of four)
     const int a_off = ta ? (lane >> 4) * PA + wm0 + (lane & 15) : (wm0 + (lane & 15)) * PK + (lane >> 4);
-    const int a_dk = ta ? 4 * PA : 4, a_dt = ta ? 16 : 16 * PK;
+    constexpr int a_dk = ta ? 4 * PA : 4, a_dt = ta ? 16 : 16 * PK;
     const int b_off = tb ? (wn0 + (lane & 15)) * PK + (lane >> 4) : (lane >> 4) * PB + wn0 + (lane & 15);
-    const int b_dk = tb ? 4 : 4 * PB, b_dt = tb ? 16 * PK : 16;
+    constexpr int b_dk = tb ? 4 : 4 * PB, b_dt = tb ? 16 * PK : 16;
 
 #pragma unroll
     for (int t = 0; t < PF; ++t)
@@ -187,20 +219,26 @@ template <int BM, int BN> constexpr size_t gemm_lds_bytes()
     return (size_t)2 * (SA + SB) * sizeof(double);
 }
 
-template <int BM, int BN, int PF> static int launch_gemm_tile(const GemmArgs& g, int batch, hipStream_t s)
+template <int BM, int BN, int PF, bool TA, bool TB> static int launch_gemm_variant(const GemmArgs& g, int batch, hipStream_t s)
 {
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     constexpr size_t lds = gemm_lds_bytes<BM, BN>();
     std::call_once(once, [] {
         if (lds > 65536)
-            attr_err = hipFuncSetAttribute((const void*)dgemm_kernel<BM, BN, PF>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            attr_err = hipFuncSetAttribute((const void*)dgemm_kernel<BM, BN, PF, TA, TB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     });
     NQ_HIP(attr_err);
     dim3 grid((g.N + BN - 1) / BN, (g.M + BM - 1) / BM, batch);
-    hipLaunchKernelGGL((dgemm_kernel<BM, BN, PF>), grid, dim3(kGemmThreads), lds, s, g);
+    hipLaunchKernelGGL((dgemm_kernel<BM, BN, PF, TA, TB>), grid, dim3(kGemmThreads), lds, s, g);
     NQ_HIP(hipGetLastError());
     return NQ_OK;
+}
+
+template <int BM, int BN, int PF> static int launch_gemm_tile(const GemmArgs& g, int batch, hipStream_t s)
+{
+    if (g.trans_a) return g.trans_b ? launch_gemm_variant<BM, BN, PF, true, true>(g, batch, s) : launch_gemm_variant<BM, BN, PF, true, false>(g, batch, s);
+    return g.trans_b ? launch_gemm_variant<BM, BN, PF, false, true>(g, batch, s) : launch_gemm_variant<BM, BN, PF, false, false>(g, batch, s);
 }
 
 // Tile choice: the largest tile that still gives every CU two workgroups; the option "dgemm_tile" (1: 128 x 128,
@@ -366,6 +404,12 @@ __global__ __launch_bounds__(256) void potrf_inv64_kernel(double* H, int ldh, do
             Linv[(size_t)(o + i) * ldi + o + c] = (c <= i) ? b[ii][cc] : 0.0;
         }
     if (bad) *status = 1;
+}
+
+// A += B, both [rows][cols] without padding (the two halves of a product whose reduction was split).
+__global__ void add_half_kernel(double* A, const double* B, size_t count)
+{
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < count; e += (size_t)gridDim.x * blockDim.x) A[e] += B[e];
 }
 
 // A += B + C on the leading r x r part of [rp][rp] matrices (the partial Gram products of a split reduction).
@@ -720,8 +764,22 @@ static int factor_step(const AdmmWs& ws, const double* W, int w_trans, int ldw, 
         NQ_HIP(hipStreamWaitEvent(ss.stream, ss.fork, 0));
     }
     GemmArgs gr = gemm_args(w_trans, 0, rows, r, cols, 1.0, W, ldw, O, r, rho, D, r, ws.RHS, r);
-    int rc = launch_gemm(gr, 1, rs);
+    // The 128 x 128 tile is the efficient one, and it wants two workgroups per CU: where the output has fewer tiles
+    // than that, the reduction is cut in two halves (the second into P's buffer, which is free until the solve) and
+    // the halves are added.
+    const long long t128 = (long long)((rows + 127) / 128) * ((r + 127) / 128);
+    const int w_parts = t128 < 512 && 2 * t128 >= 384 && cols >= 1024 ? 2 : 1;
+    if (w_parts > 1) {
+        gr.k_parts = 2;
+        gr.k_per_part = ((cols + 1) / 2 + kBK - 1) / kBK * kBK;
+        gr.Cp[0] = ws.RHS; gr.Cp[1] = ws.P;
+    }
+    int rc = launch_gemm(gr, w_parts, rs);
     if (rc != NQ_OK) return rc;
+    if (w_parts > 1) {
+        hipLaunchKernelGGL(add_half_kernel, dim3(1024), dim3(256), 0, rs, ws.RHS, (const double*)ws.P, (size_t)rows * r);
+        NQ_HIP(hipGetLastError());
+    }
     if (overlap) NQ_HIP(hipEventRecord(ss.join, ss.stream));
     // H = O^T O + (rho + lambda) I   (lower tiles), its factor and inverse
     GemmArgs gh = gemm_args(1, 0, r, r, cols, 1.0, O, r, O, r, 0.0, nullptr, 0, ws.H, ws.rp);

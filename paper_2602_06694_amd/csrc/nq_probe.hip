@@ -76,19 +76,28 @@ __global__ void __launch_bounds__(256) probe_mfma_kernel(float* __restrict__ sin
 
 typedef double pv4d __attribute__((ext_vector_type(4)));
 
-// The same loop with the binary64 instruction (16 x 16 x 4, 2048 operations each).  Eight accumulators, two rounds
-// per iteration: with sixteen the same loop measured a quarter slower.
+// The same loop with the binary64 instruction (16 x 16 x 4, 2048 operations each): eight accumulators held in named
+// variables (as an array the compiler shuttled them between the two register files every iteration).
 __global__ __launch_bounds__(256) void probe_mfma_f64_kernel(float* sink, int iters)
 {
-    pv4d acc[8];
-    for (int i = 0; i < 8; ++i) acc[i] = pv4d{0, 0, 0, 0};
-    const double a = threadIdx.x * 0.001 + 1.0, b = 1.0 + threadIdx.x * 0.5;
+    pv4d c0 = {0, 0, 0, 0}, c1 = c0, c2 = c0, c3 = c0, c4 = c0, c5 = c0, c6 = c0, c7 = c0;
+    const double a0 = threadIdx.x * 0.001 + 1.0, a1 = a0 + 1.0, b0 = 1.0 + threadIdx.x * 0.5, b1 = b0 + 2.0;
+#pragma unroll 1
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[i & 7] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc[i & 7], 0, 0, 0);
+        for (int rep = 0; rep < 2; ++rep) {
+            c0 = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, c0, 0, 0, 0);
+            c1 = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, c1, 0, 0, 0);
+            c2 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, c2, 0, 0, 0);
+            c3 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, c3, 0, 0, 0);
+            c4 = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, c4, 0, 0, 0);
+            c5 = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, c5, 0, 0, 0);
+            c6 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, c6, 0, 0, 0);
+            c7 = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, c7, 0, 0, 0);
+        }
     }
-    double s = 0.0;
-    for (int i = 0; i < 8; ++i) s += acc[i].x + acc[i].y;
+    const pv4d t = ((c0 + c1) + (c2 + c3)) + ((c4 + c5) + (c6 + c7));
+    const double s = t.x + t.y;
     if (s == 123.456) sink[threadIdx.x] = (float)s;
 }
 

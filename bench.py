@@ -51,7 +51,7 @@ def parse_args():
                     help="headline workload only: skip the extra fields (70B stack decode, config-5 prefill)")
     ap.add_argument("--case", default="",
                     help="run ONE of the side workloads only and print its JSON (for profiling a single case): "
-                         "prefill:<gate|down>:<batch> | pool_b<1..8> | stack3 | stack4 | chain3 | chain4 | admm")
+                         "prefill:<gate|down>:<batch> | pool_b<1..8> | stack3 | stack4 | chain3 | chain4 | transposed | admm")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (reference for rocprofv3 --pmc byte counters)")
     return ap.parse_args()
@@ -404,6 +404,33 @@ def time_single_layer(cfg, reps=200):
     return {"shape": [shp.d_out, shp.d_in, shp.r], "us_per_forward": us, "cache_hot_weight_GBps": wb / us / 1e3}
 
 
+def time_transposed():
+    """The transposed product w = V (U^T (s_out . g)) from the resident tiles against the forward without output scale,
+    on config 2's layer and on config 5's down layer, batch 1 / 8 / 64 (microseconds per call)."""
+    import torch
+    from paper_2602_06694_amd import binding as nq
+    from paper_2602_06694_amd import synth
+    res = {}
+    for cfg, li in ((2, 0), (5, 1)):
+        shp = synth.CONFIGS[cfg].block[li]
+        data = synth.gen_layer(cfg, 0, li, shp)
+        h = nq.nq_binlr_create(shp.d_out, shp.d_in, shp.r, data.U_words, data.V_words, data.s_out, data.s_in, nq.NQ_BF16)
+        for batch in (1, 8, 64):
+            g = torch.randn((batch, shp.d_out), dtype=torch.float32, device="cuda")
+            w = torch.empty((batch, shp.d_in), dtype=torch.float32, device="cuda")
+            x = torch.randn((batch, shp.d_in), dtype=torch.float32, device="cuda").to(torch.bfloat16)
+            z = torch.empty((batch, shp.d_out), dtype=torch.float32, device="cuda")
+            out = {}
+            for name, f in (("transposed_us", lambda: nq.nq_binlr_forward_transposed_unscaled(h, g, w, batch)),
+                            ("forward_unscaled_us", lambda: nq.nq_binlr_forward_unscaled(h, x, z, batch))):
+                prewarm(f, 0.02)
+                win = timed_windows(f, 20, 5)
+                out[name] = window_stats(win)["median"] * 1e3
+            res[f"{shp.name}_{shp.d_out}x{shp.d_in}_r{shp.r}_B{batch}"] = out
+        nq.nq_binlr_destroy(h)
+    return res
+
+
 def time_lb_admm(n=4096, m=4096, r=1024, iters=10, power_iters=8, with_oracle=False):
     """LB-ADMM (Section 3.2 Step 2-2) on one synthetic matrix of config 2's shape: time per iteration, the
     binary64 GEMM behind it on the iteration's three product shapes, and (optionally) one oracle iteration."""
@@ -539,6 +566,8 @@ def main():
             res = time_stack(int(kind[0][-1]), 1)
         elif kind[0] in ("chain3", "chain4"):
             res = time_stack_in_dependency_order(int(kind[0][-1]))
+        elif kind[0] == "transposed":
+            res = time_transposed()
         elif kind[0] == "admm":
             res = time_lb_admm(with_oracle=not args.no_cpu_baseline)
         else:

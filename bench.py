@@ -206,18 +206,25 @@ def cpu_baseline(work, batch, target_s):
                               "sample": f"{n1} layer forwards, {dt1:.1f} s"}}
 
 
-def measured_traffic(workload_name, stage):
+def measured_traffic(workload_name, stage, kernel_name):
     """HBM bytes per launch of the given stage from the committed rocprofv3 --pmc summary of this
     workload (FETCH_SIZE + WRITE_SIZE, each scaled by the copy-kernel calibration), or None if the
-    summary does not cover it."""
+    summary does not cover it: another workload, or a stage that ran a different kernel then (the
+    summary's line for the stage must name the kernel this run launched, e.g. nq::stage_selfq_kernel<4)."""
     path = os.path.join(ROOT, "profiles", "stage_kernels_cfg2_pool_pmc.txt")
+    # "nq::stage_selfq_kernel<W=4>" -> "nq::stage_selfq_kernel<4"
+    key = kernel_name.replace("<W=", "<").rstrip(">").split(" ")[0]
     try:
-        want = None
-        for line in open(path):
+        text = open(path).read()
+        want, same_kernel, value = None, False, None
+        for line in text.splitlines():
             if line.startswith("workload:"):
                 want = line.split(":", 1)[1].strip()
+            if f"[{stage}:" in line and line.startswith(key):
+                same_kernel = True
             if line.startswith(f"traffic_bytes_per_launch_{stage}:") and want == workload_name:
-                return float(line.split(":", 1)[1])
+                value = float(line.split(":", 1)[1])
+        return value if same_kernel else None
     except OSError:
         pass
     return None
@@ -681,7 +688,7 @@ def main():
                              "mfma_i8_dense_TOPs": nq.nq_probe_mfma(nq.NQ_I8),
                              "note": "plain read-only kernel over 4 GiB; register-resident matrix-instruction loop"}
         out["roofline"]["frac_of_attainable"] = achieved / hbm
-    traffic = measured_traffic(name, dom)
+    traffic = measured_traffic(name, dom, out["stage_kernels"][0 if dom == "stage1" else 1])
     if traffic is not None:
         out["roofline"]["traffic"] = traffic
         out["roofline"]["traffic_source"] = ("profiles/stage_kernels_cfg2_pool_pmc.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of "

@@ -452,7 +452,7 @@ def time_lb_admm(n=4096, m=4096, r=1024, iters=10, power_iters=8, with_oracle=Fa
     out = [torch.empty((n if i % 2 == 0 else m, r), dtype=torch.float64, device="cuda") for i in range(6)]
 
     def run(k):
-        nq.nq_lb_admm(dw, n, m, r, du0, dv0, k, 0.02, 0.3, 1e-3, power_iters, out[0], out[1], out[2], out[3], out[4], out[5], ws, nbytes)
+        nq.nq_lb_admm(dw, n, m, r, du0, dv0, k, 1.0, 20.0, 1e-3, power_iters, out[0], out[1], out[2], out[3], out[4], out[5], ws, nbytes)
     run(2)
     torch.cuda.synchronize()
     win = []
@@ -501,7 +501,7 @@ def time_lb_admm(n=4096, m=4096, r=1024, iters=10, power_iters=8, with_oracle=Fa
     if with_oracle:
         from oracle import lb_admm as O
         t0 = time.perf_counter()
-        O.lb_admm(w, u0, v0, 1, 0.02, 0.3, 1e-3, power_iters)
+        O.lb_admm(w, u0, v0, 1, 1.0, 20.0, 1e-3, power_iters)
         res["oracle_s_per_iteration"] = time.perf_counter() - t0
         res["oracle_cores"] = os.cpu_count()
     return res

@@ -222,6 +222,6 @@ def test_config2_shape_two_iterations():
     """The headline layer's shape (4096 x 4096, r = 1024): two full iterations against the oracle."""
     n, m, r = 4096, 4096, 1024
     w, u0, v0 = synth.gen_admm_problem(n, m, r, seed=42)
-    ref = O.lb_admm(w, u0, v0, 2, 0.02, 0.3, 1e-3, 4)
-    outs, _, _ = run_gpu(w, u0, v0, 2, 0.02, 0.3, 1e-3, 4)
+    ref = O.lb_admm(w, u0, v0, 2, 1.0, 20.0, 1e-3, 4)           # a penalty on the scale of this size's Gram diagonal (about 2.6)
+    outs, _, _ = run_gpu(w, u0, v0, 2, 1.0, 20.0, 1e-3, 4)
     print("worst relative error", compare(outs, ref), flush=True)

@@ -51,7 +51,7 @@ def parse_args():
                     help="headline workload only: skip the extra fields (70B stack decode, config-5 prefill)")
     ap.add_argument("--case", default="",
                     help="run ONE of the side workloads only and print its JSON (for profiling a single case): "
-                         "prefill:<gate|down>:<batch> | pool_b<1..8> | stack3 | stack4 | chain3 | chain4 | transposed | admm")
+                         "prefill:<gate|down>:<batch> | pool_b<1..8>[:two_slice] | stack3 | stack4 | chain3 | chain4 | transposed | admm")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (reference for rocprofv3 --pmc byte counters)")
     return ap.parse_args()
@@ -167,7 +167,8 @@ def stage_bytes(shp, batch, y_size=4, self_quantising=(False, False)):
 
 
 SCHEDULE_KERNEL = {1: "nq::stage_stream_kernel", 4: "nq::stage_split_kernel<W=4>", 16: "nq::stage_split_kernel<W=16>",
-                   8: "nq::stage_shared_kernel", 9: "nq::stage_shared_kernel<resident input>", 32: "nq::stage_fused_kernel", 33: "nq::stage_selfq_kernel<W=1>",
+                   8: "nq::stage_shared_kernel", 9: "nq::stage_shared_kernel<resident input>",
+                   10: "nq::stage_shared_kernel<two slices>", 11: "nq::stage_shared_kernel<resident input, two slices>", 32: "nq::stage_fused_kernel", 33: "nq::stage_selfq_kernel<W=1>",
                    34: "nq::stage_selfq_kernel<W=4>"}
 
 
@@ -347,13 +348,16 @@ def time_stack_in_dependency_order(cfg, steps=10):
             "four_plans_per_block_ms_per_step": ms_levels, "single_calls_ms_per_step": ms_single}
 
 
-def time_pool_batch(pool, batch, steps=10, warmup=2):
+def time_pool_batch(pool, batch, steps=10, warmup=2, two_slice=False):
     """Config 2's layer at a decode batch other than the headline's (the metric is quoted at batch 8 too):
-    the same rotating pool of distinct instances, one plan."""
+    the same rotating pool of distinct instances, one plan.  two_slice: with the option that feeds the launches of
+    batch 6..8 16-bit fixed point (NOT the exact path: about 3e-4 of the largest output instead of 1.5e-6)."""
     import numpy as np
     import torch
     from paper_2602_06694_amd import binding as nq
     from paper_2602_06694_amd import synth
+    if two_slice:
+        nq.nq_set_option("two_slice_b8", 1)
     shp = synth.CONFIGS[2].block[0]
     handles, xs, ys = [], [], []
     for i in range(pool):
@@ -364,6 +368,8 @@ def time_pool_batch(pool, batch, steps=10, warmup=2):
         xs.append(torch.from_numpy(x.view(np.int16).copy()).view(torch.bfloat16).cuda())
         ys.append(torch.empty((batch, shp.d_out), dtype=torch.float32, device="cuda"))
     plan = nq.nq_plan_create(handles, xs, ys, batch)
+    if two_slice:
+        nq.nq_set_option("two_slice_b8", None)        # a plan keeps the schedules of its creation
     prewarm(lambda: nq.nq_plan_forward(plan))
     for _ in range(warmup):
         nq.nq_plan_forward(plan)
@@ -568,7 +574,7 @@ def main():
         if kind[0] == "prefill":
             res = time_prefill(args, kind[1], int(kind[2]))
         elif kind[0].startswith("pool_b") and kind[0][6:].isdigit():
-            res = time_pool_batch(args.pool, int(kind[0][6:]))
+            res = time_pool_batch(args.pool, int(kind[0][6:]), two_slice=len(kind) > 1 and kind[1] == "two_slice")
         elif kind[0] in ("stack3", "stack4"):
             res = time_stack(int(kind[0][-1]), 1)
         elif kind[0] in ("chain3", "chain4"):
@@ -702,6 +708,7 @@ def main():
         out["extra"] = {"decode_cfg1_single_layer_b1": time_single_layer(1),
                         "decode_cfg2_single_layer_b1": time_single_layer(2),
                         "decode_cfg2_pool_b8": time_pool_batch(args.pool, 8),
+                        "decode_cfg2_pool_b8_two_slice_option": time_pool_batch(args.pool, 8, two_slice=True),
                         "decode_llama2_7b_stack_b1": time_stack(3, 1),
                         "decode_llama2_70b_stack_b1": time_stack(4, 1),
                         "decode_llama2_7b_in_dependency_order_b1": time_stack_in_dependency_order(3),

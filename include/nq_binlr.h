@@ -321,11 +321,16 @@ int nq_probe_mfma(int dtype, double* tera_ops_per_s);
 
 /* ---- tuning options (process-wide) ----
  * Integers that steer the library's choice of schedules and tilings; every one has a measured
- * default and none changes a result beyond the documented tolerances.  Names: "slab_mb",
+ * default and none changes a result beyond the documented tolerances -- with ONE exception:
+ * "two_slice_b8" (off by default) makes plans created at batch 6..8 feed their shared-input
+ * launches 16-bit instead of 24-bit fixed point (faster; about 3e-4 of the largest output instead
+ * of 2e-6, and about 2e-3 -- outside this build's 1e-3 bar -- for inputs with outlier channels
+ * 20 times the rest).  Names: "slab_mb",
  * "force_w", "split_steps", "selfq4_min_steps", "share_steps", "share_min_batch", "stream_steps",
  * "schedule_full", "fuse_max_mb", "no_fuse", "no_selfq", "no_selfq_c2", "no_resident",
  * "no_quant_wave", "pf_splits1", "pf_splits2", "pf_tg1", "pf_tg2", "pf_ks1", "pf_ks2", "pf_verbose",
- * "exec_spin_limit_us", "no_small_layer", "small_layer_kb", "dgemm_tile", "admm_no_overlap" (see the source for the meaning of each).  value < 0 restores the default.
+ * "exec_spin_limit_us", "no_small_layer", "small_layer_kb", "dgemm_tile", "admm_no_overlap",
+ * "two_slice_b8" (see the source for the meaning of each).  value < 0 restores the default.
  * The environment variable NQ_<NAME IN CAPITALS> gives an option its initial value; it is read once,
  * when the library first consults an option, never on a launch path.  Plans keep the schedules
  * chosen when they were created.  Not thread-safe against forwards running at the same time.

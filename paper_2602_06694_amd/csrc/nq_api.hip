@@ -39,7 +39,7 @@ static const OptEntry kOptTable[OPT_COUNT] = {
     {"no_fuse", true}, {"no_selfq", true}, {"no_selfq_c2", true}, {"no_resident", true}, {"no_quant_wave", true},
     {"pf_splits1", false}, {"pf_splits2", false}, {"pf_tg1", false}, {"pf_tg2", false}, {"pf_ks1", false}, {"pf_ks2", false},
     {"pf_verbose", true}, {"exec_spin_limit_us", false}, {"no_small_layer", true}, {"small_layer_kb", false},
-    {"dgemm_tile", false}, {"admm_no_overlap", true},
+    {"dgemm_tile", false}, {"admm_no_overlap", true}, {"two_slice_b8", true},
 };
 static int g_opt[OPT_COUNT];
 static std::once_flag g_opt_once;
@@ -571,6 +571,7 @@ static QuantDesc make_qx(nq_handle h, const DecodeWorkspace& w, const void* x)
     QuantDesc q;
     q.x = x; q.scale = h->s_in; q.bq = w.bq_x; q.meta = w.meta_x;
     q.N = (int)h->d_in; q.n_chunks = (int)n_steps(h->d_in) * 4; q.x_stride = (int)h->d_in; q.dtype = h->x_dtype;
+    q.mag_exp = 22;
     return q;
 }
 static StageDesc make_s1(nq_handle h, const DecodeWorkspace& w)
@@ -585,6 +586,7 @@ static QuantDesc make_qt(nq_handle h, const DecodeWorkspace& w)
     QuantDesc q;
     q.x = w.t; q.scale = h->s_mid; q.bq = w.bq_t; q.meta = w.meta_t;
     q.N = (int)h->r; q.n_chunks = (int)n_steps(h->r) * 4; q.x_stride = w.t_stride; q.dtype = NQ_F32;
+    q.mag_exp = 22;
     return q;
 }
 static StageDesc make_s2(nq_handle h, const DecodeWorkspace& w, void* y)
@@ -878,10 +880,16 @@ extern "C" int nq_plan_create(nq_plan* out, const nq_handle* hs, const void* con
                 selfq_fits(w, max_steps, min_steps, batch))
                 w = w == 1 ? kSelfqSchedule1 : kSelfqSchedule4;
         }
+        // Option "two_slice_b8": at batch 6..8 the shared-input launches take their input as 16-bit fixed point (the top
+        // byte slice stays zero), which puts the eight tokens into ONE group of 16 MFMA columns instead of two.
+        if (opt_flag(OPT_TWO_SLICE_B8) && batch >= 6 && (w == kSharedSchedule || w == kSharedResidentSchedule)) {
+            w = w == kSharedSchedule ? kSharedSchedule2 : kSharedResidentSchedule2;
+            for (int i = 0; i < n; ++i) (st == 0 ? qx : qt)[i].mag_exp = 14;
+        }
         sched[st] = w;
         for (int i = 0; i < n; ++i) {
             const int nrb = (int)n_rowblocks(sd[i].M);
-            if (w == kSharedSchedule || w == kSharedResidentSchedule) {
+            if (is_shared_schedule(w)) {
                 // the waves of a workgroup share an op's input: items of kShareWaves x (row blocks per wave) row blocks
                 const int group = kShareWaves * shared_per_wave(sd[i].n_steps, batch);
                 for (int rb = 0; rb < nrb; rb += group)

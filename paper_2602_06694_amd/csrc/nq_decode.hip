@@ -160,12 +160,12 @@ quantize_kernel(const QuantDesc* __restrict__ descs, QuantDesc single, int batch
     for (int w = 1; w < kQuantThreads / 64; ++w) m = fmaxf(m, smf[w]);
     bad = sm_bad;
 
-    // step = 2^(e-22) with m = f * 2^e, f in [0.5, 1)  ->  |q| <= 2^22
+    // step = 2^(e-22) with m = f * 2^e, f in [0.5, 1)  ->  |q| <= 2^22  (2^14 for the two-slice mode: the top byte slice is then zero)
     int e = 0;
     float step = 1.0f;
     if (m > 0.f && !bad) {
         (void)frexpf(m, &e);
-        int se = e - 22;
+        int se = e - (d.mag_exp > 0 ? d.mag_exp : 22);
         se = se < -126 ? -126 : se;            // stay a normal float; tiny inputs just lose bits
         step = ldexpf(1.0f, se);
     }
@@ -246,7 +246,7 @@ quantize_wave_kernel(const QuantDesc* __restrict__ descs, QuantDesc single, int 
     float step = 1.0f;
     if (m > 0.f && !bad) {
         (void)frexpf(m, &e);
-        int se = e - 22;
+        int se = e - (d.mag_exp > 0 ? d.mag_exp : 22);
         se = se < -126 ? -126 : se;
         step = ldexpf(1.0f, se);
     }
@@ -423,7 +423,9 @@ constexpr int kStreamMaxRbs = 8;
 // half), fetched by the caller ahead of time and converted only here, so that nothing waits for them early; `own_meta` (or nullptr): the constants of token 0 when the
 // caller has just computed them itself (batch 1).  Both only shorten the chain of dependent memory
 // round trips of a launch that is bound by latency.
-template <int NB, int W, bool DEFER>
+// SL: byte slices (MFMA columns) per token: 3, five tokens per column group; or 2 (16-bit fixed point, the middle and low
+// slices), eight tokens in the one group.
+template <int NB, int W, bool DEFER, int SL = 3>
 __device__ __forceinline__ void stage_epilogue(const v4i (&acc)[NB][8], int* lds, int wave, int lane, int batch,
                                                int rb, const EpilogueArgs& e, float* lds_out,
                                                const uint16_t* pre_scale = nullptr, const QMeta* own_meta = nullptr,
@@ -437,12 +439,14 @@ __device__ __forceinline__ void stage_epilogue(const v4i (&acc)[NB][8], int* lds
     const cptr_meta meta = (cptr_meta)e.meta;
 #pragma unroll
     for (int cg = 0; cg < NB; ++cg) {
-        const int tg = batch - 5 * cg < 5 ? batch - 5 * cg : 5;      // tokens in this column group
+        constexpr int kTokPerGroup = SL == 3 ? 5 : 8;
+        static_assert(SL == 3 || NB == 1, "two slices: one column group");
+        const int tg = batch - kTokPerGroup * cg < kTokPerGroup ? batch - kTokPerGroup * cg : kTokPerGroup;      // tokens in this column group
 #pragma unroll
         for (int hf = 0; hf < 2; ++hf) {
             // accumulator layout of the 16x16 result: lane (g, n), register v <-> D[row 4g+v][col n];
             // the four registers of a plane are four consecutive rows: one 16-byte LDS write per plane
-            if (n < 3 * tg) {
+            if (n < SL * tg) {
                 v4i* dst = (v4i*)(my_lds + n * 64 + 4 * g);
 #pragma unroll
                 for (int p = 0; p < 4; ++p) {
@@ -470,15 +474,20 @@ __device__ __forceinline__ void stage_epilogue(const v4i (&acc)[NB][8], int* lds
                 int h = 0, m = 0, l = 0;
 #pragma unroll
                 for (int w = 0; w < W; ++w) {
-                    const int* q = lds + w * region + (3 * tl) * 64 + row;
-                    h += q[0];
-                    m += q[64];
-                    l += q[128];
+                    const int* q = lds + w * region + (SL * tl) * 64 + row;
+                    if (SL == 3) {
+                        h += q[0];
+                        m += q[64];
+                        l += q[128];
+                    } else {
+                        m += q[0];
+                        l += q[64];
+                    }
                 }
                 // sum_n b_n q_n = (65536 h + 256 m + l) * 2^-p: the raw sums are below 2^30, so
                 // every step is exact in fp64, and the plane's weight rides on the token's step
                 const double raw = fma((double)h, 65536.0, fma((double)m, 256.0, (double)l));
-                const int tok = 5 * cg + tl;
+                const int tok = kTokPerGroup * cg + tl;
                 const double two_step = own_meta ? own_meta->two_step : meta[tok].two_step;
                 double neg_qs = own_meta ? own_meta->neg_qs : meta[tok].neg_qs;
                 if (own_meta && meta_is_partial && W > 1) {
@@ -804,7 +813,9 @@ static_assert(kShareTokStride % 256 == 48, "bank spread");
 // RESIDENT: for reductions of at most 16 steps the whole quantised input (two chunks) is staged once
 // per item and stays in its two buffers; the row blocks then need neither refills nor barriers, and
 // the waves drift apart freely.
-template <int NB, bool RESIDENT>
+// SL = 2: the input is 16-bit fixed point (slices 1 and 2 of the three-slice layout, slice 0 is zero and is not fed to the
+// matrix cores): column n of the one group is slice 1 + n % 2 of token n / 2.
+template <int NB, bool RESIDENT, int SL = 3>
 __global__ void __launch_bounds__(64 * kShareWaves) __attribute__((amdgpu_waves_per_eu(NB == 2 ? 2 : 3, NB == 2 ? 2 : 8)))
 stage_shared_kernel(const StageDesc* __restrict__ descs, const WorkItem* __restrict__ items, int n_items, int per_max,
                     int batch)
@@ -824,9 +835,10 @@ stage_shared_kernel(const StageDesc* __restrict__ descs, const WorkItem* __restr
     uint32_t b_lds[NB];
 #pragma unroll
     for (int cg = 0; cg < NB; ++cg) {
-        int tok = 5 * cg + n / 3;
-        if (n >= 15 || tok >= batch) tok = 0;
-        b_lds[cg] = (uint32_t)(tok * kShareTokStride + (g * kSlices + n % 3) * 16);
+        int tok = SL == 3 ? 5 * cg + n / 3 : n / 2;
+        const int slice = SL == 3 ? n % 3 : 1 + n % 2;
+        if ((SL == 3 && n >= 15) || tok >= batch) tok = 0;
+        b_lds[cg] = (uint32_t)(tok * kShareTokStride + (g * kSlices + slice) * 16);
     }
     // this thread's share of a chunk: 16-byte pieces id = i * 512 + tid < batch * 96 (i < 2);
     // piece id -> token id / 96, offset (id % 96) * 16 inside the token's chunk.  A thread without
@@ -960,8 +972,8 @@ stage_shared_kernel(const StageDesc* __restrict__ descs, const WorkItem* __restr
             }                                                                    \
         }                                                                        \
         if ((u) < my_n)                                                          \
-            stage_epilogue<NB, 1, true>(acc, lds_epi, 0, lane, batch, rb_first + my0 + (u), ea, \
-                                        lds_out + (u) * (kTileRows * batch));    \
+            stage_epilogue<NB, 1, true, SL>(acc, lds_epi, 0, lane, batch, rb_first + my0 + (u), ea, \
+                                            lds_out + (u) * (kTileRows * batch)); \
     } while (0)
 
         if (nst & 4) {
@@ -1369,7 +1381,7 @@ int shared_per_wave(int nst, int batch)
     return std::max(1, std::min(shared_max_per(batch), stream_target_steps(batch) / std::max(1, nst)));
 }
 
-template <int NB, bool RESIDENT>
+template <int NB, bool RESIDENT, int SL = 3>
 static int launch_shared_t(const StageDesc* d_descs, const WorkItem* d_items, int n_items, int batch, hipStream_t s)
 {
     static bool attr_set = false;
@@ -1382,11 +1394,11 @@ static int launch_shared_t(const StageDesc* d_descs, const WorkItem* d_items, in
     }
     if (n_items < 1) return NQ_OK;
     if (!attr_set) {
-        NQ_HIP(hipFuncSetAttribute((const void*)stage_shared_kernel<NB, RESIDENT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        NQ_HIP(hipFuncSetAttribute((const void*)stage_shared_kernel<NB, RESIDENT, SL>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                    160 * 1024));
         attr_set = true;
     }
-    hipLaunchKernelGGL((stage_shared_kernel<NB, RESIDENT>), dim3(n_items), dim3(64 * kShareWaves), lds_bytes, s, d_descs, d_items,
+    hipLaunchKernelGGL((stage_shared_kernel<NB, RESIDENT, SL>), dim3(n_items), dim3(64 * kShareWaves), lds_bytes, s, d_descs, d_items,
                        n_items, per_max, batch);
     NQ_HIP(hipGetLastError());
     return NQ_OK;
@@ -1534,6 +1546,14 @@ int launch_stage(const StageDesc* d_descs, const StageDesc& single, const WorkIt
                  int w, int rbs_per_item, int batch, hipStream_t s)
 {
     const int nb = batch <= 5 ? 1 : 2;
+    if (w == kSharedSchedule2 || w == kSharedResidentSchedule2) {
+        if (batch < 6 || batch > 8) {
+            set_error("launch_stage: the two-slice schedules are for batch 6..8");
+            return NQ_E_INVALID_ARG;
+        }
+        if (w == kSharedSchedule2) return launch_shared_t<1, false, 2>(d_descs, d_items, n_items, batch, s);
+        return launch_shared_t<1, true, 2>(d_descs, d_items, n_items, batch, s);
+    }
     if (w == kSharedSchedule || w == kSharedResidentSchedule) {
         if (nb == 1) {
             if (w == kSharedSchedule) return launch_shared_t<1, false>(d_descs, d_items, n_items, batch, s);

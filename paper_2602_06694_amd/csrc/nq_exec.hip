@@ -230,7 +230,7 @@ __device__ __forceinline__ void exec_body(const ExecTask* __restrict__ tasks, in
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)op.in, 0, op.in_ll ? ((op.N + 1) & ~1) * 8 : 0, 0x00020000);   // (whole 16-byte loads; the arrays are padded)
         QuantDesc qd;
         qd.x = op.in; qd.scale = op.in_scale; qd.bq = nullptr; qd.meta = nullptr;
-        qd.N = op.N; qd.n_chunks = n_chunks; qd.x_stride = op.N; qd.dtype = op.in_dtype;
+        qd.N = op.N; qd.n_chunks = n_chunks; qd.x_stride = op.N; qd.dtype = op.in_dtype; qd.mag_exp = 22;
         const unsigned long long t0 = __builtin_amdgcn_s_memrealtime();
         int gave_up = 0;
         // chunk ch of a paired input -> v; false while a pair of it does not carry this launch's epoch yet

@@ -50,6 +50,7 @@ struct QuantDesc {
     int n_chunks;            // 16-element chunks including padding (= 4 * n_steps)
     int x_stride;            // elements between tokens
     int dtype;               // NQ_F32 / NQ_F16 / NQ_BF16
+    int mag_exp;             // |q| <= 2^mag_exp: 22 (three byte slices; also when 0) or 14 (the top slice stays zero)
 };
 
 struct StageDesc {
@@ -121,6 +122,7 @@ enum Opt {
     OPT_SMALL_LAYER_KB,     // packed size (KiB, both factors) up to which it does (160)
     OPT_DGEMM_TILE,         // tile of the binary64 product: 1 = 128 x 128, 2 = 128 x 64, 3 = 64 x 64 (default: by size)
     OPT_ADMM_NO_OVERLAP,    // flag: LB-ADMM runs the product with W on the caller's stream instead of beside the factorisation
+    OPT_TWO_SLICE_B8,       // flag: plans at batch 6..8 run their shared-input launches on 16-bit fixed point (two byte slices)
     OPT_COUNT
 };
 int opt(Opt o);                                        // -1 when unset
@@ -240,6 +242,9 @@ constexpr int kShareWaves = NQ_SHARE_WAVES;    // waves of a workgroup of the sh
 constexpr int kShareLdsBytes = (kShareWaves <= 4 ? 80 : 160) * 1024 - 1024;
 constexpr int kSharedSchedule = 8;       // stage_schedule()'s value for the workgroup-shared-input kernel
 constexpr int kSharedResidentSchedule = 9;   // the same kernel with the whole input resident in LDS (reductions <= 16 steps)
+// the two with 16-bit fixed point at batch 6..8: a token takes two MFMA columns, eight tokens one group of 16
+constexpr int kSharedSchedule2 = 10, kSharedResidentSchedule2 = 11;
+inline bool is_shared_schedule(int w) { return w >= kSharedSchedule && w <= kSharedResidentSchedule2; }
 int shared_per_wave(int nst, int batch); // row blocks per wave of an item of that kernel
 // w = 1: stream kernel (items are runs of rbs_per_item row blocks); w = 4 / 16: split kernel (one row block
 // per item); w = kSharedSchedule: shared-input kernel (items of up to kShareWaves x shared_per_wave row blocks)

@@ -28,6 +28,7 @@ struct GemmArgs {
     int trans_a;           // 0: A stored [M][K];  1: stored [K][M]
     int trans_b;           // 0: B stored [K][N];  1: stored [N][K]
     double alpha, beta, diag;
+    int tile;              // 0: by size; 1 / 2 / 3: 128 x 128, 128 x 64, 64 x 64 (an in-place product needs a tile as wide as N)
     int lower_only;        // tiles that lie entirely above the diagonal are skipped
     int k_from_max;        // the reduction starts at max(first row, first column) of the tile: both operands
                            // are lower triangular in the sense  op(A)[i][k] = 0 for k < i,  op(B)[k][j] = 0 for k < j
@@ -252,7 +253,7 @@ static int launch_gemm(const GemmArgs& g, int batch, hipStream_t s)
         for (int i = 0; i < tr; ++i) n += g.lower_only ? std::min(tc, (i * bm + bm - 1) / bn + 1) : tc;
         return n * batch;
     };
-    int choice = opt_or(OPT_DGEMM_TILE, 0);
+    int choice = g.tile ? g.tile : opt_or(OPT_DGEMM_TILE, 0);
     if (choice < 1 || choice > 3) choice = tiles(128, 128) >= 512 ? 1 : tiles(128, 64) >= 384 ? 2 : 3;
     if (choice == 1) return launch_gemm_tile<128, 128, 1>(g, batch, s);
     if (choice == 2) return launch_gemm_tile<128, 64, 1>(g, batch, s);
@@ -267,16 +268,16 @@ static GemmArgs gemm_args(int ta, int tb, int M, int N, int K, double alpha, con
     g.M = M; g.N = N; g.K = K; g.lda = lda; g.ldb = ldb; g.ldcin = ldcin; g.ldc = ldc;
     g.sA = g.sB = g.sC = 0;
     g.trans_a = ta; g.trans_b = tb; g.alpha = alpha; g.beta = beta; g.diag = 0.0;
-    g.lower_only = 0; g.k_from_max = 0;
+    g.tile = 0; g.lower_only = 0; g.k_from_max = 0;
     g.k_parts = 1; g.k_per_part = 0;
     for (double*& c : g.Cp) c = nullptr;
     return g;
 }
 
 // ============================================================================================
-//  Cholesky of one 64 x 64 diagonal block and the inverse of its factor (one workgroup)
+//  Cholesky of one diagonal block and the inverse of its factor (one workgroup)
 // ============================================================================================
-constexpr int kNB = 64;
+constexpr int kNB = 64;        // width of a block column of the factorisation (128 measured slower: 110 us per diagonal block against 2 x 34)
 
 __device__ __forceinline__ double readlane_f64(double v, int lane)
 {
@@ -285,9 +286,9 @@ __device__ __forceinline__ double readlane_f64(double v, int lane)
     return __hiloint2double(hi, lo);
 }
 
-// 256 threads as 16 column groups x 16 row groups (the 16 row groups of a column group are 16 adjacent lanes of one
-// wave); a thread keeps the 4 x 4 sub-blocks of the matrix (a) and of the running right-hand side of L X = I (b, starts
-// as the identity) in registers.  The elimination advances by panels of four columns:
+// NB x NB block (64 or 128), (NB/4)^2 threads as NB/4 column groups x NB/4 row groups (the row groups of a column group
+// are adjacent lanes of one wave); a thread keeps the 4 x 4 sub-blocks of the matrix (a) and of the running right-hand
+// side of L X = I (b, starts as the identity) in registers.  The elimination advances by panels of four columns:
 //   * the wave that holds the panel factorises it on its own: pivot and multipliers travel by lane reads, the square
 //     root and its reciprocal come from the hardware's reciprocal-square-root estimate refined by two coupled Newton
 //     steps and a residual correction (ten dependent operations; within an ulp or two); it then publishes the four
@@ -298,12 +299,15 @@ __device__ __forceinline__ double readlane_f64(double v, int lane)
 // LDS buffers alternate between panels, so the next panel's columns never overwrite ones still being read.
 // H (lower part) is overwritten by L; the block of Linv receives L^-1 with an exactly zero upper part.  A pivot that is
 // not > 0 sets *status (the results are then meaningless, every thread still finishes).
-__global__ __launch_bounds__(256) void potrf_inv64_kernel(double* H, int ldh, double* Linv, int ldi, int o, int* status)
+template <int NB>
+__global__ __launch_bounds__((NB / 4) * (NB / 4)) void potrf_inv_kernel(double* H, int ldh, double* Linv, int ldi, int o, int* status)
 {
-    __shared__ double colL[2][4][kNB];
+    constexpr int G = NB / 4;                      // row groups of a column group = lanes they occupy (16 or 32)
+    constexpr int CGW = 64 / G;                    // column groups per wave
+    __shared__ double colL[2][4][NB];
     __shared__ double dinv[2][4];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int tx = threadIdx.x >> 4, ty = threadIdx.x & 15;
+    const int tx = threadIdx.x / G, ty = threadIdx.x % G;
     double a[4][4], b[4][4];
 #pragma unroll
     for (int ii = 0; ii < 4; ++ii)
@@ -313,10 +317,10 @@ __global__ __launch_bounds__(256) void potrf_inv64_kernel(double* H, int ldh, do
             b[ii][cc] = (4 * ty + ii == 4 * tx + cc) ? 1.0 : 0.0;
         }
     bool bad = false;
-    for (int jb = 0; jb < kNB / 4; ++jb) {
+    for (int jb = 0; jb < G; ++jb) {
         const int buf = jb & 1;
-        if (wave == (jb >> 2)) {
-            const int src = 16 * (jb & 3) + jb;            // lane of the thread that holds the panel's diagonal block
+        if (wave == jb / CGW) {
+            const int src = G * (jb % CGW) + jb;           // lane of the thread that holds the panel's diagonal block
             const bool mine = tx == jb;
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj) {
@@ -355,21 +359,6 @@ __global__ __launch_bounds__(256) void potrf_inv64_kernel(double* H, int ldh, do
             }
         }
         __syncthreads();
-        double lr[4][4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-#pragma unroll
-            for (int ii = 0; ii < 4; ++ii) lr[q][ii] = colL[buf][q][4 * ty + ii];
-        if (tx > jb) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-#pragma unroll
-                for (int cc = 0; cc < 4; ++cc) {
-                    const double lc = colL[buf][q][4 * tx + cc];
-#pragma unroll
-                    for (int ii = 0; ii < 4; ++ii) a[ii][cc] = fma(-lr[q][ii], lc, a[ii][cc]);
-                }
-        }
         if (ty == jb) {                                    // rows 4 jb .. 4 jb + 3 of X
 #pragma unroll
             for (int q = 0; q < 4; ++q)
@@ -381,18 +370,28 @@ __global__ __launch_bounds__(256) void potrf_inv64_kernel(double* H, int ldh, do
                     b[q][cc] = acc * dinv[buf][q];
                 }
         }
-        double xs[4][4];
+        // one panel column at a time (few live registers: sixteen waves share the CU's register file at NB = 128)
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
+        for (int q = 0; q < 4; ++q) {
+            double lr[4], xs[4];
 #pragma unroll
-            for (int cc = 0; cc < 4; ++cc) xs[q][cc] = __shfl(b[q][cc], (lane & 48) | jb);
-        if (ty > jb) {
+            for (int ii = 0; ii < 4; ++ii) lr[ii] = colL[buf][q][4 * ty + ii];
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
+            for (int cc = 0; cc < 4; ++cc) xs[cc] = __shfl(b[q][cc], (lane & (64 - G)) | jb);
+            if (tx > jb) {
+#pragma unroll
+                for (int cc = 0; cc < 4; ++cc) {
+                    const double lc = colL[buf][q][4 * tx + cc];
+#pragma unroll
+                    for (int ii = 0; ii < 4; ++ii) a[ii][cc] = fma(-lr[ii], lc, a[ii][cc]);
+                }
+            }
+            if (ty > jb) {
 #pragma unroll
                 for (int ii = 0; ii < 4; ++ii)
 #pragma unroll
-                    for (int cc = 0; cc < 4; ++cc) b[ii][cc] = fma(-lr[q][ii], xs[q][cc], b[ii][cc]);
+                    for (int cc = 0; cc < 4; ++cc) b[ii][cc] = fma(-lr[ii], xs[cc], b[ii][cc]);
+            }
         }
     }
 #pragma unroll
@@ -694,12 +693,13 @@ static int factor_and_invert(const AdmmWs& ws, hipStream_t s)
     const int rp = ws.rp, rr = ws.rr, q = rr / kNB;
     for (int k = 0; k < q; ++k) {
         const int o = k * kNB;
-        hipLaunchKernelGGL(potrf_inv64_kernel, dim3(1), dim3(256), 0, s, ws.H, rp, ws.Linv, rp, o, ws.status);
+        hipLaunchKernelGGL(potrf_inv_kernel<kNB>, dim3(1), dim3((kNB / 4) * (kNB / 4)), 0, s, ws.H, rp, ws.Linv, rp, o, ws.status);
         const int rem = rr - o - kNB;
         if (rem <= 0) break;
         double* A21 = ws.H + (size_t)(o + kNB) * rp + o;
         // panel: L21 = A21 L11^-T, in place (a workgroup reads all of its rows before it writes them)
         GemmArgs p = gemm_args(0, 1, rem, kNB, kNB, 1.0, A21, rp, ws.Linv + (size_t)o * rp + o, rp, 0.0, nullptr, 0, A21, rp);
+        p.tile = kNB > 64 ? 1 : 3;                 // whole rows per workgroup: the product is in place
         int rc = launch_gemm(p, 1, s);
         if (rc != NQ_OK) return rc;
         // trailing update: A22 -= L21 L21^T (lower tiles only)

@@ -50,11 +50,12 @@ int nq_lb_admm_workspace_bytes(int64_t n, int64_t m, int64_t r, size_t* bytes);
  * U, Z_U, Lambda_U: [n, r];  V, Z_V, Lambda_V: [m, r]  (outputs, fully overwritten).
  * workspace: device, at least nq_lb_admm_workspace_bytes(n, m, r) bytes, 256-byte aligned; its
  *            contents before and after the call mean nothing.
- * stream: hipStream_t or NULL.  The call enqueues its kernels on `stream` (and the products with W
- * on a second stream of the library's own, ordered against `stream` by events), then waits for the
- * stream and reports a failed factorisation (NQ_E_INVALID_ARG; the outputs are then unspecified).
- * That second stream and its events exist once per process: calls from different host threads must
- * not overlap in time, and `stream` must not be under graph capture.
+ * stream: hipStream_t or NULL.  The call enqueues the factorisations and solves on `stream` and
+ * the products with W and the SVIDs on a second stream of the library's own, ordered against
+ * `stream` by events; it then waits for both and reports a failed factorisation
+ * (NQ_E_INVALID_ARG; the outputs are then unspecified).  That second stream and its events exist
+ * once per process: calls from different host threads must not overlap in time, and `stream` must
+ * not be under graph capture.
  * NQ_E_NULL / NQ_E_ALIGN / NQ_E_SHAPE / NQ_E_INVALID_ARG (non-finite rho, lambda; power_iters < 0;
  * workspace too small) are returned before anything is launched. */
 int nq_lb_admm(const double* W, int64_t n, int64_t m, int64_t r, const double* U0, const double* V0,

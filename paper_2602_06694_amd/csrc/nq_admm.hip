@@ -34,6 +34,9 @@ struct GemmArgs {
                            // are lower triangular in the sense  op(A)[i][k] = 0 for k < i,  op(B)[k][j] = 0 for k < j
     int k_parts;           // > 1 (unbatched only): blockIdx.z takes the reduction range [z, z + 1) * k_per_part and
     int k_per_part;        // writes its partial product to Cp[z]; beta, Cin and diag apply to part 0 only
+    int lds_pad;           // bytes of LDS requested beyond the kernel's need (fewer workgroups per CU, room for other launches)
+    int prio;              // the waves raise their priority: a launch on the critical path that shares the CUs with a
+                           // long product on another stream then gets the issue slots first
     double* Cp[4];
 };
 
@@ -67,6 +70,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void dgemm_kernel(GemmArgs g)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i0 = blockIdx.y * BM, j0 = blockIdx.x * BN;
     if (g.lower_only && j0 > i0 + BM - 1) return;
+    if (g.prio) __builtin_amdgcn_s_setprio(2);
     const double* A = g.A + (size_t)(g.k_parts > 1 ? 0 : blockIdx.z) * g.sA;
     const double* B = g.B + (size_t)(g.k_parts > 1 ? 0 : blockIdx.z) * g.sB;
     const int part = g.k_parts > 1 ? (int)blockIdx.z : 0;
@@ -220,18 +224,22 @@ template <int BM, int BN> constexpr size_t gemm_lds_bytes()
     return (size_t)2 * (SA + SB) * sizeof(double);
 }
 
+constexpr int kGemmMaxLdsPad = 32768;
+
 template <int BM, int BN, int PF, bool TA, bool TB> static int launch_gemm_variant(const GemmArgs& g, int batch, hipStream_t s)
 {
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     constexpr size_t lds = gemm_lds_bytes<BM, BN>();
     std::call_once(once, [] {
-        if (lds > 65536)
-            attr_err = hipFuncSetAttribute((const void*)dgemm_kernel<BM, BN, PF, TA, TB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (lds + kGemmMaxLdsPad > 65536)
+            attr_err = hipFuncSetAttribute((const void*)dgemm_kernel<BM, BN, PF, TA, TB>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)(lds + kGemmMaxLdsPad));
     });
     NQ_HIP(attr_err);
     dim3 grid((g.N + BN - 1) / BN, (g.M + BM - 1) / BM, batch);
-    hipLaunchKernelGGL((dgemm_kernel<BM, BN, PF, TA, TB>), grid, dim3(kGemmThreads), lds, s, g);
+    const size_t pad = (size_t)(g.lds_pad < 0 ? 0 : g.lds_pad > kGemmMaxLdsPad ? kGemmMaxLdsPad : g.lds_pad);
+    hipLaunchKernelGGL((dgemm_kernel<BM, BN, PF, TA, TB>), grid, dim3(kGemmThreads), lds + pad, s, g);
     NQ_HIP(hipGetLastError());
     return NQ_OK;
 }
@@ -269,7 +277,7 @@ static GemmArgs gemm_args(int ta, int tb, int M, int N, int K, double alpha, con
     g.sA = g.sB = g.sC = 0;
     g.trans_a = ta; g.trans_b = tb; g.alpha = alpha; g.beta = beta; g.diag = 0.0;
     g.tile = 0; g.lower_only = 0; g.k_from_max = 0;
-    g.k_parts = 1; g.k_per_part = 0;
+    g.k_parts = 1; g.k_per_part = 0; g.prio = 0; g.lds_pad = 0;
     for (double*& c : g.Cp) c = nullptr;
     return g;
 }
@@ -300,8 +308,9 @@ __device__ __forceinline__ double readlane_f64(double v, int lane)
 // H (lower part) is overwritten by L; the block of Linv receives L^-1 with an exactly zero upper part.  A pivot that is
 // not > 0 sets *status (the results are then meaningless, every thread still finishes).
 template <int NB>
-__global__ __launch_bounds__((NB / 4) * (NB / 4)) void potrf_inv_kernel(double* H, int ldh, double* Linv, int ldi, int o, int* status)
+__global__ __launch_bounds__((NB / 4) * (NB / 4)) void potrf_inv_kernel(double* H, int ldh, double* Linv, int ldi, int o, int* status, int prio)
 {
+    if (prio) __builtin_amdgcn_s_setprio(3);
     constexpr int G = NB / 4;                      // row groups of a column group = lanes they occupy (16 or 32)
     constexpr int CGW = 64 / G;                    // column groups per wave
     __shared__ double colL[2][4][NB];
@@ -688,24 +697,26 @@ static int svid(const AdmmWs& ws, const double* P, int rows, int r, int iters, i
 }
 
 // H (leading rr x rr of [rp][rp], lower part) -> L in place, Linv = L^-1, Hinv = L^-T L^-1.
-static int factor_and_invert(const AdmmWs& ws, hipStream_t s)
+static int factor_and_invert(const AdmmWs& ws, hipStream_t s, int prio)
 {
     const int rp = ws.rp, rr = ws.rr, q = rr / kNB;
     for (int k = 0; k < q; ++k) {
         const int o = k * kNB;
-        hipLaunchKernelGGL(potrf_inv_kernel<kNB>, dim3(1), dim3((kNB / 4) * (kNB / 4)), 0, s, ws.H, rp, ws.Linv, rp, o, ws.status);
+        hipLaunchKernelGGL(potrf_inv_kernel<kNB>, dim3(1), dim3((kNB / 4) * (kNB / 4)), 0, s, ws.H, rp, ws.Linv, rp, o, ws.status, prio);
         const int rem = rr - o - kNB;
         if (rem <= 0) break;
         double* A21 = ws.H + (size_t)(o + kNB) * rp + o;
         // panel: L21 = A21 L11^-T, in place (a workgroup reads all of its rows before it writes them)
         GemmArgs p = gemm_args(0, 1, rem, kNB, kNB, 1.0, A21, rp, ws.Linv + (size_t)o * rp + o, rp, 0.0, nullptr, 0, A21, rp);
         p.tile = kNB > 64 ? 1 : 3;                 // whole rows per workgroup: the product is in place
+        p.prio = prio;
         int rc = launch_gemm(p, 1, s);
         if (rc != NQ_OK) return rc;
         // trailing update: A22 -= L21 L21^T (lower tiles only)
         double* A22 = ws.H + (size_t)(o + kNB) * rp + o + kNB;
         GemmArgs u = gemm_args(0, 1, rem, rem, kNB, -1.0, A21, rp, A21, rp, 1.0, A22, rp, A22, rp);
         u.lower_only = 1;
+        u.prio = prio;
         rc = launch_gemm(u, 1, s);
         if (rc != NQ_OK) return rc;
     }
@@ -716,24 +727,29 @@ static int factor_and_invert(const AdmmWs& ws, hipStream_t s)
         const long long stride = (long long)2 * b * rp + 2 * b;
         GemmArgs t = gemm_args(0, 0, b, b, b, 1.0, ws.H + (size_t)b * rp, rp, ws.Linv, rp, 0.0, nullptr, 0, ws.T + (size_t)b * rp, rp);
         t.sA = t.sB = t.sC = stride;
+        t.prio = prio;
         int rc = launch_gemm(t, pairs, s);
         if (rc != NQ_OK) return rc;
         GemmArgs x = gemm_args(0, 0, b, b, b, -1.0, ws.Linv + (size_t)b * rp + b, rp, ws.T + (size_t)b * rp, rp, 0.0, nullptr, 0,
                                ws.Linv + (size_t)b * rp, rp);
         x.sA = x.sB = x.sC = stride;
+        x.prio = prio;
         rc = launch_gemm(x, pairs, s);
         if (rc != NQ_OK) return rc;
     }
     GemmArgs h = gemm_args(1, 0, rr, rr, rr, 1.0, ws.Linv, rp, ws.Linv, rp, 0.0, nullptr, 0, ws.Hinv, rp);
     h.k_from_max = 1;
+    h.prio = prio;
     return launch_gemm(h, 1, s);
 }
 
-// A second stream and two events, created once: the product with W does not depend on the factorisation, so it runs
-// beside it (the factorisation is a chain of small launches that leaves most of the chip idle).
+// A second stream and three events, created once.  Two things run beside the factorisation, which is a chain of small
+// launches that leaves most of the chip idle: the product with W (it does not depend on the factorisation), and the
+// SVID of the factor just updated (nothing needs its result before that factor's NEXT update, a whole factor step later;
+// the other factor's update only reads the new factor itself).
 struct SideStream {
     hipStream_t stream = nullptr;
-    hipEvent_t fork = nullptr, join = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr, updated = nullptr;
     hipError_t err = hipSuccess;
 };
 
@@ -745,46 +761,44 @@ static SideStream& side_stream()
         ss.err = hipStreamCreateWithFlags(&ss.stream, hipStreamNonBlocking);
         if (ss.err == hipSuccess) ss.err = hipEventCreateWithFlags(&ss.fork, hipEventDisableTiming);
         if (ss.err == hipSuccess) ss.err = hipEventCreateWithFlags(&ss.join, hipEventDisableTiming);
+        if (ss.err == hipSuccess) ss.err = hipEventCreateWithFlags(&ss.updated, hipEventDisableTiming);
     });
     return ss;
 }
 
 // One factor update of Eq. 5 and Eq. 6 for X [rows][r] given the other factor O [cols][r]:
 //   op(W) is [rows][cols] (w_trans = 1: W is stored [cols][rows]).
+// An SVID whose launches are still to be issued (to the side stream): the factor step that follows issues them behind its
+// own first launch, so that the host does not hold that launch -- the head of the critical path -- back by twenty others.
+struct PendingSvid {
+    bool valid = false;
+    int rows = 0;
+    double *Z = nullptr, *Lambda = nullptr, *D = nullptr;
+};
+
+static int issue_pending_svid(const AdmmWs& ws, PendingSvid& pend, int r, int power_iters)
+{
+    if (!pend.valid) return NQ_OK;
+    pend.valid = false;
+    SideStream& ss = side_stream();
+    NQ_HIP(hipStreamWaitEvent(ss.stream, ss.updated, 0));
+    return svid(ws, ws.P, pend.rows, r, power_iters, 0, pend.Z, pend.Lambda, pend.D, ss.stream);
+}
+
 static int factor_step(const AdmmWs& ws, const double* W, int w_trans, int ldw, int rows, int cols, int r, const double* O, double rho, double lam,
-                       int power_iters, double* X, double* Z, double* Lambda, double* D, hipStream_t s)
+                       int power_iters, double* X, double* Z, double* Lambda, double* D, hipStream_t s, PendingSvid& pend)
 {
     const bool overlap = !opt_flag(OPT_ADMM_NO_OVERLAP);
+    // the launches of the caller's stream are the critical path: where another stream shares the chip, their waves
+    // ask for the issue slots first
+    const int prio = overlap && !opt_flag(OPT_ADMM_NO_PRIO);
     SideStream& ss = side_stream();
     NQ_HIP(ss.err);
-    // RHS = op(W) O + rho (Z - Lambda), on the side stream
-    hipStream_t rs = overlap ? ss.stream : s;
-    if (overlap) {
-        NQ_HIP(hipEventRecord(ss.fork, s));
-        NQ_HIP(hipStreamWaitEvent(ss.stream, ss.fork, 0));
-    }
-    GemmArgs gr = gemm_args(w_trans, 0, rows, r, cols, 1.0, W, ldw, O, r, rho, D, r, ws.RHS, r);
-    // The 128 x 128 tile is the efficient one, and it wants two workgroups per CU: where the output has fewer tiles
-    // than that, the reduction is cut in two halves (the second into P's buffer, which is free until the solve) and
-    // the halves are added.
-    const long long t128 = (long long)((rows + 127) / 128) * ((r + 127) / 128);
-    const int w_parts = t128 < 512 && 2 * t128 >= 384 && cols >= 1024 ? 2 : 1;
-    if (w_parts > 1) {
-        gr.k_parts = 2;
-        gr.k_per_part = ((cols + 1) / 2 + kBK - 1) / kBK * kBK;
-        gr.Cp[0] = ws.RHS; gr.Cp[1] = ws.P;
-    }
-    int rc = launch_gemm(gr, w_parts, rs);
-    if (rc != NQ_OK) return rc;
-    if (w_parts > 1) {
-        hipLaunchKernelGGL(add_half_kernel, dim3(1024), dim3(256), 0, rs, ws.RHS, (const double*)ws.P, (size_t)rows * r);
-        NQ_HIP(hipGetLastError());
-    }
-    if (overlap) NQ_HIP(hipEventRecord(ss.join, ss.stream));
     // H = O^T O + (rho + lambda) I   (lower tiles), its factor and inverse
     GemmArgs gh = gemm_args(1, 0, r, r, cols, 1.0, O, r, O, r, 0.0, nullptr, 0, ws.H, ws.rp);
     gh.diag = rho + lam;
     gh.lower_only = 1;
+    gh.prio = prio;
     // a long reduction over few tiles: three parts of the reduction side by side (into H and two buffers that are free
     // at this point), then added in a fixed order
     const int parts = cols >= 768 ? 3 : 1;
@@ -793,22 +807,70 @@ static int factor_step(const AdmmWs& ws, const double* W, int w_trans, int ldw, 
         gh.k_per_part = ((cols + parts - 1) / parts + kBK - 1) / kBK * kBK;
         gh.Cp[0] = ws.H; gh.Cp[1] = ws.T; gh.Cp[2] = ws.Hinv;
     }
-    rc = launch_gemm(gh, parts, s);
+    int rc = launch_gemm(gh, parts, s);
     if (rc != NQ_OK) return rc;
     if (parts > 1) {
         hipLaunchKernelGGL(add_parts_kernel, dim3((r + 255) / 256, r), dim3(256), 0, s, ws.H, (const double*)ws.T, (const double*)ws.Hinv, ws.rp, r);
         NQ_HIP(hipGetLastError());
     }
-    rc = factor_and_invert(ws, s);
+    rc = issue_pending_svid(ws, pend, r, power_iters);        // the other factor's SVID, to the side stream
+    if (rc != NQ_OK) return rc;
+    // RHS = op(W) O + rho (Z - Lambda), on the side stream (behind the SVID that produced Z and Lambda).  It is let go
+    // once the Gram matrix is done: both fill the chip, so side by side neither gains, and the product would only keep
+    // the Gram matrix -- the head of the critical path -- waiting for workgroup slots; what the product can hide behind
+    // is the factorisation that follows.
+    hipStream_t rs = overlap ? ss.stream : s;
+    if (overlap) {
+        NQ_HIP(hipEventRecord(ss.fork, s));
+        NQ_HIP(hipStreamWaitEvent(ss.stream, ss.fork, 0));
+    }
+    GemmArgs gr = gemm_args(w_trans, 0, rows, r, cols, 1.0, W, ldw, O, r, rho, D, r, ws.RHS, r);
+    // On its own (everything on one stream) the product wants the 128 x 128 tile with two workgroups per CU: where the
+    // output has fewer tiles than that, the reduction is cut in two halves (the second into P's buffer, which is free
+    // until the solve) and the halves are added.
+    // Beside the factorisation it is the other way round: the product has the whole factorisation to finish in, and what
+    // matters is that the factorisation's small launches find room at once -- with two 128 x 128 workgroups on a CU
+    // (2 x 72 KiB of LDS) a 64 x 64 workgroup (40 KiB) has to wait until one of them has finished its whole reduction
+    // (measured: a panel update of 15 workgroups took 470-570 us instead of 8).  So the product then runs with at
+    // most ONE workgroup per CU (its LDS request is padded past half a CU's) and without the cut.
+    const long long t128 = (long long)((rows + 127) / 128) * ((r + 127) / 128);
+    const bool roomy = overlap && opt_or(OPT_ADMM_PRODUCT_MODE, 0) != 1 && t128 >= 64;
+    const int w_parts = !roomy && t128 < 512 && 2 * t128 >= 384 && cols >= 1024 ? 2 : 1;
+    if (w_parts > 1) {
+        gr.k_parts = 2;
+        gr.k_per_part = ((cols + 1) / 2 + kBK - 1) / kBK * kBK;
+        gr.Cp[0] = ws.RHS; gr.Cp[1] = ws.P;
+    }
+    if (roomy) {
+        gr.tile = 1;
+        gr.lds_pad = 16384;
+    }
+    rc = launch_gemm(gr, w_parts, rs);
+    if (rc != NQ_OK) return rc;
+    if (w_parts > 1) {
+        hipLaunchKernelGGL(add_half_kernel, dim3(1024), dim3(256), 0, rs, ws.RHS, (const double*)ws.P, (size_t)rows * r);
+        NQ_HIP(hipGetLastError());
+    }
+    if (overlap) NQ_HIP(hipEventRecord(ss.join, ss.stream));
+    rc = factor_and_invert(ws, s, prio);
     if (rc != NQ_OK) return rc;
     if (overlap) NQ_HIP(hipStreamWaitEvent(s, ss.join, 0));
     // X = RHS H^-1,  P = X + Lambda
     GemmArgs gx = gemm_args(0, 0, rows, r, r, 1.0, ws.RHS, r, ws.Hinv, ws.rp, 0.0, nullptr, 0, X, r);
     gx.E = Lambda;
     gx.C2 = ws.P;
+    gx.prio = prio;
     rc = launch_gemm(gx, 1, s);
     if (rc != NQ_OK) return rc;
-    return svid(ws, ws.P, rows, r, power_iters, 0, Z, Lambda, D, s);
+    if (!overlap || opt_flag(OPT_ADMM_INLINE_SVID)) return svid(ws, ws.P, rows, r, power_iters, 0, Z, Lambda, D, s);
+    // The SVID goes to the side stream.  What keeps the buffers apart: the side stream runs SVID (reads P; writes Z,
+    // Lambda, D), then the next factor step's product (second half into P, result into RHS), in that order; the
+    // caller's stream writes P and reads RHS and Lambda only after it has waited for that product.
+    // (Its launches are issued by the next factor step, or by the caller after the last one.)
+    NQ_HIP(hipEventRecord(ss.updated, s));
+    pend.valid = true;
+    pend.rows = rows; pend.Z = Z; pend.Lambda = Lambda; pend.D = D;
+    return NQ_OK;
 }
 
 static int fail(int code, const char* msg)
@@ -869,12 +931,20 @@ extern "C" int nq_lb_admm(const double* W, int64_t n, int64_t m, int64_t r, cons
     if (rc != NQ_OK) return rc;
     rc = svid(ws, V, M, R, power_iters, 1, Z_V, Lambda_V, ws.DV, s);
     if (rc != NQ_OK) return rc;
+    PendingSvid pend;
     for (int k = 0; k < n_iters; ++k) {
         const double rho = n_iters <= 1 ? rho_start : rho_start + (rho_end - rho_start) * (double)k / (double)(n_iters - 1);
-        rc = factor_step(ws, W, 0, M, N, M, R, V, rho, lambda, power_iters, U, Z_U, Lambda_U, ws.DU, s);
+        rc = factor_step(ws, W, 0, M, N, M, R, V, rho, lambda, power_iters, U, Z_U, Lambda_U, ws.DU, s, pend);
         if (rc != NQ_OK) return rc;
-        rc = factor_step(ws, W, 1, M, M, N, R, U, rho, lambda, power_iters, V, Z_V, Lambda_V, ws.DV, s);
+        rc = factor_step(ws, W, 1, M, M, N, R, U, rho, lambda, power_iters, V, Z_V, Lambda_V, ws.DV, s, pend);
         if (rc != NQ_OK) return rc;
+    }
+    rc = issue_pending_svid(ws, pend, R, power_iters);
+    if (rc != NQ_OK) return rc;
+    if (n_iters > 0 && !opt_flag(OPT_ADMM_NO_OVERLAP)) {      // the last SVID may still be running on the side stream
+        SideStream& ss = side_stream();
+        NQ_HIP(hipEventRecord(ss.join, ss.stream));
+        NQ_HIP(hipStreamWaitEvent(s, ss.join, 0));
     }
     int status = 0;
     NQ_HIP(hipMemcpyAsync(&status, ws.status, sizeof(int), hipMemcpyDeviceToHost, s));

@@ -123,6 +123,9 @@ enum Opt {
     OPT_DGEMM_TILE,         // tile of the binary64 product: 1 = 128 x 128, 2 = 128 x 64, 3 = 64 x 64 (default: by size)
     OPT_ADMM_NO_OVERLAP,    // flag: LB-ADMM runs the product with W on the caller's stream instead of beside the factorisation
     OPT_TWO_SLICE_B8,       // flag: plans at batch 6..8 run their shared-input launches on 16-bit fixed point (two byte slices)
+    OPT_ADMM_NO_PRIO,       // flag: the kernels of LB-ADMM's factorisation chain keep the default wave priority
+    OPT_ADMM_PRODUCT_MODE,  // 1: LB-ADMM's product with W keeps two workgroups per CU also beside the factorisation (default 0: one)
+    OPT_ADMM_INLINE_SVID,   // flag: LB-ADMM runs the SVID of a factor on the caller's stream, before the next factor's update starts
     OPT_COUNT
 };
 int opt(Opt o);                                        // -1 when unset

@@ -84,6 +84,21 @@ def test_iterations_match_the_oracle(n, m, r):
     print("worst relative error", compare(outs, ref), flush=True)
 
 
+@pytest.mark.parametrize("option", ["admm_no_overlap", "admm_inline_svid", "admm_no_prio", "admm_product_mode"])
+def test_every_schedule_of_the_two_streams_gives_the_oracles_result(option, nqopt):
+    """Where the SVID and the product with W run (beside the factorisation or on the caller's stream), with how many
+    workgroups per CU, and at which wave priority, changes the order of events on the device, not the result: each
+    switch on its own, on a shape large enough for the one-workgroup-per-CU product (64 tiles of 128 x 128 or more)."""
+    n, m, r = 1100, 1030, 900
+    w, u0, v0 = synth.gen_admm_problem(n, m, r, seed=11)
+    ref = O.lb_admm(w, u0, v0, 3, 0.5, 2.0, 1e-3, 4)
+    outs, _, _ = run_gpu(w, u0, v0, 3, 0.5, 2.0, 1e-3, 4)
+    print("default schedule: worst relative error", compare(outs, ref), flush=True)
+    nqopt.set(option, 1)
+    outs, _, _ = run_gpu(w, u0, v0, 3, 0.5, 2.0, 1e-3, 4)
+    print(option, ": worst relative error", compare(outs, ref), flush=True)
+
+
 def test_many_iterations_small():
     w, u0, v0 = synth.gen_admm_problem(96, 80, 40, seed=5)
     ref = O.lb_admm(w, u0, v0, 60, 0.01, 0.5, 1e-3, 8)

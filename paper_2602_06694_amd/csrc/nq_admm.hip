@@ -285,7 +285,7 @@ static GemmArgs gemm_args(int ta, int tb, int M, int N, int K, double alpha, con
 // ============================================================================================
 //  Cholesky of one diagonal block and the inverse of its factor (one workgroup)
 // ============================================================================================
-constexpr int kNB = 64;        // width of a block column of the factorisation (128 measured slower: 110 us per diagonal block against 2 x 34)
+constexpr int kNB = 64;        // width of a block column of the factorisation (an earlier 128-wide diagonal-block kernel measured slower than two of 64)
 
 __device__ __forceinline__ double readlane_f64(double v, int lane)
 {
@@ -294,29 +294,38 @@ __device__ __forceinline__ double readlane_f64(double v, int lane)
     return __hiloint2double(hi, lo);
 }
 
-// NB x NB block (64 or 128), (NB/4)^2 threads as NB/4 column groups x NB/4 row groups (the row groups of a column group
-// are adjacent lanes of one wave); a thread keeps the 4 x 4 sub-blocks of the matrix (a) and of the running right-hand
-// side of L X = I (b, starts as the identity) in registers.  The elimination advances by panels of four columns:
-//   * the wave that holds the panel factorises it on its own: pivot and multipliers travel by lane reads, the square
-//     root and its reciprocal come from the hardware's reciprocal-square-root estimate refined by two coupled Newton
-//     steps and a residual correction (ten dependent operations; within an ulp or two); it then publishes the four
-//     scaled columns (zero at and above their pivot) and the reciprocal pivots in LDS;
-//   * after ONE barrier everybody applies the rank-4 update to its blocks right of the panel, the threads that hold
-//     rows of the panel finish those rows of X with the panel's 4 x 4 triangle, hand them to their column group by
-//     lane shuffles, and the rows below get their rank-4 update of b.
-// LDS buffers alternate between panels, so the next panel's columns never overwrite ones still being read.
+// NB x NB block (NB = 64; every panel has an LDS buffer of its own, which a 128-wide block would not fit), (NB/4)^2 threads; a thread keeps one 4 x 4 sub-block of the matrix (a) and of the running
+// right-hand side of L X = I (b, starts as the identity) in registers: row group ty = lane mod NB/4, column group tx.
+// The column groups are dealt to the waves in turn (tx = wave + waves x (lane / (NB/4))), so that consecutive panels of
+// four columns belong to different waves, and the elimination is a pipeline over panels without workgroup barriers:
+//   * the wave that owns panel j + 1 applies panel j to that panel's columns only, factorises it on its own -- pivot and
+//     multipliers travel by lane reads, the square root and its reciprocal come from the hardware's reciprocal-square-root
+//     estimate refined by two coupled Newton steps and a residual correction (ten dependent operations; within an ulp
+//     or two) -- publishes the four scaled columns (zero at and above their pivot) and the reciprocal pivots in the
+//     panel's own LDS buffer, and raises the count of published panels;
+//   * every wave, for each panel in order: waits until it is published, lets the threads that hold rows of the panel
+//     finish those rows of X with the panel's 4 x 4 triangle and hand them to their column group by lane shuffles, and
+//     applies the rank-4 update to its blocks right of the panel (a) and below it (b).
+// So the chain of dependent operations per panel is "four columns of one wave" (about 2300 cycles), not that plus a whole
+// rank-4 update and a barrier (4700): the other waves' updates run beside the next panel's factorisation.
+// A wave waits only for panels with a smaller number than any it still has to publish, so the waits end; they also give
+// up after a fixed number of polls (status is then set and the results are meaningless, every thread still finishes).
 // H (lower part) is overwritten by L; the block of Linv receives L^-1 with an exactly zero upper part.  A pivot that is
 // not > 0 sets *status (the results are then meaningless, every thread still finishes).
 template <int NB>
 __global__ __launch_bounds__((NB / 4) * (NB / 4)) void potrf_inv_kernel(double* H, int ldh, double* Linv, int ldi, int o, int* status, int prio)
 {
     if (prio) __builtin_amdgcn_s_setprio(3);
-    constexpr int G = NB / 4;                      // row groups of a column group = lanes they occupy (16 or 32)
+    static_assert(NB == 64, "one LDS buffer per panel: 32 KiB at NB = 64");
+    constexpr int G = NB / 4;                      // row groups of a column group = lanes they occupy; also the number of panels
     constexpr int CGW = 64 / G;                    // column groups per wave
-    __shared__ double colL[2][4][NB];
-    __shared__ double dinv[2][4];
+    constexpr int NW = G / CGW;                    // waves
+    __shared__ double colL[G][4][NB];
+    __shared__ double dinv[G][4];
+    __shared__ int published;                      // panels whose columns are in LDS
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int tx = threadIdx.x / G, ty = threadIdx.x % G;
+    const int local = lane / G;                    // which of the wave's column groups
+    const int tx = wave + NW * local, ty = lane % G;
     double a[4][4], b[4][4];
 #pragma unroll
     for (int ii = 0; ii < 4; ++ii)
@@ -325,49 +334,79 @@ __global__ __launch_bounds__((NB / 4) * (NB / 4)) void potrf_inv_kernel(double* 
             a[ii][cc] = H[(size_t)(o + 4 * ty + ii) * ldh + o + 4 * tx + cc];
             b[ii][cc] = (4 * ty + ii == 4 * tx + cc) ? 1.0 : 0.0;
         }
+    if (threadIdx.x == 0) published = 0;
+    __syncthreads();
     bool bad = false;
-    for (int jb = 0; jb < G; ++jb) {
-        const int buf = jb & 1;
-        if (wave == jb / CGW) {
-            const int src = G * (jb % CGW) + jb;           // lane of the thread that holds the panel's diagonal block
-            const bool mine = tx == jb;
+
+    // factorises panel jb (called by every lane of the wave that owns it) and publishes it
+    auto factor_panel = [&](int jb) {
+        const int src = G * (jb / NW) + jb;                // lane of the thread that holds the panel's diagonal block
+        const bool mine = tx == jb;
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) {
-                const int j = 4 * jb + jj;
-                const double piv = readlane_f64(a[jj][jj], src);
-                if (!(piv > 0.0)) bad = true;
-                const double y = __builtin_amdgcn_rsq(piv);
-                double g = piv * y, h = 0.5 * y;
-                double e = fma(-h, g, 0.5);
-                g = fma(g, e, g);
-                h = fma(h, e, h);
-                e = fma(-h, g, 0.5);
-                g = fma(g, e, g);
-                h = fma(h, e, h);
-                e = fma(-g, g, piv);
-                g = fma(e, h, g);
-                const double d = g, inv = 2.0 * h;
-                double l[4];
+        for (int jj = 0; jj < 4; ++jj) {
+            const int j = 4 * jb + jj;
+            const double piv = readlane_f64(a[jj][jj], src);
+            if (!(piv > 0.0)) bad = true;
+            const double y = __builtin_amdgcn_rsq(piv);
+            double g = piv * y, h = 0.5 * y;
+            double e = fma(-h, g, 0.5);
+            g = fma(g, e, g);
+            h = fma(h, e, h);
+            e = fma(-h, g, 0.5);
+            g = fma(g, e, g);
+            h = fma(h, e, h);
+            e = fma(-g, g, piv);
+            g = fma(e, h, g);
+            const double d = g, inv = 2.0 * h;
+            double l[4];
 #pragma unroll
-                for (int ii = 0; ii < 4; ++ii) {
-                    const int row = 4 * ty + ii;
-                    l[ii] = row > j ? a[ii][jj] * inv : 0.0;
-                    if (mine && row >= j) a[ii][jj] = row == j ? d : l[ii];
-                }
+            for (int ii = 0; ii < 4; ++ii) {
+                const int row = 4 * ty + ii;
+                l[ii] = row > j ? a[ii][jj] * inv : 0.0;
+                if (mine && row >= j) a[ii][jj] = row == j ? d : l[ii];
+            }
 #pragma unroll
-                for (int cc = jj + 1; cc < 4; ++cc) {
-                    const double lc = readlane_f64(a[cc][jj], src);       // L[4 jb + cc][j]
-                    if (mine)
-#pragma unroll
-                        for (int ii = 0; ii < 4; ++ii) a[ii][cc] = fma(-l[ii], lc, a[ii][cc]);
-                }
+            for (int cc = jj + 1; cc < 4; ++cc) {
+                const double lc = readlane_f64(a[cc][jj], src);       // L[4 jb + cc][j]
                 if (mine)
 #pragma unroll
-                    for (int ii = 0; ii < 4; ++ii) colL[buf][jj][4 * ty + ii] = l[ii];
-                if (lane == src) dinv[buf][jj] = inv;
+                    for (int ii = 0; ii < 4; ++ii) a[ii][cc] = fma(-l[ii], lc, a[ii][cc]);
             }
+            if (mine)
+#pragma unroll
+                for (int ii = 0; ii < 4; ++ii) colL[jb][jj][4 * ty + ii] = l[ii];
+            if (lane == src) dinv[jb][jj] = inv;
         }
-        __syncthreads();
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");         // the columns are in LDS before the count says so
+        if (lane == 0) __hip_atomic_store(&published, jb + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    };
+
+    if (wave == 0) factor_panel(0);
+    for (int jb = 0; jb < G; ++jb) {
+        // wait for panel jb (its owner published it one round ago, or just now)
+        for (int spins = 0; __hip_atomic_load(&published, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) <= jb; ++spins) {
+            if (spins > (1 << 22)) {
+                bad = true;
+                break;
+            }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        // the next panel's owner brings that panel's columns up to date first, factorises and publishes them
+        if (jb + 1 < G && wave == (jb + 1) % NW) {
+            if (tx == jb + 1) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+#pragma unroll
+                    for (int cc = 0; cc < 4; ++cc) {
+                        const double lc = colL[jb][q][4 * tx + cc];
+#pragma unroll
+                        for (int ii = 0; ii < 4; ++ii) a[ii][cc] = fma(-colL[jb][q][4 * ty + ii], lc, a[ii][cc]);
+                    }
+                }
+            }
+            factor_panel(jb + 1);
+        }
         if (ty == jb) {                                    // rows 4 jb .. 4 jb + 3 of X
 #pragma unroll
             for (int q = 0; q < 4; ++q)
@@ -375,32 +414,37 @@ __global__ __launch_bounds__((NB / 4) * (NB / 4)) void potrf_inv_kernel(double* 
                 for (int cc = 0; cc < 4; ++cc) {
                     double acc = b[q][cc];
 #pragma unroll
-                    for (int p = 0; p < q; ++p) acc = fma(-colL[buf][p][4 * jb + q], b[p][cc], acc);
-                    b[q][cc] = acc * dinv[buf][q];
+                    for (int p = 0; p < q; ++p) acc = fma(-colL[jb][p][4 * jb + q], b[p][cc], acc);
+                    b[q][cc] = acc * dinv[jb][q];
                 }
         }
-        // one panel column at a time (few live registers: sixteen waves share the CU's register file at NB = 128)
+        // the rank-4 update: everything it reads is requested first (LDS reads and lane shuffles have a long latency and
+        // there is one wave per SIMD to hide it), then the 128 multiply-adds
+        double lr[4][4], lc[4][4], xs[4][4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            double lr[4], xs[4];
 #pragma unroll
-            for (int ii = 0; ii < 4; ++ii) lr[ii] = colL[buf][q][4 * ty + ii];
+            for (int ii = 0; ii < 4; ++ii) lr[q][ii] = colL[jb][q][4 * ty + ii];
 #pragma unroll
-            for (int cc = 0; cc < 4; ++cc) xs[cc] = __shfl(b[q][cc], (lane & (64 - G)) | jb);
-            if (tx > jb) {
+            for (int cc = 0; cc < 4; ++cc) lc[q][cc] = colL[jb][q][4 * tx + cc];
 #pragma unroll
-                for (int cc = 0; cc < 4; ++cc) {
-                    const double lc = colL[buf][q][4 * tx + cc];
+            for (int cc = 0; cc < 4; ++cc) xs[q][cc] = __shfl(b[q][cc], (lane & (64 - G)) | jb);
+        }
+        if (tx > jb + 1) {                                 // (column group jb + 1 was brought up to date above)
 #pragma unroll
-                    for (int ii = 0; ii < 4; ++ii) a[ii][cc] = fma(-lr[ii], lc, a[ii][cc]);
-                }
-            }
-            if (ty > jb) {
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int cc = 0; cc < 4; ++cc)
+#pragma unroll
+                    for (int ii = 0; ii < 4; ++ii) a[ii][cc] = fma(-lr[q][ii], lc[q][cc], a[ii][cc]);
+        }
+        if (ty > jb) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
 #pragma unroll
                 for (int ii = 0; ii < 4; ++ii)
 #pragma unroll
-                    for (int cc = 0; cc < 4; ++cc) b[ii][cc] = fma(-lr[ii], xs[cc], b[ii][cc]);
-            }
+                    for (int cc = 0; cc < 4; ++cc) b[ii][cc] = fma(-lr[q][ii], xs[q][cc], b[ii][cc]);
         }
     }
 #pragma unroll

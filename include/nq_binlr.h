@@ -330,7 +330,8 @@ int nq_probe_mfma(int dtype, double* tera_ops_per_s);
  * "schedule_full", "fuse_max_mb", "no_fuse", "no_selfq", "no_selfq_c2", "no_resident",
  * "no_quant_wave", "pf_splits1", "pf_splits2", "pf_tg1", "pf_tg2", "pf_ks1", "pf_ks2", "pf_verbose",
  * "exec_spin_limit_us", "no_small_layer", "small_layer_kb", "dgemm_tile", "admm_no_overlap",
- * "two_slice_b8", "admm_no_prio", "admm_product_mode", "admm_inline_svid" (see the source for the meaning of each).  value < 0 restores the default.
+ * "two_slice_b8", "admm_no_prio", "admm_product_mode", "admm_inline_svid",
+ * "admm_no_fused_step" (see the source for the meaning of each).  value < 0 restores the default.
  * The environment variable NQ_<NAME IN CAPITALS> gives an option its initial value; it is read once,
  * when the library first consults an option, never on a launch path.  Plans keep the schedules
  * chosen when they were created.  Not thread-safe against forwards running at the same time.

@@ -34,6 +34,7 @@ struct GemmArgs {
                            // are lower triangular in the sense  op(A)[i][k] = 0 for k < i,  op(B)[k][j] = 0 for k < j
     int k_parts;           // > 1 (unbatched only): blockIdx.z takes the reduction range [z, z + 1) * k_per_part and
     int k_per_part;        // writes its partial product to Cp[z]; beta, Cin and diag apply to part 0 only
+    int skip_first_tile;   // tile (0, 0) is left alone (the launch's diagonal-block workgroup updates and factorises it)
     int lds_pad;           // bytes of LDS requested beyond the kernel's need (fewer workgroups per CU, room for other launches)
     int prio;              // the waves raise their priority: a launch on the critical path that shares the CUs with a
                            // long product on another stream then gets the issue slots first
@@ -55,7 +56,7 @@ constexpr int kBK = 16;        // reduction depth of one LDS tile = four 16x16x4
 // launches are mostly short reductions that would otherwise wait a full memory latency per 16 columns).
 // TA, TB: the transpose flags as compile-time constants (LDS offsets become immediates of the LDS instructions).
 template <int BM, int BN, int PF, bool TA, bool TB>
-__global__ __launch_bounds__(kGemmThreads, 2) void dgemm_kernel(GemmArgs g)
+__device__ __forceinline__ void dgemm_body(const GemmArgs& g, const int bx, const int by, const int bz, double* lds_gemm)
 {
     constexpr int PK = kBK + 1;
     constexpr int PA = BM + 16, PB = BN + 16;
@@ -63,18 +64,18 @@ __global__ __launch_bounds__(kGemmThreads, 2) void dgemm_kernel(GemmArgs g)
     constexpr int SB = BN * PK > kBK * PB ? BN * PK : kBK * PB;
     constexpr int TM = BM / 32, TN = BN / 32;
     constexpr int LA = BM * kBK / kGemmThreads, LB = BN * kBK / kGemmThreads;
-    extern __shared__ __align__(16) double lds_gemm[];
     double* As = lds_gemm;                 // [2][SA]
     double* Bs = lds_gemm + 2 * SA;        // [2][SB]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int i0 = blockIdx.y * BM, j0 = blockIdx.x * BN;
+    const int i0 = by * BM, j0 = bx * BN;
     if (g.lower_only && j0 > i0 + BM - 1) return;
+    if (g.skip_first_tile && bx == 0 && by == 0) return;
     if (g.prio) __builtin_amdgcn_s_setprio(2);
-    const double* A = g.A + (size_t)(g.k_parts > 1 ? 0 : blockIdx.z) * g.sA;
-    const double* B = g.B + (size_t)(g.k_parts > 1 ? 0 : blockIdx.z) * g.sB;
-    const int part = g.k_parts > 1 ? (int)blockIdx.z : 0;
-    const int zb = g.k_parts > 1 ? 0 : (int)blockIdx.z;
+    const double* A = g.A + (size_t)(g.k_parts > 1 ? 0 : bz) * g.sA;
+    const double* B = g.B + (size_t)(g.k_parts > 1 ? 0 : bz) * g.sB;
+    const int part = g.k_parts > 1 ? bz : 0;
+    const int zb = g.k_parts > 1 ? 0 : bz;
     const int k_begin = g.k_from_max ? ((i0 > j0 ? i0 : j0) / kBK) * kBK : part * g.k_per_part;
     const int k_end = g.k_parts > 1 && k_begin + g.k_per_part < g.K ? k_begin + g.k_per_part : g.K;
     const int n_kt = k_end > k_begin ? (k_end - k_begin + kBK - 1) / kBK : 0;
@@ -216,6 +217,13 @@ __global__ __launch_bounds__(kGemmThreads, 2) void dgemm_kernel(GemmArgs g)
             }
 }
 
+template <int BM, int BN, int PF, bool TA, bool TB>
+__global__ __launch_bounds__(kGemmThreads, 2) void dgemm_kernel(GemmArgs g)
+{
+    extern __shared__ __align__(16) double lds_dyn[];
+    dgemm_body<BM, BN, PF, TA, TB>(g, (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z, lds_dyn);
+}
+
 template <int BM, int BN> constexpr size_t gemm_lds_bytes()
 {
     constexpr int PK = kBK + 1;
@@ -277,7 +285,7 @@ static GemmArgs gemm_args(int ta, int tb, int M, int N, int K, double alpha, con
     g.sA = g.sB = g.sC = 0;
     g.trans_a = ta; g.trans_b = tb; g.alpha = alpha; g.beta = beta; g.diag = 0.0;
     g.tile = 0; g.lower_only = 0; g.k_from_max = 0;
-    g.k_parts = 1; g.k_per_part = 0; g.prio = 0; g.lds_pad = 0;
+    g.k_parts = 1; g.k_per_part = 0; g.prio = 0; g.lds_pad = 0; g.skip_first_tile = 0;
     for (double*& c : g.Cp) c = nullptr;
     return g;
 }
@@ -312,17 +320,23 @@ __device__ __forceinline__ double readlane_f64(double v, int lane)
 // up after a fixed number of polls (status is then set and the results are meaningless, every thread still finishes).
 // H (lower part) is overwritten by L; the block of Linv receives L^-1 with an exactly zero upper part.  A pivot that is
 // not > 0 sets *status (the results are then meaningless, every thread still finishes).
+// pre != nullptr: first  A <- A - P P^T  with P = pre [NB][NB] (leading dimension ldh): the block's own tile of the
+// trailing update of the block column before it, so that the update's other tiles can run beside this kernel's work.
+// lds: potrf_lds_bytes<NB>() bytes.
+template <int NB> constexpr size_t potrf_lds_bytes() { return (size_t)((NB / 4) * 4 * NB + (NB / 4) * 4) * sizeof(double) + 16; }
+
 template <int NB>
-__global__ __launch_bounds__((NB / 4) * (NB / 4)) void potrf_inv_kernel(double* H, int ldh, double* Linv, int ldi, int o, int* status, int prio)
+__device__ __forceinline__ void potrf_inv_body(double* H, int ldh, double* Linv, int ldi, int o, int* status, int prio, const double* pre,
+                                               double* lds)
 {
     if (prio) __builtin_amdgcn_s_setprio(3);
     static_assert(NB == 64, "one LDS buffer per panel: 32 KiB at NB = 64");
     constexpr int G = NB / 4;                      // row groups of a column group = lanes they occupy; also the number of panels
     constexpr int CGW = 64 / G;                    // column groups per wave
     constexpr int NW = G / CGW;                    // waves
-    __shared__ double colL[G][4][NB];
-    __shared__ double dinv[G][4];
-    __shared__ int published;                      // panels whose columns are in LDS
+    double (*const colL)[4][NB] = (double (*)[4][NB])lds;
+    double (*const dinv)[4] = (double (*)[4])(lds + G * 4 * NB);
+    int& published = *(int*)(lds + G * 4 * NB + G * 4);            // panels whose columns are in LDS
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int local = lane / G;                    // which of the wave's column groups
     const int tx = wave + NW * local, ty = lane % G;
@@ -334,6 +348,31 @@ __global__ __launch_bounds__((NB / 4) * (NB / 4)) void potrf_inv_kernel(double* 
             a[ii][cc] = H[(size_t)(o + 4 * ty + ii) * ldh + o + 4 * tx + cc];
             b[ii][cc] = (4 * ty + ii == 4 * tx + cc) ? 1.0 : 0.0;
         }
+    if (pre) {
+        // P transposed into LDS (where the panels will go): thread t brings 16 entries of row t mod NB
+        static_assert(NB * NB <= G * 4 * NB, "P fits the panel buffers");
+        double* const pT = lds;                    // [NB][NB]: pT[k][row]
+        {
+            const int row = threadIdx.x % NB, k0 = (threadIdx.x / NB) * (NB * NB / (G * G));
+            const double* src = pre + (size_t)row * ldh + k0;
+#pragma unroll
+            for (int k = 0; k < NB * NB / (G * G); ++k) pT[(k0 + k) * NB + row] = src[k];
+        }
+        __syncthreads();
+#pragma unroll 4
+        for (int k = 0; k < NB; ++k) {
+            double pr[4], pc[4];
+#pragma unroll
+            for (int ii = 0; ii < 4; ++ii) pr[ii] = pT[k * NB + 4 * ty + ii];
+#pragma unroll
+            for (int cc = 0; cc < 4; ++cc) pc[cc] = pT[k * NB + 4 * tx + cc];
+#pragma unroll
+            for (int ii = 0; ii < 4; ++ii)
+#pragma unroll
+                for (int cc = 0; cc < 4; ++cc) a[ii][cc] = fma(-pr[ii], pc[cc], a[ii][cc]);
+        }
+        __syncthreads();                           // everybody has read P: the buffers change hands
+    }
     if (threadIdx.x == 0) published = 0;
     __syncthreads();
     bool bad = false;
@@ -456,6 +495,37 @@ __global__ __launch_bounds__((NB / 4) * (NB / 4)) void potrf_inv_kernel(double* 
             Linv[(size_t)(o + i) * ldi + o + c] = (c <= i) ? b[ii][cc] : 0.0;
         }
     if (bad) *status = 1;
+}
+
+template <int NB>
+__global__ __launch_bounds__((NB / 4) * (NB / 4)) void potrf_inv_kernel(double* H, int ldh, double* Linv, int ldi, int o, int* status, int prio)
+{
+    extern __shared__ __align__(16) double lds_dyn[];
+    potrf_inv_body<NB>(H, ldh, Linv, ldi, o, status, prio, nullptr, lds_dyn);
+}
+
+// One launch for "the trailing update of block column k, and the diagonal block k + 1": workgroup (0, 0) brings the
+// diagonal block up to date itself and factorises it (the long pole of the step), the workgroups (x, y + 1) are the
+// tiles (x, y) of the trailing update A22 -= L21 L21^T, which skips its first tile.  The update's other tiles and the
+// factorisation do not touch each other's data, so the step costs one launch of the factorisation's length instead
+// of two launches one after the other.
+struct PotrfArgs {
+    double* H;
+    double* Linv;
+    const double* pre;
+    int ldh, ldi, o, prio;
+    int* status;
+};
+
+__global__ __launch_bounds__(kGemmThreads, 2) void chol_step_kernel(GemmArgs g, PotrfArgs pa)
+{
+    static_assert(kGemmThreads == (kNB / 4) * (kNB / 4), "both bodies are written for 256 threads");
+    extern __shared__ __align__(16) double lds_dyn[];
+    if (blockIdx.y == 0) {
+        if (blockIdx.x == 0) potrf_inv_body<kNB>(pa.H, pa.ldh, pa.Linv, pa.ldi, pa.o, pa.status, pa.prio, pa.pre, lds_dyn);
+        return;
+    }
+    dgemm_body<64, 64, 4, false, true>(g, (int)blockIdx.x, (int)blockIdx.y - 1, 0, lds_dyn);
 }
 
 // A += B, both [rows][cols] without padding (the two halves of a product whose reduction was split).
@@ -744,9 +814,14 @@ static int svid(const AdmmWs& ws, const double* P, int rows, int r, int iters, i
 static int factor_and_invert(const AdmmWs& ws, hipStream_t s, int prio)
 {
     const int rp = ws.rp, rr = ws.rr, q = rr / kNB;
+    static_assert(potrf_lds_bytes<kNB>() <= gemm_lds_bytes<64, 64>(), "the step kernel's LDS is the product's");
+    const bool fused = !opt_flag(OPT_ADMM_NO_FUSED_STEP);
+    constexpr size_t potrf_lds = potrf_lds_bytes<kNB>();
     for (int k = 0; k < q; ++k) {
         const int o = k * kNB;
-        hipLaunchKernelGGL(potrf_inv_kernel<kNB>, dim3(1), dim3((kNB / 4) * (kNB / 4)), 0, s, ws.H, rp, ws.Linv, rp, o, ws.status, prio);
+        // (with the fused step, the diagonal blocks after the first were factorised by the step launch before)
+        if (k == 0 || !fused)
+            hipLaunchKernelGGL(potrf_inv_kernel<kNB>, dim3(1), dim3((kNB / 4) * (kNB / 4)), potrf_lds, s, ws.H, rp, ws.Linv, rp, o, ws.status, prio);
         const int rem = rr - o - kNB;
         if (rem <= 0) break;
         double* A21 = ws.H + (size_t)(o + kNB) * rp + o;
@@ -761,8 +836,17 @@ static int factor_and_invert(const AdmmWs& ws, hipStream_t s, int prio)
         GemmArgs u = gemm_args(0, 1, rem, rem, kNB, -1.0, A21, rp, A21, rp, 1.0, A22, rp, A22, rp);
         u.lower_only = 1;
         u.prio = prio;
-        rc = launch_gemm(u, 1, s);
-        if (rc != NQ_OK) return rc;
+        if (!fused) {
+            rc = launch_gemm(u, 1, s);
+            if (rc != NQ_OK) return rc;
+            continue;
+        }
+        u.skip_first_tile = 1;
+        PotrfArgs pa{ws.H, ws.Linv, A21, rp, rp, o + kNB, prio, ws.status};
+        const int tiles = rem / 64;
+        constexpr size_t step_lds = gemm_lds_bytes<64, 64>();
+        hipLaunchKernelGGL(chol_step_kernel, dim3(tiles, tiles + 1), dim3(kGemmThreads), step_lds, s, u, pa);
+        NQ_HIP(hipGetLastError());
     }
     // L^-1 block-recursively: with the halves of a diagonal block inverted (X11, X22), the block below the
     // diagonal of its inverse is  -X22 L21 X11;  all pairs of one level run as one batched launch.

@@ -40,7 +40,7 @@ static const OptEntry kOptTable[OPT_COUNT] = {
     {"pf_splits1", false}, {"pf_splits2", false}, {"pf_tg1", false}, {"pf_tg2", false}, {"pf_ks1", false}, {"pf_ks2", false},
     {"pf_verbose", true}, {"exec_spin_limit_us", false}, {"no_small_layer", true}, {"small_layer_kb", false},
     {"dgemm_tile", false}, {"admm_no_overlap", true}, {"two_slice_b8", true},
-    {"admm_no_prio", true}, {"admm_product_mode", false}, {"admm_inline_svid", true},
+    {"admm_no_prio", true}, {"admm_product_mode", false}, {"admm_inline_svid", true}, {"admm_no_fused_step", true},
 };
 static int g_opt[OPT_COUNT];
 static std::once_flag g_opt_once;

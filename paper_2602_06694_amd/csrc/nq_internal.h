@@ -126,6 +126,7 @@ enum Opt {
     OPT_ADMM_NO_PRIO,       // flag: the kernels of LB-ADMM's factorisation chain keep the default wave priority
     OPT_ADMM_PRODUCT_MODE,  // 1: LB-ADMM's product with W keeps two workgroups per CU also beside the factorisation (default 0: one)
     OPT_ADMM_INLINE_SVID,   // flag: LB-ADMM runs the SVID of a factor on the caller's stream, before the next factor's update starts
+    OPT_ADMM_NO_FUSED_STEP, // flag: LB-ADMM's factorisation launches the trailing update and the next diagonal block one after the other
     OPT_COUNT
 };
 int opt(Opt o);                                        // -1 when unset

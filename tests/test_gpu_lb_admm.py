@@ -84,10 +84,11 @@ def test_iterations_match_the_oracle(n, m, r):
     print("worst relative error", compare(outs, ref), flush=True)
 
 
-@pytest.mark.parametrize("option", ["admm_no_overlap", "admm_inline_svid", "admm_no_prio", "admm_product_mode"])
+@pytest.mark.parametrize("option", ["admm_no_overlap", "admm_inline_svid", "admm_no_prio", "admm_product_mode", "admm_no_fused_step"])
 def test_every_schedule_of_the_two_streams_gives_the_oracles_result(option, nqopt):
     """Where the SVID and the product with W run (beside the factorisation or on the caller's stream), with how many
-    workgroups per CU, and at which wave priority, changes the order of events on the device, not the result: each
+    workgroups per CU, at which wave priority, and whether a diagonal block is factorised in the launch of the trailing
+    update before it or in one of its own, changes the order of events on the device, not the result: each
     switch on its own, on a shape large enough for the one-workgroup-per-CU product (64 tiles of 128 x 128 or more)."""
     n, m, r = 1100, 1030, 900
     w, u0, v0 = synth.gen_admm_problem(n, m, r, seed=11)

@@ -34,7 +34,6 @@ struct GemmArgs {
                            // are lower triangular in the sense  op(A)[i][k] = 0 for k < i,  op(B)[k][j] = 0 for k < j
     int k_parts;           // > 1 (unbatched only): blockIdx.z takes the reduction range [z, z + 1) * k_per_part and
     int k_per_part;        // writes its partial product to Cp[z]; beta, Cin and diag apply to part 0 only
-    int skip_first_tile;   // tile (0, 0) is left alone (the launch's diagonal-block workgroup updates and factorises it)
     int lds_pad;           // bytes of LDS requested beyond the kernel's need (fewer workgroups per CU, room for other launches)
     int prio;              // the waves raise their priority: a launch on the critical path that shares the CUs with a
                            // long product on another stream then gets the issue slots first
@@ -70,7 +69,6 @@ __device__ __forceinline__ void dgemm_body(const GemmArgs& g, const int bx, cons
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i0 = by * BM, j0 = bx * BN;
     if (g.lower_only && j0 > i0 + BM - 1) return;
-    if (g.skip_first_tile && bx == 0 && by == 0) return;
     if (g.prio) __builtin_amdgcn_s_setprio(2);
     const double* A = g.A + (size_t)(g.k_parts > 1 ? 0 : bz) * g.sA;
     const double* B = g.B + (size_t)(g.k_parts > 1 ? 0 : bz) * g.sB;
@@ -276,7 +274,7 @@ static int launch_gemm(const GemmArgs& g, int batch, hipStream_t s)
     return launch_gemm_tile<64, 64, 4>(g, batch, s);
 }
 
-static GemmArgs gemm_args(int ta, int tb, int M, int N, int K, double alpha, const double* A, int lda, const double* B, int ldb,
+__host__ __device__ static GemmArgs gemm_args(int ta, int tb, int M, int N, int K, double alpha, const double* A, int lda, const double* B, int ldb,
                           double beta, const double* Cin, int ldcin, double* C, int ldc)
 {
     GemmArgs g{};
@@ -285,7 +283,7 @@ static GemmArgs gemm_args(int ta, int tb, int M, int N, int K, double alpha, con
     g.sA = g.sB = g.sC = 0;
     g.trans_a = ta; g.trans_b = tb; g.alpha = alpha; g.beta = beta; g.diag = 0.0;
     g.tile = 0; g.lower_only = 0; g.k_from_max = 0;
-    g.k_parts = 1; g.k_per_part = 0; g.prio = 0; g.lds_pad = 0; g.skip_first_tile = 0;
+    g.k_parts = 1; g.k_per_part = 0; g.prio = 0; g.lds_pad = 0;
     for (double*& c : g.Cp) c = nullptr;
     return g;
 }
@@ -504,28 +502,62 @@ __global__ __launch_bounds__((NB / 4) * (NB / 4)) void potrf_inv_kernel(double* 
     potrf_inv_body<NB>(H, ldh, Linv, ldi, o, status, prio, nullptr, lds_dyn);
 }
 
-// One launch for "the trailing update of block column k, and the diagonal block k + 1": workgroup (0, 0) brings the
-// diagonal block up to date itself and factorises it (the long pole of the step), the workgroups (x, y + 1) are the
-// tiles (x, y) of the trailing update A22 -= L21 L21^T, which skips its first tile.  The update's other tiles and the
-// factorisation do not touch each other's data, so the step costs one launch of the factorisation's length instead
-// of two launches one after the other.
-struct PotrfArgs {
-    double* H;
-    double* Linv;
-    const double* pre;
-    int ldh, ldi, o, prio;
+// One launch per block column k of the factorisation, after the diagonal block k has been factorised and inverted
+// (X = L11^-1): the panel  P = A21 X^T  (the rows of L below the diagonal block), the trailing update  A22 -= P P^T
+// (lower tiles), and the factorisation of the next diagonal block.  Nothing is handed from one workgroup to another:
+//   * workgroup (0, 0) forms the first 64 rows of P, stores them as that block of L, applies  P P^T  to the diagonal
+//     block k + 1 in its registers and factorises it (the long pole of the launch);
+//   * workgroup (j, i + 1), j <= i, (i, j) != (0, 0), owns tile (i, j) of the trailing matrix: it forms the rows P_i and
+//     P_j of the panel for itself (three 64 x 64 x 64 products instead of one; they cost little next to the
+//     factorisation beside them), keeps them in its own piece of a scratch matrix -- or, tile (i, 0), stores P_i as
+//     block i of L -- and subtracts  P_i P_j^T  from its tile.
+// The panel is NOT written over A21: other workgroups still read A21, so L's blocks below the diagonal go to a matrix
+// of their own (Lb; the diagonal blocks of L stay in H).  A step is then one launch of the factorisation's length
+// where the panel, the update and the factorisation as launches of their own take three.
+struct StepArgs {
+    double* H;          // [..][ld]: A21, A22 (read and updated in place), diagonal blocks of L
+    double* Lb;         // [..][ld]: L below the diagonal
+    double* Linv;       // [..][ld]: the inverted diagonal blocks
+    double* scratch;    // tiles (tiles + 1) / 2 pieces of 2 x 64 x 64
+    int ld, o, prio;    // o: first row / column of block column k
     int* status;
 };
 
-__global__ __launch_bounds__(kGemmThreads, 2) void chol_step_kernel(GemmArgs g, PotrfArgs pa)
+__global__ __launch_bounds__(kGemmThreads, 2) void chol_step_kernel(StepArgs a)
 {
-    static_assert(kGemmThreads == (kNB / 4) * (kNB / 4), "both bodies are written for 256 threads");
+    static_assert(kGemmThreads == (kNB / 4) * (kNB / 4) && kNB == 64, "both bodies are written for 256 threads and 64-wide blocks");
     extern __shared__ __align__(16) double lds_dyn[];
+    const int ld = a.ld;
+    const double* const X = a.Linv + (size_t)a.o * ld + a.o;
+    double* const A21 = a.H + (size_t)(a.o + kNB) * ld + a.o;
+    double* const L21 = a.Lb + (size_t)(a.o + kNB) * ld + a.o;
     if (blockIdx.y == 0) {
-        if (blockIdx.x == 0) potrf_inv_body<kNB>(pa.H, pa.ldh, pa.Linv, pa.ldi, pa.o, pa.status, pa.prio, pa.pre, lds_dyn);
+        if (blockIdx.x != 0) return;
+        GemmArgs g = gemm_args(0, 1, kNB, kNB, kNB, 1.0, A21, ld, X, ld, 0.0, nullptr, 0, L21, ld);
+        g.prio = a.prio;
+        dgemm_body<64, 64, 4, false, true>(g, 0, 0, 0, lds_dyn);
+        __syncthreads();                           // P's first rows are in memory (and LDS is free again)
+        potrf_inv_body<kNB>(a.H, ld, a.Linv, ld, a.o + kNB, a.status, a.prio, L21, lds_dyn);
         return;
     }
-    dgemm_body<64, 64, 4, false, true>(g, (int)blockIdx.x, (int)blockIdx.y - 1, 0, lds_dyn);
+    const int i = (int)blockIdx.y - 1, j = (int)blockIdx.x;
+    if (j > i || i == 0) return;                   // above the diagonal; (0, 0) is the diagonal block's
+    double* const mine = a.scratch + (size_t)(i * (i + 1) / 2 + j) * (2 * kNB * kNB);
+    double* const Pi = j == 0 ? L21 + (size_t)i * kNB * ld : mine;
+    const int ldi = j == 0 ? ld : kNB;
+    double* const Pj = j == i ? Pi : mine + kNB * kNB;
+    const int ldj = j == i ? ldi : kNB;
+    GemmArgs g = gemm_args(0, 1, kNB, kNB, kNB, 1.0, A21 + (size_t)i * kNB * ld, ld, X, ld, 0.0, nullptr, 0, Pi, ldi);
+    g.prio = a.prio;
+    dgemm_body<64, 64, 4, false, true>(g, 0, 0, 0, lds_dyn);
+    if (j != i) {
+        g = gemm_args(0, 1, kNB, kNB, kNB, 1.0, A21 + (size_t)j * kNB * ld, ld, X, ld, 0.0, nullptr, 0, Pj, kNB);
+        dgemm_body<64, 64, 4, false, true>(g, 0, 0, 0, lds_dyn);
+    }
+    __syncthreads();                               // this workgroup's P_i, P_j are in memory
+    double* const Cij = a.H + (size_t)(a.o + kNB + i * kNB) * ld + a.o + kNB + j * kNB;
+    g = gemm_args(0, 1, kNB, kNB, kNB, -1.0, Pi, ldi, Pj, ldj, 1.0, Cij, ld, Cij, ld);
+    dgemm_body<64, 64, 4, false, true>(g, 0, 0, 0, lds_dyn);
 }
 
 // A += B, both [rows][cols] without padding (the two halves of a product whose reduction was split).
@@ -829,17 +861,24 @@ static int factor_and_invert(const AdmmWs& ws, hipStream_t s, int prio)
     static_assert(potrf_lds_bytes<kNB>() <= gemm_lds_bytes<64, 64>(), "the step kernel's LDS is the product's");
     const bool fused = !opt_flag(OPT_ADMM_NO_FUSED_STEP);
     constexpr size_t potrf_lds = potrf_lds_bytes<kNB>();
-    for (int k = 0; k < q; ++k) {
+    constexpr size_t step_lds = gemm_lds_bytes<64, 64>();
+    // where the blocks of L below the diagonal end up: a matrix of their own with the one-launch step (Hinv's buffer,
+    // free until the last product below), in place of A21 with separate launches
+    const double* const Lb = fused ? ws.Hinv : ws.H;
+    hipLaunchKernelGGL(potrf_inv_kernel<kNB>, dim3(1), dim3((kNB / 4) * (kNB / 4)), potrf_lds, s, ws.H, rp, ws.Linv, rp, 0, ws.status, prio);
+    for (int k = 0; k + 1 < q; ++k) {
         const int o = k * kNB;
-        // (with the fused step, the diagonal blocks after the first were factorised by the step launch before)
-        if (k == 0 || !fused)
-            hipLaunchKernelGGL(potrf_inv_kernel<kNB>, dim3(1), dim3((kNB / 4) * (kNB / 4)), potrf_lds, s, ws.H, rp, ws.Linv, rp, o, ws.status, prio);
         const int rem = rr - o - kNB;
-        if (rem <= 0) break;
+        if (fused) {
+            StepArgs sa{ws.H, ws.Hinv, ws.Linv, ws.T, rp, o, prio, ws.status};
+            const int tiles = rem / kNB;
+            hipLaunchKernelGGL(chol_step_kernel, dim3(tiles, tiles + 1), dim3(kGemmThreads), step_lds, s, sa);
+            continue;
+        }
         double* A21 = ws.H + (size_t)(o + kNB) * rp + o;
         // panel: L21 = A21 L11^-T, in place (a workgroup reads all of its rows before it writes them)
         GemmArgs p = gemm_args(0, 1, rem, kNB, kNB, 1.0, A21, rp, ws.Linv + (size_t)o * rp + o, rp, 0.0, nullptr, 0, A21, rp);
-        p.tile = kNB > 64 ? 1 : 3;                 // whole rows per workgroup: the product is in place
+        p.tile = 3;                                // whole rows per workgroup: the product is in place
         p.prio = prio;
         int rc = launch_gemm(p, 1, s);
         if (rc != NQ_OK) return rc;
@@ -848,24 +887,17 @@ static int factor_and_invert(const AdmmWs& ws, hipStream_t s, int prio)
         GemmArgs u = gemm_args(0, 1, rem, rem, kNB, -1.0, A21, rp, A21, rp, 1.0, A22, rp, A22, rp);
         u.lower_only = 1;
         u.prio = prio;
-        if (!fused) {
-            rc = launch_gemm(u, 1, s);
-            if (rc != NQ_OK) return rc;
-            continue;
-        }
-        u.skip_first_tile = 1;
-        PotrfArgs pa{ws.H, ws.Linv, A21, rp, rp, o + kNB, prio, ws.status};
-        const int tiles = rem / 64;
-        constexpr size_t step_lds = gemm_lds_bytes<64, 64>();
-        hipLaunchKernelGGL(chol_step_kernel, dim3(tiles, tiles + 1), dim3(kGemmThreads), step_lds, s, u, pa);
-        NQ_HIP(hipGetLastError());
+        rc = launch_gemm(u, 1, s);
+        if (rc != NQ_OK) return rc;
+        hipLaunchKernelGGL(potrf_inv_kernel<kNB>, dim3(1), dim3((kNB / 4) * (kNB / 4)), potrf_lds, s, ws.H, rp, ws.Linv, rp, o + kNB, ws.status, prio);
     }
+    NQ_HIP(hipGetLastError());
     // L^-1 block-recursively: with the halves of a diagonal block inverted (X11, X22), the block below the
     // diagonal of its inverse is  -X22 L21 X11;  all pairs of one level run as one batched launch.
     for (int b = kNB; b < rr; b *= 2) {
         const int pairs = (rr - b + 2 * b - 1) / (2 * b);       // pairs whose lower half holds real rows
         const long long stride = (long long)2 * b * rp + 2 * b;
-        GemmArgs t = gemm_args(0, 0, b, b, b, 1.0, ws.H + (size_t)b * rp, rp, ws.Linv, rp, 0.0, nullptr, 0, ws.T + (size_t)b * rp, rp);
+        GemmArgs t = gemm_args(0, 0, b, b, b, 1.0, Lb + (size_t)b * rp, rp, ws.Linv, rp, 0.0, nullptr, 0, ws.T + (size_t)b * rp, rp);
         t.sA = t.sB = t.sC = stride;
         t.prio = prio;
         int rc = launch_gemm(t, pairs, s);

@@ -495,12 +495,14 @@ __device__ __forceinline__ void stage_epilogue(const v4i (&acc)[NB][8], int* lds
 #pragma unroll
                     for (int w = 0; w < W; ++w) neg_qs += *(const double*)(lds + w * region + 15 * 64);
                 }
-                double val = fma(raw, __builtin_ldexp(two_step, neg_p), neg_qs);     // exact; rounded once, below
+                const double val = fma(raw, __builtin_ldexp(two_step, neg_p), neg_qs);     // exact
+                // z is rounded to fp32 here and multiplied by the output scale in fp32 -- by the flush for deferred
+                // results, below for the others: the same two roundings on every path, so that the bits of y do not
+                // depend on the schedule
                 if (DEFER) {
                     lds_out[tok * kTileRows + r128] = (float)val;       // scaled by s_out when flushed
                 } else if (grow < e.M) {
-                    val *= (double)oscale;
-                    store_out(e.out, e.out_dtype, (size_t)tok * e.out_stride + grow, (float)val, e.out_scale != nullptr);
+                    store_out(e.out, e.out_dtype, (size_t)tok * e.out_stride + grow, (float)val * oscale, e.out_scale != nullptr);
                 }
             };
             for (int tl = wave; tl < tg; tl += W) one_token(tl);

@@ -499,9 +499,9 @@ __device__ __forceinline__ void exec_body(const ExecTask* __restrict__ tasks, in
                         }
                     }
                     const double raw = fma((double)h, 65536.0, fma((double)mm, 256.0, (double)l));
-                    double val = fma(raw, __builtin_ldexp(two_step, -(row >> 4)), neg_qs);    // exact; rounded once, below
-                    if (op.out_scale) val *= (double)half_bits_to_float(u ? ps_now[1] : ps_now[0]);
-                    float f = (float)val;
+                    const double val = fma(raw, __builtin_ldexp(two_step, -(row >> 4)), neg_qs);    // exact
+                    float f = (float)val;                   // (rounded, then scaled in fp32: as the streaming kernels do)
+                    if (op.out_scale) f *= half_bits_to_float(u ? ps_now[1] : ps_now[0]);
                     if (op.out) store_out(op.out, op.out_dtype, (size_t)grow, f, op.out_scale != nullptr);
                     if (op.out_lds) lds_t[grow] = f;
                     if (op.out_ll) {

@@ -100,6 +100,32 @@ def test_every_schedule_of_the_two_streams_gives_the_oracles_result(option, nqop
     print(option, ": worst relative error", compare(outs, ref), flush=True)
 
 
+def test_random_shapes_and_settings():
+    """Seeded random sizes (around one and several 64-wide blocks, ranks above and below both sides), iteration counts,
+    power rounds and penalty schedules against the oracle."""
+    g = np.random.default_rng(20260701)
+    worst = 0.0
+    for c in range(80):
+        k = g.integers(0, 3)
+        if k == 0:
+            n, m, r = (int(g.integers(1, 200)) for _ in range(3))
+        elif k == 1:
+            n, m, r = int(g.integers(1, 900)), int(g.integers(1, 900)), int(g.integers(1, 600))
+        else:
+            n = int(g.choice([64, 128, 512, 1024])) + int(g.integers(-1, 2))
+            m = int(g.choice([64, 256, 1536, 1600])) + int(g.integers(-1, 2))
+            r = int(g.choice([63, 64, 65, 128, 256, 320]))
+        iters, power = int(g.integers(0, 6)), int(g.integers(0, 7))
+        rho0 = float(g.uniform(0.01, 1.0))
+        rho1 = float(g.uniform(rho0, 5.0))
+        lam = float(g.choice([0.0, 1e-3, 0.1]))
+        w, u0, v0 = synth.gen_admm_problem(n, m, r, seed=5000 + c)
+        ref = O.lb_admm(w, u0, v0, iters, rho0, rho1, lam, power)
+        outs, _, _ = run_gpu(w, u0, v0, iters, rho0, rho1, lam, power)
+        worst = max(worst, compare(outs, ref, 1e-8))
+    print("worst relative error over the random cases", worst, flush=True)
+
+
 def test_many_iterations_small():
     w, u0, v0 = synth.gen_admm_problem(96, 80, 40, seed=5)
     ref = O.lb_admm(w, u0, v0, 60, 0.01, 0.5, 1e-3, 8)

@@ -144,14 +144,9 @@ int hip_fail(hipError_t e, const char* what, const char* file, int line);
 
 // ---- output conversion (device code) ---------------------------------------------------------
 #if defined(__HIPCC__)
-// fp32 -> bf16 bits, round to nearest even; NaN stays NaN (quiet)
-__device__ __forceinline__ uint16_t float_to_bf16_bits(float f)
-{
-    uint32_t u = __builtin_bit_cast(uint32_t, f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
+// fp32 -> bf16 bits, round to nearest even; NaN stays NaN (quiet): the hardware's conversion (v_cvt_pk_bf16_f32),
+// one instruction where the integer arithmetic for it takes six
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
 // fp32 -> fp16 bits, round to nearest even (overflow gives infinity, as IEEE conversion does)
 __device__ __forceinline__ uint16_t float_to_f16_bits(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }
 __device__ __forceinline__ uint16_t float_to_out16(float f, int dtype)

@@ -591,10 +591,11 @@ prefill_gemm_kernel(GemmArgs a)
                             if (a.y_dtype == NQ_F32) {
                                 __builtin_nontemporal_store(o, (v4f*)((float*)a.y_out + at));
                             } else {
-                                uint2 pk;
+                                typedef uint32_t v2u32 __attribute__((ext_vector_type(2)));
+                                v2u32 pk;
                                 pk.x = (uint32_t)float_to_out16(o.x, a.y_dtype) | ((uint32_t)float_to_out16(o.y, a.y_dtype) << 16);
                                 pk.y = (uint32_t)float_to_out16(o.z, a.y_dtype) | ((uint32_t)float_to_out16(o.w, a.y_dtype) << 16);
-                                *(uint2*)((uint16_t*)a.y_out + at) = pk;
+                                __builtin_nontemporal_store(pk, (v2u32*)((uint16_t*)a.y_out + at));     // (as the fp32 store: written once, not read here)
                             }
                         }
                     } else {

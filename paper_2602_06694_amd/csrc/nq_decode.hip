@@ -398,7 +398,11 @@ struct EpilogueArgs {
 };
 
 // LDS ints one wave needs for the epilogue: 16 columns x 64 rows
-constexpr int kEpiRegion = 16 * 64;
+// ints between the 16 columns of a wave's epilogue region: the 64 rows of a half plus 4 -- with 64 (256 bytes, once round
+// the LDS banks) the 16-byte writes of the up to 15 lanes that hold the columns of one row group all fell on the same
+// banks (counters on the batch-8 kernels: 59-65 % of the LDS's active cycles were bank conflicts)
+constexpr int kEpiCol = 68;
+constexpr int kEpiRegion = 16 * kEpiCol;
 // LDS ints a wave of stage_selfq_kernel needs: its quantised share (16 steps of 192 bytes per chunk
 // a lane holds), later its epilogue region
 constexpr int selfq_region_ints(int chunks_per_lane) { return chunks_per_lane * 16 * 192 / 4 > kEpiRegion ? chunks_per_lane * 16 * 192 / 4 : kEpiRegion; }
@@ -447,7 +451,7 @@ __device__ __forceinline__ void stage_epilogue(const v4i (&acc)[NB][8], int* lds
             // accumulator layout of the 16x16 result: lane (g, n), register v <-> D[row 4g+v][col n];
             // the four registers of a plane are four consecutive rows: one 16-byte LDS write per plane
             if (n < SL * tg) {
-                v4i* dst = (v4i*)(my_lds + n * 64 + 4 * g);
+                v4i* dst = (v4i*)(my_lds + n * kEpiCol + 4 * g);
 #pragma unroll
                 for (int p = 0; p < 4; ++p) {
                     // plane 7 (the int8 sign bit) holds -128 * sum: stored negated, so that every plane p reads 2^p * sum
@@ -474,14 +478,14 @@ __device__ __forceinline__ void stage_epilogue(const v4i (&acc)[NB][8], int* lds
                 int h = 0, m = 0, l = 0;
 #pragma unroll
                 for (int w = 0; w < W; ++w) {
-                    const int* q = lds + w * region + (SL * tl) * 64 + row;
+                    const int* q = lds + w * region + (SL * tl) * kEpiCol + row;
                     if (SL == 3) {
                         h += q[0];
-                        m += q[64];
-                        l += q[128];
+                        m += q[kEpiCol];
+                        l += q[2 * kEpiCol];
                     } else {
                         m += q[0];
-                        l += q[64];
+                        l += q[kEpiCol];
                     }
                 }
                 // sum_n b_n q_n = (65536 h + 256 m + l) * 2^-p: the raw sums are below 2^30, so
@@ -493,7 +497,7 @@ __device__ __forceinline__ void stage_epilogue(const v4i (&acc)[NB][8], int* lds
                 if (own_meta && meta_is_partial && W > 1) {
                     neg_qs = 0.0;
 #pragma unroll
-                    for (int w = 0; w < W; ++w) neg_qs += *(const double*)(lds + w * region + 15 * 64);
+                    for (int w = 0; w < W; ++w) neg_qs += *(const double*)(lds + w * region + 15 * kEpiCol);
                 }
                 const double val = fma(raw, __builtin_ldexp(two_step, neg_p), neg_qs);     // exact
                 // z is rounded to fp32 here and multiplied by the output scale in fp32 -- by the flush for deferred
@@ -1169,7 +1173,7 @@ stage_selfq_kernel(const FusedItem* __restrict__ items, QuantDesc q1, StageDesc 
     // the region changes hands: quantised input -> epilogue (wave-local, so no workgroup barrier)
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __builtin_amdgcn_wave_barrier();
-    if (W > 1 && lane == 0) *(double*)(lds + wave * region + 15 * 64) = my_meta.neg_qs;
+    if (W > 1 && lane == 0) *(double*)(lds + wave * region + 15 * kEpiCol) = my_meta.neg_qs;
     EpilogueArgs ea;
     ea.meta = sd.meta; ea.out_scale = sd.out_scale; ea.out = sd.out;
     ea.M = sd.M; ea.out_stride = sd.out_stride; ea.out_dtype = sd.out_dtype;

@@ -837,13 +837,20 @@ stage_shared_kernel(const StageDesc* __restrict__ descs, const WorkItem* __restr
     int* const lds_epi = (int*)(lds_b + 2 * buf_bytes) + wave * kEpiRegion;
     float* const lds_out = (float*)((int*)(lds_b + 2 * buf_bytes) + W * kEpiRegion) + wave * (per_max * kTileRows * batch);
 
-    // this lane's operand inside a staged chunk (step 0); unused columns read token 0
+    // this lane's operand inside a staged chunk (step 0).  An unused column re-reads the group's LAST used one: the same
+    // address, which the LDS broadcasts -- token 0's pieces would be other addresses on the banks of the octet's own
+    // operands (the LDS serves 128 bytes, eight lanes of a 16-byte read, per cycle).  (The conflict counter of the
+    // batch-8 launches falls by a sixth with it; their duration does not change.)
     uint32_t b_lds[NB];
 #pragma unroll
     for (int cg = 0; cg < NB; ++cg) {
-        int tok = SL == 3 ? 5 * cg + n / 3 : n / 2;
-        const int slice = SL == 3 ? n % 3 : 1 + n % 2;
-        if ((SL == 3 && n >= 15) || tok >= batch) tok = 0;
+        constexpr int kTokPerGroup = SL == 3 ? 5 : 8;
+        int used = SL * (batch - kTokPerGroup * cg);                    // columns of this group that carry a token
+        used = used > SL * kTokPerGroup ? SL * kTokPerGroup : (used < 1 ? 1 : used);
+        const int col = n < used ? n : used - 1;
+        int tok = kTokPerGroup * cg + col / SL;
+        const int slice = SL == 3 ? col % 3 : 1 + col % 2;
+        if (tok >= batch) tok = 0;                                      // (a group without tokens: never used)
         b_lds[cg] = (uint32_t)(tok * kShareTokStride + (g * kSlices + slice) * 16);
     }
     // this thread's share of a chunk: 16-byte pieces id = i * 512 + tid < batch * 96 (i < 2);

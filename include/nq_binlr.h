@@ -238,7 +238,8 @@ int nq_plan_forward(nq_plan p, void* stream);
  * duration of each kernel in milliseconds:
  * ms[0] input quantisation, ms[1] stage 1 (t = V^T x'), ms[2] quantisation of t,
  * ms[3] stage 2 (y = s_out (.) U t).  Synchronises `stream`.  Where a stage quantises its own
- * input (short batch-1 lists) the quantisation entry is ~0 and the stage entry covers both. */
+ * input (batch-1 lists) there is no quantisation launch: its entry is 0 and the stage entry
+ * covers both (no event is recorded for a launch that does not exist). */
 int nq_plan_forward_timed(nq_plan p, void* stream, float ms[4]);
 /* Debug: which schedule each of the plan's two stage launches uses.  w[0] stage 1, w[1] stage 2:
  * 1 = one wave per item, 4 / 16 = that many waves share a row block, 8 = the waves of a workgroup share an op's

@@ -1021,15 +1021,19 @@ static int plan_run(nq_plan p, hipStream_t s, bool timed)
             return launch_selfq(fitems, n_items, qdummy, sdummy, w == kSelfqSchedule1 ? 1 : 4, max_steps, s);
         return launch_stage(sd, sdummy, items, n_items, w, stream_max_rbs(p->batch), p->batch, s);
     };
+    // (timed: an event only where a launch begins or ends -- two events with nothing between them are 5 us apart, and
+    // that would be charged to the launches next to them)
     if (timed) NQ_HIP(hipEventRecord(p->ev[0], s));
-    if (!self_quantising(p->w1) &&
-        (rc = launch_quantize(p->qx, qdummy, p->n, p->max_chunks_x, p->batch, s)) != NQ_OK) return rc;
-    if (timed) NQ_HIP(hipEventRecord(p->ev[1], s));
+    if (!self_quantising(p->w1)) {
+        if ((rc = launch_quantize(p->qx, qdummy, p->n, p->max_chunks_x, p->batch, s)) != NQ_OK) return rc;
+        if (timed) NQ_HIP(hipEventRecord(p->ev[1], s));
+    }
     if ((rc = run_stage(p->w1, p->s1, p->items1, p->fitems1, p->n_items1, p->max_steps1)) != NQ_OK) return rc;
     if (timed) NQ_HIP(hipEventRecord(p->ev[2], s));
-    if (!self_quantising(p->w2) &&
-        (rc = launch_quantize(p->qt, qdummy, p->n, p->max_chunks_t, p->batch, s)) != NQ_OK) return rc;
-    if (timed) NQ_HIP(hipEventRecord(p->ev[3], s));
+    if (!self_quantising(p->w2)) {
+        if ((rc = launch_quantize(p->qt, qdummy, p->n, p->max_chunks_t, p->batch, s)) != NQ_OK) return rc;
+        if (timed) NQ_HIP(hipEventRecord(p->ev[3], s));
+    }
     if ((rc = run_stage(p->w2, p->s2, p->items2, p->fitems2, p->n_items2, p->max_steps2)) != NQ_OK) return rc;
     if (timed) NQ_HIP(hipEventRecord(p->ev[4], s));
     return NQ_OK;
@@ -1059,7 +1063,13 @@ extern "C" int nq_plan_forward_timed(nq_plan p, void* stream, float ms[4])
     int rc = plan_run(p, (hipStream_t)stream, true);
     if (rc != NQ_OK) return rc;
     NQ_HIP(hipEventSynchronize(p->ev[4]));
-    for (int i = 0; i < 4; ++i) NQ_HIP(hipEventElapsedTime(&ms[i], p->ev[i], p->ev[i + 1]));
+    auto self_quantising = [](int w) { return w == kFusedSchedule || w == kSelfqSchedule1 || w == kSelfqSchedule4; };
+    const bool q1 = !self_quantising(p->w1), q2 = !self_quantising(p->w2);
+    ms[0] = ms[2] = 0.f;
+    if (q1) NQ_HIP(hipEventElapsedTime(&ms[0], p->ev[0], p->ev[1]));
+    NQ_HIP(hipEventElapsedTime(&ms[1], p->ev[q1 ? 1 : 0], p->ev[2]));
+    if (q2) NQ_HIP(hipEventElapsedTime(&ms[2], p->ev[2], p->ev[3]));
+    NQ_HIP(hipEventElapsedTime(&ms[3], p->ev[q2 ? 3 : 2], p->ev[4]));
     return NQ_OK;
 }
 

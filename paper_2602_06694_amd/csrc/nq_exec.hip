@@ -5,7 +5,7 @@
 // A layer forward is two sign-matrix x vector products (Section 3.1 Eq. 1; Appendix E.2), so a
 // stack of L levels is 2 L phases, each depending on ALL outputs of the one before.  Run as
 // launches, a phase costs a launch-to-launch latency (about 7 us measured) for well under 1 us of
-// streaming.  Here one workgroup of 16 waves sits on every CU and walks its own list of tasks; a
+// streaming.  Here one workgroup of 8 waves sits on every CU and walks its own list of tasks; a
 // task is a run of 128-row blocks of one phase's sign matrix.  Nothing is ever waited for except data:
 //
 //  - every value that crosses from one phase to the next (t of stage 1; y where a later layer of
@@ -39,12 +39,12 @@ constexpr int kExecThreads = 64 * kExecWaves;
 constexpr int kExecRing = 8;                       // sign tiles a wave keeps in flight
 constexpr int kExecMaxSteps = 512;                 // longest reduction: 32768 elements (96 KiB of LDS as fixed point)
 constexpr int kExecEpiInts = 3 * kTileRows;        // per wave: the three slice columns x 128 rows
-constexpr int kExecHeld = 4;                       // 16-element chunks of the input a thread keeps in registers (inputs of up to 16384 elements)
+constexpr int kExecHeld = 4;                       // 16-element chunks of the input a thread keeps in registers (4 x 512 threads x 16 = 32768 elements)
 
 // One task of one workgroup: a run of row blocks of one stage of one layer, with everything the
 // kernel needs to know about that stage in the record itself -- a workgroup's records are
 // consecutive in memory, so the next one is a neighbouring cache line, requested a task ahead.
-// W = 1 << wl waves share a row block, 16 / W row blocks are worked on side by side.
+// W = 1 << wl waves share a row block, 8 / W row blocks are worked on side by side.
 struct ExecTask {
     const uint32_t* tiles;          // sign tiles of A (V^T or U)
     const void* in;                 // the input vector: plain elements of in_dtype (in_ll 0), pairs (1), or none: the LDS array (2)
@@ -120,7 +120,7 @@ __device__ __forceinline__ long long wave_sum64(long long v)
 
 // ---------------------------------------------------------------------------------------------
 // LDS: [bq_bytes] the task's input as fixed point (layout of the global buffers of the streaming
-// kernels) | [16][3][128] raw sums of the waves | sum of q, largest magnitude, flags
+// kernels) | [8][3][128] raw sums of the waves | sum of q, largest magnitude, flags
 // ---------------------------------------------------------------------------------------------
 // tasks[ti .. t_end) of this workgroup; state == nullptr: a lone workgroup whose tasks hand over through LDS only
 __device__ __forceinline__ void exec_body(const ExecTask* __restrict__ tasks, int ti, const int t_end,
@@ -317,8 +317,9 @@ __device__ __forceinline__ void exec_body(const ExecTask* __restrict__ tasks, in
                 m = fmaxf(m, a);
             }
         };
-        // A thread owns chunks tid, tid + 256, ...; inputs of up to 16384 elements (four chunks per thread) stay in
-        // registers between the maximum and the rounding, longer ones (up to 32768) are fetched twice.
+        // A thread owns chunks tid, tid + 512, ...; inputs of up to 32768 elements (four chunks per thread: every input
+        // the executor accepts, kExecMaxSteps) stay in registers between the maximum and the rounding; the other
+        // branch, which fetches a longer input twice, is kept for a narrower workgroup.
         const int n_c = (n_chunks + kExecThreads - 1) / kExecThreads;           // chunks per thread
         const bool held = n_c <= kExecHeld;
         if (op.in_ll == 2) __syncthreads();                 // the LDS array of this workgroup's previous task is complete
@@ -417,7 +418,7 @@ __device__ __forceinline__ void exec_body(const ExecTask* __restrict__ tasks, in
         const double two_step = bad ? (double)__builtin_nanf("") : 2.0 * (double)step;
         const double neg_qs = -tot * (double)step;
 
-        // ---- the task's row blocks, 16 / W at a time ----
+        // ---- the task's row blocks, 8 / W at a time ----
         const int per = kExecWaves >> tk.wl;
         const int n_grp = (tk.n_rb + per - 1) / per;
         const uint32_t b_lane = (uint32_t)(bq_piece(g, n < 3 ? n : 0) * 16);     // unused columns re-read slice 0
@@ -566,7 +567,7 @@ struct PlannedTask {
 };
 
 // Levels are run as 2 phases each (stage 1 of every layer of the level, then stage 2).  Inside a
-// phase the row blocks are dealt to the workgroups in runs of 16 / W with the largest W (waves per row
+// phase the row blocks are dealt to the workgroups in runs of 8 / W with the largest W (waves per row
 // block) for which every run finds a workgroup of its own; consecutive phases start where the one
 // before stopped, so a workgroup's next task usually lies several phases ahead and its first tiles
 // are in registers long before its input exists.  Every workgroup's list is in phase order, which

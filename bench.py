@@ -231,6 +231,26 @@ def measured_traffic(workload_name, stage, kernel_name):
     return None
 
 
+def graph_replay_ms(run, steps, windows=3):
+    """`run` captured once into a HIP graph (torch's capture stream), then replayed: median ms per replay,
+    or the reason the capture failed -- reported, not hidden."""
+    import torch
+    try:
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):                    # first calls outside the capture (lazy set-up)
+            run()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            run()
+        prewarm(graph.replay, 0.02)
+        ms = window_stats(timed_windows(graph.replay, steps, windows))["median"]
+        del graph
+        return ms
+    except Exception as e:
+        return f"capture failed: {e}"
+
+
 def time_stack(cfg, batch, steps=10, warmup=2):
     """Whole decoder stack of config 3 / 4 as one plan of independent layers: step time (median of five
     windows), weight GB/s and per-kernel roofline; and the same stack as a loop of single-layer calls."""
@@ -267,9 +287,12 @@ def time_stack(cfg, batch, steps=10, warmup=2):
             nq.nq_binlr_forward(h, x, y, batch)
     prewarm(loop, 0.02)
     ms_loop = window_stats(timed_windows(loop, 2, 3))["median"]
+    ms_loop_graph = graph_replay_ms(loop, 2)
+    ms_plan_graph = graph_replay_ms(lambda: nq.nq_plan_forward(plan), steps)
     res = {"layers": len(handles), "ms_per_step": ms, "ms_per_step_windows": window_stats(win),
            "weight_GBps": wbytes / ms / 1e6, "tokens_per_s": batch / (ms * 1e-3),
-           "ms_per_step_loop_of_single_calls": ms_loop,
+           "ms_per_step_loop_of_single_calls": ms_loop, "ms_per_step_hip_graph_of_that_loop": ms_loop_graph,
+           "ms_per_step_hip_graph_of_the_plan": ms_plan_graph,
            "kernel_ms": {"quantize_x": pk[0], "stage1": pk[1], "quantize_t": pk[2], "stage2": pk[3]},
            "stage1_GBps": sb1 / pk[1] / 1e6, "stage2_GBps": sb2 / pk[3] / 1e6,
            "stage1_frac_of_hbm_peak": sb1 / pk[1] / 1e6 / HBM_PEAK_GBPS,
@@ -335,6 +358,9 @@ def time_stack_in_dependency_order(cfg, steps=10):
     prewarm(levels, 0.02)
     ms_levels = window_stats(timed_windows(levels, 3, 3))["median"]
     ms_single = window_stats(timed_windows(single, 2, 3))["median"]
+    ms_levels_graph = graph_replay_ms(levels, 3)
+    ms_exec_graph = graph_replay_ms(lambda: nq.nq_exec_forward(ex), steps)
+    nq.nq_exec_status(ex)
     for lp in plans:
         nq.nq_plan_destroy(lp)
     nq.nq_exec_destroy(ex)
@@ -345,7 +371,9 @@ def time_stack_in_dependency_order(cfg, steps=10):
             "executor_us_per_stage": ms * 1e3 / phases, "executor_weight_GBps": wbytes / ms / 1e6,
             "executor_bit_identical_to_single_calls": bool(identical),
             "executor_workgroups": n_wg, "executor_tasks": n_tasks, "executor_lds_bytes": lds,
-            "four_plans_per_block_ms_per_step": ms_levels, "single_calls_ms_per_step": ms_single}
+            "four_plans_per_block_ms_per_step": ms_levels, "single_calls_ms_per_step": ms_single,
+            "hip_graph_of_the_four_plans_per_block_ms_per_step": ms_levels_graph,
+            "hip_graph_of_the_executor_launch_ms_per_step": ms_exec_graph}
 
 
 def time_pool_batch(pool, batch, steps=10, warmup=2, two_slice=False):

@@ -702,6 +702,9 @@ def main():
         "config": {"workload": name, "layers_per_step": len(work), "batch": batch,
                    "weight_bytes_per_step": w_bytes, "algorithmic_bytes_per_step": all_bytes},
         "tokens_per_s_per_layer": batch * len(work) / (wall_ms * 1e-3),
+        # side figure only: the rate at which a dense bf16 copy of the same layers (2 * d_out * d_in bytes each)
+        # would have to stream to finish a step in the same time
+        "bf16_dense_equivalent_GBps": sum(2 * shp.d_out * shp.d_in for shp, _, _ in work) / (wall_ms * 1e-3) / 1e9,
         "ms_per_step_hip_events": ev_ms,
         "ms_per_step_windows": window_stats(more_windows),
         "observed_clocks": observed_clocks,

@@ -42,6 +42,9 @@ def lib() -> ctypes.CDLL:
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2602_06694_amd.build` "
                               "(there is no CPU fallback)")
+        # torch first: it brings its own copy of the HIP runtime, and a process must hold one.  Loaded the other way
+        # round (this library, then torch) the system's copy comes in first and torch then finds no GPU.
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, i64, ci, u32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_uint32
         L.nq_packed_words.argtypes = [i64, i64]; L.nq_packed_words.restype = ctypes.c_size_t

@@ -910,3 +910,29 @@ def test_layers_rebuilt_beside_a_long_lived_one_do_not_grow_device_memory(nqopt)
     assert max(counts) == counts[0], counts
     assert rel_err(keeper.forward(x_np), keeper.oracle(x_np)) <= DECODE_TOL
     keeper.close()
+
+
+def test_library_used_before_torch_touches_the_gpu_leaves_torch_working():
+    """A fresh process that creates a layer through the binding BEFORE torch has initialised the GPU, and only
+    then moves a tensor to the device: the process must hold one HIP runtime (torch's), or torch finds no GPU.
+    Runs in a child process because the order of the first loads is what is tested."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = (
+        "import numpy as np\n"
+        "from paper_2602_06694_amd import binding as nq, synth\n"
+        "shp = synth.LinearShape('t', 256, 192, 64)\n"
+        "d = synth.gen_layer(9, 0, 0, shp)\n"
+        "h = nq.nq_binlr_create(256, 192, 64, d.U_words, d.V_words, d.s_out, d.s_in, nq.NQ_F32)\n"
+        "import torch\n"
+        "x = torch.ones((1, 192), dtype=torch.float32).cuda()\n"
+        "y = torch.zeros((1, 256), dtype=torch.float32, device='cuda')\n"
+        "nq.nq_binlr_forward(h, x, y, 1)\n"
+        "torch.cuda.synchronize()\n"
+        "assert bool(torch.isfinite(y).all()) and float(y.abs().max()) > 0\n"
+        "nq.nq_binlr_destroy(h)\n"
+        "print('order ok')\n")
+    res = subprocess.run([sys.executable, "-c", code], cwd=root, capture_output=True, text=True, timeout=240)
+    assert res.returncode == 0 and "order ok" in res.stdout, res.stderr[-2000:]

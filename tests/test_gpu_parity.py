@@ -936,3 +936,31 @@ def test_library_used_before_torch_touches_the_gpu_leaves_torch_working():
         "print('order ok')\n")
     res = subprocess.run([sys.executable, "-c", code], cwd=root, capture_output=True, text=True, timeout=240)
     assert res.returncode == 0 and "order ok" in res.stdout, res.stderr[-2000:]
+
+
+def test_different_layers_run_side_by_side_on_two_streams():
+    """The header promises that forwards of DIFFERENT layers may run at the same time (a layer owns its
+    workspace; nothing is shared between layers).  Two layers, two streams of the default priority, many forwards
+    issued alternately without waiting, on every path (streaming with and without a quantisation launch, dense):
+    each output must be what the same call gives alone, bit for bit, and match the oracle."""
+    import torch
+    specs = [(1536, 4096, 1024, "bf16"), (1100, 11008, 700, "bf16")]
+    for batch in (1, 8, 70):
+        layers = [Layer(*s, seed=6400 + 10 * i) for i, s in enumerate(specs)]
+        xs_np = [synth.gen_x(batch, L.d_in, 6450 + i, L.x_dtype) for i, L in enumerate(layers)]
+        alone = [L.forward(x) for L, x in zip(layers, xs_np)]
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        xs = [to_device(x, L.x_dtype) for L, x in zip(layers, xs_np)]
+        ys = [[new_output(batch, L.d_out) for _ in range(12)] for L in layers]
+        torch.cuda.synchronize()
+        for rep in range(12):
+            for i, L in enumerate(layers):
+                nq.nq_binlr_forward(L.h, xs[i], ys[i][rep], batch, stream=streams[i])
+        torch.cuda.synchronize()
+        tol = DECODE_TOL if batch <= 8 else 7e-4
+        for i, L in enumerate(layers):
+            assert rel_err(alone[i], L.oracle(xs_np[i])) <= tol
+            for rep in range(12):
+                assert np.array_equal(ys[i][rep].cpu().numpy(), alone[i]), (batch, i, rep)
+        for L in layers:
+            L.close()

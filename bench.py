@@ -663,7 +663,8 @@ def main():
         torch.cuda.synchronize()
     observed_clocks = clocks.read()
 
-    # per-kernel durations (HIP events recorded between the four launches, on the same stream)
+    # per-kernel durations: a pair of HIP events bound to each launch on its stream (start and stop of the kernel itself,
+    # what rocprofv3 reports per dispatch; the dispatch gaps between launches belong to no kernel)
     reps = max(3, min(args.steps, 20))
     per_kernel = np.zeros(4)
     for _ in range(reps):

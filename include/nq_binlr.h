@@ -234,12 +234,13 @@ int nq_binlr_forward_many(const nq_handle* hs, const void* const* xs, void* cons
 int nq_plan_create(nq_plan* out, const nq_handle* hs, const void* const* xs, void* const* ys,
                    int n, int batch);
 int nq_plan_forward(nq_plan p, void* stream);
-/* Runs the plan once with HIP events between its kernels, waits for it, and returns the
- * duration of each kernel in milliseconds:
+/* Runs the plan once with a pair of HIP events bound to each of its kernels (start and stop of the kernel itself,
+ * hipExtLaunchKernelGGL: the dispatch gaps between launches are not part of any entry, so the entries add up to less
+ * than the step), waits for it, and returns the duration of each kernel in milliseconds:
  * ms[0] input quantisation, ms[1] stage 1 (t = V^T x'), ms[2] quantisation of t,
  * ms[3] stage 2 (y = s_out (.) U t).  Synchronises `stream`.  Where a stage quantises its own
  * input (batch-1 lists) there is no quantisation launch: its entry is 0 and the stage entry
- * covers both (no event is recorded for a launch that does not exist). */
+ * covers both. */
 int nq_plan_forward_timed(nq_plan p, void* stream, float ms[4]);
 /* Debug: which schedule each of the plan's two stage launches uses.  w[0] stage 1, w[1] stage 2:
  * 1 = one wave per item, 4 / 16 = that many waves share a row block, 8 = the waves of a workgroup share an op's

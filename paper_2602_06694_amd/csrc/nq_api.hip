@@ -65,6 +65,8 @@ int opt(Opt o)
     return g_opt[o];
 }
 
+thread_local LaunchTiming g_launch_timing;
+
 static size_t dtype_size(int dt) { return dt == NQ_F32 ? 4 : 2; }
 
 }  // namespace nq
@@ -211,7 +213,7 @@ struct nq_plan_s {
     int max_steps1, max_steps2;     // longest reduction of each stage launch
     int max_chunks_x, max_chunks_t; // longest vector of each quantisation launch (picks its block size)
     std::vector<nq_handle> handles;
-    hipEvent_t ev[5];
+    hipEvent_t ev[8];               // start / stop of the four launches of a timed run
     bool have_events;
 };
 
@@ -1021,21 +1023,28 @@ static int plan_run(nq_plan p, hipStream_t s, bool timed)
             return launch_selfq(fitems, n_items, qdummy, sdummy, w == kSelfqSchedule1 ? 1 : 4, max_steps, s);
         return launch_stage(sd, sdummy, items, n_items, w, stream_max_rbs(p->batch), p->batch, s);
     };
-    // (timed: an event only where a launch begins or ends -- two events with nothing between them are 5 us apart, and
-    // that would be charged to the launches next to them)
-    if (timed) NQ_HIP(hipEventRecord(p->ev[0], s));
+    // timed: launch k carries the event pair ev[2k], ev[2k + 1], bound to the kernel itself (see LaunchTiming)
+    struct Timed {
+        Timed(bool on, hipEvent_t a, hipEvent_t b) : on_(on) { if (on) g_launch_timing = LaunchTiming{a, b}; }
+        ~Timed() { if (on_) g_launch_timing = LaunchTiming{}; }
+        bool on_;
+    };
     if (!self_quantising(p->w1)) {
+        Timed t(timed, p->ev[0], p->ev[1]);
         if ((rc = launch_quantize(p->qx, qdummy, p->n, p->max_chunks_x, p->batch, s)) != NQ_OK) return rc;
-        if (timed) NQ_HIP(hipEventRecord(p->ev[1], s));
     }
-    if ((rc = run_stage(p->w1, p->s1, p->items1, p->fitems1, p->n_items1, p->max_steps1)) != NQ_OK) return rc;
-    if (timed) NQ_HIP(hipEventRecord(p->ev[2], s));
+    {
+        Timed t(timed, p->ev[2], p->ev[3]);
+        if ((rc = run_stage(p->w1, p->s1, p->items1, p->fitems1, p->n_items1, p->max_steps1)) != NQ_OK) return rc;
+    }
     if (!self_quantising(p->w2)) {
+        Timed t(timed, p->ev[4], p->ev[5]);
         if ((rc = launch_quantize(p->qt, qdummy, p->n, p->max_chunks_t, p->batch, s)) != NQ_OK) return rc;
-        if (timed) NQ_HIP(hipEventRecord(p->ev[3], s));
     }
-    if ((rc = run_stage(p->w2, p->s2, p->items2, p->fitems2, p->n_items2, p->max_steps2)) != NQ_OK) return rc;
-    if (timed) NQ_HIP(hipEventRecord(p->ev[4], s));
+    {
+        Timed t(timed, p->ev[6], p->ev[7]);
+        if ((rc = run_stage(p->w2, p->s2, p->items2, p->fitems2, p->n_items2, p->max_steps2)) != NQ_OK) return rc;
+    }
     return NQ_OK;
 }
 
@@ -1062,14 +1071,13 @@ extern "C" int nq_plan_forward_timed(nq_plan p, void* stream, float ms[4])
     }
     int rc = plan_run(p, (hipStream_t)stream, true);
     if (rc != NQ_OK) return rc;
-    NQ_HIP(hipEventSynchronize(p->ev[4]));
+    NQ_HIP(hipEventSynchronize(p->ev[7]));
     auto self_quantising = [](int w) { return w == kFusedSchedule || w == kSelfqSchedule1 || w == kSelfqSchedule4; };
-    const bool q1 = !self_quantising(p->w1), q2 = !self_quantising(p->w2);
     ms[0] = ms[2] = 0.f;
-    if (q1) NQ_HIP(hipEventElapsedTime(&ms[0], p->ev[0], p->ev[1]));
-    NQ_HIP(hipEventElapsedTime(&ms[1], p->ev[q1 ? 1 : 0], p->ev[2]));
-    if (q2) NQ_HIP(hipEventElapsedTime(&ms[2], p->ev[2], p->ev[3]));
-    NQ_HIP(hipEventElapsedTime(&ms[3], p->ev[q2 ? 3 : 2], p->ev[4]));
+    if (!self_quantising(p->w1)) NQ_HIP(hipEventElapsedTime(&ms[0], p->ev[0], p->ev[1]));
+    NQ_HIP(hipEventElapsedTime(&ms[1], p->ev[2], p->ev[3]));
+    if (!self_quantising(p->w2)) NQ_HIP(hipEventElapsedTime(&ms[2], p->ev[4], p->ev[5]));
+    NQ_HIP(hipEventElapsedTime(&ms[3], p->ev[6], p->ev[7]));
     return NQ_OK;
 }
 

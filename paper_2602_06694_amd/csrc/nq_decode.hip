@@ -280,8 +280,8 @@ int launch_quantize(const QuantDesc* d_descs, const QuantDesc& single, int n_ops
         const dim3 wgrid((unsigned)(((size_t)n_ops * batch + 3) / 4));
 #define NQ_LAUNCH_QWAVE(H)                                                                              \
     do {                                                                                                \
-        if (batch <= 5) hipLaunchKernelGGL((quantize_wave_kernel<H, true>), wgrid, dim3(256), 0, s, d_descs, single, n_ops, batch); \
-        else hipLaunchKernelGGL((quantize_wave_kernel<H, false>), wgrid, dim3(256), 0, s, d_descs, single, n_ops, batch);           \
+        if (batch <= 5) NQ_LAUNCH((quantize_wave_kernel<H, true>), wgrid, dim3(256), 0, s, d_descs, single, n_ops, batch); \
+        else NQ_LAUNCH((quantize_wave_kernel<H, false>), wgrid, dim3(256), 0, s, d_descs, single, n_ops, batch);           \
     } while (0)
         NQ_LAUNCH_QWAVE(1);
 #undef NQ_LAUNCH_QWAVE
@@ -291,8 +291,8 @@ int launch_quantize(const QuantDesc* d_descs, const QuantDesc& single, int n_ops
     const dim3 grid(n_ops, batch);
 #define NQ_LAUNCH_QUANT(T)                                                                              \
     do {                                                                                                \
-        if (batch <= 5) hipLaunchKernelGGL((quantize_kernel<T, true>), grid, dim3(T), 0, s, d_descs, single, batch); \
-        else hipLaunchKernelGGL((quantize_kernel<T, false>), grid, dim3(T), 0, s, d_descs, single, batch);           \
+        if (batch <= 5) NQ_LAUNCH((quantize_kernel<T, true>), grid, dim3(T), 0, s, d_descs, single, batch); \
+        else NQ_LAUNCH((quantize_kernel<T, false>), grid, dim3(T), 0, s, d_descs, single, batch);           \
     } while (0)
     if (max_chunks <= 256 * kQuantHeld) NQ_LAUNCH_QUANT(256);
     else if (max_chunks <= 512 * kQuantHeld) NQ_LAUNCH_QUANT(512);
@@ -1360,7 +1360,7 @@ static int launch_stream_t(const StageDesc* d_descs, const StageDesc& single, co
 {
     size_t lds_bytes = (size_t)kEpiRegion * sizeof(int) + (size_t)max_rbs_per_item * kTileRows * batch * sizeof(float);
     if (n_items < 1) return NQ_OK;
-    hipLaunchKernelGGL((stage_stream_kernel<NB, kRingDepth>), dim3(n_items), dim3(64), lds_bytes, s, d_descs, single,
+    NQ_LAUNCH((stage_stream_kernel<NB, kRingDepth>), dim3(n_items), dim3(64), lds_bytes, s, d_descs, single,
                        d_items, n_items, rbs_per_item, batch);
     NQ_HIP(hipGetLastError());
     return NQ_OK;
@@ -1372,7 +1372,7 @@ static int launch_split_t(const StageDesc* d_descs, const StageDesc& single, con
 {
     size_t lds_bytes = (size_t)W * kEpiRegion * sizeof(int);
     if (n_items < 1) return NQ_OK;
-    hipLaunchKernelGGL((stage_split_kernel<NB, W, (NB == 1 ? kRingDepth : 2 * kRingDepth)>), dim3(n_items), dim3(64 * W), lds_bytes, s, d_descs,
+    NQ_LAUNCH((stage_split_kernel<NB, W, (NB == 1 ? kRingDepth : 2 * kRingDepth)>), dim3(n_items), dim3(64 * W), lds_bytes, s, d_descs,
                        single, d_items, n_items, batch);
     NQ_HIP(hipGetLastError());
     return NQ_OK;
@@ -1411,7 +1411,7 @@ static int launch_shared_t(const StageDesc* d_descs, const WorkItem* d_items, in
                                    160 * 1024));
         attr_set = true;
     }
-    hipLaunchKernelGGL((stage_shared_kernel<NB, RESIDENT, SL>), dim3(n_items), dim3(64 * kShareWaves), lds_bytes, s, d_descs, d_items,
+    NQ_LAUNCH((stage_shared_kernel<NB, RESIDENT, SL>), dim3(n_items), dim3(64 * kShareWaves), lds_bytes, s, d_descs, d_items,
                        n_items, per_max, batch);
     NQ_HIP(hipGetLastError());
     return NQ_OK;
@@ -1452,7 +1452,7 @@ int launch_fused_list(const FusedItem* d_items, int n_items, int max_steps, hipS
     }
     int rc = fused_set_attr();
     if (rc != NQ_OK) return rc;
-    hipLaunchKernelGGL(stage_fused_kernel<true>, dim3((unsigned)n_items), dim3(64 * kFusedWaves),
+    NQ_LAUNCH(stage_fused_kernel<true>, dim3((unsigned)n_items), dim3(64 * kFusedWaves),
                        fused_lds_bytes(max_steps), s, d_items, QuantDesc{}, StageDesc{});
     NQ_HIP(hipGetLastError());
     return NQ_OK;
@@ -1493,17 +1493,17 @@ int launch_selfq(const FusedItem* d_items, int n_items, const QuantDesc& q1, con
     const size_t lds_bytes = (size_t)w * selfq_region_ints(c) * 4 + (w > 1 ? 2 * w * 4 : 0);     // + the waves' maxima and flags
     const dim3 grid((unsigned)n_items);
     if (w == 1 && c == 2 && d_items)
-        hipLaunchKernelGGL((stage_selfq_kernel<1, kSelfqDepth1, true, 2>), grid, dim3(64), lds_bytes, s, d_items, q1, s1);
+        NQ_LAUNCH((stage_selfq_kernel<1, kSelfqDepth1, true, 2>), grid, dim3(64), lds_bytes, s, d_items, q1, s1);
     else if (w == 1 && c == 2)
-        hipLaunchKernelGGL((stage_selfq_kernel<1, kSelfqDepth1, false, 2>), grid, dim3(64), lds_bytes, s, d_items, q1, s1);
+        NQ_LAUNCH((stage_selfq_kernel<1, kSelfqDepth1, false, 2>), grid, dim3(64), lds_bytes, s, d_items, q1, s1);
     else if (w == 1 && d_items)
-        hipLaunchKernelGGL((stage_selfq_kernel<1, kSelfqDepth1, true>), grid, dim3(64), lds_bytes, s, d_items, q1, s1);
+        NQ_LAUNCH((stage_selfq_kernel<1, kSelfqDepth1, true>), grid, dim3(64), lds_bytes, s, d_items, q1, s1);
     else if (w == 1)
-        hipLaunchKernelGGL((stage_selfq_kernel<1, kSelfqDepth1, false>), grid, dim3(64), lds_bytes, s, d_items, q1, s1);
+        NQ_LAUNCH((stage_selfq_kernel<1, kSelfqDepth1, false>), grid, dim3(64), lds_bytes, s, d_items, q1, s1);
     else if (d_items)
-        hipLaunchKernelGGL((stage_selfq_kernel<4, kSelfqDepth4, true>), grid, dim3(256), lds_bytes, s, d_items, q1, s1);
+        NQ_LAUNCH((stage_selfq_kernel<4, kSelfqDepth4, true>), grid, dim3(256), lds_bytes, s, d_items, q1, s1);
     else
-        hipLaunchKernelGGL((stage_selfq_kernel<4, kSelfqDepth4, false>), grid, dim3(256), lds_bytes, s, d_items, q1, s1);
+        NQ_LAUNCH((stage_selfq_kernel<4, kSelfqDepth4, false>), grid, dim3(256), lds_bytes, s, d_items, q1, s1);
     NQ_HIP(hipGetLastError());
     return NQ_OK;
 }

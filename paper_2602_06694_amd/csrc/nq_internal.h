@@ -1,6 +1,7 @@
 // Internal declarations shared by the translation units of libnq_binlr (not installed).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <string>
 #include "nq_binlr.h"
@@ -132,6 +133,23 @@ enum Opt {
 int opt(Opt o);                                        // -1 when unset
 inline int opt_or(Opt o, int dflt) { const int v = opt(o); return v >= 0 ? v : dflt; }
 inline bool opt_flag(Opt o) { return opt(o) > 0; }
+
+// A launch of the streaming path that is being timed carries a pair of events bound to the kernel itself
+// (hipExtLaunchKernelGGL): their difference is the kernel's own execution time, what a profiler reports for it.
+// Events recorded between launches would include the dispatch gaps and the event markers (two such events with
+// nothing between them are 5 us apart).  nq_plan_forward_timed sets the pair for one launch at a time, on its thread.
+struct LaunchTiming {
+    hipEvent_t start = nullptr, stop = nullptr;
+};
+extern thread_local LaunchTiming g_launch_timing;
+#define NQ_LAUNCH(kernel, grid, block, lds, s, ...)                                                              \
+    do {                                                                                                         \
+        if (nq::g_launch_timing.start)                                                                           \
+            hipExtLaunchKernelGGL(kernel, grid, block, lds, s, nq::g_launch_timing.start, nq::g_launch_timing.stop, 0, \
+                                  __VA_ARGS__);                                                                  \
+        else                                                                                                     \
+            hipLaunchKernelGGL(kernel, grid, block, lds, s, __VA_ARGS__);                                        \
+    } while (0)
 
 // ---- error plumbing ------------------------------------------------------------------------
 void set_error(const std::string& msg);
